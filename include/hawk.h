@@ -1,0 +1,176 @@
+/*
+ * hawk.h - C ABI of the MI355X (gfx950) library for the hot path of Hawk-style
+ * speculative decoding of autoregressive image tokens (arXiv 2510.25739).
+ *
+ * One step of the path = draft k tokens with a spatially conditioned head, score all
+ * k+1 positions in one pass of the target decoder over its KV cache, then run the fused
+ * speculative-sampling stage (top-k softmax, accept with min(1, p/q), resample the
+ * first rejected position from norm(max(0, p - q))).
+ *
+ * Conventions for every entry point
+ *   - Returns HAWK_OK (0) or a negative error code; never throws, never aborts.
+ *     hawk_last_error() returns a text for the last failure on that context.
+ *   - "host" pointers are ordinary CPU memory owned by the caller and are only read or
+ *     written during the call.  "device" pointers are GPU memory owned by the caller.
+ *   - The library allocates no device memory: all of it lives in the workspace the
+ *     caller hands to hawk_create (size from hawk_workspace_bytes) and must stay valid
+ *     and untouched until hawk_destroy.
+ *   - Work is enqueued on the HIP stream given to hawk_create.  A call that has host
+ *     outputs synchronises that stream before it returns; with all outputs NULL it
+ *     returns as soon as the work is enqueued.
+ *   - A context is not thread safe.  Call order: create, load, then per image
+ *     prefill, (draft | draft_forced, verify)*  - or generate, which does all of that.
+ *   - Token ids are full-vocabulary ids.  Sampling is restricted to the contiguous id
+ *     range [samp_lo, samp_lo + samp_n); logit rows have samp_n entries.
+ *   - Sequences: `batch` prompts; with classifier-free guidance (cfg_scale != 1) every
+ *     prompt has a conditional and an unconditional stream (2*batch sequences).
+ *   - Uniforms are fp32 in [0, 1).
+ */
+#ifndef HAWK_H
+#define HAWK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hawk_ctx hawk_ctx;
+
+enum {
+    HAWK_OK = 0,
+    HAWK_EINVAL = -1,  /* bad argument */
+    HAWK_ESTATE = -2,  /* call out of order */
+    HAWK_ENOMEM = -3,  /* workspace too small */
+    HAWK_EDEVICE = -4  /* HIP runtime error */
+};
+
+enum { HAWK_FP32 = 0, HAWK_BF16 = 1 };
+
+/* Shape of the target decoder (pre-RMSNorm, rotary positions, SwiGLU MLP, no biases),
+ * of the sampled vocabulary slice, and the capacity limits of one context.
+ * dtype is the storage type of the weight blob: HAWK_FP32 computes with fp64
+ * accumulators and activations (the exact-parity configuration), HAWK_BF16 with bf16
+ * weights and KV cache, fp32 accumulators and residual stream. */
+typedef struct {
+    int32_t n_layers, d_model, n_heads, d_mlp, vocab;
+    int32_t samp_lo, samp_n;              /* samp_n == 0: whole vocabulary */
+    int32_t max_cond, max_grid_h, max_grid_w, max_batch, k_max;
+    int32_t dtype;                        /* HAWK_FP32 or HAWK_BF16 */
+    int32_t use_cfg;                      /* 1: contexts run two streams per prompt */
+    float rms_eps, rope_theta;
+} hawk_config;
+
+/* Counters of one hawk_generate call.  steps = prompt-steps executed (one per prompt
+ * per speculate-and-verify step while the prompt was unfinished), accepted = drafts
+ * accepted, tokens = image tokens committed by those steps (accepted + steps), iters =
+ * lock-step iterations of the batch.  Accept length (Experiment, "Metrics") is
+ * tokens / steps.  Times are milliseconds of GPU time on the context's stream. */
+typedef struct {
+    int64_t steps, accepted, tokens, iters;
+    float ms_prefill, ms_decode;
+} hawk_stats;
+
+/* Bytes of device workspace a context of this configuration needs; 0 if the
+ * configuration is invalid. */
+size_t hawk_workspace_bytes(const hawk_config* cfg);
+
+/* Creates a context over `workspace` (device, 256-byte aligned, >= hawk_workspace_bytes)
+ * that enqueues on `hip_stream` (a hipStream_t, NULL = the default stream). */
+int hawk_create(const hawk_config* cfg, void* workspace, size_t workspace_bytes,
+                void* hip_stream, hawk_ctx** out);
+void hawk_destroy(hawk_ctx* ctx);
+const char* hawk_last_error(const hawk_ctx* ctx);
+
+/* hawk_load(weights): copies a weight blob (host) into the workspace and prepares the
+ * device layouts.  Blob = 64-byte header of int32 {magic 'HAWK', version 1, dtype,
+ * n_layers, d_model, n_heads, d_mlp, vocab, 0...} followed by row-major [out, in]
+ * tensors in dtype: E[vocab,d]; per layer g1[d] Wq Wk Wv Wo [d,d] g2[d] W1 W3 [m,d]
+ * W2[d,m]; g_f[d]; W_out[vocab,d]; W_d[d,3d].  The draft head is one linear map over
+ * [previous head output or target hidden | embedding of the left neighbour | embedding
+ * of the upper neighbour] followed by the target's own final norm and output projection
+ * (draft heads on the final hidden state: Preliminary, "Utilization of Draft Heads
+ * Structure"; spatial neighbours x_{T-1}, x_{T-IW}: Preliminary, "Attention Sinking").
+ * Header fields must match the context's configuration. */
+int hawk_load(hawk_ctx* ctx, const void* host_blob, size_t nbytes);
+
+/* hawk_prefill(cond): runs the target over the condition vectors (host, fp32
+ * [batch, n_cond, d]; uncond likewise or NULL without guidance), fills the KV cache,
+ * samples image token 0 of every prompt with u_first (host [batch]) and fixes the
+ * decoding parameters of this image: grid size, temperature (0 = greedy), top_k in
+ * [1, samp_n], cfg_scale (== 1 exactly iff the context was created without use_cfg;
+ * guided logits are l_u + s (l_c - l_u)).  Top-k / temperature / guidance: Experiment,
+ * "Model and Benchmark".  Raster order: Preliminary, "Autoregressive Image
+ * Generation". */
+int hawk_prefill(hawk_ctx* ctx, const float* cond, const float* uncond, int batch, int n_cond,
+                 int grid_h, int grid_w, float temperature, int top_k, float cfg_scale,
+                 const float* u_first);
+
+/* hawk_draft(k): the drafting phase (Preliminary, "Speculative Sampling").  For each
+ * unfinished prompt drafts k_eff = min(k, N - n - 1) tokens for raster positions
+ * n .. n+k_eff-1 (n = tokens committed so far), one after another: draft i reads the
+ * previous head output (the target's hidden state for i = 1), the embedding of the token
+ * left of its position (the previous draft for i > 1) and of the token above it (zeros
+ * on the first image row), and is sampled by inverse CDF with u_draft (host [batch, k])
+ * from the top-k/temperature-warped, guided draft logits.  k <= k_max and k <= grid_w.
+ * out_draft (host [batch, k], may be NULL) receives the tokens, -1 where none. */
+int hawk_draft(hawk_ctx* ctx, int k, const float* u_draft, int32_t* out_draft);
+
+/* Teacher-forced drafting: like hawk_draft, but draft i of prompt b is tokens[b][i]
+ * (host [batch, k], ids inside the sampled slice) instead of a draw; the head still runs
+ * and produces q_i from the forced left neighbours.  point_mass != 0 replaces q_i by the
+ * point mass on the forced token (replay mode: acceptance probability p_i(d_i)).
+ * hawk_draft / hawk_draft_forced may be repeated before hawk_verify; the last one counts. */
+int hawk_draft_forced(hawk_ctx* ctx, int k, const int32_t* tokens, int point_mass);
+
+/* hawk_verify(k): the verification phase (Preliminary, "Speculative Sampling"; Method,
+ * "Sampling and Verification" with one candidate per depth).  One target pass over the
+ * rows [last committed token, draft 1 .. draft k_eff] of every sequence, appended to
+ * the KV cache under a block-causal mask; then, per prompt, draft i is accepted iff
+ * u_acc[i] * q_i(d_i) < p_i(d_i) (probability min(1, p/q)), stopping at the first
+ * rejection; a = number accepted.  If a < k_eff the next token is drawn with u_final
+ * from norm(max(0, p_{a+1} - q_{a+1})), else from p_{k_eff+1}.  Commits a+1 tokens,
+ * drops the rejected rows from the cache and keeps the hidden state of row a for the
+ * next draft.  u_acc host [batch, k], u_final host [batch]; out_n_accept host [batch]
+ * (-1 for a finished prompt) and out_tokens host [batch, k+1] (-1 padded) may be NULL. */
+int hawk_verify(hawk_ctx* ctx, int k, const float* u_acc, const float* u_final,
+                int32_t* out_n_accept, int32_t* out_tokens);
+
+/* hawk_generate(cond, grid_h, grid_w, k, temperature, top_k, cfg_scale, seed): prefill,
+ * then draft + verify until every prompt has grid_h * grid_w tokens.  Uniforms come from
+ * a counter-based generator: u(seed, prompt b, step s, slot) = top 24 bits of
+ * mix(mix(seed + G) + G * (((b << 44) | (s << 8) | slot) + 1)) / 2^24 with mix the
+ * splitmix64 finaliser and G = 0x9E3779B97F4A7C15; slot = i for draft i, 64 + i for
+ * acceptance test i, 128 for the resample/bonus draw; step 0 slot 128 samples token 0,
+ * steps count from 1.  replay_tokens (host [batch, N] or NULL) switches to replay mode:
+ * the head still runs, but draft i of a step is replay_tokens[b][n + i - 1] with a
+ * point-mass draft distribution.
+ * out_grid host [batch, N]; stats may be NULL. */
+int hawk_generate(hawk_ctx* ctx, const float* cond, const float* uncond, int batch, int n_cond,
+                  int grid_h, int grid_w, int k, float temperature, int top_k, float cfg_scale,
+                  uint64_t seed, const int32_t* replay_tokens, int32_t* out_grid,
+                  hawk_stats* stats);
+
+/* Teacher forcing / re-synchronisation: rewinds prompt b to n_from[b] committed tokens
+ * (1 <= n_from[b] <= current n) and commits tokens[b][0..cnt) as if all had been
+ * accepted (cnt <= k_max + 1): runs the target over them, extends the cache, keeps the
+ * hidden state of the last row.  n_from host [batch], tokens host [batch, cnt]. */
+int hawk_force(hawk_ctx* ctx, const int32_t* n_from, const int32_t* tokens, int cnt);
+
+/* State read-back (all host outputs, each synchronises the stream). */
+int hawk_get_n(hawk_ctx* ctx, int32_t* n /*[batch]*/);
+int hawk_get_grid(hawk_ctx* ctx, int32_t* grid /*[batch, N]*/);
+/* guided target logits of the last verify/force, [batch, rows, samp_n], rows = k+1 or cnt */
+int hawk_get_logits(hawk_ctx* ctx, float* out, int rows);
+/* guided draft logits of the last draft, [batch, k, samp_n] */
+int hawk_get_draft_logits(hawk_ctx* ctx, float* out, int k);
+
+/* Selects the kernel set: 0 = generic kernels (any shape), 1 = fused weight-streaming
+ * kernels where the shape allows (default). */
+int hawk_set_path(hawk_ctx* ctx, int path);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

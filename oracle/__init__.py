@@ -47,7 +47,7 @@ def lib() -> C.CDLL:
             "orc_free_state": (None, [vp]),
             "orc_prefill": (i32, [vp, vp, vp, i32, f32, i32, f32, vp]),
             "orc_draft": (i32, [vp, i32, vp, vp]),
-            "orc_set_draft": (i32, [vp, i32, vp]),
+            "orc_draft_forced": (i32, [vp, i32, vp, i32]),
             "orc_verify": (i32, [vp, i32, vp, vp, vp, vp]),
             "orc_force": (i32, [vp, vp, vp, i32]),
             "orc_generate": (i32, [vp, vp, vp, i32, i32, f32, i32, f32, u64, vp, vp]),
@@ -187,8 +187,10 @@ class Oracle:
         self.k_last = k
         return out[:, :k]
 
-    def set_draft(self, k, tokens):
-        _chk(lib().orc_set_draft(self._s, k, _p(_i32(tokens))), "set_draft")
+    def draft_forced(self, k, tokens, point_mass):
+        t = _i32(tokens) if k > 0 else None
+        _chk(lib().orc_draft_forced(self._s, k, _p(t), int(point_mass)), "draft_forced")
+        self.k_last = k
 
     def verify(self, k, u_acc, u_final):
         na = np.zeros(self.batch, dtype=np.int32)

@@ -486,11 +486,27 @@ int orc_prefill(orc_state* st, const float* cond, const float* uncond, int n_con
     return ORC_OK;
 }
 
-int orc_draft(orc_state* st, int k, const float* u_draft, int32_t* out_draft) {
-    if (!st || k < 0 || k > st->kmax || k > st->gw || (k > 0 && !u_draft)) return ORC_EINVAL;
-    if (st->phase != 1) return ORC_ESTATE;
+/* Drafting phase.  With `forced` == NULL every draft is drawn from its own distribution
+ * with u_draft; otherwise draft i is forced[b][i] (teacher-forced drafting: the head still
+ * produces q_i from the forced left neighbours) and, if point_mass is set, q_i is replaced
+ * by the point mass on that token (replay mode).  May be repeated before the verify call:
+ * the last draft counts. */
+static int draft_impl(orc_state* st, int k, const float* u_draft, const int32_t* forced, int point_mass,
+                      int32_t* out_draft) {
+    if (!st || k < 0 || k > st->kmax || k > st->gw) return ORC_EINVAL;
+    if (k > 0 && !u_draft && !forced) return ORC_EINVAL;
+    if (st->phase != 1 && st->phase != 2) return ORC_ESTATE;
     const orc_model* M = st->M;
     int d = M->d, Vs = M->Vs, N = st->N, IW = st->gw;
+    if (forced)
+        for (int b = 0; b < st->B; ++b) {
+            int n = st->n[b];
+            int ke = n >= N ? 0 : (k < N - n - 1 ? k : N - n - 1);
+            for (int i = 0; i < ke; ++i) {
+                int t = forced[(size_t)b * k + i];
+                if (t < M->samp_lo || t >= M->samp_lo + Vs) return ORC_EINVAL;
+            }
+        }
     double* g = (double*)malloc(sizeof(double) * 2 * (size_t)d);
     double* gn = (double*)malloc(sizeof(double) * (size_t)d);
     float* lu = (float*)malloc(sizeof(float) * (size_t)Vs);
@@ -499,6 +515,8 @@ int orc_draft(orc_state* st, int k, const float* u_draft, int32_t* out_draft) {
         int n = st->n[b];
         int32_t* dr = st->draft + (size_t)b * (st->kmax + 1);
         for (int i = 0; i < k; ++i) dr[i] = -1;
+        if (out_draft)
+            for (int i = 0; i < k; ++i) out_draft[(size_t)b * k + i] = -1;
         if (n >= N) {
             st->k_eff[b] = -1;
             continue;
@@ -519,35 +537,31 @@ int orc_draft(orc_state* st, int k, const float* u_draft, int32_t* out_draft) {
                 memcpy(g + d, gn, sizeof(double) * (size_t)d);
                 guide(lq, lu, st->cfg_scale, Vs, lq);
             }
-            double Z = orc_warp(lq, Vs, st->temperature, st->top_k, w);
-            dr[i - 1] = M->samp_lo + orc_inv_cdf(w, Vs, Z, u_draft[(size_t)b * k + (i - 1)]);
+            if (forced) {
+                dr[i - 1] = forced[(size_t)b * k + (i - 1)];
+            } else {
+                double Z = orc_warp(lq, Vs, st->temperature, st->top_k, w);
+                dr[i - 1] = M->samp_lo + orc_inv_cdf(w, Vs, Z, u_draft[(size_t)b * k + (i - 1)]);
+            }
         }
         if (out_draft)
             for (int i = 0; i < k; ++i) out_draft[(size_t)b * k + i] = dr[i];
     }
     free(g); free(gn); free(lu); free(w);
     st->k_last = k;
-    st->q_onehot = 0;
+    st->q_onehot = (forced && point_mass) ? 1 : 0;
     st->phase = 2;
     return ORC_OK;
 }
 
-/* Replay mode: replace the drafted tokens; the draft distribution becomes the point mass
- * on each given token. */
-int orc_set_draft(orc_state* st, int k, const int32_t* tokens) {
-    if (!st || !tokens) return ORC_EINVAL;
-    if (st->phase != 2 || k != st->k_last) return ORC_ESTATE;
-    const orc_model* M = st->M;
-    for (int b = 0; b < st->B; ++b)
-        for (int i = 0; i < st->k_eff[b]; ++i) {
-            int t = tokens[(size_t)b * k + i];
-            if (t < M->samp_lo || t >= M->samp_lo + M->Vs) return ORC_EINVAL;
-        }
-    for (int b = 0; b < st->B; ++b)
-        for (int i = 0; i < st->k_eff[b]; ++i)
-            st->draft[(size_t)b * (st->kmax + 1) + i] = tokens[(size_t)b * k + i];
-    st->q_onehot = 1;
-    return ORC_OK;
+int orc_draft(orc_state* st, int k, const float* u_draft, int32_t* out_draft) {
+    return draft_impl(st, k, u_draft, NULL, 0, out_draft);
+}
+
+int orc_draft_forced(orc_state* st, int k, const int32_t* tokens, int point_mass) {
+    if (k > 0 && !tokens) return ORC_EINVAL;
+    static const int32_t none = 0;
+    return draft_impl(st, k, NULL, k > 0 ? tokens : &none, point_mass, NULL);
 }
 
 /* Feed rows [x_{n-1}, extra_0 .. extra_{cnt-2}] of prompt b through the target (both

@@ -62,7 +62,7 @@ void orc_free_state(orc_state*);
 int orc_prefill(orc_state*, const float* cond, const float* uncond, int n_cond,
                 float temperature, int top_k, float cfg_scale, const float* u_first);
 int orc_draft(orc_state*, int k, const float* u_draft, int32_t* out_draft);
-int orc_set_draft(orc_state*, int k, const int32_t* tokens);
+int orc_draft_forced(orc_state*, int k, const int32_t* tokens, int point_mass);
 int orc_verify(orc_state*, int k, const float* u_acc, const float* u_final,
                int32_t* out_n_accept, int32_t* out_tokens);
 int orc_force(orc_state*, const int32_t* n_from, const int32_t* tokens, int cnt);

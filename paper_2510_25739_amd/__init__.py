@@ -1,0 +1,14 @@
+"""MI355X-native hot path of Hawk-style speculative decoding for autoregressive image tokens.
+
+Thin Python binding over libhawk.so (hand-written HIP kernels behind a C ABI, see
+include/hawk.h).  PyTorch is used for device memory and the stream only.
+"""
+from .hawk import (  # noqa: F401
+    Hawk,
+    HawkConfig,
+    HawkError,
+    HawkStats,
+    lib_path,
+    load_library,
+    workspace_bytes,
+)

@@ -1,0 +1,520 @@
+// Host side of libhawk: argument checking, workspace layout, and the order in which the
+// kernels of a prefill / draft / verify / generate call are enqueued.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+
+#include "hawk_internal.h"
+
+using namespace hawk;
+
+namespace {
+
+constexpr uint32_t kMagic = 0x4B574148u;
+constexpr size_t kPinnedBytes = 1 << 20;
+
+int fail(hawk_ctx* c, int code, const char* fmt, ...) __attribute__((format(printf, 3, 4)));
+int fail(hawk_ctx* c, int code, const char* fmt, ...) {
+    if (c) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(c->err, sizeof c->err, fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+#define HIP_TRY(c, call)                                                                     \
+    do {                                                                                     \
+        hipError_t e_ = (call);                                                              \
+        if (e_ != hipSuccess) return fail((c), HAWK_EDEVICE, "%s: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Fills the derived dimensions; false if the configuration is invalid.
+bool derive(const hawk_config* g, hawk_ctx* c) {
+    if (!g) return false;
+    if (g->n_layers < 1 || g->n_layers > 128 || g->d_model < 8 || g->d_model % 8 || g->n_heads < 1 ||
+        g->d_model % g->n_heads || g->d_mlp < 8 || g->d_mlp % 8 || g->vocab < 1)
+        return false;
+    const int hd = g->d_model / g->n_heads;
+    if (hd % 2 || hd > 256 || 256 % hd) return false;
+    const int vs = g->samp_n ? g->samp_n : g->vocab;
+    if (g->samp_lo < 0 || vs < 1 || (long long)g->samp_lo + vs > g->vocab) return false;
+    if (g->max_cond < 1 || g->max_grid_h < 1 || g->max_grid_w < 1 || g->max_batch < 1 || g->max_batch > 1024 ||
+        g->k_max < 0 || g->k_max > kMaxK)
+        return false;
+    if (g->dtype != HAWK_FP32 && g->dtype != HAWK_BF16) return false;
+    if (!(g->rms_eps > 0.f) || !(g->rope_theta > 0.f) || (g->use_cfg != 0 && g->use_cfg != 1)) return false;
+    c->cfg = *g;
+    c->L = g->n_layers; c->d = g->d_model; c->H = g->n_heads; c->hd = hd; c->m = g->d_mlp; c->V = g->vocab;
+    c->Vs = vs;
+    c->Bmax = g->max_batch;
+    c->Smax = g->max_batch * (g->use_cfg ? 2 : 1);
+    c->Nmax = g->max_grid_h * g->max_grid_w;
+    c->Tmax = g->max_cond + c->Nmax;
+    c->kmax = g->k_max;
+    const int rows = g->k_max + 1 > g->max_cond ? g->k_max + 1 : g->max_cond;
+    c->Mmax = c->Smax * rows;
+    c->esz = g->dtype == HAWK_FP32 ? 4 : 2;
+    c->asz = g->dtype == HAWK_FP32 ? 8 : 4;
+    c->ksz = g->dtype == HAWK_FP32 ? 8 : 2;
+    // blob layout
+    const size_t d = c->d, m = c->m, V = c->V, e = c->esz;
+    size_t off = 64;
+    c->w.E = off; off += V * d * e;
+    for (int l = 0; l < c->L; ++l) {
+        c->w.g1[l] = off; off += d * e;
+        c->w.Wqkv[l] = off; off += 3 * d * d * e;
+        c->w.Wo[l] = off; off += d * d * e;
+        c->w.g2[l] = off; off += d * e;
+        c->w.W13[l] = off; off += 2 * m * d * e;
+        c->w.W2[l] = off; off += d * m * e;
+    }
+    c->w.g_f = off; off += d * e;
+    c->w.W_out = off; off += V * d * e;
+    c->w.W_d = off; off += 3 * d * d * e;
+    c->blob_bytes = off;
+    // workspace layout
+    Offsets& o = c->off;
+    size_t p = 0;
+    auto take = [&](size_t bytes) { size_t at = p; p = align_up(p + bytes); return at; };
+    const size_t B = c->Bmax, S = c->Smax, ks = c->kmax + 1, Vs = c->Vs, M = c->Mmax, a = c->asz;
+    o.blob = take(c->blob_bytes);
+    o.kc = take((size_t)c->L * S * c->Tmax * d * c->ksz);
+    o.vc = take((size_t)c->L * S * c->Tmax * d * c->ksz);
+    o.n = take(B * 4); o.k_eff = take(B * 4); o.step = take(4); o.done = take(4); o.counters = take(4 * 8);
+    o.grid = take(B * c->Nmax * 4); o.draft = take(B * ks * 4); o.forced = take(B * ks * 4 + B * 4);
+    o.hprev = take(S * d * a); o.qstat = take(B * ks * sizeof(WarpStat)); o.pstat = take(B * ks * sizeof(WarpStat));
+    o.x = take(M * d * a); o.a = take(M * d * a); o.qkv = take(M * 3 * d * a); o.o = take(M * d * a);
+    o.u = take(M * 2 * m * a); o.din = take(S * 3 * d * a); o.g0 = take(S * d * a); o.g1 = take(S * d * a);
+    o.ga = take(S * d * a);
+    o.logit_s = take(S * ks * Vs * 4); o.logit_b = take(B * ks * Vs * 4);
+    o.dlogit_s = take(S * Vs * 4); o.dlogit_b = take(B * ks * Vs * 4);
+    o.u_draft = take(B * ks * 4); o.u_acc = take(B * ks * 4); o.u_fin = take(B * 4);
+    o.out_na = take(B * 4); o.out_tok = take(B * ks * 4); o.inv_freq = take((size_t)(hd / 2) * 8);
+    o.replay = take(B * c->Nmax * 4); o.cond = take(S * (size_t)g->max_cond * d * 4);
+    o.total = p;
+    return true;
+}
+
+RowMap step_map(hawk_ctx* c, int k) {
+    RowMap m;
+    m.mode = 1; m.rows_per_seq = k + 1; m.n_seq = c->S; m.batch = c->B; m.n_cond = c->C;
+    m.n = wsp<int32_t>(c, c->off.n); m.k_eff = wsp<int32_t>(c, c->off.k_eff);
+    return m;
+}
+
+// All decoder layers over M rows held in x (residual stream, updated in place).
+void run_layers(hawk_ctx* c, const RowMap& map, int M) {
+    const Offsets& o = c->off;
+    const int d = c->d, m = c->m;
+    for (int l = 0; l < c->L; ++l) {
+        launch_rmsnorm(c, o.x, d, c->w.g1[l], o.a, M);
+        launch_gemm(c, o.a, d, c->w.Wqkv[l], 3 * d, d, o.qkv, 3 * d, M, false, false);
+        launch_rope_append(c, map, l, M);
+        launch_attention(c, map, l, M);
+        launch_gemm(c, o.o, d, c->w.Wo[l], d, d, o.x, d, M, true, false);
+        launch_rmsnorm(c, o.x, d, c->w.g2[l], o.a, M);
+        launch_gemm(c, o.a, d, c->w.W13[l], 2 * m, d, o.u, 2 * m, M, false, false);
+        launch_swiglu(c, M);
+        launch_gemm(c, o.u, 2 * m, c->w.W2[l], d, m, o.x, d, M, true, false);
+    }
+}
+
+size_t slice_off(const hawk_ctx* c) { return c->w.W_out + (size_t)c->cfg.samp_lo * c->d * c->esz; }
+
+// Target pass over the step rows [last committed | drafts] and logits of every row.
+void run_step_rows(hawk_ctx* c, int k) {
+    const int M = c->S * (k + 1);
+    RowMap map = step_map(c, k);
+    launch_embed_rows(c, map, M);
+    run_layers(c, map, M);
+    launch_rmsnorm(c, c->off.x, c->d, c->w.g_f, c->off.a, M);
+    launch_gemm(c, c->off.a, c->d, slice_off(c), c->Vs, c->d, c->off.logit_s, c->Vs, M, false, true);
+}
+
+void enqueue_draft(hawk_ctx* c, int k, const UniformSrc& us, const DraftMode& dm) {
+    launch_plan(c, k);
+    for (int i = 1; i <= k; ++i) {
+        const size_t g = (i & 1) ? c->off.g1 : c->off.g0;
+        launch_draft_input(c, i);
+        launch_gemm(c, c->off.din, 3 * c->d, c->w.W_d, c->d, 3 * c->d, g, c->d, c->S, false, false);
+        launch_rmsnorm(c, g, c->d, c->w.g_f, c->off.ga, c->S);
+        launch_gemm(c, c->off.ga, c->d, slice_off(c), c->Vs, c->d, c->off.dlogit_s, c->Vs, c->S, false, true);
+        launch_draft_sample(c, i, k, us, dm);
+    }
+}
+
+void enqueue_verify(hawk_ctx* c, int k, const UniformSrc& us) {
+    run_step_rows(c, k);
+    launch_verify_stats(c, k);
+    launch_accept_commit(c, k, us);
+}
+
+int check_image_args(hawk_ctx* c, int batch, int n_cond, int grid_h, int grid_w, float temperature, int top_k,
+                     float cfg_scale) {
+    if (batch < 1 || batch > c->Bmax) return fail(c, HAWK_EINVAL, "batch %d outside [1, %d]", batch, c->Bmax);
+    if (n_cond < 1 || n_cond > c->cfg.max_cond)
+        return fail(c, HAWK_EINVAL, "n_cond %d outside [1, %d]", n_cond, c->cfg.max_cond);
+    if (grid_h < 1 || grid_w < 1 || grid_h > c->cfg.max_grid_h || grid_w > c->cfg.max_grid_w)
+        return fail(c, HAWK_EINVAL, "grid %dx%d outside the context's %dx%d", grid_h, grid_w, c->cfg.max_grid_h,
+                    c->cfg.max_grid_w);
+    if (!(temperature >= 0.f) || !isfinite(temperature)) return fail(c, HAWK_EINVAL, "temperature must be >= 0");
+    if (top_k < 1 || top_k > c->Vs) return fail(c, HAWK_EINVAL, "top_k %d outside [1, %d]", top_k, c->Vs);
+    if (c->cfg.use_cfg ? (cfg_scale == 1.0f) : (cfg_scale != 1.0f))
+        return fail(c, HAWK_EINVAL, "cfg_scale %g does not match the context (use_cfg = %d)", (double)cfg_scale,
+                    c->cfg.use_cfg);
+    return HAWK_OK;
+}
+
+int enqueue_prefill(hawk_ctx* c, const float* cond, const float* uncond, int batch, int n_cond, int grid_h,
+                    int grid_w, float temperature, int top_k, float cfg_scale, const UniformSrc& us) {
+    c->B = batch; c->S = batch * (c->cfg.use_cfg ? 2 : 1); c->C = n_cond; c->gh = grid_h; c->gw = grid_w;
+    c->N = grid_h * grid_w; c->temperature = temperature; c->top_k = top_k; c->cfg_scale = cfg_scale;
+    c->greedy = (temperature == 0.f || top_k == 1) ? 1 : 0;
+    c->inv_t = c->greedy ? 1.0f : 1.0f / temperature;
+    const size_t per = (size_t)batch * n_cond * c->d * 4;
+    HIP_TRY(c, hipMemsetAsync(c->ws + c->off.n, 0, c->off.grid - c->off.n, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->ws + c->off.cond, cond, per, hipMemcpyHostToDevice, c->stream));
+    if (c->cfg.use_cfg)
+        HIP_TRY(c, hipMemcpyAsync(c->ws + c->off.cond + per, uncond, per, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));  // the host buffers may be pageable
+    const int M = c->S * n_cond;
+    RowMap map;
+    map.mode = 0; map.rows_per_seq = n_cond; map.n_seq = c->S; map.batch = c->B; map.n_cond = n_cond;
+    map.n = nullptr; map.k_eff = nullptr;
+    launch_cond_rows(c, M);
+    run_layers(c, map, M);
+    launch_keep_hprev_prefill(c);
+    // final norm + output projection of the last condition row of every sequence
+    launch_rmsnorm(c, c->off.x + (size_t)(n_cond - 1) * c->d * c->asz, (size_t)n_cond * c->d, c->w.g_f, c->off.a,
+                   c->S);
+    launch_gemm(c, c->off.a, c->d, slice_off(c), c->Vs, c->d, c->off.logit_s, c->Vs, c->S, false, true);
+    launch_first_token(c, us);
+    HIP_TRY(c, hipGetLastError());
+    return HAWK_OK;
+}
+
+int upload(hawk_ctx* c, size_t off, const void* host, size_t bytes) {
+    if (bytes == 0) return HAWK_OK;
+    HIP_TRY(c, hipMemcpyAsync(c->ws + off, host, bytes, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return HAWK_OK;
+}
+
+int download(hawk_ctx* c, void* host, size_t off, size_t bytes) {
+    if (bytes == 0) return HAWK_OK;
+    HIP_TRY(c, hipMemcpyAsync(host, c->ws + off, bytes, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return HAWK_OK;
+}
+
+bool uniforms_ok(const float* u, size_t n) {
+    for (size_t i = 0; i < n; ++i)
+        if (!(u[i] >= 0.f && u[i] < 1.f)) return false;
+    return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t hawk_workspace_bytes(const hawk_config* cfg) {
+    hawk_ctx tmp;
+    memset(&tmp, 0, sizeof tmp);
+    return derive(cfg, &tmp) ? tmp.off.total : 0;
+}
+
+int hawk_create(const hawk_config* cfg, void* workspace, size_t workspace_bytes, void* hip_stream, hawk_ctx** out) {
+    if (!out) return HAWK_EINVAL;
+    *out = nullptr;
+    hawk_ctx* c = new (std::nothrow) hawk_ctx;
+    if (!c) return HAWK_ENOMEM;
+    memset(c, 0, sizeof *c);
+    if (!derive(cfg, c)) { delete c; return HAWK_EINVAL; }
+    if (!workspace || ((uintptr_t)workspace & 255)) { delete c; return HAWK_EINVAL; }
+    if (workspace_bytes < c->off.total) { delete c; return HAWK_ENOMEM; }
+    c->ws = static_cast<uint8_t*>(workspace);
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->path = 1;
+    if (hipHostMalloc(&c->pinned, kPinnedBytes, hipHostMallocDefault) != hipSuccess) { delete c; return HAWK_EDEVICE; }
+    for (int i = 0; i < 3; ++i)
+        if (hipEventCreate(&c->ev[i]) != hipSuccess) { (void)hipHostFree(c->pinned); delete c; return HAWK_EDEVICE; }
+    // rotary frequencies theta^(-2j/hd), computed once in double
+    double* f = static_cast<double*>(c->pinned);
+    for (int j = 0; j < c->hd / 2; ++j) f[j] = pow((double)c->cfg.rope_theta, -2.0 * j / (double)c->hd);
+    if (hipMemcpyAsync(c->ws + c->off.inv_freq, f, (size_t)(c->hd / 2) * 8, hipMemcpyHostToDevice, c->stream) != hipSuccess ||
+        hipStreamSynchronize(c->stream) != hipSuccess) {
+        hawk_destroy(c);
+        return HAWK_EDEVICE;
+    }
+    *out = c;
+    return HAWK_OK;
+}
+
+void hawk_destroy(hawk_ctx* c) {
+    if (!c) return;
+    (void)hipStreamSynchronize(c->stream);
+    for (int i = 0; i < 3; ++i)
+        if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
+    if (c->pinned) (void)hipHostFree(c->pinned);
+    delete c;
+}
+
+const char* hawk_last_error(const hawk_ctx* c) { return c ? c->err : "null context"; }
+
+int hawk_set_path(hawk_ctx* c, int path) {
+    if (!c) return HAWK_EINVAL;
+    if (path != 0 && path != 1) return fail(c, HAWK_EINVAL, "path must be 0 or 1");
+    c->path = path;
+    return HAWK_OK;
+}
+
+int hawk_load(hawk_ctx* c, const void* host_blob, size_t nbytes) {
+    if (!c) return HAWK_EINVAL;
+    if (!host_blob) return fail(c, HAWK_EINVAL, "null blob");
+    if (nbytes != c->blob_bytes)
+        return fail(c, HAWK_EINVAL, "blob has %zu bytes, configuration needs %zu", nbytes, c->blob_bytes);
+    const int32_t* h = static_cast<const int32_t*>(host_blob);
+    if ((uint32_t)h[0] != kMagic || h[1] != 1) return fail(c, HAWK_EINVAL, "bad blob magic or version");
+    if (h[2] != c->cfg.dtype || h[3] != c->L || h[4] != c->d || h[5] != c->H || h[6] != c->m || h[7] != c->V)
+        return fail(c, HAWK_EINVAL, "blob header does not match the context's configuration");
+    HIP_TRY(c, hipMemcpy(c->ws + c->off.blob, host_blob, nbytes, hipMemcpyHostToDevice));
+    c->phase = 1;
+    return HAWK_OK;
+}
+
+int hawk_prefill(hawk_ctx* c, const float* cond, const float* uncond, int batch, int n_cond, int grid_h, int grid_w,
+                 float temperature, int top_k, float cfg_scale, const float* u_first) {
+    if (!c) return HAWK_EINVAL;
+    if (c->phase < 1) return fail(c, HAWK_ESTATE, "hawk_prefill before hawk_load");
+    if (!cond || !u_first || (c->cfg.use_cfg && !uncond)) return fail(c, HAWK_EINVAL, "null input");
+    int rc = check_image_args(c, batch, n_cond, grid_h, grid_w, temperature, top_k, cfg_scale);
+    if (rc) return rc;
+    if (!uniforms_ok(u_first, batch)) return fail(c, HAWK_EINVAL, "uniforms must lie in [0, 1)");
+    rc = upload(c, c->off.u_fin, u_first, (size_t)batch * 4);
+    if (rc) return rc;
+    UniformSrc us;
+    memset(&us, 0, sizeof us);
+    us.fin = wsp<float>(c, c->off.u_fin);
+    rc = enqueue_prefill(c, cond, uncond, batch, n_cond, grid_h, grid_w, temperature, top_k, cfg_scale, us);
+    if (rc) return rc;
+    c->phase = 2;
+    return HAWK_OK;
+}
+
+int hawk_draft(hawk_ctx* c, int k, const float* u_draft, int32_t* out_draft) {
+    if (!c) return HAWK_EINVAL;
+    if (c->phase != 2 && c->phase != 3) return fail(c, HAWK_ESTATE, "hawk_draft needs a prefilled context");
+    if (k < 0 || k > c->kmax || k > c->gw)
+        return fail(c, HAWK_EINVAL, "k = %d outside [0, min(k_max = %d, grid_w = %d)]", k, c->kmax, c->gw);
+    if (k > 0 && !u_draft) return fail(c, HAWK_EINVAL, "null uniforms");
+    if (k > 0 && !uniforms_ok(u_draft, (size_t)c->B * k)) return fail(c, HAWK_EINVAL, "uniforms must lie in [0, 1)");
+    int rc = upload(c, c->off.u_draft, u_draft, (size_t)c->B * k * 4);
+    if (rc) return rc;
+    UniformSrc us;
+    memset(&us, 0, sizeof us);
+    us.draft = wsp<float>(c, c->off.u_draft);
+    DraftMode dm = {0, 0};
+    enqueue_draft(c, k, us, dm);
+    HIP_TRY(c, hipGetLastError());
+    c->k_last = k;
+    c->phase = 3;
+    if (out_draft && k > 0) {
+        int32_t* tmp = static_cast<int32_t*>(c->pinned);
+        rc = download(c, tmp, c->off.draft, (size_t)c->B * (c->kmax + 1) * 4);
+        if (rc) return rc;
+        for (int b = 0; b < c->B; ++b)
+            for (int i = 0; i < k; ++i) out_draft[b * k + i] = tmp[b * (c->kmax + 1) + i];
+    }
+    return HAWK_OK;
+}
+
+int hawk_draft_forced(hawk_ctx* c, int k, const int32_t* tokens, int point_mass) {
+    if (!c) return HAWK_EINVAL;
+    if (c->phase != 2 && c->phase != 3) return fail(c, HAWK_ESTATE, "hawk_draft_forced needs a prefilled context");
+    if (k < 0 || k > c->kmax || k > c->gw)
+        return fail(c, HAWK_EINVAL, "k = %d outside [0, min(k_max = %d, grid_w = %d)]", k, c->kmax, c->gw);
+    if (k > 0 && !tokens) return fail(c, HAWK_EINVAL, "null tokens");
+    for (size_t i = 0; i < (size_t)c->B * k; ++i)
+        if (tokens[i] < c->cfg.samp_lo || tokens[i] >= c->cfg.samp_lo + c->Vs)
+            return fail(c, HAWK_EINVAL, "forced token %d outside the sampled slice", tokens[i]);
+    int rc = upload(c, c->off.forced, tokens, (size_t)c->B * k * 4);
+    if (rc) return rc;
+    UniformSrc us;
+    memset(&us, 0, sizeof us);
+    DraftMode dm = {1, point_mass ? 1 : 0};
+    enqueue_draft(c, k, us, dm);
+    HIP_TRY(c, hipGetLastError());
+    HIP_TRY(c, hipStreamSynchronize(c->stream));  // the staging buffer may be reused by the next call
+    c->k_last = k;
+    c->phase = 3;
+    return HAWK_OK;
+}
+
+int hawk_verify(hawk_ctx* c, int k, const float* u_acc, const float* u_final, int32_t* out_n_accept,
+                int32_t* out_tokens) {
+    if (!c) return HAWK_EINVAL;
+    if (c->phase != 3 || k != c->k_last) return fail(c, HAWK_ESTATE, "hawk_verify(k) must follow hawk_draft(k)");
+    if (!u_final || (k > 0 && !u_acc)) return fail(c, HAWK_EINVAL, "null uniforms");
+    if (!uniforms_ok(u_final, c->B) || (k > 0 && !uniforms_ok(u_acc, (size_t)c->B * k)))
+        return fail(c, HAWK_EINVAL, "uniforms must lie in [0, 1)");
+    int rc = upload(c, c->off.u_acc, u_acc, (size_t)c->B * k * 4);
+    if (!rc) rc = upload(c, c->off.u_fin, u_final, (size_t)c->B * 4);
+    if (rc) return rc;
+    UniformSrc us;
+    memset(&us, 0, sizeof us);
+    us.acc = wsp<float>(c, c->off.u_acc);
+    us.fin = wsp<float>(c, c->off.u_fin);
+    enqueue_verify(c, k, us);
+    HIP_TRY(c, hipGetLastError());
+    c->phase = 2;
+    if (out_n_accept) {
+        rc = download(c, out_n_accept, c->off.out_na, (size_t)c->B * 4);
+        if (rc) return rc;
+    }
+    if (out_tokens) {
+        rc = download(c, out_tokens, c->off.out_tok, (size_t)c->B * (k + 1) * 4);
+        if (rc) return rc;
+    }
+    return HAWK_OK;
+}
+
+int hawk_force(hawk_ctx* c, const int32_t* n_from, const int32_t* tokens, int cnt) {
+    if (!c) return HAWK_EINVAL;
+    if (c->phase < 2) return fail(c, HAWK_ESTATE, "hawk_force before hawk_prefill");
+    if (!n_from || !tokens) return fail(c, HAWK_EINVAL, "null input");
+    if (cnt < 1 || cnt > c->kmax + 1) return fail(c, HAWK_EINVAL, "cnt = %d outside [1, k_max + 1]", cnt);
+    int32_t* cur = static_cast<int32_t*>(c->pinned);
+    int rc = download(c, cur, c->off.n, (size_t)c->B * 4);
+    if (rc) return rc;
+    for (int b = 0; b < c->B; ++b) {
+        if (n_from[b] < 1 || n_from[b] > cur[b] || n_from[b] + cnt > c->N)
+            return fail(c, HAWK_EINVAL, "n_from[%d] = %d invalid (current n = %d, N = %d, cnt = %d)", b, n_from[b],
+                        cur[b], c->N, cnt);
+        for (int i = 0; i < cnt; ++i)
+            if (tokens[b * cnt + i] < 0 || tokens[b * cnt + i] >= c->V)
+                return fail(c, HAWK_EINVAL, "token outside the vocabulary");
+    }
+    rc = upload(c, c->off.forced, tokens, (size_t)c->B * cnt * 4);
+    if (!rc) rc = upload(c, c->off.u_draft, n_from, (size_t)c->B * 4);  // staged in the draft-uniform slot
+    if (rc) return rc;
+    launch_force_setup(c, cnt);
+    run_step_rows(c, cnt - 1);
+    launch_verify_stats(c, cnt - 1);
+    launch_force_commit(c, cnt);
+    HIP_TRY(c, hipGetLastError());
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->phase = 2;
+    return HAWK_OK;
+}
+
+int hawk_generate(hawk_ctx* c, const float* cond, const float* uncond, int batch, int n_cond, int grid_h, int grid_w,
+                  int k, float temperature, int top_k, float cfg_scale, uint64_t seed, const int32_t* replay_tokens,
+                  int32_t* out_grid, hawk_stats* stats) {
+    if (!c) return HAWK_EINVAL;
+    if (c->phase < 1) return fail(c, HAWK_ESTATE, "hawk_generate before hawk_load");
+    if (!cond || (c->cfg.use_cfg && !uncond)) return fail(c, HAWK_EINVAL, "null input");
+    int rc = check_image_args(c, batch, n_cond, grid_h, grid_w, temperature, top_k, cfg_scale);
+    if (rc) return rc;
+    if (k < 0 || k > c->kmax || k > grid_w)
+        return fail(c, HAWK_EINVAL, "k = %d outside [0, min(k_max = %d, grid_w = %d)]", k, c->kmax, grid_w);
+    const int N = grid_h * grid_w;
+    if (replay_tokens) {
+        for (size_t i = 0; i < (size_t)batch * N; ++i)
+            if (replay_tokens[i] < c->cfg.samp_lo || replay_tokens[i] >= c->cfg.samp_lo + c->Vs)
+                return fail(c, HAWK_EINVAL, "replayed token outside the sampled slice");
+        rc = upload(c, c->off.replay, replay_tokens, (size_t)batch * N * 4);
+        if (rc) return rc;
+    }
+    UniformSrc us;
+    memset(&us, 0, sizeof us);
+    us.use_gen = 1;
+    us.seed = seed;
+    us.step = wsp<int32_t>(c, c->off.step);
+    HIP_TRY(c, hipEventRecord(c->ev[0], c->stream));
+    rc = enqueue_prefill(c, cond, uncond, batch, n_cond, grid_h, grid_w, temperature, top_k, cfg_scale, us);
+    if (rc) return rc;
+    HIP_TRY(c, hipEventRecord(c->ev[1], c->stream));
+    // Every iteration commits at least one token per unfinished prompt, so N-1 iterations
+    // always suffice; the committed counts are polled every few iterations to stop early.
+    int32_t* nb = static_cast<int32_t*>(c->pinned);
+    const DraftMode dm = {replay_tokens ? 2 : 0, replay_tokens ? 1 : 0};
+    const int poll = 4;
+    bool done = N <= 1;
+    for (int it = 0; it < N - 1 && !done; ++it) {
+        enqueue_draft(c, k, us, dm);
+        enqueue_verify(c, k, us);
+        if ((it + 1) % poll == 0 || it == N - 2) {
+            HIP_TRY(c, hipGetLastError());
+            rc = download(c, nb, c->off.n, (size_t)batch * 4);
+            if (rc) return rc;
+            done = true;
+            for (int b = 0; b < batch; ++b) done = done && nb[b] >= N;
+        }
+    }
+    HIP_TRY(c, hipEventRecord(c->ev[2], c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->k_last = k;
+    c->phase = 2;
+    if (out_grid) {
+        rc = download(c, out_grid, c->off.grid, (size_t)batch * N * 4);  // rows are N long: N == c->N
+        if (rc) return rc;
+    }
+    if (stats) {
+        unsigned long long cnt[4];
+        rc = download(c, cnt, c->off.counters, sizeof cnt);
+        if (rc) return rc;
+        stats->steps = (int64_t)cnt[0];
+        stats->accepted = (int64_t)cnt[1];
+        stats->tokens = (int64_t)cnt[2];
+        stats->iters = (int64_t)cnt[3];
+        HIP_TRY(c, hipEventElapsedTime(&stats->ms_prefill, c->ev[0], c->ev[1]));
+        HIP_TRY(c, hipEventElapsedTime(&stats->ms_decode, c->ev[1], c->ev[2]));
+    }
+    return HAWK_OK;
+}
+
+int hawk_get_n(hawk_ctx* c, int32_t* n) {
+    if (!c || !n) return HAWK_EINVAL;
+    if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
+    return download(c, n, c->off.n, (size_t)c->B * 4);
+}
+
+int hawk_get_grid(hawk_ctx* c, int32_t* grid) {
+    if (!c || !grid) return HAWK_EINVAL;
+    if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
+    return download(c, grid, c->off.grid, (size_t)c->B * c->N * 4);
+}
+
+int hawk_get_logits(hawk_ctx* c, float* out, int rows) {
+    if (!c || !out) return HAWK_EINVAL;
+    if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
+    if (rows < 1 || rows > c->kmax + 1) return fail(c, HAWK_EINVAL, "rows outside [1, k_max + 1]");
+    for (int b = 0; b < c->B; ++b) {
+        int rc = download(c, out + (size_t)b * rows * c->Vs,
+                          c->off.logit_b + (size_t)b * (c->kmax + 1) * c->Vs * 4, (size_t)rows * c->Vs * 4);
+        if (rc) return rc;
+    }
+    return HAWK_OK;
+}
+
+int hawk_get_draft_logits(hawk_ctx* c, float* out, int k) {
+    if (!c || !out) return HAWK_EINVAL;
+    if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
+    if (k < 1 || k > c->kmax) return fail(c, HAWK_EINVAL, "k outside [1, k_max]");
+    for (int b = 0; b < c->B; ++b) {
+        int rc = download(c, out + (size_t)b * k * c->Vs, c->off.dlogit_b + (size_t)b * (c->kmax + 1) * c->Vs * 4,
+                          (size_t)k * c->Vs * 4);
+        if (rc) return rc;
+    }
+    return HAWK_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,377 @@
+// Generic (any-shape) kernels of the target decoder and the draft head.
+//
+// Two arithmetic configurations, selected by the weight dtype of the context:
+//   fp32 blobs: fp32 weights, fp64 activations / accumulators / KV cache (exact-parity set);
+//   bf16 blobs: bf16 weights and KV cache, fp32 activations and accumulators.
+// One wave computes one output column of a skinny GEMM for up to RT rows, streaming its
+// weight row with 16-byte loads; this is the fallback path and the only path of the
+// fp32 configuration.  The weight-streaming fast path lives in stream.hip.
+#include "hawk_internal.h"
+
+namespace hawk {
+
+struct CfgF32 {
+    using WT = float; using AT = double; using KT = double;
+    static constexpr int VE = 4;
+};
+struct CfgBF16 {
+    using WT = uint16_t; using AT = float; using KT = uint16_t;
+    static constexpr int VE = 8;
+};
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {  // round to nearest even
+    uint32_t u = __float_as_uint(f);
+    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
+__device__ __forceinline__ void load_w(const float* p, double* out) {
+    float4 v = *reinterpret_cast<const float4*>(p);
+    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+}
+__device__ __forceinline__ void load_w(const uint16_t* p, float* out) {
+    uint4 v = *reinterpret_cast<const uint4*>(p);
+    out[0] = bf16_to_f32(v.x & 0xFFFFu); out[1] = bf16_to_f32(v.x >> 16);
+    out[2] = bf16_to_f32(v.y & 0xFFFFu); out[3] = bf16_to_f32(v.y >> 16);
+    out[4] = bf16_to_f32(v.z & 0xFFFFu); out[5] = bf16_to_f32(v.z >> 16);
+    out[6] = bf16_to_f32(v.w & 0xFFFFu); out[7] = bf16_to_f32(v.w >> 16);
+}
+__device__ __forceinline__ double w1(const float* p, size_t i) { return (double)p[i]; }
+__device__ __forceinline__ float w1(const uint16_t* p, size_t i) { return bf16_to_f32(p[i]); }
+__device__ __forceinline__ double kload(const double* p, size_t i) { return p[i]; }
+__device__ __forceinline__ float kload(const uint16_t* p, size_t i) { return bf16_to_f32(p[i]); }
+__device__ __forceinline__ void kstore(double* p, size_t i, double v) { p[i] = v; }
+__device__ __forceinline__ void kstore(uint16_t* p, size_t i, float v) { p[i] = f32_to_bf16(v); }
+
+template <typename T> __device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+template <typename T> __device__ __forceinline__ T wave_max(T v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { T t = __shfl_xor(v, o, 64); v = t > v ? t : v; }
+    return v;
+}
+// Sum over a 256-thread block; every thread gets the result. red: >= 4 entries of LDS.
+template <typename T> __device__ __forceinline__ T block_sum256(T v, T* red) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return red[0] + red[1] + red[2] + red[3];
+}
+template <typename T> __device__ __forceinline__ T block_max256(T v, T* red) {
+    v = wave_max(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    T a = red[0] > red[1] ? red[0] : red[1], b = red[2] > red[3] ? red[2] : red[3];
+    return a > b ? a : b;
+}
+
+// Row R of a pass -> sequence, row within the sequence, prompt, absolute position.
+struct RowInfo { int s, r, b, pos; bool valid; };
+__device__ __forceinline__ RowInfo row_info(const RowMap& m, int R) {
+    RowInfo o;
+    o.s = R / m.rows_per_seq;
+    o.r = R - o.s * m.rows_per_seq;
+    o.b = o.s % m.batch;
+    if (m.mode == 0) {
+        o.pos = o.r;
+        o.valid = true;
+    } else {
+        int ke = m.k_eff[o.b];
+        o.valid = o.r <= ke;
+        o.pos = o.valid ? m.n_cond + m.n[o.b] - 1 + o.r : 0;
+    }
+    return o;
+}
+
+// ------------------------------------------------------------------ rows in
+
+// X[R] = E[token of row R]: row 0 of a sequence is the last committed token, row r > 0
+// is draft r-1.
+template <class Cfg>
+__global__ void embed_rows_kernel(typename Cfg::AT* X, const typename Cfg::WT* E, RowMap map,
+                                  const int32_t* grid, const int32_t* draft, int N, int kstride, int d) {
+    RowInfo ri = row_info(map, blockIdx.x);
+    int tok = 0;
+    if (ri.valid) tok = ri.r == 0 ? grid[(size_t)ri.b * N + map.n[ri.b] - 1] : draft[ri.b * kstride + ri.r - 1];
+    if (tok < 0) tok = 0;
+    for (int i = threadIdx.x; i < d; i += blockDim.x)
+        X[(size_t)blockIdx.x * d + i] = w1(E, (size_t)tok * d + i);
+}
+
+template <class Cfg>
+__global__ void cond_rows_kernel(typename Cfg::AT* X, const float* cond, size_t total) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < total) X[i] = (typename Cfg::AT)cond[i];
+}
+
+template <class Cfg>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const typename Cfg::AT* X, const typename Cfg::WT* g,
+                                                      typename Cfg::AT* out, int d, size_t in_stride,
+                                                      float eps) {
+    using AT = typename Cfg::AT;
+    __shared__ AT red[4];
+    const AT* x = X + (size_t)blockIdx.x * in_stride;
+    AT ss = 0;
+    for (int i = threadIdx.x; i < d; i += 256) ss += x[i] * x[i];
+    ss = block_sum256(ss, red);
+    AT r = (AT)1 / sqrt(ss / (AT)d + (AT)eps);
+    for (int i = threadIdx.x; i < d; i += 256) out[(size_t)blockIdx.x * d + i] = x[i] * r * w1(g, i);
+}
+
+// ------------------------------------------------------------------ skinny GEMM
+
+template <class Cfg, int RT, typename OT>
+__global__ __launch_bounds__(256) void gemm_rows_kernel(const typename Cfg::AT* A, int lda,
+                                                        const typename Cfg::WT* W, int N, int K,
+                                                        OT* Y, int ldy, int M, int accumulate) {
+    using AT = typename Cfg::AT;
+    constexpr int VE = Cfg::VE;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int n = blockIdx.x * 4 + wave;
+    if (n >= N) return;
+    const int r0 = blockIdx.y * RT;
+    AT acc[RT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r) acc[r] = 0;
+    const typename Cfg::WT* wrow = W + (size_t)n * K;
+    for (int c = lane * VE; c < K; c += 64 * VE) {
+        AT w[VE];
+        load_w(wrow + c, w);
+#pragma unroll
+        for (int r = 0; r < RT; ++r) {
+            if (r0 + r < M) {
+                const AT* a = A + (size_t)(r0 + r) * lda + c;
+#pragma unroll
+                for (int e = 0; e < VE; ++e) acc[r] += w[e] * a[e];
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < RT; ++r) acc[r] = wave_sum(acc[r]);
+    if (lane == 0) {
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+            if (r0 + r < M) {
+                OT* y = Y + (size_t)(r0 + r) * ldy + n;
+                *y = (OT)((accumulate ? (AT)*y : (AT)0) + acc[r]);
+            }
+    }
+}
+
+// ------------------------------------------------------------------ rotary + cache append
+
+// In place on QKV[R] = [q | k | v]: rotates q and k (pair (2j, 2j+1) of each head by
+// pos * inv_freq[j]) and writes k, v to the cache at (sequence, pos).
+template <class Cfg>
+__global__ void rope_append_kernel(typename Cfg::AT* QKV, typename Cfg::KT* Kc, typename Cfg::KT* Vc,
+                                   RowMap map, const double* inv_freq, int layer, int d, int hd,
+                                   int Smax, int Tmax) {
+    using AT = typename Cfg::AT;
+    RowInfo ri = row_info(map, blockIdx.x);
+    if (!ri.valid) return;
+    AT* q = QKV + (size_t)blockIdx.x * 3 * d;
+    AT* k = q + d;
+    AT* v = k + d;
+    size_t base = (((size_t)layer * Smax + ri.s) * Tmax + ri.pos) * d;
+    for (int p = threadIdx.x; p < d / 2; p += blockDim.x) {
+        int j = p % (hd / 2);
+        double ang = (double)ri.pos * inv_freq[j];
+        double sn, cs;
+        sincos(ang, &sn, &cs);
+        AT c = (AT)cs, s = (AT)sn;
+        AT a = q[2 * p], b = q[2 * p + 1];
+        q[2 * p] = a * c - b * s;
+        q[2 * p + 1] = a * s + b * c;
+        a = k[2 * p];
+        b = k[2 * p + 1];
+        kstore(Kc, base + 2 * p, a * c - b * s);
+        kstore(Kc, base + 2 * p + 1, a * s + b * c);
+        kstore(Vc, base + 2 * p, v[2 * p]);
+        kstore(Vc, base + 2 * p + 1, v[2 * p + 1]);
+    }
+}
+
+// ------------------------------------------------------------------ attention
+
+// One workgroup per (head, row): the row attends cache entries 0..pos of its sequence
+// (its own entry included), i.e. causal inside the block of new rows.
+template <class Cfg>
+__global__ __launch_bounds__(256) void attention_kernel(const typename Cfg::AT* QKV, const typename Cfg::KT* Kc,
+                                                        const typename Cfg::KT* Vc, typename Cfg::AT* O,
+                                                        RowMap map, int layer, int d, int hd, int Smax, int Tmax) {
+    using AT = typename Cfg::AT;
+    extern __shared__ double smem_raw[];
+    AT* sc = reinterpret_cast<AT*>(smem_raw);  // [Tmax] scores, then [hd] q, then [256] partials
+    AT* sq = sc + Tmax;
+    AT* part = sq + hd;
+    __shared__ AT red[4];
+    const int R = blockIdx.y, h = blockIdx.x, tid = threadIdx.x;
+    RowInfo ri = row_info(map, R);
+    if (!ri.valid) return;
+    const size_t base = (((size_t)layer * Smax + ri.s) * Tmax) * d + (size_t)h * hd;
+    for (int i = tid; i < hd; i += 256) sq[i] = QKV[(size_t)R * 3 * d + (size_t)h * hd + i];
+    __syncthreads();
+    const AT scale = (AT)1 / sqrt((AT)hd);
+    AT mx = -INFINITY;
+    for (int t = tid; t <= ri.pos; t += 256) {
+        AT s = 0;
+        for (int i = 0; i < hd; ++i) s += sq[i] * kload(Kc, base + (size_t)t * d + i);
+        s *= scale;
+        sc[t] = s;
+        mx = s > mx ? s : mx;
+    }
+    mx = block_max256(mx, red);
+    AT den = 0;
+    for (int t = tid; t <= ri.pos; t += 256) {
+        AT e = exp(sc[t] - mx);
+        sc[t] = e;
+        den += e;
+    }
+    den = block_sum256(den, red);  // also orders the sc[] writes before the reads below
+    const int i = tid % hd, sl = tid / hd, nsl = 256 / hd;
+    AT acc = 0;
+    for (int t = sl; t <= ri.pos; t += nsl) acc += sc[t] * kload(Vc, base + (size_t)t * d + i);
+    part[tid] = acc;
+    __syncthreads();
+    if (tid < hd) {
+        AT o = 0;
+        for (int s2 = 0; s2 < nsl; ++s2) o += part[s2 * hd + tid];
+        O[(size_t)R * d + (size_t)h * hd + tid] = o / den;
+    }
+}
+
+template <class Cfg>
+__global__ void swiglu_kernel(typename Cfg::AT* U, int m, size_t total) {
+    using AT = typename Cfg::AT;
+    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    size_t row = idx / m, i = idx - row * m;
+    AT a = U[row * 2 * m + i], b = U[row * 2 * m + m + i];
+    U[row * 2 * m + i] = a / ((AT)1 + exp(-a)) * b;
+}
+
+// ------------------------------------------------------------------ draft head input
+
+// DIN[s] = [previous head output (target hidden for the first draft) | E[left] | E[up]]
+// for draft i (1-based) of every sequence.
+template <class Cfg>
+__global__ void draft_input_kernel(typename Cfg::AT* DIN, const typename Cfg::AT* prev,
+                                   const typename Cfg::WT* E, const int32_t* n_arr, const int32_t* k_eff,
+                                   const int32_t* grid, const int32_t* draft, int i, int B, int N, int IW,
+                                   int kstride, int d) {
+    using AT = typename Cfg::AT;
+    const int s = blockIdx.x, b = s % B;
+    AT* out = DIN + (size_t)s * 3 * d;
+    if (i > k_eff[b]) {
+        for (int c = threadIdx.x; c < 3 * d; c += blockDim.x) out[c] = 0;
+        return;
+    }
+    const int n = n_arr[b], t = n - 1 + i;
+    const int left = (i == 1) ? grid[(size_t)b * N + n - 1] : draft[b * kstride + i - 2];
+    const int up = (t >= IW) ? grid[(size_t)b * N + t - IW] : -1;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) {
+        out[c] = prev[(size_t)s * d + c];
+        out[d + c] = w1(E, (size_t)left * d + c);
+        out[2 * d + c] = up >= 0 ? w1(E, (size_t)up * d + c) : (AT)0;
+    }
+}
+
+template <class Cfg>
+__global__ void keep_hprev_prefill_kernel(typename Cfg::AT* hprev, const typename Cfg::AT* X, int C, int d) {
+    const int s = blockIdx.x;
+    for (int c = threadIdx.x; c < d; c += blockDim.x)
+        hprev[(size_t)s * d + c] = X[((size_t)s * C + C - 1) * d + c];
+}
+
+// ------------------------------------------------------------------ launchers
+
+#define DISPATCH(ctx, CALL)                       \
+    do {                                          \
+        if ((ctx)->cfg.dtype == HAWK_FP32) {      \
+            using Cfg = CfgF32;                   \
+            CALL;                                 \
+        } else {                                  \
+            using Cfg = CfgBF16;                  \
+            CALL;                                 \
+        }                                         \
+    } while (0)
+
+template <class Cfg> static const typename Cfg::WT* wptr(hawk_ctx* c, size_t blob_off) {
+    return reinterpret_cast<const typename Cfg::WT*>(c->ws + c->off.blob + blob_off);
+}
+
+void launch_embed_rows(hawk_ctx* c, const RowMap& map, int M) {
+    DISPATCH(c, (embed_rows_kernel<Cfg><<<M, 256, 0, c->stream>>>(
+                    wsp<typename Cfg::AT>(c, c->off.x), wptr<Cfg>(c, c->w.E), map, wsp<int32_t>(c, c->off.grid),
+                    wsp<int32_t>(c, c->off.draft), c->N, c->kmax + 1, c->d)));
+}
+
+void launch_cond_rows(hawk_ctx* c, int M) {
+    size_t total = (size_t)M * c->d;
+    DISPATCH(c, (cond_rows_kernel<Cfg><<<(unsigned)((total + 255) / 256), 256, 0, c->stream>>>(
+                    wsp<typename Cfg::AT>(c, c->off.x), wsp<float>(c, c->off.cond), total)));
+}
+
+void launch_rmsnorm(hawk_ctx* c, size_t off_in, size_t in_stride, size_t off_gain, size_t off_out, int M) {
+    DISPATCH(c, (rmsnorm_kernel<Cfg><<<M, 256, 0, c->stream>>>(
+                    wsp<typename Cfg::AT>(c, off_in), wptr<Cfg>(c, off_gain), wsp<typename Cfg::AT>(c, off_out),
+                    c->d, in_stride, c->cfg.rms_eps)));
+}
+
+void launch_gemm(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, int K, size_t off_y, int ldy,
+                 int M, bool accumulate, bool out_f32) {
+    constexpr int RT = 8;
+    dim3 grid((N + 3) / 4, (M + RT - 1) / RT);
+    if (out_f32) {
+        DISPATCH(c, (gemm_rows_kernel<Cfg, RT, float><<<grid, 256, 0, c->stream>>>(
+                        wsp<typename Cfg::AT>(c, off_a), lda, wptr<Cfg>(c, w_off), N, K, wsp<float>(c, off_y), ldy,
+                        M, accumulate ? 1 : 0)));
+    } else {
+        DISPATCH(c, (gemm_rows_kernel<Cfg, RT, typename Cfg::AT><<<grid, 256, 0, c->stream>>>(
+                        wsp<typename Cfg::AT>(c, off_a), lda, wptr<Cfg>(c, w_off), N, K,
+                        wsp<typename Cfg::AT>(c, off_y), ldy, M, accumulate ? 1 : 0)));
+    }
+}
+
+void launch_rope_append(hawk_ctx* c, const RowMap& map, int layer, int M) {
+    DISPATCH(c, (rope_append_kernel<Cfg><<<M, 256, 0, c->stream>>>(
+                    wsp<typename Cfg::AT>(c, c->off.qkv), wsp<typename Cfg::KT>(c, c->off.kc),
+                    wsp<typename Cfg::KT>(c, c->off.vc), map, wsp<double>(c, c->off.inv_freq), layer, c->d, c->hd,
+                    c->Smax, c->Tmax)));
+}
+
+void launch_attention(hawk_ctx* c, const RowMap& map, int layer, int M) {
+    dim3 grid(c->H, M);
+    DISPATCH(c, (attention_kernel<Cfg><<<grid, 256, (size_t)(c->Tmax + c->hd + 256) * sizeof(typename Cfg::AT),
+                                         c->stream>>>(
+                    wsp<typename Cfg::AT>(c, c->off.qkv), wsp<typename Cfg::KT>(c, c->off.kc),
+                    wsp<typename Cfg::KT>(c, c->off.vc), wsp<typename Cfg::AT>(c, c->off.o), map, layer, c->d, c->hd,
+                    c->Smax, c->Tmax)));
+}
+
+void launch_swiglu(hawk_ctx* c, int M) {
+    size_t total = (size_t)M * c->m;
+    DISPATCH(c, (swiglu_kernel<Cfg><<<(unsigned)((total + 255) / 256), 256, 0, c->stream>>>(
+                    wsp<typename Cfg::AT>(c, c->off.u), c->m, total)));
+}
+
+void launch_draft_input(hawk_ctx* c, int i) {
+    // draft i writes its head output to g1 (i odd) / g0 (i even); draft i > 1 reads draft i-1's
+    size_t prev = (i == 1) ? c->off.hprev : (((i - 1) & 1) ? c->off.g1 : c->off.g0);
+    DISPATCH(c, (draft_input_kernel<Cfg><<<c->S, 256, 0, c->stream>>>(
+                    wsp<typename Cfg::AT>(c, c->off.din), wsp<typename Cfg::AT>(c, prev), wptr<Cfg>(c, c->w.E),
+                    wsp<int32_t>(c, c->off.n), wsp<int32_t>(c, c->off.k_eff), wsp<int32_t>(c, c->off.grid),
+                    wsp<int32_t>(c, c->off.draft), i, c->B, c->N, c->gw, c->kmax + 1, c->d)));
+}
+
+void launch_keep_hprev_prefill(hawk_ctx* c) {
+    DISPATCH(c, (keep_hprev_prefill_kernel<Cfg><<<c->S, 256, 0, c->stream>>>(
+                    wsp<typename Cfg::AT>(c, c->off.hprev), wsp<typename Cfg::AT>(c, c->off.x), c->C, c->d)));
+}
+
+}  // namespace hawk

@@ -1,0 +1,114 @@
+// Internal declarations shared by the translation units of libhawk (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/hawk.h"
+
+namespace hawk {
+
+constexpr int kMaxK = 63;          // slots 0..63 of the uniform generator are draft slots
+constexpr int kSlotDraft = 0, kSlotAcc = 64, kSlotFinal = 128;
+constexpr int kSampThreads = 1024; // threads of one sampling workgroup
+
+// Per-row result of the temperature/top-k warp: enough to re-evaluate the weight of any
+// token of the row without repeating the selection.
+struct WarpStat {
+    double total;       // sum of the kept weights exp(z - zmax)
+    float zmax;         // largest scaled logit
+    uint32_t tau;       // order-preserving key of the smallest kept scaled logit
+    int32_t tie_cut;    // entries equal to tau are kept up to and including this index
+    int32_t onehot;     // >= 0: the row is the point mass on this index (greedy / replay)
+};
+
+// Where the uniforms of a step come from: host-supplied tables already copied to the
+// device, or the counter-based generator.
+struct UniformSrc {
+    const float* draft;   // [B, k]
+    const float* acc;     // [B, k]
+    const float* fin;     // [B]
+    uint64_t seed;
+    const int32_t* step;  // device counter (generator mode)
+    int32_t use_gen;
+};
+
+// Where draft tokens come from: 0 = sampled, 1 = the [B,k] table in the `forced` buffer,
+// 2 = the replay grid at columns n + i - 1.
+struct DraftMode {
+    int32_t kind;
+    int32_t point_mass;
+};
+
+// How the rows of a forward pass map to sequences and positions.
+struct RowMap {
+    int32_t mode;          // 0 = prefill (row r of sequence s at position r), 1 = step rows
+    int32_t rows_per_seq;  // C in prefill, k+1 in a step
+    int32_t n_seq, batch, n_cond;
+    const int32_t* n;      // [B] committed tokens (step rows)
+    const int32_t* k_eff;  // [B] drafts in flight, -1 = finished (step rows)
+};
+
+struct Offsets {  // byte offsets into the workspace
+    size_t blob, kc, vc, n, k_eff, step, done, counters, grid, draft, forced, hprev, qstat, pstat;
+    size_t x, a, qkv, o, u, din, g0, g1, ga, logit_s, logit_b, dlogit_s, dlogit_b;
+    size_t u_draft, u_acc, u_fin, out_na, out_tok, inv_freq, replay, cond;
+    size_t total;
+};
+
+struct Weights {  // byte offsets into the blob
+    size_t E, g_f, W_out, W_d;
+    size_t g1[128], Wqkv[128], Wo[128], g2[128], W13[128], W2[128];
+};
+
+}  // namespace hawk
+
+struct hawk_ctx {
+    hawk_config cfg;
+    int L, d, H, hd, m, V, Vs, Smax, Bmax, Tmax, Nmax, Mmax, kmax;
+    size_t esz, asz, ksz;  // bytes of a weight, an activation, a cache element
+    uint8_t* ws;
+    hipStream_t stream;
+    hawk::Offsets off;
+    hawk::Weights w;
+    size_t blob_bytes;
+    // per image
+    int B, S, C, gh, gw, N, top_k, greedy;
+    float temperature, inv_t, cfg_scale;
+    int phase;   // 0 created, 1 loaded, 2 prefilled (draft next), 3 drafted (verify next)
+    int k_last;
+    int path;
+    void* pinned;  // small page-locked staging buffer for read-backs
+    hipEvent_t ev[3];
+    char err[256];
+};
+
+namespace hawk {
+
+template <typename T> inline T* wsp(hawk_ctx* c, size_t off) { return reinterpret_cast<T*>(c->ws + off); }
+
+// ---- launchers implemented in generic.hip (dtype chosen from ctx->cfg.dtype) ----
+void launch_embed_rows(hawk_ctx*, const RowMap&, int M);
+void launch_cond_rows(hawk_ctx*, int M);                       // X <- condition vectors
+// out[r] = rmsnorm(in[r * in_stride ...]) * gain, r < M (in_stride in elements)
+void launch_rmsnorm(hawk_ctx*, size_t off_in, size_t in_stride, size_t off_gain, size_t off_out, int M);
+// Y[M][N] (+)= A[M][K] * W[N][K]^T ; out_f32: store fp32 (logits) instead of activations
+void launch_gemm(hawk_ctx*, size_t off_a, int lda, size_t w_off, int N, int K, size_t off_y,
+                 int ldy, int M, bool accumulate, bool out_f32);
+void launch_rope_append(hawk_ctx*, const RowMap&, int layer, int M);
+void launch_attention(hawk_ctx*, const RowMap&, int layer, int M);
+void launch_swiglu(hawk_ctx*, int M);
+void launch_draft_input(hawk_ctx*, int i);                     // [g | E[left] | E[up]]
+void launch_keep_hprev_prefill(hawk_ctx*);
+
+// ---- launchers implemented in sampling.hip ----
+void launch_plan(hawk_ctx*, int k);
+void launch_first_token(hawk_ctx*, const UniformSrc&);
+void launch_draft_sample(hawk_ctx*, int i, int k, const UniformSrc&, const DraftMode&);
+void launch_verify_stats(hawk_ctx*, int k);
+void launch_accept_commit(hawk_ctx*, int k, const UniformSrc&);
+void launch_force_setup(hawk_ctx*, int cnt);
+void launch_force_commit(hawk_ctx*, int cnt);
+
+}  // namespace hawk

@@ -1,0 +1,499 @@
+// Sampling stage: guidance, temperature / top-k warp, inverse-CDF draws, the accept /
+// reject scan with residual resampling, and the commit of a step.
+//
+// Decisions (which logits survive top-k, where a uniform falls in a CDF, whether a draft is
+// accepted) are taken on fp32 logits with fp64 weights exp(z - zmax) and fp64 sums, so
+// that they do not depend on the order of summation beyond the last bits of an fp64.
+// One workgroup of 1024 threads handles one logit row; thread t owns the contiguous index
+// segment [t*E, (t+1)*E), which makes every scan an in-order prefix over token indices.
+// Reductions use wavefront shuffles, then one LDS exchange across the 16 waves.
+#include "hawk_internal.h"
+
+namespace hawk {
+
+namespace {
+
+constexpr int NT = kSampThreads;
+constexpr int NW = NT / 64;
+
+struct Shared {
+    unsigned hist[256];
+    double dred[NW];
+    int ired[NW];
+    float fred[NW];
+    unsigned ukred[NW];
+    // broadcast slots
+    unsigned b_prefix, b_remaining, b_count_eq;
+    int b_int;
+    double b_dbl;
+};
+
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+__device__ __forceinline__ float gen_uniform(uint64_t seed, uint32_t seq, uint32_t step, uint32_t slot) {
+    uint64_t ctr = ((uint64_t)seq << 44) | ((uint64_t)step << 8) | (uint64_t)(slot & 0xFFu);
+    uint64_t z = mix64(seed + 0x9E3779B97F4A7C15ull);
+    z = mix64(z + 0x9E3779B97F4A7C15ull * (ctr + 1));
+    return (float)(z >> 40) * (1.0f / 16777216.0f);
+}
+__device__ __forceinline__ float pick_uniform(const UniformSrc& u, const float* table, int idx, int b, int slot) {
+    return u.use_gen ? gen_uniform(u.seed, (uint32_t)b, (uint32_t)u.step[0], (uint32_t)slot) : table[idx];
+}
+
+// Order-preserving key of a float (larger value <=> larger key); -0 and +0 share a key.
+__device__ __forceinline__ unsigned fkey(float z) {
+    unsigned u = __float_as_uint(z);
+    if ((u << 1) == 0u) u = 0u;
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ double wave_sum_d(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// All block primitives below return the same value to every thread and may be called
+// back to back (each starts with a barrier that protects the exchange buffer).
+__device__ double block_sum_d(double v, Shared& sh) {
+    v = wave_sum_d(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh.dred[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double t = 0.0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) t += sh.dred[w];
+    return t;
+}
+__device__ float block_max_f(float v, Shared& sh) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh.fred[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float t = sh.fred[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) t = fmaxf(t, sh.fred[w]);
+    return t;
+}
+__device__ int block_min_i(int v, Shared& sh) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, 64));
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh.ired[threadIdx.x >> 6] = v;
+    __syncthreads();
+    int t = sh.ired[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) t = min(t, sh.ired[w]);
+    return t;
+}
+__device__ int block_max_i(int v, Shared& sh) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o, 64));
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh.ired[threadIdx.x >> 6] = v;
+    __syncthreads();
+    int t = sh.ired[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) t = max(t, sh.ired[w]);
+    return t;
+}
+// Exclusive prefix sums over the threads of the block, in thread order.
+__device__ double block_excl_scan_d(double v, Shared& sh) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    double inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        double t = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += t;
+    }
+    __syncthreads();
+    if (lane == 63) sh.dred[wave] = inc;
+    __syncthreads();
+    double base = 0.0;
+    for (int w = 0; w < wave; ++w) base += sh.dred[w];
+    return base + (inc - v);
+}
+__device__ int block_excl_scan_i(int v, Shared& sh) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int t = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += t;
+    }
+    __syncthreads();
+    if (lane == 63) sh.ired[wave] = inc;
+    __syncthreads();
+    int base = 0;
+    for (int w = 0; w < wave; ++w) base += sh.ired[w];
+    return base + (inc - v);
+}
+
+struct Seg { int j0, j1; };
+__device__ __forceinline__ Seg my_segment(int n) {
+    int e = (n + NT - 1) / NT;
+    Seg s;
+    s.j0 = min(n, (int)threadIdx.x * e);
+    s.j1 = min(n, s.j0 + e);
+    return s;
+}
+
+// Guided logits of one row into `out` (also the row every later pass reads).
+__device__ void combine_row(const float* lc, const float* lu, float scale, float* out, int n) {
+    for (int j = threadIdx.x; j < n; j += NT) out[j] = lu ? fmaf(scale, lc[j] - lu[j], lu[j]) : lc[j];
+    __syncthreads();
+}
+
+__device__ __forceinline__ bool kept(const WarpStat& st, float z, int j) {
+    unsigned k = fkey(z);
+    return k > st.tau || (k == st.tau && j <= st.tie_cut);
+}
+__device__ __forceinline__ double weight_of(const WarpStat& st, const float* l, float inv_t, int j) {
+    if (st.onehot >= 0) return j == st.onehot ? 1.0 : 0.0;
+    float z = l[j] * inv_t;
+    return kept(st, z, j) ? exp((double)z - (double)st.zmax) : 0.0;
+}
+
+// Temperature / top-k warp of the row l[0..n): arg-max point mass if greedy, otherwise
+// z = l * inv_t, keep the top_k largest z (equal values: lower index first).
+__device__ WarpStat warp_stats(const float* l, int n, float inv_t, int top_k, int greedy, Shared& sh) {
+    const Seg sg = my_segment(n);
+    WarpStat st;
+    st.total = 1.0; st.zmax = 0.f; st.tau = 0u; st.tie_cut = 0x7FFFFFFF; st.onehot = -1;
+    if (greedy) {
+        float best = -INFINITY;
+        for (int j = sg.j0; j < sg.j1; ++j) best = fmaxf(best, l[j]);
+        float gmax = block_max_f(best, sh);
+        int idx = 0x7FFFFFFF;
+        for (int j = sg.j0; j < sg.j1; ++j)
+            if (l[j] == gmax) { idx = j; break; }
+        st.onehot = block_min_i(idx, sh);
+        return st;
+    }
+    const int K = min(top_k, n);
+    if (K < n) {
+        unsigned prefix = 0u, mask = 0u, remaining = (unsigned)K, count_eq = 0u;
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            __syncthreads();
+            if (threadIdx.x < 256) sh.hist[threadIdx.x] = 0u;
+            __syncthreads();
+            for (int j = sg.j0; j < sg.j1; ++j) {
+                unsigned key = fkey(l[j] * inv_t);
+                if ((key & mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & 255u], 1u);
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                unsigned cum = 0u;
+                for (int bin = 255; bin >= 0; --bin) {
+                    unsigned h = sh.hist[bin];
+                    if (cum + h >= remaining) {
+                        sh.b_prefix = prefix | ((unsigned)bin << shift);
+                        sh.b_remaining = remaining - cum;
+                        sh.b_count_eq = h;
+                        break;
+                    }
+                    cum += h;
+                }
+            }
+            __syncthreads();
+            prefix = sh.b_prefix;
+            remaining = sh.b_remaining;
+            count_eq = sh.b_count_eq;
+            mask |= 255u << shift;
+        }
+        st.tau = prefix;
+        if (remaining < count_eq) {  // keep only the first `remaining` entries equal to tau
+            int c = 0;
+            for (int j = sg.j0; j < sg.j1; ++j) c += fkey(l[j] * inv_t) == prefix;
+            int before = block_excl_scan_i(c, sh);
+            __syncthreads();
+            if (before < (int)remaining && before + c >= (int)remaining) {
+                int seen = before;
+                for (int j = sg.j0; j < sg.j1; ++j)
+                    if (fkey(l[j] * inv_t) == prefix && ++seen == (int)remaining) { sh.b_int = j; break; }
+            }
+            __syncthreads();
+            st.tie_cut = sh.b_int;
+        }
+    }
+    float zm = -INFINITY;
+    for (int j = sg.j0; j < sg.j1; ++j) zm = fmaxf(zm, l[j] * inv_t);
+    st.zmax = block_max_f(zm, sh);
+    double s = 0.0;
+    for (int j = sg.j0; j < sg.j1; ++j) s += weight_of(st, l, inv_t, j);
+    st.total = block_sum_d(s, sh);
+    return st;
+}
+
+// Inverse-CDF draw over ascending index from weights w(j) >= 0 given by a functor:
+// first j whose running sum exceeds u * total, else the last j with positive weight.
+template <class WF>
+__device__ int inv_cdf(WF w, int n, double total, float u, Shared& sh) {
+    const Seg sg = my_segment(n);
+    double s = 0.0;
+    for (int j = sg.j0; j < sg.j1; ++j) s += w(j);
+    double c = block_excl_scan_d(s, sh);
+    const double target = (double)u * total;
+    int cand = 0x7FFFFFFF, last = -1;
+    for (int j = sg.j0; j < sg.j1; ++j) {
+        double wj = w(j);
+        if (wj > 0.0) {
+            c += wj;
+            last = j;
+            if (c > target) { cand = j; break; }
+        }
+    }
+    cand = block_min_i(cand, sh);
+    if (cand != 0x7FFFFFFF) return cand;
+    return block_max_i(last, sh);
+}
+
+// ---------------------------------------------------------------------------- kernels
+
+__global__ void plan_kernel(const int32_t* n, int32_t* k_eff, int32_t* draft, int32_t* step,
+                            unsigned long long* counters, int B, int N, int k, int kstride) {
+    int b = threadIdx.x;
+    if (b == 0) {
+        step[0] += 1;
+        bool any = false;
+        for (int j = 0; j < B; ++j) any = any || n[j] < N;
+        if (any) counters[3] += 1ull;  // lock-step iterations that still had work
+    }
+    if (b >= B) return;
+    int nb = n[b];
+    k_eff[b] = nb < N ? min(k, N - nb - 1) : -1;
+    for (int i = 0; i < kstride; ++i) draft[b * kstride + i] = -1;
+}
+
+struct SampParams {
+    int B, N, Vs, samp_lo, kstride, top_k, greedy, use_cfg;
+    float inv_t, cfg_scale;
+};
+
+// Token 0 of every prompt from the logits of the last condition row.
+__global__ __launch_bounds__(NT) void first_token_kernel(const float* logit_s, float* logit_b, int32_t* grid,
+                                                         int32_t* n, SampParams P, UniformSrc us) {
+    __shared__ Shared sh;
+    const int b = blockIdx.x;
+    float* row = logit_b + (size_t)b * P.kstride * P.Vs;
+    combine_row(logit_s + (size_t)b * P.Vs, P.use_cfg ? logit_s + (size_t)(P.B + b) * P.Vs : nullptr,
+                P.cfg_scale, row, P.Vs);
+    WarpStat st = warp_stats(row, P.Vs, P.inv_t, P.top_k, P.greedy, sh);
+    float u = pick_uniform(us, us.fin, b, b, kSlotFinal);
+    int idx = inv_cdf([&](int j) { return weight_of(st, row, P.inv_t, j); }, P.Vs, st.total, u, sh);
+    if (threadIdx.x == 0) {
+        grid[(size_t)b * P.N] = P.samp_lo + idx;
+        n[b] = 1;
+    }
+}
+
+// Draft i (1-based): guide, warp, then draw the token by inverse CDF - or, when a table
+// of forced tokens is given, take the token from it (teacher-forced drafting; with
+// point_mass the draft distribution becomes the point mass on that token).  Keeps the
+// guided row and its warp statistics for the accept test of the verify step.
+struct ForcedSrc {
+    const int32_t* table;  // nullptr: sample
+    int32_t stride;        // row stride of the table
+    int32_t relative;      // 1: column n[b] + i - 1 (replay grid), 0: column i - 1
+    int32_t point_mass;
+};
+
+__global__ __launch_bounds__(NT) void draft_sample_kernel(const float* dlogit_s, float* dlogit_b, const int32_t* n,
+                                                          const int32_t* k_eff, int32_t* draft, WarpStat* qstat,
+                                                          int i, int k, SampParams P, UniformSrc us, ForcedSrc fs) {
+    __shared__ Shared sh;
+    const int b = blockIdx.x;
+    if (i > k_eff[b]) return;
+    float* row = dlogit_b + ((size_t)b * P.kstride + (i - 1)) * P.Vs;
+    combine_row(dlogit_s + (size_t)b * P.Vs, P.use_cfg ? dlogit_s + (size_t)(P.B + b) * P.Vs : nullptr,
+                P.cfg_scale, row, P.Vs);
+    WarpStat st = warp_stats(row, P.Vs, P.inv_t, P.top_k, P.greedy, sh);
+    int tok;
+    if (fs.table) {
+        tok = fs.table[(size_t)b * fs.stride + (fs.relative ? n[b] : 0) + (i - 1)];
+        if (fs.point_mass) { st.onehot = tok - P.samp_lo; st.total = 1.0; }
+    } else {
+        float u = pick_uniform(us, us.draft, b * k + (i - 1), b, kSlotDraft + (i - 1));
+        tok = P.samp_lo + inv_cdf([&](int j) { return weight_of(st, row, P.inv_t, j); }, P.Vs, st.total, u, sh);
+    }
+    if (threadIdx.x == 0) {
+        draft[b * P.kstride + (i - 1)] = tok;
+        qstat[b * P.kstride + (i - 1)] = st;
+    }
+}
+
+// Guided target row r of prompt b and its warp statistics.
+__global__ __launch_bounds__(NT) void verify_stats_kernel(const float* logit_s, float* logit_b,
+                                                          const int32_t* k_eff, WarpStat* pstat, int k,
+                                                          SampParams P) {
+    __shared__ Shared sh;
+    const int r = blockIdx.x, b = blockIdx.y;
+    if (r > k_eff[b]) return;
+    float* row = logit_b + ((size_t)b * P.kstride + r) * P.Vs;
+    combine_row(logit_s + ((size_t)b * (k + 1) + r) * P.Vs,
+                P.use_cfg ? logit_s + ((size_t)(P.B + b) * (k + 1) + r) * P.Vs : nullptr, P.cfg_scale, row, P.Vs);
+    WarpStat st = warp_stats(row, P.Vs, P.inv_t, P.top_k, P.greedy, sh);
+    if (threadIdx.x == 0) pstat[b * P.kstride + r] = st;
+}
+
+// Accept scan, residual / bonus draw and commit for prompt b.
+__global__ __launch_bounds__(NT) void accept_commit_kernel(
+    const float* logit_b, const float* dlogit_b, const WarpStat* pstat, const WarpStat* qstat, const int32_t* k_eff,
+    const int32_t* draft, int32_t* grid, int32_t* n, const uint32_t* hid, uint32_t* hprev, int hid_words,
+    int32_t* out_na, int32_t* out_tok, unsigned long long* counters, int k, int n_seq_streams, SampParams P,
+    UniformSrc us) {
+    __shared__ Shared sh;
+    const int b = blockIdx.x;
+    const int ke = k_eff[b];
+    if (threadIdx.x <= k) out_tok[b * (k + 1) + threadIdx.x] = -1;
+    if (ke < 0) {
+        if (threadIdx.x == 0) out_na[b] = -1;
+        return;
+    }
+    // accept scan (every thread computes the same thing)
+    int a = 0;
+    for (; a < ke; ++a) {
+        const int dj = draft[b * P.kstride + a] - P.samp_lo;
+        const WarpStat ps = pstat[b * P.kstride + a], qs = qstat[b * P.kstride + a];
+        const double pd = weight_of(ps, logit_b + ((size_t)b * P.kstride + a) * P.Vs, P.inv_t, dj) / ps.total;
+        const double qd = weight_of(qs, dlogit_b + ((size_t)b * P.kstride + a) * P.Vs, P.inv_t, dj) / qs.total;
+        const float u = pick_uniform(us, us.acc, b * k + a, b, kSlotAcc + a);
+        if (!((double)u * qd < pd)) break;
+    }
+    const float uf = pick_uniform(us, us.fin, b, b, kSlotFinal);
+    const float* prow = logit_b + ((size_t)b * P.kstride + a) * P.Vs;
+    const WarpStat ps = pstat[b * P.kstride + a];
+    int y;
+    auto wp = [&](int j) { return weight_of(ps, prow, P.inv_t, j); };
+    if (a < ke) {
+        const float* qrow = dlogit_b + ((size_t)b * P.kstride + a) * P.Vs;
+        const WarpStat qs = qstat[b * P.kstride + a];
+        auto res = [&](int j) {
+            double r = weight_of(ps, prow, P.inv_t, j) / ps.total - weight_of(qs, qrow, P.inv_t, j) / qs.total;
+            return r > 0.0 ? r : 0.0;
+        };
+        const Seg sg = my_segment(P.Vs);
+        double s = 0.0;
+        for (int j = sg.j0; j < sg.j1; ++j) s += res(j);
+        const double R = block_sum_d(s, sh);
+        y = (R > 0.0) ? inv_cdf(res, P.Vs, R, uf, sh) : inv_cdf(wp, P.Vs, ps.total, uf, sh);
+    } else {
+        y = inv_cdf(wp, P.Vs, ps.total, uf, sh);
+    }
+    // commit: tokens, counters, hidden state of row a for the next draft
+    const int nb = n[b];
+    for (int s = b; s < n_seq_streams; s += P.B) {
+        const uint32_t* src = hid + ((size_t)s * (k + 1) + a) * hid_words;
+        uint32_t* dst = hprev + (size_t)s * hid_words;
+        for (int i = threadIdx.x; i < hid_words; i += NT) dst[i] = src[i];
+    }
+    __syncthreads();  // every thread has read n[b] before it changes
+    if (threadIdx.x == 0) {
+        for (int i = 0; i < a; ++i) {
+            int t = draft[b * P.kstride + i];
+            grid[(size_t)b * P.N + nb + i] = t;
+            out_tok[b * (k + 1) + i] = t;
+        }
+        grid[(size_t)b * P.N + nb + a] = P.samp_lo + y;
+        out_tok[b * (k + 1) + a] = P.samp_lo + y;
+        out_na[b] = a;
+        n[b] = nb + a + 1;
+        atomicAdd(&counters[0], 1ull);
+        atomicAdd(&counters[1], (unsigned long long)a);
+        atomicAdd(&counters[2], (unsigned long long)(a + 1));
+    }
+}
+
+__global__ void force_setup_kernel(const int32_t* n_from, const int32_t* forced, int32_t* n, int32_t* k_eff,
+                                   int32_t* draft, int B, int cnt, int kstride) {
+    int b = threadIdx.x;
+    if (b >= B) return;
+    n[b] = n_from[b];
+    k_eff[b] = cnt - 1;
+    for (int i = 0; i < kstride; ++i) draft[b * kstride + i] = i < cnt - 1 ? forced[b * cnt + i] : -1;
+}
+
+__global__ void force_commit_kernel(const int32_t* forced, int32_t* grid, int32_t* n, const uint32_t* hid,
+                                    uint32_t* hprev, int hid_words, int B, int N, int cnt, int n_seq_streams) {
+    const int b = blockIdx.x;
+    const int nb = n[b];
+    for (int s = b; s < n_seq_streams; s += B) {
+        const uint32_t* src = hid + ((size_t)s * cnt + (cnt - 1)) * hid_words;
+        uint32_t* dst = hprev + (size_t)s * hid_words;
+        for (int i = threadIdx.x; i < hid_words; i += blockDim.x) dst[i] = src[i];
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int i = 0; i < cnt; ++i) grid[(size_t)b * N + nb + i] = forced[b * cnt + i];
+        n[b] = nb + cnt;
+    }
+}
+
+SampParams samp_params(const hawk_ctx* c) {
+    SampParams P;
+    P.B = c->B; P.N = c->N; P.Vs = c->Vs; P.samp_lo = c->cfg.samp_lo; P.kstride = c->kmax + 1;
+    P.top_k = c->top_k; P.greedy = c->greedy; P.use_cfg = c->cfg.use_cfg;
+    P.inv_t = c->inv_t; P.cfg_scale = c->cfg_scale;
+    return P;
+}
+
+}  // namespace
+
+void launch_plan(hawk_ctx* c, int k) {
+    plan_kernel<<<1, 64 * ((c->B + 63) / 64), 0, c->stream>>>(wsp<int32_t>(c, c->off.n), wsp<int32_t>(c, c->off.k_eff),
+                                                            wsp<int32_t>(c, c->off.draft),
+                                                            wsp<int32_t>(c, c->off.step),
+                                                            wsp<unsigned long long>(c, c->off.counters), c->B, c->N,
+                                                            k, c->kmax + 1);
+}
+
+void launch_first_token(hawk_ctx* c, const UniformSrc& us) {
+    first_token_kernel<<<c->B, NT, 0, c->stream>>>(wsp<float>(c, c->off.logit_s), wsp<float>(c, c->off.logit_b),
+                                                   wsp<int32_t>(c, c->off.grid), wsp<int32_t>(c, c->off.n),
+                                                   samp_params(c), us);
+}
+
+void launch_draft_sample(hawk_ctx* c, int i, int k, const UniformSrc& us, const DraftMode& dm) {
+    ForcedSrc fs;
+    fs.table = nullptr; fs.stride = 0; fs.relative = 0; fs.point_mass = dm.point_mass;
+    if (dm.kind == 1) { fs.table = wsp<int32_t>(c, c->off.forced); fs.stride = k; }
+    if (dm.kind == 2) { fs.table = wsp<int32_t>(c, c->off.replay); fs.stride = c->N; fs.relative = 1; }
+    draft_sample_kernel<<<c->B, NT, 0, c->stream>>>(wsp<float>(c, c->off.dlogit_s), wsp<float>(c, c->off.dlogit_b),
+                                                    wsp<int32_t>(c, c->off.n), wsp<int32_t>(c, c->off.k_eff),
+                                                    wsp<int32_t>(c, c->off.draft), wsp<WarpStat>(c, c->off.qstat), i,
+                                                    k, samp_params(c), us, fs);
+}
+
+void launch_verify_stats(hawk_ctx* c, int k) {
+    verify_stats_kernel<<<dim3(k + 1, c->B), NT, 0, c->stream>>>(
+        wsp<float>(c, c->off.logit_s), wsp<float>(c, c->off.logit_b), wsp<int32_t>(c, c->off.k_eff),
+        wsp<WarpStat>(c, c->off.pstat), k, samp_params(c));
+}
+
+void launch_accept_commit(hawk_ctx* c, int k, const UniformSrc& us) {
+    accept_commit_kernel<<<c->B, NT, 0, c->stream>>>(
+        wsp<float>(c, c->off.logit_b), wsp<float>(c, c->off.dlogit_b), wsp<WarpStat>(c, c->off.pstat),
+        wsp<WarpStat>(c, c->off.qstat), wsp<int32_t>(c, c->off.k_eff), wsp<int32_t>(c, c->off.draft),
+        wsp<int32_t>(c, c->off.grid), wsp<int32_t>(c, c->off.n), wsp<uint32_t>(c, c->off.x),
+        wsp<uint32_t>(c, c->off.hprev), (int)(c->d * c->asz / 4), wsp<int32_t>(c, c->off.out_na),
+        wsp<int32_t>(c, c->off.out_tok), wsp<unsigned long long>(c, c->off.counters), k, c->S, samp_params(c), us);
+}
+
+void launch_force_setup(hawk_ctx* c, int cnt) {
+    force_setup_kernel<<<1, 64 * ((c->B + 63) / 64), 0, c->stream>>>(
+        wsp<int32_t>(c, c->off.u_draft), wsp<int32_t>(c, c->off.forced), wsp<int32_t>(c, c->off.n),
+        wsp<int32_t>(c, c->off.k_eff), wsp<int32_t>(c, c->off.draft), c->B, cnt, c->kmax + 1);
+}
+
+void launch_force_commit(hawk_ctx* c, int cnt) {
+    force_commit_kernel<<<c->B, 256, 0, c->stream>>>(wsp<int32_t>(c, c->off.forced), wsp<int32_t>(c, c->off.grid),
+                                                     wsp<int32_t>(c, c->off.n), wsp<uint32_t>(c, c->off.x),
+                                                     wsp<uint32_t>(c, c->off.hprev), (int)(c->d * c->asz / 4), c->B,
+                                                     c->N, cnt, c->S);
+}
+
+}  // namespace hawk

@@ -1,0 +1,221 @@
+"""ctypes binding of libhawk.so: argument marshalling only, same call names as the C ABI."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libhawk.so")
+_lib = None
+
+HAWK_FP32, HAWK_BF16 = 0, 1
+
+
+class HawkError(RuntimeError):
+    def __init__(self, code: int, where: str, text: str = ""):
+        super().__init__(f"{where} failed with code {code}: {text}")
+        self.code = code
+
+
+class HawkConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "n_layers", "d_model", "n_heads", "d_mlp", "vocab", "samp_lo", "samp_n", "max_cond",
+        "max_grid_h", "max_grid_w", "max_batch", "k_max", "dtype", "use_cfg")] + [
+        ("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+
+    @classmethod
+    def from_shape(cls, s, *, batch: Optional[int] = None, k_max: Optional[int] = None):
+        """From a synth.HawkShape-like object (duck typed: only attributes are read)."""
+        return cls(n_layers=s.n_layers, d_model=s.d_model, n_heads=s.n_heads, d_mlp=s.d_mlp, vocab=s.vocab,
+                   samp_lo=s.samp_lo, samp_n=s.samp_n, max_cond=s.n_cond, max_grid_h=s.grid_h,
+                   max_grid_w=s.grid_w, max_batch=s.batch if batch is None else batch,
+                   k_max=s.k if k_max is None else k_max, dtype=HAWK_FP32 if s.dtype == "fp32" else HAWK_BF16,
+                   use_cfg=int(s.cfg_scale != 1.0), rms_eps=s.rms_eps, rope_theta=s.rope_theta)
+
+
+class HawkStats(C.Structure):
+    _fields_ = [("steps", C.c_int64), ("accepted", C.c_int64), ("tokens", C.c_int64), ("iters", C.c_int64),
+                ("ms_prefill", C.c_float), ("ms_decode", C.c_float)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+EXPORTS = {
+    "hawk_workspace_bytes": (C.c_size_t, [C.POINTER(HawkConfig)]),
+    "hawk_create": (C.c_int, [C.POINTER(HawkConfig), C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_void_p)]),
+    "hawk_destroy": (None, [C.c_void_p]),
+    "hawk_last_error": (C.c_char_p, [C.c_void_p]),
+    "hawk_load": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t]),
+    "hawk_prefill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float,
+                               C.c_int, C.c_float, C.c_void_p]),
+    "hawk_draft": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]),
+    "hawk_draft_forced": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int]),
+    "hawk_verify": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "hawk_generate": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                C.c_float, C.c_int, C.c_float, C.c_uint64, C.c_void_p, C.c_void_p,
+                                C.POINTER(HawkStats)]),
+    "hawk_force": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]),
+    "hawk_get_n": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "hawk_get_grid": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "hawk_get_logits": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int]),
+    "hawk_get_draft_logits": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int]),
+    "hawk_set_path": (C.c_int, [C.c_void_p, C.c_int]),
+}
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> C.CDLL:
+    """Loads the built HIP library; never falls back to anything else."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise HawkError(-4, "load_library", f"{_LIB_PATH} is missing: run `python __graft_entry__.py` "
+                                                "(or paper_2510_25739_amd/build.py) first")
+        L = C.CDLL(_LIB_PATH)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def workspace_bytes(cfg: HawkConfig) -> int:
+    return int(load_library().hawk_workspace_bytes(C.byref(cfg)))
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+class Hawk:
+    """One context: device workspace (a torch uint8 tensor) + the C handle."""
+
+    def __init__(self, cfg: HawkConfig, device: str = "cuda:0", stream=None):
+        import torch  # device memory and stream only
+        self._L = load_library()
+        self.cfg = cfg
+        nbytes = workspace_bytes(cfg)
+        if nbytes == 0:
+            raise HawkError(-1, "hawk_workspace_bytes", "invalid configuration")
+        if not torch.cuda.is_available():
+            raise HawkError(-4, "Hawk", "no GPU visible: the HIP path has no CPU fallback")
+        self._torch = torch
+        self._dev = torch.device(device)
+        with torch.cuda.device(self._dev):
+            self._ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=self._dev)
+            self._stream = stream if stream is not None else torch.cuda.current_stream(self._dev)
+        base = self._ws.data_ptr()
+        self._ws_ptr = (base + 255) & ~255
+        h = C.c_void_p()
+        rc = self._L.hawk_create(C.byref(cfg), C.c_void_p(self._ws_ptr), nbytes, C.c_void_p(self._stream.cuda_stream),
+                                 C.byref(h))
+        if rc != 0:
+            raise HawkError(rc, "hawk_create")
+        self._h = h
+        self.v_s = cfg.samp_n if cfg.samp_n else cfg.vocab
+        self.batch = 0
+        self.n_img = 0
+
+    # -- plumbing
+    def _chk(self, rc, where):
+        if rc != 0:
+            raise HawkError(rc, where, self._L.hawk_last_error(self._h).decode())
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._L.hawk_destroy(self._h)
+            self._h = None
+            self._ws = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def stream_handle(self) -> int:
+        return int(self._stream.cuda_stream)
+
+    # -- the C calls
+    def set_path(self, path: int):
+        self._chk(self._L.hawk_set_path(self._h, path), "hawk_set_path")
+
+    def load(self, blob: np.ndarray):
+        blob = np.ascontiguousarray(blob, dtype=np.uint8)
+        self._chk(self._L.hawk_load(self._h, _p(blob), blob.nbytes), "hawk_load")
+
+    def prefill(self, cond, uncond, grid_h, grid_w, temperature, top_k, cfg_scale, u_first):
+        cond = _f32(cond)
+        unc = None if uncond is None else _f32(uncond)
+        self.batch, self.n_img = cond.shape[0], grid_h * grid_w
+        self._chk(self._L.hawk_prefill(self._h, _p(cond), _p(unc), cond.shape[0], cond.shape[1], grid_h, grid_w,
+                                       temperature, top_k, cfg_scale, _p(_f32(u_first))), "hawk_prefill")
+
+    def draft(self, k, u_draft, want=True):
+        u = _f32(u_draft) if k > 0 else None
+        out = np.full((self.batch, max(k, 1)), -1, dtype=np.int32) if want else None
+        self._chk(self._L.hawk_draft(self._h, k, _p(u), _p(out) if (want and k > 0) else None), "hawk_draft")
+        return None if out is None else out[:, :k]
+
+    def draft_forced(self, k, tokens, point_mass):
+        t = _i32(tokens) if k > 0 else None
+        self._chk(self._L.hawk_draft_forced(self._h, k, _p(t), int(point_mass)), "hawk_draft_forced")
+
+    def verify(self, k, u_acc, u_final, want=True):
+        ua = _f32(u_acc) if k > 0 else None
+        na = np.zeros(self.batch, dtype=np.int32) if want else None
+        toks = np.zeros((self.batch, k + 1), dtype=np.int32) if want else None
+        self._chk(self._L.hawk_verify(self._h, k, _p(ua), _p(_f32(u_final)), _p(na), _p(toks)), "hawk_verify")
+        return na, toks
+
+    def generate(self, cond, uncond, grid_h, grid_w, k, temperature, top_k, cfg_scale, seed, replay=None):
+        cond = _f32(cond)
+        unc = None if uncond is None else _f32(uncond)
+        self.batch, self.n_img = cond.shape[0], grid_h * grid_w
+        grid = np.zeros((self.batch, self.n_img), dtype=np.int32)
+        rp = None if replay is None else _i32(replay)
+        st = HawkStats()
+        self._chk(self._L.hawk_generate(self._h, _p(cond), _p(unc), cond.shape[0], cond.shape[1], grid_h, grid_w, k,
+                                        temperature, top_k, cfg_scale, seed, _p(rp), _p(grid), C.byref(st)),
+                  "hawk_generate")
+        return grid, st.as_dict()
+
+    def force(self, n_from, tokens):
+        t = _i32(tokens).reshape(self.batch, -1)
+        self._chk(self._L.hawk_force(self._h, _p(_i32(n_from)), _p(t), t.shape[1]), "hawk_force")
+
+    def n(self):
+        out = np.zeros(self.batch, dtype=np.int32)
+        self._chk(self._L.hawk_get_n(self._h, _p(out)), "hawk_get_n")
+        return out
+
+    def grid(self):
+        out = np.zeros((self.batch, self.n_img), dtype=np.int32)
+        self._chk(self._L.hawk_get_grid(self._h, _p(out)), "hawk_get_grid")
+        return out
+
+    def logits(self, rows):
+        out = np.zeros((self.batch, rows, self.v_s), dtype=np.float32)
+        self._chk(self._L.hawk_get_logits(self._h, _p(out), rows), "hawk_get_logits")
+        return out
+
+    def draft_logits(self, k):
+        out = np.zeros((self.batch, k, self.v_s), dtype=np.float32)
+        self._chk(self._L.hawk_get_draft_logits(self._h, _p(out), k), "hawk_get_draft_logits")
+        return out

@@ -1,0 +1,70 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared symbol, and the
+entry points that need no GPU behave (workspace sizing, rejection of bad configurations)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def H():
+    import paper_2510_25739_amd as H
+    if not os.path.exists(H.lib_path()):
+        from paper_2510_25739_amd import build
+        build.build()
+    return H
+
+
+def test_every_declared_symbol_is_exported(H):
+    hdr = open(os.path.join(ROOT, "include", "hawk.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(hawk_[a-z_]+)\s*\(", hdr))
+    assert {"hawk_load", "hawk_prefill", "hawk_draft", "hawk_verify", "hawk_generate"} <= declared
+    lib = C.CDLL(H.lib_path())
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(H.hawk.EXPORTS), "binding and header list different calls"
+
+
+def test_workspace_bytes_and_bad_configs(H):
+    for s in synth.CONFIGS.values():
+        cfg = H.HawkConfig.from_shape(s)
+        n = H.workspace_bytes(cfg)
+        kv = 2 * s.n_layers * s.n_seq * (s.n_cond + s.n_img) * s.d_model * (8 if s.dtype == "fp32" else 2)
+        assert n > s.n_params() * s.itemsize + kv
+        assert n < 2.5 * (s.n_params() * s.itemsize + kv) + (1 << 30)
+    good = H.HawkConfig.from_shape(synth.CONFIGS[0])
+    for field, bad in (("d_model", 250), ("n_heads", 3), ("k_max", 64), ("samp_n", 5000), ("dtype", 7),
+                       ("max_batch", 0), ("n_layers", 0), ("d_mlp", 1001)):
+        cfg = H.HawkConfig.from_buffer_copy(good)
+        setattr(cfg, field, bad)
+        assert H.workspace_bytes(cfg) == 0, field
+
+
+def test_create_rejects_bad_arguments_without_touching_the_device(H):
+    lib = H.load_library()
+    cfg = H.HawkConfig.from_shape(synth.CONFIGS[0])
+    h = C.c_void_p()
+    assert lib.hawk_create(C.byref(cfg), None, 1 << 30, None, C.byref(h)) == -1       # null workspace
+    assert lib.hawk_create(C.byref(cfg), C.c_void_p(4096 + 8), 1 << 30, None, C.byref(h)) == -1  # misaligned
+    assert lib.hawk_create(C.byref(cfg), C.c_void_p(4096), 16, None, C.byref(h)) == -3  # too small
+    bad = H.HawkConfig.from_buffer_copy(cfg)
+    bad.d_model = 7
+    assert lib.hawk_create(C.byref(bad), C.c_void_p(4096), 1 << 30, None, C.byref(h)) == -1
+    assert not h.value
+    assert lib.hawk_load(None, None, 0) == -1
+    assert lib.hawk_last_error(None) == b"null context"
+
+
+def test_product_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2510_25739_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f

@@ -1,0 +1,357 @@
+"""GPU parity: the HIP path against the CPU oracle, element by element, through the C ABI.
+
+fp32 configurations must give bit-exact tokens, accept counts and draft tokens; bf16
+configurations must keep guided logits within 2e-2 (max abs) of the oracle and take the
+same accept / reject / token decisions on at least 99.9 % of steps, measured with
+re-synchronisation onto the oracle's tokens after a disagreement.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    import torch
+    import paper_2510_25739_amd as H
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return H
+
+
+def make_pair(H, shape, seed=0, std=0.02, batch=None, k_max=None, path=1):
+    blob = synth.make_weights(shape, seed=seed, std=std)
+    hk = H.Hawk(H.HawkConfig.from_shape(shape, batch=batch, k_max=k_max))
+    hk.load(blob)
+    hk.set_path(path)
+    orc = oracle.Oracle.from_shape(shape, blob, batch=batch, k_max=k_max)
+    return blob, hk, orc
+
+
+def lockstep(shape, hk, orc, k, *, u_seed=1, batch=None, max_steps=10 ** 9, replay=None, temperature=None,
+             top_k=None):
+    """Runs both sides step by step on the same host uniforms and returns counters.
+
+    Per step, from the same committed prefix:
+      1. both draft with the same uniforms (`draft_same` counts identical draft tokens);
+         the oracle's sampling stage applied to the GPU's own draft logits must reproduce
+         the GPU's draft tokens exactly (`stage_bad` counts violations);
+      2. if the drafts differ, the GPU re-drafts teacher-forced onto the oracle's tokens,
+         so that both verify the same candidates;
+      3. both verify; `decision_same` counts identical accept counts, `token_same`
+         identical emitted tokens; the oracle's accept/resample stage applied to the GPU's
+         own logits must reproduce the GPU's result exactly (`stage_bad`);
+      4. on any difference the GPU is forced back onto the oracle's tokens.
+    """
+    B = shape.batch if batch is None else batch
+    T = shape.temperature if temperature is None else temperature
+    K = shape.top_k if top_k is None else top_k
+    lo = shape.samp_lo
+    cond = synth.make_cond(shape, seed=2, batch=B)
+    unc = synth.make_cond(shape, seed=3, batch=B) if shape.use_cfg else None
+    rng = np.random.Generator(np.random.PCG64(u_seed))
+
+    def uni(*shp):
+        return (rng.integers(0, 1 << 24, size=shp).astype(np.float32) / np.float32(1 << 24)).astype(np.float32)
+
+    u0 = uni(B)
+    hk.prefill(cond, unc, shape.grid_h, shape.grid_w, T, K, shape.cfg_scale, u0)
+    orc.prefill(cond, unc, T, K, shape.cfg_scale, u0)
+    res = dict(steps=0, draft_same=0, decision_same=0, token_same=0, stage_bad=0, max_logit_err=0.0,
+               max_draft_logit_err=0.0, accepted=0, first_same=True)
+    # token 0: the oracle's sampling stage on the GPU's own logits must give the GPU's token
+    l0 = hk.logits(1)
+    for b in range(B):
+        w, z = oracle.warp(l0[b, 0], T, K)
+        res["stage_bad"] += int(lo + oracle.inv_cdf(w, z, float(u0[b])) != hk.grid()[b, 0])
+    if not np.array_equal(hk.grid()[:, 0], orc.grid()[:, 0]):
+        res["first_same"] = False  # prefill samples token 0 itself: nothing to re-synchronise onto
+        return res
+    N = shape.n_img
+    lq_g = None
+    while (orc.n() < N).any() and res["steps"] < max_steps:
+        n0 = orc.n().copy()
+        ke = np.array([max(0, min(k, N - n0[b] - 1)) if n0[b] < N else -1 for b in range(B)])
+        ud, ua, uf = uni(B, max(k, 1))[:, :k], uni(B, max(k, 1))[:, :k], uni(B)
+        if replay is not None:
+            d_o = np.full((B, k), lo, np.int32)
+            for b in range(B):
+                if ke[b] > 0:
+                    d_o[b, :ke[b]] = replay[b, n0[b]:n0[b] + ke[b]]
+            hk.draft_forced(k, d_o, True)
+            orc.draft_forced(k, d_o, True)
+            res["draft_same"] += 1
+        else:
+            d_o = orc.draft(k, ud)
+            d_g = hk.draft(k, ud)
+            if k > 0:
+                lq_g = hk.draft_logits(k)
+                for b in range(B):
+                    for i in range(max(ke[b], 0)):
+                        w, z = oracle.warp(lq_g[b, i], T, K)
+                        res["stage_bad"] += int(lo + oracle.inv_cdf(w, z, float(ud[b, i])) != d_g[b, i])
+            if np.array_equal(d_g, d_o):
+                res["draft_same"] += 1
+            else:
+                hk.draft_forced(k, np.where(d_o >= 0, d_o, lo).astype(np.int32), False)
+            if k > 0:
+                lq_g, lq_o = hk.draft_logits(k), orc.draft_logits()
+                for b in range(B):
+                    if ke[b] > 0:
+                        res["max_draft_logit_err"] = max(res["max_draft_logit_err"],
+                                                         float(np.abs(lq_g[b, :ke[b]] - lq_o[b, :ke[b]]).max()))
+        na_g, t_g = hk.verify(k, ua, uf)
+        na_o, t_o = orc.verify(k, ua, uf)
+        lp_g, lp_o = hk.logits(k + 1), orc.logits()
+        for b in range(B):
+            if ke[b] < 0:
+                continue
+            res["max_logit_err"] = max(res["max_logit_err"],
+                                       float(np.abs(lp_g[b, :ke[b] + 1] - lp_o[b, :ke[b] + 1]).max()))
+            q_rows = lq_g[b, :ke[b]] if (k > 0 and replay is None) else None
+            a_s, t_s = oracle.spec_sample(lp_g[b, :ke[b] + 1], q_rows, d_o[b, :ke[b]] - lo, ua[b, :ke[b]],
+                                          float(uf[b]), T, K, q_onehot=replay is not None)
+            ok = a_s == na_g[b] and np.array_equal(t_s + lo, t_g[b, :a_s + 1])
+            res["stage_bad"] += int(not ok)
+        res["steps"] += 1
+        res["accepted"] += int(np.maximum(na_o, 0).sum())
+        dec = np.array_equal(na_g, na_o)
+        tok = np.array_equal(t_g, t_o)
+        res["decision_same"] += int(dec)
+        res["token_same"] += int(dec and tok)
+        if not (dec and tok):
+            if B != 1:
+                break
+            cnt = int(na_o[0]) + 1
+            hk.force(n0, orc.grid()[:, n0[0]:n0[0] + cnt])
+        assert np.array_equal(hk.n(), orc.n())
+    res["grid_equal"] = np.array_equal(hk.grid(), orc.grid())
+    return res
+
+
+def assert_exact(res, min_steps=1):
+    assert res["first_same"] and res["stage_bad"] == 0, res
+    assert res["steps"] >= min_steps
+    assert res["draft_same"] == res["decision_same"] == res["token_same"] == res["steps"], res
+    assert res["grid_equal"]
+
+
+# ----------------------------------------------------------------------------- fp32: bit exact
+
+def test_config0_generate_bit_exact(H):
+    s = synth.CONFIGS[0]
+    blob, hk, orc = make_pair(H, s)
+    cond = synth.make_cond(s, seed=2)
+    for seed in (1, 2):
+        g, st = hk.generate(cond, None, s.grid_h, s.grid_w, s.k, s.temperature, s.top_k, 1.0, seed)
+        r, rst = orc.generate(cond, None, s.k, s.temperature, s.top_k, 1.0, seed)
+        assert np.array_equal(g, r)
+        assert (st["steps"], st["accepted"], st["tokens"], st["iters"]) == \
+               (rst["steps"], rst["accepted"], rst["tokens"], rst["iters"])
+        assert st["tokens"] == s.n_img - 1
+
+
+def test_config0_host_uniforms_step_by_step(H):
+    s = synth.CONFIGS[0]
+    blob, hk, orc = make_pair(H, s)
+    res = lockstep(s, hk, orc, s.k, u_seed=1)
+    assert_exact(res, min_steps=30)
+    assert res["max_logit_err"] < 1e-5 and res["max_draft_logit_err"] < 1e-5
+
+
+@pytest.mark.parametrize("k", [0, 1, 8])
+def test_fp32_other_draft_lengths(H, k):
+    s = synth.CONFIGS[0].replace(n_layers=1)
+    blob, hk, orc = make_pair(H, s, k_max=8)
+    res = lockstep(s, hk, orc, k, u_seed=5 + k)
+    assert_exact(res)
+
+
+@pytest.mark.parametrize("vocab,samp,top_k", [(16384, (0, 0), 1000), (16001, (0, 0), 16001), (9000, (4, 8192), 2000),
+                                              (4096, (0, 0), 1), (70, (3, 50), 7)])
+def test_fp32_sampling_stage_over_vocab_sizes(H, vocab, samp, top_k):
+    # a thin model in front of a wide vocabulary: exercises top-k selection, ragged index
+    # segments and the sampled slice at the paper-sized codebooks
+    s = synth.HawkShape("wide", 1, 64, 2, 128, vocab, 4, 3, 4, 3, dtype="fp32", top_k=top_k,
+                        samp_lo=samp[0], samp_n=samp[1])
+    blob, hk, orc = make_pair(H, s, std=0.05)
+    res = lockstep(s, hk, orc, 3, u_seed=7)
+    assert_exact(res)
+    assert res["max_logit_err"] < 1e-5
+
+
+def test_fp32_quantised_logits_exercise_topk_ties(H):
+    # weights on a coarse grid make many logits exactly equal: the tie rule decides top-k
+    s = synth.HawkShape("ties", 1, 16, 2, 16, 512, 2, 3, 3, 2, dtype="fp32", top_k=100)
+    blob = synth.make_weights(s, seed=4, std=0.5)
+    lay = synth.blob_layout(s)
+    off, shp = lay["W_out"]
+    w = blob[off:off + int(np.prod(shp)) * 4].view(np.float32)
+    w[:] = np.sign(w) * 0.25  # +-0.25 only: logits take few distinct values
+    hk = H.Hawk(H.HawkConfig.from_shape(s))
+    hk.load(blob)
+    orc = oracle.Oracle.from_shape(s, blob)
+    res = lockstep(s, hk, orc, 2, u_seed=9)
+    # the two sides may round a logit differently (different summation order), but the
+    # sampling stage itself must follow the tie rule exactly on the logits it is given
+    assert res["stage_bad"] == 0 and res["steps"] >= 4, res
+
+
+def test_fp32_greedy_matches_oracle_and_replay_accepts_all(H):
+    s = synth.CONFIGS[0].replace(n_layers=1, temperature=0.0)
+    blob, hk, orc = make_pair(H, s)
+    cond = synth.make_cond(s, seed=2)
+    g, st = hk.generate(cond, None, s.grid_h, s.grid_w, 0, 0.0, s.top_k, 1.0, 3)   # plain AR, greedy
+    r, _ = orc.generate(cond, None, 0, 0.0, s.top_k, 1.0, 3)
+    assert np.array_equal(g, r) and st["accepted"] == 0 and st["steps"] == s.n_img - 1
+    g2, st2 = hk.generate(cond, None, s.grid_h, s.grid_w, s.k, 0.0, s.top_k, 1.0, 3)  # speculative, greedy
+    assert np.array_equal(g2, g)
+    g3, st3 = hk.generate(cond, None, s.grid_h, s.grid_w, s.k, 0.0, s.top_k, 1.0, 3, replay=g)
+    assert np.array_equal(g3, g)
+    assert st3["steps"] == -(-(s.n_img - 1) // (s.k + 1)) and st3["tokens"] == s.n_img - 1
+
+
+def test_fp32_guidance_and_batch(H):
+    s = synth.CONFIGS[0].replace(n_layers=1, cfg_scale=2.0, batch=3, grid_h=4, grid_w=6)
+    blob, hk, orc = make_pair(H, s)
+    res = lockstep(s, hk, orc, 4, u_seed=11)
+    assert_exact(res)
+    assert res["max_logit_err"] < 1e-5
+    cond, unc = synth.make_cond(s, seed=2), synth.make_cond(s, seed=3)
+    g, st = hk.generate(cond, unc, s.grid_h, s.grid_w, 4, 1.0, s.top_k, 2.0, 21)
+    r, rst = orc.generate(cond, unc, 4, 1.0, s.top_k, 2.0, 21)
+    assert np.array_equal(g, r) and st["steps"] == rst["steps"] and st["iters"] == rst["iters"]
+
+
+def test_fp32_force_and_single_token_grid(H):
+    s = synth.CONFIGS[0].replace(n_layers=1)
+    blob, hk, orc = make_pair(H, s)
+    cond = synth.make_cond(s, seed=2)
+    ref, _ = orc.generate(cond, None, s.k, 1.0, s.top_k, 1.0, 4)
+    u0 = [oracle.uniform(4, 0, 0, oracle.SLOT_FINAL)]
+    hk.prefill(cond, None, s.grid_h, s.grid_w, 1.0, s.top_k, 1.0, u0)
+    orc.prefill(cond, None, 1.0, s.top_k, 1.0, u0)
+    hk.force([1], ref[:, 1:4])
+    orc.force([1], ref[:, 1:4])
+    assert hk.n()[0] == 4 and np.array_equal(hk.grid()[0, :4], ref[0, :4])
+    assert np.abs(hk.logits(3) - orc.logits()[:, :3]).max() < 1e-5
+    hk.force([2], ref[:, 2:7])   # rewind, then five tokens
+    orc.force([2], ref[:, 2:7])
+    u = synth.make_uniforms(8, (3, 1, s.k))
+    d_g, d_o = hk.draft(s.k, u[0]), orc.draft(s.k, u[0])
+    assert np.array_equal(d_g, d_o)
+    na_g, t_g = hk.verify(s.k, u[1], u[2][:, 0])
+    na_o, t_o = orc.verify(s.k, u[1], u[2][:, 0])
+    assert np.array_equal(na_g, na_o) and np.array_equal(t_g, t_o)
+    # 1x1 grid: the image is the token sampled by prefill
+    g, st = hk.generate(cond, None, 1, 1, 0, 1.0, s.top_k, 1.0, 5)
+    s1 = s.replace(grid_h=1, grid_w=1)
+    o1 = oracle.Oracle.from_shape(s1, blob, k_max=0)
+    r, _ = o1.generate(cond, None, 0, 1.0, s.top_k, 1.0, 5)
+    assert np.array_equal(g, r) and st["steps"] == 0
+
+
+def test_error_paths(H):
+    s = synth.CONFIGS[0].replace(n_layers=1)
+    blob = synth.make_weights(s)
+    hk = H.Hawk(H.HawkConfig.from_shape(s))
+    cond = synth.make_cond(s, seed=2)
+    with pytest.raises(H.HawkError) as e:
+        hk.prefill(cond, None, s.grid_h, s.grid_w, 1.0, 10, 1.0, [0.5])     # before load
+    assert e.value.code == -2
+    with pytest.raises(H.HawkError) as e:
+        hk.load(blob[:-4])
+    assert e.value.code == -1
+    hk.load(blob)
+    for kw in (dict(top_k=0), dict(top_k=s.vocab + 1), dict(temperature=-1.0), dict(cfg=2.0), dict(grid_h=9),
+               dict(u=[1.0])):
+        with pytest.raises(H.HawkError) as e:
+            hk.prefill(cond, None, kw.get("grid_h", s.grid_h), s.grid_w, kw.get("temperature", 1.0),
+                       kw.get("top_k", 10), kw.get("cfg", 1.0), kw.get("u", [0.5]))
+        assert e.value.code == -1, kw
+    with pytest.raises(H.HawkError) as e:
+        hk.draft(2, [[0.1, 0.2]])                                            # before prefill
+    assert e.value.code == -2
+    hk.prefill(cond, None, s.grid_h, s.grid_w, 1.0, 10, 1.0, [0.5])
+    with pytest.raises(H.HawkError) as e:
+        hk.verify(2, [[0.1, 0.2]], [0.3])                                    # before draft
+    assert e.value.code == -2
+    with pytest.raises(H.HawkError) as e:
+        hk.draft(s.k + 1, np.zeros((1, s.k + 1)))                            # beyond k_max
+    assert e.value.code == -1
+    hk.draft(2, [[0.1, 0.2]])
+    with pytest.raises(H.HawkError) as e:
+        hk.verify(3, [[0.1, 0.2, 0.3]], [0.3])                               # other k than drafted
+    assert e.value.code == -2
+    with pytest.raises(H.HawkError) as e:
+        hk.draft_forced(2, [[s.vocab, 0]], True)                             # token outside the slice
+    assert e.value.code == -1
+    na, toks = hk.verify(2, [[0.1, 0.2]], [0.3])
+    assert 0 <= na[0] <= 2
+
+
+# ----------------------------------------------------------------------------- bf16: tolerance
+
+def bf16_case(H, shape, k, path, steps, u_seed=1, **kw):
+    blob, hk, orc = make_pair(H, shape, path=path)
+    return lockstep(shape, hk, orc, k, u_seed=u_seed, max_steps=steps, **kw)
+
+
+def assert_bf16(res, min_steps, min_decision_rate):
+    assert res["stage_bad"] == 0, res                       # sampling stage exact on its own logits
+    assert res["max_logit_err"] <= 2e-2 and res["max_draft_logit_err"] <= 2e-2, res
+    assert res["steps"] >= min_steps, res
+    assert res["decision_same"] >= min_decision_rate * res["steps"], res
+
+
+@pytest.mark.parametrize("path,top_k", [(0, 1000), (1, 1000), (1, 16384)])
+def test_bf16_decisions_over_many_steps(H, path, top_k):
+    # The paper-sized codebook (16384) and draft length on a narrow, shallow decoder, so that
+    # the oracle covers > 1000 steps: identical accept / reject decisions on >= 99.9 % of
+    # steps.  top_k = V removes the truncation, which raises the acceptance rate and makes
+    # the accept tests non-trivial.
+    s = synth.CONFIGS[1].replace(n_layers=2, d_model=384, n_heads=6, d_mlp=1024, n_cond=16, grid_h=16,
+                                 grid_w=16, top_k=top_k)
+    total = dict(steps=0, decision_same=0, token_same=0, draft_same=0, accepted=0)
+    for u_seed in range(1, 60):
+        res = bf16_case(H, s, s.k, path, steps=10 ** 6, u_seed=u_seed)
+        assert res["stage_bad"] == 0, res
+        if not res["first_same"]:
+            continue
+        assert_bf16(res, 1, 0.0)
+        for key in total:
+            total[key] += res[key]
+        if total["steps"] >= 1200:
+            break
+    print("bf16 agreement", path, top_k, total)
+    assert total["steps"] >= 1200
+    assert total["decision_same"] >= 0.999 * total["steps"], total
+    if top_k == 16384:
+        assert total["accepted"] > 0.2 * total["steps"]      # the accept tests were exercised
+
+
+@pytest.mark.parametrize("path", [0, 1])
+def test_bf16_config1_full_depth_sampled_steps(H, path):
+    s = synth.CONFIGS[1]
+    for u_seed in (1, 2, 3, 4, 5, 6):
+        res = bf16_case(H, s, s.k, path, steps=12, u_seed=u_seed)
+        assert res["stage_bad"] == 0, res
+        if res["first_same"]:
+            break
+    assert_bf16(res, 12, 0.99)
+
+
+def test_bf16_replay_and_greedy(H):
+    s = synth.CONFIGS[1].replace(n_layers=2, n_cond=16, grid_h=8, grid_w=8)
+    blob, hk, orc = make_pair(H, s)
+    cond = synth.make_cond(s, seed=2)
+    g, st = hk.generate(cond, None, s.grid_h, s.grid_w, 0, 0.0, s.top_k, 1.0, 3)          # greedy AR on the GPU
+    g2, st2 = hk.generate(cond, None, s.grid_h, s.grid_w, s.k, 0.0, s.top_k, 1.0, 3)      # greedy speculative
+    assert np.array_equal(g, g2)
+    g3, st3 = hk.generate(cond, None, s.grid_h, s.grid_w, s.k, 0.0, s.top_k, 1.0, 3, replay=g)
+    assert np.array_equal(g, g3) and st3["steps"] == -(-(s.n_img - 1) // (s.k + 1))
+    res = lockstep(s, hk, orc, s.k, u_seed=4, replay=g, temperature=1.0)
+    assert res["stage_bad"] == 0 and res["max_logit_err"] <= 2e-2 and res["steps"] >= 10

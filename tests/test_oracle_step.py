@@ -60,7 +60,6 @@ def test_greedy_with_adversarial_drafts_equals_plain_ar(micro, k):
     total_acc = 0
     while o.n()[0] < s.n_img:
         n = int(o.n()[0])
-        o.draft(k, rng.random((1, k)))
         # random drafts, sometimes the true continuation so that acceptances occur too
         d = rng.integers(0, s.vocab, size=(1, k)).astype(np.int32)
         for i in range(k):
@@ -68,7 +67,7 @@ def test_greedy_with_adversarial_drafts_equals_plain_ar(micro, k):
                 d[0, i] = ref[n + i]
             else:
                 break
-        o.set_draft(k, d)
+        o.draft_forced(k, d, point_mass=bool(rng.integers(2)))
         na, toks = o.verify(k, rng.random((1, k)), rng.random(1))
         total_acc += int(na[0])
         assert (o.grid()[0, : o.n()[0]] == ref[: o.n()[0]]).all()
@@ -98,10 +97,9 @@ def test_replay_of_greedy_tokens_accepts_everything(micro):
     while o.n()[0] < s.n_img:
         n = int(o.n()[0])
         k_eff = min(k, s.n_img - n - 1)
-        o.draft(k, np.zeros((1, k)))
         d = np.zeros((1, k), np.int32)
         d[0, :k_eff] = ref[n:n + k_eff]
-        o.set_draft(k, d)
+        o.draft_forced(k, d, point_mass=True)
         na, toks = o.verify(k, np.full((1, k), 0.999), [0.0])
         assert na[0] == k_eff                      # tokens per step == k_eff + 1 exactly
         assert list(toks[0, : k_eff + 1]) == list(ref[n:n + k_eff + 1])
