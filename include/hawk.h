@@ -152,6 +152,22 @@ int hawk_generate(hawk_ctx* ctx, const float* cond, const float* uncond, int bat
                   uint64_t seed, const int32_t* replay_tokens, int32_t* out_grid,
                   hawk_stats* stats);
 
+/* Runs n_steps speculate-and-verify steps (draft + verify) from the current state with
+ * generator uniforms (seed; the step counter continues from the context's), without host
+ * outputs: the benchmark's timed region.  replay != 0 drafts from the table given to the
+ * last hawk_generate / hawk_set_replay in point-mass mode.  Steps after every prompt has
+ * finished do nothing.  If ms_draft / ms_verify (host, single floats) are both non-NULL the
+ * two phases are bracketed by events, the call synchronises and returns the summed GPU
+ * milliseconds of each phase; otherwise it returns once the work is enqueued. */
+int hawk_run_steps(hawk_ctx* ctx, int k, int n_steps, uint64_t seed, int replay, float* ms_draft,
+                   float* ms_verify);
+
+/* Stores the replay table (host [batch, N]) used by hawk_run_steps(replay = 1). */
+int hawk_set_replay(hawk_ctx* ctx, const int32_t* replay_tokens);
+
+/* Counters accumulated since the last hawk_prefill (times are left zero). */
+int hawk_get_stats(hawk_ctx* ctx, hawk_stats* out);
+
 /* Teacher forcing / re-synchronisation: rewinds prompt b to n_from[b] committed tokens
  * (1 <= n_from[b] <= current n) and commits tokens[b][0..cnt) as if all had been
  * accepted (cnt <= k_max + 1): runs the target over them, extends the cache, keeps the

@@ -63,6 +63,7 @@ def lib() -> C.CDLL:
             "orc_forward_row": (i32, [vp, i32, i32, vp, vp]),
             "orc_draft_head": (i32, [vp, vp, i32, i32, vp, vp]),
             "orc_margins": (None, [vp, i32]),
+            "orc_num_threads": (i32, []),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -120,6 +121,10 @@ def spec_sample(p_logits, q_logits, drafts, u_acc, u_final: float, temperature: 
     a = lib().orc_spec_sample(k_eff, n, _p(p), _p(q), _p(d), int(q_onehot), temperature,
                               n if top_k is None else top_k, _p(ua), u_final, _p(out))
     return int(a), out[: a + 1].copy()
+
+
+def num_threads() -> int:
+    return int(lib().orc_num_threads())
 
 
 def margins(reset: bool = False) -> np.ndarray:

@@ -10,6 +10,9 @@
 #include "hawk_oracle.h"
 
 #include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 #include <stdlib.h>
 #include <string.h>
 
@@ -694,6 +697,16 @@ int orc_generate(orc_state* st, const float* cond, const float* uncond, int n_co
 }
 
 /* ------------------------------------------------------------ inspection */
+
+/* Threads the matrix-vector products run on. */
+int orc_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
 
 int orc_get_n(const orc_state* st, int32_t* n) {
     if (!st || !n) return ORC_EINVAL;

@@ -71,6 +71,7 @@ int orc_generate(orc_state*, const float* cond, const float* uncond, int n_cond,
                  int32_t* out_grid, int64_t* out_stats /* steps, accepted, tokens, iters */);
 
 /* State inspection. */
+int orc_num_threads(void);
 int orc_get_n(const orc_state*, int32_t* n /*[batch]*/);
 int orc_get_grid(const orc_state*, int32_t* grid /*[batch, N]*/);
 int orc_get_logits(const orc_state*, float* out /*[batch, k_last+1, V_s]*/);

@@ -264,6 +264,8 @@ void hawk_destroy(hawk_ctx* c) {
     for (int i = 0; i < 3; ++i)
         if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
     if (c->pinned) (void)hipHostFree(c->pinned);
+    for (size_t i = 0; i < c->n_tev; ++i) (void)hipEventDestroy(c->tev[i]);
+    free(c->tev);
     delete c;
 }
 
@@ -478,6 +480,75 @@ int hawk_generate(hawk_ctx* c, const float* cond, const float* uncond, int batch
         HIP_TRY(c, hipEventElapsedTime(&stats->ms_prefill, c->ev[0], c->ev[1]));
         HIP_TRY(c, hipEventElapsedTime(&stats->ms_decode, c->ev[1], c->ev[2]));
     }
+    return HAWK_OK;
+}
+
+int hawk_set_replay(hawk_ctx* c, const int32_t* replay_tokens) {
+    if (!c) return HAWK_EINVAL;
+    if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
+    if (!replay_tokens) return fail(c, HAWK_EINVAL, "null tokens");
+    for (size_t i = 0; i < (size_t)c->B * c->N; ++i)
+        if (replay_tokens[i] < c->cfg.samp_lo || replay_tokens[i] >= c->cfg.samp_lo + c->Vs)
+            return fail(c, HAWK_EINVAL, "replayed token outside the sampled slice");
+    return upload(c, c->off.replay, replay_tokens, (size_t)c->B * c->N * 4);
+}
+
+int hawk_run_steps(hawk_ctx* c, int k, int n_steps, uint64_t seed, int replay, float* ms_draft, float* ms_verify) {
+    if (!c) return HAWK_EINVAL;
+    if (c->phase != 2) return fail(c, HAWK_ESTATE, "hawk_run_steps needs a prefilled context with no draft pending");
+    if (k < 0 || k > c->kmax || k > c->gw)
+        return fail(c, HAWK_EINVAL, "k = %d outside [0, min(k_max = %d, grid_w = %d)]", k, c->kmax, c->gw);
+    if (n_steps < 0 || n_steps > 1 << 20) return fail(c, HAWK_EINVAL, "n_steps out of range");
+    const bool timed = ms_draft && ms_verify;
+    if (timed && (size_t)(2 * n_steps + 1) > c->n_tev) {
+        size_t want = (size_t)(2 * n_steps + 1);
+        hipEvent_t* ev = static_cast<hipEvent_t*>(realloc(c->tev, want * sizeof(hipEvent_t)));
+        if (!ev) return fail(c, HAWK_ENOMEM, "out of host memory");
+        c->tev = ev;
+        for (; c->n_tev < want; ++c->n_tev) HIP_TRY(c, hipEventCreate(&c->tev[c->n_tev]));
+    }
+    UniformSrc us;
+    memset(&us, 0, sizeof us);
+    us.use_gen = 1;
+    us.seed = seed;
+    us.step = wsp<int32_t>(c, c->off.step);
+    const DraftMode dm = {replay ? 2 : 0, replay ? 1 : 0};
+    if (timed) HIP_TRY(c, hipEventRecord(c->tev[0], c->stream));
+    for (int it = 0; it < n_steps; ++it) {
+        enqueue_draft(c, k, us, dm);
+        if (timed) HIP_TRY(c, hipEventRecord(c->tev[2 * it + 1], c->stream));
+        enqueue_verify(c, k, us);
+        if (timed) HIP_TRY(c, hipEventRecord(c->tev[2 * it + 2], c->stream));
+    }
+    HIP_TRY(c, hipGetLastError());
+    c->k_last = k;
+    if (timed) {
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        double md = 0.0, mv = 0.0;
+        for (int it = 0; it < n_steps; ++it) {
+            float a = 0.f, b = 0.f;
+            HIP_TRY(c, hipEventElapsedTime(&a, c->tev[2 * it], c->tev[2 * it + 1]));
+            HIP_TRY(c, hipEventElapsedTime(&b, c->tev[2 * it + 1], c->tev[2 * it + 2]));
+            md += a;
+            mv += b;
+        }
+        *ms_draft = (float)md;
+        *ms_verify = (float)mv;
+    }
+    return HAWK_OK;
+}
+
+int hawk_get_stats(hawk_ctx* c, hawk_stats* out) {
+    if (!c || !out) return HAWK_EINVAL;
+    if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
+    unsigned long long cnt[4];
+    int rc = download(c, cnt, c->off.counters, sizeof cnt);
+    if (rc) return rc;
+    memset(out, 0, sizeof *out);
+    out->steps = (int64_t)cnt[0];
+    out->accepted = (int64_t)cnt[1];
+    out->tokens = (int64_t)cnt[2];
+    out->iters = (int64_t)cnt[3];
     return HAWK_OK;
 }
 

@@ -81,6 +81,8 @@ struct hawk_ctx {
     int path;
     void* pinned;  // small page-locked staging buffer for read-backs
     hipEvent_t ev[3];
+    hipEvent_t* tev;  // event pool of hawk_run_steps phase timing
+    size_t n_tev;
     char err[256];
 };
 

@@ -58,6 +58,10 @@ EXPORTS = {
     "hawk_generate": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                 C.c_float, C.c_int, C.c_float, C.c_uint64, C.c_void_p, C.c_void_p,
                                 C.POINTER(HawkStats)]),
+    "hawk_run_steps": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_uint64, C.c_int, C.POINTER(C.c_float),
+                                 C.POINTER(C.c_float)]),
+    "hawk_set_replay": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "hawk_get_stats": (C.c_int, [C.c_void_p, C.POINTER(HawkStats)]),
     "hawk_force": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]),
     "hawk_get_n": (C.c_int, [C.c_void_p, C.c_void_p]),
     "hawk_get_grid": (C.c_int, [C.c_void_p, C.c_void_p]),
@@ -195,6 +199,27 @@ class Hawk:
                                         temperature, top_k, cfg_scale, seed, _p(rp), _p(grid), C.byref(st)),
                   "hawk_generate")
         return grid, st.as_dict()
+
+    def run_steps(self, k, n_steps, seed, replay=False, timed=False):
+        """Enqueues n_steps steps; with timed=True returns (ms_draft, ms_verify) summed over them."""
+        if timed:
+            a, b = C.c_float(), C.c_float()
+            self._chk(self._L.hawk_run_steps(self._h, k, n_steps, seed, int(replay), C.byref(a), C.byref(b)),
+                      "hawk_run_steps")
+            return a.value, b.value
+        self._chk(self._L.hawk_run_steps(self._h, k, n_steps, seed, int(replay), None, None), "hawk_run_steps")
+        return None
+
+    def set_replay(self, tokens):
+        self._chk(self._L.hawk_set_replay(self._h, _p(_i32(tokens))), "hawk_set_replay")
+
+    def stats(self):
+        st = HawkStats()
+        self._chk(self._L.hawk_get_stats(self._h, C.byref(st)), "hawk_get_stats")
+        return st.as_dict()
+
+    def synchronize(self):
+        self._stream.synchronize()
 
     def force(self, n_from, tokens):
         t = _i32(tokens).reshape(self.batch, -1)
