@@ -52,7 +52,7 @@ enum { HAWK_FP32 = 0, HAWK_BF16 = 1 };
  * of the sampled vocabulary slice, and the capacity limits of one context.
  * dtype is the storage type of the weight blob: HAWK_FP32 computes with fp64
  * accumulators and activations (the exact-parity configuration), HAWK_BF16 with bf16
- * weights and KV cache, fp32 accumulators and residual stream. */
+ * weights, a 16-bit (fp16) KV cache, fp32 accumulators and residual stream. */
 typedef struct {
     int32_t n_layers, d_model, n_heads, d_mlp, vocab;
     int32_t samp_lo, samp_n;              /* samp_n == 0: whole vocabulary */
@@ -75,6 +75,13 @@ typedef struct {
 /* Bytes of device workspace a context of this configuration needs; 0 if the
  * configuration is invalid. */
 size_t hawk_workspace_bytes(const hawk_config* cfg);
+
+/* Host-only diagnostic of how the persistent weight-streaming kernel would split this
+ * configuration over its workgroups (no GPU needed).  out8 (host, 8 x int64): [0] 1 if the
+ * shape is supported by that kernel, [1] 1 KB weight tiles per layer, [2] tiles in total,
+ * [3] / [4] fewest / most tiles one workgroup streams per layer, [5] rounds of the output
+ * projection, [6] 1 if the job tables cover every tile exactly once, [7] workgroups. */
+int hawk_plan_info(const hawk_config* cfg, int64_t* out8);
 
 /* Creates a context over `workspace` (device, 256-byte aligned, >= hawk_workspace_bytes)
  * that enqueues on `hip_stream` (a hipStream_t, NULL = the default stream). */
@@ -182,9 +189,12 @@ int hawk_get_logits(hawk_ctx* ctx, float* out, int rows);
 /* guided draft logits of the last draft, [batch, k, samp_n] */
 int hawk_get_draft_logits(hawk_ctx* ctx, float* out, int k);
 
-/* Selects the kernel set: 0 = generic kernels (any shape), 1 = fused weight-streaming
- * kernels where the shape allows (default). */
+/* Selects the kernel set: 0 = generic kernels (any shape), 1 = the persistent
+ * weight-streaming kernel where the shape allows (default).  hawk_last_path reports which
+ * one the last target pass of hawk_verify / hawk_force / hawk_generate / hawk_run_steps
+ * actually used (0 or 1; -1 before any). */
 int hawk_set_path(hawk_ctx* ctx, int path);
+int hawk_last_path(const hawk_ctx* ctx);
 
 #ifdef __cplusplus
 }

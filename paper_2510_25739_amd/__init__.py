@@ -10,5 +10,6 @@ from .hawk import (  # noqa: F401
     HawkStats,
     lib_path,
     load_library,
+    plan_info,
     workspace_bytes,
 )

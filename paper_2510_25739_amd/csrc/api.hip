@@ -99,6 +99,7 @@ bool derive(const hawk_config* g, hawk_ctx* c) {
     o.u_draft = take(B * ks * 4); o.u_acc = take(B * ks * 4); o.u_fin = take(B * 4);
     o.out_na = take(B * 4); o.out_tok = take(B * ks * 4); o.inv_freq = take((size_t)(hd / 2) * 8);
     o.replay = take(B * c->Nmax * 4); o.cond = take(S * (size_t)g->max_cond * d * 4);
+    p += stream_workspace(c, p, &c->soff);
     o.total = p;
     return true;
 }
@@ -134,6 +135,12 @@ void run_step_rows(hawk_ctx* c, int k) {
     const int M = c->S * (k + 1);
     RowMap map = step_map(c, k);
     launch_embed_rows(c, map, M);
+    if (stream_ok(c, k)) {  // one persistent kernel: all layers and the output projection
+        if (launch_verify_stream(c, k) != 0) c->launch_failed = 1;
+        c->last_path = 1;
+        return;
+    }
+    c->last_path = 0;
     run_layers(c, map, M);
     launch_rmsnorm(c, c->off.x, c->d, c->w.g_f, c->off.a, M);
     launch_gemm(c, c->off.a, c->d, slice_off(c), c->Vs, c->d, c->off.logit_s, c->Vs, M, false, true);
@@ -215,6 +222,13 @@ int download(hawk_ctx* c, void* host, size_t off, size_t bytes) {
     return HAWK_OK;
 }
 
+// After a synchronisation: did a streaming kernel fail to launch or give up on a barrier?
+int check_stream(hawk_ctx* c) {
+    if (c->launch_failed) return fail(c, HAWK_EDEVICE, "launch of the streaming kernel failed");
+    if (stream_error(c)) return fail(c, HAWK_EDEVICE, "a grid barrier of the streaming kernel timed out");
+    return HAWK_OK;
+}
+
 bool uniforms_ok(const float* u, size_t n) {
     for (size_t i = 0; i < n; ++i)
         if (!(u[i] >= 0.f && u[i] < 1.f)) return false;
@@ -231,6 +245,15 @@ size_t hawk_workspace_bytes(const hawk_config* cfg) {
     return derive(cfg, &tmp) ? tmp.off.total : 0;
 }
 
+int hawk_plan_info(const hawk_config* cfg, int64_t* out8) {
+    if (!out8) return HAWK_EINVAL;
+    hawk_ctx tmp;
+    memset(&tmp, 0, sizeof tmp);
+    if (!derive(cfg, &tmp)) return HAWK_EINVAL;
+    stream_plan_info(&tmp, out8);
+    return HAWK_OK;
+}
+
 int hawk_create(const hawk_config* cfg, void* workspace, size_t workspace_bytes, void* hip_stream, hawk_ctx** out) {
     if (!out) return HAWK_EINVAL;
     *out = nullptr;
@@ -243,6 +266,7 @@ int hawk_create(const hawk_config* cfg, void* workspace, size_t workspace_bytes,
     c->ws = static_cast<uint8_t*>(workspace);
     c->stream = static_cast<hipStream_t>(hip_stream);
     c->path = 1;
+    c->last_path = -1;
     if (hipHostMalloc(&c->pinned, kPinnedBytes, hipHostMallocDefault) != hipSuccess) { delete c; return HAWK_EDEVICE; }
     for (int i = 0; i < 3; ++i)
         if (hipEventCreate(&c->ev[i]) != hipSuccess) { (void)hipHostFree(c->pinned); delete c; return HAWK_EDEVICE; }
@@ -254,6 +278,11 @@ int hawk_create(const hawk_config* cfg, void* workspace, size_t workspace_bytes,
         hawk_destroy(c);
         return HAWK_EDEVICE;
     }
+    c->plan = stream_create(c);
+    if (hipGetLastError() != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+        hawk_destroy(c);
+        return HAWK_EDEVICE;
+    }
     *out = c;
     return HAWK_OK;
 }
@@ -261,6 +290,7 @@ int hawk_create(const hawk_config* cfg, void* workspace, size_t workspace_bytes,
 void hawk_destroy(hawk_ctx* c) {
     if (!c) return;
     (void)hipStreamSynchronize(c->stream);
+    stream_destroy(c->plan);
     for (int i = 0; i < 3; ++i)
         if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
     if (c->pinned) (void)hipHostFree(c->pinned);
@@ -278,6 +308,8 @@ int hawk_set_path(hawk_ctx* c, int path) {
     return HAWK_OK;
 }
 
+int hawk_last_path(const hawk_ctx* c) { return c ? c->last_path : -1; }
+
 int hawk_load(hawk_ctx* c, const void* host_blob, size_t nbytes) {
     if (!c) return HAWK_EINVAL;
     if (!host_blob) return fail(c, HAWK_EINVAL, "null blob");
@@ -288,6 +320,7 @@ int hawk_load(hawk_ctx* c, const void* host_blob, size_t nbytes) {
     if (h[2] != c->cfg.dtype || h[3] != c->L || h[4] != c->d || h[5] != c->H || h[6] != c->m || h[7] != c->V)
         return fail(c, HAWK_EINVAL, "blob header does not match the context's configuration");
     HIP_TRY(c, hipMemcpy(c->ws + c->off.blob, host_blob, nbytes, hipMemcpyHostToDevice));
+    if (stream_repack(c) != 0) return fail(c, HAWK_EDEVICE, "re-tiling the weights for the streaming path failed");
     c->phase = 1;
     return HAWK_OK;
 }
@@ -385,6 +418,7 @@ int hawk_verify(hawk_ctx* c, int k, const float* u_acc, const float* u_final, in
         rc = download(c, out_tokens, c->off.out_tok, (size_t)c->B * (k + 1) * 4);
         if (rc) return rc;
     }
+    if (out_n_accept || out_tokens) return check_stream(c);
     return HAWK_OK;
 }
 
@@ -414,7 +448,7 @@ int hawk_force(hawk_ctx* c, const int32_t* n_from, const int32_t* tokens, int cn
     HIP_TRY(c, hipGetLastError());
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     c->phase = 2;
-    return HAWK_OK;
+    return check_stream(c);
 }
 
 int hawk_generate(hawk_ctx* c, const float* cond, const float* uncond, int batch, int n_cond, int grid_h, int grid_w,
@@ -465,6 +499,8 @@ int hawk_generate(hawk_ctx* c, const float* cond, const float* uncond, int batch
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     c->k_last = k;
     c->phase = 2;
+    rc = check_stream(c);
+    if (rc) return rc;
     if (out_grid) {
         rc = download(c, out_grid, c->off.grid, (size_t)batch * N * 4);  // rows are N long: N == c->N
         if (rc) return rc;
@@ -534,6 +570,7 @@ int hawk_run_steps(hawk_ctx* c, int k, int n_steps, uint64_t seed, int replay, f
         }
         *ms_draft = (float)md;
         *ms_verify = (float)mv;
+        return check_stream(c);
     }
     return HAWK_OK;
 }
@@ -549,7 +586,7 @@ int hawk_get_stats(hawk_ctx* c, hawk_stats* out) {
     out->accepted = (int64_t)cnt[1];
     out->tokens = (int64_t)cnt[2];
     out->iters = (int64_t)cnt[3];
-    return HAWK_OK;
+    return check_stream(c);
 }
 
 int hawk_get_n(hawk_ctx* c, int32_t* n) {

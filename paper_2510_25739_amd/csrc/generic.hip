@@ -2,7 +2,9 @@
 //
 // Two arithmetic configurations, selected by the weight dtype of the context:
 //   fp32 blobs: fp32 weights, fp64 activations / accumulators / KV cache (exact-parity set);
-//   bf16 blobs: bf16 weights and KV cache, fp32 activations and accumulators.
+//   bf16 blobs: bf16 weights, fp16 KV cache (same bytes as bf16, 3 more mantissa bits: the
+//               cache's rounding is what dominates the logit error), fp32 activations and
+//               accumulators.
 // One wave computes one output column of a skinny GEMM for up to RT rows, streaming its
 // weight row with 16-byte loads; this is the fallback path and the only path of the
 // fp32 configuration.  The weight-streaming fast path lives in stream.hip.
@@ -15,7 +17,7 @@ struct CfgF32 {
     static constexpr int VE = 4;
 };
 struct CfgBF16 {
-    using WT = uint16_t; using AT = float; using KT = uint16_t;
+    using WT = uint16_t; using AT = float; using KT = _Float16;
     static constexpr int VE = 8;
 };
 
@@ -39,9 +41,9 @@ __device__ __forceinline__ void load_w(const uint16_t* p, float* out) {
 __device__ __forceinline__ double w1(const float* p, size_t i) { return (double)p[i]; }
 __device__ __forceinline__ float w1(const uint16_t* p, size_t i) { return bf16_to_f32(p[i]); }
 __device__ __forceinline__ double kload(const double* p, size_t i) { return p[i]; }
-__device__ __forceinline__ float kload(const uint16_t* p, size_t i) { return bf16_to_f32(p[i]); }
+__device__ __forceinline__ float kload(const _Float16* p, size_t i) { return (float)p[i]; }
 __device__ __forceinline__ void kstore(double* p, size_t i, double v) { p[i] = v; }
-__device__ __forceinline__ void kstore(uint16_t* p, size_t i, float v) { p[i] = f32_to_bf16(v); }
+__device__ __forceinline__ void kstore(_Float16* p, size_t i, float v) { p[i] = (_Float16)v; }
 
 template <typename T> __device__ __forceinline__ T wave_sum(T v) {
 #pragma unroll

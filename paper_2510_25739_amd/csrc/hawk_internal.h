@@ -57,6 +57,12 @@ struct Offsets {  // byte offsets into the workspace
     size_t total;
 };
 
+// Streaming (persistent-kernel) path: matrix kinds, workgroup count, workspace regions.
+enum StreamKind { K_A = 0, K_C, K_D, K_E, K_LM, K_WD, K_NKIND };  // QKV, Wo, W1|W3, W2, output, draft
+constexpr int kNWG = 256;  // persistent workgroups: one per compute unit
+struct StreamOffsets { size_t wpack, tab, desc, hasmask, x2, q, o, h, p, bar, err, rope; };
+struct StreamPlan;
+
 struct Weights {  // byte offsets into the blob
     size_t E, g_f, W_out, W_d;
     size_t g1[128], Wqkv[128], Wo[128], g2[128], W13[128], W2[128];
@@ -72,6 +78,8 @@ struct hawk_ctx {
     hipStream_t stream;
     hawk::Offsets off;
     hawk::Weights w;
+    hawk::StreamOffsets soff;
+    hawk::StreamPlan* plan;  // streaming path: job tables and barrier epoch (null until created)
     size_t blob_bytes;
     // per image
     int B, S, C, gh, gw, N, top_k, greedy;
@@ -79,6 +87,8 @@ struct hawk_ctx {
     int phase;   // 0 created, 1 loaded, 2 prefilled (draft next), 3 drafted (verify next)
     int k_last;
     int path;
+    int launch_failed;
+    int last_path;
     void* pinned;  // small page-locked staging buffer for read-backs
     hipEvent_t ev[3];
     hipEvent_t* tev;  // event pool of hawk_run_steps phase timing
@@ -103,6 +113,16 @@ void launch_attention(hawk_ctx*, const RowMap&, int layer, int M);
 void launch_swiglu(hawk_ctx*, int M);
 void launch_draft_input(hawk_ctx*, int i);                     // [g | E[left] | E[up]]
 void launch_keep_hprev_prefill(hawk_ctx*);
+
+// ---- streaming path, implemented in stream.hip ----
+size_t stream_workspace(const hawk_ctx*, size_t base, StreamOffsets* out);  // extra workspace bytes
+StreamPlan* stream_create(hawk_ctx*);     // plans the jobs, uploads tables (context has its workspace)
+void stream_destroy(StreamPlan*);
+void stream_plan_info(const hawk_ctx*, int64_t* out8);  // host-only summary of the plan
+int stream_repack(hawk_ctx*);             // after the blob is on the device; 0 = ok
+bool stream_ok(const hawk_ctx*, int k);   // can a step with k drafts run on the streaming path?
+int launch_verify_stream(hawk_ctx*, int k);  // 0 = enqueued
+int stream_error(hawk_ctx*);              // 1 if a grid barrier timed out (synchronises)
 
 // ---- launchers implemented in sampling.hip ----
 void launch_plan(hawk_ctx*, int k);

@@ -46,6 +46,7 @@ class HawkStats(C.Structure):
 
 EXPORTS = {
     "hawk_workspace_bytes": (C.c_size_t, [C.POINTER(HawkConfig)]),
+    "hawk_plan_info": (C.c_int, [C.POINTER(HawkConfig), C.POINTER(C.c_int64)]),
     "hawk_create": (C.c_int, [C.POINTER(HawkConfig), C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_void_p)]),
     "hawk_destroy": (None, [C.c_void_p]),
     "hawk_last_error": (C.c_char_p, [C.c_void_p]),
@@ -68,6 +69,7 @@ EXPORTS = {
     "hawk_get_logits": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int]),
     "hawk_get_draft_logits": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int]),
     "hawk_set_path": (C.c_int, [C.c_void_p, C.c_int]),
+    "hawk_last_path": (C.c_int, [C.c_void_p]),
 }
 
 
@@ -92,6 +94,15 @@ def load_library() -> C.CDLL:
 
 def workspace_bytes(cfg: HawkConfig) -> int:
     return int(load_library().hawk_workspace_bytes(C.byref(cfg)))
+
+
+def plan_info(cfg: HawkConfig) -> dict:
+    out = (C.c_int64 * 8)()
+    rc = load_library().hawk_plan_info(C.byref(cfg), out)
+    if rc != 0:
+        raise HawkError(rc, "hawk_plan_info")
+    keys = ("supported", "layer_tiles", "total_tiles", "min_wg_tiles", "max_wg_tiles", "lm_rounds", "tables_ok", "workgroups")
+    return dict(zip(keys, [int(v) for v in out]))
 
 
 def _f32(a):
@@ -159,6 +170,9 @@ class Hawk:
     # -- the C calls
     def set_path(self, path: int):
         self._chk(self._L.hawk_set_path(self._h, path), "hawk_set_path")
+
+    def last_path(self) -> int:
+        return int(self._L.hawk_last_path(self._h))
 
     def load(self, blob: np.ndarray):
         blob = np.ascontiguousarray(blob, dtype=np.uint8)

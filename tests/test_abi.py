@@ -68,3 +68,17 @@ def test_product_never_imports_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower(), f
+
+
+def test_streaming_plan_covers_every_weight_tile_once(H):
+    # host logic of the persistent kernel: job tables and tile descriptors
+    for idx in (1, 2):
+        s = synth.CONFIGS[idx]
+        info = H.plan_info(H.HawkConfig.from_shape(s))
+        assert info["supported"] == 1 and info["tables_ok"] == 1
+        per_layer = (4 * s.d_model ** 2 + 3 * s.d_model * s.d_mlp) // 512     # 16x32 bf16 tiles
+        assert info["layer_tiles"] == per_layer
+        assert info["total_tiles"] == s.n_layers * per_layer + s.v_s * s.d_model // 512 + 3 * s.d_model ** 2 // 512
+        mean = per_layer / info["workgroups"]
+        assert info["min_wg_tiles"] <= mean <= info["max_wg_tiles"] <= 1.35 * mean
+    assert H.plan_info(H.HawkConfig.from_shape(synth.CONFIGS[0]))["supported"] == 0   # fp32: generic kernels

@@ -355,3 +355,67 @@ def test_bf16_replay_and_greedy(H):
     assert np.array_equal(g, g3) and st3["steps"] == -(-(s.n_img - 1) // (s.k + 1))
     res = lockstep(s, hk, orc, s.k, u_seed=4, replay=g, temperature=1.0)
     assert res["stage_bad"] == 0 and res["max_logit_err"] <= 2e-2 and res["steps"] >= 10
+
+
+# ----------------------------------------------------------------------------- streaming path
+
+@pytest.mark.parametrize("cfg,layers", [(1, 2), (2, 2)])
+def test_streaming_kernel_matches_generic_kernels_and_oracle(H, cfg, layers):
+    # the persistent weight-streaming kernel against the generic kernels (same logits up to
+    # fp32 summation order and the bf16 hi/lo split) and against the oracle
+    s = synth.CONFIGS[cfg].replace(n_layers=layers, n_cond=24, grid_h=6, grid_w=8)
+    blob = synth.make_weights(s, seed=0)
+    cond = synth.make_cond(s, seed=2)
+    out = {}
+    for path in (0, 1):
+        hk = H.Hawk(H.HawkConfig.from_shape(s))
+        hk.load(blob)
+        hk.set_path(path)
+        hk.prefill(cond, None, s.grid_h, s.grid_w, 1.0, s.top_k, 1.0, [0.25])
+        toks = np.full((1, s.k), s.samp_lo + 7, np.int32)
+        hk.draft_forced(s.k, toks, False)
+        na, t = hk.verify(s.k, np.full((1, s.k), 0.5, np.float32), [0.5])
+        assert hk.last_path() == path
+        out[path] = (hk.logits(s.k + 1).copy(), na.copy(), t.copy(), hk.grid()[0, 0])
+        hk.close()
+    assert out[0][3] == out[1][3]
+    err = np.abs(out[0][0] - out[1][0]).max()
+    print("streaming vs generic max logit diff", err)
+    assert err < 2e-3
+    # both agree with the oracle's logits for the same forced drafts
+    orc = oracle.Oracle.from_shape(s, blob)
+    orc.prefill(cond, None, 1.0, s.top_k, 1.0, [0.25])
+    if orc.grid()[0, 0] == out[1][3]:
+        orc.draft_forced(s.k, toks, False)
+        orc.verify(s.k, np.full((1, s.k), 0.5, np.float32), [0.5])
+        e1 = np.abs(out[1][0] - orc.logits()).max()
+        e0 = np.abs(out[0][0] - orc.logits()).max()
+        print("max logit err vs oracle: streaming", e1, "generic", e0)
+        assert e1 <= 2e-2 and e0 <= 2e-2
+
+
+@pytest.mark.parametrize("cfg,layers,steps", [(1, 3, 25), (2, 3, 25)])
+def test_streaming_kernel_lockstep_with_oracle(H, cfg, layers, steps):
+    s = synth.CONFIGS[cfg].replace(n_layers=layers, n_cond=24)
+    for u_seed in (1, 2, 3, 4, 5, 6):
+        blob, hk, orc = make_pair(H, s, path=1)
+        res = lockstep(s, hk, orc, s.k, u_seed=u_seed, max_steps=steps)
+        assert res["stage_bad"] == 0, res
+        if res["first_same"]:
+            assert hk.last_path() == 1
+            break
+    print("streaming lockstep", res)
+    assert_bf16(res, steps, 0.95)
+
+
+def test_streaming_kernel_xl_full_depth_sampled_steps(H):
+    s = synth.CONFIGS[2]
+    for u_seed in (1, 2, 3):
+        blob, hk, orc = make_pair(H, s, path=1)
+        res = lockstep(s, hk, orc, s.k, u_seed=u_seed, max_steps=6)
+        assert res["stage_bad"] == 0, res
+        if res["first_same"]:
+            assert hk.last_path() == 1
+            break
+    print("XL full depth", res)
+    assert_bf16(res, 6, 0.8)
