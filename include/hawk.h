@@ -196,6 +196,13 @@ int hawk_get_draft_logits(hawk_ctx* ctx, float* out, int k);
 int hawk_set_path(hawk_ctx* ctx, int path);
 int hawk_last_path(const hawk_ctx* ctx);
 
+/* Diagnostic: switches per-stage time stamps of the streaming kernel on or off (they cost
+ * a few stores per stage) and, if out != NULL, copies the stamps of the last launch to
+ * out (host, n_words x uint64, at most 2*4096*8): [workgroup 0 | workgroup 128][stage][8],
+ * 100 MHz ticks at: stage entry, barrier crossed, input staged, workgroup sync 1, workgroup
+ * sync 2 (MFMAs done), results stored, arrival posted. */
+int hawk_phase_trace(hawk_ctx* ctx, int enable, uint64_t* out, size_t n_words);
+
 #ifdef __cplusplus
 }
 #endif

@@ -310,6 +310,16 @@ int hawk_set_path(hawk_ctx* c, int path) {
 
 int hawk_last_path(const hawk_ctx* c) { return c ? c->last_path : -1; }
 
+int hawk_phase_trace(hawk_ctx* c, int enable, uint64_t* out, size_t n_words) {
+    if (!c) return HAWK_EINVAL;
+    c->stream_dbg = enable ? 1 : 0;
+    if (out && c->plan) {
+        if (n_words > 2 * 4096 * 8) n_words = 2 * 4096 * 8;
+        return download(c, out, c->soff.dbg, n_words * 8);
+    }
+    return HAWK_OK;
+}
+
 int hawk_load(hawk_ctx* c, const void* host_blob, size_t nbytes) {
     if (!c) return HAWK_EINVAL;
     if (!host_blob) return fail(c, HAWK_EINVAL, "null blob");

@@ -60,7 +60,7 @@ struct Offsets {  // byte offsets into the workspace
 // Streaming (persistent-kernel) path: matrix kinds, workgroup count, workspace regions.
 enum StreamKind { K_A = 0, K_C, K_D, K_E, K_LM, K_WD, K_NKIND };  // QKV, Wo, W1|W3, W2, output, draft
 constexpr int kNWG = 256;  // persistent workgroups: one per compute unit
-struct StreamOffsets { size_t wpack, tab, desc, hasmask, x2, q, o, h, p, bar, err, rope; };
+struct StreamOffsets { size_t wpack, tab, desc, hasmask, arena, slot_bytes, bar, err, dbg, rope; };
 struct StreamPlan;
 
 struct Weights {  // byte offsets into the blob
@@ -89,6 +89,7 @@ struct hawk_ctx {
     int path;
     int launch_failed;
     int last_path;
+    int stream_dbg;  // 1: the streaming kernel records per-phase timestamps
     void* pinned;  // small page-locked staging buffer for read-backs
     hipEvent_t ev[3];
     hipEvent_t* tev;  // event pool of hawk_run_steps phase timing

@@ -38,12 +38,16 @@ typedef unsigned long long u64;
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
 constexpr int kCW = 4;                          // compute waves per workgroup
-constexpr int kNIO = 2;                         // IO waves per workgroup
+constexpr int kNIO = 4;                         // IO waves per workgroup
 constexpr int kThreads = (kCW + kNIO) * 64;
-constexpr int kTMax = 30;                       // tiles (1 KB each) a wave holds for one job
+constexpr int kTMax = 27;                       // tiles (1 KB each) a wave holds for one job
 constexpr int kMaxStrips = 3;
 constexpr int kGroups = 16, kReplicas = 8;      // barrier fan-in / release fan-out
 constexpr unsigned kSpinLimit = 1u << 21;
+constexpr int kRing = 3;
+constexpr int kPS = 68;                         // floats per attention partial row: 64 outputs, max, sum, pad
+constexpr int kNIT = 12;                        // cache positions per (wave, lane group) of an attention job
+constexpr int kNCMax = 4;                       // chunks per (sequence, head)                        // exchange arenas used round robin by successive launches
 
 // ------------------------------------------------------------------------- kernel parameters
 
@@ -58,13 +62,17 @@ struct SP {
     const float2* rope;
     _Float16* Kc;
     _Float16* Vc;
-    float *X, *X2, *Q, *P, *O, *Hb, *logit_s;
+    float* X;        // embedded rows in, final hidden rows out ([MR][d], written by the previous kernel)
+    float* arena;    // exchange slots of this launch: slot l = arena + l * slot_floats, l = 0..L
+    u64 slot_floats, ax, ax2, aq, ao, ah, ap;  // offsets of x, x', q, o, h, partials inside a slot
+    float* logit_s;
+    u64* dbg;        // optional per-phase timestamps of the first IO wave of workgroups 0 and 128 (null: off)
     unsigned* bar;
     unsigned* err;
     const int32_t* n;
     const int32_t* k_eff;
     unsigned epoch0;
-    int32_t L, d, H, m, Vs, S, B, C, RS, MR, NC, Smax, Tmax, Kp;
+    int32_t L, d, H, m, Vs, S, B, C, RS, MR, NC, Smax, Tmax, Kp, act_bytes;
     float eps;
 };
 
@@ -85,6 +93,13 @@ __device__ __forceinline__ void st_f32x2(float* p, float a, float b) {
     u64 v = (u64)__float_as_uint(a) | ((u64)__float_as_uint(b) << 32);
     __hip_atomic_store(reinterpret_cast<u64*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// Exchange data is written once per launch into a slot that no cache has seen yet (stores go
+// through to memory), so after the barrier ordinary cached loads return it and the 32 workgroups
+// of an XCD share one L2 fill instead of each pulling the vector across the fabric.
+__device__ __forceinline__ void compiler_fence() { __atomic_signal_fence(__ATOMIC_SEQ_CST); }
+__device__ __forceinline__ float* slot(const SP& p, int l) { return p.arena + (u64)l * p.slot_floats; }
+__device__ __forceinline__ const float* x_in(const SP& p, int l) { return l == 0 ? p.X : slot(p, l) + p.ax; }
+
 __device__ __forceinline__ uint16_t bf16_rne(float f) {
     unsigned u = __float_as_uint(f);
     return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
@@ -104,6 +119,7 @@ struct Barrier {
     unsigned* err;
     unsigned id;       // barriers completed so far (global count)
     unsigned first;    // id at kernel start
+    unsigned joins;    // io_join calls so far (IO waves)
     bool dead;
     __device__ void arrive() {  // one lane of one wave per workgroup
         ++id;
@@ -123,7 +139,7 @@ struct Barrier {
         const unsigned* rel = mem + (size_t)(kGroups + 1 + blockIdx.x % kReplicas) * 1024;
         for (unsigned spins = 0; spins < kSpinLimit; ++spins) {
             unsigned v = __hip_atomic_load(rel, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if ((int)(v - id) >= 0) return;
+            if ((int)(v - id) >= 0) { compiler_fence(); return; }
             if (__hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
             __builtin_amdgcn_s_sleep(2);
         }
@@ -131,6 +147,12 @@ struct Barrier {
         __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 };
+
+// Timestamp slot `what` (0..7) of phase `phase` (constant 100 MHz clock).
+__device__ __forceinline__ void stamp(const SP& p, unsigned phase, int what) {
+    if (p.dbg && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == kCW && (blockIdx.x & 127) == 0)
+        p.dbg[((size_t)(blockIdx.x >> 7) * 4096 + phase) * 8 + what] = __builtin_amdgcn_s_memrealtime();
+}
 
 struct Job {
     u64 tile0;       // first tile of wave 0 in wpack
@@ -164,40 +186,117 @@ __device__ __forceinline__ void issue_tiles(const SP& p, const Job& j, int tps, 
 }
 
 // Stage input rows into LDS as bf16 hi / lo pairs: act[c][j] = split(src[c][j] * scale_c * gain_j).
-// Row c is handled by IO wave (c mod kNIO).  NORM: RMS-normalise with the gain vector.
-template <bool NORM, int KREG>
-__device__ __forceinline__ void stage_rows(const float* src, int K, int MR, const uint16_t* gain, float eps, int io,
+// IO wave `io` handles rows io, io + kNIO, ...  NORM: RMS-normalise with the gain vector; all
+// loads of a wave's rows are issued before the first is used.
+__device__ __forceinline__ void put_split(float4 v, uint16_t* hi, uint16_t* lo) {
+    const unsigned h0 = bf16_rne(v.x), h1 = bf16_rne(v.y), h2 = bf16_rne(v.z), h3 = bf16_rne(v.w);
+    const unsigned l0 = bf16_rne(v.x - bf16_f32(h0)), l1 = bf16_rne(v.y - bf16_f32(h1));
+    const unsigned l2 = bf16_rne(v.z - bf16_f32(h2)), l3 = bf16_rne(v.w - bf16_f32(h3));
+    *reinterpret_cast<uint2*>(hi) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+    *reinterpret_cast<uint2*>(lo) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+}
+
+template <int KREG>  // gains of the lane's columns, fetched before the barrier is crossed
+__device__ __forceinline__ void load_gains(const uint16_t* gain, int K, int lane, uint2 (&g)[KREG]) {
+#pragma unroll
+    for (int i = 0; i < KREG; ++i) {
+        const int j = (i * 64 + lane) * 4;
+        g[i] = j < K ? *reinterpret_cast<const uint2*>(gain + j) : make_uint2(0u, 0u);
+    }
+}
+
+template <bool NORM, int KREG>  // KREG: float4 per lane per row (K <= 256 * KREG)
+__device__ __forceinline__ void stage_rows(const float* src, int K, int MR, const uint2 (&g)[KREG], float eps, int io,
                                            int lane, uint16_t* act_hi, uint16_t* act_lo, int Kp) {
-    for (int c = io; c < MR; c += kNIO) {
-        float2 v[KREG];
-        const float* row = src + (size_t)c * K;
+    constexpr int RPW = (16 + kNIO - 1) / kNIO;  // rows one IO wave may own
+    constexpr int RB = KREG > 8 ? 2 : RPW;       // rows whose loads are in flight together
 #pragma unroll
-        for (int i = 0; i < KREG; ++i) {
-            int j = (i * 64 + lane) * 2;
-            v[i] = j < K ? ld_f32x2(row + j) : make_float2(0.f, 0.f);
+    for (int q0 = 0; q0 < RPW; q0 += RB) {
+        if (io + q0 * kNIO >= MR) break;
+        float4 v[RB][KREG];
+#pragma unroll
+        for (int q = 0; q < RB; ++q) {
+            const int c = io + (q0 + q) * kNIO;
+#pragma unroll
+            for (int i = 0; i < KREG; ++i) {
+                const int j = (i * 64 + lane) * 4;
+                v[q][i] = (c < MR && j < K) ? *reinterpret_cast<const float4*>(src + (size_t)c * K + j)
+                                            : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
         }
-        float r = 1.f;
-        if (NORM) {
-            float ss = 0.f;
 #pragma unroll
-            for (int i = 0; i < KREG; ++i) ss += v[i].x * v[i].x + v[i].y * v[i].y;
-            ss = wsum(ss);
-            r = 1.0f / sqrtf(ss / (float)K + eps);
-        }
-#pragma unroll
-        for (int i = 0; i < KREG; ++i) {
-            int j = (i * 64 + lane) * 2;
-            if (j < K) {
-                float a = v[i].x, b = v[i].y;
+        for (int q = 0; q < RB; ++q) {
+            const int c = io + (q0 + q) * kNIO;
+            if (c < MR) {
+                float r = 1.f;
                 if (NORM) {
-                    unsigned g2 = *reinterpret_cast<const unsigned*>(gain + j);
-                    a = a * r * bf16_f32(g2 & 0xFFFFu);
-                    b = b * r * bf16_f32(g2 >> 16);
+                    float ss = 0.f;
+#pragma unroll
+                    for (int i = 0; i < KREG; ++i)
+                        ss += v[q][i].x * v[q][i].x + v[q][i].y * v[q][i].y + v[q][i].z * v[q][i].z + v[q][i].w * v[q][i].w;
+                    ss = wsum(ss);
+                    r = 1.0f / sqrtf(ss / (float)K + eps);
                 }
-                unsigned ha = bf16_rne(a), hb = bf16_rne(b);
-                unsigned la = bf16_rne(a - bf16_f32(ha)), lb = bf16_rne(b - bf16_f32(hb));
-                *reinterpret_cast<unsigned*>(act_hi + (size_t)c * Kp + j) = ha | (hb << 16);
-                *reinterpret_cast<unsigned*>(act_lo + (size_t)c * Kp + j) = la | (lb << 16);
+#pragma unroll
+                for (int i = 0; i < KREG; ++i) {
+                    const int j = (i * 64 + lane) * 4;
+                    if (j < K) {
+                        float4 y = v[q][i];
+                        if (NORM) {
+                            y.x = y.x * r * bf16_f32(g[i].x & 0xFFFFu);
+                            y.y = y.y * r * bf16_f32(g[i].x >> 16);
+                            y.z = y.z * r * bf16_f32(g[i].y & 0xFFFFu);
+                            y.w = y.w * r * bf16_f32(g[i].y >> 16);
+                        }
+                        put_split(y, act_hi + (size_t)c * Kp + j, act_lo + (size_t)c * Kp + j);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// Stage the attention output rows for the Wo stage: merges the NC chunk partials of every
+// (sequence, head) - softmax statistics (max, sum) and un-normalised outputs - on the fly.
+template <int KREG>
+__device__ __forceinline__ void stage_attention(const SP& p, int layer, int io, int lane, uint16_t* act_hi,
+                                                uint16_t* act_lo) {
+    const float* P = slot(p, layer) + p.ap;
+    const int d = p.d, RS = p.RS, NC = p.NC;
+    for (int c = io; c < p.MR; c += kNIO) {
+        const int seq = c / RS, r = c - seq * RS;
+        float4 o[KREG][kNCMax];
+        float2 st[KREG][kNCMax];
+#pragma unroll
+        for (int i = 0; i < KREG; ++i) {
+            const int j = (i * 64 + lane) * 4;
+            const int h = j >> 6, dim = j & 63;
+#pragma unroll
+            for (int cc = 0; cc < kNCMax; ++cc) {
+                const bool on = j < d && cc < NC;
+                const float* row = P + ((size_t)((seq * p.H + (on ? h : 0)) * NC + (on ? cc : 0)) * RS + r) * kPS;
+                o[i][cc] = on ? *reinterpret_cast<const float4*>(row + dim) : make_float4(0.f, 0.f, 0.f, 0.f);
+                st[i][cc] = on ? *reinterpret_cast<const float2*>(row + 64) : make_float2(-1e30f, 0.f);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < KREG; ++i) {
+            const int j = (i * 64 + lane) * 4;
+            if (j < d) {
+                float m2 = -1e30f;
+#pragma unroll
+                for (int cc = 0; cc < kNCMax; ++cc) m2 = fmaxf(m2, st[i][cc].x);
+                float dn = 0.f;
+                float4 y = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                for (int cc = 0; cc < kNCMax; ++cc) {
+                    const float f = __expf(st[i][cc].x - m2);
+                    dn += st[i][cc].y * f;
+                    y.x += o[i][cc].x * f; y.y += o[i][cc].y * f; y.z += o[i][cc].z * f; y.w += o[i][cc].w * f;
+                }
+                const float inv = dn > 0.f ? 1.0f / dn : 0.f;
+                y.x *= inv; y.y *= inv; y.z *= inv; y.w *= inv;
+                put_split(y, act_hi + (size_t)c * p.Kp + j, act_lo + (size_t)c * p.Kp + j);
             }
         }
     }
@@ -215,6 +314,9 @@ __device__ __forceinline__ void mfma_job(const v4u (&w)[kTMax], int nstrips, int
     const uint16_t* bl_base = act_lo + (size_t)(live ? col : 0) * Kp + kg * 8 + (size_t)wave * TPS * 32;
     const v4u zero = (v4u){0u, 0u, 0u, 0u};
     v4u bh[3], bl[3];
+    f32x4 acl[NS];
+#pragma unroll
+    for (int si = 0; si < NS; ++si) acl[si] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int j = 0; j < 2 && j < TPS; ++j) {
         bh[j] = live ? *reinterpret_cast<const v4u*>(bh_base + j * 32) : zero;
@@ -229,14 +331,16 @@ __device__ __forceinline__ void mfma_job(const v4u (&w)[kTMax], int nstrips, int
         const bf16x8 h = __builtin_bit_cast(bf16x8, bh[j % 3]), l = __builtin_bit_cast(bf16x8, bl[j % 3]);
 #pragma unroll
         for (int si = 0; si < NS; ++si) {
-            if (si < nstrips) {
+            if (si < nstrips) {  // hi and lo products accumulate in separate chains (no back-to-back dependency)
                 const bf16x8 a = __builtin_bit_cast(bf16x8, w[si * TPS + j]);
                 acc[si] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, h, acc[si], 0, 0, 0);
-                acc[si] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, l, acc[si], 0, 0, 0);
+                acl[si] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, l, acl[si], 0, 0, 0);
             }
         }
         __builtin_amdgcn_sched_barrier(0);
     }
+#pragma unroll
+    for (int si = 0; si < NS; ++si) acc[si] += acl[si];
 }
 
 struct RowPos { int seq, r, pos; bool valid; };
@@ -253,46 +357,87 @@ __device__ __forceinline__ RowPos row_pos(const SP& p, int c) {
 
 // ------------------------------------------------------------------------- GEMV phases
 
-// vals[si][row][col] holds the finished strip; writes it where the next stage expects it.
+// Operands of a strip's epilogue that do not depend on this stage (residual slice, rotary
+// factors), fetched by the epilogue wave before the barrier is crossed.
+struct EpiPre {
+    float res[4];    // residual x[c][strip*16 + row] of items e = lane + 64 q
+    float2 rot[2];   // cos, sin of items idx = lane + 64 q
+};
+
 template <int KIND>
-__device__ __forceinline__ void epilogue(const SP& p, int layer, int strip, const float* vals, int lane) {
+__device__ __forceinline__ void epilogue_prefetch(const SP& p, int layer, int strip, int lane, EpiPre& pre) {
     const int MR = p.MR, d = p.d;
     if (KIND == K_A) {
-        const int o0 = strip * 16, seg = o0 / d, j0 = o0 - seg * d;
-        const int hd = d / p.H;
-        for (int idx = lane; idx < 8 * MR; idx += 64) {
-            const int t = idx & 7, c = idx >> 3;
-            float e0 = vals[(2 * t) * 16 + c], e1 = vals[(2 * t + 1) * 16 + c];
-            const RowPos rp = row_pos(p, c);
-            if (seg < 2) {
-                const float2 cs = p.rope[(size_t)rp.pos * (hd / 2) + ((j0 % hd) >> 1) + t];
-                const float a = e0 * cs.x - e1 * cs.y, b = e0 * cs.y + e1 * cs.x;
-                e0 = a; e1 = b;
-            }
-            if (seg == 0) {
-                st_f32x2(p.Q + (size_t)c * d + j0 + 2 * t, e0, e1);
-            } else if (rp.valid) {
-                _Float16* dst = (seg == 1 ? p.Kc : p.Vc) +
-                                (((size_t)layer * p.Smax + rp.seq) * p.Tmax + rp.pos) * d + j0 + 2 * t;
-                const _Float16 h0 = (_Float16)e0, h1 = (_Float16)e1;
-                const unsigned pk = (unsigned)__builtin_bit_cast(unsigned short, h0) |
-                                    ((unsigned)__builtin_bit_cast(unsigned short, h1) << 16);
-                __hip_atomic_store(reinterpret_cast<unsigned*>(dst), pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int o0 = strip * 16, seg = o0 / d, j0 = o0 - seg * d, hd = d / p.H;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int idx = lane + 64 * q;
+            pre.rot[q] = make_float2(1.f, 0.f);
+            if (idx < 8 * MR && seg < 2) {
+                const RowPos rp = row_pos(p, idx >> 3);
+                pre.rot[q] = p.rope[(size_t)rp.pos * (hd / 2) + ((j0 % hd) >> 1) + (idx & 7)];
             }
         }
     } else if (KIND == K_C || KIND == K_E) {
-        const float* in = KIND == K_C ? p.X : p.X2;
-        float* out = KIND == K_C ? p.X2 : p.X;
-        for (int e = lane; e < 16 * MR; e += 64) {
-            const int row = e & 15, c = e >> 4;
-            const size_t at = (size_t)c * d + strip * 16 + row;
-            st_f32(out + at, ld_f32(in + at) + vals[row * 16 + c]);
+        const float* in = KIND == K_C ? x_in(p, layer) : slot(p, layer) + p.ax2;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int e = lane + 64 * q;
+            pre.res[q] = e < 16 * MR ? in[(size_t)(e >> 4) * d + strip * 16 + (e & 15)] : 0.f;
+        }
+    }
+}
+
+// vals[row][col] holds the finished strip; writes it where the next stage expects it.
+template <int KIND>
+__device__ __forceinline__ void epilogue(const SP& p, int layer, int strip, const float* vals, int lane,
+                                         const EpiPre& pre) {
+    const int MR = p.MR, d = p.d;
+    if (KIND == K_A) {
+        const int o0 = strip * 16, seg = o0 / d, j0 = o0 - seg * d;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int idx = lane + 64 * q;
+            if (idx < 8 * MR) {
+                const int t = idx & 7, c = idx >> 3;
+                float e0 = vals[(2 * t) * 16 + c], e1 = vals[(2 * t + 1) * 16 + c];
+                const float2 cs = pre.rot[q];  // (1, 0) for the value rows
+                const float a = e0 * cs.x - e1 * cs.y, b = e0 * cs.y + e1 * cs.x;
+                e0 = a; e1 = b;
+                if (seg == 0) {
+                    st_f32x2(slot(p, layer) + p.aq + (size_t)c * d + j0 + 2 * t, e0, e1);
+                } else {
+                    const RowPos rp = row_pos(p, c);
+                    if (rp.valid) {
+                        _Float16* dst = (seg == 1 ? p.Kc : p.Vc) +
+                                        (((size_t)layer * p.Smax + rp.seq) * p.Tmax + rp.pos) * d + j0 + 2 * t;
+                        const _Float16 h0 = (_Float16)e0, h1 = (_Float16)e1;
+                        const unsigned pk = (unsigned)__builtin_bit_cast(unsigned short, h0) |
+                                            ((unsigned)__builtin_bit_cast(unsigned short, h1) << 16);
+                        __hip_atomic_store(reinterpret_cast<unsigned*>(dst), pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                }
+            }
+        }
+    } else if (KIND == K_C || KIND == K_E) {
+        // residual add: x' = x + Wo o (stage C), x(next layer) = x' + W2 h (stage E)
+        float* out = KIND == K_C ? slot(p, layer) + p.ax2 : slot(p, layer + 1) + p.ax;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int e = lane + 64 * q;
+            if (e < 16 * MR) {
+                const int row = e & 15, c = e >> 4;
+                const size_t at = (size_t)c * d + strip * 16 + row;
+                const float y = pre.res[q] + vals[row * 16 + c];
+                st_f32(out + at, y);
+                if (KIND == K_E && layer == p.L - 1) p.X[at] = y;  // final hidden rows, for the next kernel
+            }
         }
     } else if (KIND == K_D) {
         for (int e = lane; e < 8 * MR; e += 64) {
             const int i = e & 7, c = e >> 3;
             const float u1 = vals[i * 16 + c], u3 = vals[(8 + i) * 16 + c];
-            st_f32(p.Hb + (size_t)c * p.m + strip * 8 + i, u1 / (1.0f + expf(-u1)) * u3);
+            st_f32(slot(p, layer) + p.ah + (size_t)c * p.m + strip * 8 + i, u1 / (1.0f + expf(-u1)) * u3);
         }
     } else if (KIND == K_LM) {
         for (int e = lane; e < 16 * MR; e += 64) {
@@ -305,10 +450,23 @@ __device__ __forceinline__ void epilogue(const SP& p, int layer, int strip, cons
 struct Lds {
     uint16_t* act_hi;
     uint16_t* act_lo;
-    float* red;   // [kCW][kMaxStrips][64][4]
-    float* vals;  // [kMaxStrips][16][16]
-    float* att;   // attention scratch
+    float* red;      // [kCW][kMaxStrips][64][4]
+    float* vals;     // [kMaxStrips][16][16]
+    float* att;      // attention: scaled queries
+    unsigned* join;  // arrivals of the IO waves (only ever grows)
 };
+
+// Waits until all IO waves of the workgroup have reached this point of stage `bar.id`
+// (their global stores already acknowledged).  LDS only; bounded like the grid barrier.
+__device__ __forceinline__ void io_join(const Lds& s, Barrier& bar, int lane) {
+    const unsigned want = ++bar.joins * kNIO;
+    if (lane == 0) atomicAdd(s.join, 1u);
+    for (unsigned spins = 0; spins < kSpinLimit; ++spins) {
+        if ((int)(__hip_atomic_load(s.join, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - want) >= 0) break;
+        __builtin_amdgcn_s_sleep(1);
+    }
+    compiler_fence();
+}
 
 template <int KIND, int TPS, bool NORM, int KREG>
 __device__ __forceinline__ void gemv_phase(const SP& p, const Lds& s, Barrier& bar, int layer, int round,
@@ -316,15 +474,33 @@ __device__ __forceinline__ void gemv_phase(const SP& p, const Lds& s, Barrier& b
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const bool is_io = wave >= kCW;
     const Job job = load_job(p, KIND, round, layer);
-    // The weights do not depend on the previous stage: their loads go out before the barrier is
-    // crossed and land while the IO waves synchronise and stage the input.
+    const unsigned ph = bar.id - bar.first;
+    // Nothing below depends on the previous stage, so it is requested before the barrier is
+    // crossed and lands while the IO waves synchronise: the weights (compute waves), the norm
+    // gains and the epilogue's residual slice / rotary factors (IO waves).
     v4u w[kTMax];
-    if (!is_io) issue_tiles(p, job, TPS, wave, lane, w);
-    if (is_io) {
+    uint2 g[KREG];
+    EpiPre pre[kMaxStrips];
+    if (!is_io) {
+        issue_tiles(p, job, TPS, wave, lane, w);
+    } else {
+        stamp(p, ph, 0);
+        if (NORM && job.nstrips) load_gains<KREG>(gain, K, lane, g);
+        if (wave == kCW) {
+#pragma unroll
+            for (int i = 0; i < kMaxStrips; ++i)
+                if (i < job.nstrips) epilogue_prefetch<KIND>(p, layer, job.strip[i], lane, pre[i]);
+        }
         bar.wait();
-        if (job.nstrips) stage_rows<NORM, KREG>(src, K, p.MR, gain, p.eps, wave - kCW, lane, s.act_hi, s.act_lo, p.Kp);
+        stamp(p, ph, 1);
+        if (job.nstrips) {
+            if (KIND == K_C) stage_attention<KREG>(p, layer, wave - kCW, lane, s.act_hi, s.act_lo);
+            else stage_rows<NORM, KREG>(src, K, p.MR, g, p.eps, wave - kCW, lane, s.act_hi, s.act_lo, p.Kp);
+        }
+        stamp(p, ph, 2);
     }
     __syncthreads();
+    stamp(p, ph, 3);
     if (!is_io && job.nstrips) {
         f32x4 acc[kMaxStrips];
 #pragma unroll
@@ -335,6 +511,7 @@ __device__ __forceinline__ void gemv_phase(const SP& p, const Lds& s, Barrier& b
             if (i < job.nstrips) *reinterpret_cast<f32x4*>(s.red + (((size_t)wave * kMaxStrips + i) * 64 + lane) * 4) = acc[i];
     }
     __syncthreads();
+    stamp(p, ph, 4);
     if (wave == kCW) {
 #pragma unroll
         for (int i = 0; i < kMaxStrips; ++i) {
@@ -348,12 +525,14 @@ __device__ __forceinline__ void gemv_phase(const SP& p, const Lds& s, Barrier& b
                 for (int q = 0; q < 4; ++q) vs[((lane >> 4) * 4 + q) * 16 + (lane & 15)] = v[q];
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the LDS writes above are visible to the wave
-                epilogue<KIND>(p, layer, job.strip[i], vs, lane);
+                epilogue<KIND>(p, layer, job.strip[i], vs, lane, pre[i]);
                 __builtin_amdgcn_wave_barrier();
             }
         }
         __builtin_amdgcn_s_waitcnt(0);  // results are out before this workgroup arrives
+        stamp(p, ph, 5);
         if (lane == 0) bar.arrive(); else ++bar.id;
+        stamp(p, ph, 6);
     } else {
         ++bar.id;
     }
@@ -361,158 +540,162 @@ __device__ __forceinline__ void gemv_phase(const SP& p, const Lds& s, Barrier& b
 
 // ------------------------------------------------------------------------- attention
 
-// Stage 1: workgroup (seq, head, chunk) reduces its slice of cache positions for the RS rows
-// of its sequence to an un-normalised partial (m, l, o~).  RSMAX bounds the register arrays.
+// Workgroup (seq, head, chunk) reduces its slice of the cached positions - requested before
+// the barrier is crossed, they were written by earlier launches - and, for the last chunk,
+// the rows appended by this launch, to an un-normalised partial (m, l, o~) per query row.
+// Lane layout: 8 positions per wave load, 8 lanes x 8 dims per position.
+struct AttnAcc {
+    float acc[8], mx, den;
+};
+
+// Sum over the 8 lanes that share a cache position (cross-lane moves in the VALU, no LDS).
+__device__ __forceinline__ float sum8(float v) {
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // row_half_mirror
+    return v;
+}
+
 template <int RSMAX>
-__device__ __forceinline__ void attn_partial(const SP& p, const Lds& s, Barrier& bar, int layer) {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const bool is_io = wave >= kCW;
-    const int njobs = p.S * p.H * p.NC;
-    const int wg = blockIdx.x;
-    const bool have = wg < njobs;
-    const int seq = wg / (p.H * p.NC), h = (wg / p.NC) % p.H, ch = wg % p.NC;
-    const int d = p.d, RS = p.RS;
-    float* qs = s.att;                      // [RS][64] scaled queries
-    float* part = s.att + 8 * 64;           // [kCW][RS][66]
-    if (is_io) {
-        bar.wait();
-        if (have && wave == kCW)
-            for (int r = 0; r < RS; ++r) qs[r * 64 + lane] = ld_f32(p.Q + (size_t)(seq * RS + r) * d + h * 64 + lane) * 0.125f;
+__device__ __forceinline__ void attend(const float* qs, int RS, int dg, v4u kraw, v4u vraw, int row_lo, int ke,
+                                       AttnAcc (&A)[RSMAX]) {
+    float kf[8], vf[8];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        kf[2 * e] = (float)__builtin_bit_cast(_Float16, (unsigned short)(kraw[e] & 0xFFFFu));
+        kf[2 * e + 1] = (float)__builtin_bit_cast(_Float16, (unsigned short)(kraw[e] >> 16));
+        vf[2 * e] = (float)__builtin_bit_cast(_Float16, (unsigned short)(vraw[e] & 0xFFFFu));
+        vf[2 * e + 1] = (float)__builtin_bit_cast(_Float16, (unsigned short)(vraw[e] >> 16));
     }
-    __syncthreads();
-    if (!is_io && have) {
-        const int b = seq % p.B, ke = p.k_eff[b];
-        const int kv0 = ke >= 0 ? p.C + p.n[b] - 1 : 0;   // cached positions before this step
-        const int total = ke >= 0 ? kv0 + ke + 1 : 0;     // positions any row may attend
-        const int p0 = (int)((long long)total * ch / p.NC), p1 = (int)((long long)total * (ch + 1) / p.NC);
-        const int pg = lane >> 3, dg = lane & 7;
-        float acc[RSMAX][8], mx[RSMAX], den[RSMAX];
 #pragma unroll
-        for (int r = 0; r < RSMAX; ++r) {
-            mx[r] = -1e30f; den[r] = 0.f;
+    for (int r = 0; r < RSMAX; ++r) {
+        if (r < RS) {
+            const float4 qa = *reinterpret_cast<const float4*>(qs + r * 64 + dg * 8);
+            const float4 qb = *reinterpret_cast<const float4*>(qs + r * 64 + dg * 8 + 4);
+            float sc = qa.x * kf[0] + qa.y * kf[1] + qa.z * kf[2] + qa.w * kf[3] + qb.x * kf[4] + qb.y * kf[5] +
+                       qb.z * kf[6] + qb.w * kf[7];
+            sc = sum8(sc);
+            if (r >= row_lo && r <= ke) {  // row_lo: first query row that may see this position
+                const float mn = fmaxf(A[r].mx, sc);
+                const float corr = __expf(A[r].mx - mn), pw = __expf(sc - mn);
+                A[r].den = A[r].den * corr + pw;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[r][e] = 0.f;
-        }
-        const size_t base = (((size_t)layer * p.Smax + seq) * p.Tmax) * d + (size_t)h * 64 + dg * 8;
-        for (int pos = p0 + wave * 8 + pg; pos < p1; pos += kCW * 8) {
-            uint4 kraw, vraw;
-            const _Float16* kp = p.Kc + base + (size_t)pos * d;
-            const _Float16* vp = p.Vc + base + (size_t)pos * d;
-            if (pos >= kv0) {  // written by this launch: device-coherent loads
-                u64 a0 = __hip_atomic_load(reinterpret_cast<const u64*>(kp), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                u64 a1 = __hip_atomic_load(reinterpret_cast<const u64*>(kp) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                u64 b0 = __hip_atomic_load(reinterpret_cast<const u64*>(vp), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                u64 b1 = __hip_atomic_load(reinterpret_cast<const u64*>(vp) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                kraw = make_uint4((unsigned)a0, (unsigned)(a0 >> 32), (unsigned)a1, (unsigned)(a1 >> 32));
-                vraw = make_uint4((unsigned)b0, (unsigned)(b0 >> 32), (unsigned)b1, (unsigned)(b1 >> 32));
-            } else {
-                kraw = *reinterpret_cast<const uint4*>(kp);
-                vraw = *reinterpret_cast<const uint4*>(vp);
-            }
-            float kf[8], vf[8];
-            const unsigned ku[4] = {kraw.x, kraw.y, kraw.z, kraw.w}, vu[4] = {vraw.x, vraw.y, vraw.z, vraw.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                kf[2 * e] = (float)__builtin_bit_cast(_Float16, (unsigned short)(ku[e] & 0xFFFFu));
-                kf[2 * e + 1] = (float)__builtin_bit_cast(_Float16, (unsigned short)(ku[e] >> 16));
-                vf[2 * e] = (float)__builtin_bit_cast(_Float16, (unsigned short)(vu[e] & 0xFFFFu));
-                vf[2 * e + 1] = (float)__builtin_bit_cast(_Float16, (unsigned short)(vu[e] >> 16));
-            }
-#pragma unroll
-            for (int r = 0; r < RSMAX; ++r) {
-                if (r < RS) {
-                    const float4 qa = *reinterpret_cast<const float4*>(qs + r * 64 + dg * 8);
-                    const float4 qb = *reinterpret_cast<const float4*>(qs + r * 64 + dg * 8 + 4);
-                    float sc = qa.x * kf[0] + qa.y * kf[1] + qa.z * kf[2] + qa.w * kf[3] + qb.x * kf[4] + qb.y * kf[5] +
-                               qb.z * kf[6] + qb.w * kf[7];
-                    sc += __shfl_xor(sc, 1, 64);
-                    sc += __shfl_xor(sc, 2, 64);
-                    sc += __shfl_xor(sc, 4, 64);
-                    if (pos <= kv0 + r && r <= ke) {  // causal inside the block of new rows
-                        const float mn = fmaxf(mx[r], sc);
-                        const float corr = __expf(mx[r] - mn), pw = __expf(sc - mn);
-                        den[r] = den[r] * corr + pw;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) acc[r][e] = acc[r][e] * corr + pw * vf[e];
-                        mx[r] = mn;
-                    }
-                }
+                for (int e = 0; e < 8; ++e) A[r].acc[e] = A[r].acc[e] * corr + pw * vf[e];
+                A[r].mx = mn;
             }
         }
-        // merge the 8 position groups of the wave (lanes that share dg), then hand over to LDS
-#pragma unroll
-        for (int r = 0; r < RSMAX; ++r) {
-            if (r < RS) {
-                float m2 = mx[r];
-                m2 = fmaxf(m2, __shfl_xor(m2, 8, 64));
-                m2 = fmaxf(m2, __shfl_xor(m2, 16, 64));
-                m2 = fmaxf(m2, __shfl_xor(m2, 32, 64));
-                const float f = __expf(mx[r] - m2);
-                float dn = den[r] * f;
-                dn += __shfl_xor(dn, 8, 64); dn += __shfl_xor(dn, 16, 64); dn += __shfl_xor(dn, 32, 64);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    float a = acc[r][e] * f;
-                    a += __shfl_xor(a, 8, 64); a += __shfl_xor(a, 16, 64); a += __shfl_xor(a, 32, 64);
-                    if (pg == 0) part[((size_t)wave * RS + r) * 66 + dg * 8 + e] = a;
-                }
-                if (lane == 0) { part[((size_t)wave * RS + r) * 66 + 64] = m2; part[((size_t)wave * RS + r) * 66 + 65] = dn; }
-            }
-        }
-    }
-    __syncthreads();
-    if (wave == kCW) {
-        if (have) {
-            float* out = p.P + (size_t)wg * RS * 66;
-            for (int r = 0; r < RS; ++r) {
-                float m2 = -1e30f;
-                for (int cw = 0; cw < kCW; ++cw) m2 = fmaxf(m2, part[((size_t)cw * RS + r) * 66 + 64]);
-                float dn = 0.f, o = 0.f;
-                for (int cw = 0; cw < kCW; ++cw) {
-                    const float f = __expf(part[((size_t)cw * RS + r) * 66 + 64] - m2);
-                    dn += part[((size_t)cw * RS + r) * 66 + 65] * f;
-                    o += part[((size_t)cw * RS + r) * 66 + lane] * f;
-                }
-                st_f32(out + r * 66 + lane, o);
-                if (lane == 0) st_f32x2(out + r * 66 + 64, m2, dn);
-            }
-        }
-        __builtin_amdgcn_s_waitcnt(0);
-        if (lane == 0) bar.arrive(); else ++bar.id;
-    } else {
-        ++bar.id;
     }
 }
 
-// Stage 2: workgroup (seq, head) merges the NC chunk partials into the attention output.
-__device__ __forceinline__ void attn_merge(const SP& p, Barrier& bar) {
+template <int RSMAX>
+__device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& bar, int layer) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const bool is_io = wave >= kCW;
-    if (is_io) bar.wait();
+    const int wg = blockIdx.x;
+    const bool have = wg < p.S * p.H * p.NC;
+    const int seq = wg / (p.H * p.NC), h = (wg / p.NC) % p.H, ch = wg % p.NC;
+    const int d = p.d, RS = p.RS;
+    float* qs = s.att;                                   // [RS][64] scaled queries
+    float* part = reinterpret_cast<float*>(s.act_hi);    // [kCW*8][RSMAX][kPS], over the idle activation buffers
+    const unsigned ph = bar.id - bar.first;
+    const int pg = lane >> 3, dg = lane & 7;
+    const int b = seq % p.B;
+    const int ke = have ? p.k_eff[b] : -1;
+    const int kv0 = ke >= 0 ? p.C + p.n[b] - 1 : 0;  // positions cached before this launch
+    const int o0 = (int)((long long)kv0 * ch / p.NC), o1 = (int)((long long)kv0 * (ch + 1) / p.NC);
+    const size_t base = (((size_t)layer * p.Smax + seq) * p.Tmax) * d + (size_t)h * 64 + dg * 8;
+    v4u kk[kNIT], vv[kNIT];
+    if (!is_io && have) {
+#pragma unroll
+        for (int it = 0; it < kNIT; ++it) {
+            const int pos = o0 + it * (kCW * 8) + wave * 8 + pg;
+            if (pos < o1) {
+                kk[it] = *reinterpret_cast<const v4u*>(p.Kc + base + (size_t)pos * d);
+                vv[it] = *reinterpret_cast<const v4u*>(p.Vc + base + (size_t)pos * d);
+            } else {
+                kk[it] = (v4u){0u, 0u, 0u, 0u};
+                vv[it] = (v4u){0u, 0u, 0u, 0u};
+            }
+        }
+    }
+    if (is_io) {
+        stamp(p, ph, 0);
+        bar.wait();
+        stamp(p, ph, 1);
+        if (have && wave == kCW)
+            for (int r = 0; r < RS; ++r)
+                qs[r * 64 + lane] = (slot(p, layer) + p.aq)[(size_t)(seq * RS + r) * d + h * 64 + lane] * 0.125f;
+        stamp(p, ph, 2);
+    }
     __syncthreads();
-    if (wave == kCW) {
-        const int wg = blockIdx.x;
-        if (wg < p.S * p.H) {
-            const int seq = wg / p.H, h = wg % p.H;
-            for (int r = 0; r < p.RS; ++r) {
+    stamp(p, ph, 3);
+    if (!is_io && have) {
+        AttnAcc A[RSMAX];
+#pragma unroll
+        for (int r = 0; r < RSMAX; ++r) {
+            A[r].mx = -1e30f; A[r].den = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) A[r].acc[e] = 0.f;
+        }
+#pragma unroll
+        for (int it = 0; it < kNIT; ++it) {
+            const int pos = o0 + it * (kCW * 8) + wave * 8 + pg;
+            if (pos < o1) attend<RSMAX>(qs, RS, dg, kk[it], vv[it], 0, ke, A);
+        }
+        if (ch == p.NC - 1 && wave == 0 && pg <= ke) {  // rows appended by this launch: coherent loads
+            const _Float16* kp = p.Kc + base + (size_t)(kv0 + pg) * d;
+            const _Float16* vp = p.Vc + base + (size_t)(kv0 + pg) * d;
+            const u64 a0 = __hip_atomic_load(reinterpret_cast<const u64*>(kp), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const u64 a1 = __hip_atomic_load(reinterpret_cast<const u64*>(kp) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const u64 b0 = __hip_atomic_load(reinterpret_cast<const u64*>(vp), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const u64 b1 = __hip_atomic_load(reinterpret_cast<const u64*>(vp) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const v4u kraw = (v4u){(unsigned)a0, (unsigned)(a0 >> 32), (unsigned)a1, (unsigned)(a1 >> 32)};
+            const v4u vraw = (v4u){(unsigned)b0, (unsigned)(b0 >> 32), (unsigned)b1, (unsigned)(b1 >> 32)};
+            attend<RSMAX>(qs, RS, dg, kraw, vraw, pg, ke, A);  // row r sees appended row pg iff pg <= r
+        }
+        // hand the (wave, lane group) partials to the IO waves through LDS (the activation
+        // buffers are idle during this stage): [wave*8 + pg][row][kPS]
+        float* mine = part + ((size_t)(wave * 8 + pg) * RSMAX) * kPS + dg * 8;
+#pragma unroll
+        for (int r = 0; r < RSMAX; ++r) {
+            if (r < RS) {
+                *reinterpret_cast<float4*>(mine + r * kPS) = make_float4(A[r].acc[0], A[r].acc[1], A[r].acc[2], A[r].acc[3]);
+                *reinterpret_cast<float4*>(mine + r * kPS + 4) = make_float4(A[r].acc[4], A[r].acc[5], A[r].acc[6], A[r].acc[7]);
+                if (dg == 0) *reinterpret_cast<float2*>(mine + r * kPS + 64) = make_float2(A[r].mx, A[r].den);
+            }
+        }
+    }
+    __syncthreads();
+    stamp(p, ph, 4);
+    if (is_io) {
+        if (have) {  // IO wave i merges the 32 partials of rows i, i + kNIO, ...; lane = output dim
+            float* out = slot(p, layer) + p.ap + (size_t)wg * RS * kPS;
+            for (int r = wave - kCW; r < RS; r += kNIO) {
                 float m2 = -1e30f;
-                const float* src = p.P + ((size_t)wg * p.NC) * p.RS * 66 + (size_t)r * 66;
-                for (int c = 0; c < p.NC; ++c) m2 = fmaxf(m2, ld_f32(src + (size_t)c * p.RS * 66 + 64));
+                for (int g = 0; g < kCW * 8; ++g) m2 = fmaxf(m2, part[((size_t)g * RSMAX + r) * kPS + 64]);
                 float dn = 0.f, o = 0.f;
-                for (int c = 0; c < p.NC; ++c) {
-                    const float f = __expf(ld_f32(src + (size_t)c * p.RS * 66 + 64) - m2);
-                    dn += ld_f32(src + (size_t)c * p.RS * 66 + 65) * f;
-                    o += ld_f32(src + (size_t)c * p.RS * 66 + lane) * f;
+                for (int g = 0; g < kCW * 8; ++g) {
+                    const float* src = part + ((size_t)g * RSMAX + r) * kPS;
+                    const float f = __expf(src[64] - m2);
+                    dn += src[65] * f;
+                    o += src[lane] * f;
                 }
-                st_f32(p.O + (size_t)(seq * p.RS + r) * p.d + h * 64 + lane, dn > 0.f ? o / dn : 0.f);
+                st_f32(out + r * kPS + lane, o);
+                if (lane == 0) st_f32x2(out + r * kPS + 64, m2, dn);
             }
         }
         __builtin_amdgcn_s_waitcnt(0);
-        if (lane == 0) bar.arrive(); else ++bar.id;
+        io_join(s, bar, lane);  // every IO wave's stores are out before the arrival is posted
+        stamp(p, ph, 5);
+        if (wave == kCW) {
+            if (lane == 0) bar.arrive(); else ++bar.id;
+        } else {
+            ++bar.id;
+        }
+        stamp(p, ph, 6);
     } else {
         ++bar.id;
     }
-    __syncthreads();
 }
 
 // ------------------------------------------------------------------------- the kernel
@@ -523,24 +706,26 @@ __global__ __launch_bounds__(kThreads, 1) void verify_stream_kernel(SP p) {
     Lds s;
     s.act_hi = reinterpret_cast<uint16_t*>(smem_raw);
     s.act_lo = s.act_hi + (size_t)p.MR * p.Kp;
-    s.red = reinterpret_cast<float*>(s.act_lo + (size_t)p.MR * p.Kp);
+    s.red = reinterpret_cast<float*>(reinterpret_cast<char*>(smem_raw) + p.act_bytes);
     s.vals = s.red + kCW * kMaxStrips * 64 * 4;
     s.att = s.vals + kMaxStrips * 256;
+    s.join = reinterpret_cast<unsigned*>(s.att + 8 * 64);
+    if (threadIdx.x == 0) *s.join = 0u;
+    __syncthreads();
     Barrier bar;
-    bar.mem = p.bar; bar.err = p.err; bar.id = p.epoch0; bar.first = p.epoch0; bar.dead = false;
+    bar.mem = p.bar; bar.err = p.err; bar.id = p.epoch0; bar.first = p.epoch0; bar.joins = 0; bar.dead = false;
     for (int l = 0; l < p.L; ++l) {
         const uint16_t* g1 = p.blob + (p.g1_off + (u64)l * p.layer_bytes) / 2;
         const uint16_t* g2 = p.blob + (p.g2_off + (u64)l * p.layer_bytes) / 2;
-        gemv_phase<K_A, TPS_D, true, KREG_D>(p, s, bar, l, 0, p.X, p.d, g1);
-        attn_partial<RSMAX>(p, s, bar, l);
-        attn_merge(p, bar);
-        gemv_phase<K_C, TPS_D, false, KREG_D>(p, s, bar, l, 0, p.O, p.d, nullptr);
-        gemv_phase<K_D, TPS_D, true, KREG_D>(p, s, bar, l, 0, p.X2, p.d, g2);
-        gemv_phase<K_E, TPS_M, false, KREG_M>(p, s, bar, l, 0, p.Hb, p.m, nullptr);
+        gemv_phase<K_A, TPS_D, true, KREG_D>(p, s, bar, l, 0, x_in(p, l), p.d, g1);
+        attn_phase<RSMAX>(p, s, bar, l);
+        gemv_phase<K_C, TPS_D, false, KREG_D>(p, s, bar, l, 0, nullptr, p.d, nullptr);
+        gemv_phase<K_D, TPS_D, true, KREG_D>(p, s, bar, l, 0, slot(p, l) + p.ax2, p.d, g2);
+        gemv_phase<K_E, TPS_M, false, KREG_M>(p, s, bar, l, 0, slot(p, l) + p.ah, p.m, nullptr);
     }
     const uint16_t* gf = p.blob + p.gf_off / 2;
     for (int r = 0; r < p.rounds[K_LM]; ++r)
-        gemv_phase<K_LM, TPS_D, true, KREG_D>(p, s, bar, p.L - 1, r, p.X, p.d, gf);
+        gemv_phase<K_LM, TPS_D, true, KREG_D>(p, s, bar, p.L - 1, r, slot(p, p.L) + p.ax, p.d, gf);
 }
 
 // Copies one matrix into the tile order of its kind: tile T of the packed stream is
@@ -550,8 +735,14 @@ __global__ void repack_kernel(const uint16_t* W, int K, int kind, int m, int row
     const int lane = threadIdx.x;
     const uint32_t dsc = desc[tile];
     const int strip = dsc >> 12, kt = dsc & 4095, r = lane & 15;
-    const size_t row = kind == K_D ? (size_t)((r < 8 ? 0 : m) + strip * 8 + (r & 7)) : (size_t)(row0 + strip * 16 + r);
-    out[tile * 64 + lane] = *reinterpret_cast<const uint4*>(W + row * K + kt * 32 + (lane >> 4) * 8);
+    size_t row = (size_t)(row0 + strip * 16 + r), col = (size_t)kt * 32 + (lane >> 4) * 8;
+    if (kind == K_D) row = (size_t)((r < 8 ? 0 : m) + strip * 8 + (r & 7));
+    if (kind == K_WD) {  // strip = block * (d/16) + s of the [d, 3d] matrix, K = 3d, row0 carries d
+        const int per = row0 / 16, blk = strip / per;
+        row = (size_t)((strip - blk * per) * 16 + r);
+        col += (size_t)blk * row0;
+    }
+    out[tile * 64 + lane] = *reinterpret_cast<const uint4*>(W + row * K + col);
 }
 
 // ------------------------------------------------------------------------- host: plan
@@ -572,8 +763,8 @@ struct StreamPlan {
     std::vector<int32_t> tab;
     std::vector<uint32_t> desc;
     std::vector<uint32_t> hasmask;
-    unsigned epoch;
-    size_t lds_bytes_per_row;
+    unsigned epoch;     // grid barriers completed by all launches so far
+    unsigned launches;
 };
 
 namespace {
@@ -582,7 +773,7 @@ bool shape_ok(const hawk_ctx* c) {
     if (c->cfg.dtype != HAWK_BF16) return false;
     if (c->hd != 64) return false;
     if (c->d % 128 || c->m % 128 || c->Vs % 16 || (3 * c->d) % 128) return false;
-    if (c->d / 128 > kTMax || c->m / 128 > kTMax || 3 * c->d / 128 > kTMax) return false;
+    if (c->d / 128 > kTMax || c->m / 128 > kTMax) return false;
     if (!((c->d == 1280 && c->m == 3456) || (c->d == 768 && c->m == 2048))) return false;  // instantiated tilings
     if (c->Vs / 16 > 65535 || (2 * c->m) / 16 > 65535) return false;
     return true;
@@ -595,8 +786,10 @@ void build_plan(const hawk_ctx* c, StreamPlan* P) {
     P->ok = shape_ok(c);
     if (!P->ok) return;
     const int d = c->d, m = c->m;
-    const int nstrips[K_NKIND] = {3 * d / 16, d / 16, 2 * m / 16, d / 16, c->Vs / 16, d / 16};
-    const int KT[K_NKIND] = {d / 32, d / 32, d / 32, m / 32, d / 32, 3 * d / 32};
+    // The draft projection W_d [d, 3d] is planned as three [d, d] blocks (previous head output,
+    // left neighbour, upper neighbour): 3 d/16 strips whose partial outputs the consumer adds.
+    const int nstrips[K_NKIND] = {3 * d / 16, d / 16, 2 * m / 16, d / 16, c->Vs / 16, 3 * d / 16};
+    const int KT[K_NKIND] = {d / 32, d / 32, d / 32, m / 32, d / 32, d / 32};
     for (int k = 0; k < K_NKIND; ++k) {
         KindPlan& kp = P->kind[k];
         kp.nstrips = nstrips[k]; kp.KT = KT[k]; kp.TPS = KT[k] / 4;
@@ -682,10 +875,12 @@ size_t stream_workspace(const hawk_ctx* c, size_t base, StreamOffsets* o) {
     o->tab = take((size_t)(K_NKIND + (size_t)c->Vs / 16 / kNWG + 2) * kNWG * 16);
     o->desc = take(((4 * d * d + 3 * d * m) / 512 + (size_t)c->Vs * d / 512 + 3 * d * d / 512 + 64) * 4);
     o->hasmask = take(kNWG * 4);
-    o->x2 = take(16 * d * 4); o->q = take(16 * d * 4); o->o = take(16 * d * 4); o->h = take(16 * m * 4);
-    o->p = take((size_t)kNWG * 8 * 66 * 4);
+    // one exchange slot per layer (+1): x, x', q, o [16][d], h [16][m], attention partials; kRing arenas
+    o->slot_bytes = up256((4 * 16 * d + 16 * m + (size_t)kNWG * 8 * kPS) * 4 + 1024);
+    o->arena = take(o->slot_bytes * (L + 1) * kRing);
     o->bar = take((size_t)(kGroups + 1 + kReplicas) * 4096);
     o->err = take(256);
+    o->dbg = take(2 * 4096 * 8 * 8);
     o->rope = take((size_t)c->Tmax * (c->hd / 2) * 8);
     return p - base;
 }
@@ -694,6 +889,7 @@ StreamPlan* stream_create(hawk_ctx* c) {
     StreamPlan* P = new StreamPlan();
     build_plan(c, P);
     P->epoch = 0;
+    P->launches = 0;
     if (!P->ok) return P;
     const StreamOffsets& o = c->soff;
     // tables, rotary table, zeroed barrier memory
@@ -756,14 +952,27 @@ void stream_plan_info(const hawk_ctx* c, int64_t* out) {
     out[6] = sane ? 1 : 0;
 }
 
+// LDS of one workgroup: activation hi/lo (or, during attention, the per-lane-group partials),
+// K-quarter partial strips, finished strips, scaled queries, IO join word.
+static size_t stream_lds_bytes(const hawk_ctx* c, int MR) {
+    const size_t act = std::max((size_t)MR * (std::max(c->d, c->m) + 8) * 4, (size_t)kCW * 8 * 6 * kPS * 4);
+    return act + (kCW * kMaxStrips * 256 + kMaxStrips * 256) * 4 + (8 * 64 + 16) * 4;
+}
+
+// Chunks per (sequence, head) of the attention stage: enough that one chunk's cached positions
+// fit the per-wave register window, more while workgroups are free.
+static int stream_chunks(const hawk_ctx* c) {
+    const int need = (c->Tmax + kNIT * kCW * 8 - 1) / (kNIT * kCW * 8);
+    const int room = kNWG / (c->S * c->H);
+    return std::max(need, std::min(kNCMax, room));
+}
+
 bool stream_ok(const hawk_ctx* c, int k) {
     if (!c->plan || !c->plan->ok || c->path != 1) return false;
     const int MR = c->S * (k + 1);
     if (MR > 16 || k + 1 > 6) return false;
-    if (c->S * c->H > kNWG) return false;
-    const size_t lds = (size_t)MR * (std::max(c->d, c->m) + 8) * 4 + (kCW * kMaxStrips * 256 + kMaxStrips * 256) * 4 +
-                       (8 * 64 + kCW * 8 * 66) * 4;
-    return lds <= 150 * 1024;
+    if (c->S * c->H * stream_chunks(c) > kNWG || stream_chunks(c) > kNCMax) return false;
+    return stream_lds_bytes(c, MR) <= 150 * 1024;
 }
 
 // Re-tiles every matrix of the loaded blob into the streaming order (after hawk_load).
@@ -786,7 +995,7 @@ int stream_repack(hawk_ctx* c) {
         run(c->w.W2[l], c->m, K_E, lb + P->kind_base[K_E], 0);
     }
     run(c->w.W_out, c->d, K_LM, P->lm_base, c->cfg.samp_lo);
-    run(c->w.W_d, 3 * c->d, K_WD, P->wd_base, 0);
+    run(c->w.W_d, 3 * c->d, K_WD, P->wd_base, c->d);
     if (hipGetLastError() != hipSuccess) return -1;
     return hipStreamSynchronize(c->stream) == hipSuccess ? 0 : -1;
 }
@@ -813,23 +1022,30 @@ int launch_verify_stream(hawk_ctx* c, int k) {
     p.gf_off = c->w.g_f;
     p.rope = wsp<float2>(c, o.rope);
     p.Kc = wsp<_Float16>(c, c->off.kc); p.Vc = wsp<_Float16>(c, c->off.vc);
-    p.X = wsp<float>(c, c->off.x); p.X2 = wsp<float>(c, o.x2); p.Q = wsp<float>(c, o.q); p.P = wsp<float>(c, o.p);
-    p.O = wsp<float>(c, o.o); p.Hb = wsp<float>(c, o.h); p.logit_s = wsp<float>(c, c->off.logit_s);
+    p.X = wsp<float>(c, c->off.x);
+    p.arena = wsp<float>(c, o.arena + (size_t)(P->launches % kRing) * o.slot_bytes * (c->L + 1));
+    p.slot_floats = o.slot_bytes / 4;
+    p.ax = 0; p.ax2 = (u64)16 * c->d; p.aq = (u64)32 * c->d; p.ao = (u64)48 * c->d; p.ah = (u64)64 * c->d;
+    p.ap = p.ah + (u64)16 * c->m;
+    p.logit_s = wsp<float>(c, c->off.logit_s);
+    p.dbg = c->stream_dbg ? wsp<u64>(c, o.dbg) : nullptr;
     p.bar = wsp<unsigned>(c, o.bar); p.err = wsp<unsigned>(c, o.err);
     p.n = wsp<int32_t>(c, c->off.n); p.k_eff = wsp<int32_t>(c, c->off.k_eff);
     p.epoch0 = P->epoch;
     p.L = c->L; p.d = c->d; p.H = c->H; p.m = c->m; p.Vs = c->Vs; p.S = c->S; p.B = c->B; p.C = c->C;
     p.RS = k + 1; p.MR = c->S * (k + 1);
-    p.NC = std::max(1, kNWG / (c->S * c->H));
+    p.NC = stream_chunks(c);
     p.Smax = c->Smax; p.Tmax = c->Tmax; p.Kp = std::max(c->d, c->m) + 8;
     p.eps = c->cfg.rms_eps;
-    const size_t lds = (size_t)p.MR * p.Kp * 4 + (kCW * kMaxStrips * 256 + kMaxStrips * 256) * 4 + (8 * 64 + kCW * 8 * 66) * 4;
-    const void* kern = c->d == 1280 ? reinterpret_cast<const void*>(verify_stream_kernel<10, 27, 10, 27, 6>)
-                                    : reinterpret_cast<const void*>(verify_stream_kernel<6, 16, 6, 16, 6>);
+    p.act_bytes = (int32_t)std::max((size_t)p.MR * p.Kp * 4, (size_t)kCW * 8 * 6 * kPS * 4);
+    const size_t lds = stream_lds_bytes(c, p.MR);
+    const void* kern = c->d == 1280 ? reinterpret_cast<const void*>(verify_stream_kernel<10, 27, 5, 14, 6>)
+                                    : reinterpret_cast<const void*>(verify_stream_kernel<6, 16, 3, 8, 6>);
     if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return -1;
     void* args[] = {&p};
     if (hipLaunchCooperativeKernel(kern, dim3(kNWG), dim3(kThreads), args, lds, c->stream) != hipSuccess) return -1;
-    P->epoch += 6u * (unsigned)c->L + (unsigned)P->kind[K_LM].rounds;
+    P->epoch += 5u * (unsigned)c->L + (unsigned)P->kind[K_LM].rounds;
+    P->launches += 1;
     return 0;
 }
 

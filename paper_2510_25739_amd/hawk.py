@@ -70,6 +70,7 @@ EXPORTS = {
     "hawk_get_draft_logits": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int]),
     "hawk_set_path": (C.c_int, [C.c_void_p, C.c_int]),
     "hawk_last_path": (C.c_int, [C.c_void_p]),
+    "hawk_phase_trace": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t]),
 }
 
 
@@ -173,6 +174,15 @@ class Hawk:
 
     def last_path(self) -> int:
         return int(self._L.hawk_last_path(self._h))
+
+    def phase_trace(self, enable: bool, n_stages: int = 0):
+        """Switches the streaming kernel's stage time stamps; returns [2, n_stages, 8] uint64 if asked."""
+        if n_stages <= 0:
+            self._chk(self._L.hawk_phase_trace(self._h, int(enable), None, 0), "hawk_phase_trace")
+            return None
+        out = np.zeros((2, 4096, 8), dtype=np.uint64)
+        self._chk(self._L.hawk_phase_trace(self._h, int(enable), _p(out), out.size), "hawk_phase_trace")
+        return out[:, :n_stages]
 
     def load(self, blob: np.ndarray):
         blob = np.ascontiguousarray(blob, dtype=np.uint8)
