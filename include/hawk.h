@@ -165,9 +165,11 @@ int hawk_generate(hawk_ctx* ctx, const float* cond, const float* uncond, int bat
  * last hawk_generate / hawk_set_replay in point-mass mode.  Steps after every prompt has
  * finished do nothing.  If ms_draft / ms_verify (host, single floats) are both non-NULL the
  * two phases are bracketed by events, the call synchronises and returns the summed GPU
- * milliseconds of each phase; otherwise it returns once the work is enqueued. */
+ * milliseconds of each phase - and in ms_kernel (may be NULL) those of the persistent
+ * target-pass kernel alone (0 if the generic kernels ran); otherwise it returns once the
+ * work is enqueued. */
 int hawk_run_steps(hawk_ctx* ctx, int k, int n_steps, uint64_t seed, int replay, float* ms_draft,
-                   float* ms_verify);
+                   float* ms_verify, float* ms_kernel);
 
 /* Stores the replay table (host [batch, N]) used by hawk_run_steps(replay = 1). */
 int hawk_set_replay(hawk_ctx* ctx, const int32_t* replay_tokens);

@@ -136,7 +136,9 @@ void run_step_rows(hawk_ctx* c, int k) {
     RowMap map = step_map(c, k);
     launch_embed_rows(c, map, M);
     if (stream_ok(c, k)) {  // one persistent kernel: all layers and the output projection
+        if (c->kev_a) (void)hipEventRecord(c->kev_a, c->stream);
         if (launch_verify_stream(c, k) != 0) c->launch_failed = 1;
+        if (c->kev_b) (void)hipEventRecord(c->kev_b, c->stream);
         c->last_path = 1;
         return;
     }
@@ -539,15 +541,16 @@ int hawk_set_replay(hawk_ctx* c, const int32_t* replay_tokens) {
     return upload(c, c->off.replay, replay_tokens, (size_t)c->B * c->N * 4);
 }
 
-int hawk_run_steps(hawk_ctx* c, int k, int n_steps, uint64_t seed, int replay, float* ms_draft, float* ms_verify) {
+int hawk_run_steps(hawk_ctx* c, int k, int n_steps, uint64_t seed, int replay, float* ms_draft, float* ms_verify,
+                   float* ms_kernel) {
     if (!c) return HAWK_EINVAL;
     if (c->phase != 2) return fail(c, HAWK_ESTATE, "hawk_run_steps needs a prefilled context with no draft pending");
     if (k < 0 || k > c->kmax || k > c->gw)
         return fail(c, HAWK_EINVAL, "k = %d outside [0, min(k_max = %d, grid_w = %d)]", k, c->kmax, c->gw);
     if (n_steps < 0 || n_steps > 1 << 20) return fail(c, HAWK_EINVAL, "n_steps out of range");
     const bool timed = ms_draft && ms_verify;
-    if (timed && (size_t)(2 * n_steps + 1) > c->n_tev) {
-        size_t want = (size_t)(2 * n_steps + 1);
+    if (timed && (size_t)(4 * n_steps + 1) > c->n_tev) {
+        size_t want = (size_t)(4 * n_steps + 1);
         hipEvent_t* ev = static_cast<hipEvent_t*>(realloc(c->tev, want * sizeof(hipEvent_t)));
         if (!ev) return fail(c, HAWK_ENOMEM, "out of host memory");
         c->tev = ev;
@@ -562,8 +565,13 @@ int hawk_run_steps(hawk_ctx* c, int k, int n_steps, uint64_t seed, int replay, f
     if (timed) HIP_TRY(c, hipEventRecord(c->tev[0], c->stream));
     for (int it = 0; it < n_steps; ++it) {
         enqueue_draft(c, k, us, dm);
-        if (timed) HIP_TRY(c, hipEventRecord(c->tev[2 * it + 1], c->stream));
+        if (timed) {
+            HIP_TRY(c, hipEventRecord(c->tev[2 * it + 1], c->stream));
+            c->kev_a = c->tev[2 * n_steps + 1 + 2 * it];
+            c->kev_b = c->tev[2 * n_steps + 2 + 2 * it];
+        }
         enqueue_verify(c, k, us);
+        c->kev_a = c->kev_b = nullptr;
         if (timed) HIP_TRY(c, hipEventRecord(c->tev[2 * it + 2], c->stream));
     }
     HIP_TRY(c, hipGetLastError());
@@ -580,6 +588,16 @@ int hawk_run_steps(hawk_ctx* c, int k, int n_steps, uint64_t seed, int replay, f
         }
         *ms_draft = (float)md;
         *ms_verify = (float)mv;
+        if (ms_kernel) {  // the persistent target-pass kernel alone (0 when the generic kernels ran)
+            double mk = 0.0;
+            if (c->last_path == 1)
+                for (int it = 0; it < n_steps; ++it) {
+                    float a = 0.f;
+                    HIP_TRY(c, hipEventElapsedTime(&a, c->tev[2 * n_steps + 1 + 2 * it], c->tev[2 * n_steps + 2 + 2 * it]));
+                    mk += a;
+                }
+            *ms_kernel = (float)mk;
+        }
         return check_stream(c);
     }
     return HAWK_OK;

@@ -94,6 +94,7 @@ struct hawk_ctx {
     hipEvent_t ev[3];
     hipEvent_t* tev;  // event pool of hawk_run_steps phase timing
     size_t n_tev;
+    hipEvent_t kev_a, kev_b;  // when set: recorded around the streaming kernel of the next target pass
     char err[256];
 };
 

@@ -433,6 +433,311 @@ __global__ void force_commit_kernel(const int32_t* forced, int32_t* grid, int32_
     }
 }
 
+// ---------------------------------------------------------------------------- register-resident rows
+//
+// Fast variants for rows of at most 1024 * E entries: a thread keeps its E scaled logits in
+// registers for the whole kernel (one coalesced read of the row), the radix select counts
+// digits in per-wave LDS histograms (all logits of a row share their high bits, so a single
+// shared histogram serialises on two or three counters), the digit scan runs on one wave, and
+// the fp64 weights exp(z - zmax) are computed once and reused by the sum and by the
+// inverse-CDF scan.  Same decisions, to the bit, as the generic functions above.
+
+struct FastShared {
+    unsigned hist[NW][256];
+    unsigned tot[256];
+    Shared sh;
+};
+
+template <int E>
+__device__ __forceinline__ void load_row(const float* lc, const float* lu, float scale, float inv_t, float* out, int n,
+                                         float (&z)[E]) {
+    const int base = threadIdx.x * E;
+    if ((n & 3) == 0 && (E & 3) == 0 && base + E <= n) {
+#pragma unroll
+        for (int q = 0; q < E / 4; ++q) {
+            float4 a = *reinterpret_cast<const float4*>(lc + base + 4 * q);
+            if (lu) {
+                const float4 u = *reinterpret_cast<const float4*>(lu + base + 4 * q);
+                a.x = fmaf(scale, a.x - u.x, u.x); a.y = fmaf(scale, a.y - u.y, u.y);
+                a.z = fmaf(scale, a.z - u.z, u.z); a.w = fmaf(scale, a.w - u.w, u.w);
+            }
+            if (out) *reinterpret_cast<float4*>(out + base + 4 * q) = a;
+            z[4 * q] = a.x * inv_t; z[4 * q + 1] = a.y * inv_t; z[4 * q + 2] = a.z * inv_t; z[4 * q + 3] = a.w * inv_t;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int j = base + e;
+            if (j < n) {
+                const float l = lu ? fmaf(scale, lc[j] - lu[j], lu[j]) : lc[j];
+                if (out) out[j] = l;
+                z[e] = l * inv_t;
+            } else {
+                z[e] = -INFINITY;  // its key lies below that of every finite value
+            }
+        }
+    }
+}
+
+// Statistics of the warp of the row held in z (see warp_stats) and, in w, the weight of every entry.
+template <int E>
+__device__ WarpStat warp_row(const float (&z)[E], int n, int top_k, int greedy, FastShared& fs, double (&w)[E]) {
+    Shared& sh = fs.sh;
+    const int base = threadIdx.x * E, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    WarpStat st;
+    st.total = 1.0; st.zmax = 0.f; st.tau = 0x007FFFFFu; st.tie_cut = -1; st.onehot = -1;  // keeps every finite entry
+    if (greedy) {
+        float best = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < E; ++e) best = fmaxf(best, z[e]);
+        const float gmax = block_max_f(best, sh);
+        int idx = 0x7FFFFFFF;
+#pragma unroll
+        for (int e = E - 1; e >= 0; --e)
+            if (base + e < n && z[e] == gmax) idx = base + e;
+        st.onehot = block_min_i(idx, sh);
+#pragma unroll
+        for (int e = 0; e < E; ++e) w[e] = (base + e == st.onehot) ? 1.0 : 0.0;
+        return st;
+    }
+    const int K = min(top_k, n);
+    if (K < n) {
+        unsigned prefix = 0u, mask = 0u, remaining = (unsigned)K, count_eq = 0u;
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < 4; ++q) fs.hist[wave][lane * 4 + q] = 0u;
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                const unsigned key = fkey(z[e]);
+                if ((key & mask) == prefix) atomicAdd(&fs.hist[wave][(key >> shift) & 255u], 1u);
+            }
+            __syncthreads();
+            if (threadIdx.x < 256) {
+                unsigned t = 0u;
+#pragma unroll
+                for (int q = 0; q < NW; ++q) t += fs.hist[q][threadIdx.x];
+                fs.tot[threadIdx.x] = t;
+            }
+            __syncthreads();
+            if (wave == 0) {  // lane owns bins 4*lane .. 4*lane+3; suffix sums from the top bin down
+                const unsigned c0 = fs.tot[lane * 4], c1 = fs.tot[lane * 4 + 1], c2 = fs.tot[lane * 4 + 2], c3 = fs.tot[lane * 4 + 3];
+                unsigned suf = c0 + c1 + c2 + c3;  // inclusive suffix over lanes >= this one
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) {
+                    const unsigned t = __shfl_down(suf, o, 64);
+                    if (lane + o < 64) suf += t;
+                }
+                const unsigned above = suf - (c0 + c1 + c2 + c3);  // entries in higher lanes' bins
+                // highest bin b with (entries in bins >= b) >= remaining
+                int found = -1;
+                unsigned rem_out = 0u, cnt_out = 0u;
+                unsigned cum = above;
+                const unsigned cs[4] = {c0, c1, c2, c3};
+#pragma unroll
+                for (int q = 3; q >= 0; --q) {
+                    if (found < 0 && cum < remaining && cum + cs[q] >= remaining) {
+                        found = lane * 4 + q; rem_out = remaining - cum; cnt_out = cs[q];
+                    }
+                    cum += cs[q];
+                }
+                if (found >= 0) {  // exactly one lane finds it
+                    sh.b_prefix = prefix | ((unsigned)found << shift);
+                    sh.b_remaining = rem_out;
+                    sh.b_count_eq = cnt_out;
+                }
+            }
+            __syncthreads();
+            prefix = sh.b_prefix;
+            remaining = sh.b_remaining;
+            count_eq = sh.b_count_eq;
+            mask |= 255u << shift;
+        }
+        st.tau = prefix;
+        st.tie_cut = 0x7FFFFFFF;
+        if (remaining < count_eq) {  // keep only the first `remaining` entries equal to tau
+            int c = 0;
+#pragma unroll
+            for (int e = 0; e < E; ++e) c += fkey(z[e]) == prefix;
+            const int before = block_excl_scan_i(c, sh);
+            __syncthreads();
+            if (before < (int)remaining && before + c >= (int)remaining) {
+                int seen = before;
+#pragma unroll
+                for (int e = 0; e < E; ++e)
+                    if (fkey(z[e]) == prefix && ++seen == (int)remaining) sh.b_int = base + e;
+            }
+            __syncthreads();
+            st.tie_cut = sh.b_int;
+        }
+    }
+    float zm = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < E; ++e) zm = fmaxf(zm, z[e]);
+    st.zmax = block_max_f(zm, sh);
+    double s = 0.0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        w[e] = kept(st, z[e], base + e) ? exp((double)z[e] - (double)st.zmax) : 0.0;
+        s += w[e];
+    }
+    st.total = block_sum_d(s, sh);
+    return st;
+}
+
+// Inverse-CDF draw from the per-thread weights w (ascending index order).
+template <int E>
+__device__ int inv_cdf_row(const double (&w)[E], double total, float u, Shared& sh) {
+    const int base = threadIdx.x * E;
+    double s = 0.0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) s += w[e];
+    double c = block_excl_scan_d(s, sh);
+    const double target = (double)u * total;
+    int cand = 0x7FFFFFFF, last = -1;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        if (w[e] > 0.0) {
+            c += w[e];
+            last = base + e;
+            if (c > target && cand == 0x7FFFFFFF) cand = base + e;
+        }
+    }
+    cand = block_min_i(cand, sh);
+    if (cand != 0x7FFFFFFF) return cand;
+    return block_max_i(last, sh);
+}
+
+template <int E>
+__global__ __launch_bounds__(NT) void first_token_fast(const float* logit_s, float* logit_b, int32_t* grid, int32_t* n,
+                                                       SampParams P, UniformSrc us) {
+    __shared__ FastShared fs;
+    const int b = blockIdx.x;
+    float z[E];
+    double w[E];
+    load_row<E>(logit_s + (size_t)b * P.Vs, P.use_cfg ? logit_s + (size_t)(P.B + b) * P.Vs : nullptr, P.cfg_scale,
+                P.inv_t, logit_b + (size_t)b * P.kstride * P.Vs, P.Vs, z);
+    const WarpStat st = warp_row<E>(z, P.Vs, P.top_k, P.greedy, fs, w);
+    const float u = pick_uniform(us, us.fin, b, b, kSlotFinal);
+    const int idx = inv_cdf_row<E>(w, st.total, u, fs.sh);
+    if (threadIdx.x == 0) {
+        grid[(size_t)b * P.N] = P.samp_lo + idx;
+        n[b] = 1;
+    }
+}
+
+template <int E>
+__global__ __launch_bounds__(NT) void draft_sample_fast(const float* dlogit_s, float* dlogit_b, const int32_t* n,
+                                                        const int32_t* k_eff, int32_t* draft, WarpStat* qstat, int i,
+                                                        int k, SampParams P, UniformSrc us, ForcedSrc fsrc) {
+    __shared__ FastShared fs;
+    const int b = blockIdx.x;
+    if (i > k_eff[b]) return;
+    float z[E];
+    double w[E];
+    load_row<E>(dlogit_s + (size_t)b * P.Vs, P.use_cfg ? dlogit_s + (size_t)(P.B + b) * P.Vs : nullptr, P.cfg_scale,
+                P.inv_t, dlogit_b + ((size_t)b * P.kstride + (i - 1)) * P.Vs, P.Vs, z);
+    WarpStat st = warp_row<E>(z, P.Vs, P.top_k, P.greedy, fs, w);
+    int tok;
+    if (fsrc.table) {
+        tok = fsrc.table[(size_t)b * fsrc.stride + (fsrc.relative ? n[b] : 0) + (i - 1)];
+        if (fsrc.point_mass) { st.onehot = tok - P.samp_lo; st.total = 1.0; }
+    } else {
+        const float u = pick_uniform(us, us.draft, b * k + (i - 1), b, kSlotDraft + (i - 1));
+        tok = P.samp_lo + inv_cdf_row<E>(w, st.total, u, fs.sh);
+    }
+    if (threadIdx.x == 0) {
+        draft[b * P.kstride + (i - 1)] = tok;
+        qstat[b * P.kstride + (i - 1)] = st;
+    }
+}
+
+template <int E>
+__global__ __launch_bounds__(NT) void verify_stats_fast(const float* logit_s, float* logit_b, const int32_t* k_eff,
+                                                        WarpStat* pstat, int k, SampParams P) {
+    __shared__ FastShared fs;
+    const int r = blockIdx.x, b = blockIdx.y;
+    if (r > k_eff[b]) return;
+    float z[E];
+    double w[E];
+    load_row<E>(logit_s + ((size_t)b * (k + 1) + r) * P.Vs,
+                P.use_cfg ? logit_s + ((size_t)(P.B + b) * (k + 1) + r) * P.Vs : nullptr, P.cfg_scale, P.inv_t,
+                logit_b + ((size_t)b * P.kstride + r) * P.Vs, P.Vs, z);
+    const WarpStat st = warp_row<E>(z, P.Vs, P.top_k, P.greedy, fs, w);
+    if (threadIdx.x == 0) pstat[b * P.kstride + r] = st;
+}
+
+template <int E>
+__global__ __launch_bounds__(NT) void accept_commit_fast(
+    const float* logit_b, const float* dlogit_b, const WarpStat* pstat, const WarpStat* qstat, const int32_t* k_eff,
+    const int32_t* draft, int32_t* grid, int32_t* n, const uint32_t* hid, uint32_t* hprev, int hid_words,
+    int32_t* out_na, int32_t* out_tok, unsigned long long* counters, int k, int n_seq_streams, SampParams P,
+    UniformSrc us) {
+    __shared__ Shared sh;
+    const int b = blockIdx.x;
+    const int ke = k_eff[b];
+    if (threadIdx.x <= k) out_tok[b * (k + 1) + threadIdx.x] = -1;
+    if (ke < 0) {
+        if (threadIdx.x == 0) out_na[b] = -1;
+        return;
+    }
+    int a = 0;
+    for (; a < ke; ++a) {
+        const int dj = draft[b * P.kstride + a] - P.samp_lo;
+        const WarpStat ps = pstat[b * P.kstride + a], qs = qstat[b * P.kstride + a];
+        const double pd = weight_of(ps, logit_b + ((size_t)b * P.kstride + a) * P.Vs, P.inv_t, dj) / ps.total;
+        const double qd = weight_of(qs, dlogit_b + ((size_t)b * P.kstride + a) * P.Vs, P.inv_t, dj) / qs.total;
+        const float u = pick_uniform(us, us.acc, b * k + a, b, kSlotAcc + a);
+        if (!((double)u * qd < pd)) break;
+    }
+    const float uf = pick_uniform(us, us.fin, b, b, kSlotFinal);
+    const float* prow = logit_b + ((size_t)b * P.kstride + a) * P.Vs;
+    const WarpStat ps = pstat[b * P.kstride + a];
+    const int base = threadIdx.x * E;
+    double w[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) w[e] = base + e < P.Vs ? weight_of(ps, prow, P.inv_t, base + e) : 0.0;
+    int y;
+    if (a < ke) {
+        const float* qrow = dlogit_b + ((size_t)b * P.kstride + a) * P.Vs;
+        const WarpStat qs = qstat[b * P.kstride + a];
+        double res[E], s = 0.0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const double q = base + e < P.Vs ? weight_of(qs, qrow, P.inv_t, base + e) / qs.total : 0.0;
+            const double r = w[e] / ps.total - q;
+            res[e] = r > 0.0 ? r : 0.0;
+            s += res[e];
+        }
+        const double R = block_sum_d(s, sh);
+        y = (R > 0.0) ? inv_cdf_row<E>(res, R, uf, sh) : inv_cdf_row<E>(w, ps.total, uf, sh);
+    } else {
+        y = inv_cdf_row<E>(w, ps.total, uf, sh);
+    }
+    const int nb = n[b];
+    for (int s2 = b; s2 < n_seq_streams; s2 += P.B) {
+        const uint32_t* src = hid + ((size_t)s2 * (k + 1) + a) * hid_words;
+        uint32_t* dst = hprev + (size_t)s2 * hid_words;
+        for (int i = threadIdx.x; i < hid_words; i += NT) dst[i] = src[i];
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int i = 0; i < a; ++i) {
+            const int t = draft[b * P.kstride + i];
+            grid[(size_t)b * P.N + nb + i] = t;
+            out_tok[b * (k + 1) + i] = t;
+        }
+        grid[(size_t)b * P.N + nb + a] = P.samp_lo + y;
+        out_tok[b * (k + 1) + a] = P.samp_lo + y;
+        out_na[b] = a;
+        n[b] = nb + a + 1;
+        atomicAdd(&counters[0], 1ull);
+        atomicAdd(&counters[1], (unsigned long long)a);
+        atomicAdd(&counters[2], (unsigned long long)(a + 1));
+    }
+}
+
 SampParams samp_params(const hawk_ctx* c) {
     SampParams P;
     P.B = c->B; P.N = c->N; P.Vs = c->Vs; P.samp_lo = c->cfg.samp_lo; P.kstride = c->kmax + 1;
@@ -451,7 +756,16 @@ void launch_plan(hawk_ctx* c, int k) {
                                                             k, c->kmax + 1);
 }
 
+// Entries per thread of the register-resident kernels for this vocabulary slice (0: too large).
+static int fast_e(const hawk_ctx* c) { return c->Vs <= 4 * NT ? 4 : (c->Vs <= 16 * NT ? 16 : 0); }
+
 void launch_first_token(hawk_ctx* c, const UniformSrc& us) {
+    if (fast_e(c)) {
+        auto kern = fast_e(c) == 4 ? first_token_fast<4> : first_token_fast<16>;
+        kern<<<c->B, NT, 0, c->stream>>>(wsp<float>(c, c->off.logit_s), wsp<float>(c, c->off.logit_b),
+                                         wsp<int32_t>(c, c->off.grid), wsp<int32_t>(c, c->off.n), samp_params(c), us);
+        return;
+    }
     first_token_kernel<<<c->B, NT, 0, c->stream>>>(wsp<float>(c, c->off.logit_s), wsp<float>(c, c->off.logit_b),
                                                    wsp<int32_t>(c, c->off.grid), wsp<int32_t>(c, c->off.n),
                                                    samp_params(c), us);
@@ -462,6 +776,14 @@ void launch_draft_sample(hawk_ctx* c, int i, int k, const UniformSrc& us, const 
     fs.table = nullptr; fs.stride = 0; fs.relative = 0; fs.point_mass = dm.point_mass;
     if (dm.kind == 1) { fs.table = wsp<int32_t>(c, c->off.forced); fs.stride = k; }
     if (dm.kind == 2) { fs.table = wsp<int32_t>(c, c->off.replay); fs.stride = c->N; fs.relative = 1; }
+    if (fast_e(c)) {
+        auto kern = fast_e(c) == 4 ? draft_sample_fast<4> : draft_sample_fast<16>;
+        kern<<<c->B, NT, 0, c->stream>>>(wsp<float>(c, c->off.dlogit_s), wsp<float>(c, c->off.dlogit_b),
+                                         wsp<int32_t>(c, c->off.n), wsp<int32_t>(c, c->off.k_eff),
+                                         wsp<int32_t>(c, c->off.draft), wsp<WarpStat>(c, c->off.qstat), i, k,
+                                         samp_params(c), us, fs);
+        return;
+    }
     draft_sample_kernel<<<c->B, NT, 0, c->stream>>>(wsp<float>(c, c->off.dlogit_s), wsp<float>(c, c->off.dlogit_b),
                                                     wsp<int32_t>(c, c->off.n), wsp<int32_t>(c, c->off.k_eff),
                                                     wsp<int32_t>(c, c->off.draft), wsp<WarpStat>(c, c->off.qstat), i,
@@ -469,12 +791,29 @@ void launch_draft_sample(hawk_ctx* c, int i, int k, const UniformSrc& us, const 
 }
 
 void launch_verify_stats(hawk_ctx* c, int k) {
+    if (fast_e(c)) {
+        auto kern = fast_e(c) == 4 ? verify_stats_fast<4> : verify_stats_fast<16>;
+        kern<<<dim3(k + 1, c->B), NT, 0, c->stream>>>(wsp<float>(c, c->off.logit_s), wsp<float>(c, c->off.logit_b),
+                                                      wsp<int32_t>(c, c->off.k_eff), wsp<WarpStat>(c, c->off.pstat), k,
+                                                      samp_params(c));
+        return;
+    }
     verify_stats_kernel<<<dim3(k + 1, c->B), NT, 0, c->stream>>>(
         wsp<float>(c, c->off.logit_s), wsp<float>(c, c->off.logit_b), wsp<int32_t>(c, c->off.k_eff),
         wsp<WarpStat>(c, c->off.pstat), k, samp_params(c));
 }
 
 void launch_accept_commit(hawk_ctx* c, int k, const UniformSrc& us) {
+    if (fast_e(c)) {
+        auto kern = fast_e(c) == 4 ? accept_commit_fast<4> : accept_commit_fast<16>;
+        kern<<<c->B, NT, 0, c->stream>>>(
+            wsp<float>(c, c->off.logit_b), wsp<float>(c, c->off.dlogit_b), wsp<WarpStat>(c, c->off.pstat),
+            wsp<WarpStat>(c, c->off.qstat), wsp<int32_t>(c, c->off.k_eff), wsp<int32_t>(c, c->off.draft),
+            wsp<int32_t>(c, c->off.grid), wsp<int32_t>(c, c->off.n), wsp<uint32_t>(c, c->off.x),
+            wsp<uint32_t>(c, c->off.hprev), (int)(c->d * c->asz / 4), wsp<int32_t>(c, c->off.out_na),
+            wsp<int32_t>(c, c->off.out_tok), wsp<unsigned long long>(c, c->off.counters), k, c->S, samp_params(c), us);
+        return;
+    }
     accept_commit_kernel<<<c->B, NT, 0, c->stream>>>(
         wsp<float>(c, c->off.logit_b), wsp<float>(c, c->off.dlogit_b), wsp<WarpStat>(c, c->off.pstat),
         wsp<WarpStat>(c, c->off.qstat), wsp<int32_t>(c, c->off.k_eff), wsp<int32_t>(c, c->off.draft),

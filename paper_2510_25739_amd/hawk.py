@@ -60,7 +60,7 @@ EXPORTS = {
                                 C.c_float, C.c_int, C.c_float, C.c_uint64, C.c_void_p, C.c_void_p,
                                 C.POINTER(HawkStats)]),
     "hawk_run_steps": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_uint64, C.c_int, C.POINTER(C.c_float),
-                                 C.POINTER(C.c_float)]),
+                                 C.POINTER(C.c_float), C.POINTER(C.c_float)]),
     "hawk_set_replay": (C.c_int, [C.c_void_p, C.c_void_p]),
     "hawk_get_stats": (C.c_int, [C.c_void_p, C.POINTER(HawkStats)]),
     "hawk_force": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]),
@@ -225,13 +225,13 @@ class Hawk:
         return grid, st.as_dict()
 
     def run_steps(self, k, n_steps, seed, replay=False, timed=False):
-        """Enqueues n_steps steps; with timed=True returns (ms_draft, ms_verify) summed over them."""
+        """Enqueues n_steps steps; with timed=True returns (ms_draft, ms_verify, ms_kernel) summed over them."""
         if timed:
-            a, b = C.c_float(), C.c_float()
-            self._chk(self._L.hawk_run_steps(self._h, k, n_steps, seed, int(replay), C.byref(a), C.byref(b)),
-                      "hawk_run_steps")
-            return a.value, b.value
-        self._chk(self._L.hawk_run_steps(self._h, k, n_steps, seed, int(replay), None, None), "hawk_run_steps")
+            a, b, k_ = C.c_float(), C.c_float(), C.c_float()
+            self._chk(self._L.hawk_run_steps(self._h, k, n_steps, seed, int(replay), C.byref(a), C.byref(b),
+                                             C.byref(k_)), "hawk_run_steps")
+            return a.value, b.value, k_.value
+        self._chk(self._L.hawk_run_steps(self._h, k, n_steps, seed, int(replay), None, None, None), "hawk_run_steps")
         return None
 
     def set_replay(self, tokens):
