@@ -26,8 +26,8 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
-# scaled by a copy kernel of known size (see profiles/); None until measured.
-TRAFFIC_BYTES_PER_LAUNCH = None
+# scaled by a 1 GiB device copy in the same run (FETCH_SIZE factor 2.000, WRITE_SIZE 1.000).
+TRAFFIC_BYTES_PER_LAUNCH = int(791727 * 1024 * 2.000 + 42931 * 1024 * 1.000)   # config 2, streaming kernel
 
 
 def verify_bytes(s, kv_len: float) -> float:
@@ -177,7 +177,7 @@ def main():
                                 "paper_context": "1.71x on 1x RTX 3090 with trained heads (not comparable)"},
         "roofline": {"bound": "hbm", "kernel": kname,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": TRAFFIC_BYTES_PER_LAUNCH, "bytes_per_launch": vb, "ms_per_launch": ms_dom,
+                     "traffic": TRAFFIC_BYTES_PER_LAUNCH if (args.config == 2 and rnd["ms_kernel"] > 0) else None, "bytes_per_launch": vb, "ms_per_launch": ms_dom,
                      "verify_step_ms": rnd["ms_verify"],
                      "draft_phase": {"bytes": draft_bytes(s), "ms": rnd["ms_draft"],
                                      "GB/s": draft_bytes(s) / (rnd["ms_draft"] * 1e-3) / 1e9}},
