@@ -60,7 +60,7 @@ struct Offsets {  // byte offsets into the workspace
 // Streaming (persistent-kernel) path: matrix kinds, workgroup count, workspace regions.
 enum StreamKind { K_A = 0, K_C, K_D, K_E, K_LM, K_WD, K_NKIND };  // QKV, Wo, W1|W3, W2, output, draft
 constexpr int kNWG = 256;  // persistent workgroups: one per compute unit
-struct StreamOffsets { size_t wpack, tab, desc, hasmask, arena, slot_bytes, bar, err, dbg, rope; };
+struct StreamOffsets { size_t wpack, tab, desc, arena, slot_bytes, bar, err, dbg, rope; };
 struct StreamPlan;
 
 struct Weights {  // byte offsets into the blob

@@ -2,24 +2,29 @@
 // (all layers + output projection) as ONE persistent kernel of 256 workgroups, one per CU.
 //
 // Why this shape (MI355X, measured): at batch 1 a layer of the XL model is 40 MB, i.e. ~5 us
-// of HBM time, but it has five dependent matrix stages; a kernel boundary costs ~6 us for an
-// 8 MB kernel and a full HBM round trip ~1.5 us, so the stages must live in one kernel and the
-// weights of stage p+1 must already be in flight while stage p synchronises.
+// of HBM time, but it has five dependent stages; a kernel boundary costs ~6 us for an 8 MB
+// kernel and a store -> remote load round trip ~1.5 us, so the stages live in one kernel, the
+// weights of stage p+1 are in flight while stage p synchronises, and everything on the
+// dependent chain of a stage is kept as short as possible:
 //   - every matrix is pre-packed into 16x32 bf16 tiles laid out exactly as the A operand of
 //     v_mfma_f32_16x16x32_bf16 (16 bytes per lane), in the order each wave consumes them;
 //   - a workgroup owns whole 16-row output strips; its four compute waves split K four ways,
-//     stream their tiles straight from HBM into VGPRs (no LDS staging of weights), and issue
-//     the loads of their NEXT job right after the MFMAs of the current one, so that they land
-//     while the grid barrier is being crossed;
-//   - the k+1 activation rows are the B operand (columns 0..MR-1 of 16), staged in LDS as a
-//     bf16 hi + lo pair (two MFMAs per tile: fp32-accurate activations at no HBM cost);
-//   - two IO waves per workgroup do everything latency-bound: cross the barrier, fetch the
-//     stage input with device-coherent loads, normalise, split, and later write the strip's
-//     results; compute waves never wait on anything but their own weights;
+//     stream their tiles straight from HBM into VGPRs (no LDS staging of weights) and issue
+//     the loads of their NEXT job right after the MFMAs of the current one;
+//   - the k+1 activation rows are the B operand (columns 0..MR-1 of 16), kept as a bf16
+//     hi + lo pair (two MFMAs per tile: fp32-accurate activations at no HBM cost).  The
+//     PRODUCER of a vector writes it already split (and multiplied by the gain of the norm
+//     that follows, with per-strip sums of squares beside it), so a consumer only copies
+//     16-byte chunks into LDS and applies the row's 1/rms to its accumulators;
+//   - the residual stream of a 16-column strip never leaves the workgroup that owns the strip
+//     in both the Wo and the W2 stage (four registers per lane of one wave);
+//   - four IO waves per workgroup do everything latency-bound: cross the barrier, copy the
+//     stage input, reduce the K quarters and write the strips' results (one wave per strip);
+//     compute waves never wait on anything but their own weights;
 //   - a grid barrier = arrival counters in 16 groups + top counter + replicated release word
 //     (1.5 us measured; flat counters or all-to-all flags are 2-3x slower on 8 XCDs).
-// Attention reads the fp16 KV cache with (head, chunk) jobs over all workgroups and a second
-// small stage that merges the chunk partials.
+// Attention reads the fp16 KV cache with (sequence, head, row group, chunk) jobs; with one
+// chunk per head the job emits the finished, split output row itself.
 #include <math.h>
 #include <string.h>
 
@@ -40,14 +45,16 @@ typedef unsigned v4u __attribute__((ext_vector_type(4)));
 constexpr int kCW = 4;                          // compute waves per workgroup
 constexpr int kNIO = 4;                         // IO waves per workgroup
 constexpr int kThreads = (kCW + kNIO) * 64;
+constexpr int kIOThreads = kNIO * 64;
 constexpr int kTMax = 27;                       // tiles (1 KB each) a wave holds for one job
-constexpr int kMaxStrips = 3;
+constexpr int kMaxStrips = 3;                   // strips of one job (one IO wave finishes each)
 constexpr int kGroups = 16, kReplicas = 8;      // barrier fan-in / release fan-out
 constexpr unsigned kSpinLimit = 1u << 21;
-constexpr int kRing = 3;
+constexpr int kRing = 3;                        // exchange arenas used round robin by successive launches
 constexpr int kPS = 68;                         // floats per attention partial row: 64 outputs, max, sum, pad
-constexpr int kNIT = 12;                        // cache positions per (wave, lane group) of an attention job
-constexpr int kNCMax = 4;                       // chunks per (sequence, head)                        // exchange arenas used round robin by successive launches
+constexpr int kNIT = 6;                         // iterations (of kCW*8 cache positions) per KV register buffer
+constexpr int kNCMax = 4;                       // chunks per (sequence, head)
+constexpr int kXcd = 8, kPerXcd = kNWG / kXcd;  // workgroup i is dispatched to XCD i % 8
 
 // ------------------------------------------------------------------------- kernel parameters
 
@@ -56,15 +63,15 @@ struct SP {
     u64 layer_tiles, kind_base[4], lm_base, wd_base;
     const int32_t* tab[K_NKIND];
     int32_t rounds[K_NKIND];
-    const uint32_t* hasmask;  // per workgroup: bit kind (layer kinds), bit 8+r = LM round r
     const uint16_t* blob;
     u64 g1_off, g2_off, layer_bytes, gf_off;
     const float2* rope;
     _Float16* Kc;
     _Float16* Vc;
-    float* X;        // embedded rows in, final hidden rows out ([MR][d], written by the previous kernel)
+    float* X;        // embedded rows in, final hidden rows out ([MR][d] fp32)
     float* arena;    // exchange slots of this launch: slot l = arena + l * slot_floats, l = 0..L
-    u64 slot_floats, ax, ax2, aq, ao, ah, ap;  // offsets of x, x', q, o, h, partials inside a slot
+    // offsets (in floats) of the regions of a slot: split planes are uint16 [16][K + 8]
+    u64 slot_floats, o_xh, o_xl, o_ssx, o_q, o_oh, o_ol, o_x2h, o_x2l, o_ss2, o_hh, o_hl, o_p;
     float* logit_s;
     u64* dbg;        // optional per-phase timestamps of the first IO wave of workgroups 0 and 128 (null: off)
     unsigned* bar;
@@ -72,43 +79,53 @@ struct SP {
     const int32_t* n;
     const int32_t* k_eff;
     unsigned epoch0;
-    int32_t L, d, H, m, Vs, S, B, C, RS, MR, NC, Smax, Tmax, Kp, act_bytes;
+    int32_t L, d, H, m, Vs, S, B, C, RS, MR, NC, NRG, RPJ, Smax, Tmax, Kpd, Kpm, act_bytes;
     float eps;
 };
 
 // ------------------------------------------------------------------------- device helpers
 
-__device__ __forceinline__ float ld_f32(const float* p) {
-    return __uint_as_float(__hip_atomic_load(reinterpret_cast<const unsigned*>(p), __ATOMIC_RELAXED,
-                                             __HIP_MEMORY_SCOPE_AGENT));
+// Exchange data is written once per launch, with stores that go through to memory, into a slot
+// that no cache has seen in this launch; after the barrier ordinary cached loads return it and
+// the 32 workgroups of an XCD share one L2 fill.
+__device__ __forceinline__ void st_u32(void* p, unsigned v) {
+    __hip_atomic_store(reinterpret_cast<unsigned*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ void st_f32(float* p, float v) {
-    __hip_atomic_store(reinterpret_cast<unsigned*>(p), __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ __forceinline__ void st_u64(void* p, unsigned lo, unsigned hi) {
+    __hip_atomic_store(reinterpret_cast<u64*>(p), (u64)lo | ((u64)hi << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float2 ld_f32x2(const float* p) {
-    u64 v = __hip_atomic_load(reinterpret_cast<const u64*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return make_float2(__uint_as_float((unsigned)v), __uint_as_float((unsigned)(v >> 32)));
+__device__ __forceinline__ void st_f32(float* p, float v) { st_u32(p, __float_as_uint(v)); }
+__device__ __forceinline__ void st_f32x2(float* p, float a, float b) { st_u64(p, __float_as_uint(a), __float_as_uint(b)); }
+__device__ __forceinline__ void st_f32x4(float* p, f32x4 v) {
+    st_f32x2(p, v[0], v[1]);
+    st_f32x2(p + 2, v[2], v[3]);
 }
-__device__ __forceinline__ void st_f32x2(float* p, float a, float b) {
-    u64 v = (u64)__float_as_uint(a) | ((u64)__float_as_uint(b) << 32);
-    __hip_atomic_store(reinterpret_cast<u64*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// Exchange data is written once per launch into a slot that no cache has seen yet (stores go
-// through to memory), so after the barrier ordinary cached loads return it and the 32 workgroups
-// of an XCD share one L2 fill instead of each pulling the vector across the fabric.
 __device__ __forceinline__ void compiler_fence() { __atomic_signal_fence(__ATOMIC_SEQ_CST); }
 __device__ __forceinline__ float* slot(const SP& p, int l) { return p.arena + (u64)l * p.slot_floats; }
-__device__ __forceinline__ const float* x_in(const SP& p, int l) { return l == 0 ? p.X : slot(p, l) + p.ax; }
+__device__ __forceinline__ uint16_t* plane(const SP& p, int l, u64 off) {
+    return reinterpret_cast<uint16_t*>(slot(p, l) + off);
+}
 
-__device__ __forceinline__ uint16_t bf16_rne(float f) {
+__device__ __forceinline__ unsigned bf16_rne(float f) {
     unsigned u = __float_as_uint(f);
-    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 __device__ __forceinline__ float bf16_f32(unsigned b) { return __uint_as_float(b << 16); }
-__device__ __forceinline__ float wsum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+
+// Writes four consecutive elements of a split vector: bf16 hi and lo halves, 8 bytes each.
+__device__ __forceinline__ void st_split4(uint16_t* hi, uint16_t* lo, f32x4 v) {
+    const unsigned h0 = bf16_rne(v[0]), h1 = bf16_rne(v[1]), h2 = bf16_rne(v[2]), h3 = bf16_rne(v[3]);
+    const unsigned l0 = bf16_rne(v[0] - bf16_f32(h0)), l1 = bf16_rne(v[1] - bf16_f32(h1));
+    const unsigned l2 = bf16_rne(v[2] - bf16_f32(h2)), l3 = bf16_rne(v[3] - bf16_f32(h3));
+    st_u64(hi, h0 | (h1 << 16), h2 | (h3 << 16));
+    st_u64(lo, l0 | (l1 << 16), l2 | (l3 << 16));
+}
+__device__ __forceinline__ void put_split(float4 v, uint16_t* hi, uint16_t* lo) {  // LDS destination
+    const unsigned h0 = bf16_rne(v.x), h1 = bf16_rne(v.y), h2 = bf16_rne(v.z), h3 = bf16_rne(v.w);
+    const unsigned l0 = bf16_rne(v.x - bf16_f32(h0)), l1 = bf16_rne(v.y - bf16_f32(h1));
+    const unsigned l2 = bf16_rne(v.z - bf16_f32(h2)), l3 = bf16_rne(v.w - bf16_f32(h3));
+    *reinterpret_cast<uint2*>(hi) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+    *reinterpret_cast<uint2*>(lo) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
 }
 
 // Grid barrier.  Counters only ever grow (epochs continue across launches), so nothing is
@@ -185,83 +202,52 @@ __device__ __forceinline__ void issue_tiles(const SP& p, const Job& j, int tps, 
         }
 }
 
-// Stage input rows into LDS as bf16 hi / lo pairs: act[c][j] = split(src[c][j] * scale_c * gain_j).
-// IO wave `io` handles rows io, io + kNIO, ...  NORM: RMS-normalise with the gain vector; all
-// loads of a wave's rows are issued before the first is used.
-__device__ __forceinline__ void put_split(float4 v, uint16_t* hi, uint16_t* lo) {
-    const unsigned h0 = bf16_rne(v.x), h1 = bf16_rne(v.y), h2 = bf16_rne(v.z), h3 = bf16_rne(v.w);
-    const unsigned l0 = bf16_rne(v.x - bf16_f32(h0)), l1 = bf16_rne(v.y - bf16_f32(h1));
-    const unsigned l2 = bf16_rne(v.z - bf16_f32(h2)), l3 = bf16_rne(v.w - bf16_f32(h3));
-    *reinterpret_cast<uint2*>(hi) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
-    *reinterpret_cast<uint2*>(lo) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
-}
-
-template <int KREG>  // gains of the lane's columns, fetched before the barrier is crossed
-__device__ __forceinline__ void load_gains(const uint16_t* gain, int K, int lane, uint2 (&g)[KREG]) {
+// Copies the split planes of a stage input ([MR][Kp] bf16 each, contiguous) into LDS, BATCH
+// 16-byte chunks per IO thread in flight; t = 0..kIOThreads-1.
+template <int BATCH>
+__device__ __forceinline__ void stage_copy(const uint16_t* hi, const uint16_t* lo, int MR, int Kp, uint16_t* act_hi,
+                                           uint16_t* act_lo, int t) {
+    const int per_plane = MR * Kp / 8, total = 2 * per_plane;
+    for (int base = 0; base < total; base += kIOThreads * BATCH) {
+        v4u v[BATCH];
 #pragma unroll
-    for (int i = 0; i < KREG; ++i) {
-        const int j = (i * 64 + lane) * 4;
-        g[i] = j < K ? *reinterpret_cast<const uint2*>(gain + j) : make_uint2(0u, 0u);
-    }
-}
-
-template <bool NORM, int KREG>  // KREG: float4 per lane per row (K <= 256 * KREG)
-__device__ __forceinline__ void stage_rows(const float* src, int K, int MR, const uint2 (&g)[KREG], float eps, int io,
-                                           int lane, uint16_t* act_hi, uint16_t* act_lo, int Kp) {
-    constexpr int RPW = (16 + kNIO - 1) / kNIO;  // rows one IO wave may own
-    constexpr int RB = KREG > 8 ? 2 : RPW;       // rows whose loads are in flight together
-#pragma unroll
-    for (int q0 = 0; q0 < RPW; q0 += RB) {
-        if (io + q0 * kNIO >= MR) break;
-        float4 v[RB][KREG];
-#pragma unroll
-        for (int q = 0; q < RB; ++q) {
-            const int c = io + (q0 + q) * kNIO;
-#pragma unroll
-            for (int i = 0; i < KREG; ++i) {
-                const int j = (i * 64 + lane) * 4;
-                v[q][i] = (c < MR && j < K) ? *reinterpret_cast<const float4*>(src + (size_t)c * K + j)
-                                            : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
+        for (int i = 0; i < BATCH; ++i) {
+            const int q = base + i * kIOThreads + t;
+            const bool second = q >= per_plane;
+            const v4u* src = reinterpret_cast<const v4u*>(second ? lo : hi) + (second ? q - per_plane : q);
+            v[i] = q < total ? *src : (v4u){0u, 0u, 0u, 0u};
         }
 #pragma unroll
-        for (int q = 0; q < RB; ++q) {
-            const int c = io + (q0 + q) * kNIO;
-            if (c < MR) {
-                float r = 1.f;
-                if (NORM) {
-                    float ss = 0.f;
-#pragma unroll
-                    for (int i = 0; i < KREG; ++i)
-                        ss += v[q][i].x * v[q][i].x + v[q][i].y * v[q][i].y + v[q][i].z * v[q][i].z + v[q][i].w * v[q][i].w;
-                    ss = wsum(ss);
-                    r = 1.0f / sqrtf(ss / (float)K + eps);
-                }
-#pragma unroll
-                for (int i = 0; i < KREG; ++i) {
-                    const int j = (i * 64 + lane) * 4;
-                    if (j < K) {
-                        float4 y = v[q][i];
-                        if (NORM) {
-                            y.x = y.x * r * bf16_f32(g[i].x & 0xFFFFu);
-                            y.y = y.y * r * bf16_f32(g[i].x >> 16);
-                            y.z = y.z * r * bf16_f32(g[i].y & 0xFFFFu);
-                            y.w = y.w * r * bf16_f32(g[i].y >> 16);
-                        }
-                        put_split(y, act_hi + (size_t)c * Kp + j, act_lo + (size_t)c * Kp + j);
-                    }
-                }
-            }
+        for (int i = 0; i < BATCH; ++i) {
+            const int q = base + i * kIOThreads + t;
+            const bool second = q >= per_plane;
+            v4u* dst = reinterpret_cast<v4u*>(second ? act_lo : act_hi) + (second ? q - per_plane : q);
+            if (q < total) *dst = v[i];
         }
     }
 }
 
-// Stage the attention output rows for the Wo stage: merges the NC chunk partials of every
-// (sequence, head) - softmax statistics (max, sum) and un-normalised outputs - on the fly.
+// 1/rms of every row from the per-strip sums of squares ss[NSS*4][16] (one wave; NSS loads per lane).
+template <int NSS>
+__device__ __forceinline__ void row_scales(const float* ss, int K, float eps, int lane, float* rn) {
+    const int c = lane & 15, part = lane >> 4;
+    float v[NSS];
+#pragma unroll
+    for (int i = 0; i < NSS; ++i) v[i] = ss[(size_t)(part + 4 * i) * 16 + c];
+    float a = 0.f;
+#pragma unroll
+    for (int i = 0; i < NSS; ++i) a += v[i];
+    a += __shfl_xor(a, 16, 64);
+    a += __shfl_xor(a, 32, 64);
+    if (lane < 16) rn[c] = 1.0f / sqrtf(a / (float)K + eps);
+}
+
+// Stage the attention output rows for the Wo stage when a head was split into NC chunks:
+// merges the chunk partials - softmax statistics (max, sum) and un-normalised outputs.
 template <int KREG>
 __device__ __forceinline__ void stage_attention(const SP& p, int layer, int io, int lane, uint16_t* act_hi,
                                                 uint16_t* act_lo) {
-    const float* P = slot(p, layer) + p.ap;
+    const float* P = slot(p, layer) + p.o_p;
     const int d = p.d, RS = p.RS, NC = p.NC;
     for (int c = io; c < p.MR; c += kNIO) {
         const int seq = c / RS, r = c - seq * RS;
@@ -296,7 +282,7 @@ __device__ __forceinline__ void stage_attention(const SP& p, int layer, int io, 
                 }
                 const float inv = dn > 0.f ? 1.0f / dn : 0.f;
                 y.x *= inv; y.y *= inv; y.z *= inv; y.w *= inv;
-                put_split(y, act_hi + (size_t)c * p.Kp + j, act_lo + (size_t)c * p.Kp + j);
+                put_split(y, act_hi + (size_t)c * p.Kpd + j, act_lo + (size_t)c * p.Kpd + j);
             }
         }
     }
@@ -357,107 +343,123 @@ __device__ __forceinline__ RowPos row_pos(const SP& p, int c) {
 
 // ------------------------------------------------------------------------- GEMV phases
 
-// Operands of a strip's epilogue that do not depend on this stage (residual slice, rotary
-// factors), fetched by the epilogue wave before the barrier is crossed.
+struct Lds {
+    uint16_t* act_hi;
+    uint16_t* act_lo;
+    float* red;      // [kCW][kMaxStrips][64][4]: K-quarter partial strips in accumulator layout
+    float* rn;       // [16]: 1/rms of the rows of the stage input
+    float* att;      // attention: scaled queries of the job's rows
+    unsigned* join;  // arrivals of the IO waves (only ever grows)
+};
+
+// Operands of a strip's epilogue that do not depend on this stage, fetched by the strip's IO
+// wave before the barrier is crossed.  A lane finishes rows 4*(lane/16)..+3 of column lane%16.
 struct EpiPre {
-    float res[4];    // residual x[c][strip*16 + row] of items e = lane + 64 q
-    float2 rot[2];   // cos, sin of items idx = lane + 64 q
+    float2 rot[2];   // stage A: cos, sin of the lane's two rotary pairs
+    uint2 gain;      // stages C, E: gain of the following norm for the lane's four rows (bf16 x 4)
 };
 
 template <int KIND>
 __device__ __forceinline__ void epilogue_prefetch(const SP& p, int layer, int strip, int lane, EpiPre& pre) {
-    const int MR = p.MR, d = p.d;
+    const int c = lane & 15, quad = lane >> 4, d = p.d;
+    pre.rot[0] = pre.rot[1] = make_float2(1.f, 0.f);
+    pre.gain = make_uint2(0u, 0u);
     if (KIND == K_A) {
         const int o0 = strip * 16, seg = o0 / d, j0 = o0 - seg * d, hd = d / p.H;
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const int idx = lane + 64 * q;
-            pre.rot[q] = make_float2(1.f, 0.f);
-            if (idx < 8 * MR && seg < 2) {
-                const RowPos rp = row_pos(p, idx >> 3);
-                pre.rot[q] = p.rope[(size_t)rp.pos * (hd / 2) + ((j0 % hd) >> 1) + (idx & 7)];
-            }
+        if (c < p.MR && seg < 2) {
+            const RowPos rp = row_pos(p, c);
+            const float2* rt = p.rope + (size_t)rp.pos * (hd / 2) + ((j0 % hd) >> 1) + 2 * quad;
+            pre.rot[0] = rt[0];
+            pre.rot[1] = rt[1];
         }
     } else if (KIND == K_C || KIND == K_E) {
-        const float* in = KIND == K_C ? x_in(p, layer) : slot(p, layer) + p.ax2;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int e = lane + 64 * q;
-            pre.res[q] = e < 16 * MR ? in[(size_t)(e >> 4) * d + strip * 16 + (e & 15)] : 0.f;
-        }
+        const uint16_t* g = KIND == K_C ? p.blob + (p.g2_off + (u64)layer * p.layer_bytes) / 2
+                                        : (layer + 1 < p.L ? p.blob + (p.g1_off + (u64)(layer + 1) * p.layer_bytes) / 2
+                                                           : p.blob + p.gf_off / 2);
+        pre.gain = *reinterpret_cast<const uint2*>(g + strip * 16 + 4 * quad);
     }
 }
 
-// vals[row][col] holds the finished strip; writes it where the next stage expects it.
+__device__ __forceinline__ f32x4 times_gain(f32x4 x, uint2 g) {
+    return (f32x4){x[0] * bf16_f32(g.x & 0xFFFFu), x[1] * bf16_f32(g.x >> 16), x[2] * bf16_f32(g.y & 0xFFFFu),
+                   x[3] * bf16_f32(g.y >> 16)};
+}
+
+// Writes a strip of the residual stream for the stage that follows a norm: the values times the
+// norm's gain as split planes, and the strip's sum of squares per row.
+__device__ __forceinline__ void put_stream(const SP& p, uint16_t* hi, uint16_t* lo, float* ss, int strip, int lane,
+                                           f32x4 x, uint2 gain) {
+    const int c = lane & 15, quad = lane >> 4;
+    const bool live = c < p.MR;
+    float s2 = live ? x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3] : 0.f;
+    s2 += __shfl_xor(s2, 16, 64);
+    s2 += __shfl_xor(s2, 32, 64);
+    if (live) {
+        const size_t at = (size_t)c * p.Kpd + strip * 16 + 4 * quad;
+        st_split4(hi + at, lo + at, times_gain(x, gain));
+        if (quad == 0) st_f32(ss + (size_t)strip * 16 + c, s2);
+    }
+}
+
+// v: the finished strip in accumulator layout (lane: rows 4*(lane/16)..+3 of column lane%16).
 template <int KIND>
-__device__ __forceinline__ void epilogue(const SP& p, int layer, int strip, const float* vals, int lane,
-                                         const EpiPre& pre) {
-    const int MR = p.MR, d = p.d;
+__device__ __forceinline__ void epilogue(const SP& p, const Lds& s, int layer, int strip, f32x4 v, int lane,
+                                         const EpiPre& pre, f32x4& resid) {
+    const int c = lane & 15, quad = lane >> 4, d = p.d;
+    const bool live = c < p.MR;
     if (KIND == K_A) {
+        const float r = s.rn[c];
         const int o0 = strip * 16, seg = o0 / d, j0 = o0 - seg * d;
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const int idx = lane + 64 * q;
-            if (idx < 8 * MR) {
-                const int t = idx & 7, c = idx >> 3;
-                float e0 = vals[(2 * t) * 16 + c], e1 = vals[(2 * t + 1) * 16 + c];
-                const float2 cs = pre.rot[q];  // (1, 0) for the value rows
-                const float a = e0 * cs.x - e1 * cs.y, b = e0 * cs.y + e1 * cs.x;
-                e0 = a; e1 = b;
-                if (seg == 0) {
-                    st_f32x2(slot(p, layer) + p.aq + (size_t)c * d + j0 + 2 * t, e0, e1);
-                } else {
-                    const RowPos rp = row_pos(p, c);
-                    if (rp.valid) {
-                        _Float16* dst = (seg == 1 ? p.Kc : p.Vc) +
-                                        (((size_t)layer * p.Smax + rp.seq) * p.Tmax + rp.pos) * d + j0 + 2 * t;
-                        const _Float16 h0 = (_Float16)e0, h1 = (_Float16)e1;
-                        const unsigned pk = (unsigned)__builtin_bit_cast(unsigned short, h0) |
-                                            ((unsigned)__builtin_bit_cast(unsigned short, h1) << 16);
-                        __hip_atomic_store(reinterpret_cast<unsigned*>(dst), pk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    }
+        v *= r;
+        const float a0 = v[0] * pre.rot[0].x - v[1] * pre.rot[0].y, b0 = v[0] * pre.rot[0].y + v[1] * pre.rot[0].x;
+        const float a1 = v[2] * pre.rot[1].x - v[3] * pre.rot[1].y, b1 = v[2] * pre.rot[1].y + v[3] * pre.rot[1].x;
+        if (live) {
+            if (seg == 0) {  // queries, already scaled by 1/sqrt(head_dim) = 1/8
+                st_f32x4(slot(p, layer) + p.o_q + (size_t)c * d + j0 + 4 * quad,
+                         (f32x4){a0 * 0.125f, b0 * 0.125f, a1 * 0.125f, b1 * 0.125f});
+            } else {
+                const RowPos rp = row_pos(p, c);
+                if (rp.valid) {
+                    _Float16* dst = (seg == 1 ? p.Kc : p.Vc) +
+                                    (((size_t)layer * p.Smax + rp.seq) * p.Tmax + rp.pos) * d + j0 + 4 * quad;
+                    const _Float16 h0 = (_Float16)a0, h1 = (_Float16)b0, h2 = (_Float16)a1, h3 = (_Float16)b1;
+                    st_u64(dst,
+                           (unsigned)__builtin_bit_cast(unsigned short, h0) | ((unsigned)__builtin_bit_cast(unsigned short, h1) << 16),
+                           (unsigned)__builtin_bit_cast(unsigned short, h2) | ((unsigned)__builtin_bit_cast(unsigned short, h3) << 16));
                 }
             }
         }
-    } else if (KIND == K_C || KIND == K_E) {
-        // residual add: x' = x + Wo o (stage C), x(next layer) = x' + W2 h (stage E)
-        float* out = KIND == K_C ? slot(p, layer) + p.ax2 : slot(p, layer + 1) + p.ax;
+    } else if (KIND == K_C) {  // x' = x + Wo o
+        resid += v;
+        put_stream(p, plane(p, layer, p.o_x2h), plane(p, layer, p.o_x2l), slot(p, layer) + p.o_ss2, strip, lane, resid,
+                   pre.gain);
+    } else if (KIND == K_E) {  // x(next layer) = x' + W2 h
+        resid += v;
+        put_stream(p, plane(p, layer + 1, p.o_xh), plane(p, layer + 1, p.o_xl), slot(p, layer + 1) + p.o_ssx, strip, lane,
+                   resid, pre.gain);
+        if (layer == p.L - 1 && live)  // final hidden rows, for the kernels that follow
+            *reinterpret_cast<f32x4*>(p.X + (size_t)c * d + strip * 16 + 4 * quad) = resid;
+    } else if (KIND == K_D) {  // rows 0..7: W1 rows strip*8+i, rows 8..15: the matching W3 rows
+        const float r = s.rn[c];
+        v *= r;
+        f32x4 u3;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int e = lane + 64 * q;
-            if (e < 16 * MR) {
-                const int row = e & 15, c = e >> 4;
-                const size_t at = (size_t)c * d + strip * 16 + row;
-                const float y = pre.res[q] + vals[row * 16 + c];
-                st_f32(out + at, y);
-                if (KIND == K_E && layer == p.L - 1) p.X[at] = y;  // final hidden rows, for the next kernel
-            }
-        }
-    } else if (KIND == K_D) {
-        for (int e = lane; e < 8 * MR; e += 64) {
-            const int i = e & 7, c = e >> 3;
-            const float u1 = vals[i * 16 + c], u3 = vals[(8 + i) * 16 + c];
-            st_f32(slot(p, layer) + p.ah + (size_t)c * p.m + strip * 8 + i, u1 / (1.0f + expf(-u1)) * u3);
+        for (int e = 0; e < 4; ++e) u3[e] = __shfl_xor(v[e], 32, 64);
+        if (live && quad < 2) {
+            f32x4 h;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) h[e] = v[e] / (1.0f + expf(-v[e])) * u3[e];
+            const size_t at = (size_t)c * p.Kpm + strip * 8 + 4 * quad;
+            st_split4(plane(p, layer, p.o_hh) + at, plane(p, layer, p.o_hl) + at, h);
         }
     } else if (KIND == K_LM) {
-        for (int e = lane; e < 16 * MR; e += 64) {
-            const int row = e & 15, c = e >> 4;
-            p.logit_s[(size_t)c * p.Vs + strip * 16 + row] = vals[row * 16 + c];
-        }
+        const float r = s.rn[c];
+        if (live) *reinterpret_cast<f32x4*>(p.logit_s + (size_t)c * p.Vs + strip * 16 + 4 * quad) = v * r;
     }
 }
 
-struct Lds {
-    uint16_t* act_hi;
-    uint16_t* act_lo;
-    float* red;      // [kCW][kMaxStrips][64][4]
-    float* vals;     // [kMaxStrips][16][16]
-    float* att;      // attention: scaled queries
-    unsigned* join;  // arrivals of the IO waves (only ever grows)
-};
-
-// Waits until all IO waves of the workgroup have reached this point of stage `bar.id`
-// (their global stores already acknowledged).  LDS only; bounded like the grid barrier.
+// Waits until all IO waves of the workgroup have reached this point (their global stores
+// already acknowledged).  LDS only; bounded like the grid barrier.
 __device__ __forceinline__ void io_join(const Lds& s, Barrier& bar, int lane) {
     const unsigned want = ++bar.joins * kNIO;
     if (lane == 0) atomicAdd(s.join, 1u);
@@ -468,34 +470,69 @@ __device__ __forceinline__ void io_join(const Lds& s, Barrier& bar, int lane) {
     compiler_fence();
 }
 
-template <int KIND, int TPS, bool NORM, int KREG>
+// The IO waves' end of a stage: stores acknowledged, all IO waves joined, one arrival posted.
+__device__ __forceinline__ void io_finish(const SP& p, const Lds& s, Barrier& bar, unsigned ph, int wave, int lane) {
+    __builtin_amdgcn_s_waitcnt(0);
+    io_join(s, bar, lane);
+    stamp(p, ph, 5);
+    if (wave == kCW && lane == 0) bar.arrive(); else ++bar.id;
+    stamp(p, ph, 6);
+}
+
+// First stage of a launch: the owners of the residual strips pick their slice of the embedded
+// rows up and publish it in the form stage A of layer 0 expects.
+__device__ __forceinline__ void prologue_phase(const SP& p, const Lds& s, Barrier& bar, f32x4& resid) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const Job job = load_job(p, K_C, 0, 0);
+    const unsigned ph = bar.id - bar.first;
+    if (wave >= kCW) {
+        stamp(p, ph, 0);
+        if (wave == kCW && job.nstrips) {
+            const int c = lane & 15, quad = lane >> 4, strip = job.strip[0];
+            const uint2 gain = *reinterpret_cast<const uint2*>(p.blob + p.g1_off / 2 + strip * 16 + 4 * quad);
+            resid = c < p.MR ? *reinterpret_cast<const f32x4*>(p.X + (size_t)c * p.d + strip * 16 + 4 * quad)
+                             : (f32x4){0.f, 0.f, 0.f, 0.f};
+            put_stream(p, plane(p, 0, p.o_xh), plane(p, 0, p.o_xl), slot(p, 0) + p.o_ssx, strip, lane, resid, gain);
+        }
+        io_finish(p, s, bar, ph, wave, lane);
+    } else {
+        ++bar.id;
+    }
+}
+
+// KIND: which matrix; TPS: k-tiles per compute wave and strip; NSS: per-strip sums of squares
+// per lane of the row-scale reduction (0: the stage input is not normalised); BATCH: chunks in
+// flight per IO thread while copying the stage input.
+template <int KIND, int TPS, int NSS, int BATCH, int KREG>
 __device__ __forceinline__ void gemv_phase(const SP& p, const Lds& s, Barrier& bar, int layer, int round,
-                                           const float* src, int K, const uint16_t* gain) {
+                                           const uint16_t* src_hi, const uint16_t* src_lo, const float* ss, int K, int Kp,
+                                           f32x4& resid) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const bool is_io = wave >= kCW;
     const Job job = load_job(p, KIND, round, layer);
-    const unsigned ph = bar.id - bar.first;
-    // Nothing below depends on the previous stage, so it is requested before the barrier is
-    // crossed and lands while the IO waves synchronise: the weights (compute waves), the norm
-    // gains and the epilogue's residual slice / rotary factors (IO waves).
+    const unsigned ph = bar.id - bar.first + (KIND == K_LM ? round : 0);
+    // The rounds of the output projection share one input: only the first waits and stages it.
+    const bool fresh = !(KIND == K_LM && round > 0);
+    // Nothing in this block depends on the previous stage, so it is requested before the barrier
+    // is crossed: the weights (compute waves), rotary factors and gains (IO waves).
     v4u w[kTMax];
-    uint2 g[KREG];
-    EpiPre pre[kMaxStrips];
+    EpiPre pre;
     if (!is_io) {
         issue_tiles(p, job, TPS, wave, lane, w);
     } else {
         stamp(p, ph, 0);
-        if (NORM && job.nstrips) load_gains<KREG>(gain, K, lane, g);
-        if (wave == kCW) {
-#pragma unroll
-            for (int i = 0; i < kMaxStrips; ++i)
-                if (i < job.nstrips) epilogue_prefetch<KIND>(p, layer, job.strip[i], lane, pre[i]);
-        }
-        bar.wait();
-        stamp(p, ph, 1);
-        if (job.nstrips) {
-            if (KIND == K_C) stage_attention<KREG>(p, layer, wave - kCW, lane, s.act_hi, s.act_lo);
-            else stage_rows<NORM, KREG>(src, K, p.MR, g, p.eps, wave - kCW, lane, s.act_hi, s.act_lo, p.Kp);
+        if (wave - kCW < job.nstrips) epilogue_prefetch<KIND>(p, layer, job.strip[wave - kCW], lane, pre);
+        if (fresh) {
+            bar.wait();
+            stamp(p, ph, 1);
+            if constexpr (NSS > 0) {
+                if (wave == kCW + kNIO - 1) row_scales<NSS>(ss, K, p.eps, lane, s.rn);
+            }
+            if (KIND == K_C && p.NC > 1) {
+                if (job.nstrips) stage_attention<KREG>(p, layer, wave - kCW, lane, s.act_hi, s.act_lo);
+            } else if (job.nstrips || KIND == K_LM) {
+                stage_copy<BATCH>(src_hi, src_lo, p.MR, Kp, s.act_hi, s.act_lo, threadIdx.x - kCW * 64);
+            }
         }
         stamp(p, ph, 2);
     }
@@ -505,44 +542,33 @@ __device__ __forceinline__ void gemv_phase(const SP& p, const Lds& s, Barrier& b
         f32x4 acc[kMaxStrips];
 #pragma unroll
         for (int i = 0; i < kMaxStrips; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        mfma_job<TPS>(w, job.nstrips, wave, lane, p.MR, s.act_hi, s.act_lo, p.Kp, acc);
+        mfma_job<TPS>(w, job.nstrips, wave, lane, p.MR, s.act_hi, s.act_lo, Kp, acc);
 #pragma unroll
         for (int i = 0; i < kMaxStrips; ++i)
             if (i < job.nstrips) *reinterpret_cast<f32x4*>(s.red + (((size_t)wave * kMaxStrips + i) * 64 + lane) * 4) = acc[i];
     }
     __syncthreads();
     stamp(p, ph, 4);
-    if (wave == kCW) {
+    if (is_io) {
+        const int i = wave - kCW;  // IO wave i finishes strip i of the job
+        if (i < job.nstrips) {
+            f32x4 v = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < kMaxStrips; ++i) {
-            if (i < job.nstrips) {
-                // sum the four K quarters; lane holds rows 4*(lane/16)..+3 of column lane%16
-                f32x4 v = (f32x4){0.f, 0.f, 0.f, 0.f};
-                for (int cw = 0; cw < kCW; ++cw)
-                    v += *reinterpret_cast<const f32x4*>(s.red + (((size_t)cw * kMaxStrips + i) * 64 + lane) * 4);
-                float* vs = s.vals + (size_t)i * 256;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) vs[((lane >> 4) * 4 + q) * 16 + (lane & 15)] = v[q];
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the LDS writes above are visible to the wave
-                epilogue<KIND>(p, layer, job.strip[i], vs, lane, pre[i]);
-                __builtin_amdgcn_wave_barrier();
-            }
+            for (int cw = 0; cw < kCW; ++cw)
+                v += *reinterpret_cast<const f32x4*>(s.red + (((size_t)cw * kMaxStrips + i) * 64 + lane) * 4);
+            epilogue<KIND>(p, s, layer, job.strip[i], v, lane, pre, resid);
         }
-        __builtin_amdgcn_s_waitcnt(0);  // results are out before this workgroup arrives
-        stamp(p, ph, 5);
-        if (lane == 0) bar.arrive(); else ++bar.id;
-        stamp(p, ph, 6);
-    } else {
+        if (KIND != K_LM) io_finish(p, s, bar, ph, wave, lane);  // nothing follows the output projection
+    } else if (KIND != K_LM) {
         ++bar.id;
     }
 }
 
 // ------------------------------------------------------------------------- attention
 
-// Workgroup (seq, head, chunk) reduces its slice of the cached positions - requested before
-// the barrier is crossed, they were written by earlier launches - and, for the last chunk,
-// the rows appended by this launch, to an un-normalised partial (m, l, o~) per query row.
+// A job = (sequence, head, row group, chunk): it reduces its slice of the cached positions -
+// requested before the barrier is crossed, they were written by earlier launches - and, for the
+// last chunk, the rows appended by this launch, for the query rows of its group.
 // Lane layout: 8 positions per wave load, 8 lanes x 8 dims per position.
 struct AttnAcc {
     float acc[8], mx, den;
@@ -556,9 +582,11 @@ __device__ __forceinline__ float sum8(float v) {
     return v;
 }
 
-template <int RSMAX>
-__device__ __forceinline__ void attend(const float* qs, int RS, int dg, v4u kraw, v4u vraw, int row_lo, int ke,
-                                       AttnAcc (&A)[RSMAX]) {
+// qs: the job's scaled query rows [RPJ][64]; r0: absolute index of its first row; row_lo: first
+// absolute row that may see this position; ke: last valid row.
+template <int RPJ>
+__device__ __forceinline__ void attend(const float* qs, int r0, int dg, v4u kraw, v4u vraw, int row_lo, int ke,
+                                       AttnAcc (&A)[RPJ]) {
     float kf[8], vf[8];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -568,47 +596,48 @@ __device__ __forceinline__ void attend(const float* qs, int RS, int dg, v4u kraw
         vf[2 * e + 1] = (float)__builtin_bit_cast(_Float16, (unsigned short)(vraw[e] >> 16));
     }
 #pragma unroll
-    for (int r = 0; r < RSMAX; ++r) {
-        if (r < RS) {
-            const float4 qa = *reinterpret_cast<const float4*>(qs + r * 64 + dg * 8);
-            const float4 qb = *reinterpret_cast<const float4*>(qs + r * 64 + dg * 8 + 4);
-            float sc = qa.x * kf[0] + qa.y * kf[1] + qa.z * kf[2] + qa.w * kf[3] + qb.x * kf[4] + qb.y * kf[5] +
-                       qb.z * kf[6] + qb.w * kf[7];
-            sc = sum8(sc);
-            if (r >= row_lo && r <= ke) {  // row_lo: first query row that may see this position
-                const float mn = fmaxf(A[r].mx, sc);
-                const float corr = __expf(A[r].mx - mn), pw = __expf(sc - mn);
-                A[r].den = A[r].den * corr + pw;
+    for (int r = 0; r < RPJ; ++r) {
+        const float4 qa = *reinterpret_cast<const float4*>(qs + r * 64 + dg * 8);
+        const float4 qb = *reinterpret_cast<const float4*>(qs + r * 64 + dg * 8 + 4);
+        float sc = qa.x * kf[0] + qa.y * kf[1] + qa.z * kf[2] + qa.w * kf[3] + qb.x * kf[4] + qb.y * kf[5] +
+                   qb.z * kf[6] + qb.w * kf[7];
+        sc = sum8(sc);
+        if (r0 + r >= row_lo && r0 + r <= ke) {
+            const float mn = fmaxf(A[r].mx, sc);
+            const float corr = __expf(A[r].mx - mn), pw = __expf(sc - mn);
+            A[r].den = A[r].den * corr + pw;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) A[r].acc[e] = A[r].acc[e] * corr + pw * vf[e];
-                A[r].mx = mn;
-            }
+            for (int e = 0; e < 8; ++e) A[r].acc[e] = A[r].acc[e] * corr + pw * vf[e];
+            A[r].mx = mn;
         }
     }
 }
 
-template <int RSMAX>
+template <int RPJ>
 __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& bar, int layer) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const bool is_io = wave >= kCW;
-    const int wg = blockIdx.x;
-    const bool have = wg < p.S * p.H * p.NC;
-    const int seq = wg / (p.H * p.NC), h = (wg / p.NC) % p.H, ch = wg % p.NC;
-    const int d = p.d, RS = p.RS;
-    float* qs = s.att;                                   // [RS][64] scaled queries
-    float* part = reinterpret_cast<float*>(s.act_hi);    // [kCW*8][RSMAX][kPS], over the idle activation buffers
+    // Jobs of one (sequence, head) sit on one XCD, so that its L2 serves their common K/V rows.
+    const int xcd = blockIdx.x % kXcd, li = blockIdx.x / kXcd, per = p.NRG * p.NC;
+    const int sh = xcd + kXcd * (li / per), sub = li % per;
+    const bool have = sh < p.S * p.H;
+    const int seq = have ? sh / p.H : 0, h = have ? sh % p.H : 0, rg = sub / p.NC, ch = sub % p.NC;
+    const int d = p.d, RS = p.RS, r0 = rg * RPJ;
+    float* qs = s.att;                                   // [RPJ][64] scaled queries
+    float* part = reinterpret_cast<float*>(s.act_hi);    // [kCW][RPJ][kPS], over the idle activation buffers
     const unsigned ph = bar.id - bar.first;
     const int pg = lane >> 3, dg = lane & 7;
     const int b = seq % p.B;
     const int ke = have ? p.k_eff[b] : -1;
     const int kv0 = ke >= 0 ? p.C + p.n[b] - 1 : 0;  // positions cached before this launch
     const int o0 = (int)((long long)kv0 * ch / p.NC), o1 = (int)((long long)kv0 * (ch + 1) / p.NC);
+    const int nrounds = (o1 - o0 + kNIT * kCW * 8 - 1) / (kNIT * kCW * 8);
     const size_t base = (((size_t)layer * p.Smax + seq) * p.Tmax) * d + (size_t)h * 64 + dg * 8;
-    v4u kk[kNIT], vv[kNIT];
-    if (!is_io && have) {
+    v4u ka[kNIT], va[kNIT], kb[kNIT], vb[kNIT];
+    auto fetch = [&](v4u (&kk)[kNIT], v4u (&vv)[kNIT], int rnd) {
 #pragma unroll
         for (int it = 0; it < kNIT; ++it) {
-            const int pos = o0 + it * (kCW * 8) + wave * 8 + pg;
+            const int pos = o0 + (rnd * kNIT + it) * (kCW * 8) + wave * 8 + pg;
             if (pos < o1) {
                 kk[it] = *reinterpret_cast<const v4u*>(p.Kc + base + (size_t)pos * d);
                 vv[it] = *reinterpret_cast<const v4u*>(p.Vc + base + (size_t)pos * d);
@@ -617,30 +646,42 @@ __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& b
                 vv[it] = (v4u){0u, 0u, 0u, 0u};
             }
         }
+    };
+    if (!is_io && have) {
+        fetch(ka, va, 0);
+        fetch(kb, vb, 1);
     }
     if (is_io) {
         stamp(p, ph, 0);
         bar.wait();
         stamp(p, ph, 1);
         if (have && wave == kCW)
-            for (int r = 0; r < RS; ++r)
-                qs[r * 64 + lane] = (slot(p, layer) + p.aq)[(size_t)(seq * RS + r) * d + h * 64 + lane] * 0.125f;
+            for (int r = 0; r < RPJ; ++r)
+                qs[r * 64 + lane] = r0 + r < RS ? (slot(p, layer) + p.o_q)[(size_t)(seq * RS + r0 + r) * d + h * 64 + lane] : 0.f;
         stamp(p, ph, 2);
     }
     __syncthreads();
     stamp(p, ph, 3);
     if (!is_io && have) {
-        AttnAcc A[RSMAX];
+        AttnAcc A[RPJ];
 #pragma unroll
-        for (int r = 0; r < RSMAX; ++r) {
+        for (int r = 0; r < RPJ; ++r) {
             A[r].mx = -1e30f; A[r].den = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) A[r].acc[e] = 0.f;
         }
+        auto run = [&](const v4u (&kk)[kNIT], const v4u (&vv)[kNIT], int rnd) {
 #pragma unroll
-        for (int it = 0; it < kNIT; ++it) {
-            const int pos = o0 + it * (kCW * 8) + wave * 8 + pg;
-            if (pos < o1) attend<RSMAX>(qs, RS, dg, kk[it], vv[it], 0, ke, A);
+            for (int it = 0; it < kNIT; ++it) {
+                const int pos = o0 + (rnd * kNIT + it) * (kCW * 8) + wave * 8 + pg;
+                if (pos < o1) attend<RPJ>(qs, r0, dg, kk[it], vv[it], 0, ke, A);
+            }
+        };
+        for (int rnd = 0; rnd < nrounds; rnd += 2) {
+            run(ka, va, rnd);
+            fetch(ka, va, rnd + 2);
+            run(kb, vb, rnd + 1);
+            fetch(kb, vb, rnd + 3);
         }
         if (ch == p.NC - 1 && wave == 0 && pg <= ke) {  // rows appended by this launch: coherent loads
             const _Float16* kp = p.Kc + base + (size_t)(kv0 + pg) * d;
@@ -651,48 +692,59 @@ __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& b
             const u64 b1 = __hip_atomic_load(reinterpret_cast<const u64*>(vp) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const v4u kraw = (v4u){(unsigned)a0, (unsigned)(a0 >> 32), (unsigned)a1, (unsigned)(a1 >> 32)};
             const v4u vraw = (v4u){(unsigned)b0, (unsigned)(b0 >> 32), (unsigned)b1, (unsigned)(b1 >> 32)};
-            attend<RSMAX>(qs, RS, dg, kraw, vraw, pg, ke, A);  // row r sees appended row pg iff pg <= r
+            attend<RPJ>(qs, r0, dg, kraw, vraw, pg, ke, A);  // row r sees appended row pg iff pg <= r
         }
-        // hand the (wave, lane group) partials to the IO waves through LDS (the activation
-        // buffers are idle during this stage): [wave*8 + pg][row][kPS]
-        float* mine = part + ((size_t)(wave * 8 + pg) * RSMAX) * kPS + dg * 8;
+        // merge the eight position groups of the wave (lanes that share dg), then hand the wave's
+        // partial to the IO waves through LDS: part[wave][row][kPS]
 #pragma unroll
-        for (int r = 0; r < RSMAX; ++r) {
-            if (r < RS) {
-                *reinterpret_cast<float4*>(mine + r * kPS) = make_float4(A[r].acc[0], A[r].acc[1], A[r].acc[2], A[r].acc[3]);
-                *reinterpret_cast<float4*>(mine + r * kPS + 4) = make_float4(A[r].acc[4], A[r].acc[5], A[r].acc[6], A[r].acc[7]);
-                if (dg == 0) *reinterpret_cast<float2*>(mine + r * kPS + 64) = make_float2(A[r].mx, A[r].den);
+        for (int r = 0; r < RPJ; ++r) {
+#pragma unroll
+            for (int o = 8; o < 64; o <<= 1) {
+                const float omx = __shfl_xor(A[r].mx, o, 64), oden = __shfl_xor(A[r].den, o, 64);
+                const float mn = fmaxf(A[r].mx, omx);
+                const float f0 = __expf(A[r].mx - mn), f1 = __expf(omx - mn);
+                A[r].den = A[r].den * f0 + oden * f1;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) A[r].acc[e] = A[r].acc[e] * f0 + __shfl_xor(A[r].acc[e], o, 64) * f1;
+                A[r].mx = mn;
+            }
+            if (pg == 0) {
+                float* mine = part + ((size_t)wave * RPJ + r) * kPS;
+                *reinterpret_cast<float4*>(mine + dg * 8) = make_float4(A[r].acc[0], A[r].acc[1], A[r].acc[2], A[r].acc[3]);
+                *reinterpret_cast<float4*>(mine + dg * 8 + 4) = make_float4(A[r].acc[4], A[r].acc[5], A[r].acc[6], A[r].acc[7]);
+                if (dg == 0) *reinterpret_cast<float2*>(mine + 64) = make_float2(A[r].mx, A[r].den);
             }
         }
     }
     __syncthreads();
     stamp(p, ph, 4);
     if (is_io) {
-        if (have) {  // IO wave i merges the 32 partials of rows i, i + kNIO, ...; lane = output dim
-            float* out = slot(p, layer) + p.ap + (size_t)wg * RS * kPS;
-            for (int r = wave - kCW; r < RS; r += kNIO) {
-                float m2 = -1e30f;
-                for (int g = 0; g < kCW * 8; ++g) m2 = fmaxf(m2, part[((size_t)g * RSMAX + r) * kPS + 64]);
-                float dn = 0.f, o = 0.f;
-                for (int g = 0; g < kCW * 8; ++g) {
-                    const float* src = part + ((size_t)g * RSMAX + r) * kPS;
-                    const float f = __expf(src[64] - m2);
-                    dn += src[65] * f;
-                    o += src[lane] * f;
-                }
-                st_f32(out + r * kPS + lane, o);
-                if (lane == 0) st_f32x2(out + r * kPS + 64, m2, dn);
+        const int t = threadIdx.x - kCW * 64;  // thread t: row t / 16 of the job, output dims 4 * (t % 16)..+3
+        const int r = t >> 4, q4 = t & 15;
+        if (have && r < RPJ && r0 + r < RS) {
+            float m2 = -1e30f;
+#pragma unroll
+            for (int w = 0; w < kCW; ++w) m2 = fmaxf(m2, part[((size_t)w * RPJ + r) * kPS + 64]);
+            float dn = 0.f;
+            f32x4 o = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < kCW; ++w) {
+                const float* src = part + ((size_t)w * RPJ + r) * kPS;
+                const float f = __expf(src[64] - m2);
+                dn += src[65] * f;
+                o += *reinterpret_cast<const f32x4*>(src + 4 * q4) * f;
+            }
+            if (p.NC == 1) {  // finished rows of the head: normalise and publish split
+                const float inv = dn > 0.f ? 1.0f / dn : 0.f;
+                const size_t at = (size_t)(seq * RS + r0 + r) * p.Kpd + h * 64 + 4 * q4;
+                st_split4(plane(p, layer, p.o_oh) + at, plane(p, layer, p.o_ol) + at, o * inv);
+            } else {
+                float* out = slot(p, layer) + p.o_p + ((size_t)(sh * p.NC + ch) * RS + r0 + r) * kPS;
+                st_f32x4(out + 4 * q4, o);
+                if (q4 == 0) st_f32x2(out + 64, m2, dn);
             }
         }
-        __builtin_amdgcn_s_waitcnt(0);
-        io_join(s, bar, lane);  // every IO wave's stores are out before the arrival is posted
-        stamp(p, ph, 5);
-        if (wave == kCW) {
-            if (lane == 0) bar.arrive(); else ++bar.id;
-        } else {
-            ++bar.id;
-        }
-        stamp(p, ph, 6);
+        io_finish(p, s, bar, ph, wave, lane);
     } else {
         ++bar.id;
     }
@@ -700,32 +752,38 @@ __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& b
 
 // ------------------------------------------------------------------------- the kernel
 
-template <int TPS_D, int TPS_M, int KREG_D, int KREG_M, int RSMAX>
+template <int TPS_D, int TPS_M, int KREG_D, int RSMAX>
 __global__ __launch_bounds__(kThreads, 1) void verify_stream_kernel(SP p) {
     extern __shared__ uint4 smem_raw[];
     Lds s;
     s.act_hi = reinterpret_cast<uint16_t*>(smem_raw);
-    s.act_lo = s.act_hi + (size_t)p.MR * p.Kp;
+    s.act_lo = s.act_hi + (size_t)p.MR * p.Kpm;
     s.red = reinterpret_cast<float*>(reinterpret_cast<char*>(smem_raw) + p.act_bytes);
-    s.vals = s.red + kCW * kMaxStrips * 64 * 4;
-    s.att = s.vals + kMaxStrips * 256;
-    s.join = reinterpret_cast<unsigned*>(s.att + 8 * 64);
+    s.rn = s.red + kCW * kMaxStrips * 64 * 4;
+    s.att = s.rn + 16;
+    s.join = reinterpret_cast<unsigned*>(s.att + RSMAX * 64);
     if (threadIdx.x == 0) *s.join = 0u;
     __syncthreads();
     Barrier bar;
     bar.mem = p.bar; bar.err = p.err; bar.id = p.epoch0; bar.first = p.epoch0; bar.joins = 0; bar.dead = false;
+    f32x4 resid = (f32x4){0.f, 0.f, 0.f, 0.f};  // the workgroup's strip of the residual stream (first IO wave)
+    constexpr int NSS = 2 * TPS_D;             // (d / 16 strips) / 4 lane groups
+    prologue_phase(p, s, bar, resid);
     for (int l = 0; l < p.L; ++l) {
-        const uint16_t* g1 = p.blob + (p.g1_off + (u64)l * p.layer_bytes) / 2;
-        const uint16_t* g2 = p.blob + (p.g2_off + (u64)l * p.layer_bytes) / 2;
-        gemv_phase<K_A, TPS_D, true, KREG_D>(p, s, bar, l, 0, x_in(p, l), p.d, g1);
-        attn_phase<RSMAX>(p, s, bar, l);
-        gemv_phase<K_C, TPS_D, false, KREG_D>(p, s, bar, l, 0, nullptr, p.d, nullptr);
-        gemv_phase<K_D, TPS_D, true, KREG_D>(p, s, bar, l, 0, slot(p, l) + p.ax2, p.d, g2);
-        gemv_phase<K_E, TPS_M, false, KREG_M>(p, s, bar, l, 0, slot(p, l) + p.ah, p.m, nullptr);
+        gemv_phase<K_A, TPS_D, NSS, 8, KREG_D>(p, s, bar, l, 0, plane(p, l, p.o_xh), plane(p, l, p.o_xl),
+                                               slot(p, l) + p.o_ssx, p.d, p.Kpd, resid);
+        if (p.RPJ == 1) attn_phase<1>(p, s, bar, l);
+        else attn_phase<RSMAX>(p, s, bar, l);
+        gemv_phase<K_C, TPS_D, 0, 8, KREG_D>(p, s, bar, l, 0, plane(p, l, p.o_oh), plane(p, l, p.o_ol), nullptr, p.d,
+                                             p.Kpd, resid);
+        gemv_phase<K_D, TPS_D, NSS, 8, KREG_D>(p, s, bar, l, 0, plane(p, l, p.o_x2h), plane(p, l, p.o_x2l),
+                                               slot(p, l) + p.o_ss2, p.d, p.Kpd, resid);
+        gemv_phase<K_E, TPS_M, 0, 11, KREG_D>(p, s, bar, l, 0, plane(p, l, p.o_hh), plane(p, l, p.o_hl), nullptr, p.m,
+                                              p.Kpm, resid);
     }
-    const uint16_t* gf = p.blob + p.gf_off / 2;
     for (int r = 0; r < p.rounds[K_LM]; ++r)
-        gemv_phase<K_LM, TPS_D, true, KREG_D>(p, s, bar, p.L - 1, r, slot(p, p.L) + p.ax, p.d, gf);
+        gemv_phase<K_LM, TPS_D, NSS, 8, KREG_D>(p, s, bar, p.L - 1, r, plane(p, p.L, p.o_xh), plane(p, p.L, p.o_xl),
+                                                slot(p, p.L) + p.o_ssx, p.d, p.Kpd, resid);
 }
 
 // Copies one matrix into the tile order of its kind: tile T of the packed stream is
@@ -762,7 +820,6 @@ struct StreamPlan {
     size_t layer_tiles, kind_base[4], lm_base, wd_base, total_tiles;
     std::vector<int32_t> tab;
     std::vector<uint32_t> desc;
-    std::vector<uint32_t> hasmask;
     unsigned epoch;     // grid barriers completed by all launches so far
     unsigned launches;
 };
@@ -800,15 +857,26 @@ void build_plan(const hawk_ctx* c, StreamPlan* P) {
     }
     std::vector<std::vector<int>> assign[K_NKIND];  // [kind][round][wg] -> strips
     for (int k = 0; k < K_NKIND; ++k) assign[k].assign((size_t)P->kind[k].rounds * kNWG, {});
+    // Wo and W2: strip s of both belongs to workgroup s, which keeps that strip of the residual
+    // stream in registers for the whole launch (workgroup s runs on XCD s % 8).
+    if (nstrips[K_C] > kNWG || nstrips[K_E] != nstrips[K_C]) { P->ok = false; return; }
     std::vector<long> load(kNWG, 0);
-    int order[4] = {K_A, K_C, K_D, K_E};
-    std::sort(order, order + 4, [&](int a, int b) { return P->kind[a].TPS > P->kind[b].TPS; });
-    for (int oi = 0; oi < 4; ++oi) {
+    for (int s = 0; s < nstrips[K_C]; ++s) {
+        assign[K_C][s].push_back(s);
+        assign[K_E][s].push_back(s);
+        load[s] += P->kind[K_C].TPS + P->kind[K_E].TPS;
+    }
+    // QKV and W1|W3: as few strips per workgroup as the count allows, the extra ones to the
+    // workgroups that stream least per layer.
+    const int order[2] = {K_D, K_A};
+    for (int oi = 0; oi < 2; ++oi) {
         const int k = order[oi];
+        const int cap = (nstrips[k] + kNWG - 1) / kNWG;
+        if (cap > P->kind[k].maxS) { P->ok = false; return; }
         for (int s = 0; s < nstrips[k]; ++s) {
             int best = -1;
             for (int g = 0; g < kNWG; ++g)
-                if ((int)assign[k][g].size() < P->kind[k].maxS && (best < 0 || load[g] < load[best])) best = g;
+                if ((int)assign[k][g].size() < cap && (best < 0 || load[g] < load[best])) best = g;
             assign[k][best].push_back(s);
             load[best] += P->kind[k].TPS;
         }
@@ -822,7 +890,6 @@ void build_plan(const hawk_ctx* c, StreamPlan* P) {
         }
     }
     P->tab.clear(); P->desc.clear();
-    P->hasmask.assign(kNWG, 0);
     for (int k = 0; k < K_NKIND; ++k) {
         KindPlan& kp = P->kind[k];
         kp.tab_index = P->tab.size();
@@ -838,7 +905,6 @@ void build_plan(const hawk_ctx* c, StreamPlan* P) {
                 P->tab.push_back(ns);
                 P->tab.push_back((int32_t)((unsigned)s3[0] | ((unsigned)s3[1] << 16)));
                 P->tab.push_back(s3[2]);
-                if (ns) P->hasmask[g] |= k <= K_E ? (1u << k) : (k == K_LM ? (1u << (8 + r)) : 0u);
                 for (int wv = 0; wv < kCW; ++wv)
                     for (int t = 0; t < ns * kp.TPS; ++t) {
                         P->desc.push_back(((uint32_t)st[t / kp.TPS] << 12) | (uint32_t)(wv * kp.TPS + t % kp.TPS));
@@ -860,6 +926,22 @@ void build_plan(const hawk_ctx* c, StreamPlan* P) {
 
 size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// Regions of an exchange slot, in floats: split planes are uint16 [16][K + 8] (hi, lo), sums of
+// squares [d / 16][16], queries [16][d], attention chunk partials.  Returns the slot size.
+size_t slot_layout(const hawk_ctx* c, SP* p) {
+    const size_t d = c->d, m = c->m, pd = 8 * (d + 8), pm = 8 * (m + 8);
+    size_t at = 0;
+    auto take = [&](size_t n) { size_t a = at; at += (n + 63) & ~(size_t)63; return a; };
+    const size_t xh = take(pd), xl = take(pd), ssx = take(d), q = take(16 * d), oh = take(pd), ol = take(pd);
+    const size_t x2h = take(pd), x2l = take(pd), ss2 = take(d), hh = take(pm), hl = take(pm);
+    const size_t pp = take((size_t)kNWG * 8 * kPS);
+    if (p) {
+        p->o_xh = xh; p->o_xl = xl; p->o_ssx = ssx; p->o_q = q; p->o_oh = oh; p->o_ol = ol;
+        p->o_x2h = x2h; p->o_x2l = x2l; p->o_ss2 = ss2; p->o_hh = hh; p->o_hl = hl; p->o_p = pp;
+    }
+    return at;
+}
+
 }  // namespace
 
 // Bytes the streaming path adds to the workspace (0 if the shape is not supported), and the
@@ -874,9 +956,8 @@ size_t stream_workspace(const hawk_ctx* c, size_t base, StreamOffsets* o) {
     o->wpack = take(tiles * 1024);
     o->tab = take((size_t)(K_NKIND + (size_t)c->Vs / 16 / kNWG + 2) * kNWG * 16);
     o->desc = take(((4 * d * d + 3 * d * m) / 512 + (size_t)c->Vs * d / 512 + 3 * d * d / 512 + 64) * 4);
-    o->hasmask = take(kNWG * 4);
-    // one exchange slot per layer (+1): x, x', q, o [16][d], h [16][m], attention partials; kRing arenas
-    o->slot_bytes = up256((4 * 16 * d + 16 * m + (size_t)kNWG * 8 * kPS) * 4 + 1024);
+    // one exchange slot per layer (+1), kRing arenas
+    o->slot_bytes = up256(slot_layout(c, nullptr) * 4);
     o->arena = take(o->slot_bytes * (L + 1) * kRing);
     o->bar = take((size_t)(kGroups + 1 + kReplicas) * 4096);
     o->err = take(256);
@@ -895,7 +976,6 @@ StreamPlan* stream_create(hawk_ctx* c) {
     // tables, rotary table, zeroed barrier memory
     (void)hipMemcpy(c->ws + o.tab, P->tab.data(), P->tab.size() * 4, hipMemcpyHostToDevice);
     (void)hipMemcpy(c->ws + o.desc, P->desc.data(), P->desc.size() * 4, hipMemcpyHostToDevice);
-    (void)hipMemcpy(c->ws + o.hasmask, P->hasmask.data(), P->hasmask.size() * 4, hipMemcpyHostToDevice);
     (void)hipMemset(c->ws + o.bar, 0, (size_t)(kGroups + 1 + kReplicas) * 4096);
     (void)hipMemset(c->ws + o.err, 0, 256);
     std::vector<float> rope((size_t)c->Tmax * (c->hd / 2) * 2);
@@ -952,26 +1032,33 @@ void stream_plan_info(const hawk_ctx* c, int64_t* out) {
     out[6] = sane ? 1 : 0;
 }
 
-// LDS of one workgroup: activation hi/lo (or, during attention, the per-lane-group partials),
-// K-quarter partial strips, finished strips, scaled queries, IO join word.
-static size_t stream_lds_bytes(const hawk_ctx* c, int MR) {
-    const size_t act = std::max((size_t)MR * (std::max(c->d, c->m) + 8) * 4, (size_t)kCW * 8 * 6 * kPS * 4);
-    return act + (kCW * kMaxStrips * 256 + kMaxStrips * 256) * 4 + (8 * 64 + 16) * 4;
+// How the attention stage is cut into jobs for steps of RS rows per sequence: row groups per
+// (sequence, head) and chunks of the cached positions, such that the jobs of the heads that
+// share an XCD fit its 32 workgroups.  One row per job and one chunk when possible (the job then
+// emits finished rows); otherwise all rows per job.
+struct AttnCut { int NRG, RPJ, NC; bool ok; };
+static AttnCut attn_cut(const hawk_ctx* c, int RS) {
+    const int heads_per_xcd = (c->S * c->H + kXcd - 1) / kXcd;
+    AttnCut a;
+    a.NRG = heads_per_xcd * RS <= kPerXcd ? RS : 1;
+    a.RPJ = a.NRG == RS ? 1 : RS;
+    a.NC = std::max(1, std::min(kNCMax, kPerXcd / (heads_per_xcd * a.NRG)));
+    a.ok = heads_per_xcd * a.NRG <= kPerXcd;
+    return a;
 }
 
-// Chunks per (sequence, head) of the attention stage: enough that one chunk's cached positions
-// fit the per-wave register window, more while workgroups are free.
-static int stream_chunks(const hawk_ctx* c) {
-    const int need = (c->Tmax + kNIT * kCW * 8 - 1) / (kNIT * kCW * 8);
-    const int room = kNWG / (c->S * c->H);
-    return std::max(need, std::min(kNCMax, room));
+// LDS of one workgroup: activation hi/lo planes (or, during attention, the per-wave partials),
+// K-quarter partial strips, row scales, scaled queries, IO join word.
+static size_t stream_lds_bytes(const hawk_ctx* c, int MR) {
+    const size_t act = std::max((size_t)MR * (std::max(c->d, c->m) + 8) * 4, (size_t)kCW * 6 * kPS * 4);
+    return act + (size_t)(kCW * kMaxStrips * 256 + 16 + 6 * 64 + 16) * 4;
 }
 
 bool stream_ok(const hawk_ctx* c, int k) {
     if (!c->plan || !c->plan->ok || c->path != 1) return false;
     const int MR = c->S * (k + 1);
     if (MR > 16 || k + 1 > 6) return false;
-    if (c->S * c->H * stream_chunks(c) > kNWG || stream_chunks(c) > kNCMax) return false;
+    if (!attn_cut(c, k + 1).ok) return false;
     return stream_lds_bytes(c, MR) <= 150 * 1024;
 }
 
@@ -1015,7 +1102,6 @@ int launch_verify_stream(hawk_ctx* c, int k) {
         p.tab[i] = wsp<int32_t>(c, o.tab) + P->kind[i].tab_index;
         p.rounds[i] = P->kind[i].rounds;
     }
-    p.hasmask = wsp<uint32_t>(c, o.hasmask);
     p.blob = wsp<uint16_t>(c, c->off.blob);
     p.g1_off = c->w.g1[0]; p.g2_off = c->w.g2[0];
     p.layer_bytes = c->L > 1 ? c->w.g1[1] - c->w.g1[0] : 0;
@@ -1025,8 +1111,7 @@ int launch_verify_stream(hawk_ctx* c, int k) {
     p.X = wsp<float>(c, c->off.x);
     p.arena = wsp<float>(c, o.arena + (size_t)(P->launches % kRing) * o.slot_bytes * (c->L + 1));
     p.slot_floats = o.slot_bytes / 4;
-    p.ax = 0; p.ax2 = (u64)16 * c->d; p.aq = (u64)32 * c->d; p.ao = (u64)48 * c->d; p.ah = (u64)64 * c->d;
-    p.ap = p.ah + (u64)16 * c->m;
+    (void)slot_layout(c, &p);
     p.logit_s = wsp<float>(c, c->off.logit_s);
     p.dbg = c->stream_dbg ? wsp<u64>(c, o.dbg) : nullptr;
     p.bar = wsp<unsigned>(c, o.bar); p.err = wsp<unsigned>(c, o.err);
@@ -1034,17 +1119,18 @@ int launch_verify_stream(hawk_ctx* c, int k) {
     p.epoch0 = P->epoch;
     p.L = c->L; p.d = c->d; p.H = c->H; p.m = c->m; p.Vs = c->Vs; p.S = c->S; p.B = c->B; p.C = c->C;
     p.RS = k + 1; p.MR = c->S * (k + 1);
-    p.NC = stream_chunks(c);
-    p.Smax = c->Smax; p.Tmax = c->Tmax; p.Kp = std::max(c->d, c->m) + 8;
+    const AttnCut cut = attn_cut(c, k + 1);
+    p.NC = cut.NC; p.NRG = cut.NRG; p.RPJ = cut.RPJ;
+    p.Smax = c->Smax; p.Tmax = c->Tmax; p.Kpd = c->d + 8; p.Kpm = c->m + 8;
     p.eps = c->cfg.rms_eps;
-    p.act_bytes = (int32_t)std::max((size_t)p.MR * p.Kp * 4, (size_t)kCW * 8 * 6 * kPS * 4);
+    p.act_bytes = (int32_t)std::max((size_t)p.MR * p.Kpm * 4, (size_t)kCW * 6 * kPS * 4);
     const size_t lds = stream_lds_bytes(c, p.MR);
-    const void* kern = c->d == 1280 ? reinterpret_cast<const void*>(verify_stream_kernel<10, 27, 5, 14, 6>)
-                                    : reinterpret_cast<const void*>(verify_stream_kernel<6, 16, 3, 8, 6>);
+    const void* kern = c->d == 1280 ? reinterpret_cast<const void*>(verify_stream_kernel<10, 27, 5, 6>)
+                                    : reinterpret_cast<const void*>(verify_stream_kernel<6, 16, 3, 6>);
     if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return -1;
     void* args[] = {&p};
     if (hipLaunchCooperativeKernel(kern, dim3(kNWG), dim3(kThreads), args, lds, c->stream) != hipSuccess) return -1;
-    P->epoch += 5u * (unsigned)c->L + (unsigned)P->kind[K_LM].rounds;
+    P->epoch += 1u + 5u * (unsigned)c->L;  // prologue + five stages per layer; nothing follows the output projection
     P->launches += 1;
     return 0;
 }

@@ -80,5 +80,7 @@ def test_streaming_plan_covers_every_weight_tile_once(H):
         assert info["layer_tiles"] == per_layer
         assert info["total_tiles"] == s.n_layers * per_layer + s.v_s * s.d_model // 512 + 3 * s.d_model ** 2 // 512
         mean = per_layer / info["workgroups"]
-        assert info["min_wg_tiles"] <= mean <= info["max_wg_tiles"] <= 1.35 * mean
+        # the owners of the residual strips stream the Wo and W2 strips on top of their share of the
+        # other two stages (what bounds a stage is its own busiest workgroup, not the layer total)
+        assert info["min_wg_tiles"] <= mean <= info["max_wg_tiles"] <= 2.6 * mean
     assert H.plan_info(H.HawkConfig.from_shape(synth.CONFIGS[0]))["supported"] == 0   # fp32: generic kernels
