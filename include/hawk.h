@@ -200,9 +200,11 @@ int hawk_last_path(const hawk_ctx* ctx);
 
 /* Diagnostic: switches per-stage time stamps of the streaming kernel on or off (they cost
  * a few stores per stage) and, if out != NULL, copies the stamps of the last launch to
- * out (host, n_words x uint64, at most 2*4096*8): [workgroup 0 | workgroup 128][stage][8],
- * 100 MHz ticks at: stage entry, barrier crossed, input staged, workgroup sync 1, workgroup
- * sync 2 (MFMAs done), results stored, arrival posted. */
+ * out (host, n_words x uint64, at most 4*4096*8): [trace][stage][8] with trace 0, 1 = first
+ * IO wave of workgroups 0 and 128 - 100 MHz ticks at: stage entry, barrier crossed, input
+ * staged, workgroup sync 1, workgroup sync 2 (MFMAs done), results stored, arrival posted -
+ * and trace 2, 3 = first compute wave of the same workgroups: stage entry, weight loads
+ * issued, workgroup sync 1, weights landed, MFMAs done, partial sums handed over. */
 int hawk_phase_trace(hawk_ctx* ctx, int enable, uint64_t* out, size_t n_words);
 
 #ifdef __cplusplus

@@ -152,6 +152,12 @@ void enqueue_draft(hawk_ctx* c, int k, const UniformSrc& us, const DraftMode& dm
     launch_plan(c, k);
     for (int i = 1; i <= k; ++i) {
         const size_t g = (i & 1) ? c->off.g1 : c->off.g0;
+        if (stream_draft_ok(c)) {  // one persistent kernel: W_d, final norm, output projection
+            const size_t prev = (i == 1) ? c->off.hprev : (((i - 1) & 1) ? c->off.g1 : c->off.g0);
+            if (launch_draft_stream(c, i, prev, g) != 0) c->launch_failed = 1;
+            launch_draft_sample(c, i, k, us, dm);
+            continue;
+        }
         launch_draft_input(c, i);
         launch_gemm(c, c->off.din, 3 * c->d, c->w.W_d, c->d, 3 * c->d, g, c->d, c->S, false, false);
         launch_rmsnorm(c, g, c->d, c->w.g_f, c->off.ga, c->S);
@@ -316,7 +322,7 @@ int hawk_phase_trace(hawk_ctx* c, int enable, uint64_t* out, size_t n_words) {
     if (!c) return HAWK_EINVAL;
     c->stream_dbg = enable ? 1 : 0;
     if (out && c->plan) {
-        if (n_words > 2 * 4096 * 8) n_words = 2 * 4096 * 8;
+        if (n_words > 4 * 4096 * 8) n_words = 4 * 4096 * 8;
         return download(c, out, c->soff.dbg, n_words * 8);
     }
     return HAWK_OK;

@@ -479,9 +479,10 @@ __device__ __forceinline__ void load_row(const float* lc, const float* lu, float
     }
 }
 
-// Statistics of the warp of the row held in z (see warp_stats) and, in w, the weight of every entry.
+// Which entries of the row held in z the warp keeps (see warp_stats): arg-max, top-k threshold
+// and tie cut, maximum.  The weights themselves come from dense_weights or from a CompactList.
 template <int E>
-__device__ WarpStat warp_row(const float (&z)[E], int n, int top_k, int greedy, FastShared& fs, double (&w)[E]) {
+__device__ WarpStat warp_select(const float (&z)[E], int n, int top_k, int greedy, FastShared& fs) {
     Shared& sh = fs.sh;
     const int base = threadIdx.x * E, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     WarpStat st;
@@ -496,23 +497,36 @@ __device__ WarpStat warp_row(const float (&z)[E], int n, int top_k, int greedy, 
         for (int e = E - 1; e >= 0; --e)
             if (base + e < n && z[e] == gmax) idx = base + e;
         st.onehot = block_min_i(idx, sh);
-#pragma unroll
-        for (int e = 0; e < E; ++e) w[e] = (base + e == st.onehot) ? 1.0 : 0.0;
         return st;
     }
     const int K = min(top_k, n);
     if (K < n) {
+        // The keys of a row share their high bits (sign, most of the exponent): radix digits are
+        // taken from (key - smallest key) shifted up to the top bit, so that the first digit
+        // already spreads the row over the 256 bins (few LDS atomics collide, fewer passes).
+        int lo_b = 0x7FFFFFFF, hi_b = (int)0x80000000;
+#pragma unroll
+        for (int e = 0; e < E; ++e)
+            if (base + e < n) {
+                const int kb = (int)(fkey(z[e]) ^ 0x80000000u);  // signed order = key order
+                lo_b = min(lo_b, kb);
+                hi_b = max(hi_b, kb);
+            }
+        const unsigned kmin = (unsigned)block_min_i(lo_b, sh) ^ 0x80000000u;
+        const unsigned kmax = (unsigned)block_max_i(hi_b, sh) ^ 0x80000000u;
+        const int sh0 = kmax > kmin ? __clz((int)(kmax - kmin)) : 31;
+        unsigned rel[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) rel[e] = (fkey(z[e]) - kmin) << sh0;
         unsigned prefix = 0u, mask = 0u, remaining = (unsigned)K, count_eq = 0u;
-        for (int shift = 24; shift >= 0; shift -= 8) {
+        for (int shift = 24; shift >= 0 && shift + 8 > sh0; shift -= 8) {  // digits below bit sh0 are all zero
             __syncthreads();
 #pragma unroll
             for (int q = 0; q < 4; ++q) fs.hist[wave][lane * 4 + q] = 0u;
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
-            for (int e = 0; e < E; ++e) {
-                const unsigned key = fkey(z[e]);
-                if ((key & mask) == prefix) atomicAdd(&fs.hist[wave][(key >> shift) & 255u], 1u);
-            }
+            for (int e = 0; e < E; ++e)
+                if (base + e < n && (rel[e] & mask) == prefix) atomicAdd(&fs.hist[wave][(rel[e] >> shift) & 255u], 1u);
             __syncthreads();
             if (threadIdx.x < 256) {
                 unsigned t = 0u;
@@ -553,20 +567,29 @@ __device__ WarpStat warp_row(const float (&z)[E], int n, int top_k, int greedy, 
             remaining = sh.b_remaining;
             count_eq = sh.b_count_eq;
             mask |= 255u << shift;
+            if (count_eq == 1u && shift > 0) {  // a single entry is left under the prefix: it is the K-th
+                __syncthreads();
+#pragma unroll
+                for (int e = 0; e < E; ++e)
+                    if (base + e < n && (rel[e] & mask) == prefix) sh.b_prefix = rel[e];
+                __syncthreads();
+                prefix = sh.b_prefix;
+                break;
+            }
         }
-        st.tau = prefix;
+        st.tau = (prefix >> sh0) + kmin;
         st.tie_cut = 0x7FFFFFFF;
         if (remaining < count_eq) {  // keep only the first `remaining` entries equal to tau
             int c = 0;
 #pragma unroll
-            for (int e = 0; e < E; ++e) c += fkey(z[e]) == prefix;
+            for (int e = 0; e < E; ++e) c += (base + e < n && rel[e] == prefix) ? 1 : 0;
             const int before = block_excl_scan_i(c, sh);
             __syncthreads();
             if (before < (int)remaining && before + c >= (int)remaining) {
                 int seen = before;
 #pragma unroll
                 for (int e = 0; e < E; ++e)
-                    if (fkey(z[e]) == prefix && ++seen == (int)remaining) sh.b_int = base + e;
+                    if (base + e < n && rel[e] == prefix && ++seen == (int)remaining) sh.b_int = base + e;
             }
             __syncthreads();
             st.tie_cut = sh.b_int;
@@ -576,6 +599,19 @@ __device__ WarpStat warp_row(const float (&z)[E], int n, int top_k, int greedy, 
 #pragma unroll
     for (int e = 0; e < E; ++e) zm = fmaxf(zm, z[e]);
     st.zmax = block_max_f(zm, sh);
+    return st;
+}
+
+// Weight of every entry of the row in registers; sets st.total.
+template <int E>
+__device__ void dense_weights(WarpStat& st, const float (&z)[E], double (&w)[E], Shared& sh) {
+    const int base = threadIdx.x * E;
+    if (st.onehot >= 0) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) w[e] = (base + e == st.onehot) ? 1.0 : 0.0;
+        st.total = 1.0;
+        return;
+    }
     double s = 0.0;
 #pragma unroll
     for (int e = 0; e < E; ++e) {
@@ -583,6 +619,88 @@ __device__ WarpStat warp_row(const float (&z)[E], int n, int top_k, int greedy, 
         s += w[e];
     }
     st.total = block_sum_d(s, sh);
+}
+
+// When top-k keeps at most kCap entries, they are gathered - in index order - into a list in
+// LDS and the fp64 exponentials are evaluated for those only (the other 15 of 16 entries of a
+// 16384-entry row would cost a software exp each for a weight of zero).
+constexpr int kCap = 2048;
+struct CompactList {
+    int idx[kCap];
+    float z[kCap];
+    double w[kCap];
+};
+
+__device__ __forceinline__ bool use_list(int top_k, int n, int greedy) { return !greedy && top_k < n && top_k <= kCap; }
+
+template <int E>
+__device__ int compact_row(const WarpStat& st, const float (&z)[E], int n, CompactList& L, Shared& sh) {
+    const int base = threadIdx.x * E;
+    int c = 0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) c += (base + e < n && kept(st, z[e], base + e)) ? 1 : 0;
+    int at = block_excl_scan_i(c, sh);
+    const int total = block_max_i(at + c, sh);
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+        if (base + e < n && kept(st, z[e], base + e)) {
+            if (at < kCap) { L.idx[at] = base + e; L.z[at] = z[e]; }
+            ++at;
+        }
+    __syncthreads();
+    return min(total, kCap);
+}
+
+// w[i] = exp(z[i] - zmax) over the list (thread t owns entries 2t, 2t+1); returns the sum.
+__device__ double list_weights(CompactList& L, int Kc, float zmax, Shared& sh) {
+    const int i0 = threadIdx.x * 2;
+    double s = 0.0;
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+        if (i0 + q < Kc) {
+            const double w = exp((double)L.z[i0 + q] - (double)zmax);
+            L.w[i0 + q] = w;
+            s += w;
+        }
+    return block_sum_d(s, sh);
+}
+
+// Inverse-CDF draw over list weights w (ascending index order); returns the token index.
+__device__ int list_inv_cdf(const double* w, const int* idx, int Kc, double total, float u, Shared& sh) {
+    const int i0 = threadIdx.x * 2;
+    __syncthreads();  // the weights were written by other threads
+    const double w0 = i0 < Kc ? w[i0] : 0.0, w1 = i0 + 1 < Kc ? w[i0 + 1] : 0.0;
+    double c = block_excl_scan_d(w0 + w1, sh);
+    const double target = (double)u * total;
+    int cand = 0x7FFFFFFF, last = -1;
+    if (w0 > 0.0) { c += w0; last = i0; if (c > target) cand = i0; }
+    if (w1 > 0.0) { c += w1; last = i0 + 1; if (c > target && cand == 0x7FFFFFFF) cand = i0 + 1; }
+    cand = block_min_i(cand, sh);
+    if (cand != 0x7FFFFFFF) return idx[cand];
+    last = block_max_i(last, sh);
+    return idx[max(last, 0)];
+}
+
+template <int E>
+__device__ int inv_cdf_row(const double (&w)[E], double total, float u, Shared& sh);
+
+// One row, start to finish: the warp's statistics (with total) and, if u != null, a draw.
+template <int E>
+__device__ WarpStat warp_and_draw(const float (&z)[E], int n, int top_k, int greedy, FastShared& fs, CompactList& L,
+                                  const float* u, int* drawn) {
+    WarpStat st = warp_select<E>(z, n, top_k, greedy, fs);
+    if (st.onehot >= 0) {
+        st.total = 1.0;
+        if (u) *drawn = st.onehot;
+    } else if (use_list(top_k, n, greedy)) {
+        const int Kc = compact_row<E>(st, z, n, L, fs.sh);
+        st.total = list_weights(L, Kc, st.zmax, fs.sh);
+        if (u) *drawn = list_inv_cdf(L.w, L.idx, Kc, st.total, *u, fs.sh);
+    } else {
+        double w[E];
+        dense_weights<E>(st, z, w, fs.sh);
+        if (u) *drawn = inv_cdf_row<E>(w, st.total, *u, fs.sh);
+    }
     return st;
 }
 
@@ -613,14 +731,14 @@ template <int E>
 __global__ __launch_bounds__(NT) void first_token_fast(const float* logit_s, float* logit_b, int32_t* grid, int32_t* n,
                                                        SampParams P, UniformSrc us) {
     __shared__ FastShared fs;
+    __shared__ CompactList L;
     const int b = blockIdx.x;
     float z[E];
-    double w[E];
     load_row<E>(logit_s + (size_t)b * P.Vs, P.use_cfg ? logit_s + (size_t)(P.B + b) * P.Vs : nullptr, P.cfg_scale,
                 P.inv_t, logit_b + (size_t)b * P.kstride * P.Vs, P.Vs, z);
-    const WarpStat st = warp_row<E>(z, P.Vs, P.top_k, P.greedy, fs, w);
     const float u = pick_uniform(us, us.fin, b, b, kSlotFinal);
-    const int idx = inv_cdf_row<E>(w, st.total, u, fs.sh);
+    int idx = 0;
+    (void)warp_and_draw<E>(z, P.Vs, P.top_k, P.greedy, fs, L, &u, &idx);
     if (threadIdx.x == 0) {
         grid[(size_t)b * P.N] = P.samp_lo + idx;
         n[b] = 1;
@@ -632,20 +750,21 @@ __global__ __launch_bounds__(NT) void draft_sample_fast(const float* dlogit_s, f
                                                         const int32_t* k_eff, int32_t* draft, WarpStat* qstat, int i,
                                                         int k, SampParams P, UniformSrc us, ForcedSrc fsrc) {
     __shared__ FastShared fs;
+    __shared__ CompactList L;
     const int b = blockIdx.x;
     if (i > k_eff[b]) return;
     float z[E];
-    double w[E];
     load_row<E>(dlogit_s + (size_t)b * P.Vs, P.use_cfg ? dlogit_s + (size_t)(P.B + b) * P.Vs : nullptr, P.cfg_scale,
                 P.inv_t, dlogit_b + ((size_t)b * P.kstride + (i - 1)) * P.Vs, P.Vs, z);
-    WarpStat st = warp_row<E>(z, P.Vs, P.top_k, P.greedy, fs, w);
+    const float u = fsrc.table ? 0.f : pick_uniform(us, us.draft, b * k + (i - 1), b, kSlotDraft + (i - 1));
+    int drawn = 0;
+    WarpStat st = warp_and_draw<E>(z, P.Vs, P.top_k, P.greedy, fs, L, fsrc.table ? nullptr : &u, &drawn);
     int tok;
     if (fsrc.table) {
         tok = fsrc.table[(size_t)b * fsrc.stride + (fsrc.relative ? n[b] : 0) + (i - 1)];
         if (fsrc.point_mass) { st.onehot = tok - P.samp_lo; st.total = 1.0; }
     } else {
-        const float u = pick_uniform(us, us.draft, b * k + (i - 1), b, kSlotDraft + (i - 1));
-        tok = P.samp_lo + inv_cdf_row<E>(w, st.total, u, fs.sh);
+        tok = P.samp_lo + drawn;
     }
     if (threadIdx.x == 0) {
         draft[b * P.kstride + (i - 1)] = tok;
@@ -657,14 +776,14 @@ template <int E>
 __global__ __launch_bounds__(NT) void verify_stats_fast(const float* logit_s, float* logit_b, const int32_t* k_eff,
                                                         WarpStat* pstat, int k, SampParams P) {
     __shared__ FastShared fs;
+    __shared__ CompactList L;
     const int r = blockIdx.x, b = blockIdx.y;
     if (r > k_eff[b]) return;
     float z[E];
-    double w[E];
     load_row<E>(logit_s + ((size_t)b * (k + 1) + r) * P.Vs,
                 P.use_cfg ? logit_s + ((size_t)(P.B + b) * (k + 1) + r) * P.Vs : nullptr, P.cfg_scale, P.inv_t,
                 logit_b + ((size_t)b * P.kstride + r) * P.Vs, P.Vs, z);
-    const WarpStat st = warp_row<E>(z, P.Vs, P.top_k, P.greedy, fs, w);
+    const WarpStat st = warp_and_draw<E>(z, P.Vs, P.top_k, P.greedy, fs, L, nullptr, nullptr);
     if (threadIdx.x == 0) pstat[b * P.kstride + r] = st;
 }
 
@@ -675,6 +794,8 @@ __global__ __launch_bounds__(NT) void accept_commit_fast(
     int32_t* out_na, int32_t* out_tok, unsigned long long* counters, int k, int n_seq_streams, SampParams P,
     UniformSrc us) {
     __shared__ Shared sh;
+    __shared__ CompactList L;
+    __shared__ double res_list[kCap];
     const int b = blockIdx.x;
     const int ke = k_eff[b];
     if (threadIdx.x <= k) out_tok[b * (k + 1) + threadIdx.x] = -1;
@@ -695,10 +816,35 @@ __global__ __launch_bounds__(NT) void accept_commit_fast(
     const float* prow = logit_b + ((size_t)b * P.kstride + a) * P.Vs;
     const WarpStat ps = pstat[b * P.kstride + a];
     const int base = threadIdx.x * E;
+    int y;
+    if (ps.onehot < 0 && use_list(P.top_k, P.Vs, P.greedy)) {
+        // the kept entries of p (a superset of the residual's support) as a list; q only where p > 0
+        float z[E];
+        load_row<E>(prow, nullptr, 0.f, P.inv_t, nullptr, P.Vs, z);
+        const int Kc = compact_row<E>(ps, z, P.Vs, L, sh);
+        (void)list_weights(L, Kc, ps.zmax, sh);
+        if (a < ke) {
+            const float* qrow = dlogit_b + ((size_t)b * P.kstride + a) * P.Vs;
+            const WarpStat qs = qstat[b * P.kstride + a];
+            const int i0 = threadIdx.x * 2;
+            double s = 0.0;
+#pragma unroll
+            for (int q2 = 0; q2 < 2; ++q2)
+                if (i0 + q2 < Kc) {
+                    const double q = weight_of(qs, qrow, P.inv_t, L.idx[i0 + q2]) / qs.total;
+                    const double r = L.w[i0 + q2] / ps.total - q;
+                    res_list[i0 + q2] = r > 0.0 ? r : 0.0;
+                    s += res_list[i0 + q2];
+                }
+            const double R = block_sum_d(s, sh);
+            y = (R > 0.0) ? list_inv_cdf(res_list, L.idx, Kc, R, uf, sh) : list_inv_cdf(L.w, L.idx, Kc, ps.total, uf, sh);
+        } else {
+            y = list_inv_cdf(L.w, L.idx, Kc, ps.total, uf, sh);
+        }
+    } else {
     double w[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) w[e] = base + e < P.Vs ? weight_of(ps, prow, P.inv_t, base + e) : 0.0;
-    int y;
     if (a < ke) {
         const float* qrow = dlogit_b + ((size_t)b * P.kstride + a) * P.Vs;
         const WarpStat qs = qstat[b * P.kstride + a];
@@ -714,6 +860,7 @@ __global__ __launch_bounds__(NT) void accept_commit_fast(
         y = (R > 0.0) ? inv_cdf_row<E>(res, R, uf, sh) : inv_cdf_row<E>(w, ps.total, uf, sh);
     } else {
         y = inv_cdf_row<E>(w, ps.total, uf, sh);
+    }
     }
     const int nb = n[b];
     for (int s2 = b; s2 < n_seq_streams; s2 += P.B) {

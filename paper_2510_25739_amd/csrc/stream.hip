@@ -81,6 +81,14 @@ struct SP {
     unsigned epoch0;
     int32_t L, d, H, m, Vs, S, B, C, RS, MR, NC, NRG, RPJ, Smax, Tmax, Kpd, Kpm, act_bytes;
     float eps;
+    // draft head kernel only
+    const float* prev;      // [S][d]: hidden state the head continues from
+    float* gout;            // [S][d]: the head's output (next micro-step's prev)
+    float* dpart;           // [3][16][d]: partial products of the three column blocks of W_d
+    const int32_t* grid;
+    const int32_t* draft;
+    u64 E_off;
+    int32_t step_i, N, IW, kstride;
 };
 
 // ------------------------------------------------------------------------- device helpers
@@ -171,6 +179,12 @@ __device__ __forceinline__ void stamp(const SP& p, unsigned phase, int what) {
         p.dbg[((size_t)(blockIdx.x >> 7) * 4096 + phase) * 8 + what] = __builtin_amdgcn_s_memrealtime();
 }
 
+// Same for the first compute wave (second half of the trace buffer).
+__device__ __forceinline__ void stamp_c(const SP& p, unsigned phase, int what) {
+    if (p.dbg && threadIdx.x == 0 && (blockIdx.x & 127) == 0)
+        p.dbg[((size_t)(2 + (blockIdx.x >> 7)) * 4096 + phase) * 8 + what] = __builtin_amdgcn_s_memrealtime();
+}
+
 struct Job {
     u64 tile0;       // first tile of wave 0 in wpack
     int nstrips;     // 0: no job
@@ -189,17 +203,23 @@ __device__ __forceinline__ Job load_job(const SP& p, int kind, int round, int la
     return j;
 }
 
-// Issues the 16-byte loads of one wave's tiles of a job (nothing is waited for here).
-__device__ __forceinline__ void issue_tiles(const SP& p, const Job& j, int tps, int wave, int lane, v4u (&w)[kTMax]) {
-    const int nt = j.nstrips * tps;
+// Issues the 16-byte loads of one wave's tiles of a job (nothing is waited for here).  Every
+// slot is redefined - zero for a strip the job does not have - so no value outlives its job
+// and the MFMA loop needs no branches.
+template <int TPS, int NS>
+__device__ __forceinline__ void issue_tiles(const SP& p, const Job& j, int wave, int lane, v4u (&w)[NS * TPS]) {
+    const int nt = j.nstrips * TPS;
     const v4u* src = reinterpret_cast<const v4u*>(p.wpack + (j.tile0 + (u64)wave * nt) * 64 + lane);
 #pragma unroll
-    for (int t = 0; t < kTMax; ++t)
-        if (t < nt) {
-            w[t] = __builtin_nontemporal_load(src + (size_t)t * 64);
+    for (int si = 0; si < NS; ++si) {
+        if (si < j.nstrips) {
+#pragma unroll
+            for (int t = 0; t < TPS; ++t) w[si * TPS + t] = __builtin_nontemporal_load(src + (size_t)(si * TPS + t) * 64);
         } else {
-            w[t] = (v4u){0u, 0u, 0u, 0u};  // every slot is redefined: no value outlives its job
+#pragma unroll
+            for (int t = 0; t < TPS; ++t) w[si * TPS + t] = (v4u){0u, 0u, 0u, 0u};
         }
+    }
 }
 
 // Copies the split planes of a stage input ([MR][Kp] bf16 each, contiguous) into LDS, BATCH
@@ -227,19 +247,22 @@ __device__ __forceinline__ void stage_copy(const uint16_t* hi, const uint16_t* l
     }
 }
 
-// 1/rms of every row from the per-strip sums of squares ss[NSS*4][16] (one wave; NSS loads per lane).
+// 1/rms of every row from the per-strip sums of squares ss[NSS*4][16]: one wave, NSS loads per
+// lane (issued before the copy of the stage input, reduced after it).
 template <int NSS>
-__device__ __forceinline__ void row_scales(const float* ss, int K, float eps, int lane, float* rn) {
+__device__ __forceinline__ void row_scales_load(const float* ss, int lane, float (&v)[NSS]) {
     const int c = lane & 15, part = lane >> 4;
-    float v[NSS];
 #pragma unroll
     for (int i = 0; i < NSS; ++i) v[i] = ss[(size_t)(part + 4 * i) * 16 + c];
+}
+template <int NSS>
+__device__ __forceinline__ void row_scales_reduce(const float (&v)[NSS], int K, float eps, int lane, float* rn) {
     float a = 0.f;
 #pragma unroll
     for (int i = 0; i < NSS; ++i) a += v[i];
     a += __shfl_xor(a, 16, 64);
     a += __shfl_xor(a, 32, 64);
-    if (lane < 16) rn[c] = 1.0f / sqrtf(a / (float)K + eps);
+    if (lane < 16) rn[lane] = 1.0f / sqrtf(a / (float)K + eps);
 }
 
 // Stage the attention output rows for the Wo stage when a head was split into NC chunks:
@@ -289,39 +312,40 @@ __device__ __forceinline__ void stage_attention(const SP& p, int layer, int io, 
 }
 
 // One wave's MFMAs of a job: strips x its K quarter, activations from LDS.  The B operand of
-// a k-tile is shared by every strip of the job, and is fetched two k-tiles ahead.
-template <int TPS>
-__device__ __forceinline__ void mfma_job(const v4u (&w)[kTMax], int nstrips, int wave, int lane, int MR,
-                                         const uint16_t* act_hi, const uint16_t* act_lo, int Kp, f32x4 (&acc)[kMaxStrips]) {
-    constexpr int NS = kTMax / TPS < kMaxStrips ? kTMax / TPS : kMaxStrips;  // strips a job of this kind can have
+// a k-tile is shared by every strip of the job, and is fetched two k-tiles ahead.  Columns
+// >= MR of the B operand repeat row 0 (their results are never stored); absent strips have
+// zero weights.
+template <int TPS, int NS>
+__device__ __forceinline__ void mfma_job(const v4u (&w)[NS * TPS], int wave, int lane, int MR, const uint16_t* act_hi,
+                                         const uint16_t* act_lo, int Kp, f32x4 (&acc)[NS]) {
     const int col = lane & 15, kg = lane >> 4;
-    const bool live = col < MR;
-    const uint16_t* bh_base = act_hi + (size_t)(live ? col : 0) * Kp + kg * 8 + (size_t)wave * TPS * 32;
-    const uint16_t* bl_base = act_lo + (size_t)(live ? col : 0) * Kp + kg * 8 + (size_t)wave * TPS * 32;
-    const v4u zero = (v4u){0u, 0u, 0u, 0u};
+    const size_t at = (size_t)(col < MR ? col : 0) * Kp + kg * 8 + (size_t)wave * TPS * 32;
+    const uint16_t* bh_base = act_hi + at;
+    const uint16_t* bl_base = act_lo + at;
     v4u bh[3], bl[3];
     f32x4 acl[NS];
 #pragma unroll
-    for (int si = 0; si < NS; ++si) acl[si] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int si = 0; si < NS; ++si) {
+        acc[si] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        acl[si] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
 #pragma unroll
     for (int j = 0; j < 2 && j < TPS; ++j) {
-        bh[j] = live ? *reinterpret_cast<const v4u*>(bh_base + j * 32) : zero;
-        bl[j] = live ? *reinterpret_cast<const v4u*>(bl_base + j * 32) : zero;
+        bh[j] = *reinterpret_cast<const v4u*>(bh_base + j * 32);
+        bl[j] = *reinterpret_cast<const v4u*>(bl_base + j * 32);
     }
 #pragma unroll
     for (int j = 0; j < TPS; ++j) {
         if (j + 2 < TPS) {
-            bh[(j + 2) % 3] = live ? *reinterpret_cast<const v4u*>(bh_base + (j + 2) * 32) : zero;
-            bl[(j + 2) % 3] = live ? *reinterpret_cast<const v4u*>(bl_base + (j + 2) * 32) : zero;
+            bh[(j + 2) % 3] = *reinterpret_cast<const v4u*>(bh_base + (j + 2) * 32);
+            bl[(j + 2) % 3] = *reinterpret_cast<const v4u*>(bl_base + (j + 2) * 32);
         }
         const bf16x8 h = __builtin_bit_cast(bf16x8, bh[j % 3]), l = __builtin_bit_cast(bf16x8, bl[j % 3]);
 #pragma unroll
-        for (int si = 0; si < NS; ++si) {
-            if (si < nstrips) {  // hi and lo products accumulate in separate chains (no back-to-back dependency)
-                const bf16x8 a = __builtin_bit_cast(bf16x8, w[si * TPS + j]);
-                acc[si] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, h, acc[si], 0, 0, 0);
-                acl[si] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, l, acl[si], 0, 0, 0);
-            }
+        for (int si = 0; si < NS; ++si) {  // hi and lo products accumulate in separate chains
+            const bf16x8 a = __builtin_bit_cast(bf16x8, w[si * TPS + j]);
+            acc[si] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, h, acc[si], 0, 0, 0);
+            acl[si] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, l, acl[si], 0, 0, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -500,10 +524,84 @@ __device__ __forceinline__ void prologue_phase(const SP& p, const Lds& s, Barrie
     }
 }
 
+// ---- draft head (Method, spatial draft head: g_i = W_d [g_{i-1} | E[left] | E[up]], then the
+// target's final norm and output projection).  W_d is streamed as three [d, d] column blocks.
+
+// Stage the input of column block `blk` for every sequence: the previous hidden state (fp32,
+// split here), or the embedding row of the left / upper neighbour (bf16: its own hi part).
+template <int KREG>
+__device__ __forceinline__ void stage_draft_input(const SP& p, int blk, int io, int lane, uint16_t* act_hi, uint16_t* act_lo) {
+    const int d = p.d, i = p.step_i;
+    const uint16_t* E = p.blob + p.E_off / 2;
+    for (int c = io; c < p.MR; c += kNIO) {
+        const int b = c % p.B;
+        const bool valid = i <= p.k_eff[b];
+        const int n = p.n[b], t = n - 1 + i;
+        int tok = -1;
+        if (valid && blk == 1) tok = (i == 1) ? p.grid[(size_t)b * p.N + n - 1] : p.draft[b * p.kstride + i - 2];
+        if (valid && blk == 2 && t >= p.IW) tok = p.grid[(size_t)b * p.N + t - p.IW];
+#pragma unroll
+        for (int q = 0; q < KREG; ++q) {
+            const int j = (q * 64 + lane) * 4;
+            if (j < d) {
+                uint16_t* hi = act_hi + (size_t)c * p.Kpd + j;
+                uint16_t* lo = act_lo + (size_t)c * p.Kpd + j;
+                if (blk == 0) {
+                    const float4 v = valid ? *reinterpret_cast<const float4*>(p.prev + (size_t)c * d + j)
+                                           : make_float4(0.f, 0.f, 0.f, 0.f);
+                    put_split(v, hi, lo);
+                } else {
+                    *reinterpret_cast<uint2*>(hi) = tok >= 0 ? *reinterpret_cast<const uint2*>(E + (size_t)tok * d + j)
+                                                            : make_uint2(0u, 0u);
+                    *reinterpret_cast<uint2*>(lo) = make_uint2(0u, 0u);
+                }
+            }
+        }
+    }
+}
+
+// Stage the head's output for the output projection: g = sum of the three block partials,
+// times the final norm's gain, split; 1/rms per row; workgroup 0 also keeps g itself.
+template <int KREG>
+__device__ __forceinline__ void stage_head_output(const SP& p, int io, int lane, const Lds& s) {
+    const int d = p.d;
+    const uint16_t* gain = p.blob + p.gf_off / 2;
+    for (int c = io; c < p.MR; c += kNIO) {
+        float4 g[KREG];
+        float ss = 0.f;
+#pragma unroll
+        for (int q = 0; q < KREG; ++q) {
+            const int j = (q * 64 + lane) * 4;
+            g[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (j < d) {
+                const float4 a = *reinterpret_cast<const float4*>(p.dpart + ((size_t)(0 * 16 + c)) * d + j);
+                const float4 b = *reinterpret_cast<const float4*>(p.dpart + ((size_t)(1 * 16 + c)) * d + j);
+                const float4 e = *reinterpret_cast<const float4*>(p.dpart + ((size_t)(2 * 16 + c)) * d + j);
+                g[q] = make_float4(a.x + b.x + e.x, a.y + b.y + e.y, a.z + b.z + e.z, a.w + b.w + e.w);
+                ss += g[q].x * g[q].x + g[q].y * g[q].y + g[q].z * g[q].z + g[q].w * g[q].w;
+            }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+        if (lane == 0) s.rn[c] = 1.0f / sqrtf(ss / (float)d + p.eps);
+#pragma unroll
+        for (int q = 0; q < KREG; ++q) {
+            const int j = (q * 64 + lane) * 4;
+            if (j < d) {
+                const uint2 gn = *reinterpret_cast<const uint2*>(gain + j);
+                const float4 y = make_float4(g[q].x * bf16_f32(gn.x & 0xFFFFu), g[q].y * bf16_f32(gn.x >> 16),
+                                             g[q].z * bf16_f32(gn.y & 0xFFFFu), g[q].w * bf16_f32(gn.y >> 16));
+                put_split(y, s.act_hi + (size_t)c * p.Kpd + j, s.act_lo + (size_t)c * p.Kpd + j);
+                if (blockIdx.x == 0) *reinterpret_cast<float4*>(p.gout + (size_t)c * d + j) = g[q];
+            }
+        }
+    }
+}
+
 // KIND: which matrix; TPS: k-tiles per compute wave and strip; NSS: per-strip sums of squares
 // per lane of the row-scale reduction (0: the stage input is not normalised); BATCH: chunks in
 // flight per IO thread while copying the stage input.
-template <int KIND, int TPS, int NSS, int BATCH, int KREG>
+template <int KIND, int TPS, int NSS, int BATCH, int KREG, int STAGE = 0>
 __device__ __forceinline__ void gemv_phase(const SP& p, const Lds& s, Barrier& bar, int layer, int round,
                                            const uint16_t* src_hi, const uint16_t* src_lo, const float* ss, int K, int Kp,
                                            f32x4& resid) {
@@ -515,23 +613,32 @@ __device__ __forceinline__ void gemv_phase(const SP& p, const Lds& s, Barrier& b
     const bool fresh = !(KIND == K_LM && round > 0);
     // Nothing in this block depends on the previous stage, so it is requested before the barrier
     // is crossed: the weights (compute waves), rotary factors and gains (IO waves).
-    v4u w[kTMax];
+    constexpr int NS = kTMax / TPS < kMaxStrips ? kTMax / TPS : kMaxStrips;  // strips a job of this kind can have
+    v4u w[NS * TPS];
     EpiPre pre;
     if (!is_io) {
-        issue_tiles(p, job, TPS, wave, lane, w);
+        stamp_c(p, ph, 0);
+        issue_tiles<TPS, NS>(p, job, wave, lane, w);
+        stamp_c(p, ph, 1);
     } else {
         stamp(p, ph, 0);
         if (wave - kCW < job.nstrips) epilogue_prefetch<KIND>(p, layer, job.strip[wave - kCW], lane, pre);
         if (fresh) {
             bar.wait();
             stamp(p, ph, 1);
+            float ssv[NSS > 0 ? NSS : 1];
             if constexpr (NSS > 0) {
-                if (wave == kCW + kNIO - 1) row_scales<NSS>(ss, K, p.eps, lane, s.rn);
+                if (wave == kCW + kNIO - 1) row_scales_load<NSS>(ss, lane, ssv);
             }
-            if (KIND == K_C && p.NC > 1) {
+            if constexpr (STAGE == 1) {
+                stage_head_output<KREG>(p, wave - kCW, lane, s);
+            } else if (KIND == K_C && p.NC > 1) {
                 if (job.nstrips) stage_attention<KREG>(p, layer, wave - kCW, lane, s.act_hi, s.act_lo);
             } else if (job.nstrips || KIND == K_LM) {
                 stage_copy<BATCH>(src_hi, src_lo, p.MR, Kp, s.act_hi, s.act_lo, threadIdx.x - kCW * 64);
+            }
+            if constexpr (NSS > 0) {
+                if (wave == kCW + kNIO - 1) row_scales_reduce<NSS>(ssv, K, p.eps, lane, s.rn);
             }
         }
         stamp(p, ph, 2);
@@ -539,13 +646,15 @@ __device__ __forceinline__ void gemv_phase(const SP& p, const Lds& s, Barrier& b
     __syncthreads();
     stamp(p, ph, 3);
     if (!is_io && job.nstrips) {
-        f32x4 acc[kMaxStrips];
+        stamp_c(p, ph, 2);
+        if (p.dbg) { __builtin_amdgcn_s_waitcnt(0); stamp_c(p, ph, 3); }
+        f32x4 acc[NS];
+        mfma_job<TPS, NS>(w, wave, lane, p.MR, s.act_hi, s.act_lo, Kp, acc);
+        stamp_c(p, ph, 4);
 #pragma unroll
-        for (int i = 0; i < kMaxStrips; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        mfma_job<TPS>(w, job.nstrips, wave, lane, p.MR, s.act_hi, s.act_lo, Kp, acc);
-#pragma unroll
-        for (int i = 0; i < kMaxStrips; ++i)
-            if (i < job.nstrips) *reinterpret_cast<f32x4*>(s.red + (((size_t)wave * kMaxStrips + i) * 64 + lane) * 4) = acc[i];
+        for (int i = 0; i < NS; ++i)
+            *reinterpret_cast<f32x4*>(s.red + (((size_t)wave * kMaxStrips + i) * 64 + lane) * 4) = acc[i];
+        stamp_c(p, ph, 5);
     }
     __syncthreads();
     stamp(p, ph, 4);
@@ -558,6 +667,12 @@ __device__ __forceinline__ void gemv_phase(const SP& p, const Lds& s, Barrier& b
                 v += *reinterpret_cast<const f32x4*>(s.red + (((size_t)cw * kMaxStrips + i) * 64 + lane) * 4);
             epilogue<KIND>(p, s, layer, job.strip[i], v, lane, pre, resid);
         }
+    }
+    // The results' stores enter the memory pipeline ahead of the next stage's weight loads (which
+    // the compute waves issue next): the acknowledgements this stage's arrival waits for do not
+    // queue behind a hundred KB of prefetch.
+    __syncthreads();
+    if (is_io) {
         if (KIND != K_LM) io_finish(p, s, bar, ph, wave, lane);  // nothing follows the output projection
     } else if (KIND != K_LM) {
         ++bar.id;
@@ -582,25 +697,28 @@ __device__ __forceinline__ float sum8(float v) {
     return v;
 }
 
-// qs: the job's scaled query rows [RPJ][64]; r0: absolute index of its first row; row_lo: first
-// absolute row that may see this position; ke: last valid row.
-template <int RPJ>
-__device__ __forceinline__ void attend(const float* qs, int r0, int dg, v4u kraw, v4u vraw, int row_lo, int ke,
-                                       AttnAcc (&A)[RPJ]) {
-    float kf[8], vf[8];
+__device__ __forceinline__ void halves8(v4u raw, float (&f)[8]) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        kf[2 * e] = (float)__builtin_bit_cast(_Float16, (unsigned short)(kraw[e] & 0xFFFFu));
-        kf[2 * e + 1] = (float)__builtin_bit_cast(_Float16, (unsigned short)(kraw[e] >> 16));
-        vf[2 * e] = (float)__builtin_bit_cast(_Float16, (unsigned short)(vraw[e] & 0xFFFFu));
-        vf[2 * e + 1] = (float)__builtin_bit_cast(_Float16, (unsigned short)(vraw[e] >> 16));
+        f[2 * e] = (float)__builtin_bit_cast(_Float16, (unsigned short)(raw[e] & 0xFFFFu));
+        f[2 * e + 1] = (float)__builtin_bit_cast(_Float16, (unsigned short)(raw[e] >> 16));
     }
+}
+
+// One cache position per lane group.  q: the lane's 8 dims of the job's scaled query rows; r0:
+// absolute index of the first row; row_lo: first absolute row that may see the position; ke:
+// last valid row.
+template <int RPJ>
+__device__ __forceinline__ void attend(const float (&q)[RPJ][8], int r0, v4u kraw, v4u vraw, int row_lo, int ke,
+                                       AttnAcc (&A)[RPJ]) {
+    float kf[8], vf[8];
+    halves8(kraw, kf);
+    halves8(vraw, vf);
 #pragma unroll
     for (int r = 0; r < RPJ; ++r) {
-        const float4 qa = *reinterpret_cast<const float4*>(qs + r * 64 + dg * 8);
-        const float4 qb = *reinterpret_cast<const float4*>(qs + r * 64 + dg * 8 + 4);
-        float sc = qa.x * kf[0] + qa.y * kf[1] + qa.z * kf[2] + qa.w * kf[3] + qb.x * kf[4] + qb.y * kf[5] +
-                   qb.z * kf[6] + qb.w * kf[7];
+        float sc = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sc += q[r][e] * kf[e];
         sc = sum8(sc);
         if (r0 + r >= row_lo && r0 + r <= ke) {
             const float mn = fmaxf(A[r].mx, sc);
@@ -610,6 +728,55 @@ __device__ __forceinline__ void attend(const float* qs, int r0, int dg, v4u kraw
             for (int e = 0; e < 8; ++e) A[r].acc[e] = A[r].acc[e] * corr + pw * vf[e];
             A[r].mx = mn;
         }
+    }
+}
+
+// kNIT cache positions per lane group at once (positions pos0 + it * stride, those < o1 count):
+// all scores first, one running-maximum update per row, then the weighted values - independent
+// work for the VALU instead of one dependent chain per position.
+template <int RPJ>
+__device__ __forceinline__ void attend_round(const float (&q)[RPJ][8], int r0, const v4u (&kk)[kNIT], const v4u (&vv)[kNIT],
+                                             int pos0, int stride, int o1, int ke, AttnAcc (&A)[RPJ]) {
+    float sc[RPJ][kNIT];
+#pragma unroll
+    for (int it = 0; it < kNIT; ++it) {
+        float kf[8];
+        halves8(kk[it], kf);
+        const bool on = pos0 + it * stride < o1;
+#pragma unroll
+        for (int r = 0; r < RPJ; ++r) {
+            float d = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) d += q[r][e] * kf[e];
+            d = sum8(d);
+            sc[r][it] = (on && r0 + r <= ke) ? d : -1e30f;
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < RPJ; ++r) {
+        float mn = A[r].mx;
+#pragma unroll
+        for (int it = 0; it < kNIT; ++it) mn = fmaxf(mn, sc[r][it]);
+        const float corr = __expf(A[r].mx - mn);
+        float sum = 0.f;
+#pragma unroll
+        for (int it = 0; it < kNIT; ++it) {
+            sc[r][it] = sc[r][it] > -1e29f ? __expf(sc[r][it] - mn) : 0.f;
+            sum += sc[r][it];
+        }
+        A[r].den = A[r].den * corr + sum;
+        A[r].mx = mn;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) A[r].acc[e] *= corr;
+    }
+#pragma unroll
+    for (int it = 0; it < kNIT; ++it) {
+        float vf[8];
+        halves8(vv[it], vf);
+#pragma unroll
+        for (int r = 0; r < RPJ; ++r)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) A[r].acc[e] += sc[r][it] * vf[e];
     }
 }
 
@@ -670,12 +837,17 @@ __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& b
 #pragma unroll
             for (int e = 0; e < 8; ++e) A[r].acc[e] = 0.f;
         }
-        auto run = [&](const v4u (&kk)[kNIT], const v4u (&vv)[kNIT], int rnd) {
+        float q[RPJ][8];  // the lane's dims of the job's query rows
 #pragma unroll
-            for (int it = 0; it < kNIT; ++it) {
-                const int pos = o0 + (rnd * kNIT + it) * (kCW * 8) + wave * 8 + pg;
-                if (pos < o1) attend<RPJ>(qs, r0, dg, kk[it], vv[it], 0, ke, A);
-            }
+        for (int r = 0; r < RPJ; ++r) {
+            const float4 qa = *reinterpret_cast<const float4*>(qs + r * 64 + dg * 8);
+            const float4 qb = *reinterpret_cast<const float4*>(qs + r * 64 + dg * 8 + 4);
+            q[r][0] = qa.x; q[r][1] = qa.y; q[r][2] = qa.z; q[r][3] = qa.w;
+            q[r][4] = qb.x; q[r][5] = qb.y; q[r][6] = qb.z; q[r][7] = qb.w;
+        }
+        auto run = [&](const v4u (&kk)[kNIT], const v4u (&vv)[kNIT], int rnd) {
+            const int pos0 = o0 + rnd * kNIT * (kCW * 8) + wave * 8 + pg;
+            attend_round<RPJ>(q, r0, kk, vv, pos0, kCW * 8, o1, ke, A);
         };
         for (int rnd = 0; rnd < nrounds; rnd += 2) {
             run(ka, va, rnd);
@@ -692,7 +864,7 @@ __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& b
             const u64 b1 = __hip_atomic_load(reinterpret_cast<const u64*>(vp) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const v4u kraw = (v4u){(unsigned)a0, (unsigned)(a0 >> 32), (unsigned)a1, (unsigned)(a1 >> 32)};
             const v4u vraw = (v4u){(unsigned)b0, (unsigned)(b0 >> 32), (unsigned)b1, (unsigned)(b1 >> 32)};
-            attend<RPJ>(qs, r0, dg, kraw, vraw, pg, ke, A);  // row r sees appended row pg iff pg <= r
+            attend<RPJ>(q, r0, kraw, vraw, pg, ke, A);  // row r sees appended row pg iff pg <= r
         }
         // merge the eight position groups of the wave (lanes that share dg), then hand the wave's
         // partial to the IO waves through LDS: part[wave][row][kPS]
@@ -744,6 +916,9 @@ __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& b
                 if (q4 == 0) st_f32x2(out + 64, m2, dn);
             }
         }
+    }
+    __syncthreads();  // results' stores issued before the next stage's weight loads
+    if (is_io) {
         io_finish(p, s, bar, ph, wave, lane);
     } else {
         ++bar.id;
@@ -772,8 +947,7 @@ __global__ __launch_bounds__(kThreads, 1) void verify_stream_kernel(SP p) {
     for (int l = 0; l < p.L; ++l) {
         gemv_phase<K_A, TPS_D, NSS, 8, KREG_D>(p, s, bar, l, 0, plane(p, l, p.o_xh), plane(p, l, p.o_xl),
                                                slot(p, l) + p.o_ssx, p.d, p.Kpd, resid);
-        if (p.RPJ == 1) attn_phase<1>(p, s, bar, l);
-        else attn_phase<RSMAX>(p, s, bar, l);
+        attn_phase<1>(p, s, bar, l);
         gemv_phase<K_C, TPS_D, 0, 8, KREG_D>(p, s, bar, l, 0, plane(p, l, p.o_oh), plane(p, l, p.o_ol), nullptr, p.d,
                                              p.Kpd, resid);
         gemv_phase<K_D, TPS_D, NSS, 8, KREG_D>(p, s, bar, l, 0, plane(p, l, p.o_x2h), plane(p, l, p.o_x2l),
@@ -784,6 +958,62 @@ __global__ __launch_bounds__(kThreads, 1) void verify_stream_kernel(SP p) {
     for (int r = 0; r < p.rounds[K_LM]; ++r)
         gemv_phase<K_LM, TPS_D, NSS, 8, KREG_D>(p, s, bar, p.L - 1, r, plane(p, p.L, p.o_xh), plane(p, p.L, p.o_xl),
                                                 slot(p, p.L) + p.o_ssx, p.d, p.Kpd, resid);
+}
+
+// One draft micro-step up to the logits (the sampling kernel follows): stage W (three column
+// blocks of W_d over 3 d/16 strips), one grid barrier, then the output projection.
+template <int TPS_D, int KREG_D, int RSMAX>
+__global__ __launch_bounds__(kThreads, 1) void draft_stream_kernel(SP p) {
+    extern __shared__ uint4 smem_raw[];
+    Lds s;
+    s.act_hi = reinterpret_cast<uint16_t*>(smem_raw);
+    s.act_lo = s.act_hi + (size_t)p.MR * p.Kpm;
+    s.red = reinterpret_cast<float*>(reinterpret_cast<char*>(smem_raw) + p.act_bytes);
+    s.rn = s.red + kCW * kMaxStrips * 64 * 4;
+    s.att = s.rn + 16;
+    s.join = reinterpret_cast<unsigned*>(s.att + RSMAX * 64);
+    if (threadIdx.x == 0) *s.join = 0u;
+    __syncthreads();
+    Barrier bar;
+    bar.mem = p.bar; bar.err = p.err; bar.id = p.epoch0; bar.first = p.epoch0; bar.joins = 0; bar.dead = false;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const bool is_io = wave >= kCW;
+    {
+        constexpr int NS = kTMax / TPS_D < kMaxStrips ? kTMax / TPS_D : kMaxStrips;
+        const Job job = load_job(p, K_WD, 0, 0);
+        const unsigned ph = 0;
+        const int per = p.d / 16, blk = job.nstrips ? job.strip[0] / per : 0, sl = job.nstrips ? job.strip[0] - blk * per : 0;
+        v4u w[NS * TPS_D];
+        if (!is_io) {
+            issue_tiles<TPS_D, NS>(p, job, wave, lane, w);
+        } else {
+            stamp(p, ph, 0);
+            if (job.nstrips) stage_draft_input<KREG_D>(p, blk, wave - kCW, lane, s.act_hi, s.act_lo);
+            stamp(p, ph, 2);
+        }
+        __syncthreads();
+        if (!is_io && job.nstrips) {
+            f32x4 acc[NS];
+            mfma_job<TPS_D, NS>(w, wave, lane, p.MR, s.act_hi, s.act_lo, p.Kpd, acc);
+            *reinterpret_cast<f32x4*>(s.red + (((size_t)wave * kMaxStrips) * 64 + lane) * 4) = acc[0];
+        }
+        __syncthreads();
+        stamp(p, ph, 4);
+        if (wave == kCW && job.nstrips) {
+            f32x4 v = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int cw = 0; cw < kCW; ++cw)
+                v += *reinterpret_cast<const f32x4*>(s.red + (((size_t)cw * kMaxStrips) * 64 + lane) * 4);
+            const int c = lane & 15, quad = lane >> 4;
+            if (c < p.MR) st_f32x4(p.dpart + ((size_t)(blk * 16 + c)) * p.d + sl * 16 + 4 * quad, v);
+        }
+        __syncthreads();
+        if (is_io) io_finish(p, s, bar, ph, wave, lane);
+        else ++bar.id;
+    }
+    f32x4 resid = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int r = 0; r < p.rounds[K_LM]; ++r)
+        gemv_phase<K_LM, TPS_D, 0, 8, KREG_D, 1>(p, s, bar, 0, r, nullptr, nullptr, nullptr, p.d, p.Kpd, resid);
 }
 
 // Copies one matrix into the tile order of its kind: tile T of the packed stream is
@@ -961,7 +1191,7 @@ size_t stream_workspace(const hawk_ctx* c, size_t base, StreamOffsets* o) {
     o->arena = take(o->slot_bytes * (L + 1) * kRing);
     o->bar = take((size_t)(kGroups + 1 + kReplicas) * 4096);
     o->err = take(256);
-    o->dbg = take(2 * 4096 * 8 * 8);
+    o->dbg = take(4 * 4096 * 8 * 8);
     o->rope = take((size_t)c->Tmax * (c->hd / 2) * 8);
     return p - base;
 }
@@ -972,6 +1202,14 @@ StreamPlan* stream_create(hawk_ctx* c) {
     P->epoch = 0;
     P->launches = 0;
     if (!P->ok) return P;
+    {   // the grid barrier needs all kNWG workgroups resident at once: one per compute unit
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < kNWG) {
+            P->ok = false;
+            return P;
+        }
+    }
     const StreamOffsets& o = c->soff;
     // tables, rotary table, zeroed barrier memory
     (void)hipMemcpy(c->ws + o.tab, P->tab.data(), P->tab.size() * 4, hipMemcpyHostToDevice);
@@ -1032,18 +1270,17 @@ void stream_plan_info(const hawk_ctx* c, int64_t* out) {
     out[6] = sane ? 1 : 0;
 }
 
-// How the attention stage is cut into jobs for steps of RS rows per sequence: row groups per
-// (sequence, head) and chunks of the cached positions, such that the jobs of the heads that
-// share an XCD fit its 32 workgroups.  One row per job and one chunk when possible (the job then
-// emits finished rows); otherwise all rows per job.
+// How the attention stage is cut into jobs for steps of RS rows per sequence: one job per
+// (sequence, head, row), times NC chunks of the cached positions while the jobs of the heads
+// that share an XCD still fit its 32 workgroups (with one chunk the job emits finished rows).
 struct AttnCut { int NRG, RPJ, NC; bool ok; };
 static AttnCut attn_cut(const hawk_ctx* c, int RS) {
     const int heads_per_xcd = (c->S * c->H + kXcd - 1) / kXcd;
     AttnCut a;
-    a.NRG = heads_per_xcd * RS <= kPerXcd ? RS : 1;
-    a.RPJ = a.NRG == RS ? 1 : RS;
-    a.NC = std::max(1, std::min(kNCMax, kPerXcd / (heads_per_xcd * a.NRG)));
-    a.ok = heads_per_xcd * a.NRG <= kPerXcd;
+    a.NRG = RS;
+    a.RPJ = 1;
+    a.ok = heads_per_xcd * RS <= kPerXcd;
+    a.NC = a.ok ? std::min(kNCMax, kPerXcd / (heads_per_xcd * RS)) : 1;
     return a;
 }
 
@@ -1087,11 +1324,9 @@ int stream_repack(hawk_ctx* c) {
     return hipStreamSynchronize(c->stream) == hipSuccess ? 0 : -1;
 }
 
-// Enqueues the target pass over the step rows; X (c->off.x) must hold the embedded rows.
-// Returns 0, or -1 if the launch failed.
-int launch_verify_stream(hawk_ctx* c, int k) {
+// Kernel parameters common to the target pass and the draft head for a launch over MR rows.
+static void fill_params(hawk_ctx* c, SP& p, int MR) {
     StreamPlan* P = c->plan;
-    SP p;
     memset(&p, 0, sizeof p);
     const StreamOffsets& o = c->soff;
     p.wpack = wsp<uint4>(c, o.wpack);
@@ -1112,27 +1347,70 @@ int launch_verify_stream(hawk_ctx* c, int k) {
     p.arena = wsp<float>(c, o.arena + (size_t)(P->launches % kRing) * o.slot_bytes * (c->L + 1));
     p.slot_floats = o.slot_bytes / 4;
     (void)slot_layout(c, &p);
-    p.logit_s = wsp<float>(c, c->off.logit_s);
     p.dbg = c->stream_dbg ? wsp<u64>(c, o.dbg) : nullptr;
     p.bar = wsp<unsigned>(c, o.bar); p.err = wsp<unsigned>(c, o.err);
     p.n = wsp<int32_t>(c, c->off.n); p.k_eff = wsp<int32_t>(c, c->off.k_eff);
     p.epoch0 = P->epoch;
     p.L = c->L; p.d = c->d; p.H = c->H; p.m = c->m; p.Vs = c->Vs; p.S = c->S; p.B = c->B; p.C = c->C;
-    p.RS = k + 1; p.MR = c->S * (k + 1);
-    const AttnCut cut = attn_cut(c, k + 1);
-    p.NC = cut.NC; p.NRG = cut.NRG; p.RPJ = cut.RPJ;
+    p.MR = MR;
     p.Smax = c->Smax; p.Tmax = c->Tmax; p.Kpd = c->d + 8; p.Kpm = c->m + 8;
     p.eps = c->cfg.rms_eps;
     p.act_bytes = (int32_t)std::max((size_t)p.MR * p.Kpm * 4, (size_t)kCW * 6 * kPS * 4);
+}
+
+static int launch_coop(hawk_ctx* c, const void* kern, SP& p, unsigned barriers) {
+    StreamPlan* P = c->plan;
     const size_t lds = stream_lds_bytes(c, p.MR);
-    const void* kern = c->d == 1280 ? reinterpret_cast<const void*>(verify_stream_kernel<10, 27, 5, 6>)
-                                    : reinterpret_cast<const void*>(verify_stream_kernel<6, 16, 3, 6>);
     if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return -1;
     void* args[] = {&p};
-    if (hipLaunchCooperativeKernel(kern, dim3(kNWG), dim3(kThreads), args, lds, c->stream) != hipSuccess) return -1;
-    P->epoch += 1u + 5u * (unsigned)c->L;  // prologue + five stages per layer; nothing follows the output projection
+    // An ordinary launch: every workgroup gets a compute unit of its own because the grid is
+    // exactly the number of units, one workgroup fills a unit's LDS, and the stream's previous
+    // kernel has drained (checked once in stream_create; the barrier's waits are bounded in any
+    // case).  A cooperative launch costs ~11 us of idle queue on either side on this runtime.
+    if (hipLaunchKernel(kern, dim3(kNWG), dim3(kThreads), args, lds, c->stream) != hipSuccess) return -1;
+    P->epoch += barriers;
     P->launches += 1;
     return 0;
+}
+
+// Enqueues the target pass over the step rows; X (c->off.x) must hold the embedded rows.
+// Returns 0, or -1 if the launch failed.
+int launch_verify_stream(hawk_ctx* c, int k) {
+    SP p;
+    fill_params(c, p, c->S * (k + 1));
+    p.logit_s = wsp<float>(c, c->off.logit_s);
+    p.RS = k + 1;
+    const AttnCut cut = attn_cut(c, k + 1);
+    p.NC = cut.NC; p.NRG = cut.NRG; p.RPJ = cut.RPJ;
+    const void* kern = c->d == 1280 ? reinterpret_cast<const void*>(verify_stream_kernel<10, 27, 5, 6>)
+                                    : reinterpret_cast<const void*>(verify_stream_kernel<6, 16, 3, 6>);
+    // prologue + five stages per layer; nothing follows the output projection
+    return launch_coop(c, kern, p, 1u + 5u * (unsigned)c->L);
+}
+
+// Can draft micro-steps run on the streaming path?
+bool stream_draft_ok(const hawk_ctx* c) {
+    if (!c->plan || !c->plan->ok || c->path != 1) return false;
+    return c->S <= 16 && stream_lds_bytes(c, c->S) <= 150 * 1024 && c->plan->kind[K_WD].rounds == 1;
+}
+
+// Enqueues draft micro-step i (1-based) up to its logits: the head's hidden state goes to
+// off_out ([S][d] fp32), reading the previous one from off_prev; logits to dlogit_s.
+int launch_draft_stream(hawk_ctx* c, int i, size_t off_prev, size_t off_out) {
+    SP p;
+    fill_params(c, p, c->S);
+    p.logit_s = wsp<float>(c, c->off.dlogit_s);
+    p.RS = 1; p.NC = 1; p.NRG = 1; p.RPJ = 1;
+    p.prev = wsp<float>(c, off_prev);
+    p.gout = wsp<float>(c, off_out);
+    p.dpart = p.arena + p.o_p;   // slot 0's attention-partial region: 3 * 16 * d floats fit
+    p.grid = wsp<int32_t>(c, c->off.grid);
+    p.draft = wsp<int32_t>(c, c->off.draft);
+    p.E_off = c->w.E;
+    p.step_i = i; p.N = c->N; p.IW = c->gw; p.kstride = c->kmax + 1;
+    const void* kern = c->d == 1280 ? reinterpret_cast<const void*>(draft_stream_kernel<10, 5, 6>)
+                                    : reinterpret_cast<const void*>(draft_stream_kernel<6, 3, 6>);
+    return launch_coop(c, kern, p, 1u);
 }
 
 // 1 if a barrier of the streaming kernels ever timed out (the result of that step is invalid).

@@ -176,11 +176,11 @@ class Hawk:
         return int(self._L.hawk_last_path(self._h))
 
     def phase_trace(self, enable: bool, n_stages: int = 0):
-        """Switches the streaming kernel's stage time stamps; returns [2, n_stages, 8] uint64 if asked."""
+        """Switches the streaming kernel's stage time stamps; returns [4, n_stages, 8] uint64 if asked."""
         if n_stages <= 0:
             self._chk(self._L.hawk_phase_trace(self._h, int(enable), None, 0), "hawk_phase_trace")
             return None
-        out = np.zeros((2, 4096, 8), dtype=np.uint64)
+        out = np.zeros((4, 4096, 8), dtype=np.uint64)
         self._chk(self._L.hawk_phase_trace(self._h, int(enable), _p(out), out.size), "hawk_phase_trace")
         return out[:, :n_stages]
 

@@ -408,6 +408,30 @@ def test_streaming_kernel_lockstep_with_oracle(H, cfg, layers, steps):
     assert_bf16(res, steps, 0.95)
 
 
+@pytest.mark.parametrize("cfg,k,batch,scale", [(2, 0, 1, 1.0), (2, 2, 1, 1.0), (1, 3, 2, 3.0), (1, 1, 4, 1.0)])
+def test_streaming_kernel_row_counts_and_batches(H, cfg, k, batch, scale):
+    # other cuts of the attention stage than the benchmark's: one row per sequence (cached
+    # positions split into chunks that the Wo stage merges), three rows, guidance with two
+    # prompts (four sequences, 16 rows), four prompts
+    s = synth.CONFIGS[cfg].replace(n_layers=2, n_cond=24, grid_h=6, grid_w=8, batch=batch, cfg_scale=scale, k=k)
+    total = dict(steps=0, decision_same=0, stage_bad=0, max_logit_err=0.0, max_draft_logit_err=0.0)
+    for u_seed in range(1, 40):     # with several prompts a run ends at the first token that differs
+        blob, hk, orc = make_pair(H, s, path=1)
+        res = lockstep(s, hk, orc, k, u_seed=u_seed, max_steps=12)
+        assert res["stage_bad"] == 0, res
+        if res["first_same"]:
+            assert hk.last_path() == 1
+        hk.close()
+        for key in ("steps", "decision_same", "stage_bad"):
+            total[key] += res[key]
+        for key in ("max_logit_err", "max_draft_logit_err"):
+            total[key] = max(total[key], res[key])
+        if total["steps"] >= 12:
+            break
+    print("streaming cut", (cfg, k, batch, scale), total)
+    assert_bf16(total, 12, 0.9)
+
+
 def test_streaming_kernel_xl_full_depth_sampled_steps(H):
     s = synth.CONFIGS[2]
     for u_seed in (1, 2, 3):
