@@ -442,11 +442,20 @@ __global__ void force_commit_kernel(const int32_t* forced, int32_t* grid, int32_
 // the fp64 weights exp(z - zmax) are computed once and reused by the sum and by the
 // inverse-CDF scan.  Same decisions, to the bit, as the generic functions above.
 
+constexpr int kCand = 256;   // entries of the threshold's first-digit bin that are ranked directly
 struct FastShared {
     unsigned hist[NW][256];
     unsigned tot[256];
+    unsigned cand_rel[kCand];
+    int cand_idx[kCand];
+    unsigned cand_n;
     Shared sh;
 };
+
+// Inverse of fkey (the key of -0 maps back to +0).
+__device__ __forceinline__ float key_to_float(unsigned k) {
+    return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
+}
 
 template <int E>
 __device__ __forceinline__ void load_row(const float* lc, const float* lu, float scale, float inv_t, float* out, int n,
@@ -481,12 +490,14 @@ __device__ __forceinline__ void load_row(const float* lc, const float* lu, float
 
 // Which entries of the row held in z the warp keeps (see warp_stats): arg-max, top-k threshold
 // and tie cut, maximum.  The weights themselves come from dense_weights or from a CompactList.
+// *kmask: bit e set iff the thread's entry e is kept (not set in the greedy case).
 template <int E>
-__device__ WarpStat warp_select(const float (&z)[E], int n, int top_k, int greedy, FastShared& fs) {
+__device__ WarpStat warp_select(const float (&z)[E], int n, int top_k, int greedy, FastShared& fs, unsigned* kmask) {
     Shared& sh = fs.sh;
     const int base = threadIdx.x * E, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     WarpStat st;
     st.total = 1.0; st.zmax = 0.f; st.tau = 0x007FFFFFu; st.tie_cut = -1; st.onehot = -1;  // keeps every finite entry
+    *kmask = 0u;
     if (greedy) {
         float best = -INFINITY;
 #pragma unroll
@@ -519,6 +530,7 @@ __device__ WarpStat warp_select(const float (&z)[E], int n, int top_k, int greed
 #pragma unroll
         for (int e = 0; e < E; ++e) rel[e] = (fkey(z[e]) - kmin) << sh0;
         unsigned prefix = 0u, mask = 0u, remaining = (unsigned)K, count_eq = 0u;
+        int ranked_cut = -1;
         for (int shift = 24; shift >= 0 && shift + 8 > sh0; shift -= 8) {  // digits below bit sh0 are all zero
             __syncthreads();
 #pragma unroll
@@ -567,6 +579,34 @@ __device__ WarpStat warp_select(const float (&z)[E], int n, int top_k, int greed
             remaining = sh.b_remaining;
             count_eq = sh.b_count_eq;
             mask |= 255u << shift;
+            if (shift == 24 && count_eq <= (unsigned)kCand) {
+                // Few entries share the threshold's first digit: gather them and rank each one
+                // directly (larger value first, lower index first among equals); the entry of
+                // rank `remaining` is the threshold and the tie cut in one.
+                if (threadIdx.x == 0) fs.cand_n = 0u;
+                __syncthreads();
+#pragma unroll
+                for (int e = 0; e < E; ++e)
+                    if (base + e < n && (rel[e] & mask) == prefix) {
+                        const unsigned at = atomicAdd(&fs.cand_n, 1u);
+                        if (at < (unsigned)kCand) { fs.cand_rel[at] = rel[e]; fs.cand_idx[at] = base + e; }
+                    }
+                __syncthreads();
+                if (threadIdx.x < count_eq) {
+                    const unsigned mine = fs.cand_rel[threadIdx.x];
+                    const int mi = fs.cand_idx[threadIdx.x];
+                    unsigned rank = 0u;
+                    for (unsigned j = 0; j < count_eq; ++j) {
+                        const unsigned r = fs.cand_rel[j];
+                        rank += (r > mine || (r == mine && fs.cand_idx[j] < mi)) ? 1u : 0u;
+                    }
+                    if (rank + 1u == remaining) { sh.b_prefix = mine; sh.b_int = mi; }
+                }
+                __syncthreads();
+                prefix = sh.b_prefix;
+                ranked_cut = sh.b_int;
+                break;
+            }
             if (count_eq == 1u && shift > 0) {  // a single entry is left under the prefix: it is the K-th
                 __syncthreads();
 #pragma unroll
@@ -579,7 +619,9 @@ __device__ WarpStat warp_select(const float (&z)[E], int n, int top_k, int greed
         }
         st.tau = (prefix >> sh0) + kmin;
         st.tie_cut = 0x7FFFFFFF;
-        if (remaining < count_eq) {  // keep only the first `remaining` entries equal to tau
+        if (ranked_cut >= 0) {
+            st.tie_cut = ranked_cut;
+        } else if (remaining < count_eq) {  // keep only the first `remaining` entries equal to tau
             int c = 0;
 #pragma unroll
             for (int e = 0; e < E; ++e) c += (base + e < n && rel[e] == prefix) ? 1 : 0;
@@ -594,12 +636,30 @@ __device__ WarpStat warp_select(const float (&z)[E], int n, int top_k, int greed
             __syncthreads();
             st.tie_cut = sh.b_int;
         }
+        unsigned km = 0u;
+#pragma unroll
+        for (int e = 0; e < E; ++e)
+            km |= (base + e < n && (rel[e] > prefix || (rel[e] == prefix && base + e <= st.tie_cut))) ? (1u << e) : 0u;
+        *kmask = km;
+        st.zmax = key_to_float(kmax);  // the largest entry is always kept
+        return st;
     }
     float zm = -INFINITY;
 #pragma unroll
     for (int e = 0; e < E; ++e) zm = fmaxf(zm, z[e]);
     st.zmax = block_max_f(zm, sh);
+#pragma unroll
+    for (int e = 0; e < E; ++e) *kmask |= (base + e < n && kept(st, z[e], base + e)) ? (1u << e) : 0u;
     return st;
+}
+
+template <int E>
+__device__ __forceinline__ unsigned kept_mask(const WarpStat& st, const float (&z)[E], int n) {
+    const int base = threadIdx.x * E;
+    unsigned km = 0u;
+#pragma unroll
+    for (int e = 0; e < E; ++e) km |= (base + e < n && kept(st, z[e], base + e)) ? (1u << e) : 0u;
+    return km;
 }
 
 // Weight of every entry of the row in registers; sets st.total.
@@ -634,21 +694,19 @@ struct CompactList {
 __device__ __forceinline__ bool use_list(int top_k, int n, int greedy) { return !greedy && top_k < n && top_k <= kCap; }
 
 template <int E>
-__device__ int compact_row(const WarpStat& st, const float (&z)[E], int n, CompactList& L, Shared& sh) {
+__device__ int compact_row(unsigned kmask, const float (&z)[E], CompactList& L, Shared& sh) {
     const int base = threadIdx.x * E;
-    int c = 0;
-#pragma unroll
-    for (int e = 0; e < E; ++e) c += (base + e < n && kept(st, z[e], base + e)) ? 1 : 0;
+    const int c = __popc(kmask);
     int at = block_excl_scan_i(c, sh);
-    const int total = block_max_i(at + c, sh);
+    if (threadIdx.x == NT - 1) sh.b_int = at + c;
 #pragma unroll
     for (int e = 0; e < E; ++e)
-        if (base + e < n && kept(st, z[e], base + e)) {
+        if ((kmask >> e) & 1u) {
             if (at < kCap) { L.idx[at] = base + e; L.z[at] = z[e]; }
             ++at;
         }
     __syncthreads();
-    return min(total, kCap);
+    return min(sh.b_int, kCap);
 }
 
 // w[i] = exp(z[i] - zmax) over the list (thread t owns entries 2t, 2t+1); returns the sum.
@@ -688,12 +746,13 @@ __device__ int inv_cdf_row(const double (&w)[E], double total, float u, Shared& 
 template <int E>
 __device__ WarpStat warp_and_draw(const float (&z)[E], int n, int top_k, int greedy, FastShared& fs, CompactList& L,
                                   const float* u, int* drawn) {
-    WarpStat st = warp_select<E>(z, n, top_k, greedy, fs);
+    unsigned kmask = 0u;
+    WarpStat st = warp_select<E>(z, n, top_k, greedy, fs, &kmask);
     if (st.onehot >= 0) {
         st.total = 1.0;
         if (u) *drawn = st.onehot;
     } else if (use_list(top_k, n, greedy)) {
-        const int Kc = compact_row<E>(st, z, n, L, fs.sh);
+        const int Kc = compact_row<E>(kmask, z, L, fs.sh);
         st.total = list_weights(L, Kc, st.zmax, fs.sh);
         if (u) *drawn = list_inv_cdf(L.w, L.idx, Kc, st.total, *u, fs.sh);
     } else {
@@ -821,7 +880,7 @@ __global__ __launch_bounds__(NT) void accept_commit_fast(
         // the kept entries of p (a superset of the residual's support) as a list; q only where p > 0
         float z[E];
         load_row<E>(prow, nullptr, 0.f, P.inv_t, nullptr, P.Vs, z);
-        const int Kc = compact_row<E>(ps, z, P.Vs, L, sh);
+        const int Kc = compact_row<E>(kept_mask<E>(ps, z, P.Vs), z, L, sh);
         (void)list_weights(L, Kc, ps.zmax, sh);
         if (a < ke) {
             const float* qrow = dlogit_b + ((size_t)b * P.kstride + a) * P.Vs;
