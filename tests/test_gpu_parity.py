@@ -22,8 +22,9 @@ def H():
     return H
 
 
-def make_pair(H, shape, seed=0, std=0.02, batch=None, k_max=None, path=1):
-    blob = synth.make_weights(shape, seed=seed, std=std)
+def make_pair(H, shape, seed=0, std=0.02, batch=None, k_max=None, path=1, blob=None):
+    if blob is None:
+        blob = synth.make_weights(shape, seed=seed, std=std)
     hk = H.Hawk(H.HawkConfig.from_shape(shape, batch=batch, k_max=k_max))
     hk.load(blob)
     hk.set_path(path)
@@ -408,28 +409,58 @@ def test_streaming_kernel_lockstep_with_oracle(H, cfg, layers, steps):
     assert_bf16(res, steps, 0.95)
 
 
+def accumulate_lockstep(H, s, k, path, min_steps, max_runs=40, expect_path=None, **kw):
+    """Lockstep runs over successive uniform seeds until min_steps steps are covered (with
+    several prompts a run ends at the first token that differs); returns the summed counters."""
+    total = dict(steps=0, decision_same=0, stage_bad=0, token_same=0, accepted=0, max_logit_err=0.0,
+                 max_draft_logit_err=0.0)
+    blob = synth.make_weights(s, seed=0)
+    for u_seed in range(1, max_runs + 1):
+        _, hk, orc = make_pair(H, s, path=path, blob=blob)
+        res = lockstep(s, hk, orc, k, u_seed=u_seed, max_steps=min_steps, **kw)
+        assert res["stage_bad"] == 0, res
+        if res["first_same"] and expect_path is not None:
+            assert hk.last_path() == expect_path
+        hk.close()
+        for key in ("steps", "decision_same", "stage_bad", "token_same", "accepted"):
+            total[key] += res[key]
+        for key in ("max_logit_err", "max_draft_logit_err"):
+            total[key] = max(total[key], res[key])
+        if total["steps"] >= min_steps:
+            break
+    return total
+
+
 @pytest.mark.parametrize("cfg,k,batch,scale", [(2, 0, 1, 1.0), (2, 2, 1, 1.0), (1, 3, 2, 3.0), (1, 1, 4, 1.0)])
 def test_streaming_kernel_row_counts_and_batches(H, cfg, k, batch, scale):
     # other cuts of the attention stage than the benchmark's: one row per sequence (cached
     # positions split into chunks that the Wo stage merges), three rows, guidance with two
     # prompts (four sequences, 16 rows), four prompts
     s = synth.CONFIGS[cfg].replace(n_layers=2, n_cond=24, grid_h=6, grid_w=8, batch=batch, cfg_scale=scale, k=k)
-    total = dict(steps=0, decision_same=0, stage_bad=0, max_logit_err=0.0, max_draft_logit_err=0.0)
-    for u_seed in range(1, 40):     # with several prompts a run ends at the first token that differs
-        blob, hk, orc = make_pair(H, s, path=1)
-        res = lockstep(s, hk, orc, k, u_seed=u_seed, max_steps=12)
-        assert res["stage_bad"] == 0, res
-        if res["first_same"]:
-            assert hk.last_path() == 1
-        hk.close()
-        for key in ("steps", "decision_same", "stage_bad"):
-            total[key] += res[key]
-        for key in ("max_logit_err", "max_draft_logit_err"):
-            total[key] = max(total[key], res[key])
-        if total["steps"] >= 12:
-            break
+    total = accumulate_lockstep(H, s, k, 1, 12, expect_path=1)
     print("streaming cut", (cfg, k, batch, scale), total)
     assert_bf16(total, 12, 0.9)
+
+
+def test_config3_guidance_batch16_reduced_depth(H):
+    # configuration 3 (XL-shaped, guidance 4.0, 16 prompts, k = 5: 32 sequences, 192 rows per
+    # target pass) at two layers, a short condition and a small grid, sampled and greedy
+    s = synth.CONFIGS[3].replace(n_layers=2, n_cond=16, grid_h=4, grid_w=8)
+    total = accumulate_lockstep(H, s, s.k, 1, 6, max_runs=12)
+    print("config 3 sampled", total)
+    assert_bf16(total, 6, 0.8)
+    greedy = accumulate_lockstep(H, s, s.k, 1, 6, max_runs=4, temperature=0.0)
+    print("config 3 greedy", greedy)
+    assert_bf16(greedy, 6, 0.8)
+
+
+def test_config4_7b_shape_slice_and_guidance_reduced(H):
+    # configuration 4's shape - d = 4096, 32 heads of 128, MLP 11008, 8192-entry slice at id 4,
+    # top-k 2000, guidance 3.0 - with one layer, a 12288-entry vocabulary, short condition
+    s = synth.CONFIGS[4].replace(n_layers=1, vocab=12288, n_cond=8, grid_h=4, grid_w=8)
+    total = accumulate_lockstep(H, s, s.k, 1, 8, max_runs=10)
+    print("config 4 shape", total)
+    assert_bf16(total, 8, 0.8)
 
 
 def test_streaming_kernel_xl_full_depth_sampled_steps(H):
