@@ -200,11 +200,14 @@ int hawk_last_path(const hawk_ctx* ctx);
 
 /* Diagnostic: switches per-stage time stamps of the streaming kernel on or off (they cost
  * a few stores per stage) and, if out != NULL, copies the stamps of the last launch to
- * out (host, n_words x uint64, at most 4*4096*8): [trace][stage][8] with trace 0, 1 = first
+ * out (host, n_words x uint64, at most 4*4096*8 + 2*256*256): [trace][stage][8] with trace 0, 1 = first
  * IO wave of workgroups 0 and 128 - 100 MHz ticks at: stage entry, barrier crossed, input
  * staged, workgroup sync 1, workgroup sync 2 (MFMAs done), results stored, arrival posted -
  * and trace 2, 3 = first compute wave of the same workgroups: stage entry, weight loads
- * issued, workgroup sync 1, weights landed, MFMAs done, partial sums handed over. */
+ * issued, workgroup sync 1, weights landed, MFMAs done, partial sums handed over.  Behind
+ * these 4*4096*8 words follow [2][256][256] words: for each of the first 256 stages, every
+ * workgroup's arrival time at the stage's barrier, then the time it saw the previous
+ * barrier's release. */
 int hawk_phase_trace(hawk_ctx* ctx, int enable, uint64_t* out, size_t n_words);
 
 #ifdef __cplusplus

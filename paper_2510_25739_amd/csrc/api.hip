@@ -322,7 +322,7 @@ int hawk_phase_trace(hawk_ctx* c, int enable, uint64_t* out, size_t n_words) {
     if (!c) return HAWK_EINVAL;
     c->stream_dbg = enable ? 1 : 0;
     if (out && c->plan) {
-        if (n_words > 4 * 4096 * 8) n_words = 4 * 4096 * 8;
+        if (n_words > 4 * 4096 * 8 + 2 * 256 * 256) n_words = 4 * 4096 * 8 + 2 * 256 * 256;
         return download(c, out, c->soff.dbg, n_words * 8);
     }
     return HAWK_OK;

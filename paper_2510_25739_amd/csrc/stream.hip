@@ -71,7 +71,7 @@ struct SP {
     float* X;        // embedded rows in, final hidden rows out ([MR][d] fp32)
     float* arena;    // exchange slots of this launch: slot l = arena + l * slot_floats, l = 0..L
     // offsets (in floats) of the regions of a slot: split planes are uint16 [16][K + 8]
-    u64 slot_floats, o_xh, o_xl, o_ssx, o_q, o_oh, o_ol, o_x2h, o_x2l, o_ss2, o_hh, o_hl, o_p;
+    u64 slot_floats, o_xh, o_xl, o_ssx, o_q, o_oh, o_ol, o_x2h, o_x2l, o_ss2, o_hh, o_hl, o_p, o_ep;
     float* logit_s;
     u64* dbg;        // optional per-phase timestamps of the first IO wave of workgroups 0 and 128 (null: off)
     unsigned* bar;
@@ -79,7 +79,7 @@ struct SP {
     const int32_t* n;
     const int32_t* k_eff;
     unsigned epoch0;
-    int32_t L, d, H, m, Vs, S, B, C, RS, MR, NC, NRG, RPJ, Smax, Tmax, Kpd, Kpm, act_bytes;
+    int32_t L, d, H, m, Vs, S, B, C, RS, MR, NC, NRG, RPJ, Smax, Tmax, Kpd, Kpm, KpE, esplit, act_bytes;
     float eps;
     // draft head kernel only
     const float* prev;      // [S][d]: hidden state the head continues from
@@ -162,11 +162,10 @@ struct Barrier {
     __device__ void wait() {  // whole wave; returns when barrier `id` has been released
         if (id == first || dead) return;
         const unsigned* rel = mem + (size_t)(kGroups + 1 + blockIdx.x % kReplicas) * 1024;
-        for (unsigned spins = 0; spins < kSpinLimit; ++spins) {
+        for (unsigned spins = 0; spins < kSpinLimit; ++spins) {  // one round trip per spin
             unsigned v = __hip_atomic_load(rel, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if ((int)(v - id) >= 0) { compiler_fence(); return; }
-            if (__hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
-            __builtin_amdgcn_s_sleep(2);
+            if ((spins & 255u) == 255u && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
         }
         dead = true;
         __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -183,6 +182,14 @@ __device__ __forceinline__ void stamp(const SP& p, unsigned phase, int what) {
 __device__ __forceinline__ void stamp_c(const SP& p, unsigned phase, int what) {
     if (p.dbg && threadIdx.x == 0 && (blockIdx.x & 127) == 0)
         p.dbg[((size_t)(2 + (blockIdx.x >> 7)) * 4096 + phase) * 8 + what] = __builtin_amdgcn_s_memrealtime();
+}
+
+// Every workgroup's arrival (what = 0) and release-seen (what = 1) time of a stage, behind the
+// per-wave traces: [what][stage < 256][workgroup].
+constexpr size_t kDbgAll = (size_t)4 * 4096 * 8;
+__device__ __forceinline__ void stamp_all(const SP& p, unsigned phase, int what) {
+    if (p.dbg && phase < 256u && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == kCW)
+        p.dbg[kDbgAll + ((size_t)what * 256 + phase) * kNWG + blockIdx.x] = __builtin_amdgcn_s_memrealtime();
 }
 
 struct Job {
@@ -499,6 +506,7 @@ __device__ __forceinline__ void io_finish(const SP& p, const Lds& s, Barrier& ba
     __builtin_amdgcn_s_waitcnt(0);
     io_join(s, bar, lane);
     stamp(p, ph, 5);
+    stamp_all(p, ph, 0);
     if (wave == kCW && lane == 0) bar.arrive(); else ++bar.id;
     stamp(p, ph, 6);
 }
@@ -626,6 +634,7 @@ __device__ __forceinline__ void gemv_phase(const SP& p, const Lds& s, Barrier& b
         if (fresh) {
             bar.wait();
             stamp(p, ph, 1);
+            stamp_all(p, ph, 1);
             float ssv[NSS > 0 ? NSS : 1];
             if constexpr (NSS > 0) {
                 if (wave == kCW + kNIO - 1) row_scales_load<NSS>(ss, lane, ssv);
@@ -677,6 +686,97 @@ __device__ __forceinline__ void gemv_phase(const SP& p, const Lds& s, Barrier& b
     } else if (KIND != K_LM) {
         ++bar.id;
     }
+}
+
+// Stage E (W2): `esplit` workgroups share a strip, each with its own K range.  Part 0 owns the
+// strip's residual; the others hand it their partial sums through words that read 0xFFFFFFFF
+// until written (a NaN pattern no sum can produce; the owner restores it after reading), so the
+// hand-over costs one store -> poll trip instead of a grid barrier.
+template <int TPS, int BATCH>
+__device__ __forceinline__ void w2_phase(const SP& p, const Lds& s, Barrier& bar, int layer, f32x4& resid) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const bool is_io = wave >= kCW;
+    const Job job = load_job(p, K_E, 0, layer);
+    const int strip = job.strip[0], part = job.strip[1];
+    const unsigned ph = bar.id - bar.first;
+    constexpr int KPART = TPS * kCW * 32;        // K range of one part
+    constexpr int CPR = KPART / 8;               // 16-byte chunks per row of it
+    v4u w[TPS];
+    EpiPre pre;
+    if (!is_io) {
+        issue_tiles<TPS, 1>(p, job, wave, lane, w);
+    } else {
+        stamp(p, ph, 0);
+        if (wave == kCW && job.nstrips && part == 0) epilogue_prefetch<K_E>(p, layer, strip, lane, pre);
+        bar.wait();
+        stamp(p, ph, 1);
+        stamp_all(p, ph, 1);
+        if (job.nstrips) {  // copy the part's columns of the split planes: chunk q = (plane, row, column chunk)
+            const int t = threadIdx.x - kCW * 64, total = 2 * p.MR * CPR;
+            const uint16_t* hi = plane(p, layer, p.o_hh) + (size_t)part * KPART;
+            const uint16_t* lo = plane(p, layer, p.o_hl) + (size_t)part * KPART;
+            for (int base = 0; base < total; base += BATCH * kIOThreads) {
+                v4u v[BATCH];
+#pragma unroll
+                for (int i = 0; i < BATCH; ++i) {
+                    const int q = base + i * kIOThreads + t, pr = q / CPR, j8 = q - pr * CPR;
+                    const int c = pr >= p.MR ? pr - p.MR : pr;
+                    const uint16_t* src = (pr >= p.MR ? lo : hi) + (size_t)c * p.Kpm + j8 * 8;
+                    v[i] = q < total ? *reinterpret_cast<const v4u*>(src) : (v4u){0u, 0u, 0u, 0u};
+                }
+#pragma unroll
+                for (int i = 0; i < BATCH; ++i) {
+                    const int q = base + i * kIOThreads + t, pr = q / CPR, j8 = q - pr * CPR;
+                    const int c = pr >= p.MR ? pr - p.MR : pr;
+                    uint16_t* dst = (pr >= p.MR ? s.act_lo : s.act_hi) + (size_t)c * p.KpE + j8 * 8;
+                    if (q < total) *reinterpret_cast<v4u*>(dst) = v[i];
+                }
+            }
+        }
+        stamp(p, ph, 2);
+    }
+    __syncthreads();
+    stamp(p, ph, 3);
+    if (!is_io && job.nstrips) {
+        f32x4 acc[1];
+        mfma_job<TPS, 1>(w, wave, lane, p.MR, s.act_hi, s.act_lo, p.KpE, acc);
+        *reinterpret_cast<f32x4*>(s.red + (((size_t)wave * kMaxStrips) * 64 + lane) * 4) = acc[0];
+    }
+    __syncthreads();
+    stamp(p, ph, 4);
+    if (wave == kCW && job.nstrips) {
+        f32x4 v = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int cw = 0; cw < kCW; ++cw)
+            v += *reinterpret_cast<const f32x4*>(s.red + (((size_t)cw * kMaxStrips) * 64 + lane) * 4);
+        float* mail = slot(p, layer) + p.o_ep + ((size_t)strip * (p.esplit - 1)) * 256 + lane * 4;
+        if (part > 0) {
+            st_f32x4(mail + (size_t)(part - 1) * 256, v);
+        } else {
+            for (int j = 0; j + 1 < p.esplit; ++j) {
+                u64* src = reinterpret_cast<u64*>(mail + (size_t)j * 256);
+                u64 a = ~0ull, b = ~0ull;
+                bool ok = false;
+                for (unsigned spins = 0; spins < kSpinLimit && !ok; ++spins) {
+                    a = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    b = __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    ok = (unsigned)a != ~0u && (unsigned)(a >> 32) != ~0u && (unsigned)b != ~0u && (unsigned)(b >> 32) != ~0u;
+                    ok = __all(ok);  // the wave leaves the loop together
+                    if (!ok && (spins & 255u) == 255u &&
+                        __hip_atomic_load(p.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
+                }
+                if (!ok) __hip_atomic_store(p.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                v += (f32x4){__uint_as_float((unsigned)a), __uint_as_float((unsigned)(a >> 32)),
+                             __uint_as_float((unsigned)b), __uint_as_float((unsigned)(b >> 32))};
+                __hip_atomic_store(src, ~0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);      // "not written yet" again
+                __hip_atomic_store(src + 1, ~0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            epilogue<K_E>(p, s, layer, strip, v, lane, pre, resid);
+        }
+    }
+    __syncthreads();
+    if (is_io) io_finish(p, s, bar, ph, wave, lane);
+    else ++bar.id;
 }
 
 // ------------------------------------------------------------------------- attention
@@ -815,13 +915,16 @@ __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& b
         }
     };
     if (!is_io && have) {
+        stamp_c(p, ph, 0);
         fetch(ka, va, 0);
         fetch(kb, vb, 1);
+        stamp_c(p, ph, 1);
     }
     if (is_io) {
         stamp(p, ph, 0);
         bar.wait();
         stamp(p, ph, 1);
+        stamp_all(p, ph, 1);
         if (have && wave == kCW)
             for (int r = 0; r < RPJ; ++r)
                 qs[r * 64 + lane] = r0 + r < RS ? (slot(p, layer) + p.o_q)[(size_t)(seq * RS + r0 + r) * d + h * 64 + lane] : 0.f;
@@ -830,6 +933,7 @@ __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& b
     __syncthreads();
     stamp(p, ph, 3);
     if (!is_io && have) {
+        stamp_c(p, ph, 2);
         AttnAcc A[RPJ];
 #pragma unroll
         for (int r = 0; r < RPJ; ++r) {
@@ -855,6 +959,7 @@ __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& b
             run(kb, vb, rnd + 1);
             fetch(kb, vb, rnd + 3);
         }
+        stamp_c(p, ph, 3);
         if (ch == p.NC - 1 && wave == 0 && pg <= ke) {  // rows appended by this launch: coherent loads
             const _Float16* kp = p.Kc + base + (size_t)(kv0 + pg) * d;
             const _Float16* vp = p.Vc + base + (size_t)(kv0 + pg) * d;
@@ -866,6 +971,7 @@ __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& b
             const v4u vraw = (v4u){(unsigned)b0, (unsigned)(b0 >> 32), (unsigned)b1, (unsigned)(b1 >> 32)};
             attend<RPJ>(q, r0, kraw, vraw, pg, ke, A);  // row r sees appended row pg iff pg <= r
         }
+        stamp_c(p, ph, 4);
         // merge the eight position groups of the wave (lanes that share dg), then hand the wave's
         // partial to the IO waves through LDS: part[wave][row][kPS]
 #pragma unroll
@@ -888,6 +994,7 @@ __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& b
             }
         }
     }
+    if (!is_io && have) stamp_c(p, ph, 5);
     __syncthreads();
     stamp(p, ph, 4);
     if (is_io) {
@@ -932,7 +1039,7 @@ __global__ __launch_bounds__(kThreads, 1) void verify_stream_kernel(SP p) {
     extern __shared__ uint4 smem_raw[];
     Lds s;
     s.act_hi = reinterpret_cast<uint16_t*>(smem_raw);
-    s.act_lo = s.act_hi + (size_t)p.MR * p.Kpm;
+    s.act_lo = s.act_hi + (size_t)(p.act_bytes / 4);
     s.red = reinterpret_cast<float*>(reinterpret_cast<char*>(smem_raw) + p.act_bytes);
     s.rn = s.red + kCW * kMaxStrips * 64 * 4;
     s.att = s.rn + 16;
@@ -952,8 +1059,7 @@ __global__ __launch_bounds__(kThreads, 1) void verify_stream_kernel(SP p) {
                                              p.Kpd, resid);
         gemv_phase<K_D, TPS_D, NSS, 8, KREG_D>(p, s, bar, l, 0, plane(p, l, p.o_x2h), plane(p, l, p.o_x2l),
                                                slot(p, l) + p.o_ss2, p.d, p.Kpd, resid);
-        gemv_phase<K_E, TPS_M, 0, 11, KREG_D>(p, s, bar, l, 0, plane(p, l, p.o_hh), plane(p, l, p.o_hl), nullptr, p.m,
-                                              p.Kpm, resid);
+        w2_phase<TPS_M, (2 * 6 * TPS_M * kCW * 4 + kIOThreads - 1) / kIOThreads>(p, s, bar, l, resid);
     }
     for (int r = 0; r < p.rounds[K_LM]; ++r)
         gemv_phase<K_LM, TPS_D, NSS, 8, KREG_D>(p, s, bar, p.L - 1, r, plane(p, p.L, p.o_xh), plane(p, p.L, p.o_xl),
@@ -967,7 +1073,7 @@ __global__ __launch_bounds__(kThreads, 1) void draft_stream_kernel(SP p) {
     extern __shared__ uint4 smem_raw[];
     Lds s;
     s.act_hi = reinterpret_cast<uint16_t*>(smem_raw);
-    s.act_lo = s.act_hi + (size_t)p.MR * p.Kpm;
+    s.act_lo = s.act_hi + (size_t)(p.act_bytes / 4);
     s.red = reinterpret_cast<float*>(reinterpret_cast<char*>(smem_raw) + p.act_bytes);
     s.rn = s.red + kCW * kMaxStrips * 64 * 4;
     s.att = s.rn + 16;
@@ -1037,6 +1143,7 @@ __global__ void repack_kernel(const uint16_t* W, int K, int kind, int m, int row
 
 struct KindPlan {
     int nstrips, KT, TPS, maxS, rounds;
+    int ksplit;          // workgroups that share one strip, each with 1/ksplit of K (W2 only; else 1)
     size_t tiles;        // tiles of one instance of this kind
     size_t tab_index;    // int32 index of the job table
     size_t desc_index;   // uint32 index of the tile descriptors
@@ -1079,7 +1186,13 @@ void build_plan(const hawk_ctx* c, StreamPlan* P) {
     const int KT[K_NKIND] = {d / 32, d / 32, d / 32, m / 32, d / 32, d / 32};
     for (int k = 0; k < K_NKIND; ++k) {
         KindPlan& kp = P->kind[k];
-        kp.nstrips = nstrips[k]; kp.KT = KT[k]; kp.TPS = KT[k] / 4;
+        kp.nstrips = nstrips[k]; kp.KT = KT[k];
+        kp.ksplit = 1;
+        if (k == K_E) {  // W2 has few, long strips: as many workgroups per strip as divide its K evenly
+            for (int f = kNWG / nstrips[k]; f > 1; --f)
+                if (KT[k] % (4 * f) == 0) { kp.ksplit = f; break; }
+        }
+        kp.TPS = KT[k] / (4 * kp.ksplit);
         kp.maxS = std::min(kMaxStrips, kTMax / kp.TPS);
         kp.tiles = (size_t)nstrips[k] * KT[k];
         kp.rounds = k <= K_E ? 1 : (nstrips[k] + kNWG * kp.maxS - 1) / (kNWG * kp.maxS);
@@ -1091,11 +1204,18 @@ void build_plan(const hawk_ctx* c, StreamPlan* P) {
     // stream in registers for the whole launch (workgroup s runs on XCD s % 8).
     if (nstrips[K_C] > kNWG || nstrips[K_E] != nstrips[K_C]) { P->ok = false; return; }
     std::vector<long> load(kNWG, 0);
+    const int fE = P->kind[K_E].ksplit;
     for (int s = 0; s < nstrips[K_C]; ++s) {
         assign[K_C][s].push_back(s);
-        assign[K_E][s].push_back(s);
-        load[s] += P->kind[K_C].TPS + P->kind[K_E].TPS;
+        load[s] += P->kind[K_C].TPS;
     }
+    // W2: part j of strip s (K range j / fE) goes to workgroup j * strips + s; part 0 - the owner of
+    // the residual strip - adds the other parts' partial sums (entry = part * strips + strip)
+    for (int j = 0; j < fE; ++j)
+        for (int s = 0; s < nstrips[K_E]; ++s) {
+            assign[K_E][(size_t)j * nstrips[K_E] + s].push_back(j * nstrips[K_E] + s);
+            load[(size_t)j * nstrips[K_E] + s] += P->kind[K_E].TPS;
+        }
     // QKV and W1|W3: as few strips per workgroup as the count allows, the extra ones to the
     // workgroups that stream least per layer.
     const int order[2] = {K_D, K_A};
@@ -1131,13 +1251,19 @@ void build_plan(const hawk_ctx* c, StreamPlan* P) {
                 const int ns = (int)st.size();
                 int s3[3] = {0xFFFF, 0xFFFF, 0xFFFF};
                 for (int i = 0; i < ns; ++i) s3[i] = st[i];
+                int kt0 = 0;
+                if (k == K_E && ns) {  // (strip, part) in the first two fields
+                    s3[0] = st[0] % kp.nstrips; s3[1] = st[0] / kp.nstrips;
+                    kt0 = s3[1] * (kp.KT / kp.ksplit);
+                }
                 P->tab.push_back((int32_t)tile);
                 P->tab.push_back(ns);
                 P->tab.push_back((int32_t)((unsigned)s3[0] | ((unsigned)s3[1] << 16)));
                 P->tab.push_back(s3[2]);
                 for (int wv = 0; wv < kCW; ++wv)
                     for (int t = 0; t < ns * kp.TPS; ++t) {
-                        P->desc.push_back(((uint32_t)st[t / kp.TPS] << 12) | (uint32_t)(wv * kp.TPS + t % kp.TPS));
+                        P->desc.push_back(((uint32_t)(k == K_E ? s3[0] : st[t / kp.TPS]) << 12) |
+                                          (uint32_t)(kt0 + wv * kp.TPS + t % kp.TPS));
                         ++tile;
                     }
             }
@@ -1165,7 +1291,9 @@ size_t slot_layout(const hawk_ctx* c, SP* p) {
     const size_t xh = take(pd), xl = take(pd), ssx = take(d), q = take(16 * d), oh = take(pd), ol = take(pd);
     const size_t x2h = take(pd), x2l = take(pd), ss2 = take(d), hh = take(pm), hl = take(pm);
     const size_t pp = take((size_t)kNWG * 8 * kPS);
+    const size_t ep = take((size_t)kNWG * 256);   // W2 partial strips: [strip * (parts - 1) + part - 1][64 lanes][4]
     if (p) {
+        p->o_ep = ep;
         p->o_xh = xh; p->o_xl = xl; p->o_ssx = ssx; p->o_q = q; p->o_oh = oh; p->o_ol = ol;
         p->o_x2h = x2h; p->o_x2l = x2l; p->o_ss2 = ss2; p->o_hh = hh; p->o_hl = hl; p->o_p = pp;
     }
@@ -1191,7 +1319,7 @@ size_t stream_workspace(const hawk_ctx* c, size_t base, StreamOffsets* o) {
     o->arena = take(o->slot_bytes * (L + 1) * kRing);
     o->bar = take((size_t)(kGroups + 1 + kReplicas) * 4096);
     o->err = take(256);
-    o->dbg = take(4 * 4096 * 8 * 8);
+    o->dbg = take((4 * 4096 * 8 + 2 * 256 * kNWG) * 8);
     o->rope = take((size_t)c->Tmax * (c->hd / 2) * 8);
     return p - base;
 }
@@ -1215,6 +1343,8 @@ StreamPlan* stream_create(hawk_ctx* c) {
     (void)hipMemcpy(c->ws + o.tab, P->tab.data(), P->tab.size() * 4, hipMemcpyHostToDevice);
     (void)hipMemcpy(c->ws + o.desc, P->desc.data(), P->desc.size() * 4, hipMemcpyHostToDevice);
     (void)hipMemset(c->ws + o.bar, 0, (size_t)(kGroups + 1 + kReplicas) * 4096);
+    // every word of the exchange arenas starts as the "not written yet" pattern the W2 stage polls for
+    (void)hipMemset(c->ws + o.arena, 0xFF, o.slot_bytes * (size_t)(c->L + 1) * kRing);
     (void)hipMemset(c->ws + o.err, 0, 256);
     std::vector<float> rope((size_t)c->Tmax * (c->hd / 2) * 2);
     for (int pos = 0; pos < c->Tmax; ++pos)
@@ -1284,10 +1414,17 @@ static AttnCut attn_cut(const hawk_ctx* c, int RS) {
     return a;
 }
 
+// Elements between the hi and the lo plane rows in LDS: the longest stage input a workgroup
+// stages (d, or its share of m in the W2 stage), padded.
+static size_t act_stride(const hawk_ctx* c) {
+    const int f = c->plan ? c->plan->kind[K_E].ksplit : 1;
+    return (size_t)std::max(c->d, c->m / f) + 8;
+}
+
 // LDS of one workgroup: activation hi/lo planes (or, during attention, the per-wave partials),
 // K-quarter partial strips, row scales, scaled queries, IO join word.
 static size_t stream_lds_bytes(const hawk_ctx* c, int MR) {
-    const size_t act = std::max((size_t)MR * (std::max(c->d, c->m) + 8) * 4, (size_t)kCW * 6 * kPS * 4);
+    const size_t act = std::max((size_t)MR * act_stride(c) * 4, (size_t)kCW * 6 * kPS * 4);
     return act + (size_t)(kCW * kMaxStrips * 256 + 16 + 6 * 64 + 16) * 4;
 }
 
@@ -1354,8 +1491,9 @@ static void fill_params(hawk_ctx* c, SP& p, int MR) {
     p.L = c->L; p.d = c->d; p.H = c->H; p.m = c->m; p.Vs = c->Vs; p.S = c->S; p.B = c->B; p.C = c->C;
     p.MR = MR;
     p.Smax = c->Smax; p.Tmax = c->Tmax; p.Kpd = c->d + 8; p.Kpm = c->m + 8;
+    p.esplit = P->kind[K_E].ksplit; p.KpE = c->m / p.esplit + 8;
     p.eps = c->cfg.rms_eps;
-    p.act_bytes = (int32_t)std::max((size_t)p.MR * p.Kpm * 4, (size_t)kCW * 6 * kPS * 4);
+    p.act_bytes = (int32_t)std::max((size_t)p.MR * act_stride(c) * 4, (size_t)kCW * 6 * kPS * 4);
 }
 
 static int launch_coop(hawk_ctx* c, const void* kern, SP& p, unsigned barriers) {
@@ -1382,8 +1520,8 @@ int launch_verify_stream(hawk_ctx* c, int k) {
     p.RS = k + 1;
     const AttnCut cut = attn_cut(c, k + 1);
     p.NC = cut.NC; p.NRG = cut.NRG; p.RPJ = cut.RPJ;
-    const void* kern = c->d == 1280 ? reinterpret_cast<const void*>(verify_stream_kernel<10, 27, 5, 6>)
-                                    : reinterpret_cast<const void*>(verify_stream_kernel<6, 16, 3, 6>);
+    const void* kern = c->d == 1280 ? reinterpret_cast<const void*>(verify_stream_kernel<10, 9, 5, 6>)
+                                    : reinterpret_cast<const void*>(verify_stream_kernel<6, 4, 3, 6>);
     // prologue + five stages per layer; nothing follows the output projection
     return launch_coop(c, kern, p, 1u + 5u * (unsigned)c->L);
 }

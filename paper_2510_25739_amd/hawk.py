@@ -180,9 +180,10 @@ class Hawk:
         if n_stages <= 0:
             self._chk(self._L.hawk_phase_trace(self._h, int(enable), None, 0), "hawk_phase_trace")
             return None
-        out = np.zeros((4, 4096, 8), dtype=np.uint64)
+        out = np.zeros(4 * 4096 * 8 + 2 * 256 * 256, dtype=np.uint64)
         self._chk(self._L.hawk_phase_trace(self._h, int(enable), _p(out), out.size), "hawk_phase_trace")
-        return out[:, :n_stages]
+        self.last_arrivals = out[4 * 4096 * 8:].reshape(2, 256, 256)   # [arrive | release seen][stage][workgroup]
+        return out[:4 * 4096 * 8].reshape(4, 4096, 8)[:, :n_stages]
 
     def load(self, blob: np.ndarray):
         blob = np.ascontiguousarray(blob, dtype=np.uint8)
