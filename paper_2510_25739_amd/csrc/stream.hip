@@ -146,10 +146,15 @@ struct Barrier {
     unsigned first;    // id at kernel start
     unsigned joins;    // io_join calls so far (IO waves)
     bool dead;
-    __device__ void arrive() {  // one lane of one wave per workgroup
+    // Arrival in two halves, so that the workgroup can be told that the arrival is on its way
+    // (and may queue loads behind it) before the counter's old value has come back.
+    __device__ unsigned arrive_issue() {  // one lane of one wave per workgroup
+        const unsigned g = blockIdx.x % kGroups;
+        return __hip_atomic_fetch_add(mem + (size_t)g * 1024, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __device__ void arrive_finish(unsigned prev) {
         ++id;
-        const unsigned g = blockIdx.x % kGroups, per = gridDim.x / kGroups;
-        unsigned prev = __hip_atomic_fetch_add(mem + (size_t)g * 1024, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned per = gridDim.x / kGroups;
         if (prev + 1 == id * per) {
             unsigned t = __hip_atomic_fetch_add(mem + (size_t)kGroups * 1024, 1u, __ATOMIC_RELAXED,
                                                 __HIP_MEMORY_SCOPE_AGENT);
@@ -507,8 +512,20 @@ __device__ __forceinline__ void io_finish(const SP& p, const Lds& s, Barrier& ba
     io_join(s, bar, lane);
     stamp(p, ph, 5);
     stamp_all(p, ph, 0);
-    if (wave == kCW && lane == 0) bar.arrive(); else ++bar.id;
+    const bool poster = wave == kCW && lane == 0;
+    unsigned prev = 0u;
+    if (poster) prev = bar.arrive_issue();
+    __builtin_amdgcn_s_barrier();  // pairs with compute_finish: the next stage's loads queue behind the arrival
+    if (poster) bar.arrive_finish(prev); else ++bar.id;
     stamp(p, ph, 6);
+}
+
+// The compute waves' end of a stage: they go on to request the next stage's weights only once
+// this stage's results are acknowledged and its arrival has been sent, so that neither waits in
+// the compute unit's memory pipeline behind a hundred KB of prefetch.
+__device__ __forceinline__ void compute_finish(Barrier& bar) {
+    __builtin_amdgcn_s_barrier();
+    ++bar.id;
 }
 
 // First stage of a launch: the owners of the residual strips pick their slice of the embedded
@@ -528,7 +545,7 @@ __device__ __forceinline__ void prologue_phase(const SP& p, const Lds& s, Barrie
         }
         io_finish(p, s, bar, ph, wave, lane);
     } else {
-        ++bar.id;
+        compute_finish(bar);
     }
 }
 
@@ -677,14 +694,10 @@ __device__ __forceinline__ void gemv_phase(const SP& p, const Lds& s, Barrier& b
             epilogue<KIND>(p, s, layer, job.strip[i], v, lane, pre, resid);
         }
     }
-    // The results' stores enter the memory pipeline ahead of the next stage's weight loads (which
-    // the compute waves issue next): the acknowledgements this stage's arrival waits for do not
-    // queue behind a hundred KB of prefetch.
-    __syncthreads();
     if (is_io) {
         if (KIND != K_LM) io_finish(p, s, bar, ph, wave, lane);  // nothing follows the output projection
     } else if (KIND != K_LM) {
-        ++bar.id;
+        compute_finish(bar);
     }
 }
 
@@ -774,9 +787,8 @@ __device__ __forceinline__ void w2_phase(const SP& p, const Lds& s, Barrier& bar
             epilogue<K_E>(p, s, layer, strip, v, lane, pre, resid);
         }
     }
-    __syncthreads();
     if (is_io) io_finish(p, s, bar, ph, wave, lane);
-    else ++bar.id;
+    else compute_finish(bar);
 }
 
 // ------------------------------------------------------------------------- attention
@@ -1024,11 +1036,10 @@ __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& b
             }
         }
     }
-    __syncthreads();  // results' stores issued before the next stage's weight loads
     if (is_io) {
         io_finish(p, s, bar, ph, wave, lane);
     } else {
-        ++bar.id;
+        compute_finish(bar);
     }
 }
 
@@ -1113,9 +1124,8 @@ __global__ __launch_bounds__(kThreads, 1) void draft_stream_kernel(SP p) {
             const int c = lane & 15, quad = lane >> 4;
             if (c < p.MR) st_f32x4(p.dpart + ((size_t)(blk * 16 + c)) * p.d + sl * 16 + 4 * quad, v);
         }
-        __syncthreads();
         if (is_io) io_finish(p, s, bar, ph, wave, lane);
-        else ++bar.id;
+        else compute_finish(bar);
     }
     f32x4 resid = (f32x4){0.f, 0.f, 0.f, 0.f};
     for (int r = 0; r < p.rounds[K_LM]; ++r)
