@@ -79,6 +79,20 @@ __device__ float block_max_f(float v, Shared& sh) {
     for (int w = 1; w < NW; ++w) t = fmaxf(t, sh.fred[w]);
     return t;
 }
+// Minimum and maximum over the block in one exchange.
+__device__ void block_minmax_f(float& lo, float& hi, Shared& sh) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        lo = fminf(lo, __shfl_xor(lo, o, 64));
+        hi = fmaxf(hi, __shfl_xor(hi, o, 64));
+    }
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) { sh.fred[threadIdx.x >> 6] = lo; sh.dred[threadIdx.x >> 6] = (double)hi; }
+    __syncthreads();
+    lo = sh.fred[0]; hi = (float)sh.dred[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) { lo = fminf(lo, sh.fred[w]); hi = fmaxf(hi, (float)sh.dred[w]); }
+}
 __device__ int block_min_i(int v, Shared& sh) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, 64));
@@ -446,11 +460,34 @@ constexpr int kCand = 256;   // entries of the threshold's first-digit bin that 
 struct FastShared {
     unsigned hist[NW][256];
     unsigned tot[256];
-    unsigned cand_rel[kCand];
+    alignas(16) unsigned cand_rel[kCand];
     int cand_idx[kCand];
     unsigned cand_n;
     Shared sh;
 };
+
+// Number of gathered candidates that come before candidate i (larger key first, lower index
+// first among equal keys).  Whole waves call this (i = threadIdx.x, also for i >= cnt): each
+// lane loads one candidate per group of 64 and the wave walks them with lane broadcasts, so the
+// loop has no LDS latency in it.
+__device__ __forceinline__ unsigned cand_rank(const FastShared& fs, unsigned i, unsigned cnt) {
+    const unsigned lane = threadIdx.x & 63u;
+    const unsigned mine = i < cnt ? fs.cand_rel[i] : 0u;
+    const int mi = i < cnt ? fs.cand_idx[i] : 0x7FFFFFFF;
+    unsigned rank = 0u;
+    for (unsigned g = 0; g * 64u < cnt; ++g) {
+        const bool on = g * 64u + lane < cnt;
+        const unsigned kj = on ? fs.cand_rel[g * 64u + lane] : 0u;
+        const int ij = on ? fs.cand_idx[g * 64u + lane] : 0x7FFFFFFF;
+        const unsigned lim = min(64u, cnt - g * 64u);
+        for (unsigned j = 0; j < lim; ++j) {
+            const unsigned r = (unsigned)__builtin_amdgcn_readlane((int)kj, (int)j);
+            const int ix = __builtin_amdgcn_readlane(ij, (int)j);
+            rank += (r > mine || (r == mine && ix < mi)) ? 1u : 0u;
+        }
+    }
+    return rank;
+}
 
 // Inverse of fkey (the key of -0 maps back to +0).
 __device__ __forceinline__ float key_to_float(unsigned k) {
@@ -515,30 +552,34 @@ __device__ WarpStat warp_select(const float (&z)[E], int n, int top_k, int greed
         // The keys of a row share their high bits (sign, most of the exponent): radix digits are
         // taken from (key - smallest key) shifted up to the top bit, so that the first digit
         // already spreads the row over the 256 bins (few LDS atomics collide, fewer passes).
-        int lo_b = 0x7FFFFFFF, hi_b = (int)0x80000000;
+        float gmin = INFINITY, gmax = -INFINITY;
 #pragma unroll
         for (int e = 0; e < E; ++e)
-            if (base + e < n) {
-                const int kb = (int)(fkey(z[e]) ^ 0x80000000u);  // signed order = key order
-                lo_b = min(lo_b, kb);
-                hi_b = max(hi_b, kb);
-            }
-        const unsigned kmin = (unsigned)block_min_i(lo_b, sh) ^ 0x80000000u;
-        const unsigned kmax = (unsigned)block_max_i(hi_b, sh) ^ 0x80000000u;
+            if (base + e < n) { gmin = fminf(gmin, z[e]); gmax = fmaxf(gmax, z[e]); }
+        block_minmax_f(gmin, gmax, sh);
+        const unsigned kmin = fkey(gmin), kmax = fkey(gmax);  // the key order is the value order
         const int sh0 = kmax > kmin ? __clz((int)(kmax - kmin)) : 31;
+        // First the row is cut into 256 bins that are linear in the value (the float keys are
+        // logarithmic: two or three of their first digits would hold nearly everything); the
+        // threshold's bin then holds a few dozen entries, which are ranked directly.  If it holds
+        // too many (ties, odd distributions), the exact radix select on the keys takes over.
+        bool lin = gmax > gmin && gmin > -INFINITY && gmax < INFINITY;
+        const float scale = lin ? 255.99f / (gmax - gmin) : 0.f;
         unsigned rel[E];
 #pragma unroll
         for (int e = 0; e < E; ++e) rel[e] = (fkey(z[e]) - kmin) << sh0;
         unsigned prefix = 0u, mask = 0u, remaining = (unsigned)K, count_eq = 0u;
         int ranked_cut = -1;
-        for (int shift = 24; shift >= 0 && shift + 8 > sh0; shift -= 8) {  // digits below bit sh0 are all zero
+        for (int shift = 24; shift >= 0 && shift + 8 > sh0;) {  // digits below bit sh0 are all zero
             __syncthreads();
 #pragma unroll
             for (int q = 0; q < 4; ++q) fs.hist[wave][lane * 4 + q] = 0u;
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
-            for (int e = 0; e < E; ++e)
-                if (base + e < n && (rel[e] & mask) == prefix) atomicAdd(&fs.hist[wave][(rel[e] >> shift) & 255u], 1u);
+            for (int e = 0; e < E; ++e) {
+                const unsigned digit = lin ? min(255u, (unsigned)((z[e] - gmin) * scale)) : ((rel[e] >> shift) & 255u);
+                if (base + e < n && (lin || (rel[e] & mask) == prefix)) atomicAdd(&fs.hist[wave][digit], 1u);
+            }
             __syncthreads();
             if (threadIdx.x < 256) {
                 unsigned t = 0u;
@@ -569,12 +610,33 @@ __device__ WarpStat warp_select(const float (&z)[E], int n, int top_k, int greed
                     cum += cs[q];
                 }
                 if (found >= 0) {  // exactly one lane finds it
-                    sh.b_prefix = prefix | ((unsigned)found << shift);
+                    sh.b_prefix = lin ? (unsigned)found : (prefix | ((unsigned)found << shift));
                     sh.b_remaining = rem_out;
                     sh.b_count_eq = cnt_out;
                 }
             }
             __syncthreads();
+            if (lin) {
+                const unsigned bin = sh.b_prefix, want = sh.b_remaining, cnt = sh.b_count_eq;
+                if (cnt > (unsigned)kCand) { lin = false; continue; }  // same digit again, on the keys
+                if (threadIdx.x == 0) fs.cand_n = 0u;
+                __syncthreads();
+#pragma unroll
+                for (int e = 0; e < E; ++e)
+                    if (base + e < n && min(255u, (unsigned)((z[e] - gmin) * scale)) == bin) {
+                        const unsigned at = atomicAdd(&fs.cand_n, 1u);
+                        if (at < (unsigned)kCand) { fs.cand_rel[at] = rel[e]; fs.cand_idx[at] = base + e; }
+                    }
+                __syncthreads();
+                if ((threadIdx.x & ~63u) < cnt) {  // whole waves
+                    const unsigned rank = cand_rank(fs, threadIdx.x, cnt);
+                    if (threadIdx.x < cnt && rank + 1u == want) { sh.b_prefix = fs.cand_rel[threadIdx.x]; sh.b_int = fs.cand_idx[threadIdx.x]; }
+                }
+                __syncthreads();
+                prefix = sh.b_prefix;
+                ranked_cut = sh.b_int;
+                break;
+            }
             prefix = sh.b_prefix;
             remaining = sh.b_remaining;
             count_eq = sh.b_count_eq;
@@ -592,15 +654,9 @@ __device__ WarpStat warp_select(const float (&z)[E], int n, int top_k, int greed
                         if (at < (unsigned)kCand) { fs.cand_rel[at] = rel[e]; fs.cand_idx[at] = base + e; }
                     }
                 __syncthreads();
-                if (threadIdx.x < count_eq) {
-                    const unsigned mine = fs.cand_rel[threadIdx.x];
-                    const int mi = fs.cand_idx[threadIdx.x];
-                    unsigned rank = 0u;
-                    for (unsigned j = 0; j < count_eq; ++j) {
-                        const unsigned r = fs.cand_rel[j];
-                        rank += (r > mine || (r == mine && fs.cand_idx[j] < mi)) ? 1u : 0u;
-                    }
-                    if (rank + 1u == remaining) { sh.b_prefix = mine; sh.b_int = mi; }
+                if ((threadIdx.x & ~63u) < count_eq) {  // whole waves
+                    const unsigned rank = cand_rank(fs, threadIdx.x, count_eq);
+                    if (threadIdx.x < count_eq && rank + 1u == remaining) { sh.b_prefix = fs.cand_rel[threadIdx.x]; sh.b_int = fs.cand_idx[threadIdx.x]; }
                 }
                 __syncthreads();
                 prefix = sh.b_prefix;
@@ -616,6 +672,7 @@ __device__ WarpStat warp_select(const float (&z)[E], int n, int top_k, int greed
                 prefix = sh.b_prefix;
                 break;
             }
+            shift -= 8;
         }
         st.tau = (prefix >> sh0) + kmin;
         st.tie_cut = 0x7FFFFFFF;
@@ -641,7 +698,7 @@ __device__ WarpStat warp_select(const float (&z)[E], int n, int top_k, int greed
         for (int e = 0; e < E; ++e)
             km |= (base + e < n && (rel[e] > prefix || (rel[e] == prefix && base + e <= st.tie_cut))) ? (1u << e) : 0u;
         *kmask = km;
-        st.zmax = key_to_float(kmax);  // the largest entry is always kept
+        st.zmax = gmax;  // the largest entry is always kept
         return st;
     }
     float zm = -INFINITY;
