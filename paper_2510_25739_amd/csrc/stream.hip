@@ -155,21 +155,21 @@ struct Barrier {
     __device__ void arrive_finish(unsigned prev) {
         ++id;
         const unsigned per = gridDim.x / kGroups;
-        if (prev + 1 == id * per) {
-            unsigned t = __hip_atomic_fetch_add(mem + (size_t)kGroups * 1024, 1u, __ATOMIC_RELAXED,
-                                                __HIP_MEMORY_SCOPE_AGENT);
-            if (t + 1 == id * kGroups)
-                for (int r = 0; r < kReplicas; ++r)
-                    __hip_atomic_store(mem + (size_t)(kGroups + 1 + r) * 1024, id, __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
+        if (prev + 1 == id * per) {  // last of its group: publish the group's word in every replica line
+            const unsigned g = blockIdx.x % kGroups;
+            for (int r = 0; r < kReplicas; ++r)
+                __hip_atomic_store(mem + (size_t)(kGroups + 1 + r) * 1024 + g, id, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     __device__ void wait() {  // whole wave; returns when barrier `id` has been released
         if (id == first || dead) return;
-        const unsigned* rel = mem + (size_t)(kGroups + 1 + blockIdx.x % kReplicas) * 1024;
+        // the 16 groups' words of one replica sit in one 64-byte line: lanes 0..15 read one each
+        const unsigned l = threadIdx.x & 63u;
+        const unsigned* rel = mem + (size_t)(kGroups + 1 + blockIdx.x % kReplicas) * 1024 + (l < (unsigned)kGroups ? l : 0u);
         for (unsigned spins = 0; spins < kSpinLimit; ++spins) {  // one round trip per spin
             unsigned v = __hip_atomic_load(rel, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if ((int)(v - id) >= 0) { compiler_fence(); return; }
+            if (__all((int)(v - id) >= 0)) { compiler_fence(); return; }
             if ((spins & 255u) == 255u && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
         }
         dead = true;
