@@ -48,7 +48,7 @@ constexpr int kThreads = (kCW + kNIO) * 64;
 constexpr int kIOThreads = kNIO * 64;
 constexpr int kTMax = 27;                       // tiles (1 KB each) a wave holds for one job
 constexpr int kMaxStrips = 3;                   // strips of one job (one IO wave finishes each)
-constexpr int kGroups = 16, kReplicas = 8;      // barrier fan-in / release fan-out
+constexpr int kGroups = 8, kReplicas = 8;       // barrier fan-in (one group per XCD) / release fan-out
 constexpr unsigned kSpinLimit = 1u << 21;
 constexpr int kRing = 3;                        // exchange arenas used round robin by successive launches
 constexpr int kPS = 68;                         // floats per attention partial row: 64 outputs, max, sum, pad
