@@ -50,10 +50,79 @@ __device__ __forceinline__ unsigned fkey(float z) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// Cross-lane moves inside the VALU (DPP) instead of LDS-crossbar shuffles: within a row of 16
+// lanes by quad permutes and mirrors, across the four rows by lane broadcasts.
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true); }
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) { return __builtin_bit_cast(float, dpp_i<CTRL>(__builtin_bit_cast(int, v))); }
+template <int CTRL>
+__device__ __forceinline__ double dpp_d(double v) {
+    const unsigned long long b = __builtin_bit_cast(unsigned long long, v);
+    const unsigned lo = (unsigned)dpp_i<CTRL>((int)(unsigned)b), hi = (unsigned)dpp_i<CTRL>((int)(unsigned)(b >> 32));
+    return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+}
+__device__ __forceinline__ float lane_f(float v, int l) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+}
+__device__ __forceinline__ double lane_d(double v, int l) {
+    const unsigned long long b = __builtin_bit_cast(unsigned long long, v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)b, l);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(b >> 32), l);
+    return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+}
+// 0xB1 = quad_perm [1,0,3,2], 0x4E = quad_perm [2,3,0,1], 0x141 = row_half_mirror, 0x140 = row_mirror:
+// after the four steps every lane of a row holds the row's result.
+#define ROW_ALLREDUCE(v, OP, DPP)         \
+    v = OP(v, DPP<0xB1>(v));              \
+    v = OP(v, DPP<0x4E>(v));              \
+    v = OP(v, DPP<0x141>(v));             \
+    v = OP(v, DPP<0x140>(v));
+__device__ __forceinline__ double addd(double a, double b) { return a + b; }
+__device__ __forceinline__ int mini(int a, int b) { return min(a, b); }
+__device__ __forceinline__ int maxi(int a, int b) { return max(a, b); }
+
 __device__ __forceinline__ double wave_sum_d(double v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+    ROW_ALLREDUCE(v, addd, dpp_d)
+    return (lane_d(v, 0) + lane_d(v, 16)) + (lane_d(v, 32) + lane_d(v, 48));
+}
+__device__ __forceinline__ float wave_max_f(float v) {
+    ROW_ALLREDUCE(v, fmaxf, dpp_f)
+    return fmaxf(fmaxf(lane_f(v, 0), lane_f(v, 16)), fmaxf(lane_f(v, 32), lane_f(v, 48)));
+}
+__device__ __forceinline__ float wave_min_f(float v) {
+    ROW_ALLREDUCE(v, fminf, dpp_f)
+    return fminf(fminf(lane_f(v, 0), lane_f(v, 16)), fminf(lane_f(v, 32), lane_f(v, 48)));
+}
+__device__ __forceinline__ int wave_min_i(int v) {
+    ROW_ALLREDUCE(v, mini, dpp_i)
+    return min(min(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+               min(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
+}
+__device__ __forceinline__ int wave_max_i(int v) {
+    ROW_ALLREDUCE(v, maxi, dpp_i)
+    return max(max(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+               max(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
+}
+// Inclusive prefix sums over the lanes of the wave, in lane order: row_shr 1, 2, 4, 8 with zero
+// fill inside each row of 16 (0x111, 0x112, 0x114, 0x118), then the totals of the rows before.
+__device__ __forceinline__ double wave_incl_scan_d(double v) {
+    v += dpp_d<0x111>(v);
+    v += dpp_d<0x112>(v);
+    v += dpp_d<0x114>(v);
+    v += dpp_d<0x118>(v);
+    const double r0 = lane_d(v, 15), r1 = lane_d(v, 31), r2 = lane_d(v, 47);
+    const int row = (threadIdx.x & 63) >> 4;
+    return v + (row == 0 ? 0.0 : row == 1 ? r0 : row == 2 ? r0 + r1 : (r0 + r1) + r2);
+}
+__device__ __forceinline__ int wave_incl_scan_i(int v) {
+    v += dpp_i<0x111>(v);
+    v += dpp_i<0x112>(v);
+    v += dpp_i<0x114>(v);
+    v += dpp_i<0x118>(v);
+    const int r0 = __builtin_amdgcn_readlane(v, 15), r1 = __builtin_amdgcn_readlane(v, 31), r2 = __builtin_amdgcn_readlane(v, 47);
+    const int row = (threadIdx.x & 63) >> 4;
+    return v + (row == 0 ? 0 : row == 1 ? r0 : row == 2 ? r0 + r1 : r0 + r1 + r2);
 }
 
 // All block primitives below return the same value to every thread and may be called
@@ -69,8 +138,7 @@ __device__ double block_sum_d(double v, Shared& sh) {
     return t;
 }
 __device__ float block_max_f(float v, Shared& sh) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    v = wave_max_f(v);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) sh.fred[threadIdx.x >> 6] = v;
     __syncthreads();
@@ -81,11 +149,8 @@ __device__ float block_max_f(float v, Shared& sh) {
 }
 // Minimum and maximum over the block in one exchange.
 __device__ void block_minmax_f(float& lo, float& hi, Shared& sh) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        lo = fminf(lo, __shfl_xor(lo, o, 64));
-        hi = fmaxf(hi, __shfl_xor(hi, o, 64));
-    }
+    lo = wave_min_f(lo);
+    hi = wave_max_f(hi);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) { sh.fred[threadIdx.x >> 6] = lo; sh.dred[threadIdx.x >> 6] = (double)hi; }
     __syncthreads();
@@ -94,8 +159,7 @@ __device__ void block_minmax_f(float& lo, float& hi, Shared& sh) {
     for (int w = 1; w < NW; ++w) { lo = fminf(lo, sh.fred[w]); hi = fmaxf(hi, (float)sh.dred[w]); }
 }
 __device__ int block_min_i(int v, Shared& sh) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, 64));
+    v = wave_min_i(v);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) sh.ired[threadIdx.x >> 6] = v;
     __syncthreads();
@@ -105,8 +169,7 @@ __device__ int block_min_i(int v, Shared& sh) {
     return t;
 }
 __device__ int block_max_i(int v, Shared& sh) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o, 64));
+    v = wave_max_i(v);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) sh.ired[threadIdx.x >> 6] = v;
     __syncthreads();
@@ -118,32 +181,24 @@ __device__ int block_max_i(int v, Shared& sh) {
 // Exclusive prefix sums over the threads of the block, in thread order.
 __device__ double block_excl_scan_d(double v, Shared& sh) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    double inc = v;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        double t = __shfl_up(inc, o, 64);
-        if (lane >= o) inc += t;
-    }
+    const double inc = wave_incl_scan_d(v);
     __syncthreads();
     if (lane == 63) sh.dred[wave] = inc;
     __syncthreads();
     double base = 0.0;
-    for (int w = 0; w < wave; ++w) base += sh.dred[w];
+#pragma unroll
+    for (int w = 0; w < NW; ++w) base += w < wave ? sh.dred[w] : 0.0;
     return base + (inc - v);
 }
 __device__ int block_excl_scan_i(int v, Shared& sh) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int inc = v;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        int t = __shfl_up(inc, o, 64);
-        if (lane >= o) inc += t;
-    }
+    const int inc = wave_incl_scan_i(v);
     __syncthreads();
     if (lane == 63) sh.ired[wave] = inc;
     __syncthreads();
     int base = 0;
-    for (int w = 0; w < wave; ++w) base += sh.ired[w];
+#pragma unroll
+    for (int w = 0; w < NW; ++w) base += w < wave ? sh.ired[w] : 0;
     return base + (inc - v);
 }
 
