@@ -27,7 +27,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
 # scaled by a 1 GiB device copy in the same run (FETCH_SIZE factor 2.000, WRITE_SIZE 1.000).
-TRAFFIC_BYTES_PER_LAUNCH = int(779903 * 1024 * 2.000 + 61958 * 1024 * 1.000)   # config 2, streaming kernel
+TRAFFIC_BYTES_PER_LAUNCH = int(780214 * 1024 * 2.000 + 60533 * 1024 * 1.000)   # config 2, streaming kernel
 
 
 def verify_bytes(s, kv_len: float) -> float:
