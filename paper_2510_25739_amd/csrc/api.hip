@@ -99,6 +99,9 @@ bool derive(const hawk_config* g, hawk_ctx* c) {
     o.u_draft = take(B * ks * 4); o.u_acc = take(B * ks * 4); o.u_fin = take(B * 4);
     o.out_na = take(B * 4); o.out_tok = take(B * ks * 4); o.inv_freq = take((size_t)(hd / 2) * 8);
     o.replay = take(B * c->Nmax * 4); o.cond = take(S * (size_t)g->max_cond * d * 4);
+    const size_t widest = 3 * d > m ? 3 * d : m;
+    c->split_bytes = g->dtype == HAWK_BF16 ? M * widest * 4 : 0;
+    o.split = c->split_bytes ? take(c->split_bytes) : 0;
     p += stream_workspace(c, p, &c->soff);
     o.total = p;
     return true;

@@ -1,0 +1,185 @@
+// Dense GEMM for the batched shapes (many rows per target pass: several prompts, guidance
+// doubling, the prefill): Y[M][N] (+)= A[M][K] * W[N][K]^T with bf16 weights on the MFMA units.
+//
+// The k+1-row verify step of one sequence is a weight-streaming problem and has its own kernels;
+// here every weight byte meets tens to hundreds of rows, so this is a real contraction:
+//   - the fp32 activations are split once per GEMM input into a bf16 hi and a bf16 lo plane
+//     (two MFMAs per tile: fp32-accurate activations), by a small kernel of its own, so that the
+//     GEMM's inner loop only copies 16-byte chunks;
+//   - a workgroup of four waves computes a tile of 16*SR*2 output features x 16*CT*2 rows: the
+//     waves sit 2 x 2 over the tile, each holds SR x CT accumulators of v_mfma_f32_16x16x32_bf16;
+//   - weights (the A operand: 16 rows x 32 k per tile, 16 bytes per lane) come straight from
+//     global memory in their stored row-major order, one k-step ahead; the activation planes of
+//     the tile's rows go through LDS (padded rows, double-buffered, 64 k per stage) because all
+//     four waves read them;
+//   - per k-step a wave issues 2*CT LDS reads for 2*SR*CT MFMAs.
+#include "hawk_internal.h"
+
+namespace hawk {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+
+constexpr int kKC = 64;          // k per LDS stage (two MFMA k-steps)
+constexpr int kLdsK = kKC + 8;   // padded row length in halves
+
+__device__ __forceinline__ unsigned bf16_rne_u(float f) {
+    unsigned u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// hi[r][j], lo[r][j] = bf16 split of A[r * lda + j], r < M, j < K (K % 4 == 0).
+__global__ void split_rows_kernel(const float* A, int lda, int K, uint16_t* hi, uint16_t* lo, size_t total4) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total4) return;
+    const int k4 = K / 4;
+    const size_t r = i / k4;
+    const int j = (int)(i - r * k4) * 4;
+    const float4 v = *reinterpret_cast<const float4*>(A + r * lda + j);
+    const unsigned h0 = bf16_rne_u(v.x), h1 = bf16_rne_u(v.y), h2 = bf16_rne_u(v.z), h3 = bf16_rne_u(v.w);
+    const unsigned l0 = bf16_rne_u(v.x - __uint_as_float(h0 << 16)), l1 = bf16_rne_u(v.y - __uint_as_float(h1 << 16));
+    const unsigned l2 = bf16_rne_u(v.z - __uint_as_float(h2 << 16)), l3 = bf16_rne_u(v.w - __uint_as_float(h3 << 16));
+    *reinterpret_cast<uint2*>(hi + r * K + j) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+    *reinterpret_cast<uint2*>(lo + r * K + j) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+}
+
+// SR: 16-feature strips per wave, CT: 16-row tiles per wave.  Tile = (32 SR) features x (32 CT) rows.
+template <int SR, int CT>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restrict__ hi, const uint16_t* __restrict__ lo,
+                                                        const uint16_t* __restrict__ W, int N, int K, float* Y, int ldy,
+                                                        int M, int accumulate) {
+    constexpr int BM = 32 * CT, BN = 32 * SR;
+    constexpr int CHUNKS = 2 * BM * (kKC / 8);       // 16-byte chunks of one stage (both planes)
+    constexpr int PER_T = (CHUNKS + 255) / 256;
+    __shared__ __attribute__((aligned(16))) uint16_t lds[2][2][BM][kLdsK];   // [stage][plane][row][k]
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wn = wave >> 1, wm = wave & 1;                     // wave position over (features, rows)
+    const int n0 = blockIdx.x * BN + wn * 16 * SR, m0 = blockIdx.y * BM;
+    const int r16 = lane & 15, kg = lane >> 4;
+    const int nk = K / kKC;
+
+    // stage loader: chunk q -> (plane, row, 8-k group)
+    auto load_stage = [&](int it, v4u (&buf)[PER_T]) {
+#pragma unroll
+        for (int i = 0; i < PER_T; ++i) {
+            const int q = i * 256 + threadIdx.x;
+            const int pl = q / (BM * (kKC / 8)), rem = q - pl * (BM * (kKC / 8));
+            const int row = rem / (kKC / 8), g = rem - row * (kKC / 8);
+            const bool on = q < CHUNKS && m0 + row < M;
+            const uint16_t* src = (pl ? lo : hi) + (size_t)(m0 + row) * K + it * kKC + g * 8;
+            buf[i] = on ? *reinterpret_cast<const v4u*>(src) : (v4u){0u, 0u, 0u, 0u};
+        }
+    };
+    auto store_stage = [&](int st, const v4u (&buf)[PER_T]) {
+#pragma unroll
+        for (int i = 0; i < PER_T; ++i) {
+            const int q = i * 256 + threadIdx.x;
+            const int pl = q / (BM * (kKC / 8)), rem = q - pl * (BM * (kKC / 8));
+            const int row = rem / (kKC / 8), g = rem - row * (kKC / 8);
+            if (q < CHUNKS) *reinterpret_cast<v4u*>(&lds[st][pl][row][g * 8]) = buf[i];
+        }
+    };
+    // weights of one stage: SR strips x 2 k-steps, 16 bytes per lane each
+    auto load_w = [&](int it, v4u (&w)[SR][2]) {
+#pragma unroll
+        for (int s = 0; s < SR; ++s) {
+            const int n = n0 + s * 16 + r16;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+                w[s][ks] = n < N ? __builtin_nontemporal_load(reinterpret_cast<const v4u*>(W + (size_t)n * K + it * kKC + ks * 32 + kg * 8))
+                                 : (v4u){0u, 0u, 0u, 0u};
+        }
+    };
+
+    f32x4 acc[SR][CT], acl[SR][CT];
+#pragma unroll
+    for (int s = 0; s < SR; ++s)
+#pragma unroll
+        for (int t = 0; t < CT; ++t) {
+            acc[s][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            acl[s][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        }
+    v4u bufB[PER_T];
+    v4u wcur[SR][2], wnext[SR][2];
+    load_stage(0, bufB);
+    load_w(0, wcur);
+    store_stage(0, bufB);
+    __syncthreads();
+    for (int it = 0; it < nk; ++it) {
+        const int st = it & 1;
+        if (it + 1 < nk) {  // next stage's operands are on their way while this one is multiplied
+            load_stage(it + 1, bufB);
+            load_w(it + 1, wnext);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            v4u bh[CT], bl[CT];
+#pragma unroll
+            for (int t = 0; t < CT; ++t) {
+                const int row = wm * 16 * CT + t * 16 + r16;
+                bh[t] = *reinterpret_cast<const v4u*>(&lds[st][0][row][ks * 32 + kg * 8]);
+                bl[t] = *reinterpret_cast<const v4u*>(&lds[st][1][row][ks * 32 + kg * 8]);
+            }
+#pragma unroll
+            for (int s = 0; s < SR; ++s) {
+                const bf16x8 a = __builtin_bit_cast(bf16x8, wcur[s][ks]);
+#pragma unroll
+                for (int t = 0; t < CT; ++t) {
+                    acc[s][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bh[t]), acc[s][t], 0, 0, 0);
+                    acl[s][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bl[t]), acl[s][t], 0, 0, 0);
+                }
+            }
+        }
+        if (it + 1 < nk) {
+            store_stage(st ^ 1, bufB);
+#pragma unroll
+            for (int s = 0; s < SR; ++s) { wcur[s][0] = wnext[s][0]; wcur[s][1] = wnext[s][1]; }
+        }
+        __syncthreads();
+    }
+    // lane holds features n0 + s*16 + 4*kg .. +3 of row m0 + wm*16*CT + t*16 + r16
+#pragma unroll
+    for (int s = 0; s < SR; ++s)
+#pragma unroll
+        for (int t = 0; t < CT; ++t) {
+            const int m = m0 + wm * 16 * CT + t * 16 + r16, n = n0 + s * 16 + 4 * kg;
+            if (m < M && n < N) {
+                float4* dst = reinterpret_cast<float4*>(Y + (size_t)m * ldy + n);
+                f32x4 v = acc[s][t] + acl[s][t];
+                if (accumulate) {
+                    const float4 old = *dst;
+                    v += (f32x4){old.x, old.y, old.z, old.w};
+                }
+                *dst = make_float4(v[0], v[1], v[2], v[3]);
+            }
+        }
+}
+
+}  // namespace
+
+// Runs Y (+)= A W^T on the MFMA path if the shape allows; false: the caller uses the generic kernel.
+bool launch_gemm_mfma(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, int K, size_t off_y, int ldy, int M,
+                      bool accumulate) {
+    if (c->cfg.dtype != HAWK_BF16 || !c->off.split || M < 9) return false;
+    if (N % 16 || K % kKC || ldy % 4 || lda % 4) return false;
+    if ((size_t)M * K * 4 > c->split_bytes) return false;
+    uint16_t* hi = wsp<uint16_t>(c, c->off.split);
+    uint16_t* lo = hi + (size_t)M * K;
+    const size_t total4 = (size_t)M * (K / 4);
+    split_rows_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, c->stream>>>(wsp<float>(c, off_a), lda, K, hi, lo, total4);
+    const uint16_t* W = reinterpret_cast<const uint16_t*>(c->ws + c->off.blob + w_off);
+    float* Y = wsp<float>(c, off_y);
+    if (N <= 2048 || M <= 64) {   // few tiles: smaller ones, so that more compute units take part
+        dim3 grid((N + 31) / 32, (M + 63) / 64);
+        gemm_mfma_kernel<1, 2><<<grid, 256, 0, c->stream>>>(hi, lo, W, N, K, Y, ldy, M, accumulate ? 1 : 0);
+    } else {
+        dim3 grid((N + 63) / 64, (M + 95) / 96);
+        gemm_mfma_kernel<2, 3><<<grid, 256, 0, c->stream>>>(hi, lo, W, N, K, Y, ldy, M, accumulate ? 1 : 0);
+    }
+    return true;
+}
+
+}  // namespace hawk

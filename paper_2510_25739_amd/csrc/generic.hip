@@ -327,6 +327,7 @@ void launch_rmsnorm(hawk_ctx* c, size_t off_in, size_t in_stride, size_t off_gai
 
 void launch_gemm(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, int K, size_t off_y, int ldy,
                  int M, bool accumulate, bool out_f32) {
+    if (launch_gemm_mfma(c, off_a, lda, w_off, N, K, off_y, ldy, M, accumulate)) return;
     constexpr int RT = 8;
     dim3 grid((N + 3) / 4, (M + RT - 1) / RT);
     if (out_f32) {

@@ -54,6 +54,7 @@ struct Offsets {  // byte offsets into the workspace
     size_t blob, kc, vc, n, k_eff, step, done, counters, grid, draft, forced, hprev, qstat, pstat;
     size_t x, a, qkv, o, u, din, g0, g1, ga, logit_s, logit_b, dlogit_s, dlogit_b;
     size_t u_draft, u_acc, u_fin, out_na, out_tok, inv_freq, replay, cond;
+    size_t split;   // bf16 hi / lo planes of a GEMM input (batched shapes; 0: not present)
     size_t total;
 };
 
@@ -81,6 +82,7 @@ struct hawk_ctx {
     hawk::StreamOffsets soff;
     hawk::StreamPlan* plan;  // streaming path: job tables and barrier epoch (null until created)
     size_t blob_bytes;
+    size_t split_bytes;
     // per image
     int B, S, C, gh, gw, N, top_k, greedy;
     float temperature, inv_t, cfg_scale;
@@ -110,6 +112,9 @@ void launch_rmsnorm(hawk_ctx*, size_t off_in, size_t in_stride, size_t off_gain,
 // Y[M][N] (+)= A[M][K] * W[N][K]^T ; out_f32: store fp32 (logits) instead of activations
 void launch_gemm(hawk_ctx*, size_t off_a, int lda, size_t w_off, int N, int K, size_t off_y,
                  int ldy, int M, bool accumulate, bool out_f32);
+// the same on the MFMA units (bf16, many rows); false if the shape is not covered (gemm.hip)
+bool launch_gemm_mfma(hawk_ctx*, size_t off_a, int lda, size_t w_off, int N, int K, size_t off_y, int ldy, int M,
+                      bool accumulate);
 void launch_rope_append(hawk_ctx*, const RowMap&, int layer, int M);
 void launch_attention(hawk_ctx*, const RowMap&, int layer, int M);
 void launch_swiglu(hawk_ctx*, int M);
