@@ -9,10 +9,12 @@
 //   - a workgroup of four waves computes a tile of 16*SR*2 output features x 16*CT*2 rows: the
 //     waves sit 2 x 2 over the tile, each holds SR x CT accumulators of v_mfma_f32_16x16x32_bf16;
 //   - weights (the A operand: 16 rows x 32 k per tile, 16 bytes per lane) come straight from
-//     global memory in their stored row-major order, one k-step ahead; the activation planes of
-//     the tile's rows go through LDS (padded rows, double-buffered, 64 k per stage) because all
-//     four waves read them;
-//   - per k-step a wave issues 2*CT LDS reads for 2*SR*CT MFMAs.
+//     global memory in their stored row-major order; the activation planes of the tile's rows go
+//     through LDS (padded rows, double-buffered, 64 k per stage) because all four waves read them;
+//   - D stages are in flight per workgroup, held in a register ring, and the barrier between
+//     stages orders LDS traffic only, so a stage costs its arithmetic and not a memory round trip;
+//   - per k-step a wave issues 2*CT LDS reads for 2*SR*CT MFMAs;
+//   - GEMMs with few output features split K over blockIdx.z and add partial tiles atomically.
 #include "hawk_internal.h"
 
 namespace hawk {
@@ -31,6 +33,15 @@ __device__ __forceinline__ unsigned bf16_rne_u(float f) {
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+// Workgroup barrier that orders LDS traffic only: __syncthreads() also waits for every global
+// load in flight, which would end the prefetch of the coming stages at each k-stage.
+__device__ __forceinline__ void lds_barrier() {
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0); vmcnt and expcnt left alone
+    __builtin_amdgcn_s_barrier();
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+}
+
 // hi[r][j], lo[r][j] = bf16 split of A[r * lda + j], r < M, j < K (K % 4 == 0).
 __global__ void split_rows_kernel(const float* A, int lda, int K, uint16_t* hi, uint16_t* lo, size_t total4) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -46,51 +57,57 @@ __global__ void split_rows_kernel(const float* A, int lda, int K, uint16_t* hi, 
     *reinterpret_cast<uint2*>(lo + r * K + j) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
 }
 
-// SR: 16-feature strips per wave, CT: 16-row tiles per wave.  Tile = (32 SR) features x (32 CT) rows.
-template <int SR, int CT>
+// SR: 16-feature strips per wave, CT: 16-row tiles per wave, D: stages (64 k each) in flight.
+// Tile = (32 SR) features x (32 CT) rows; blockIdx.z takes one of gridDim.z equal K ranges and,
+// if there are several, adds its partial tile into Y with float atomics (Y then already holds
+// what is accumulated onto).
+template <int SR, int CT, int D>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restrict__ hi, const uint16_t* __restrict__ lo,
                                                         const uint16_t* __restrict__ W, int N, int K, float* Y, int ldy,
                                                         int M, int accumulate) {
     constexpr int BM = 32 * CT, BN = 32 * SR;
     constexpr int CHUNKS = 2 * BM * (kKC / 8);       // 16-byte chunks of one stage (both planes)
     constexpr int PER_T = (CHUNKS + 255) / 256;
-    __shared__ __attribute__((aligned(16))) uint16_t lds[2][2][BM][kLdsK];   // [stage][plane][row][k]
+    __shared__ __attribute__((aligned(16))) uint16_t lds[2][2][BM][kLdsK];   // [buffer][plane][row][k]
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int wn = wave >> 1, wm = wave & 1;                     // wave position over (features, rows)
     const int n0 = blockIdx.x * BN + wn * 16 * SR, m0 = blockIdx.y * BM;
     const int r16 = lane & 15, kg = lane >> 4;
-    const int nk = K / kKC;
+    const int nk = K / kKC / (int)gridDim.z, it0 = (int)blockIdx.z * nk;   // this block's stages
 
-    // stage loader: chunk q -> (plane, row, 8-k group)
-    auto load_stage = [&](int it, v4u (&buf)[PER_T]) {
+    static_assert(CHUNKS % 256 == 0, "a stage is a whole number of 16-byte chunks per thread");
+
+    struct Stage { v4u b[PER_T]; v4u w[SR][2]; };
+    // Everything of stage `it` that comes from global memory: the tile rows' activation planes
+    // (chunk q -> plane, row, 8-k group) and the wave's weight tiles (SR strips x 2 k-steps).
+    // Every lane always loads (rows and features past the end are clamped to the last one; what
+    // they produce is never stored), and the loop below never branches around a load: only then
+    // can the waits for an old stage be counted past the younger requests behind it.
+    auto load_stage = [&](int it, Stage& s) {
+        const size_t k0 = (size_t)(it0 + min(it, nk - 1)) * kKC;
 #pragma unroll
         for (int i = 0; i < PER_T; ++i) {
             const int q = i * 256 + threadIdx.x;
             const int pl = q / (BM * (kKC / 8)), rem = q - pl * (BM * (kKC / 8));
             const int row = rem / (kKC / 8), g = rem - row * (kKC / 8);
-            const bool on = q < CHUNKS && m0 + row < M;
-            const uint16_t* src = (pl ? lo : hi) + (size_t)(m0 + row) * K + it * kKC + g * 8;
-            buf[i] = on ? *reinterpret_cast<const v4u*>(src) : (v4u){0u, 0u, 0u, 0u};
+            const uint16_t* src = (pl ? lo : hi) + (size_t)min(m0 + row, M - 1) * K + k0 + g * 8;
+            s.b[i] = *reinterpret_cast<const v4u*>(src);
         }
-    };
-    auto store_stage = [&](int st, const v4u (&buf)[PER_T]) {
 #pragma unroll
-        for (int i = 0; i < PER_T; ++i) {
-            const int q = i * 256 + threadIdx.x;
-            const int pl = q / (BM * (kKC / 8)), rem = q - pl * (BM * (kKC / 8));
-            const int row = rem / (kKC / 8), g = rem - row * (kKC / 8);
-            if (q < CHUNKS) *reinterpret_cast<v4u*>(&lds[st][pl][row][g * 8]) = buf[i];
-        }
-    };
-    // weights of one stage: SR strips x 2 k-steps, 16 bytes per lane each
-    auto load_w = [&](int it, v4u (&w)[SR][2]) {
-#pragma unroll
-        for (int s = 0; s < SR; ++s) {
-            const int n = n0 + s * 16 + r16;
+        for (int t = 0; t < SR; ++t) {
+            const int n = min(n0 + t * 16 + r16, N - 1);
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
-                w[s][ks] = n < N ? __builtin_nontemporal_load(reinterpret_cast<const v4u*>(W + (size_t)n * K + it * kKC + ks * 32 + kg * 8))
-                                 : (v4u){0u, 0u, 0u, 0u};
+                s.w[t][ks] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(W + (size_t)n * K + k0 + ks * 32 + kg * 8));
+        }
+    };
+    auto store_stage = [&](int buf, const Stage& s) {
+#pragma unroll
+        for (int i = 0; i < PER_T; ++i) {
+            const int q = i * 256 + threadIdx.x;
+            const int pl = q / (BM * (kKC / 8)), rem = q - pl * (BM * (kKC / 8));
+            const int row = rem / (kKC / 8), g = rem - row * (kKC / 8);
+            *reinterpret_cast<v4u*>(&lds[buf][pl][row][g * 8]) = s.b[i];
         }
     };
 
@@ -102,30 +119,20 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
             acc[s][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
             acl[s][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
         }
-    v4u bufB[PER_T];
-    v4u wcur[SR][2], wnext[SR][2];
-    load_stage(0, bufB);
-    load_w(0, wcur);
-    store_stage(0, bufB);
-    __syncthreads();
-    for (int it = 0; it < nk; ++it) {
-        const int st = it & 1;
-        if (it + 1 < nk) {  // next stage's operands are on their way while this one is multiplied
-            load_stage(it + 1, bufB);
-            load_w(it + 1, wnext);
-        }
+    // one k-stage: weights from the ring slot, activations from LDS buffer `buf`
+    auto compute = [&](int buf, const Stage& st) {
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             v4u bh[CT], bl[CT];
 #pragma unroll
             for (int t = 0; t < CT; ++t) {
                 const int row = wm * 16 * CT + t * 16 + r16;
-                bh[t] = *reinterpret_cast<const v4u*>(&lds[st][0][row][ks * 32 + kg * 8]);
-                bl[t] = *reinterpret_cast<const v4u*>(&lds[st][1][row][ks * 32 + kg * 8]);
+                bh[t] = *reinterpret_cast<const v4u*>(&lds[buf][0][row][ks * 32 + kg * 8]);
+                bl[t] = *reinterpret_cast<const v4u*>(&lds[buf][1][row][ks * 32 + kg * 8]);
             }
 #pragma unroll
             for (int s = 0; s < SR; ++s) {
-                const bf16x8 a = __builtin_bit_cast(bf16x8, wcur[s][ks]);
+                const bf16x8 a = __builtin_bit_cast(bf16x8, st.w[s][ks]);
 #pragma unroll
                 for (int t = 0; t < CT; ++t) {
                     acc[s][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bh[t]), acc[s][t], 0, 0, 0);
@@ -133,12 +140,31 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
                 }
             }
         }
-        if (it + 1 < nk) {
-            store_stage(st ^ 1, bufB);
+    };
+    Stage ring[D];   // stage s lives in slot s % D from its request until its last use
 #pragma unroll
-            for (int s = 0; s < SR; ++s) { wcur[s][0] = wnext[s][0]; wcur[s][1] = wnext[s][1]; }
+    for (int j = 0; j < D; ++j) load_stage(j, ring[j]);
+    store_stage(0, ring[0]);
+    lds_barrier();
+    int it = 0;
+    for (; it + D <= nk; it += D) {
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            const int buf = (it + j) & 1;
+            compute(buf, ring[j]);
+            store_stage(buf ^ 1, ring[(j + 1) % D]);   // stage it + j + 1, requested D - 1 stages ago
+            load_stage(it + j + D, ring[j]);
+            lds_barrier();
         }
-        __syncthreads();
+    }
+#pragma unroll
+    for (int j = 0; j < D - 1; ++j) {   // the last nk % D stages: nothing left to request
+        if (it + j < nk) {
+            const int buf = (it + j) & 1;
+            compute(buf, ring[j]);
+            store_stage(buf ^ 1, ring[j + 1]);
+            lds_barrier();
+        }
     }
     // lane holds features n0 + s*16 + 4*kg .. +3 of row m0 + wm*16*CT + t*16 + r16
 #pragma unroll
@@ -147,13 +173,18 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
         for (int t = 0; t < CT; ++t) {
             const int m = m0 + wm * 16 * CT + t * 16 + r16, n = n0 + s * 16 + 4 * kg;
             if (m < M && n < N) {
-                float4* dst = reinterpret_cast<float4*>(Y + (size_t)m * ldy + n);
+                float* dst = Y + (size_t)m * ldy + n;
                 f32x4 v = acc[s][t] + acl[s][t];
-                if (accumulate) {
-                    const float4 old = *dst;
-                    v += (f32x4){old.x, old.y, old.z, old.w};
+                if (gridDim.z > 1) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) unsafeAtomicAdd(dst + e, v[e]);   // the hardware add, not a compare-and-swap loop
+                } else {
+                    if (accumulate) {
+                        const float4 old = *reinterpret_cast<const float4*>(dst);
+                        v += (f32x4){old.x, old.y, old.z, old.w};
+                    }
+                    *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
                 }
-                *dst = make_float4(v[0], v[1], v[2], v[3]);
             }
         }
 }
@@ -172,12 +203,18 @@ bool launch_gemm_mfma(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, i
     split_rows_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, c->stream>>>(wsp<float>(c, off_a), lda, K, hi, lo, total4);
     const uint16_t* W = reinterpret_cast<const uint16_t*>(c->ws + c->off.blob + w_off);
     float* Y = wsp<float>(c, off_y);
+    // K ranges per tile: the accumulating GEMMs with few features (Wo, W2) would otherwise leave
+    // most compute units idle; their partial tiles are added into Y with float atomics.
+    int ksplit = 1;
+    if (accumulate && N <= 2048)
+        for (int f = 4; f > 1; --f)
+            if ((K / kKC) % f == 0) { ksplit = f; break; }
     if (N <= 2048 || M <= 64) {   // few tiles: smaller ones, so that more compute units take part
-        dim3 grid((N + 31) / 32, (M + 63) / 64);
-        gemm_mfma_kernel<1, 2><<<grid, 256, 0, c->stream>>>(hi, lo, W, N, K, Y, ldy, M, accumulate ? 1 : 0);
+        dim3 grid((N + 31) / 32, (M + 63) / 64, ksplit);
+        gemm_mfma_kernel<1, 2, 4><<<grid, 256, 0, c->stream>>>(hi, lo, W, N, K, Y, ldy, M, accumulate ? 1 : 0);
     } else {
-        dim3 grid((N + 63) / 64, (M + 95) / 96);
-        gemm_mfma_kernel<2, 3><<<grid, 256, 0, c->stream>>>(hi, lo, W, N, K, Y, ldy, M, accumulate ? 1 : 0);
+        dim3 grid((N + 63) / 64, (M + 95) / 96, 1);
+        gemm_mfma_kernel<2, 3, 3><<<grid, 256, 0, c->stream>>>(hi, lo, W, N, K, Y, ldy, M, accumulate ? 1 : 0);
     }
     return true;
 }

@@ -247,6 +247,121 @@ __global__ __launch_bounds__(256) void attention_kernel(const typename Cfg::AT* 
     }
 }
 
+// Step rows of the bf16 configuration, one workgroup per (head, sequence): the sequence's k+1 new
+// rows share one pass over its cached keys and one over its values (a workgroup per row would
+// read them k+1 times).  Row r attends entries 0..pos0+r.  RM >= rows per sequence; hd % 8 == 0,
+// 256 % hd == 0.
+template <int RM>
+__global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, const _Float16* Kc, const _Float16* Vc,
+                                                             float* O, RowMap map, int layer, int d, int hd, int Smax,
+                                                             int Tmax) {
+    extern __shared__ double smem_raw[];
+    float* sq = reinterpret_cast<float*>(smem_raw);   // [RM][hd] queries
+    float* sc = sq + RM * hd;                         // [Tmax][RM] scores, then weights
+    float* part = sc + (size_t)Tmax * RM;             // [256 / hd][RM][hd] partial outputs
+    __shared__ float red[4][RM];
+    const int h = blockIdx.x, s = blockIdx.y, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int R0 = s * map.rows_per_seq;
+    const RowInfo r0 = row_info(map, R0);
+    if (!r0.valid) return;
+    const int nrows = min(map.k_eff[r0.b] + 1, RM), pos0 = r0.pos, last = pos0 + nrows - 1;
+    const size_t base = (((size_t)layer * Smax + s) * Tmax) * d + (size_t)h * hd;
+    for (int i = tid; i < RM * hd; i += 256) {
+        const int r = i / hd, c = i - r * hd;
+        sq[i] = r < nrows ? QKV[(size_t)(R0 + r) * 3 * d + (size_t)h * hd + c] : 0.f;
+    }
+    __syncthreads();
+    const float scale = 1.f / sqrtf((float)hd);
+    float mx[RM];
+#pragma unroll
+    for (int r = 0; r < RM; ++r) mx[r] = -INFINITY;
+    typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+    for (int t = tid; t <= last; t += 256) {
+        float a[RM];
+#pragma unroll
+        for (int r = 0; r < RM; ++r) a[r] = 0.f;
+        const h8* kp = reinterpret_cast<const h8*>(Kc + base + (size_t)t * d);
+        for (int c = 0; c < hd / 8; ++c) {
+            const h8 kv = kp[c];
+#pragma unroll
+            for (int r = 0; r < RM; ++r) {
+                const float4 q0 = *reinterpret_cast<const float4*>(sq + r * hd + c * 8);
+                const float4 q1 = *reinterpret_cast<const float4*>(sq + r * hd + c * 8 + 4);
+                a[r] += q0.x * (float)kv[0] + q0.y * (float)kv[1] + q0.z * (float)kv[2] + q0.w * (float)kv[3] +
+                        q1.x * (float)kv[4] + q1.y * (float)kv[5] + q1.z * (float)kv[6] + q1.w * (float)kv[7];
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < RM; ++r) {
+            const float v = (r < nrows && t <= pos0 + r) ? a[r] * scale : -INFINITY;
+            sc[(size_t)t * RM + r] = v;
+            mx[r] = fmaxf(mx[r], v);
+        }
+    }
+    // per-row maximum, then weights and their sum, over the workgroup
+#pragma unroll
+    for (int r = 0; r < RM; ++r) {
+        float v = mx[r];
+        for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+        if (lane == 0) red[wave][r] = v;
+    }
+    __syncthreads();
+    float den[RM];
+#pragma unroll
+    for (int r = 0; r < RM; ++r) {
+        mx[r] = fmaxf(fmaxf(red[0][r], red[1][r]), fmaxf(red[2][r], red[3][r]));
+        den[r] = 0.f;
+    }
+    __syncthreads();
+    for (int t = tid; t <= last; t += 256) {
+#pragma unroll
+        for (int r = 0; r < RM; ++r) {
+            const float v = sc[(size_t)t * RM + r];
+            const float e = (r < nrows && v != -INFINITY) ? expf(v - mx[r]) : 0.f;
+            sc[(size_t)t * RM + r] = e;
+            den[r] += e;
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < RM; ++r) {
+        float v = den[r];
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+        if (lane == 0) red[wave][r] = v;
+    }
+    __syncthreads();   // also orders the sc[] writes before the reads below
+#pragma unroll
+    for (int r = 0; r < RM; ++r) den[r] = (red[0][r] + red[1][r]) + (red[2][r] + red[3][r]);
+    const int i = tid % hd, sl = tid / hd, nsl = 256 / hd;
+    float acc[RM];
+#pragma unroll
+    for (int r = 0; r < RM; ++r) acc[r] = 0.f;
+    const _Float16* vp = Vc + base + i;
+    int t = sl;
+    for (; t + 3 * nsl <= last; t += 4 * nsl) {   // four values in flight per lane
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = (float)vp[(size_t)(t + u * nsl) * d];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int r = 0; r < RM; ++r) acc[r] += sc[(size_t)(t + u * nsl) * RM + r] * v[u];
+    }
+    for (; t <= last; t += nsl) {
+        const float v = (float)vp[(size_t)t * d];
+#pragma unroll
+        for (int r = 0; r < RM; ++r) acc[r] += sc[(size_t)t * RM + r] * v;
+    }
+#pragma unroll
+    for (int r = 0; r < RM; ++r) part[(sl * RM + r) * hd + i] = acc[r];
+    __syncthreads();
+    for (int j = tid; j < nrows * hd; j += 256) {
+        const int r = j / hd, c = j - r * hd;
+        float o = 0.f;
+        for (int s2 = 0; s2 < nsl; ++s2) o += part[(s2 * RM + r) * hd + c];
+        O[(size_t)(R0 + r) * d + (size_t)h * hd + c] = o / den[r];
+    }
+}
+
 template <class Cfg>
 __global__ void swiglu_kernel(typename Cfg::AT* U, int m, size_t total) {
     using AT = typename Cfg::AT;
@@ -349,6 +464,17 @@ void launch_rope_append(hawk_ctx* c, const RowMap& map, int layer, int M) {
 }
 
 void launch_attention(hawk_ctx* c, const RowMap& map, int layer, int M) {
+    constexpr int RM = 8;
+    if (c->cfg.dtype == HAWK_BF16 && map.mode == 1 && map.rows_per_seq <= RM && c->hd % 8 == 0 && 256 % c->hd == 0) {
+        const size_t lds = ((size_t)RM * c->hd + (size_t)c->Tmax * RM + (size_t)(256 / c->hd) * RM * c->hd) * sizeof(float);
+        if (lds <= 60 * 1024) {
+            dim3 grid(c->H, M / map.rows_per_seq);
+            attention_rows_kernel<RM><<<grid, 256, lds, c->stream>>>(
+                wsp<float>(c, c->off.qkv), wsp<_Float16>(c, c->off.kc), wsp<_Float16>(c, c->off.vc),
+                wsp<float>(c, c->off.o), map, layer, c->d, c->hd, c->Smax, c->Tmax);
+            return;
+        }
+    }
     dim3 grid(c->H, M);
     DISPATCH(c, (attention_kernel<Cfg><<<grid, 256, (size_t)(c->Tmax + c->hd + 256) * sizeof(typename Cfg::AT),
                                          c->stream>>>(
