@@ -13,8 +13,7 @@
 //     through LDS (padded rows, double-buffered, 64 k per stage) because all four waves read them;
 //   - D stages are in flight per workgroup, held in a register ring, and the barrier between
 //     stages orders LDS traffic only, so a stage costs its arithmetic and not a memory round trip;
-//   - per k-step a wave issues 2*CT LDS reads for 2*SR*CT MFMAs;
-//   - GEMMs with few output features split K over blockIdx.z and add partial tiles atomically.
+//   - per k-step a wave issues 2*CT LDS reads for 2*SR*CT MFMAs.
 #include "hawk_internal.h"
 
 namespace hawk {
@@ -58,9 +57,7 @@ __global__ void split_rows_kernel(const float* A, int lda, int K, uint16_t* hi, 
 }
 
 // SR: 16-feature strips per wave, CT: 16-row tiles per wave, D: stages (64 k each) in flight.
-// Tile = (32 SR) features x (32 CT) rows; blockIdx.z takes one of gridDim.z equal K ranges and,
-// if there are several, adds its partial tile into Y with float atomics (Y then already holds
-// what is accumulated onto).
+// Tile = (32 SR) features x (32 CT) rows.
 template <int SR, int CT, int D>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restrict__ hi, const uint16_t* __restrict__ lo,
                                                         const uint16_t* __restrict__ W, int N, int K, float* Y, int ldy,
@@ -73,7 +70,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
     const int wn = wave >> 1, wm = wave & 1;                     // wave position over (features, rows)
     const int n0 = blockIdx.x * BN + wn * 16 * SR, m0 = blockIdx.y * BM;
     const int r16 = lane & 15, kg = lane >> 4;
-    const int nk = K / kKC / (int)gridDim.z, it0 = (int)blockIdx.z * nk;   // this block's stages
+    const int nk = K / kKC, it0 = 0;
 
     static_assert(CHUNKS % 256 == 0, "a stage is a whole number of 16-byte chunks per thread");
 
@@ -98,7 +95,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
             const int n = min(n0 + t * 16 + r16, N - 1);
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
-                s.w[t][ks] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(W + (size_t)n * K + k0 + ks * 32 + kg * 8));
+                s.w[t][ks] = *reinterpret_cast<const v4u*>(W + (size_t)n * K + k0 + ks * 32 + kg * 8);
         }
     };
     auto store_stage = [&](int buf, const Stage& s) {
@@ -175,16 +172,11 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
             if (m < M && n < N) {
                 float* dst = Y + (size_t)m * ldy + n;
                 f32x4 v = acc[s][t] + acl[s][t];
-                if (gridDim.z > 1) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) unsafeAtomicAdd(dst + e, v[e]);   // the hardware add, not a compare-and-swap loop
-                } else {
-                    if (accumulate) {
-                        const float4 old = *reinterpret_cast<const float4*>(dst);
-                        v += (f32x4){old.x, old.y, old.z, old.w};
-                    }
-                    *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+                if (accumulate) {
+                    const float4 old = *reinterpret_cast<const float4*>(dst);
+                    v += (f32x4){old.x, old.y, old.z, old.w};
                 }
+                *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
             }
         }
 }
@@ -203,19 +195,28 @@ bool launch_gemm_mfma(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, i
     split_rows_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, c->stream>>>(wsp<float>(c, off_a), lda, K, hi, lo, total4);
     const uint16_t* W = reinterpret_cast<const uint16_t*>(c->ws + c->off.blob + w_off);
     float* Y = wsp<float>(c, off_y);
-    // K ranges per tile: the accumulating GEMMs with few features (Wo, W2) would otherwise leave
-    // most compute units idle; their partial tiles are added into Y with float atomics.
-    int ksplit = 1;
-    if (accumulate && N <= 2048)
-        for (int f = 4; f > 1; --f)
-            if ((K / kKC) % f == 0) { ksplit = f; break; }
-    if (N <= 2048 || M <= 64) {   // few tiles: smaller ones, so that more compute units take part
-        dim3 grid((N + 31) / 32, (M + 63) / 64, ksplit);
-        gemm_mfma_kernel<1, 2, 4><<<grid, 256, 0, c->stream>>>(hi, lo, W, N, K, Y, ldy, M, accumulate ? 1 : 0);
-    } else {
-        dim3 grid((N + 63) / 64, (M + 95) / 96, 1);
-        gemm_mfma_kernel<2, 3, 3><<<grid, 256, 0, c->stream>>>(hi, lo, W, N, K, Y, ldy, M, accumulate ? 1 : 0);
-    }
+    // The smallest tile that still gives every compute unit at most one workgroup: with so few
+    // rows the kernel is bound by what one compute unit can stage and feed per k-stage, so the
+    // work is spread as widely as one round of workgroups allows; larger grids than that only
+    // re-read the activations more often.
+    static const int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        return n;
+    }();
+    auto tiles = [&](int bn, int bm) { return (long)((N + bn - 1) / bn) * ((M + bm - 1) / bm); };
+    const int acc = accumulate ? 1 : 0;
+#define HAWK_GEMM_TILE(SR, CT, D)                                                                      \
+    do {                                                                                               \
+        dim3 grid((N + 32 * SR - 1) / (32 * SR), (M + 32 * CT - 1) / (32 * CT), 1);                    \
+        gemm_mfma_kernel<SR, CT, D><<<grid, 256, 0, c->stream>>>(hi, lo, W, N, K, Y, ldy, M, acc);     \
+    } while (0)
+    if (tiles(32, 32) <= cus) HAWK_GEMM_TILE(1, 1, 4);
+    else if (tiles(32, 64) <= cus) HAWK_GEMM_TILE(1, 2, 4);
+    else if (tiles(32, 96) <= cus) HAWK_GEMM_TILE(1, 3, 4);
+    else if (tiles(64, 96) <= cus) HAWK_GEMM_TILE(2, 3, 3);
+    else HAWK_GEMM_TILE(4, 3, 2);
+#undef HAWK_GEMM_TILE
     return true;
 }
 
