@@ -119,12 +119,12 @@ void run_layers(hawk_ctx* c, const RowMap& map, int M) {
     const Offsets& o = c->off;
     const int d = c->d, m = c->m;
     for (int l = 0; l < c->L; ++l) {
-        launch_rmsnorm(c, o.x, d, c->w.g1[l], o.a, M);
+        launch_rmsnorm(c, o.x, d, c->w.g1[l], o.a, M, true);
         launch_gemm(c, o.a, d, c->w.Wqkv[l], 3 * d, d, o.qkv, 3 * d, M, false, false);
         launch_rope_append(c, map, l, M);
         launch_attention(c, map, l, M);
         launch_gemm(c, o.o, d, c->w.Wo[l], d, d, o.x, d, M, true, false);
-        launch_rmsnorm(c, o.x, d, c->w.g2[l], o.a, M);
+        launch_rmsnorm(c, o.x, d, c->w.g2[l], o.a, M, true);
         launch_gemm(c, o.a, d, c->w.W13[l], 2 * m, d, o.u, 2 * m, M, false, false);
         launch_swiglu(c, M);
         launch_gemm(c, o.u, 2 * m, c->w.W2[l], d, m, o.x, d, M, true, false);
@@ -147,7 +147,7 @@ void run_step_rows(hawk_ctx* c, int k) {
     }
     c->last_path = 0;
     run_layers(c, map, M);
-    launch_rmsnorm(c, c->off.x, c->d, c->w.g_f, c->off.a, M);
+    launch_rmsnorm(c, c->off.x, c->d, c->w.g_f, c->off.a, M, true);
     launch_gemm(c, c->off.a, c->d, slice_off(c), c->Vs, c->d, c->off.logit_s, c->Vs, M, false, true);
 }
 

@@ -27,11 +27,6 @@ typedef unsigned v4u __attribute__((ext_vector_type(4)));
 constexpr int kKC = 64;          // k per LDS stage (two MFMA k-steps)
 constexpr int kLdsK = kKC + 8;   // padded row length in halves
 
-__device__ __forceinline__ unsigned bf16_rne_u(float f) {
-    unsigned u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-
 // Workgroup barrier that orders LDS traffic only: __syncthreads() also waits for every global
 // load in flight, which would end the prefetch of the coming stages at each k-stage.
 __device__ __forceinline__ void lds_barrier() {
@@ -49,9 +44,11 @@ __global__ void split_rows_kernel(const float* A, int lda, int K, uint16_t* hi, 
     const size_t r = i / k4;
     const int j = (int)(i - r * k4) * 4;
     const float4 v = *reinterpret_cast<const float4*>(A + r * lda + j);
-    const unsigned h0 = bf16_rne_u(v.x), h1 = bf16_rne_u(v.y), h2 = bf16_rne_u(v.z), h3 = bf16_rne_u(v.w);
-    const unsigned l0 = bf16_rne_u(v.x - __uint_as_float(h0 << 16)), l1 = bf16_rne_u(v.y - __uint_as_float(h1 << 16));
-    const unsigned l2 = bf16_rne_u(v.z - __uint_as_float(h2 << 16)), l3 = bf16_rne_u(v.w - __uint_as_float(h3 << 16));
+    unsigned h0, h1, h2, h3, l0, l1, l2, l3;
+    bf16_split(v.x, h0, l0);
+    bf16_split(v.y, h1, l1);
+    bf16_split(v.z, h2, l2);
+    bf16_split(v.w, h3, l3);
     *reinterpret_cast<uint2*>(hi + r * K + j) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
     *reinterpret_cast<uint2*>(lo + r * K + j) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
 }
@@ -184,15 +181,32 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
 }  // namespace
 
 // Runs Y (+)= A W^T on the MFMA path if the shape allows; false: the caller uses the generic kernel.
+static bool mfma_input_ok(const hawk_ctx* c, int M, int K) {
+    return c->cfg.dtype == HAWK_BF16 && c->off.split && M >= 9 && K % kKC == 0 && (size_t)M * K * 4 <= c->split_bytes;
+}
+
+bool presplit_planes(hawk_ctx* c, size_t off_a, int M, int K, uint16_t** hi, uint16_t** lo) {
+    if (!mfma_input_ok(c, M, K)) return false;
+    *hi = wsp<uint16_t>(c, c->off.split);
+    *lo = *hi + (size_t)M * K;
+    c->presplit_off = off_a;
+    c->presplit_M = M;
+    c->presplit_K = K;
+    return true;
+}
+
 bool launch_gemm_mfma(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, int K, size_t off_y, int ldy, int M,
                       bool accumulate) {
-    if (c->cfg.dtype != HAWK_BF16 || !c->off.split || M < 9) return false;
-    if (N % 16 || K % kKC || ldy % 4 || lda % 4) return false;
-    if ((size_t)M * K * 4 > c->split_bytes) return false;
+    const bool presplit = c->presplit_off == off_a && c->presplit_M == M && c->presplit_K == K;
+    c->presplit_off = 0;
+    if (!mfma_input_ok(c, M, K)) return false;
+    if (N % 16 || ldy % 4 || lda % 4) return false;
     uint16_t* hi = wsp<uint16_t>(c, c->off.split);
     uint16_t* lo = hi + (size_t)M * K;
-    const size_t total4 = (size_t)M * (K / 4);
-    split_rows_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, c->stream>>>(wsp<float>(c, off_a), lda, K, hi, lo, total4);
+    if (!presplit) {
+        const size_t total4 = (size_t)M * (K / 4);
+        split_rows_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, c->stream>>>(wsp<float>(c, off_a), lda, K, hi, lo, total4);
+    }
     const uint16_t* W = reinterpret_cast<const uint16_t*>(c->ws + c->off.blob + w_off);
     float* Y = wsp<float>(c, off_y);
     // The smallest tile that still gives every compute unit at most one workgroup: with so few

@@ -114,7 +114,7 @@ __global__ void cond_rows_kernel(typename Cfg::AT* X, const float* cond, size_t 
 template <class Cfg>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const typename Cfg::AT* X, const typename Cfg::WT* g,
                                                       typename Cfg::AT* out, int d, size_t in_stride,
-                                                      float eps) {
+                                                      float eps, uint16_t* hi, uint16_t* lo) {
     using AT = typename Cfg::AT;
     __shared__ AT red[4];
     const AT* x = X + (size_t)blockIdx.x * in_stride;
@@ -122,7 +122,16 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const typename Cfg::AT* X,
     for (int i = threadIdx.x; i < d; i += 256) ss += x[i] * x[i];
     ss = block_sum256(ss, red);
     AT r = (AT)1 / sqrt(ss / (AT)d + (AT)eps);
-    for (int i = threadIdx.x; i < d; i += 256) out[(size_t)blockIdx.x * d + i] = x[i] * r * w1(g, i);
+    for (int i = threadIdx.x; i < d; i += 256) {
+        const AT v = x[i] * r * w1(g, i);
+        out[(size_t)blockIdx.x * d + i] = v;
+        if (hi) {   // bf16 planes of the same row for the GEMM that follows
+            unsigned h, l;
+            bf16_split((float)v, h, l);
+            hi[(size_t)blockIdx.x * d + i] = (uint16_t)h;
+            lo[(size_t)blockIdx.x * d + i] = (uint16_t)l;
+        }
+    }
 }
 
 // ------------------------------------------------------------------ skinny GEMM
@@ -254,7 +263,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const typename Cfg::AT* 
 template <int RM>
 __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, const _Float16* Kc, const _Float16* Vc,
                                                              float* O, RowMap map, int layer, int d, int hd, int Smax,
-                                                             int Tmax) {
+                                                             int Tmax, uint16_t* hi, uint16_t* lo) {
     extern __shared__ double smem_raw[];
     float* sq = reinterpret_cast<float*>(smem_raw);   // [RM][hd] queries
     float* sc = sq + RM * hd;                         // [Tmax][RM] scores, then weights
@@ -263,8 +272,15 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, c
     const int h = blockIdx.x, s = blockIdx.y, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int R0 = s * map.rows_per_seq;
     const RowInfo r0 = row_info(map, R0);
+    const int nrows = r0.valid ? min(map.k_eff[r0.b] + 1, RM) : 0;
+    if (hi)   // rows not in flight: defined planes (their results are never used)
+        for (int j = nrows * hd + tid; j < map.rows_per_seq * hd; j += 256) {
+            const size_t at = (size_t)(R0 + j / hd) * d + (size_t)h * hd + j % hd;
+            hi[at] = 0;
+            lo[at] = 0;
+        }
     if (!r0.valid) return;
-    const int nrows = min(map.k_eff[r0.b] + 1, RM), pos0 = r0.pos, last = pos0 + nrows - 1;
+    const int pos0 = r0.pos, last = pos0 + nrows - 1;
     const size_t base = (((size_t)layer * Smax + s) * Tmax) * d + (size_t)h * hd;
     for (int i = tid; i < RM * hd; i += 256) {
         const int r = i / hd, c = i - r * hd;
@@ -358,18 +374,33 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, c
         const int r = j / hd, c = j - r * hd;
         float o = 0.f;
         for (int s2 = 0; s2 < nsl; ++s2) o += part[(s2 * RM + r) * hd + c];
-        O[(size_t)(R0 + r) * d + (size_t)h * hd + c] = o / den[r];
+        const float v = o / den[r];
+        const size_t at = (size_t)(R0 + r) * d + (size_t)h * hd + c;
+        O[at] = v;
+        if (hi) {   // bf16 planes for the Wo GEMM that follows
+            unsigned hh, ll;
+            bf16_split(v, hh, ll);
+            hi[at] = (uint16_t)hh;
+            lo[at] = (uint16_t)ll;
+        }
     }
 }
 
 template <class Cfg>
-__global__ void swiglu_kernel(typename Cfg::AT* U, int m, size_t total) {
+__global__ void swiglu_kernel(typename Cfg::AT* U, int m, size_t total, uint16_t* hi, uint16_t* lo) {
     using AT = typename Cfg::AT;
     size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= total) return;
     size_t row = idx / m, i = idx - row * m;
     AT a = U[row * 2 * m + i], b = U[row * 2 * m + m + i];
-    U[row * 2 * m + i] = a / ((AT)1 + exp(-a)) * b;
+    const AT v = a / ((AT)1 + exp(-a)) * b;
+    U[row * 2 * m + i] = v;
+    if (hi) {   // bf16 planes [row][m] for the GEMM that follows
+        unsigned h, l;
+        bf16_split((float)v, h, l);
+        hi[idx] = (uint16_t)h;
+        lo[idx] = (uint16_t)l;
+    }
 }
 
 // ------------------------------------------------------------------ draft head input
@@ -434,10 +465,13 @@ void launch_cond_rows(hawk_ctx* c, int M) {
                     wsp<typename Cfg::AT>(c, c->off.x), wsp<float>(c, c->off.cond), total)));
 }
 
-void launch_rmsnorm(hawk_ctx* c, size_t off_in, size_t in_stride, size_t off_gain, size_t off_out, int M) {
+void launch_rmsnorm(hawk_ctx* c, size_t off_in, size_t in_stride, size_t off_gain, size_t off_out, int M,
+                    bool for_gemm) {
+    uint16_t *hi = nullptr, *lo = nullptr;
+    if (for_gemm) presplit_planes(c, off_out, M, c->d, &hi, &lo);
     DISPATCH(c, (rmsnorm_kernel<Cfg><<<M, 256, 0, c->stream>>>(
                     wsp<typename Cfg::AT>(c, off_in), wptr<Cfg>(c, off_gain), wsp<typename Cfg::AT>(c, off_out),
-                    c->d, in_stride, c->cfg.rms_eps)));
+                    c->d, in_stride, c->cfg.rms_eps, hi, lo)));
 }
 
 void launch_gemm(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, int K, size_t off_y, int ldy,
@@ -469,9 +503,11 @@ void launch_attention(hawk_ctx* c, const RowMap& map, int layer, int M) {
         const size_t lds = ((size_t)RM * c->hd + (size_t)c->Tmax * RM + (size_t)(256 / c->hd) * RM * c->hd) * sizeof(float);
         if (lds <= 60 * 1024) {
             dim3 grid(c->H, M / map.rows_per_seq);
+            uint16_t *hi = nullptr, *lo = nullptr;
+            presplit_planes(c, c->off.o, M, c->d, &hi, &lo);   // the Wo GEMM reads the result next
             attention_rows_kernel<RM><<<grid, 256, lds, c->stream>>>(
                 wsp<float>(c, c->off.qkv), wsp<_Float16>(c, c->off.kc), wsp<_Float16>(c, c->off.vc),
-                wsp<float>(c, c->off.o), map, layer, c->d, c->hd, c->Smax, c->Tmax);
+                wsp<float>(c, c->off.o), map, layer, c->d, c->hd, c->Smax, c->Tmax, hi, lo);
             return;
         }
     }
@@ -485,8 +521,10 @@ void launch_attention(hawk_ctx* c, const RowMap& map, int layer, int M) {
 
 void launch_swiglu(hawk_ctx* c, int M) {
     size_t total = (size_t)M * c->m;
+    uint16_t *hi = nullptr, *lo = nullptr;
+    presplit_planes(c, c->off.u, M, c->m, &hi, &lo);   // the W2 GEMM reads the result next
     DISPATCH(c, (swiglu_kernel<Cfg><<<(unsigned)((total + 255) / 256), 256, 0, c->stream>>>(
-                    wsp<typename Cfg::AT>(c, c->off.u), c->m, total)));
+                    wsp<typename Cfg::AT>(c, c->off.u), c->m, total, hi, lo)));
 }
 
 void launch_draft_input(hawk_ctx* c, int i) {

@@ -83,6 +83,8 @@ struct hawk_ctx {
     hawk::StreamPlan* plan;  // streaming path: job tables and barrier epoch (null until created)
     size_t blob_bytes;
     size_t split_bytes;
+    size_t presplit_off;  // activation buffer whose bf16 planes are current (presplit_M rows of presplit_K), 0: none
+    int presplit_M, presplit_K;
     // per image
     int B, S, C, gh, gw, N, top_k, greedy;
     float temperature, inv_t, cfg_scale;
@@ -102,19 +104,33 @@ struct hawk_ctx {
 
 namespace hawk {
 
+// fp32 -> bf16 hi (round to nearest even) and the bf16 remainder: v ~ hi + lo to about 16 bits
+__device__ __forceinline__ void bf16_split(float v, unsigned& hi, unsigned& lo) {
+    unsigned u = __float_as_uint(v);
+    hi = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    u = __float_as_uint(v - __uint_as_float(hi << 16));
+    lo = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
 template <typename T> inline T* wsp(hawk_ctx* c, size_t off) { return reinterpret_cast<T*>(c->ws + off); }
 
 // ---- launchers implemented in generic.hip (dtype chosen from ctx->cfg.dtype) ----
 void launch_embed_rows(hawk_ctx*, const RowMap&, int M);
 void launch_cond_rows(hawk_ctx*, int M);                       // X <- condition vectors
 // out[r] = rmsnorm(in[r * in_stride ...]) * gain, r < M (in_stride in elements)
-void launch_rmsnorm(hawk_ctx*, size_t off_in, size_t in_stride, size_t off_gain, size_t off_out, int M);
+// for_gemm: the next call is the GEMM that reads the output; its bf16 planes are written here too
+void launch_rmsnorm(hawk_ctx*, size_t off_in, size_t in_stride, size_t off_gain, size_t off_out, int M,
+                    bool for_gemm = false);
 // Y[M][N] (+)= A[M][K] * W[N][K]^T ; out_f32: store fp32 (logits) instead of activations
 void launch_gemm(hawk_ctx*, size_t off_a, int lda, size_t w_off, int N, int K, size_t off_y,
                  int ldy, int M, bool accumulate, bool out_f32);
 // the same on the MFMA units (bf16, many rows); false if the shape is not covered (gemm.hip)
 bool launch_gemm_mfma(hawk_ctx*, size_t off_a, int lda, size_t w_off, int N, int K, size_t off_y, int ldy, int M,
                       bool accumulate);
+// A kernel that produces the input of the next GEMM (M rows of K values at off_a) can write that
+// GEMM's bf16 hi / lo planes itself, [row][K] each: true and the planes if such a GEMM takes the
+// MFMA path; the planes then count as current until the next launch_gemm call.
+bool presplit_planes(hawk_ctx*, size_t off_a, int M, int K, uint16_t** hi, uint16_t** lo);
 void launch_rope_append(hawk_ctx*, const RowMap&, int layer, int M);
 void launch_attention(hawk_ctx*, const RowMap&, int layer, int M);
 void launch_swiglu(hawk_ctx*, int M);
