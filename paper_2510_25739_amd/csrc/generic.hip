@@ -258,8 +258,8 @@ __global__ __launch_bounds__(256) void attention_kernel(const typename Cfg::AT* 
 
 // Step rows of the bf16 configuration, one workgroup per (head, sequence): the sequence's k+1 new
 // rows share one pass over its cached keys and one over its values (a workgroup per row would
-// read them k+1 times).  Row r attends entries 0..pos0+r.  RM >= rows per sequence; hd % 8 == 0,
-// 256 % hd == 0.
+// read them k+1 times).  Row r attends entries 0..pos0+r.  RM >= rows per sequence, RM % 4 == 0;
+// hd % 64 == 0, hd / 8 a power of two <= 64.
 template <int RM>
 __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, const _Float16* Kc, const _Float16* Vc,
                                                              float* O, RowMap map, int layer, int d, int hd, int Smax,
@@ -267,7 +267,7 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, c
     extern __shared__ double smem_raw[];
     float* sq = reinterpret_cast<float*>(smem_raw);   // [RM][hd] queries
     float* sc = sq + RM * hd;                         // [Tmax][RM] scores, then weights
-    float* part = sc + (size_t)Tmax * RM;             // [256 / hd][RM][hd] partial outputs
+    float* part = sc + (size_t)Tmax * RM;             // [4 waves][RM][hd] partial outputs
     __shared__ float red[4][RM];
     const int h = blockIdx.x, s = blockIdx.y, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int R0 = s * map.rows_per_seq;
@@ -292,26 +292,49 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, c
 #pragma unroll
     for (int r = 0; r < RM; ++r) mx[r] = -INFINITY;
     typedef _Float16 h8 __attribute__((ext_vector_type(8)));
-    for (int t = tid; t <= last; t += 256) {
-        float a[RM];
+    // scores: a lane takes whole keys, two at a time, and requests all of a key's 64-feature block
+    // before using it (16 loads of 16 bytes in flight per lane)
+    for (int t0 = tid; t0 <= last; t0 += 512) {
+        const int t1 = t0 + 256;
+        const bool two = t1 <= last;
+        float a[2][RM];
 #pragma unroll
-        for (int r = 0; r < RM; ++r) a[r] = 0.f;
-        const h8* kp = reinterpret_cast<const h8*>(Kc + base + (size_t)t * d);
-        for (int c = 0; c < hd / 8; ++c) {
-            const h8 kv = kp[c];
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int r = 0; r < RM; ++r) {
-                const float4 q0 = *reinterpret_cast<const float4*>(sq + r * hd + c * 8);
-                const float4 q1 = *reinterpret_cast<const float4*>(sq + r * hd + c * 8 + 4);
-                a[r] += q0.x * (float)kv[0] + q0.y * (float)kv[1] + q0.z * (float)kv[2] + q0.w * (float)kv[3] +
-                        q1.x * (float)kv[4] + q1.y * (float)kv[5] + q1.z * (float)kv[6] + q1.w * (float)kv[7];
+            for (int r = 0; r < RM; ++r) a[u][r] = 0.f;
+        const h8* kp0 = reinterpret_cast<const h8*>(Kc + base + (size_t)t0 * d);
+        const h8* kp1 = reinterpret_cast<const h8*>(Kc + base + (size_t)(two ? t1 : t0) * d);
+        for (int cb = 0; cb < hd / 8; cb += 8) {
+            h8 kv[2][8];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                kv[0][c] = kp0[cb + c];
+                kv[1][c] = kp1[cb + c];
             }
+#pragma unroll
+            for (int c = 0; c < 8; ++c)
+#pragma unroll
+                for (int r = 0; r < RM; ++r) {
+                    const float4 q0 = *reinterpret_cast<const float4*>(sq + r * hd + (cb + c) * 8);
+                    const float4 q1 = *reinterpret_cast<const float4*>(sq + r * hd + (cb + c) * 8 + 4);
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        const h8 k8 = kv[u][c];
+                        a[u][r] += q0.x * (float)k8[0] + q0.y * (float)k8[1] + q0.z * (float)k8[2] + q0.w * (float)k8[3] +
+                                   q1.x * (float)k8[4] + q1.y * (float)k8[5] + q1.z * (float)k8[6] + q1.w * (float)k8[7];
+                    }
+                }
         }
 #pragma unroll
-        for (int r = 0; r < RM; ++r) {
-            const float v = (r < nrows && t <= pos0 + r) ? a[r] * scale : -INFINITY;
-            sc[(size_t)t * RM + r] = v;
-            mx[r] = fmaxf(mx[r], v);
+        for (int u = 0; u < 2; ++u) {
+            const int t = u ? t1 : t0;
+            if (u && !two) break;
+#pragma unroll
+            for (int r = 0; r < RM; ++r) {
+                const float v = (r < nrows && t <= pos0 + r) ? a[u][r] * scale : -INFINITY;
+                sc[(size_t)t * RM + r] = v;
+                mx[r] = fmaxf(mx[r], v);
+            }
         }
     }
     // per-row maximum, then weights and their sum, over the workgroup
@@ -347,33 +370,59 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, c
     __syncthreads();   // also orders the sc[] writes before the reads below
 #pragma unroll
     for (int r = 0; r < RM; ++r) den[r] = (red[0][r] + red[1][r]) + (red[2][r] + red[3][r]);
-    const int i = tid % hd, sl = tid / hd, nsl = 256 / hd;
-    float acc[RM];
+    // weighted values: a lane takes 8 features (16 bytes) of every (256 / (hd / 8))-th entry, so a
+    // wave requests whole rows of the head; partial sums are folded over the lanes that share a
+    // feature group, then over the waves through LDS
+    const int cpr = hd / 8, c8 = tid % cpr, nsl = 256 / cpr, sl = tid / cpr;   // chunks per row, slices
+    float acc[RM][8];
 #pragma unroll
-    for (int r = 0; r < RM; ++r) acc[r] = 0.f;
-    const _Float16* vp = Vc + base + i;
+    for (int r = 0; r < RM; ++r)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[r][e] = 0.f;
+    const _Float16* vp = Vc + base + c8 * 8;
+    auto fold = [&](int t, const h8& v) {
+        float p[RM];
+#pragma unroll
+        for (int r = 0; r < RM; r += 4) {
+            const float4 q = *reinterpret_cast<const float4*>(sc + (size_t)t * RM + r);
+            p[r] = q.x;
+            if (r + 1 < RM) p[r + 1] = q.y;
+            if (r + 2 < RM) p[r + 2] = q.z;
+            if (r + 3 < RM) p[r + 3] = q.w;
+        }
+#pragma unroll
+        for (int r = 0; r < RM; ++r)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[r][e] += p[r] * (float)v[e];
+    };
     int t = sl;
-    for (; t + 3 * nsl <= last; t += 4 * nsl) {   // four values in flight per lane
-        float v[4];
+    for (; t + 3 * nsl <= last; t += 4 * nsl) {   // four rows in flight per lane
+        h8 v[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = (float)vp[(size_t)(t + u * nsl) * d];
+        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const h8*>(vp + (size_t)(t + u * nsl) * d);
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-            for (int r = 0; r < RM; ++r) acc[r] += sc[(size_t)(t + u * nsl) * RM + r] * v[u];
+        for (int u = 0; u < 4; ++u) fold(t + u * nsl, v[u]);
     }
-    for (; t <= last; t += nsl) {
-        const float v = (float)vp[(size_t)t * d];
+    for (; t <= last; t += nsl) fold(t, *reinterpret_cast<const h8*>(vp + (size_t)t * d));
+    // lanes of a wave with the same c8 differ in lane / cpr
 #pragma unroll
-        for (int r = 0; r < RM; ++r) acc[r] += sc[(size_t)t * RM + r] * v;
+    for (int r = 0; r < RM; ++r)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float v = acc[r][e];
+            for (int o = cpr; o < 64; o <<= 1) v += __shfl_xor(v, o);
+            acc[r][e] = v;
+        }
+    if (lane < cpr) {
+#pragma unroll
+        for (int r = 0; r < RM; ++r)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) part[(wave * RM + r) * hd + lane * 8 + e] = acc[r][e];
     }
-#pragma unroll
-    for (int r = 0; r < RM; ++r) part[(sl * RM + r) * hd + i] = acc[r];
     __syncthreads();
     for (int j = tid; j < nrows * hd; j += 256) {
         const int r = j / hd, c = j - r * hd;
-        float o = 0.f;
-        for (int s2 = 0; s2 < nsl; ++s2) o += part[(s2 * RM + r) * hd + c];
+        const float o = (part[r * hd + c] + part[(RM + r) * hd + c]) + (part[(2 * RM + r) * hd + c] + part[(3 * RM + r) * hd + c]);
         const float v = o / den[r];
         const size_t at = (size_t)(R0 + r) * d + (size_t)h * hd + c;
         O[at] = v;
@@ -499,15 +548,22 @@ void launch_rope_append(hawk_ctx* c, const RowMap& map, int layer, int M) {
 
 void launch_attention(hawk_ctx* c, const RowMap& map, int layer, int M) {
     constexpr int RM = 8;
-    if (c->cfg.dtype == HAWK_BF16 && map.mode == 1 && map.rows_per_seq <= RM && c->hd % 8 == 0 && 256 % c->hd == 0) {
-        const size_t lds = ((size_t)RM * c->hd + (size_t)c->Tmax * RM + (size_t)(256 / c->hd) * RM * c->hd) * sizeof(float);
+    const int cpr = c->hd / 8;
+    if (c->cfg.dtype == HAWK_BF16 && map.mode == 1 && map.rows_per_seq <= RM && c->hd % 64 == 0 && cpr <= 64 &&
+        (cpr & (cpr - 1)) == 0) {
+        const size_t lds = ((size_t)RM * c->hd + (size_t)c->Tmax * RM + (size_t)4 * RM * c->hd) * sizeof(float);
         if (lds <= 60 * 1024) {
             dim3 grid(c->H, M / map.rows_per_seq);
             uint16_t *hi = nullptr, *lo = nullptr;
             presplit_planes(c, c->off.o, M, c->d, &hi, &lo);   // the Wo GEMM reads the result next
-            attention_rows_kernel<RM><<<grid, 256, lds, c->stream>>>(
-                wsp<float>(c, c->off.qkv), wsp<_Float16>(c, c->off.kc), wsp<_Float16>(c, c->off.vc),
-                wsp<float>(c, c->off.o), map, layer, c->d, c->hd, c->Smax, c->Tmax, hi, lo);
+            if (map.rows_per_seq <= 4)
+                attention_rows_kernel<4><<<grid, 256, lds, c->stream>>>(
+                    wsp<float>(c, c->off.qkv), wsp<_Float16>(c, c->off.kc), wsp<_Float16>(c, c->off.vc),
+                    wsp<float>(c, c->off.o), map, layer, c->d, c->hd, c->Smax, c->Tmax, hi, lo);
+            else
+                attention_rows_kernel<RM><<<grid, 256, lds, c->stream>>>(
+                    wsp<float>(c, c->off.qkv), wsp<_Float16>(c, c->off.kc), wsp<_Float16>(c, c->off.vc),
+                    wsp<float>(c, c->off.o), map, layer, c->d, c->hd, c->Smax, c->Tmax, hi, lo);
             return;
         }
     }
