@@ -256,7 +256,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const typename Cfg::AT* 
     }
 }
 
-// Step rows of the bf16 configuration, one workgroup per (head, sequence): the sequence's k+1 new
+// Step rows of the bf16 configuration, one workgroup per (sequence, head): the sequence's k+1 new
 // rows share one pass over its cached keys and one over its values (a workgroup per row would
 // read them k+1 times).  Row r attends entries 0..pos0+r.  RM >= rows per sequence, RM % 4 == 0;
 // hd % 64 == 0, hd / 8 a power of two <= 64.
@@ -269,7 +269,10 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, c
     float* sc = sq + RM * hd;                         // [Tmax][RM] scores, then weights
     float* part = sc + (size_t)Tmax * RM;             // [4 waves][RM][hd] partial outputs
     __shared__ float red[4][RM];
-    const int h = blockIdx.x, s = blockIdx.y, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    // sequences along x: consecutive workgroup ids go to the XCDs in turn, so with the sequence
+    // count a multiple of the XCD count all heads of a sequence - which share every 2d-byte cache
+    // row - run on one XCD at about the same time (one L2, open DRAM pages)
+    const int s = blockIdx.x, h = blockIdx.y, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int R0 = s * map.rows_per_seq;
     const RowInfo r0 = row_info(map, R0);
     const int nrows = r0.valid ? min(map.k_eff[r0.b] + 1, RM) : 0;
@@ -288,62 +291,65 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, c
     }
     __syncthreads();
     const float scale = 1.f / sqrtf((float)hd);
-    float mx[RM];
-#pragma unroll
-    for (int r = 0; r < RM; ++r) mx[r] = -INFINITY;
     typedef _Float16 h8 __attribute__((ext_vector_type(8)));
-    // scores: a lane takes whole keys, two at a time, and requests all of a key's 64-feature block
-    // before using it (16 loads of 16 bytes in flight per lane)
-    for (int t0 = tid; t0 <= last; t0 += 512) {
-        const int t1 = t0 + 256;
-        const bool two = t1 <= last;
-        float a[2][RM];
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int r = 0; r < RM; ++r) a[u][r] = 0.f;
-        const h8* kp0 = reinterpret_cast<const h8*>(Kc + base + (size_t)t0 * d);
-        const h8* kp1 = reinterpret_cast<const h8*>(Kc + base + (size_t)(two ? t1 : t0) * d);
-        for (int cb = 0; cb < hd / 8; cb += 8) {
-            h8 kv[2][8];
-#pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                kv[0][c] = kp0[cb + c];
-                kv[1][c] = kp1[cb + c];
-            }
-#pragma unroll
-            for (int c = 0; c < 8; ++c)
-#pragma unroll
-                for (int r = 0; r < RM; ++r) {
-                    const float4 q0 = *reinterpret_cast<const float4*>(sq + r * hd + (cb + c) * 8);
-                    const float4 q1 = *reinterpret_cast<const float4*>(sq + r * hd + (cb + c) * 8 + 4);
-#pragma unroll
-                    for (int u = 0; u < 2; ++u) {
-                        const h8 k8 = kv[u][c];
-                        a[u][r] += q0.x * (float)k8[0] + q0.y * (float)k8[1] + q0.z * (float)k8[2] + q0.w * (float)k8[3] +
-                                   q1.x * (float)k8[4] + q1.y * (float)k8[5] + q1.z * (float)k8[6] + q1.w * (float)k8[7];
-                    }
-                }
-        }
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int t = u ? t1 : t0;
-            if (u && !two) break;
-#pragma unroll
-            for (int r = 0; r < RM; ++r) {
-                const float v = (r < nrows && t <= pos0 + r) ? a[u][r] * scale : -INFINITY;
-                sc[(size_t)t * RM + r] = v;
-                mx[r] = fmaxf(mx[r], v);
-            }
-        }
-    }
-    // per-row maximum, then weights and their sum, over the workgroup
+    // A lane takes 8 features (16 bytes) of every (256 / (hd / 8))-th cache entry, so a wave
+    // requests whole rows of the head (a lane per entry would touch 64 cache lines per request and
+    // fetch each of them hd / 8 times).
+    const int cpr = hd / 8, c8 = tid % cpr, nsl = 256 / cpr, sl = tid / cpr;   // chunks per row, slices
+    // scores: partial dot products over the lane's features, folded over the cpr lanes of an entry
+    // so that lane l ends up with the score of row l % RM
+    float q[RM][8];
 #pragma unroll
     for (int r = 0; r < RM; ++r) {
-        float v = mx[r];
-        for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-        if (lane == 0) red[wave][r] = v;
+        const float4 q0 = *reinterpret_cast<const float4*>(sq + r * hd + c8 * 8);
+        const float4 q1 = *reinterpret_cast<const float4*>(sq + r * hd + c8 * 8 + 4);
+        q[r][0] = q0.x * scale; q[r][1] = q0.y * scale; q[r][2] = q0.z * scale; q[r][3] = q0.w * scale;
+        q[r][4] = q1.x * scale; q[r][5] = q1.y * scale; q[r][6] = q1.z * scale; q[r][7] = q1.w * scale;
     }
+    const int myr = lane % RM;
+    float mxl = -INFINITY;
+    {
+        const _Float16* kp = Kc + base + c8 * 8;
+        auto score = [&](int t, const h8& k8) {
+            float a[RM];
+#pragma unroll
+            for (int r = 0; r < RM; ++r) {
+                float acc = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc += q[r][e] * (float)k8[e];
+                a[r] = acc;
+            }
+            for (int w = cpr; w > RM; w >>= 1)   // more lanes than rows: plain folds first
+#pragma unroll
+                for (int r = 0; r < RM; ++r) a[r] += __shfl_xor(a[r], w >> 1);
+#pragma unroll
+            for (int n = RM; n > 1; n >>= 1) {   // then each fold halves the rows a lane carries
+                const int hb = n >> 1;
+                const bool up = (lane & hb) != 0;
+#pragma unroll
+                for (int i = 0; i < hb; ++i) {
+                    const float send = up ? a[i] : a[i + hb], keep = up ? a[i + hb] : a[i];
+                    a[i] = keep + __shfl_xor(send, hb);
+                }
+            }
+            const float v = (t <= last && myr < nrows && t <= pos0 + myr) ? a[0] : -INFINITY;
+            if (t <= last && c8 < RM) sc[(size_t)t * RM + myr] = v;
+            mxl = fmaxf(mxl, v);
+        };
+        const int nj = (last + nsl) / nsl;   // the same trip count for every lane: the folds need whole groups
+        for (int j0 = 0; j0 < nj; j0 += 4) {
+            h8 k8[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                k8[u] = *reinterpret_cast<const h8*>(kp + (size_t)min(sl + (j0 + u) * nsl, last) * d);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) score(sl + (j0 + u) * nsl, k8[u]);
+        }
+    }
+    // per-row maximum over the workgroup (lanes l, l + RM, ... of a wave hold row l % RM)
+    for (int o = RM; o < 64; o <<= 1) mxl = fmaxf(mxl, __shfl_xor(mxl, o));
+    if (lane < RM) red[wave][lane] = mxl;
+    float mx[RM];
     __syncthreads();
     float den[RM];
 #pragma unroll
@@ -370,10 +376,8 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, c
     __syncthreads();   // also orders the sc[] writes before the reads below
 #pragma unroll
     for (int r = 0; r < RM; ++r) den[r] = (red[0][r] + red[1][r]) + (red[2][r] + red[3][r]);
-    // weighted values: a lane takes 8 features (16 bytes) of every (256 / (hd / 8))-th entry, so a
-    // wave requests whole rows of the head; partial sums are folded over the lanes that share a
+    // weighted values, same lane layout; partial sums are folded over the lanes that share a
     // feature group, then over the waves through LDS
-    const int cpr = hd / 8, c8 = tid % cpr, nsl = 256 / cpr, sl = tid / cpr;   // chunks per row, slices
     float acc[RM][8];
 #pragma unroll
     for (int r = 0; r < RM; ++r)
@@ -553,7 +557,7 @@ void launch_attention(hawk_ctx* c, const RowMap& map, int layer, int M) {
         (cpr & (cpr - 1)) == 0) {
         const size_t lds = ((size_t)RM * c->hd + (size_t)c->Tmax * RM + (size_t)4 * RM * c->hd) * sizeof(float);
         if (lds <= 60 * 1024) {
-            dim3 grid(c->H, M / map.rows_per_seq);
+            dim3 grid(M / map.rows_per_seq, c->H);
             uint16_t *hi = nullptr, *lo = nullptr;
             presplit_planes(c, c->off.o, M, c->d, &hi, &lo);   // the Wo GEMM reads the result next
             if (map.rows_per_seq <= 4)
