@@ -256,11 +256,18 @@ __global__ __launch_bounds__(256) void attention_kernel(const typename Cfg::AT* 
     }
 }
 
+// v of another lane of the same 16-lane row, chosen by a DPP control: 0xB1 lane ^ 1, 0x4E lane ^ 2
+// (quad permutes), 0x141 lane l <-> 7 - l within each 8 lanes, 0x140 l <-> 15 - l within the row.
+template <int CTRL> __device__ __forceinline__ float dpp_lane(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+
 // Step rows of the bf16 configuration, one workgroup per (sequence, head): the sequence's k+1 new
 // rows share one pass over its cached keys and one over its values (a workgroup per row would
-// read them k+1 times).  Row r attends entries 0..pos0+r.  RM >= rows per sequence, RM % 4 == 0;
-// hd % 64 == 0, hd / 8 a power of two <= 64.
-template <int RM>
+// read them k+1 times).  Row r attends entries 0..pos0+r.  RM (4 or 8) >= NR >= rows per sequence:
+// storage and lane folds are laid out for RM rows, arithmetic is spent on NR;
+// hd = 64 or 128.
+template <int RM, int NR>
 __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, const _Float16* Kc, const _Float16* Vc,
                                                              float* O, RowMap map, int layer, int d, int hd, int Smax,
                                                              int Tmax, uint16_t* hi, uint16_t* lo) {
@@ -306,6 +313,7 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, c
         q[r][0] = q0.x * scale; q[r][1] = q0.y * scale; q[r][2] = q0.z * scale; q[r][3] = q0.w * scale;
         q[r][4] = q1.x * scale; q[r][5] = q1.y * scale; q[r][6] = q1.z * scale; q[r][7] = q1.w * scale;
     }
+    static_assert(RM == 4 || RM == 8, "the lane folds are written for 4 or 8 rows");
     const int myr = lane % RM;
     float mxl = -INFINITY;
     {
@@ -315,35 +323,55 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, c
 #pragma unroll
             for (int r = 0; r < RM; ++r) {
                 float acc = 0.f;
+                if (r < NR) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc += q[r][e] * (float)k8[e];
+                    for (int e = 0; e < 8; ++e) acc += q[r][e] * (float)k8[e];
+                }
                 a[r] = acc;
             }
-            for (int w = cpr; w > RM; w >>= 1)   // more lanes than rows: plain folds first
+            // fold over the entry's cpr consecutive lanes with DPP moves: while there are more lanes
+            // than rows every lane adds its partner's values, then each fold halves the rows a lane
+            // carries (the partner keeps the other half)
+            if (cpr == 16) {
 #pragma unroll
-                for (int r = 0; r < RM; ++r) a[r] += __shfl_xor(a[r], w >> 1);
+                for (int r = 0; r < RM; ++r) a[r] += dpp_lane<0x140>(a[r]);
+            }
+            if constexpr (RM == 8) {
+                const bool up = (lane & 4) != 0;
 #pragma unroll
-            for (int n = RM; n > 1; n >>= 1) {   // then each fold halves the rows a lane carries
-                const int hb = n >> 1;
-                const bool up = (lane & hb) != 0;
-#pragma unroll
-                for (int i = 0; i < hb; ++i) {
-                    const float send = up ? a[i] : a[i + hb], keep = up ? a[i + hb] : a[i];
-                    a[i] = keep + __shfl_xor(send, hb);
+                for (int i = 0; i < 4; ++i) {
+                    const float send = up ? a[i] : a[i + 4], keep = up ? a[i + 4] : a[i];
+                    a[i] = keep + dpp_lane<0x141>(send);
                 }
+            } else {
+#pragma unroll
+                for (int r = 0; r < RM; ++r) a[r] += dpp_lane<0x141>(a[r]);
+            }
+            {
+                const bool up = (lane & 2) != 0;
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const float send = up ? a[i] : a[i + 2], keep = up ? a[i + 2] : a[i];
+                    a[i] = keep + dpp_lane<0x4E>(send);
+                }
+            }
+            {
+                const bool up = (lane & 1) != 0;
+                const float send = up ? a[0] : a[1], keep = up ? a[1] : a[0];
+                a[0] = keep + dpp_lane<0xB1>(send);
             }
             const float v = (t <= last && myr < nrows && t <= pos0 + myr) ? a[0] : -INFINITY;
             if (t <= last && c8 < RM) sc[(size_t)t * RM + myr] = v;
             mxl = fmaxf(mxl, v);
         };
         const int nj = (last + nsl) / nsl;   // the same trip count for every lane: the folds need whole groups
-        for (int j0 = 0; j0 < nj; j0 += 4) {
-            h8 k8[4];
+        for (int j0 = 0; j0 < nj; j0 += 8) {   // eight entries in flight per lane
+            h8 k8[8];
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < 8; ++u)
                 k8[u] = *reinterpret_cast<const h8*>(kp + (size_t)min(sl + (j0 + u) * nsl, last) * d);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) score(sl + (j0 + u) * nsl, k8[u]);
+            for (int u = 0; u < 8; ++u) score(sl + (j0 + u) * nsl, k8[u]);
         }
     }
     // per-row maximum over the workgroup (lanes l, l + RM, ... of a wave hold row l % RM)
@@ -376,52 +404,55 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, c
     __syncthreads();   // also orders the sc[] writes before the reads below
 #pragma unroll
     for (int r = 0; r < RM; ++r) den[r] = (red[0][r] + red[1][r]) + (red[2][r] + red[3][r]);
-    // weighted values, same lane layout; partial sums are folded over the lanes that share a
-    // feature group, then over the waves through LDS
+    // weighted values: here the lanes that share a feature group sit next to each other (lane =
+    // group * slots + slot, a slot takes every nsv-th entry), so that their partial sums fold with
+    // DPP moves; a wave still requests whole rows of the head
+    const int slots = 64 / cpr, c8v = lane / slots, nsv = 4 * slots, slv = wave * slots + lane % slots;
     float acc[RM][8];
 #pragma unroll
     for (int r = 0; r < RM; ++r)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[r][e] = 0.f;
-    const _Float16* vp = Vc + base + c8 * 8;
+    const _Float16* vp = Vc + base + c8v * 8;
     auto fold = [&](int t, const h8& v) {
         float p[RM];
 #pragma unroll
         for (int r = 0; r < RM; r += 4) {
-            const float4 q = *reinterpret_cast<const float4*>(sc + (size_t)t * RM + r);
-            p[r] = q.x;
-            if (r + 1 < RM) p[r + 1] = q.y;
-            if (r + 2 < RM) p[r + 2] = q.z;
-            if (r + 3 < RM) p[r + 3] = q.w;
+            const float4 q4 = *reinterpret_cast<const float4*>(sc + (size_t)t * RM + r);
+            p[r] = q4.x;
+            p[r + 1] = q4.y;
+            p[r + 2] = q4.z;
+            p[r + 3] = q4.w;
         }
 #pragma unroll
-        for (int r = 0; r < RM; ++r)
+        for (int r = 0; r < NR; ++r)
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[r][e] += p[r] * (float)v[e];
     };
-    int t = sl;
-    for (; t + 3 * nsl <= last; t += 4 * nsl) {   // four rows in flight per lane
-        h8 v[4];
+    int t = slv;
+    for (; t + 7 * nsv <= last; t += 8 * nsv) {   // eight entries in flight per lane
+        h8 v[8];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const h8*>(vp + (size_t)(t + u * nsl) * d);
+        for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const h8*>(vp + (size_t)(t + u * nsv) * d);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) fold(t + u * nsl, v[u]);
+        for (int u = 0; u < 8; ++u) fold(t + u * nsv, v[u]);
     }
-    for (; t <= last; t += nsl) fold(t, *reinterpret_cast<const h8*>(vp + (size_t)t * d));
-    // lanes of a wave with the same c8 differ in lane / cpr
+    for (; t <= last; t += nsv) fold(t, *reinterpret_cast<const h8*>(vp + (size_t)t * d));
 #pragma unroll
     for (int r = 0; r < RM; ++r)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             float v = acc[r][e];
-            for (int o = cpr; o < 64; o <<= 1) v += __shfl_xor(v, o);
+            v += dpp_lane<0xB1>(v);
+            v += dpp_lane<0x4E>(v);
+            if (slots == 8) v += dpp_lane<0x141>(v);
             acc[r][e] = v;
         }
-    if (lane < cpr) {
+    if (lane % slots == 0) {
 #pragma unroll
         for (int r = 0; r < RM; ++r)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) part[(wave * RM + r) * hd + lane * 8 + e] = acc[r][e];
+            for (int e = 0; e < 8; ++e) part[(wave * RM + r) * hd + c8v * 8 + e] = acc[r][e];
     }
     __syncthreads();
     for (int j = tid; j < nrows * hd; j += 256) {
@@ -553,21 +584,21 @@ void launch_rope_append(hawk_ctx* c, const RowMap& map, int layer, int M) {
 void launch_attention(hawk_ctx* c, const RowMap& map, int layer, int M) {
     constexpr int RM = 8;
     const int cpr = c->hd / 8;
-    if (c->cfg.dtype == HAWK_BF16 && map.mode == 1 && map.rows_per_seq <= RM && c->hd % 64 == 0 && cpr <= 64 &&
-        (cpr & (cpr - 1)) == 0) {
+    if (c->cfg.dtype == HAWK_BF16 && map.mode == 1 && map.rows_per_seq <= RM && (cpr == 8 || cpr == 16)) {
         const size_t lds = ((size_t)RM * c->hd + (size_t)c->Tmax * RM + (size_t)4 * RM * c->hd) * sizeof(float);
         if (lds <= 60 * 1024) {
             dim3 grid(M / map.rows_per_seq, c->H);
             uint16_t *hi = nullptr, *lo = nullptr;
             presplit_planes(c, c->off.o, M, c->d, &hi, &lo);   // the Wo GEMM reads the result next
-            if (map.rows_per_seq <= 4)
-                attention_rows_kernel<4><<<grid, 256, lds, c->stream>>>(
-                    wsp<float>(c, c->off.qkv), wsp<_Float16>(c, c->off.kc), wsp<_Float16>(c, c->off.vc),
-                    wsp<float>(c, c->off.o), map, layer, c->d, c->hd, c->Smax, c->Tmax, hi, lo);
-            else
-                attention_rows_kernel<RM><<<grid, 256, lds, c->stream>>>(
-                    wsp<float>(c, c->off.qkv), wsp<_Float16>(c, c->off.kc), wsp<_Float16>(c, c->off.vc),
-                    wsp<float>(c, c->off.o), map, layer, c->d, c->hd, c->Smax, c->Tmax, hi, lo);
+#define HAWK_ATTN_ROWS(RMV, NRV)                                                                       \
+    attention_rows_kernel<RMV, NRV><<<grid, 256, lds, c->stream>>>(                                    \
+        wsp<float>(c, c->off.qkv), wsp<_Float16>(c, c->off.kc), wsp<_Float16>(c, c->off.vc),           \
+        wsp<float>(c, c->off.o), map, layer, c->d, c->hd, c->Smax, c->Tmax, hi, lo)
+            if (map.rows_per_seq <= 2) HAWK_ATTN_ROWS(4, 2);
+            else if (map.rows_per_seq <= 4) HAWK_ATTN_ROWS(4, 4);
+            else if (map.rows_per_seq <= 6) HAWK_ATTN_ROWS(8, 6);
+            else HAWK_ATTN_ROWS(8, 8);
+#undef HAWK_ATTN_ROWS
             return;
         }
     }
