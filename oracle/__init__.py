@@ -60,6 +60,7 @@ def lib() -> C.CDLL:
             "orc_warp": (f64, [vp, i32, f32, i32, vp]),
             "orc_inv_cdf": (i32, [vp, i32, f64, f32]),
             "orc_spec_sample": (i32, [i32, i32, vp, vp, vp, i32, f32, i32, vp, f32, vp]),
+            "orc_multi_verify": (i32, [i32, i32, vp, vp, vp, f32, i32, vp, f32, vp, vp]),
             "orc_forward_row": (i32, [vp, i32, i32, vp, vp]),
             "orc_draft_head": (i32, [vp, vp, i32, i32, vp, vp]),
             "orc_margins": (None, [vp, i32]),
@@ -121,6 +122,25 @@ def spec_sample(p_logits, q_logits, drafts, u_acc, u_final: float, temperature: 
     a = lib().orc_spec_sample(k_eff, n, _p(p), _p(q), _p(d), int(q_onehot), temperature,
                               n if top_k is None else top_k, _p(ua), u_final, _p(out))
     return int(a), out[: a + 1].copy()
+
+
+def multi_verify(p_logits, q_logits, cand, u_acc, u_final: float, temperature: float = 1.0,
+                 top_k: Optional[int] = None, want_resid: bool = False):
+    """Several candidates at one position, each from its own proposal row of q_logits [m, n].
+
+    Returns (index of the accepted candidate or m, emitted token[, residual masses [m]])."""
+    p = _f32(p_logits)
+    q = _f32(q_logits)
+    m, n = q.shape
+    assert p.shape == (n,)
+    c = _i32(cand)
+    ua = _f32(u_acc)
+    assert c.shape == (m,) and ua.shape == (m,)
+    tok = np.full(1, -1, dtype=np.int32)
+    resid = np.zeros(m, dtype=np.float64) if want_resid else None
+    a = lib().orc_multi_verify(m, n, _p(p), _p(q), _p(c), temperature, n if top_k is None else top_k, _p(ua),
+                               u_final, _p(tok), _p(resid))
+    return (int(a), int(tok[0]), resid) if want_resid else (int(a), int(tok[0]))
 
 
 def num_threads() -> int:

@@ -261,6 +261,63 @@ int orc_spec_sample(int k_eff, int n, const float* p_logits, const float* q_logi
     return a;
 }
 
+/* Several candidates at one position, each drawn from a proposal of its own (Method,
+ * "Sampling and Verification", the recursion over consecutive rejections; appendix
+ * "Theoretical Justification", general form with the ordered proposals q_1..q_m).
+ * p^(1) = p.  Candidate i (1-based) is accepted with probability
+ * min(1, p^(i)(s_i) / q_i(s_i)), decided as u_acc[i-1] * q_i(s_i) < p^(i)(s_i); after a
+ * rejection p^(i+1) = norm(max(0, p^(i) - q_i)): the proposal subtracted is the rejected
+ * candidate's own (the appendix's two-head case prints q_vert in both steps; its derivation
+ * and the general form use q_i).  If a residual has no mass p^(i+1) = p^(i), as in
+ * orc_spec_sample.  After m rejections the token is drawn from p^(m+1) by inverse CDF with
+ * u_final.
+ * p_logits: n; q_logits: m rows of n; cand: m tokens.  resid (may be NULL): m values, the
+ * residual mass sum_x max(0, p^(i) - q_i) = 1 - alpha_i of every step that was evaluated
+ * (steps after an acceptance: -1).
+ * Returns the 0-based index of the accepted candidate, or m when all were rejected;
+ * *out_token is the emitted token. */
+int orc_multi_verify(int m, int n, const float* p_logits, const float* q_logits,
+                     const int32_t* cand, float temperature, int top_k, const float* u_acc,
+                     float u_final, int32_t* out_token, double* resid) {
+    double* p = (double*)malloc(sizeof(double) * (size_t)n);
+    double* q = (double*)malloc(sizeof(double) * (size_t)n);
+    double Zp = orc_warp(p_logits, n, temperature, top_k, p);
+    for (int j = 0; j < n; ++j) p[j] /= Zp;
+    if (resid)
+        for (int i = 0; i < m; ++i) resid[i] = -1.0;
+    int acc = m;
+    for (int i = 0; i < m; ++i) {
+        double Zq = orc_warp(q_logits + (size_t)i * n, n, temperature, top_k, q);
+        for (int j = 0; j < n; ++j) q[j] /= Zq;
+        int s = cand[i];
+        double lhs = (double)u_acc[i] * q[s];
+        double mg = fabs(lhs - p[s]);
+        if (mg < g_margin[0]) g_margin[0] = mg;
+        double R = 0.0;
+        for (int j = 0; j < n; ++j) {
+            double r = p[j] - q[j];
+            q[j] = r > 0.0 ? r : 0.0;   /* q now holds max(0, p^(i) - q_i) */
+            R += q[j];
+        }
+        if (resid) resid[i] = R;
+        if (lhs < p[s]) {
+            acc = i;
+            *out_token = s;
+            break;
+        }
+        if (R > 0.0)
+            for (int j = 0; j < n; ++j) p[j] = q[j] / R;
+    }
+    if (acc == m) {
+        double total = 0.0;
+        for (int j = 0; j < n; ++j) total += p[j];
+        *out_token = orc_inv_cdf(p, n, total, u_final);
+    }
+    free(p);
+    free(q);
+    return acc;
+}
+
 /* ------------------------------------------------------------ model / state */
 
 orc_model* orc_load(const void* blob, size_t nbytes, int samp_lo, int samp_n,

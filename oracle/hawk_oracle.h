@@ -27,7 +27,9 @@
  * Pinned by tests/test_oracle_*.py: greedy speculative == plain AR; chi-square of the
  * emitted token against p; exact enumeration of accept/reject paths with rational
  * arithmetic; acceptance rate == sum min(p,q); residual identity; softmax / argmax
- * special cases of the warp; incremental KV forward == full causal recompute and ==
+ * special cases of the warp; the multi-candidate recursion by exact integration over its
+ * uniforms (output law == p for distinct proposals) and its one-candidate case against
+ * orc_spec_sample; incremental KV forward == full causal recompute and ==
  * an independent PyTorch fp64 forward; hand-computed draft head.
  * Parity unpinned: behaviour with trained weights (accept length, FID, CLIP).
  */
@@ -85,6 +87,11 @@ int orc_inv_cdf(const double* w, int n, double total, float u);
 int orc_spec_sample(int k_eff, int n, const float* p_logits, const float* q_logits,
                     const int32_t* drafts, int q_onehot, float temperature, int top_k,
                     const float* u_acc, float u_final, int32_t* out_tokens);
+/* m candidates at one position, each from its own proposal: sequential accept tests with
+ * the recursively updated target p^(i+1) = norm(max(0, p^(i) - q_i)); see the definition. */
+int orc_multi_verify(int m, int n, const float* p_logits, const float* q_logits,
+                     const int32_t* cand, float temperature, int top_k, const float* u_acc,
+                     float u_final, int32_t* out_token, double* resid);
 /* One target row: x (d values: in = input embedding, out = hidden before the final
  * norm) at absolute position pos of sequence seq; appends K,V; logits may be NULL. */
 int orc_forward_row(orc_state*, int seq, int pos, double* x, float* logits);
