@@ -210,6 +210,31 @@ int hawk_last_path(const hawk_ctx* ctx);
  * barrier's release. */
 int hawk_phase_trace(hawk_ctx* ctx, int enable, uint64_t* out, size_t n_words);
 
+/* Verification of several candidates at one position, each drawn from a proposal of its own
+ * (Method, "Sampling and Verification": the iterated update of the target after consecutive
+ * rejections; appendix "Theoretical Justification": general form for an ordered sequence of
+ * proposals q_1..q_m, e.g. the vertical head's candidate first, then the horizontal one's).
+ * For each of `rows` independent positions r:
+ *   p^(1) = warp(p_logits[r]); for i = 1..m: q_i = warp(q_logits[r][i-1]), s_i = cand[r][i-1];
+ *   s_i is accepted iff u_acc[r][i-1] * q_i(s_i) < p^(i)(s_i), i.e. with probability
+ *   min(1, p^(i)(s_i) / q_i(s_i)); on rejection p^(i+1) = norm(max(0, p^(i) - q_i)) (p^(i) itself
+ *   if that residual has no mass).  After m rejections the token is drawn from p^(m+1) by
+ *   inverse CDF over ascending token index with u_final[r].
+ * warp = temperature and top-k as in hawk_prefill (temperature 0 or top_k 1: point mass on the
+ * arg-max); probabilities and sums in fp64.
+ * All pointers are DEVICE pointers, rows contiguous: p_logits [rows][n] fp32, q_logits
+ * [rows][m][n] fp32, cand [rows][m] (0 <= token < n), u_acc [rows][m] and u_final [rows] in
+ * [0, 1), out_index [rows] (0-based index of the accepted candidate, m if none), out_token
+ * [rows], out_resid (may be NULL) [rows][m] fp64: the residual mass sum_x max(0, p^(i) - q_i)
+ * = 1 - acceptance probability of every evaluated step, -1 for steps after an acceptance.
+ * n <= 16384.  The caller owns every buffer; nothing is allocated.  The launch is
+ * asynchronous on `stream` (a hipStream_t, NULL: the default stream).
+ * Returns HAWK_OK, HAWK_EINVAL (null pointer, m < 1, n out of range, top_k < 1, negative
+ * temperature) or HAWK_EDEVICE (the launch failed). */
+int hawk_multi_verify(const float* p_logits, const float* q_logits, const int32_t* cand, const float* u_acc,
+                      const float* u_final, int rows, int m, int n, float temperature, int top_k,
+                      int32_t* out_index, int32_t* out_token, double* out_resid, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -10,6 +10,7 @@ from .hawk import (  # noqa: F401
     HawkStats,
     lib_path,
     load_library,
+    multi_verify,
     plan_info,
     workspace_bytes,
 )

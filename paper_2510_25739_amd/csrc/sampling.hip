@@ -1056,6 +1056,78 @@ __global__ __launch_bounds__(NT) void accept_commit_fast(
     }
 }
 
+// Several candidates at one position, each from a proposal of its own (Method, "Sampling and
+// Verification", the recursion over consecutive rejections; appendix "Theoretical
+// Justification", general form): p^(1) = p; candidate i is accepted iff u_i q_i(s_i) < p^(i)(s_i),
+// otherwise p^(i+1) = norm(max(0, p^(i) - q_i)) (unchanged if that residual has no mass); after m
+// rejections the token comes from p^(m+1) by inverse CDF.  One workgroup per position, the
+// running target in registers (E fp64 values per thread), every proposal row read once.
+template <int E>
+__global__ __launch_bounds__(NT) void multi_verify_kernel(const float* p_logits, const float* q_logits,
+                                                          const int32_t* cand, const float* u_acc,
+                                                          const float* u_final, int m, int n, float inv_t, int top_k,
+                                                          int greedy, int32_t* out_index, int32_t* out_token,
+                                                          double* out_resid) {
+    __shared__ FastShared fs;
+    __shared__ double pick[2];
+    const int row = blockIdx.x, base = threadIdx.x * E;
+    float z[E];
+    unsigned km;
+    load_row<E>(p_logits + (size_t)row * n, nullptr, 0.f, inv_t, nullptr, n, z);
+    WarpStat ps = warp_select<E>(z, n, top_k, greedy, fs, &km);
+    double p[E];
+    dense_weights<E>(ps, z, p, fs.sh);
+#pragma unroll
+    for (int e = 0; e < E; ++e) p[e] /= ps.total;
+    int acc = m, tok = -1;
+    for (int i = 0; i < m; ++i) {
+        load_row<E>(q_logits + ((size_t)row * m + i) * n, nullptr, 0.f, inv_t, nullptr, n, z);
+        WarpStat qs = warp_select<E>(z, n, top_k, greedy, fs, &km);
+        double q[E];
+        dense_weights<E>(qs, z, q, fs.sh);
+        const int s = cand[(size_t)row * m + i];
+        double rs = 0.0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            q[e] /= qs.total;
+            if (base + e == s) {   // the owner of the candidate's entry publishes p^(i)(s), q_i(s)
+                pick[0] = p[e];
+                pick[1] = q[e];
+            }
+            const double r = p[e] - q[e];
+            q[e] = r > 0.0 ? r : 0.0;   // q now holds max(0, p^(i) - q_i)
+            rs += q[e];
+        }
+        const double R = block_sum_d(rs, fs.sh);   // its barriers also publish pick[]
+        const double pd = pick[0], qd = pick[1];
+        if (out_resid && threadIdx.x == 0) out_resid[(size_t)row * m + i] = R;
+        const bool accept = (double)u_acc[(size_t)row * m + i] * qd < pd;
+        __syncthreads();   // pick[] is rewritten by the next candidate
+        if (accept) {
+            acc = i;
+            tok = s;
+            break;
+        }
+        if (R > 0.0) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) p[e] = q[e] / R;
+        }
+    }
+    if (acc == m) {
+        double sp = 0.0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) sp += p[e];
+        const double total = block_sum_d(sp, fs.sh);
+        tok = inv_cdf_row<E>(p, total, u_final[row], fs.sh);
+    }
+    if (threadIdx.x == 0) {
+        out_index[row] = acc;
+        out_token[row] = tok;
+        if (out_resid)
+            for (int i = acc + 1; i < m; ++i) out_resid[(size_t)row * m + i] = -1.0;
+    }
+}
+
 SampParams samp_params(const hawk_ctx* c) {
     SampParams P;
     P.B = c->B; P.N = c->N; P.Vs = c->Vs; P.samp_lo = c->cfg.samp_lo; P.kstride = c->kmax + 1;
@@ -1151,6 +1223,19 @@ void launch_force_commit(hawk_ctx* c, int cnt) {
                                                      wsp<int32_t>(c, c->off.n), wsp<uint32_t>(c, c->off.x),
                                                      wsp<uint32_t>(c, c->off.hprev), (int)(c->d * c->asz / 4), c->B,
                                                      c->N, cnt, c->S);
+}
+
+int launch_multi_verify(const float* p_logits, const float* q_logits, const int32_t* cand, const float* u_acc,
+                        const float* u_final, int rows, int m, int n, float temperature, int top_k,
+                        int32_t* out_index, int32_t* out_token, double* out_resid, hipStream_t stream) {
+    const int E = n <= 4 * NT ? 4 : (n <= 16 * NT ? 16 : 0);
+    if (!E) return HAWK_EINVAL;
+    const int greedy = (temperature == 0.0f || top_k == 1) ? 1 : 0;
+    const float inv_t = greedy ? 1.0f : 1.0f / temperature;
+    auto kern = E == 4 ? multi_verify_kernel<4> : multi_verify_kernel<16>;
+    kern<<<rows, NT, 0, stream>>>(p_logits, q_logits, cand, u_acc, u_final, m, n, inv_t, top_k < n ? top_k : n, greedy,
+                                  out_index, out_token, out_resid);
+    return hipGetLastError() == hipSuccess ? HAWK_OK : HAWK_EDEVICE;
 }
 
 }  // namespace hawk

@@ -71,6 +71,8 @@ EXPORTS = {
     "hawk_set_path": (C.c_int, [C.c_void_p, C.c_int]),
     "hawk_last_path": (C.c_int, [C.c_void_p]),
     "hawk_phase_trace": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t]),
+    "hawk_multi_verify": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
+                                    C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
 }
 
 
@@ -116,6 +118,30 @@ def _i32(a):
 
 def _p(a):
     return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def multi_verify(p_logits, q_logits, cand, u_acc, u_final, temperature: float, top_k: int, want_resid: bool = False):
+    """hawk_multi_verify on device tensors (torch, on the GPU): p_logits [rows, n] fp32, q_logits
+    [rows, m, n] fp32, cand [rows, m] int32, u_acc [rows, m] fp32, u_final [rows] fp32.
+    Returns device tensors (index [rows] int32, token [rows] int32[, residual masses [rows, m] fp64]);
+    the launch is asynchronous on torch's current stream."""
+    import torch  # device memory and stream only
+    rows, m, n = q_logits.shape
+    for t, shape, dt in ((p_logits, (rows, n), torch.float32), (q_logits, (rows, m, n), torch.float32),
+                         (cand, (rows, m), torch.int32), (u_acc, (rows, m), torch.float32),
+                         (u_final, (rows,), torch.float32)):
+        if not (t.is_cuda and t.is_contiguous() and t.dtype == dt and tuple(t.shape) == shape):
+            raise HawkError(-1, "hawk_multi_verify", "arguments must be contiguous device tensors of the documented shapes")
+    idx = torch.empty(rows, dtype=torch.int32, device=p_logits.device)
+    tok = torch.empty(rows, dtype=torch.int32, device=p_logits.device)
+    resid = torch.empty((rows, m), dtype=torch.float64, device=p_logits.device) if want_resid else None
+    rc = load_library().hawk_multi_verify(p_logits.data_ptr(), q_logits.data_ptr(), cand.data_ptr(), u_acc.data_ptr(),
+                                          u_final.data_ptr(), rows, m, n, float(temperature), int(top_k),
+                                          idx.data_ptr(), tok.data_ptr(), resid.data_ptr() if want_resid else None,
+                                          torch.cuda.current_stream(p_logits.device).cuda_stream)
+    if rc != 0:
+        raise HawkError(rc, "hawk_multi_verify")
+    return (idx, tok, resid) if want_resid else (idx, tok)
 
 
 class Hawk:
