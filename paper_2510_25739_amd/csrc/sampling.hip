@@ -803,7 +803,7 @@ struct CompactList {
     double w[kCap];
 };
 
-__device__ __forceinline__ bool use_list(int top_k, int n, int greedy) { return !greedy && top_k < n && top_k <= kCap; }
+__host__ __device__ __forceinline__ bool use_list(int top_k, int n, int greedy) { return !greedy && top_k < n && top_k <= kCap; }
 
 template <int E>
 __device__ int compact_row(unsigned kmask, const float (&z)[E], CompactList& L, Shared& sh) {
@@ -1062,6 +1062,105 @@ __global__ __launch_bounds__(NT) void accept_commit_fast(
 // otherwise p^(i+1) = norm(max(0, p^(i) - q_i)) (unchanged if that residual has no mass); after m
 // rejections the token comes from p^(m+1) by inverse CDF.  One workgroup per position, the
 // running target in registers (E fp64 values per thread), every proposal row read once.
+// Kept entries of a row gathered as scaled logits only (no indices): for the sum of their weights.
+template <int E>
+__device__ int compact_z(unsigned kmask, const float (&z)[E], float (&qz)[kCap], Shared& sh) {
+    const int c = __popc(kmask);
+    int at = block_excl_scan_i(c, sh);
+    if (threadIdx.x == NT - 1) sh.b_int = at + c;
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+        if ((kmask >> e) & 1u) {
+            if (at < kCap) qz[at] = z[e];
+            ++at;
+        }
+    __syncthreads();
+    return min(sh.b_int, kCap);
+}
+
+// The same recursion with the running target held as a list in LDS: top-k leaves at most kCap
+// entries of p with mass, max(0, p - q) lives on those, and fp64 exponentials are evaluated for
+// kept entries only, two per thread (the dense form spends one per vocabulary entry).
+template <int E>
+__global__ __launch_bounds__(NT) void multi_verify_list_kernel(const float* p_logits, const float* q_logits,
+                                                               const int32_t* cand, const float* u_acc,
+                                                               const float* u_final, int m, int n, float inv_t,
+                                                               int top_k, int32_t* out_index, int32_t* out_token,
+                                                               double* out_resid) {
+    __shared__ FastShared fs;
+    __shared__ CompactList L;       // entries of p with mass: index, scaled logit, current p^(i)
+    __shared__ float qz[kCap];      // kept scaled logits of the proposal at hand
+    __shared__ double pick;
+    const int row = blockIdx.x, i0 = threadIdx.x * 2;
+    int Kp = 0, acc = m, tok = -1;
+    // One loop over the target row (i = -1) and the proposal rows, so that the top-k selection has
+    // a single call site and is inlined with its LDS operands (a second copy would be called
+    // through generic pointers).
+    for (int i = -1; i < m; ++i) {
+        const float* qrow = i < 0 ? p_logits + (size_t)row * n : q_logits + ((size_t)row * m + i) * n;
+        float z[E];
+        unsigned km = 0u;
+        load_row<E>(qrow, nullptr, 0.f, inv_t, nullptr, n, z);
+        WarpStat qs = warp_select<E>(z, n, top_k, 0, fs, &km);
+        if (i < 0) {   // p^(1): the kept entries of the target, normalised
+            Kp = compact_row<E>(km, z, L, fs.sh);
+            const double Zp = list_weights(L, Kp, qs.zmax, fs.sh);
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+                if (i0 + e < Kp) L.w[i0 + e] /= Zp;   // the thread's own entries
+            continue;
+        }
+        const int Kq = compact_z<E>(km, z, qz, fs.sh);
+        double sq = 0.0;
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+            if (i0 + e < Kq) sq += exp((double)qz[i0 + e] - (double)qs.zmax);
+        if (threadIdx.x == 0) pick = 0.0;   // p^(i)(s) if s has no mass left
+        qs.total = block_sum_d(sq, fs.sh);
+        const int s = cand[(size_t)row * m + i];
+        double res[2], rs = 0.0;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            res[e] = 0.0;
+            if (i0 + e < Kp) {
+                const int j = L.idx[i0 + e];
+                const double pv = L.w[i0 + e];
+                if (j == s) pick = pv;
+                const double r = pv - weight_of(qs, qrow, inv_t, j) / qs.total;
+                res[e] = r > 0.0 ? r : 0.0;
+                rs += res[e];
+            }
+        }
+        const double R = block_sum_d(rs, fs.sh);   // its barriers also publish pick
+        const double pd = pick, qd = weight_of(qs, qrow, inv_t, s) / qs.total;
+        if (out_resid && threadIdx.x == 0) out_resid[(size_t)row * m + i] = R;
+        if ((double)u_acc[(size_t)row * m + i] * qd < pd) {
+            acc = i;
+            tok = s;
+            break;
+        }
+        if (R > 0.0) {
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+                if (i0 + e < Kp) L.w[i0 + e] = res[e] / R;
+        }
+    }
+    if (acc == m) {
+        double sp = 0.0;
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+            if (i0 + e < Kp) sp += L.w[i0 + e];
+        const double total = block_sum_d(sp, fs.sh);
+        tok = list_inv_cdf(L.w, L.idx, Kp, total, u_final[row], fs.sh);
+    }
+    if (threadIdx.x == 0) {
+        out_index[row] = acc;
+        out_token[row] = tok;
+        if (out_resid)
+            for (int i = acc + 1; i < m; ++i) out_resid[(size_t)row * m + i] = -1.0;
+    }
+}
+
 template <int E>
 __global__ __launch_bounds__(NT) void multi_verify_kernel(const float* p_logits, const float* q_logits,
                                                           const int32_t* cand, const float* u_acc,
@@ -1232,9 +1331,16 @@ int launch_multi_verify(const float* p_logits, const float* q_logits, const int3
     if (!E) return HAWK_EINVAL;
     const int greedy = (temperature == 0.0f || top_k == 1) ? 1 : 0;
     const float inv_t = greedy ? 1.0f : 1.0f / temperature;
-    auto kern = E == 4 ? multi_verify_kernel<4> : multi_verify_kernel<16>;
-    kern<<<rows, NT, 0, stream>>>(p_logits, q_logits, cand, u_acc, u_final, m, n, inv_t, top_k < n ? top_k : n, greedy,
-                                  out_index, out_token, out_resid);
+    const int tk = top_k < n ? top_k : n;
+    if (use_list(tk, n, greedy)) {
+        auto kern = E == 4 ? multi_verify_list_kernel<4> : multi_verify_list_kernel<16>;
+        kern<<<rows, NT, 0, stream>>>(p_logits, q_logits, cand, u_acc, u_final, m, n, inv_t, tk, out_index, out_token,
+                                      out_resid);
+    } else {
+        auto kern = E == 4 ? multi_verify_kernel<4> : multi_verify_kernel<16>;
+        kern<<<rows, NT, 0, stream>>>(p_logits, q_logits, cand, u_acc, u_final, m, n, inv_t, tk, greedy, out_index,
+                                      out_token, out_resid);
+    }
     return hipGetLastError() == hipSuccess ? HAWK_OK : HAWK_EDEVICE;
 }
 
