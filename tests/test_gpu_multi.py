@@ -107,3 +107,30 @@ def test_multi_verify_rejects_bad_arguments(H):
     assert L.hawk_multi_verify(ptr, ptr, ptr, ptr, ptr, 1, 0, 8, 1.0, 8, ptr, ptr, None, None) == -1
     assert L.hawk_multi_verify(ptr, ptr, ptr, ptr, ptr, 1, 1, 16385, 1.0, 8, ptr, ptr, None, None) == -1
     assert L.hawk_multi_verify(ptr, ptr, ptr, ptr, ptr, 0, 1, 8, 1.0, 8, ptr, ptr, None, None) == 0
+
+
+def test_rejection_probability_curve_matches_oracle(H):
+    # Experiment, the rejection probability r = prod_j (1 - alpha_j) against the number of candidates:
+    # the same proposal repeated against distinct proposals, 8 steps, all evaluated (the candidates
+    # are tokens without target mass), residual masses from the kernel against the oracle's
+    import torch
+    rows, m, n, top_k = 24, 8, 16384, 1000
+    rng = np.random.Generator(np.random.PCG64(5))
+    p = (rng.standard_normal((rows, n)) * 1.5).astype(np.float32)
+    qd = (p[:, None, :] + rng.standard_normal((rows, m, n))).astype(np.float32)
+    qs = np.repeat(qd[:, :1], m, axis=1).copy()
+    cand = np.repeat(np.argmin(p, axis=1).astype(np.int32)[:, None], m, axis=1).copy()
+    u_acc = np.full((rows, m), np.float32(1.0) - np.float32(2.0 ** -24), dtype=np.float32)
+    u_fin = np.full(rows, 0.5, dtype=np.float32)
+    curves = {}
+    for name, q in (("same", qs), ("distinct", qd)):
+        (idx, tok, resid), (o_idx, o_tok, o_res) = run_both(H, p, q, cand, u_acc, u_fin, 1.0, top_k)
+        assert (o_idx == m).all()
+        np.testing.assert_array_equal(idx, o_idx)
+        np.testing.assert_array_equal(tok, o_tok)
+        np.testing.assert_allclose(resid, o_res, rtol=1e-11, atol=0)
+        curves[name] = np.cumprod(resid, 1).mean(0)
+    print("r(m), same proposal    :", np.round(curves["same"], 4))
+    print("r(m), distinct proposals:", np.round(curves["distinct"], 4))
+    assert np.all(curves["distinct"][1:] < curves["same"][1:])
+    assert curves["same"][-1] / curves["same"][-2] > 0.97

@@ -182,3 +182,47 @@ def test_residual_mass_is_total_variation_distance():
         p1 = np.maximum(0, p - q1)
         p1 /= p1.sum()
         assert abs(resid[1] - (1 - np.minimum(p1, q2).sum())) < 1e-12
+
+
+def rejection_curves(rows, m, n, top_k, seed, verify):
+    """Residual masses 1 - alpha_j of every step for the same proposal repeated and for distinct
+    proposals; the candidates are tokens the target gives no mass, so every step is evaluated."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    same, distinct = [], []
+    for r in range(rows):
+        p = (rng.standard_normal(n) * 1.5).astype(np.float32)
+        qd = (p[None, :] + rng.standard_normal((m, n))).astype(np.float32)
+        qs = np.repeat(qd[:1], m, axis=0)
+        out = int(np.argmin(p))
+        for q, acc in ((qs, same), (qd, distinct)):
+            idx, tok, resid = verify(p, q, [out] * m, [ONE_BELOW] * m, 0.5, 1.0, top_k)
+            assert idx == m
+            acc.append(resid)
+    return np.array(same), np.array(distinct)
+
+
+def test_rejection_probability_same_proposal_stalls_distinct_proposals_do_not():
+    # Experiment, the paragraph on the rejection probability r(x) and its figure: with one proposal
+    # used again and again the residual reaches a fixed point (1 - alpha_j -> 1, r stops falling);
+    # distinct proposals keep lowering r = prod_j (1 - alpha_j).
+    m = 8
+    same, distinct = rejection_curves(12, m, 2048, 200, 5,
+                                      lambda *a: oracle.multi_verify(*a, want_resid=True))
+    assert np.all((same > 0) & (same <= 1)) and np.all((distinct > 0) & (distinct <= 1))
+    np.testing.assert_allclose(same[:, 0], distinct[:, 0], rtol=0, atol=0)   # the first step is the same
+    ms, md = same.mean(0), distinct.mean(0)
+    assert np.all(np.diff(ms) > 0) and ms[-1] > 0.97            # approaches the fixed point
+    r_same, r_dist = np.cumprod(same, 1).mean(0), np.cumprod(distinct, 1).mean(0)
+    assert np.all(r_dist[1:] < r_same[1:])
+    assert r_same[-1] / r_same[-2] > 0.97                       # r has stopped falling
+    assert r_dist[-1] < 0.5 * r_same[-1]
+    # the fixed point itself: with q repeated for ever what survives is the target's mass where it
+    # exceeds every multiple of q that fits under it - in the limit the mass p puts where q has none
+    p = np.array([0.5, 0.3, 0.2, 0.0])
+    q = np.array([0.0, 0.6, 0.2, 0.2])
+    lp = np.log(np.maximum(p, 1e-300)).astype(np.float32)
+    lq = np.log(np.maximum(q, 1e-300)).astype(np.float32)
+    idx, tok, resid = oracle.multi_verify(lp, np.repeat(lq[None], 6, 0), [3] * 6, [ONE_BELOW] * 6, 0.0, 1.0, 4, want_resid=True)
+    # step 1: sum max(0, p - q) = 0.5; afterwards the residual is the point mass on token 0, q(0) = 0
+    np.testing.assert_allclose(resid, [0.5, 1, 1, 1, 1, 1], rtol=0, atol=1e-6)
+    assert idx == 6 and tok == 0
