@@ -60,6 +60,7 @@ CASES = [
     (32, 3, 5000, 1.3, 1000, 2.0),      # ragged row, sixteen entries per thread
     (32, 2, 8192, 1.0, 2000, 1.0),      # the 7B configuration's slice and top-k
     (32, 1, 300, 1.0, 300, 1.0),        # a single candidate
+    (16, 2, 16384, 1.0, 3000, 1.0),     # top-k beyond the list capacity: dense form, sixteen entries per thread
     (32, 3, 16384, 0.0, 1000, 0.3),     # greedy by temperature
     (32, 2, 16384, 1.0, 1, 0.3),        # greedy by top-k
 ]
