@@ -454,6 +454,70 @@ def test_config3_guidance_batch16_reduced_depth(H):
     assert_bf16(greedy, 6, 0.8)
 
 
+def test_config3_full_depth_sampled_prompts(H):
+    # configuration 3 at its full size (36 layers, 16 prompts with guidance: 192 rows per target pass
+    # through the MFMA GEMMs and the per-sequence attention kernel); the oracle follows three of the
+    # 16 prompts (each a pair of sequences) through the prefill and one speculate-and-verify step
+    s = synth.CONFIGS[3]
+    B, k, lo = s.batch, s.k, s.samp_lo
+    T, K = s.temperature, s.top_k
+    blob = synth.make_weights(s, seed=0)
+    hk = H.Hawk(H.HawkConfig.from_shape(s))
+    hk.load(blob)
+    hk.set_path(1)
+    cond, unc = synth.make_cond(s, seed=2, batch=B), synth.make_cond(s, seed=3, batch=B)
+    rng = np.random.Generator(np.random.PCG64(1))
+
+    def uni(*shp):
+        return (rng.integers(0, 1 << 24, size=shp).astype(np.float32) / np.float32(1 << 24)).astype(np.float32)
+
+    u0, ud, ua, uf = uni(B), uni(B, k), uni(B, k), uni(B)
+    hk.prefill(cond, unc, s.grid_h, s.grid_w, T, K, s.cfg_scale, u0)
+    l0 = hk.logits(1)
+    orcs = {}
+    for b in range(B):   # the first three prompts whose token 0 (sampled by the prefill itself) agrees
+        orc = oracle.Oracle.from_shape(s, blob, batch=1)
+        orc.prefill(cond[b:b + 1], unc[b:b + 1], T, K, s.cfg_scale, u0[b:b + 1])
+        w, z = oracle.warp(l0[b, 0], T, K)
+        assert lo + oracle.inv_cdf(w, z, float(u0[b])) == hk.grid()[b, 0]
+        if hk.grid()[b, 0] == orc.grid()[0, 0]:
+            orcs[b] = orc
+            if len(orcs) == 3:
+                break
+        else:
+            orc.close()
+    picks = tuple(orcs)
+    assert len(picks) >= 2, "too few prompts to synchronise onto"
+    d_g = hk.draft(k, ud)
+    lq_g = hk.draft_logits(k)
+    forced, d_o = d_g.copy(), {}
+    for b in picks:
+        d_o[b] = orcs[b].draft(k, ud[b:b + 1])[0]
+        for i in range(k):   # the sampling stage on the GPU's own draft logits gives the GPU's tokens
+            w, z = oracle.warp(lq_g[b, i], T, K)
+            assert lo + oracle.inv_cdf(w, z, float(ud[b, i])) == d_g[b, i]
+        forced[b] = d_o[b]
+    if not np.array_equal(forced, d_g):   # teacher-force the oracle's candidates where they differ
+        hk.draft_forced(k, forced, False)
+        lq_g = hk.draft_logits(k)
+    na_g, t_g = hk.verify(k, ua, uf)
+    lp_g = hk.logits(k + 1)
+    err_q = err_p = 0.0
+    for b in picks:
+        orc = orcs[b]
+        err_q = max(err_q, float(np.abs(lq_g[b] - orc.draft_logits()[0]).max()))
+        na_o, t_o = orc.verify(k, ua[b:b + 1], uf[b:b + 1])
+        err_p = max(err_p, float(np.abs(lp_g[b] - orc.logits()[0]).max()))
+        a_s, t_s = oracle.spec_sample(lp_g[b], lq_g[b], d_o[b] - lo, ua[b], float(uf[b]), T, K)
+        assert a_s == na_g[b] and np.array_equal(t_s + lo, t_g[b, :a_s + 1])   # stage exact on its own logits
+        assert na_g[b] == na_o[0], (b, na_g[b], na_o[0])                       # same accept / reject decisions
+        assert np.array_equal(t_g[b, :na_g[b]], t_o[0, :na_o[0]])
+        orc.close()
+    print("config 3 full depth, prompts", picks, ": max-abs logit error target", err_p, "draft", err_q)
+    assert err_p <= 2e-2 and err_q <= 2e-2
+    hk.close()
+
+
 def test_config4_7b_shape_slice_and_guidance_reduced(H):
     # configuration 4's shape - d = 4096, 32 heads of 128, MLP 11008, 8192-entry slice at id 4,
     # top-k 2000, guidance 3.0 - with one layer, a 12288-entry vocabulary, short condition
