@@ -54,7 +54,9 @@ __global__ void split_rows_kernel(const float* A, int lda, int K, uint16_t* hi, 
 }
 
 // SR: 16-feature strips per wave, CT: 16-row tiles per wave, D: stages (64 k each) in flight.
-// Tile = (32 SR) features x (32 CT) rows.
+// Tile = (32 SR) features x (32 CT) rows.  blockIdx.z takes one of gridDim.z equal K ranges; if
+// there are several, the partial tiles are added into Y with float atomics (Y then already holds
+// what is accumulated onto, or zeros).
 template <int SR, int CT, int D>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restrict__ hi, const uint16_t* __restrict__ lo,
                                                         const uint16_t* __restrict__ W, int N, int K, float* Y, int ldy,
@@ -67,7 +69,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
     const int wn = wave >> 1, wm = wave & 1;                     // wave position over (features, rows)
     const int n0 = blockIdx.x * BN + wn * 16 * SR, m0 = blockIdx.y * BM;
     const int r16 = lane & 15, kg = lane >> 4;
-    const int nk = K / kKC, it0 = 0;
+    const int nk = K / kKC / (int)gridDim.z, it0 = (int)blockIdx.z * nk;   // this workgroup's k-stages
 
     static_assert(CHUNKS % 256 == 0, "a stage is a whole number of 16-byte chunks per thread");
 
@@ -169,6 +171,11 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
             if (m < M && n < N) {
                 float* dst = Y + (size_t)m * ldy + n;
                 f32x4 v = acc[s][t] + acl[s][t];
+                if (gridDim.z > 1) {   // one of several K ranges: Y already holds what is added onto
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) unsafeAtomicAdd(dst + e, v[e]);   // the hardware add, not a compare-and-swap loop
+                    continue;
+                }
                 if (accumulate) {
                     const float4 old = *reinterpret_cast<const float4*>(dst);
                     v += (f32x4){old.x, old.y, old.z, old.w};
@@ -225,6 +232,19 @@ bool launch_gemm_mfma(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, i
         dim3 grid((N + 32 * SR - 1) / (32 * SR), (M + 32 * CT - 1) / (32 * CT), 1);                    \
         gemm_mfma_kernel<SR, CT, D><<<grid, 256, 0, c->stream>>>(hi, lo, W, N, K, Y, ldy, M, acc);     \
     } while (0)
+    if (M <= 32) {
+        // A handful of rows: pure weight streaming, and a workgroup's k-stages are a chain of memory
+        // round trips.  K is split over several workgroups per tile (about six resident workgroups
+        // per compute unit keep enough bytes in flight); with so few outputs the atomics are cheap.
+        int ks = 1;
+        const long t = tiles(32, 32);
+        while (ks < 16 && t * ks * 2 <= 6L * cus && (K / kKC) % (ks * 2) == 0 && K / kKC / (ks * 2) >= 4) ks *= 2;
+        if (ks > 1 && !accumulate)
+            (void)hipMemset2DAsync(Y, (size_t)ldy * sizeof(float), 0, (size_t)N * sizeof(float), M, c->stream);
+        dim3 grid((N + 31) / 32, 1, ks);
+        gemm_mfma_kernel<1, 1, 4><<<grid, 256, 0, c->stream>>>(hi, lo, W, N, K, Y, ldy, M, acc);
+        return true;
+    }
     if (tiles(32, 32) <= cus) HAWK_GEMM_TILE(1, 1, 4);
     else if (tiles(32, 64) <= cus) HAWK_GEMM_TILE(1, 2, 4);
     else if (tiles(32, 96) <= cus) HAWK_GEMM_TILE(1, 3, 4);

@@ -134,6 +134,51 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const typename Cfg::AT* X,
     }
 }
 
+// The same for fp32 activations and bf16 gains with the row held in registers (V float4 per
+// thread: d <= 1024 V, d % 4 == 0, rows 16-byte aligned): one pass over the row instead of two
+// loops of dependent scalar loads.
+template <int V>
+__global__ __launch_bounds__(256) void rmsnorm_rows_kernel(const float* X, const uint16_t* g, float* out, int d,
+                                                           size_t in_stride, float eps, uint16_t* hi, uint16_t* lo) {
+    __shared__ float red[4];
+    const float4* x = reinterpret_cast<const float4*>(X + (size_t)blockIdx.x * in_stride);
+    const int n4 = d / 4;
+    float4 v[V];
+    uint2 gw[V];
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+        const int q = threadIdx.x + i * 256;
+        v[i] = q < n4 ? x[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+        gw[i] = q < n4 ? reinterpret_cast<const uint2*>(g)[q] : make_uint2(0u, 0u);
+    }
+#pragma unroll
+    for (int i = 0; i < V; ++i) ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
+    ss = block_sum256(ss, red);
+    const float r = 1.0f / sqrtf(ss / (float)d + eps);
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+        const int q = threadIdx.x + i * 256;
+        if (q < n4) {
+            float4 o;
+            o.x = v[i].x * r * __uint_as_float(gw[i].x << 16);
+            o.y = v[i].y * r * __uint_as_float(gw[i].x & 0xFFFF0000u);
+            o.z = v[i].z * r * __uint_as_float(gw[i].y << 16);
+            o.w = v[i].w * r * __uint_as_float(gw[i].y & 0xFFFF0000u);
+            reinterpret_cast<float4*>(out + (size_t)blockIdx.x * d)[q] = o;
+            if (hi) {   // bf16 planes of the same row for the GEMM that follows
+                unsigned h0, h1, h2, h3, l0, l1, l2, l3;
+                bf16_split(o.x, h0, l0);
+                bf16_split(o.y, h1, l1);
+                bf16_split(o.z, h2, l2);
+                bf16_split(o.w, h3, l3);
+                reinterpret_cast<uint2*>(hi + (size_t)blockIdx.x * d)[q] = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+                reinterpret_cast<uint2*>(lo + (size_t)blockIdx.x * d)[q] = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------ skinny GEMM
 
 template <class Cfg, int RT, typename OT>
@@ -189,21 +234,37 @@ __global__ void rope_append_kernel(typename Cfg::AT* QKV, typename Cfg::KT* Kc, 
     AT* k = q + d;
     AT* v = k + d;
     size_t base = (((size_t)layer * Smax + ri.s) * Tmax + ri.pos) * d;
-    for (int p = threadIdx.x; p < d / 2; p += blockDim.x) {
-        int j = p % (hd / 2);
-        double ang = (double)ri.pos * inv_freq[j];
-        double sn, cs;
-        sincos(ang, &sn, &cs);
-        AT c = (AT)cs, s = (AT)sn;
-        AT a = q[2 * p], b = q[2 * p + 1];
-        q[2 * p] = a * c - b * s;
-        q[2 * p + 1] = a * s + b * c;
-        a = k[2 * p];
-        b = k[2 * p + 1];
-        kstore(Kc, base + 2 * p, a * c - b * s);
-        kstore(Kc, base + 2 * p + 1, a * s + b * c);
-        kstore(Vc, base + 2 * p, v[2 * p]);
-        kstore(Vc, base + 2 * p + 1, v[2 * p + 1]);
+    // the angles depend on the position and the pair index within a head only: one sincos per pair
+    // index and row, shared by all heads through LDS (hd <= 512)
+    __shared__ double tab_c[256], tab_s[256];
+    for (int j = threadIdx.x; j < hd / 2; j += blockDim.x) sincos((double)ri.pos * inv_freq[j], &tab_s[j], &tab_c[j]);
+    __syncthreads();
+    constexpr int U = 4;   // pairs per thread in flight
+    for (int p0 = threadIdx.x; p0 < d / 2; p0 += U * blockDim.x) {
+        AT qa[U], qb[U], ka[U], kb[U], va[U], vb[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int p = p0 + u * blockDim.x;
+            if (p < d / 2) {
+                qa[u] = q[2 * p]; qb[u] = q[2 * p + 1];
+                ka[u] = k[2 * p]; kb[u] = k[2 * p + 1];
+                va[u] = v[2 * p]; vb[u] = v[2 * p + 1];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int p = p0 + u * blockDim.x;
+            if (p < d / 2) {
+                const int j = p % (hd / 2);
+                const AT c = (AT)tab_c[j], sn = (AT)tab_s[j];
+                q[2 * p] = qa[u] * c - qb[u] * sn;
+                q[2 * p + 1] = qa[u] * sn + qb[u] * c;
+                kstore(Kc, base + 2 * p, ka[u] * c - kb[u] * sn);
+                kstore(Kc, base + 2 * p + 1, ka[u] * sn + kb[u] * c);
+                kstore(Vc, base + 2 * p, va[u]);
+                kstore(Vc, base + 2 * p + 1, vb[u]);
+            }
+        }
     }
 }
 
@@ -553,6 +614,19 @@ void launch_rmsnorm(hawk_ctx* c, size_t off_in, size_t in_stride, size_t off_gai
                     bool for_gemm) {
     uint16_t *hi = nullptr, *lo = nullptr;
     if (for_gemm) presplit_planes(c, off_out, M, c->d, &hi, &lo);
+    if (c->cfg.dtype == HAWK_BF16 && c->d % 4 == 0 && in_stride % 4 == 0 && off_in % 16 == 0 && off_out % 16 == 0 && (c->off.blob + off_gain) % 8 == 0 &&
+        c->d <= 8192) {
+        const float* X = wsp<float>(c, off_in);
+        const uint16_t* g = reinterpret_cast<const uint16_t*>(c->ws + c->off.blob + off_gain);
+        float* out = wsp<float>(c, off_out);
+        if (c->d <= 2048)
+            rmsnorm_rows_kernel<2><<<M, 256, 0, c->stream>>>(X, g, out, c->d, in_stride, c->cfg.rms_eps, hi, lo);
+        else if (c->d <= 4096)
+            rmsnorm_rows_kernel<4><<<M, 256, 0, c->stream>>>(X, g, out, c->d, in_stride, c->cfg.rms_eps, hi, lo);
+        else
+            rmsnorm_rows_kernel<8><<<M, 256, 0, c->stream>>>(X, g, out, c->d, in_stride, c->cfg.rms_eps, hi, lo);
+        return;
+    }
     DISPATCH(c, (rmsnorm_kernel<Cfg><<<M, 256, 0, c->stream>>>(
                     wsp<typename Cfg::AT>(c, off_in), wptr<Cfg>(c, off_gain), wsp<typename Cfg::AT>(c, off_out),
                     c->d, in_stride, c->cfg.rms_eps, hi, lo)));
