@@ -102,6 +102,27 @@ bool derive(const hawk_config* g, hawk_ctx* c) {
     const size_t widest = 3 * d > m ? 3 * d : m;
     c->split_bytes = g->dtype == HAWK_BF16 ? M * widest * 4 : 0;
     o.split = c->split_bytes ? take(c->split_bytes) : 0;
+    // Tile-major copy of every GEMM weight (16 x 32 tiles, 1 KB each, in MFMA operand order): the
+    // MFMA kernels then fetch whole kilobytes per request instead of 64-byte pieces of 16 rows.
+    c->n_gpk = 0;
+    o.gpack = 0;
+    if (g->dtype == HAWK_BF16 && d % 32 == 0 && m % 32 == 0 && Vs % 16 == 0) {
+        size_t q = 0;
+        auto reg = [&](size_t blob_off, size_t N, size_t K) {
+            auto& e2 = c->gpk[c->n_gpk++];
+            e2.blob_off = blob_off; e2.pack_off = q; e2.N = (int)N; e2.K = (int)K;
+            q += N * K * 2;
+        };
+        for (int l = 0; l < c->L; ++l) {
+            reg(c->w.Wqkv[l], 3 * d, d);
+            reg(c->w.Wo[l], d, d);
+            reg(c->w.W13[l], 2 * m, d);
+            reg(c->w.W2[l], d, m);
+        }
+        reg(c->w.W_out + (size_t)g->samp_lo * d * e, Vs, d);
+        reg(c->w.W_d, d, 3 * d);
+        o.gpack = take(q);
+    }
     p += stream_workspace(c, p, &c->soff);
     o.total = p;
     return true;
@@ -352,6 +373,7 @@ int hawk_load(hawk_ctx* c, const void* host_blob, size_t nbytes) {
         return fail(c, HAWK_EINVAL, "blob header does not match the context's configuration");
     HIP_TRY(c, hipMemcpy(c->ws + c->off.blob, host_blob, nbytes, hipMemcpyHostToDevice));
     if (stream_repack(c) != 0) return fail(c, HAWK_EDEVICE, "re-tiling the weights for the streaming path failed");
+    if (gemm_pack_weights(c) != 0) return fail(c, HAWK_EDEVICE, "re-tiling the weights for the MFMA GEMMs failed");
     c->phase = 1;
     return HAWK_OK;
 }

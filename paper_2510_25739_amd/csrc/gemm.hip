@@ -36,6 +36,17 @@ __device__ __forceinline__ void lds_barrier() {
     __atomic_signal_fence(__ATOMIC_SEQ_CST);
 }
 
+// Tile-major copy of W[N][K] (N % 16 == 0, K % 32 == 0): tile (strip s, k-tile kt) is the 1 KB
+// block number s * (K / 32) + kt; inside it lane l of a wave owns bytes 16 l .. 16 l + 15 = row
+// s * 16 + l % 16, columns kt * 32 + (l / 16) * 8 .. + 7: one MFMA A operand per tile.
+__global__ void pack_tiles_kernel(const uint16_t* W, int K, v4u* dst, size_t total) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int lane = (int)(i & 63);
+    const size_t tile = i >> 6, kts = (size_t)K / 32, s = tile / kts, kt = tile - s * kts;
+    dst[i] = *reinterpret_cast<const v4u*>(W + (s * 16 + (lane & 15)) * (size_t)K + kt * 32 + (lane >> 4) * 8);
+}
+
 // hi[r][j], lo[r][j] = bf16 split of A[r * lda + j], r < M, j < K (K % 4 == 0).
 __global__ void split_rows_kernel(const float* A, int lda, int K, uint16_t* hi, uint16_t* lo, size_t total4) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -59,8 +70,8 @@ __global__ void split_rows_kernel(const float* A, int lda, int K, uint16_t* hi, 
 // what is accumulated onto, or zeros).
 template <int SR, int CT, int D>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restrict__ hi, const uint16_t* __restrict__ lo,
-                                                        const uint16_t* __restrict__ W, int N, int K, float* Y, int ldy,
-                                                        int M, int accumulate) {
+                                                        const uint16_t* __restrict__ W, int packed, int N, int K,
+                                                        float* Y, int ldy, int M, int accumulate) {
     constexpr int BM = 32 * CT, BN = 32 * SR;
     constexpr int CHUNKS = 2 * BM * (kKC / 8);       // 16-byte chunks of one stage (both planes)
     constexpr int PER_T = (CHUNKS + 255) / 256;
@@ -73,6 +84,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
 
     static_assert(CHUNKS % 256 == 0, "a stage is a whole number of 16-byte chunks per thread");
 
+    // weights: W is either row-major [N][K] or the tile-major copy (see pack_tiles_kernel); per
+    // strip a base pointer for this lane and a stride per 32-k tile
+    const size_t wstride = packed ? 512 : 32;
+    const uint16_t* wbase[SR];
+#pragma unroll
+    for (int t = 0; t < SR; ++t) {
+        const int strip = min((n0 + t * 16) / 16, N / 16 - 1);   // strips past the end repeat the last (never stored)
+        wbase[t] = packed ? W + ((size_t)strip * (K / 32)) * 512 + lane * 8 : W + (size_t)(strip * 16 + r16) * K + kg * 8;
+    }
     struct Stage { v4u b[PER_T]; v4u w[SR][2]; };
     // Everything of stage `it` that comes from global memory: the tile rows' activation planes
     // (chunk q -> plane, row, 8-k group) and the wave's weight tiles (SR strips x 2 k-steps).
@@ -91,10 +111,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
         }
 #pragma unroll
         for (int t = 0; t < SR; ++t) {
-            const int n = min(n0 + t * 16 + r16, N - 1);
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
-                s.w[t][ks] = *reinterpret_cast<const v4u*>(W + (size_t)n * K + k0 + ks * 32 + kg * 8);
+                s.w[t][ks] = *reinterpret_cast<const v4u*>(wbase[t] + (k0 / 32 + ks) * wstride);
         }
     };
     auto store_stage = [&](int buf, const Stage& s) {
@@ -185,11 +204,110 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
         }
 }
 
+// At most 16 rows: Y[M][N] (+)= A W^T is weight streaming with a sliver of arithmetic, and staging
+// the rows through LDS with a barrier per k-stage would cost more than the streaming itself.  Here
+// a wave works alone: it owns SR strips of 16 features over a quarter of K, loads weight tiles
+// (A operand) and the rows' bf16 planes (B operand, from L2) straight into registers in MFMA
+// layout, D k-steps ahead, with no barrier in the loop; the four waves of a workgroup - the four
+// K quarters of the same strips - add their tiles through LDS at the end.  K % 128 == 0.
+template <int SR, int D>
+__global__ __launch_bounds__(256) void gemv_mfma_kernel(const uint16_t* __restrict__ hi, const uint16_t* __restrict__ lo,
+                                                        const uint16_t* __restrict__ W, int packed, int N, int K,
+                                                        float* Y, int ldy, int M, int accumulate) {
+    __shared__ f32x4 red[3][SR][64];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r16 = lane & 15, kg = lane >> 4;
+    const int n0 = blockIdx.x * 16 * SR;
+    const int nk = K / 128;                               // k-steps (32 k each) of this wave's quarter
+    const size_t kbase = (size_t)wave * (K / 4) + kg * 8;
+    // weights row-major or tile-major (see pack_tiles_kernel): base pointer per strip, stride per k-step
+    const size_t wstride = packed ? 512 : 32;
+    const uint16_t* wp[SR];
+#pragma unroll
+    for (int s = 0; s < SR; ++s) {
+        const int strip = min(n0 / 16 + s, N / 16 - 1);   // strips past the end repeat the last (never stored)
+        wp[s] = packed ? W + ((size_t)strip * (K / 32) + (size_t)wave * (K / 128)) * 512 + lane * 8
+                       : W + (size_t)(strip * 16 + r16) * K + kbase;
+    }
+    const size_t arow = (size_t)min(r16, M - 1) * K + kbase;   // rows past the end repeat the last one (never stored)
+    const uint16_t *hp = hi + arow, *lp = lo + arow;
+    struct Step { v4u w[SR], bh, bl; };
+    auto load = [&](int ks, Step& st) {
+        const int kc = min(ks, nk - 1);          // requests past the end repeat the last step (unused)
+        const int off = kc * 32;
+#pragma unroll
+        for (int s = 0; s < SR; ++s) st.w[s] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(wp[s] + kc * wstride));
+        st.bh = *reinterpret_cast<const v4u*>(hp + off);
+        st.bl = *reinterpret_cast<const v4u*>(lp + off);
+    };
+    f32x4 acc[SR], acl[SR];
+#pragma unroll
+    for (int s = 0; s < SR; ++s) {
+        acc[s] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        acl[s] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+    auto fma_step = [&](const Step& st) {
+#pragma unroll
+        for (int s = 0; s < SR; ++s) {
+            const bf16x8 a = __builtin_bit_cast(bf16x8, st.w[s]);
+            acc[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, st.bh), acc[s], 0, 0, 0);
+            acl[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, st.bl), acl[s], 0, 0, 0);
+        }
+    };
+    Step ring[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) load(j, ring[j]);
+    int ks = 0;
+    for (; ks + D <= nk; ks += D) {
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            fma_step(ring[j]);
+            load(ks + j + D, ring[j]);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < D - 1; ++j)
+        if (ks + j < nk) fma_step(ring[j]);
+    // lane holds features n0 + s*16 + 4*kg .. +3 of row r16
+    if (wave > 0) {
+#pragma unroll
+        for (int s = 0; s < SR; ++s) red[wave - 1][s][lane] = acc[s] + acl[s];
+    }
+    __syncthreads();
+    if (wave > 0) return;
+#pragma unroll
+    for (int s = 0; s < SR; ++s) {
+        f32x4 v = (acc[s] + acl[s]) + red[0][s][lane] + (red[1][s][lane] + red[2][s][lane]);
+        const int n = n0 + s * 16 + 4 * kg;
+        if (r16 < M && n < N) {
+            float* dst = Y + (size_t)r16 * ldy + n;
+            if (accumulate) {
+                const float4 old = *reinterpret_cast<const float4*>(dst);
+                v += (f32x4){old.x, old.y, old.z, old.w};
+            }
+            *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+        }
+    }
+}
+
 }  // namespace
 
 // Runs Y (+)= A W^T on the MFMA path if the shape allows; false: the caller uses the generic kernel.
 static bool mfma_input_ok(const hawk_ctx* c, int M, int K) {
-    return c->cfg.dtype == HAWK_BF16 && c->off.split && M >= 9 && K % kKC == 0 && (size_t)M * K * 4 <= c->split_bytes;
+    return c->cfg.dtype == HAWK_BF16 && c->off.split && M >= 1 && K % kKC == 0 && (size_t)M * K * 4 <= c->split_bytes;
+}
+
+int gemm_pack_weights(hawk_ctx* c) {
+    if (!c->off.gpack) return 0;
+    for (int i = 0; i < c->n_gpk; ++i) {
+        const auto& e = c->gpk[i];
+        const size_t total = (size_t)e.N * e.K / 8;   // 16-byte chunks
+        pack_tiles_kernel<<<(unsigned)((total + 255) / 256), 256, 0, c->stream>>>(
+            reinterpret_cast<const uint16_t*>(c->ws + c->off.blob + e.blob_off), e.K,
+            reinterpret_cast<v4u*>(c->ws + c->off.gpack + e.pack_off), total);
+    }
+    if (hipGetLastError() != hipSuccess) return -1;
+    return hipStreamSynchronize(c->stream) == hipSuccess ? 0 : -1;
 }
 
 bool presplit_planes(hawk_ctx* c, size_t off_a, int M, int K, uint16_t** hi, uint16_t** lo) {
@@ -215,6 +333,14 @@ bool launch_gemm_mfma(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, i
         split_rows_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, c->stream>>>(wsp<float>(c, off_a), lda, K, hi, lo, total4);
     }
     const uint16_t* W = reinterpret_cast<const uint16_t*>(c->ws + c->off.blob + w_off);
+    int packed = 0;
+    if (c->off.gpack)
+        for (int i = 0; i < c->n_gpk; ++i)
+            if (c->gpk[i].blob_off == w_off && c->gpk[i].N == N && c->gpk[i].K == K) {
+                W = reinterpret_cast<const uint16_t*>(c->ws + c->off.gpack + c->gpk[i].pack_off);
+                packed = 1;
+                break;
+            }
     float* Y = wsp<float>(c, off_y);
     // The smallest tile that still gives every compute unit at most one workgroup: with so few
     // rows the kernel is bound by what one compute unit can stage and feed per k-stage, so the
@@ -230,8 +356,16 @@ bool launch_gemm_mfma(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, i
 #define HAWK_GEMM_TILE(SR, CT, D)                                                                      \
     do {                                                                                               \
         dim3 grid((N + 32 * SR - 1) / (32 * SR), (M + 32 * CT - 1) / (32 * CT), 1);                    \
-        gemm_mfma_kernel<SR, CT, D><<<grid, 256, 0, c->stream>>>(hi, lo, W, N, K, Y, ldy, M, acc);     \
+        gemm_mfma_kernel<SR, CT, D><<<grid, 256, 0, c->stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc);     \
     } while (0)
+    if (M <= 16 && K % 128 == 0) {   // a sliver of rows: barrier-free weight streaming, one wave per K quarter
+        if ((long)(N / 32) >= 2L * cus) {
+            gemv_mfma_kernel<2, 8><<<(N + 31) / 32, 256, 0, c->stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc);
+        } else {
+            gemv_mfma_kernel<1, 8><<<(N + 15) / 16, 256, 0, c->stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc);
+        }
+        return true;
+    }
     if (M <= 32) {
         // A handful of rows: pure weight streaming, and a workgroup's k-stages are a chain of memory
         // round trips.  K is split over several workgroups per tile (about six resident workgroups
@@ -242,7 +376,7 @@ bool launch_gemm_mfma(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, i
         if (ks > 1 && !accumulate)
             (void)hipMemset2DAsync(Y, (size_t)ldy * sizeof(float), 0, (size_t)N * sizeof(float), M, c->stream);
         dim3 grid((N + 31) / 32, 1, ks);
-        gemm_mfma_kernel<1, 1, 4><<<grid, 256, 0, c->stream>>>(hi, lo, W, N, K, Y, ldy, M, acc);
+        gemm_mfma_kernel<1, 1, 4><<<grid, 256, 0, c->stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc);
         return true;
     }
     if (tiles(32, 32) <= cus) HAWK_GEMM_TILE(1, 1, 4);

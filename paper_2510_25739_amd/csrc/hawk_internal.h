@@ -55,6 +55,7 @@ struct Offsets {  // byte offsets into the workspace
     size_t x, a, qkv, o, u, din, g0, g1, ga, logit_s, logit_b, dlogit_s, dlogit_b;
     size_t u_draft, u_acc, u_fin, out_na, out_tok, inv_freq, replay, cond;
     size_t split;   // bf16 hi / lo planes of a GEMM input (batched shapes; 0: not present)
+    size_t gpack;   // tile-major copy of the GEMM weights for the MFMA GEMM / GEMV kernels (0: not present)
     size_t total;
 };
 
@@ -83,6 +84,8 @@ struct hawk_ctx {
     hawk::StreamPlan* plan;  // streaming path: job tables and barrier epoch (null until created)
     size_t blob_bytes;
     size_t split_bytes;
+    struct { size_t blob_off, pack_off; int N, K; } gpk[4 * 128 + 2];  // matrices in the tile-major copy
+    int n_gpk;
     size_t presplit_off;  // activation buffer whose bf16 planes are current (presplit_M rows of presplit_K), 0: none
     int presplit_M, presplit_K;
     // per image
@@ -131,6 +134,8 @@ bool launch_gemm_mfma(hawk_ctx*, size_t off_a, int lda, size_t w_off, int N, int
 // GEMM's bf16 hi / lo planes itself, [row][K] each: true and the planes if such a GEMM takes the
 // MFMA path; the planes then count as current until the next launch_gemm call.
 bool presplit_planes(hawk_ctx*, size_t off_a, int M, int K, uint16_t** hi, uint16_t** lo);
+// fills the tile-major weight copy from the blob (after hawk_load's upload); 0 or -1
+int gemm_pack_weights(hawk_ctx*);
 void launch_rope_append(hawk_ctx*, const RowMap&, int layer, int M);
 void launch_attention(hawk_ctx*, const RowMap&, int layer, int M);
 void launch_swiglu(hawk_ctx*, int M);
