@@ -359,7 +359,7 @@ bool launch_gemm_mfma(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, i
         gemm_mfma_kernel<SR, CT, D><<<grid, 256, 0, c->stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc);     \
     } while (0)
     if (M <= 16 && K % 128 == 0) {   // a sliver of rows: barrier-free weight streaming, one wave per K quarter
-        if ((long)(N / 32) >= 2L * cus) {
+        if ((long)(N / 32) >= (long)cus) {
             gemv_mfma_kernel<2, 8><<<(N + 31) / 32, 256, 0, c->stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc);
         } else {
             gemv_mfma_kernel<1, 8><<<(N + 15) / 16, 256, 0, c->stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc);
