@@ -61,6 +61,21 @@ def test_create_rejects_bad_arguments_without_touching_the_device(H):
     assert lib.hawk_last_error(None) == b"null context"
 
 
+def test_multi_verify_rejects_bad_arguments_before_any_launch(H):
+    lib = C.CDLL(H.lib_path())
+    fn = lib.hawk_multi_verify
+    fn.restype = C.c_int
+    fn.argtypes = [C.c_void_p] * 5 + [C.c_int] * 3 + [C.c_float, C.c_int] + [C.c_void_p] * 4
+    one = C.c_void_p(16)   # never dereferenced: every call below fails validation first
+    assert fn(None, one, one, one, one, 1, 1, 8, 1.0, 8, one, one, None, None) == -1
+    assert fn(one, one, one, one, one, 1, 0, 8, 1.0, 8, one, one, None, None) == -1      # no candidates
+    assert fn(one, one, one, one, one, 1, 1, 0, 1.0, 8, one, one, None, None) == -1      # empty vocabulary
+    assert fn(one, one, one, one, one, 1, 1, 8, -1.0, 8, one, one, None, None) == -1     # negative temperature
+    assert fn(one, one, one, one, one, 1, 1, 8, 1.0, 0, one, one, None, None) == -1      # top_k < 1
+    assert fn(one, one, one, one, one, -1, 1, 8, 1.0, 8, one, one, None, None) == -1
+    assert fn(one, one, one, one, one, 0, 1, 8, 1.0, 8, one, one, None, None) == 0       # no rows: nothing to do
+
+
 def test_product_never_imports_the_oracle():
     pkg = os.path.join(ROOT, "paper_2510_25739_amd")
     for dirpath, _, files in os.walk(pkg):

@@ -442,6 +442,17 @@ def test_streaming_kernel_row_counts_and_batches(H, cfg, k, batch, scale):
     assert_bf16(total, 12, 0.9)
 
 
+@pytest.mark.parametrize("cfg,k,batch,scale,rows", [(1, 3, 3, 3.0, 24), (2, 5, 2, 4.0, 24), (1, 2, 2, 1.0, 6), (2, 5, 1, 4.0, 12)])
+def test_one_kernel_per_operation_row_counts(H, cfg, k, batch, scale, rows):
+    # the one-kernel-per-operation path at row counts between its kernels' regimes: 6 and 12 rows
+    # (MFMA GEMV, one wave per K quarter), 24 rows (MFMA GEMM tiles with K split over workgroups)
+    s = synth.CONFIGS[cfg].replace(n_layers=2, n_cond=24, grid_h=6, grid_w=8, batch=batch, cfg_scale=scale, k=k)
+    assert batch * (2 if scale != 1.0 else 1) * (k + 1) == rows
+    total = accumulate_lockstep(H, s, k, 0, 10, expect_path=0)
+    print("one kernel per operation", (cfg, k, batch, scale), total)
+    assert_bf16(total, 10, 0.9)
+
+
 def test_config3_guidance_batch16_reduced_depth(H):
     # configuration 3 (XL-shaped, guidance 4.0, 16 prompts, k = 5: 32 sequences, 192 rows per
     # target pass) at two layers, a short condition and a small grid, sampled and greedy
