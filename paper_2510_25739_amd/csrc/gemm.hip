@@ -1,19 +1,25 @@
-// Dense GEMM for the batched shapes (many rows per target pass: several prompts, guidance
-// doubling, the prefill): Y[M][N] (+)= A[M][K] * W[N][K]^T with bf16 weights on the MFMA units.
+// GEMMs of the one-kernel-per-operation path on the MFMA units, bf16 weights:
+// Y[M][N] (+)= A[M][K] * W[N][K]^T.
 //
-// The k+1-row verify step of one sequence is a weight-streaming problem and has its own kernels;
-// here every weight byte meets tens to hundreds of rows, so this is a real contraction:
-//   - the fp32 activations are split once per GEMM input into a bf16 hi and a bf16 lo plane
-//     (two MFMAs per tile: fp32-accurate activations), by a small kernel of its own, so that the
-//     GEMM's inner loop only copies 16-byte chunks;
+// The fp32 activations enter as two bf16 planes, hi and lo (two MFMAs per tile: fp32-accurate
+// activations); the kernel that produces a GEMM's input writes them, or split_rows_kernel does.
+// The weights are read from a tile-major copy made when the blob is loaded (pack_tiles_kernel):
+// 16 x 32 tiles of 1 KB in MFMA A-operand order, so that a wave's request is one contiguous
+// kilobyte instead of 64-byte pieces of 16 rows (row-major weights still work, at about half the
+// bandwidth).
+//
+// More than 16 rows (several prompts, guidance doubling, the prefill) - gemm_mfma_kernel: here
+// every weight byte meets tens to hundreds of rows, a real contraction.
 //   - a workgroup of four waves computes a tile of 16*SR*2 output features x 16*CT*2 rows: the
 //     waves sit 2 x 2 over the tile, each holds SR x CT accumulators of v_mfma_f32_16x16x32_bf16;
-//   - weights (the A operand: 16 rows x 32 k per tile, 16 bytes per lane) come straight from
-//     global memory in their stored row-major order; the activation planes of the tile's rows go
-//     through LDS (padded rows, double-buffered, 64 k per stage) because all four waves read them;
+//   - weight tiles go straight from global memory into VGPRs; the activation planes of the tile's
+//     rows go through LDS (padded rows, double-buffered, 64 k per stage) because all four waves
+//     read them;
 //   - D stages are in flight per workgroup, held in a register ring, and the barrier between
 //     stages orders LDS traffic only, so a stage costs its arithmetic and not a memory round trip;
 //   - per k-step a wave issues 2*CT LDS reads for 2*SR*CT MFMAs.
+// Up to 16 rows - gemv_mfma_kernel: weight streaming with a sliver of arithmetic; waves work
+// alone, no LDS staging and no barrier in the loop (see there).
 #include "hawk_internal.h"
 
 namespace hawk {
@@ -65,9 +71,7 @@ __global__ void split_rows_kernel(const float* A, int lda, int K, uint16_t* hi, 
 }
 
 // SR: 16-feature strips per wave, CT: 16-row tiles per wave, D: stages (64 k each) in flight.
-// Tile = (32 SR) features x (32 CT) rows.  blockIdx.z takes one of gridDim.z equal K ranges; if
-// there are several, the partial tiles are added into Y with float atomics (Y then already holds
-// what is accumulated onto, or zeros).
+// Tile = (32 SR) features x (32 CT) rows.
 template <int SR, int CT, int D>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restrict__ hi, const uint16_t* __restrict__ lo,
                                                         const uint16_t* __restrict__ W, int packed, int N, int K,
@@ -80,7 +84,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
     const int wn = wave >> 1, wm = wave & 1;                     // wave position over (features, rows)
     const int n0 = blockIdx.x * BN + wn * 16 * SR, m0 = blockIdx.y * BM;
     const int r16 = lane & 15, kg = lane >> 4;
-    const int nk = K / kKC / (int)gridDim.z, it0 = (int)blockIdx.z * nk;   // this workgroup's k-stages
+    const int nk = K / kKC, it0 = 0;
 
     static_assert(CHUNKS % 256 == 0, "a stage is a whole number of 16-byte chunks per thread");
 
@@ -190,11 +194,6 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
             if (m < M && n < N) {
                 float* dst = Y + (size_t)m * ldy + n;
                 f32x4 v = acc[s][t] + acl[s][t];
-                if (gridDim.z > 1) {   // one of several K ranges: Y already holds what is added onto
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) unsafeAtomicAdd(dst + e, v[e]);   // the hardware add, not a compare-and-swap loop
-                    continue;
-                }
                 if (accumulate) {
                     const float4 old = *reinterpret_cast<const float4*>(dst);
                     v += (f32x4){old.x, old.y, old.z, old.w};
@@ -364,19 +363,6 @@ bool launch_gemm_mfma(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, i
         } else {
             gemv_mfma_kernel<1, 8><<<(N + 15) / 16, 256, 0, c->stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc);
         }
-        return true;
-    }
-    if (M <= 32) {
-        // A handful of rows: pure weight streaming, and a workgroup's k-stages are a chain of memory
-        // round trips.  K is split over several workgroups per tile (about six resident workgroups
-        // per compute unit keep enough bytes in flight); with so few outputs the atomics are cheap.
-        int ks = 1;
-        const long t = tiles(32, 32);
-        while (ks < 16 && t * ks * 2 <= 6L * cus && (K / kKC) % (ks * 2) == 0 && K / kKC / (ks * 2) >= 4) ks *= 2;
-        if (ks > 1 && !accumulate)
-            (void)hipMemset2DAsync(Y, (size_t)ldy * sizeof(float), 0, (size_t)N * sizeof(float), M, c->stream);
-        dim3 grid((N + 31) / 32, 1, ks);
-        gemm_mfma_kernel<1, 1, 4><<<grid, 256, 0, c->stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc);
         return true;
     }
     if (tiles(32, 32) <= cus) HAWK_GEMM_TILE(1, 1, 4);
