@@ -367,8 +367,8 @@ bool launch_gemm_mfma(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, i
     }
     if (tiles(32, 32) <= cus) HAWK_GEMM_TILE(1, 1, 4);
     else if (tiles(32, 64) <= cus) HAWK_GEMM_TILE(1, 2, 4);
-    else if (tiles(32, 96) <= cus) HAWK_GEMM_TILE(1, 3, 4);
-    else if (tiles(64, 96) <= cus) HAWK_GEMM_TILE(2, 3, 3);
+    else if (tiles(64, 64) <= cus) HAWK_GEMM_TILE(2, 2, 3);   // at equal area more features per tile: fewer LDS reads per MFMA
+    else if (tiles(96, 64) <= cus) HAWK_GEMM_TILE(3, 2, 3);
     else HAWK_GEMM_TILE(4, 3, 2);
 #undef HAWK_GEMM_TILE
     return true;
