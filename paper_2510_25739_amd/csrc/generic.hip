@@ -360,83 +360,56 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, c
     __syncthreads();
     const float scale = 1.f / sqrtf((float)hd);
     typedef _Float16 h8 __attribute__((ext_vector_type(8)));
-    // A lane takes 8 features (16 bytes) of every (256 / (hd / 8))-th cache entry, so a wave
-    // requests whole rows of the head (a lane per entry would touch 64 cache lines per request and
-    // fetch each of them hd / 8 times).
-    const int cpr = hd / 8, c8 = tid % cpr, nsl = 256 / cpr, sl = tid / cpr;   // chunks per row, slices
-    // scores: partial dot products over the lane's features, folded over the cpr lanes of an entry
-    // so that lane l ends up with the score of row l % RM
-    float q[RM][8];
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const int cpr = hd / 8;   // 16-byte chunks per cache row of the head
+    // Scores on the matrix cores: a tile of 16 cache entries is the A operand (lane (e, g) holds
+    // features 32 ks + 8 g .. + 7 of entry t0 + e: 16 bytes straight from the fp16 cache), the
+    // query rows - scaled, split into an fp16 hi and lo half so that they keep fp32 accuracy - are
+    // the B operand, and the result lane (row, g) holds the scores of entries t0 + 4 g .. + 3.
+    // Each wave takes every fourth tile.
+    const int r16 = lane & 15, kg = lane >> 4, KS = hd / 32;
+    h8 qh[4], ql[4];
 #pragma unroll
-    for (int r = 0; r < RM; ++r) {
-        const float4 q0 = *reinterpret_cast<const float4*>(sq + r * hd + c8 * 8);
-        const float4 q1 = *reinterpret_cast<const float4*>(sq + r * hd + c8 * 8 + 4);
-        q[r][0] = q0.x * scale; q[r][1] = q0.y * scale; q[r][2] = q0.z * scale; q[r][3] = q0.w * scale;
-        q[r][4] = q1.x * scale; q[r][5] = q1.y * scale; q[r][6] = q1.z * scale; q[r][7] = q1.w * scale;
-    }
-    static_assert(RM == 4 || RM == 8, "the lane folds are written for 4 or 8 rows");
-    const int myr = lane % RM;
-    float mxl = -INFINITY;
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float v = (ks < KS && r16 < RM) ? sq[r16 * hd + ks * 32 + kg * 8 + e] * scale : 0.f;
+            const _Float16 h = (_Float16)v;
+            qh[ks][e] = h;
+            ql[ks][e] = (_Float16)(v - (float)h);
+        }
+    float mxl = -INFINITY;   // running maximum of row r16 over this lane's entries
     {
-        const _Float16* kp = Kc + base + c8 * 8;
-        auto score = [&](int t, const h8& k8) {
-            float a[RM];
+        const _Float16* kp = Kc + base + kg * 8;
+        const int ntile = last / 16 + 1;
+        for (int it = wave; it < ntile; it += 4) {
+            const int t0 = it * 16;
+            const _Float16* row = kp + (size_t)min(t0 + r16, last) * d;   // entries past the end repeat the last (masked below)
+            h8 k8[4];
 #pragma unroll
-            for (int r = 0; r < RM; ++r) {
-                float acc = 0.f;
-                if (r < NR) {
+            for (int ks = 0; ks < 4; ++ks)
+                if (ks < KS) k8[ks] = *reinterpret_cast<const h8*>(row + ks * 32);
+            f4 acc = (f4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) acc += q[r][e] * (float)k8[e];
+            for (int ks = 0; ks < 4; ++ks)
+                if (ks < KS) {
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(k8[ks], qh[ks], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(k8[ks], ql[ks], acc, 0, 0, 0);
                 }
-                a[r] = acc;
-            }
-            // fold over the entry's cpr consecutive lanes with DPP moves: while there are more lanes
-            // than rows every lane adds its partner's values, then each fold halves the rows a lane
-            // carries (the partner keeps the other half)
-            if (cpr == 16) {
+            if (r16 < RM) {
 #pragma unroll
-                for (int r = 0; r < RM; ++r) a[r] += dpp_lane<0x140>(a[r]);
-            }
-            if constexpr (RM == 8) {
-                const bool up = (lane & 4) != 0;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float send = up ? a[i] : a[i + 4], keep = up ? a[i + 4] : a[i];
-                    a[i] = keep + dpp_lane<0x141>(send);
-                }
-            } else {
-#pragma unroll
-                for (int r = 0; r < RM; ++r) a[r] += dpp_lane<0x141>(a[r]);
-            }
-            {
-                const bool up = (lane & 2) != 0;
-#pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    const float send = up ? a[i] : a[i + 2], keep = up ? a[i + 2] : a[i];
-                    a[i] = keep + dpp_lane<0x4E>(send);
+                for (int e = 0; e < 4; ++e) {
+                    const int t = t0 + 4 * kg + e;
+                    const float v = (t <= last && r16 < nrows && t <= pos0 + r16) ? acc[e] : -INFINITY;
+                    if (t <= last) sc[(size_t)t * RM + r16] = v;
+                    mxl = fmaxf(mxl, v);
                 }
             }
-            {
-                const bool up = (lane & 1) != 0;
-                const float send = up ? a[0] : a[1], keep = up ? a[1] : a[0];
-                a[0] = keep + dpp_lane<0xB1>(send);
-            }
-            const float v = (t <= last && myr < nrows && t <= pos0 + myr) ? a[0] : -INFINITY;
-            if (t <= last && c8 < RM) sc[(size_t)t * RM + myr] = v;
-            mxl = fmaxf(mxl, v);
-        };
-        const int nj = (last + nsl) / nsl;   // the same trip count for every lane: the folds need whole groups
-        for (int j0 = 0; j0 < nj; j0 += 8) {   // eight entries in flight per lane
-            h8 k8[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                k8[u] = *reinterpret_cast<const h8*>(kp + (size_t)min(sl + (j0 + u) * nsl, last) * d);
-#pragma unroll
-            for (int u = 0; u < 8; ++u) score(sl + (j0 + u) * nsl, k8[u]);
         }
     }
-    // per-row maximum over the workgroup (lanes l, l + RM, ... of a wave hold row l % RM)
-    for (int o = RM; o < 64; o <<= 1) mxl = fmaxf(mxl, __shfl_xor(mxl, o));
+    // per-row maximum over the workgroup (lanes r, r + 16, r + 32, r + 48 of a wave hold row r)
+    mxl = fmaxf(mxl, __shfl_xor(mxl, 16));
+    mxl = fmaxf(mxl, __shfl_xor(mxl, 32));
     if (lane < RM) red[wave][lane] = mxl;
     float mx[RM];
     __syncthreads();
