@@ -233,7 +233,12 @@ __global__ void rope_append_kernel(typename Cfg::AT* QKV, typename Cfg::KT* Kc, 
     AT* q = QKV + (size_t)blockIdx.x * 3 * d;
     AT* k = q + d;
     AT* v = k + d;
-    size_t base = (((size_t)layer * Smax + ri.s) * Tmax + ri.pos) * d;
+    // cache layout [layer][sequence][head][position][hd]: one head's entries are contiguous
+    const int H = d / hd;
+    auto at = [&](int e) {   // element e of the row (feature index within d)
+        const int h = e / hd;
+        return ((((size_t)layer * Smax + ri.s) * H + h) * Tmax + ri.pos) * hd + (e - h * hd);
+    };
     // the angles depend on the position and the pair index within a head only: one sincos per pair
     // index and row, shared by all heads through LDS (hd <= 512)
     __shared__ double tab_c[256], tab_s[256];
@@ -259,10 +264,10 @@ __global__ void rope_append_kernel(typename Cfg::AT* QKV, typename Cfg::KT* Kc, 
                 const AT c = (AT)tab_c[j], sn = (AT)tab_s[j];
                 q[2 * p] = qa[u] * c - qb[u] * sn;
                 q[2 * p + 1] = qa[u] * sn + qb[u] * c;
-                kstore(Kc, base + 2 * p, ka[u] * c - kb[u] * sn);
-                kstore(Kc, base + 2 * p + 1, ka[u] * sn + kb[u] * c);
-                kstore(Vc, base + 2 * p, va[u]);
-                kstore(Vc, base + 2 * p + 1, vb[u]);
+                kstore(Kc, at(2 * p), ka[u] * c - kb[u] * sn);
+                kstore(Kc, at(2 * p + 1), ka[u] * sn + kb[u] * c);
+                kstore(Vc, at(2 * p), va[u]);
+                kstore(Vc, at(2 * p + 1), vb[u]);
             }
         }
     }
@@ -285,14 +290,14 @@ __global__ __launch_bounds__(256) void attention_kernel(const typename Cfg::AT* 
     const int R = blockIdx.y, h = blockIdx.x, tid = threadIdx.x;
     RowInfo ri = row_info(map, R);
     if (!ri.valid) return;
-    const size_t base = (((size_t)layer * Smax + ri.s) * Tmax) * d + (size_t)h * hd;
+    const size_t base = ((((size_t)layer * Smax + ri.s) * (d / hd) + h) * Tmax) * hd;   // this head's entries, contiguous
     for (int i = tid; i < hd; i += 256) sq[i] = QKV[(size_t)R * 3 * d + (size_t)h * hd + i];
     __syncthreads();
     const AT scale = (AT)1 / sqrt((AT)hd);
     AT mx = -INFINITY;
     for (int t = tid; t <= ri.pos; t += 256) {
         AT s = 0;
-        for (int i = 0; i < hd; ++i) s += sq[i] * kload(Kc, base + (size_t)t * d + i);
+        for (int i = 0; i < hd; ++i) s += sq[i] * kload(Kc, base + (size_t)t * hd + i);
         s *= scale;
         sc[t] = s;
         mx = s > mx ? s : mx;
@@ -307,7 +312,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const typename Cfg::AT* 
     den = block_sum256(den, red);  // also orders the sc[] writes before the reads below
     const int i = tid % hd, sl = tid / hd, nsl = 256 / hd;
     AT acc = 0;
-    for (int t = sl; t <= ri.pos; t += nsl) acc += sc[t] * kload(Vc, base + (size_t)t * d + i);
+    for (int t = sl; t <= ri.pos; t += nsl) acc += sc[t] * kload(Vc, base + (size_t)t * hd + i);
     part[tid] = acc;
     __syncthreads();
     if (tid < hd) {
@@ -352,7 +357,7 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, c
         }
     if (!r0.valid) return;
     const int pos0 = r0.pos, last = pos0 + nrows - 1;
-    const size_t base = (((size_t)layer * Smax + s) * Tmax) * d + (size_t)h * hd;
+    const size_t base = ((((size_t)layer * Smax + s) * (d / hd) + h) * Tmax) * hd;   // this head's entries, contiguous
     for (int i = tid; i < RM * hd; i += 256) {
         const int r = i / hd, c = i - r * hd;
         sq[i] = r < nrows ? QKV[(size_t)(R0 + r) * 3 * d + (size_t)h * hd + c] : 0.f;
@@ -384,7 +389,7 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, c
         const int ntile = last / 16 + 1;
         for (int it = wave; it < ntile; it += 4) {
             const int t0 = it * 16;
-            const _Float16* row = kp + (size_t)min(t0 + r16, last) * d;   // entries past the end repeat the last (masked below)
+            const _Float16* row = kp + (size_t)min(t0 + r16, last) * hd;   // entries past the end repeat the last (masked below)
             h8 k8[4];
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
@@ -467,11 +472,11 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, c
     for (; t + 7 * nsv <= last; t += 8 * nsv) {   // eight entries in flight per lane
         h8 v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const h8*>(vp + (size_t)(t + u * nsv) * d);
+        for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const h8*>(vp + (size_t)(t + u * nsv) * hd);
 #pragma unroll
         for (int u = 0; u < 8; ++u) fold(t + u * nsv, v[u]);
     }
-    for (; t <= last; t += nsv) fold(t, *reinterpret_cast<const h8*>(vp + (size_t)t * d));
+    for (; t <= last; t += nsv) fold(t, *reinterpret_cast<const h8*>(vp + (size_t)t * hd));
 #pragma unroll
     for (int r = 0; r < RM; ++r)
 #pragma unroll

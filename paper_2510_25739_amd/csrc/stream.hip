@@ -456,8 +456,9 @@ __device__ __forceinline__ void epilogue(const SP& p, const Lds& s, int layer, i
             } else {
                 const RowPos rp = row_pos(p, c);
                 if (rp.valid) {
+                    // cache layout [layer][sequence][head][position][64]: a strip lies inside one head
                     _Float16* dst = (seg == 1 ? p.Kc : p.Vc) +
-                                    (((size_t)layer * p.Smax + rp.seq) * p.Tmax + rp.pos) * d + j0 + 4 * quad;
+                                    ((((size_t)layer * p.Smax + rp.seq) * p.H + j0 / 64) * p.Tmax + rp.pos) * 64 + j0 % 64 + 4 * quad;
                     const _Float16 h0 = (_Float16)a0, h1 = (_Float16)b0, h2 = (_Float16)a1, h3 = (_Float16)b1;
                     st_u64(dst,
                            (unsigned)__builtin_bit_cast(unsigned short, h0) | ((unsigned)__builtin_bit_cast(unsigned short, h1) << 16),
@@ -911,15 +912,15 @@ __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& b
     const int kv0 = ke >= 0 ? p.C + p.n[b] - 1 : 0;  // positions cached before this launch
     const int o0 = (int)((long long)kv0 * ch / p.NC), o1 = (int)((long long)kv0 * (ch + 1) / p.NC);
     const int nrounds = (o1 - o0 + kNIT * kCW * 8 - 1) / (kNIT * kCW * 8);
-    const size_t base = (((size_t)layer * p.Smax + seq) * p.Tmax) * d + (size_t)h * 64 + dg * 8;
+    const size_t base = ((((size_t)layer * p.Smax + seq) * p.H + h) * p.Tmax) * 64 + dg * 8;   // this head's entries, contiguous
     v4u ka[kNIT], va[kNIT], kb[kNIT], vb[kNIT];
     auto fetch = [&](v4u (&kk)[kNIT], v4u (&vv)[kNIT], int rnd) {
 #pragma unroll
         for (int it = 0; it < kNIT; ++it) {
             const int pos = o0 + (rnd * kNIT + it) * (kCW * 8) + wave * 8 + pg;
             if (pos < o1) {
-                kk[it] = *reinterpret_cast<const v4u*>(p.Kc + base + (size_t)pos * d);
-                vv[it] = *reinterpret_cast<const v4u*>(p.Vc + base + (size_t)pos * d);
+                kk[it] = *reinterpret_cast<const v4u*>(p.Kc + base + (size_t)pos * 64);
+                vv[it] = *reinterpret_cast<const v4u*>(p.Vc + base + (size_t)pos * 64);
             } else {
                 kk[it] = (v4u){0u, 0u, 0u, 0u};
                 vv[it] = (v4u){0u, 0u, 0u, 0u};
@@ -973,8 +974,8 @@ __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& b
         }
         stamp_c(p, ph, 3);
         if (ch == p.NC - 1 && wave == 0 && pg <= ke) {  // rows appended by this launch: coherent loads
-            const _Float16* kp = p.Kc + base + (size_t)(kv0 + pg) * d;
-            const _Float16* vp = p.Vc + base + (size_t)(kv0 + pg) * d;
+            const _Float16* kp = p.Kc + base + (size_t)(kv0 + pg) * 64;
+            const _Float16* vp = p.Vc + base + (size_t)(kv0 + pg) * 64;
             const u64 a0 = __hip_atomic_load(reinterpret_cast<const u64*>(kp), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const u64 a1 = __hip_atomic_load(reinterpret_cast<const u64*>(kp) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const u64 b0 = __hip_atomic_load(reinterpret_cast<const u64*>(vp), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
