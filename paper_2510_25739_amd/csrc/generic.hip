@@ -387,27 +387,35 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, c
     {
         const _Float16* kp = Kc + base + kg * 8;
         const int ntile = last / 16 + 1;
-        for (int it = wave; it < ntile; it += 4) {
-            const int t0 = it * 16;
-            const _Float16* row = kp + (size_t)min(t0 + r16, last) * hd;   // entries past the end repeat the last (masked below)
-            h8 k8[4];
+        constexpr int TB = 4;   // tiles requested together: their loads overlap
+        for (int ib = wave; ib < ntile; ib += 4 * TB) {
+            h8 k8[TB][4];
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                if (ks < KS) k8[ks] = *reinterpret_cast<const h8*>(row + ks * 32);
-            f4 acc = (f4){0.f, 0.f, 0.f, 0.f};
+            for (int u = 0; u < TB; ++u) {
+                // tiles and entries past the end repeat the last entry (masked below)
+                const _Float16* row = kp + (size_t)min((ib + 4 * u) * 16 + r16, last) * hd;
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                if (ks < KS) {
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(k8[ks], qh[ks], acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(k8[ks], ql[ks], acc, 0, 0, 0);
-                }
-            if (r16 < RM) {
+                for (int ks = 0; ks < 4; ++ks)
+                    if (ks < KS) k8[u][ks] = *reinterpret_cast<const h8*>(row + ks * 32);
+            }
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int t = t0 + 4 * kg + e;
-                    const float v = (t <= last && r16 < nrows && t <= pos0 + r16) ? acc[e] : -INFINITY;
-                    if (t <= last) sc[(size_t)t * RM + r16] = v;
-                    mxl = fmaxf(mxl, v);
+            for (int u = 0; u < TB; ++u) {
+                const int t0 = (ib + 4 * u) * 16;
+                f4 acc = (f4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    if (ks < KS) {
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(k8[u][ks], qh[ks], acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(k8[u][ks], ql[ks], acc, 0, 0, 0);
+                    }
+                if (r16 < RM) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int t = t0 + 4 * kg + e;
+                        const float v = (t <= last && r16 < nrows && t <= pos0 + r16) ? acc[e] : -INFINITY;
+                        if (t <= last) sc[(size_t)t * RM + r16] = v;
+                        mxl = fmaxf(mxl, v);
+                    }
                 }
             }
         }
