@@ -99,7 +99,10 @@ const char* hawk_last_error(const hawk_ctx* ctx);
  * of the upper neighbour] followed by the target's own final norm and output projection
  * (draft heads on the final hidden state: Preliminary, "Utilization of Draft Heads
  * Structure"; spatial neighbours x_{T-1}, x_{T-IW}: Preliminary, "Attention Sinking").
- * Header fields must match the context's configuration. */
+ * Header fields must match the context's configuration.  For bf16 the workspace then holds
+ * the blob plus re-tiled copies of the GEMM weights in MFMA operand order (one for the
+ * persistent kernel where it covers the shape, one tile-major copy for the other GEMM kernels):
+ * hawk_workspace_bytes accounts for them. */
 int hawk_load(hawk_ctx* ctx, const void* host_blob, size_t nbytes);
 
 /* hawk_prefill(cond): runs the target over the condition vectors (host, fp32
