@@ -142,7 +142,7 @@ void run_layers(hawk_ctx* c, const RowMap& map, int M) {
     for (int l = 0; l < c->L; ++l) {
         launch_rmsnorm(c, o.x, d, c->w.g1[l], o.a, M, true);
         launch_gemm(c, o.a, d, c->w.Wqkv[l], 3 * d, d, o.qkv, 3 * d, M, false, false);
-        launch_rope_append(c, map, l, M);
+        if (!attention_does_rope(c, map)) launch_rope_append(c, map, l, M);
         launch_attention(c, map, l, M);
         launch_gemm(c, o.o, d, c->w.Wo[l], d, d, o.x, d, M, true, false);
         launch_rmsnorm(c, o.x, d, c->w.g2[l], o.a, M, true);

@@ -334,17 +334,15 @@ template <int CTRL> __device__ __forceinline__ float dpp_lane(float v) {
 // storage and lane folds are laid out for RM rows, arithmetic is spent on NR;
 // hd = 64 or 128.
 template <int RM, int NR>
-__global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, const _Float16* Kc, const _Float16* Vc,
-                                                             float* O, RowMap map, int layer, int d, int hd, int Smax,
-                                                             int Tmax, uint16_t* hi, uint16_t* lo) {
+__global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, _Float16* Kc, _Float16* Vc, float* O,
+                                                             RowMap map, const double* inv_freq, int layer, int d,
+                                                             int hd, int Smax, int Tmax, uint16_t* hi, uint16_t* lo) {
     extern __shared__ double smem_raw[];
     float* sq = reinterpret_cast<float*>(smem_raw);   // [RM][hd] queries
     float* sc = sq + RM * hd;                         // [Tmax][RM] scores, then weights
     float* part = sc + (size_t)Tmax * RM;             // [4 waves][RM][hd] partial outputs
     __shared__ float red[4][RM];
-    // sequences along x: consecutive workgroup ids go to the XCDs in turn, so with the sequence
-    // count a multiple of the XCD count all heads of a sequence - which share every 2d-byte cache
-    // row - run on one XCD at about the same time (one L2, open DRAM pages)
+    // sequences along x, heads along y
     const int s = blockIdx.x, h = blockIdx.y, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int R0 = s * map.rows_per_seq;
     const RowInfo r0 = row_info(map, R0);
@@ -358,11 +356,31 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, c
     if (!r0.valid) return;
     const int pos0 = r0.pos, last = pos0 + nrows - 1;
     const size_t base = ((((size_t)layer * Smax + s) * (d / hd) + h) * Tmax) * hd;   // this head's entries, contiguous
-    for (int i = tid; i < RM * hd; i += 256) {
-        const int r = i / hd, c = i - r * hd;
-        sq[i] = r < nrows ? QKV[(size_t)(R0 + r) * 3 * d + (size_t)h * hd + c] : 0.f;
+    // The rows' own rotary step and cache append happen here (QKV holds the raw projections): the
+    // workgroup rotates its head's q and k rows (pair (2j, 2j+1) by pos * inv_freq[j], as
+    // rope_append_kernel does), keeps q in LDS and writes k, v to the cache, where the passes below
+    // read them back like every other entry.
+    for (int i = tid; i < RM * (hd / 2); i += 256) {
+        const int r = i / (hd / 2), j = i - r * (hd / 2);
+        float q0 = 0.f, q1 = 0.f;
+        if (r < nrows) {
+            double sn, cs;
+            sincos((double)(pos0 + r) * inv_freq[j], &sn, &cs);
+            const float c = (float)cs, sf = (float)sn;
+            const float* row = QKV + (size_t)(R0 + r) * 3 * d + (size_t)h * hd + 2 * j;
+            const float qa = row[0], qb = row[1], ka = row[d], kb = row[d + 1];
+            q0 = qa * c - qb * sf;
+            q1 = qa * sf + qb * c;
+            const size_t at = base + (size_t)(pos0 + r) * hd + 2 * j;
+            Kc[at] = (_Float16)(ka * c - kb * sf);
+            Kc[at + 1] = (_Float16)(ka * sf + kb * c);
+            Vc[at] = (_Float16)row[2 * d];
+            Vc[at + 1] = (_Float16)row[2 * d + 1];
+        }
+        sq[r * hd + 2 * j] = q0;
+        sq[r * hd + 2 * j + 1] = q1;
     }
-    __syncthreads();
+    __syncthreads();   // also makes the appended entries visible to the other waves of the workgroup
     const float scale = 1.f / sqrtf((float)hd);
     typedef _Float16 h8 __attribute__((ext_vector_type(8)));
     typedef float f4 __attribute__((ext_vector_type(4)));
@@ -641,19 +659,28 @@ void launch_rope_append(hawk_ctx* c, const RowMap& map, int layer, int M) {
                     c->Smax, c->Tmax)));
 }
 
-void launch_attention(hawk_ctx* c, const RowMap& map, int layer, int M) {
-    constexpr int RM = 8;
+// Step rows of a bf16 context go through attention_rows_kernel, which also does the rotary step
+// and the cache append of its rows.
+static size_t attention_rows_lds(const hawk_ctx* c) {
+    return ((size_t)8 * c->hd + (size_t)c->Tmax * 8 + (size_t)4 * 8 * c->hd) * sizeof(float);
+}
+bool attention_does_rope(const hawk_ctx* c, const RowMap& map) {
     const int cpr = c->hd / 8;
-    if (c->cfg.dtype == HAWK_BF16 && map.mode == 1 && map.rows_per_seq <= RM && (cpr == 8 || cpr == 16)) {
-        const size_t lds = ((size_t)RM * c->hd + (size_t)c->Tmax * RM + (size_t)4 * RM * c->hd) * sizeof(float);
-        if (lds <= 60 * 1024) {
+    return c->cfg.dtype == HAWK_BF16 && map.mode == 1 && map.rows_per_seq <= 8 && (cpr == 8 || cpr == 16) &&
+           attention_rows_lds(c) <= 60 * 1024;
+}
+
+void launch_attention(hawk_ctx* c, const RowMap& map, int layer, int M) {
+    if (attention_does_rope(c, map)) {
+        const size_t lds = attention_rows_lds(c);
+        {
             dim3 grid(M / map.rows_per_seq, c->H);
             uint16_t *hi = nullptr, *lo = nullptr;
             presplit_planes(c, c->off.o, M, c->d, &hi, &lo);   // the Wo GEMM reads the result next
 #define HAWK_ATTN_ROWS(RMV, NRV)                                                                       \
     attention_rows_kernel<RMV, NRV><<<grid, 256, lds, c->stream>>>(                                    \
         wsp<float>(c, c->off.qkv), wsp<_Float16>(c, c->off.kc), wsp<_Float16>(c, c->off.vc),           \
-        wsp<float>(c, c->off.o), map, layer, c->d, c->hd, c->Smax, c->Tmax, hi, lo)
+        wsp<float>(c, c->off.o), map, wsp<double>(c, c->off.inv_freq), layer, c->d, c->hd, c->Smax, c->Tmax, hi, lo)
             if (map.rows_per_seq <= 2) HAWK_ATTN_ROWS(4, 2);
             else if (map.rows_per_seq <= 4) HAWK_ATTN_ROWS(4, 4);
             else if (map.rows_per_seq <= 6) HAWK_ATTN_ROWS(8, 6);

@@ -138,6 +138,8 @@ bool presplit_planes(hawk_ctx*, size_t off_a, int M, int K, uint16_t** hi, uint1
 int gemm_pack_weights(hawk_ctx*);
 void launch_rope_append(hawk_ctx*, const RowMap&, int layer, int M);
 void launch_attention(hawk_ctx*, const RowMap&, int layer, int M);
+// true: launch_attention also rotates q, k and appends k, v for these rows (no launch_rope_append)
+bool attention_does_rope(const hawk_ctx*, const RowMap&);
 void launch_swiglu(hawk_ctx*, int M);
 void launch_draft_input(hawk_ctx*, int i);                     // [g | E[left] | E[up]]
 void launch_keep_hprev_prefill(hawk_ctx*);
