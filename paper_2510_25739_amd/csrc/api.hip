@@ -102,21 +102,22 @@ bool derive(const hawk_config* g, hawk_ctx* c) {
     const size_t widest = 3 * d > m ? 3 * d : m;
     c->split_bytes = g->dtype == HAWK_BF16 ? M * widest * 4 : 0;
     o.split = c->split_bytes ? take(c->split_bytes) : 0;
+    o.split2 = c->split_bytes ? take(M * m * 4) : 0;
     // Tile-major copy of every GEMM weight (16 x 32 tiles, 1 KB each, in MFMA operand order): the
     // MFMA kernels then fetch whole kilobytes per request instead of 64-byte pieces of 16 rows.
     c->n_gpk = 0;
     o.gpack = 0;
     if (g->dtype == HAWK_BF16 && d % 32 == 0 && m % 32 == 0 && Vs % 16 == 0) {
         size_t q = 0;
-        auto reg = [&](size_t blob_off, size_t N, size_t K) {
+        auto reg = [&](size_t blob_off, size_t N, size_t K, int pairs = 0) {
             auto& e2 = c->gpk[c->n_gpk++];
-            e2.blob_off = blob_off; e2.pack_off = q; e2.N = (int)N; e2.K = (int)K;
+            e2.blob_off = blob_off; e2.pack_off = q; e2.N = (int)N; e2.K = (int)K; e2.pairs = pairs;
             q += N * K * 2;
         };
         for (int l = 0; l < c->L; ++l) {
             reg(c->w.Wqkv[l], 3 * d, d);
             reg(c->w.Wo[l], d, d);
-            reg(c->w.W13[l], 2 * m, d);
+            reg(c->w.W13[l], 2 * m, d, (int)m);   // W1 and W3 rows interleaved: SwiGLU in the GEMM's epilogue
             reg(c->w.W2[l], d, m);
         }
         reg(c->w.W_out + (size_t)g->samp_lo * d * e, Vs, d);
@@ -146,8 +147,10 @@ void run_layers(hawk_ctx* c, const RowMap& map, int M) {
         launch_attention(c, map, l, M);
         launch_gemm(c, o.o, d, c->w.Wo[l], d, d, o.x, d, M, true, false);
         launch_rmsnorm(c, o.x, d, c->w.g2[l], o.a, M, true);
-        launch_gemm(c, o.a, d, c->w.W13[l], 2 * m, d, o.u, 2 * m, M, false, false);
-        launch_swiglu(c, M);
+        if (!launch_gemm_swiglu(c, o.a, d, c->w.W13[l], m, d, o.u, M)) {
+            launch_gemm(c, o.a, d, c->w.W13[l], 2 * m, d, o.u, 2 * m, M, false, false);
+            launch_swiglu(c, M);
+        }
         launch_gemm(c, o.u, 2 * m, c->w.W2[l], d, m, o.x, d, M, true, false);
     }
 }

@@ -45,12 +45,30 @@ __device__ __forceinline__ void lds_barrier() {
 // Tile-major copy of W[N][K] (N % 16 == 0, K % 32 == 0): tile (strip s, k-tile kt) is the 1 KB
 // block number s * (K / 32) + kt; inside it lane l of a wave owns bytes 16 l .. 16 l + 15 = row
 // s * 16 + l % 16, columns kt * 32 + (l / 16) * 8 .. + 7: one MFMA A operand per tile.
-__global__ void pack_tiles_kernel(const uint16_t* W, int K, v4u* dst, size_t total) {
+// pairs > 0 (W1|W3, pairs = m): strip s holds W1 rows 8 s .. 8 s + 7 and the matching W3 rows
+// interleaved (row 2 j = W1 row 8 s + j, row 2 j + 1 = W3 row 8 s + j), so that an MFMA result lane
+// holds both halves of a SwiGLU pair.
+__global__ void pack_tiles_kernel(const uint16_t* W, int K, v4u* dst, size_t total, int pairs) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= total) return;
-    const int lane = (int)(i & 63);
+    const int lane = (int)(i & 63), r = lane & 15;
     const size_t tile = i >> 6, kts = (size_t)K / 32, s = tile / kts, kt = tile - s * kts;
-    dst[i] = *reinterpret_cast<const v4u*>(W + (s * 16 + (lane & 15)) * (size_t)K + kt * 32 + (lane >> 4) * 8);
+    const size_t row = pairs ? (size_t)(r & 1) * pairs + s * 8 + (r >> 1) : s * 16 + r;
+    dst[i] = *reinterpret_cast<const v4u*>(W + row * (size_t)K + kt * 32 + (lane >> 4) * 8);
+}
+
+// SwiGLU of an MFMA result lane of a pair-interleaved W1|W3 tile: v = (a0, b0, a1, b1) -> two
+// hidden features; writes them as fp32 into U (row stride ldy) and as bf16 hi / lo into the planes
+// of the GEMM that follows (row stride om).
+__device__ __forceinline__ void swiglu_store(f32x4 v, float* U, int ldy, uint16_t* ohi, uint16_t* olo, int om, int row,
+                                             int f0) {
+    const float h0 = v[0] / (1.0f + expf(-v[0])) * v[1], h1 = v[2] / (1.0f + expf(-v[2])) * v[3];
+    *reinterpret_cast<float2*>(U + (size_t)row * ldy + f0) = make_float2(h0, h1);
+    unsigned a0, b0, a1, b1;
+    bf16_split(h0, a0, b0);
+    bf16_split(h1, a1, b1);
+    *reinterpret_cast<unsigned*>(ohi + (size_t)row * om + f0) = a0 | (a1 << 16);
+    *reinterpret_cast<unsigned*>(olo + (size_t)row * om + f0) = b0 | (b1 << 16);
 }
 
 // hi[r][j], lo[r][j] = bf16 split of A[r * lda + j], r < M, j < K (K % 4 == 0).
@@ -75,7 +93,8 @@ __global__ void split_rows_kernel(const float* A, int lda, int K, uint16_t* hi, 
 template <int SR, int CT, int D>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restrict__ hi, const uint16_t* __restrict__ lo,
                                                         const uint16_t* __restrict__ W, int packed, int N, int K,
-                                                        float* Y, int ldy, int M, int accumulate) {
+                                                        float* Y, int ldy, int M, int accumulate, uint16_t* ohi,
+                                                        uint16_t* olo, int om) {
     constexpr int BM = 32 * CT, BN = 32 * SR;
     constexpr int CHUNKS = 2 * BM * (kKC / 8);       // 16-byte chunks of one stage (both planes)
     constexpr int PER_T = (CHUNKS + 255) / 256;
@@ -194,6 +213,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
             if (m < M && n < N) {
                 float* dst = Y + (size_t)m * ldy + n;
                 f32x4 v = acc[s][t] + acl[s][t];
+                if (om > 0) {   // pair-interleaved W1|W3: n / 2 is the first of the lane's two hidden features
+                    swiglu_store(v, Y, ldy, ohi, olo, om, m, n / 2);
+                    continue;
+                }
                 if (accumulate) {
                     const float4 old = *reinterpret_cast<const float4*>(dst);
                     v += (f32x4){old.x, old.y, old.z, old.w};
@@ -212,7 +235,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const uint16_t* __restri
 template <int SR, int D>
 __global__ __launch_bounds__(256) void gemv_mfma_kernel(const uint16_t* __restrict__ hi, const uint16_t* __restrict__ lo,
                                                         const uint16_t* __restrict__ W, int packed, int N, int K,
-                                                        float* Y, int ldy, int M, int accumulate) {
+                                                        float* Y, int ldy, int M, int accumulate, uint16_t* ohi,
+                                                        uint16_t* olo, int om) {
     __shared__ f32x4 red[3][SR][64];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r16 = lane & 15, kg = lane >> 4;
@@ -280,6 +304,10 @@ __global__ __launch_bounds__(256) void gemv_mfma_kernel(const uint16_t* __restri
         const int n = n0 + s * 16 + 4 * kg;
         if (r16 < M && n < N) {
             float* dst = Y + (size_t)r16 * ldy + n;
+            if (om > 0) {   // pair-interleaved W1|W3
+                swiglu_store(v, Y, ldy, ohi, olo, om, r16, n / 2);
+                continue;
+            }
             if (accumulate) {
                 const float4 old = *reinterpret_cast<const float4*>(dst);
                 v += (f32x4){old.x, old.y, old.z, old.w};
@@ -303,7 +331,7 @@ int gemm_pack_weights(hawk_ctx* c) {
         const size_t total = (size_t)e.N * e.K / 8;   // 16-byte chunks
         pack_tiles_kernel<<<(unsigned)((total + 255) / 256), 256, 0, c->stream>>>(
             reinterpret_cast<const uint16_t*>(c->ws + c->off.blob + e.blob_off), e.K,
-            reinterpret_cast<v4u*>(c->ws + c->off.gpack + e.pack_off), total);
+            reinterpret_cast<v4u*>(c->ws + c->off.gpack + e.pack_off), total, e.pairs);
     }
     if (hipGetLastError() != hipSuccess) return -1;
     return hipStreamSynchronize(c->stream) == hipSuccess ? 0 : -1;
@@ -316,31 +344,45 @@ bool presplit_planes(hawk_ctx* c, size_t off_a, int M, int K, uint16_t** hi, uin
     c->presplit_off = off_a;
     c->presplit_M = M;
     c->presplit_K = K;
+    c->presplit_buf = 0;
     return true;
 }
 
-bool launch_gemm_mfma(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, int K, size_t off_y, int ldy, int M,
-                      bool accumulate) {
-    const bool presplit = c->presplit_off == off_a && c->presplit_M == M && c->presplit_K == K;
-    c->presplit_off = 0;
-    if (!mfma_input_ok(c, M, K)) return false;
-    if (N % 16 || ldy % 4 || lda % 4) return false;
-    uint16_t* hi = wsp<uint16_t>(c, c->off.split);
-    uint16_t* lo = hi + (size_t)M * K;
-    if (!presplit) {
-        const size_t total4 = (size_t)M * (K / 4);
-        split_rows_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, c->stream>>>(wsp<float>(c, off_a), lda, K, hi, lo, total4);
+// Common body: Y (+)= A W^T, or with swiglu_m > 0 the fused W1|W3 form (N = 2 swiglu_m).
+static bool run_mfma(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, int K, size_t off_y, int ldy, int M,
+                     bool accumulate, int swiglu_m) {
+    if (!mfma_input_ok(c, M, K) || N % 16 || ldy % 4 || lda % 4) {
+        if (!swiglu_m) c->presplit_off = 0;
+        return false;
     }
     const uint16_t* W = reinterpret_cast<const uint16_t*>(c->ws + c->off.blob + w_off);
     int packed = 0;
     if (c->off.gpack)
         for (int i = 0; i < c->n_gpk; ++i)
-            if (c->gpk[i].blob_off == w_off && c->gpk[i].N == N && c->gpk[i].K == K) {
+            if (c->gpk[i].blob_off == w_off && c->gpk[i].N == N && c->gpk[i].K == K && c->gpk[i].pairs == swiglu_m) {
                 W = reinterpret_cast<const uint16_t*>(c->ws + c->off.gpack + c->gpk[i].pack_off);
                 packed = 1;
                 break;
             }
+    if (swiglu_m && (!packed || !c->off.split2)) return false;   // the caller falls back to GEMM + SwiGLU kernel
+    const bool presplit = c->presplit_off == off_a && c->presplit_M == M && c->presplit_K == K;
+    c->presplit_off = 0;
+    uint16_t* hi = wsp<uint16_t>(c, presplit && c->presplit_buf ? c->off.split2 : c->off.split);
+    uint16_t* lo = hi + (size_t)M * K;
+    if (!presplit) {
+        const size_t total4 = (size_t)M * (K / 4);
+        split_rows_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, c->stream>>>(wsp<float>(c, off_a), lda, K, hi, lo, total4);
+    }
     float* Y = wsp<float>(c, off_y);
+    uint16_t *ohi = nullptr, *olo = nullptr;
+    if (swiglu_m) {   // the result's planes go to the second pair (the first is being read) and count as current
+        ohi = wsp<uint16_t>(c, c->off.split2);
+        olo = ohi + (size_t)M * swiglu_m;
+        c->presplit_off = off_y;
+        c->presplit_M = M;
+        c->presplit_K = swiglu_m;
+        c->presplit_buf = 1;
+    }
     // The smallest tile that still gives every compute unit at most one workgroup: with so few
     // rows the kernel is bound by what one compute unit can stage and feed per k-stage, so the
     // work is spread as widely as one round of workgroups allows; larger grids than that only
@@ -355,13 +397,14 @@ bool launch_gemm_mfma(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, i
 #define HAWK_GEMM_TILE(SR, CT, D)                                                                      \
     do {                                                                                               \
         dim3 grid((N + 32 * SR - 1) / (32 * SR), (M + 32 * CT - 1) / (32 * CT), 1);                    \
-        gemm_mfma_kernel<SR, CT, D><<<grid, 256, 0, c->stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc);     \
+        gemm_mfma_kernel<SR, CT, D><<<grid, 256, 0, c->stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc, ohi, olo,    \
+                                                                  swiglu_m);                            \
     } while (0)
     if (M <= 16 && K % 128 == 0) {   // a sliver of rows: barrier-free weight streaming, one wave per K quarter
         if ((long)(N / 32) >= (long)cus) {
-            gemv_mfma_kernel<2, 8><<<(N + 31) / 32, 256, 0, c->stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc);
+            gemv_mfma_kernel<2, 8><<<(N + 31) / 32, 256, 0, c->stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc, ohi, olo, swiglu_m);
         } else {
-            gemv_mfma_kernel<1, 8><<<(N + 15) / 16, 256, 0, c->stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc);
+            gemv_mfma_kernel<1, 8><<<(N + 15) / 16, 256, 0, c->stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc, ohi, olo, swiglu_m);
         }
         return true;
     }
@@ -372,6 +415,15 @@ bool launch_gemm_mfma(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, i
     else HAWK_GEMM_TILE(4, 3, 2);
 #undef HAWK_GEMM_TILE
     return true;
+}
+
+bool launch_gemm_mfma(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, int K, size_t off_y, int ldy, int M,
+                      bool accumulate) {
+    return run_mfma(c, off_a, lda, w_off, N, K, off_y, ldy, M, accumulate, 0);
+}
+
+bool launch_gemm_swiglu(hawk_ctx* c, size_t off_a, int lda, size_t w13_off, int m, int K, size_t off_u, int M) {
+    return run_mfma(c, off_a, lda, w13_off, 2 * m, K, off_u, 2 * m, M, false, m);
 }
 
 }  // namespace hawk

@@ -55,6 +55,7 @@ struct Offsets {  // byte offsets into the workspace
     size_t x, a, qkv, o, u, din, g0, g1, ga, logit_s, logit_b, dlogit_s, dlogit_b;
     size_t u_draft, u_acc, u_fin, out_na, out_tok, inv_freq, replay, cond;
     size_t split;   // bf16 hi / lo planes of a GEMM input (batched shapes; 0: not present)
+    size_t split2;  // second pair of planes: written by a GEMM's own epilogue while it reads the first
     size_t gpack;   // tile-major copy of the GEMM weights for the MFMA GEMM / GEMV kernels (0: not present)
     size_t total;
 };
@@ -84,10 +85,11 @@ struct hawk_ctx {
     hawk::StreamPlan* plan;  // streaming path: job tables and barrier epoch (null until created)
     size_t blob_bytes;
     size_t split_bytes;
-    struct { size_t blob_off, pack_off; int N, K; } gpk[4 * 128 + 2];  // matrices in the tile-major copy
+    // matrices in the tile-major copy; pairs = m for W1|W3 stored with rows interleaved (W1 row f, W3 row f, ...)
+    struct { size_t blob_off, pack_off; int N, K, pairs; } gpk[4 * 128 + 2];
     int n_gpk;
     size_t presplit_off;  // activation buffer whose bf16 planes are current (presplit_M rows of presplit_K), 0: none
-    int presplit_M, presplit_K;
+    int presplit_M, presplit_K, presplit_buf;
     // per image
     int B, S, C, gh, gw, N, top_k, greedy;
     float temperature, inv_t, cfg_scale;
@@ -140,6 +142,9 @@ void launch_rope_append(hawk_ctx*, const RowMap&, int layer, int M);
 void launch_attention(hawk_ctx*, const RowMap&, int layer, int M);
 // true: launch_attention also rotates q, k and appends k, v for these rows (no launch_rope_append)
 bool attention_does_rope(const hawk_ctx*, const RowMap&);
+// U[:, 0..m) = SiLU(A W1^T) * (A W3^T) in one MFMA kernel (and the bf16 planes of the result for the W2
+// GEMM); false: not applicable, the caller runs the GEMM and launch_swiglu
+bool launch_gemm_swiglu(hawk_ctx*, size_t off_a, int lda, size_t w13_off, int m, int K, size_t off_u, int M);
 void launch_swiglu(hawk_ctx*, int M);
 void launch_draft_input(hawk_ctx*, int i);                     // [g | E[left] | E[up]]
 void launch_keep_hprev_prefill(hawk_ctx*);
