@@ -109,6 +109,30 @@ __device__ __forceinline__ void st_f32x4(float* p, f32x4 v) {
     st_f32x2(p + 2, v[2], v[3]);
 }
 __device__ __forceinline__ void compiler_fence() { __atomic_signal_fence(__ATOMIC_SEQ_CST); }
+
+// Cross-row lane exchanges in the VALU (gfx950 lane swaps; a shuffle would go through the LDS
+// crossbar).  swap16(v, v) returns {rows 0,0,2,2 | rows 1,1,3,3} of v, swap32(v, v) returns
+// {lower half twice | upper half twice}: their sum is v[l] + v[l ^ 16] (resp. v[l ^ 32]) in every
+// lane, and a select by the lane's own row / half gives the partner's value.
+__device__ __forceinline__ float sum_xor16(float v) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float sum_xor32(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float lane_xor16(float v) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float((threadIdx.x & 16u) ? r[0] : r[1]);
+}
+__device__ __forceinline__ float lane_xor32(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float((threadIdx.x & 32u) ? r[0] : r[1]);
+}
+__device__ __forceinline__ float lane_xor8(float v) {   // row_ror:8 - the other half of the 16-lane row
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128, 0xF, 0xF, true));
+}
 __device__ __forceinline__ float* slot(const SP& p, int l) { return p.arena + (u64)l * p.slot_floats; }
 __device__ __forceinline__ uint16_t* plane(const SP& p, int l, u64 off) {
     return reinterpret_cast<uint16_t*>(slot(p, l) + off);
@@ -272,8 +296,8 @@ __device__ __forceinline__ void row_scales_reduce(const float (&v)[NSS], int K, 
     float a = 0.f;
 #pragma unroll
     for (int i = 0; i < NSS; ++i) a += v[i];
-    a += __shfl_xor(a, 16, 64);
-    a += __shfl_xor(a, 32, 64);
+    a = sum_xor16(a);
+    a = sum_xor32(a);
     if (lane < 16) rn[lane] = 1.0f / sqrtf(a / (float)K + eps);
 }
 
@@ -428,8 +452,8 @@ __device__ __forceinline__ void put_stream(const SP& p, uint16_t* hi, uint16_t* 
     const int c = lane & 15, quad = lane >> 4;
     const bool live = c < p.MR;
     float s2 = live ? x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3] : 0.f;
-    s2 += __shfl_xor(s2, 16, 64);
-    s2 += __shfl_xor(s2, 32, 64);
+    s2 = sum_xor16(s2);
+    s2 = sum_xor32(s2);
     if (live) {
         const size_t at = (size_t)c * p.Kpd + strip * 16 + 4 * quad;
         st_split4(hi + at, lo + at, times_gain(x, gain));
@@ -481,7 +505,7 @@ __device__ __forceinline__ void epilogue(const SP& p, const Lds& s, int layer, i
         v *= r;
         f32x4 u3;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) u3[e] = __shfl_xor(v[e], 32, 64);
+        for (int e = 0; e < 4; ++e) u3[e] = lane_xor32(v[e]);
         if (live && quad < 2) {
             f32x4 h;
 #pragma unroll
@@ -991,12 +1015,13 @@ __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& b
         for (int r = 0; r < RPJ; ++r) {
 #pragma unroll
             for (int o = 8; o < 64; o <<= 1) {
-                const float omx = __shfl_xor(A[r].mx, o, 64), oden = __shfl_xor(A[r].den, o, 64);
+                auto other = [&](float x) { return o == 8 ? lane_xor8(x) : (o == 16 ? lane_xor16(x) : lane_xor32(x)); };
+                const float omx = other(A[r].mx), oden = other(A[r].den);
                 const float mn = fmaxf(A[r].mx, omx);
                 const float f0 = __expf(A[r].mx - mn), f1 = __expf(omx - mn);
                 A[r].den = A[r].den * f0 + oden * f1;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) A[r].acc[e] = A[r].acc[e] * f0 + __shfl_xor(A[r].acc[e], o, 64) * f1;
+                for (int e = 0; e < 8; ++e) A[r].acc[e] = A[r].acc[e] * f0 + other(A[r].acc[e]) * f1;
                 A[r].mx = mn;
             }
             if (pg == 0) {
