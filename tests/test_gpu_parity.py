@@ -453,6 +453,15 @@ def test_one_kernel_per_operation_row_counts(H, cfg, k, batch, scale, rows):
     assert_bf16(total, 10, 0.9)
 
 
+def test_one_kernel_per_operation_without_the_tile_major_copy(H):
+    # an MLP width that is no multiple of 32: no tile-major weight copy, so the MFMA GEMV reads the
+    # row-major weights for K = d, and the W2 GEMM (K = m) falls back to the FMA kernel
+    s = synth.CONFIGS[1].replace(n_layers=2, n_cond=24, grid_h=6, grid_w=8, d_mlp=2056, k=3)
+    total = accumulate_lockstep(H, s, s.k, 0, 10, expect_path=0)
+    print("row-major weights", total)
+    assert_bf16(total, 10, 0.9)
+
+
 def test_config3_guidance_batch16_reduced_depth(H):
     # configuration 3 (XL-shaped, guidance 4.0, 16 prompts, k = 5: 32 sequences, 192 rows per
     # target pass) at two layers, a short condition and a small grid, sampled and greedy
