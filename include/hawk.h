@@ -230,13 +230,19 @@ int hawk_phase_trace(hawk_ctx* ctx, int enable, uint64_t* out, size_t n_words);
  * [0, 1), out_index [rows] (0-based index of the accepted candidate, m if none), out_token
  * [rows], out_resid (may be NULL) [rows][m] fp64: the residual mass sum_x max(0, p^(i) - q_i)
  * = 1 - acceptance probability of every evaluated step, -1 for steps after an acceptance.
- * n <= 16384.  The caller owns every buffer; nothing is allocated.  The launch is
- * asynchronous on `stream` (a hipStream_t, NULL: the default stream).
+ * n <= 16384.  workspace (device, may be NULL): with at least
+ * hawk_multi_verify_workspace_bytes(rows, m) bytes the top-k selections of the target row and of
+ * the m proposal rows of every position run in parallel workgroups (two launches) instead of one
+ * after the other; the results are identical.  The caller owns every buffer; nothing is
+ * allocated.  The launches are asynchronous on `stream` (a hipStream_t, NULL: the default
+ * stream).
  * Returns HAWK_OK, HAWK_EINVAL (null pointer, m < 1, n out of range, top_k < 1, negative
- * temperature) or HAWK_EDEVICE (the launch failed). */
+ * temperature) or HAWK_EDEVICE (a launch failed). */
+size_t hawk_multi_verify_workspace_bytes(int rows, int m);
 int hawk_multi_verify(const float* p_logits, const float* q_logits, const int32_t* cand, const float* u_acc,
                       const float* u_final, int rows, int m, int n, float temperature, int top_k,
-                      int32_t* out_index, int32_t* out_token, double* out_resid, void* stream);
+                      int32_t* out_index, int32_t* out_token, double* out_resid, void* workspace,
+                      size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -355,14 +355,20 @@ int hawk_phase_trace(hawk_ctx* c, int enable, uint64_t* out, size_t n_words) {
     return HAWK_OK;
 }
 
+size_t hawk_multi_verify_workspace_bytes(int rows, int m) {
+    return rows > 0 && m > 0 ? hawk::multi_verify_workspace_bytes(rows, m) : 0;
+}
+
 int hawk_multi_verify(const float* p_logits, const float* q_logits, const int32_t* cand, const float* u_acc,
                       const float* u_final, int rows, int m, int n, float temperature, int top_k,
-                      int32_t* out_index, int32_t* out_token, double* out_resid, void* stream) {
+                      int32_t* out_index, int32_t* out_token, double* out_resid, void* workspace,
+                      size_t workspace_bytes, void* stream) {
     if (!p_logits || !q_logits || !cand || !u_acc || !u_final || !out_index || !out_token) return HAWK_EINVAL;
     if (rows < 0 || m < 1 || n < 1 || top_k < 1 || !(temperature >= 0.0f)) return HAWK_EINVAL;
     if (rows == 0) return HAWK_OK;
     return hawk::launch_multi_verify(p_logits, q_logits, cand, u_acc, u_final, rows, m, n, temperature, top_k,
-                                     out_index, out_token, out_resid, static_cast<hipStream_t>(stream));
+                                     out_index, out_token, out_resid, workspace, workspace_bytes,
+                                     static_cast<hipStream_t>(stream));
 }
 
 int hawk_load(hawk_ctx* c, const void* host_blob, size_t nbytes) {

@@ -172,6 +172,8 @@ void launch_force_commit(hawk_ctx*, int cnt);
 // multi-candidate verification of `rows` independent positions (device pointers); HAWK_* code
 int launch_multi_verify(const float* p_logits, const float* q_logits, const int32_t* cand, const float* u_acc,
                         const float* u_final, int rows, int m, int n, float temperature, int top_k,
-                        int32_t* out_index, int32_t* out_token, double* out_resid, hipStream_t stream);
+                        int32_t* out_index, int32_t* out_token, double* out_resid, void* workspace,
+                        size_t workspace_bytes, hipStream_t stream);
+size_t multi_verify_workspace_bytes(int rows, int m);
 
 }  // namespace hawk

@@ -1161,6 +1161,91 @@ __global__ __launch_bounds__(NT) void multi_verify_list_kernel(const float* p_lo
     }
 }
 
+// The same in two launches when the caller lends room for the rows' statistics: the top-k
+// selection of the target row and of every proposal row runs in a workgroup of its own (all of
+// them in parallel), and the walk over the candidates then only gathers.
+template <int E>
+__global__ __launch_bounds__(NT) void multi_row_stats_kernel(const float* p_logits, const float* q_logits, int m, int n,
+                                                             float inv_t, int top_k, WarpStat* stats) {
+    __shared__ FastShared fs;
+    __shared__ CompactList L;
+    const int j = blockIdx.x, row = blockIdx.y;   // j = 0: the target row, j >= 1: proposal j - 1
+    const float* l = j == 0 ? p_logits + (size_t)row * n : q_logits + ((size_t)row * m + (j - 1)) * n;
+    float z[E];
+    load_row<E>(l, nullptr, 0.f, inv_t, nullptr, n, z);
+    const WarpStat st = warp_and_draw<E>(z, n, top_k, 0, fs, L, nullptr, nullptr);
+    if (threadIdx.x == 0) stats[(size_t)row * (m + 1) + j] = st;
+}
+
+template <int E>
+__global__ __launch_bounds__(NT) void multi_verify_walk_kernel(const float* p_logits, const float* q_logits,
+                                                               const int32_t* cand, const float* u_acc,
+                                                               const float* u_final, int m, int n, float inv_t,
+                                                               const WarpStat* stats, int32_t* out_index,
+                                                               int32_t* out_token, double* out_resid) {
+    __shared__ Shared sh;
+    __shared__ CompactList L;       // entries of p with mass: index, scaled logit, current p^(i)
+    __shared__ double pick;
+    const int row = blockIdx.x, i0 = threadIdx.x * 2;
+    const WarpStat ps = stats[(size_t)row * (m + 1)];
+    float z[E];
+    load_row<E>(p_logits + (size_t)row * n, nullptr, 0.f, inv_t, nullptr, n, z);
+    const int Kp = compact_row<E>(kept_mask<E>(ps, z, n), z, L, sh);
+    const double Zp = list_weights(L, Kp, ps.zmax, sh);
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+        if (i0 + e < Kp) L.w[i0 + e] /= Zp;   // the thread's own entries
+    int acc = m, tok = -1;
+    for (int i = 0; i < m; ++i) {
+        const float* qrow = q_logits + ((size_t)row * m + i) * n;
+        const WarpStat qs = stats[(size_t)row * (m + 1) + 1 + i];
+        const int s = cand[(size_t)row * m + i];
+        if (threadIdx.x == 0) pick = 0.0;   // p^(i)(s) if s has no mass left
+        __syncthreads();
+        double res[2], rs = 0.0;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            res[e] = 0.0;
+            if (i0 + e < Kp) {
+                const int j = L.idx[i0 + e];
+                const double pv = L.w[i0 + e];
+                if (j == s) pick = pv;
+                const double r = pv - weight_of(qs, qrow, inv_t, j) / qs.total;
+                res[e] = r > 0.0 ? r : 0.0;
+                rs += res[e];
+            }
+        }
+        const double R = block_sum_d(rs, sh);   // its barriers also publish pick
+        const double pd = pick, qd = weight_of(qs, qrow, inv_t, s) / qs.total;
+        __syncthreads();   // pick is rewritten at the top of the next round
+        if (out_resid && threadIdx.x == 0) out_resid[(size_t)row * m + i] = R;
+        if ((double)u_acc[(size_t)row * m + i] * qd < pd) {
+            acc = i;
+            tok = s;
+            break;
+        }
+        if (R > 0.0) {
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+                if (i0 + e < Kp) L.w[i0 + e] = res[e] / R;
+        }
+    }
+    if (acc == m) {
+        double sp = 0.0;
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+            if (i0 + e < Kp) sp += L.w[i0 + e];
+        const double total = block_sum_d(sp, sh);
+        tok = list_inv_cdf(L.w, L.idx, Kp, total, u_final[row], sh);
+    }
+    if (threadIdx.x == 0) {
+        out_index[row] = acc;
+        out_token[row] = tok;
+        if (out_resid)
+            for (int i = acc + 1; i < m; ++i) out_resid[(size_t)row * m + i] = -1.0;
+    }
+}
+
 template <int E>
 __global__ __launch_bounds__(NT) void multi_verify_kernel(const float* p_logits, const float* q_logits,
                                                           const int32_t* cand, const float* u_acc,
@@ -1324,15 +1409,25 @@ void launch_force_commit(hawk_ctx* c, int cnt) {
                                                      c->N, cnt, c->S);
 }
 
+size_t multi_verify_workspace_bytes(int rows, int m) { return (size_t)rows * (m + 1) * sizeof(WarpStat); }
+
 int launch_multi_verify(const float* p_logits, const float* q_logits, const int32_t* cand, const float* u_acc,
                         const float* u_final, int rows, int m, int n, float temperature, int top_k,
-                        int32_t* out_index, int32_t* out_token, double* out_resid, hipStream_t stream) {
+                        int32_t* out_index, int32_t* out_token, double* out_resid, void* workspace,
+                        size_t workspace_bytes, hipStream_t stream) {
     const int E = n <= 4 * NT ? 4 : (n <= 16 * NT ? 16 : 0);
     if (!E) return HAWK_EINVAL;
     const int greedy = (temperature == 0.0f || top_k == 1) ? 1 : 0;
     const float inv_t = greedy ? 1.0f : 1.0f / temperature;
     const int tk = top_k < n ? top_k : n;
-    if (use_list(tk, n, greedy)) {
+    if (use_list(tk, n, greedy) && workspace && workspace_bytes >= multi_verify_workspace_bytes(rows, m)) {
+        WarpStat* stats = static_cast<WarpStat*>(workspace);
+        auto k1 = E == 4 ? multi_row_stats_kernel<4> : multi_row_stats_kernel<16>;
+        auto k2 = E == 4 ? multi_verify_walk_kernel<4> : multi_verify_walk_kernel<16>;
+        k1<<<dim3(m + 1, rows), NT, 0, stream>>>(p_logits, q_logits, m, n, inv_t, tk, stats);
+        k2<<<rows, NT, 0, stream>>>(p_logits, q_logits, cand, u_acc, u_final, m, n, inv_t, stats, out_index, out_token,
+                                    out_resid);
+    } else if (use_list(tk, n, greedy)) {
         auto kern = E == 4 ? multi_verify_list_kernel<4> : multi_verify_list_kernel<16>;
         kern<<<rows, NT, 0, stream>>>(p_logits, q_logits, cand, u_acc, u_final, m, n, inv_t, tk, out_index, out_token,
                                       out_resid);

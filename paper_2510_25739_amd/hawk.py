@@ -71,8 +71,10 @@ EXPORTS = {
     "hawk_set_path": (C.c_int, [C.c_void_p, C.c_int]),
     "hawk_last_path": (C.c_int, [C.c_void_p]),
     "hawk_phase_trace": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t]),
+    "hawk_multi_verify_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int]),
     "hawk_multi_verify": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
-                                    C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+                                    C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.c_size_t, C.c_void_p]),
 }
 
 
@@ -120,9 +122,15 @@ def _p(a):
     return None if a is None else a.ctypes.data_as(C.c_void_p)
 
 
-def multi_verify(p_logits, q_logits, cand, u_acc, u_final, temperature: float, top_k: int, want_resid: bool = False):
+def multi_verify_workspace_bytes(rows: int, m: int) -> int:
+    return int(load_library().hawk_multi_verify_workspace_bytes(rows, m))
+
+
+def multi_verify(p_logits, q_logits, cand, u_acc, u_final, temperature: float, top_k: int, want_resid: bool = False,
+                 workspace=None):
     """hawk_multi_verify on device tensors (torch, on the GPU): p_logits [rows, n] fp32, q_logits
     [rows, m, n] fp32, cand [rows, m] int32, u_acc [rows, m] fp32, u_final [rows] fp32.
+    workspace: None, or a device uint8 tensor of at least multi_verify_workspace_bytes(rows, m) bytes.
     Returns device tensors (index [rows] int32, token [rows] int32[, residual masses [rows, m] fp64]);
     the launch is asynchronous on torch's current stream."""
     import torch  # device memory and stream only
@@ -138,6 +146,8 @@ def multi_verify(p_logits, q_logits, cand, u_acc, u_final, temperature: float, t
     rc = load_library().hawk_multi_verify(p_logits.data_ptr(), q_logits.data_ptr(), cand.data_ptr(), u_acc.data_ptr(),
                                           u_final.data_ptr(), rows, m, n, float(temperature), int(top_k),
                                           idx.data_ptr(), tok.data_ptr(), resid.data_ptr() if want_resid else None,
+                                          workspace.data_ptr() if workspace is not None else None,
+                                          workspace.numel() * workspace.element_size() if workspace is not None else 0,
                                           torch.cuda.current_stream(p_logits.device).cuda_stream)
     if rc != 0:
         raise HawkError(rc, "hawk_multi_verify")

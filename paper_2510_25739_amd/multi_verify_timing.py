@@ -19,16 +19,20 @@ def bench_multi_verify(H, s, rows_list=(6, 192), m=2, reps=50):
         cand = q.argmax(2).to(torch.int32).contiguous()
         u_acc = torch.rand(rows, m, device="cuda:0", generator=g)
         u_fin = torch.rand(rows, device="cuda:0", generator=g)
-        for _ in range(5):
-            H.multi_verify(p, q, cand, u_acc, u_fin, s.temperature, s.top_k)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            idx, tok = H.multi_verify(p, q, cand, u_acc, u_fin, s.temperature, s.top_k)
-        e1.record()
-        torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / reps
-        out[f"rows_{rows}"] = {"us_per_launch": us, "logit_bytes": rows * (m + 1) * n * 4,
+        ws = torch.empty(H.multi_verify_workspace_bytes(rows, m), dtype=torch.uint8, device="cuda:0")
+        timed = {}
+        for name, w in (("one_launch", None), ("two_launches", ws)):
+            for _ in range(5):
+                H.multi_verify(p, q, cand, u_acc, u_fin, s.temperature, s.top_k, workspace=w)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                idx, tok = H.multi_verify(p, q, cand, u_acc, u_fin, s.temperature, s.top_k, workspace=w)
+            e1.record()
+            torch.cuda.synchronize()
+            timed[name] = e0.elapsed_time(e1) * 1e3 / reps
+        us = timed["two_launches"]
+        out[f"rows_{rows}"] = {"us_per_launch": us, "us_one_launch": timed["one_launch"], "logit_bytes": rows * (m + 1) * n * 4,
                                "GB/s": rows * (m + 1) * n * 4 / (us * 1e-6) / 1e9,
                                "rejected_all_frac": float((idx == m).float().mean())}
     out["config"] = f"m={m} candidates per position, slice {n}, top-k {s.top_k}, T={s.temperature}"

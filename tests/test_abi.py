@@ -65,15 +65,18 @@ def test_multi_verify_rejects_bad_arguments_before_any_launch(H):
     lib = C.CDLL(H.lib_path())
     fn = lib.hawk_multi_verify
     fn.restype = C.c_int
-    fn.argtypes = [C.c_void_p] * 5 + [C.c_int] * 3 + [C.c_float, C.c_int] + [C.c_void_p] * 4
+    fn.argtypes = [C.c_void_p] * 5 + [C.c_int] * 3 + [C.c_float, C.c_int] + [C.c_void_p] * 4 + [C.c_size_t, C.c_void_p]
     one = C.c_void_p(16)   # never dereferenced: every call below fails validation first
-    assert fn(None, one, one, one, one, 1, 1, 8, 1.0, 8, one, one, None, None) == -1
-    assert fn(one, one, one, one, one, 1, 0, 8, 1.0, 8, one, one, None, None) == -1      # no candidates
-    assert fn(one, one, one, one, one, 1, 1, 0, 1.0, 8, one, one, None, None) == -1      # empty vocabulary
-    assert fn(one, one, one, one, one, 1, 1, 8, -1.0, 8, one, one, None, None) == -1     # negative temperature
-    assert fn(one, one, one, one, one, 1, 1, 8, 1.0, 0, one, one, None, None) == -1      # top_k < 1
-    assert fn(one, one, one, one, one, -1, 1, 8, 1.0, 8, one, one, None, None) == -1
-    assert fn(one, one, one, one, one, 0, 1, 8, 1.0, 8, one, one, None, None) == 0       # no rows: nothing to do
+    assert fn(None, one, one, one, one, 1, 1, 8, 1.0, 8, one, one, None, None, 0, None) == -1
+    assert fn(one, one, one, one, one, 1, 0, 8, 1.0, 8, one, one, None, None, 0, None) == -1      # no candidates
+    assert fn(one, one, one, one, one, 1, 1, 0, 1.0, 8, one, one, None, None, 0, None) == -1      # empty vocabulary
+    assert fn(one, one, one, one, one, 1, 1, 8, -1.0, 8, one, one, None, None, 0, None) == -1     # negative temperature
+    assert fn(one, one, one, one, one, 1, 1, 8, 1.0, 0, one, one, None, None, 0, None) == -1      # top_k < 1
+    assert fn(one, one, one, one, one, -1, 1, 8, 1.0, 8, one, one, None, None, 0, None) == -1
+    assert fn(one, one, one, one, one, 0, 1, 8, 1.0, 8, one, one, None, None, 0, None) == 0       # no rows: nothing to do
+    ws = lib.hawk_multi_verify_workspace_bytes
+    ws.restype, ws.argtypes = C.c_size_t, [C.c_int, C.c_int]
+    assert ws(6, 2) == 6 * 3 * 24 and ws(12, 2) == 2 * ws(6, 2) and ws(0, 2) == 0   # one 24-byte record per logit row
 
 
 def test_product_never_imports_the_oracle():

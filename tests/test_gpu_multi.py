@@ -40,10 +40,16 @@ def run_both(H, p, q, cand, u_acc, u_fin, temperature, top_k):
     import torch
     dev = "cuda:0"
     t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
-    idx, tok, resid = H.multi_verify(t(p), t(q), t(cand), t(u_acc), t(u_fin), temperature, top_k, want_resid=True)
-    torch.cuda.synchronize()
-    idx, tok, resid = idx.cpu().numpy(), tok.cpu().numpy(), resid.cpu().numpy()
+    args = (t(p), t(q), t(cand), t(u_acc), t(u_fin), temperature, top_k)
+    idx, tok, resid = H.multi_verify(*args, want_resid=True)
+    # the two-launch form (rows' selections in parallel, statistics in a caller-provided workspace)
+    # must give the same result, to the bit
     rows, m = cand.shape
+    ws = torch.empty(H.multi_verify_workspace_bytes(rows, m), dtype=torch.uint8, device=dev)
+    idx2, tok2, resid2 = H.multi_verify(*args, want_resid=True, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2) and torch.equal(tok, tok2) and torch.equal(resid, resid2)
+    idx, tok, resid = idx.cpu().numpy(), tok.cpu().numpy(), resid.cpu().numpy()
     o_idx, o_tok, o_res = np.zeros(rows, np.int32), np.zeros(rows, np.int32), np.zeros((rows, m))
     for r in range(rows):
         o_idx[r], o_tok[r], o_res[r] = oracle.multi_verify(p[r], q[r], cand[r], u_acc[r], float(u_fin[r]), temperature,
@@ -104,10 +110,10 @@ def test_multi_verify_rejects_bad_arguments(H):
     L = H.load_library()
     z = torch.zeros(8, device="cuda:0")
     ptr = z.data_ptr()
-    assert L.hawk_multi_verify(None, ptr, ptr, ptr, ptr, 1, 1, 8, 1.0, 8, ptr, ptr, None, None) == -1
-    assert L.hawk_multi_verify(ptr, ptr, ptr, ptr, ptr, 1, 0, 8, 1.0, 8, ptr, ptr, None, None) == -1
-    assert L.hawk_multi_verify(ptr, ptr, ptr, ptr, ptr, 1, 1, 16385, 1.0, 8, ptr, ptr, None, None) == -1
-    assert L.hawk_multi_verify(ptr, ptr, ptr, ptr, ptr, 0, 1, 8, 1.0, 8, ptr, ptr, None, None) == 0
+    assert L.hawk_multi_verify(None, ptr, ptr, ptr, ptr, 1, 1, 8, 1.0, 8, ptr, ptr, None, None, 0, None) == -1
+    assert L.hawk_multi_verify(ptr, ptr, ptr, ptr, ptr, 1, 0, 8, 1.0, 8, ptr, ptr, None, None, 0, None) == -1
+    assert L.hawk_multi_verify(ptr, ptr, ptr, ptr, ptr, 1, 1, 16385, 1.0, 8, ptr, ptr, None, None, 0, None) == -1
+    assert L.hawk_multi_verify(ptr, ptr, ptr, ptr, ptr, 0, 1, 8, 1.0, 8, ptr, ptr, None, None, 0, None) == 0
 
 
 def test_rejection_probability_curve_matches_oracle(H):
