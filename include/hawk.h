@@ -230,6 +230,10 @@ int hawk_phase_trace(hawk_ctx* ctx, int enable, uint64_t* out, size_t n_words);
  * [0, 1), out_index [rows] (0-based index of the accepted candidate, m if none), out_token
  * [rows], out_resid (may be NULL) [rows][m] fp64: the residual mass sum_x max(0, p^(i) - q_i)
  * = 1 - acceptance probability of every evaluated step, -1 for steps after an acceptance.
+ * m_rows (device, may be NULL) [rows]: the number of candidates position r really has, clamped to
+ * 0..m (a sampling pool near the top of the image has fewer members); candidates, proposals and
+ * uniforms beyond it are not read, out_index[r] is then that count if none was accepted, and with
+ * no candidate at all the token is drawn from the warped target itself.
  * n <= 16384.  workspace (device, may be NULL): with at least
  * hawk_multi_verify_workspace_bytes(rows, m) bytes the top-k selections of the target row and of
  * the m proposal rows of every position run in parallel workgroups (two launches) instead of one
@@ -240,9 +244,68 @@ int hawk_phase_trace(hawk_ctx* ctx, int enable, uint64_t* out, size_t n_words);
  * temperature) or HAWK_EDEVICE (a launch failed). */
 size_t hawk_multi_verify_workspace_bytes(int rows, int m);
 int hawk_multi_verify(const float* p_logits, const float* q_logits, const int32_t* cand, const float* u_acc,
-                      const float* u_final, int rows, int m, int n, float temperature, int top_k,
+                      const float* u_final, const int32_t* m_rows, int rows, int m, int n, float temperature, int top_k,
                       int32_t* out_index, int32_t* out_token, double* out_resid, void* workspace,
                       size_t workspace_bytes, void* stream);
+
+/* ---- Spatial drafting structures ------------------------------------------------------------
+ * Method, "Dual Direction Drafting Heads" and "Spatial Sampling Pool"; appendix "Draft Heads
+ * Structure and Memory Overhead".  Positions count in raster order (position = row * IW +
+ * column); T below is the position a hidden state predicts through the model's own output layer.
+ * These entry points need no context: all pointers are DEVICE pointers unless stated, the caller
+ * owns every buffer, nothing is allocated, launches are asynchronous on `stream` (a hipStream_t,
+ * NULL: the default stream). */
+
+/* Dual-direction draft heads.  Head j is a linear layer of the hidden size with SiLU, added back
+ * to its input (the Medusa block the appendix names), and all heads share the model's output
+ * layer:  g[r][j] = h[r] + silu(W_heads[j] h[r]),  q_logits[r][j] = W_out g[r][j].
+ * The caller decides which heads are horizontal (head for T + j) and which vertical (T + d * IW).
+ * h [rows][d] fp32; W_heads [n_heads][d][d] bf16, [out][in]; W_out [V_s][d] bf16 (the rows of the
+ * output layer that are sampled from); q_logits [rows][n_heads][V_s] fp32; g_out (may be NULL)
+ * [rows][n_heads][d] fp32.  Products on the matrix units: activations as two bf16 planes (about 16
+ * bits), fp32 accumulation.  d % 64 == 0, V_s % 16 == 0, pointers 16-byte aligned; workspace of at
+ * least hawk_spatial_heads_workspace_bytes(rows, n_heads, d) bytes.
+ * Returns HAWK_OK, HAWK_EINVAL (null pointer, shape not supported, workspace too small or
+ * misaligned) or HAWK_EDEVICE. */
+size_t hawk_spatial_heads_workspace_bytes(int rows, int n_heads, int d);
+int hawk_spatial_heads(const float* h, const void* W_heads, const void* W_out, int rows, int n_heads, int d, int V_s,
+                       float* q_logits, float* g_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Speculation cache: vertical predictions (rows of V_s logits) kept from the moment the position
+ * they were made from is committed until raster order reaches the position they point to.  It
+ * holds IW * VSD * (VSD + 1) / 2 entries, the size the method states: hawk_spec_cache_bytes is
+ * that many rows of V_s floats plus one int32 tag per entry (rounded up to 256 bytes).
+ * hawk_spec_cache_slot (host arithmetic only) is the entry a prediction of `depth` for position
+ * `pos` waits in, -1 for bad arguments; entries that are outstanding at the same time never share
+ * a slot.  hawk_spec_cache_reset marks every entry empty (once per image).
+ * hawk_spec_cache_push: for r < rows with 0 <= pos[r] < IW * IH, the hidden state that predicted
+ * position pos[r] gave q_vert[r * row_stride + (dep - 1) * V_s ...] as the logits for position
+ * pos[r] + dep * IW, dep = 1..VSD; predictions for positions below the image are dropped, rows with
+ * pos[r] out of range skipped (the rows of a verify pass that were not committed).  The positions
+ * of one call are distinct, rows <= IW; row_stride (in floats) >= VSD * V_s. */
+size_t hawk_spec_cache_bytes(int IW, int VSD, int V_s);
+int hawk_spec_cache_slot(int IW, int VSD, int pos, int depth);
+int hawk_spec_cache_reset(void* cache, int IW, int VSD, int V_s, void* stream);
+int hawk_spec_cache_push(void* cache, int IW, int IH, int VSD, int V_s, const int32_t* pos, const float* q_vert,
+                         size_t row_stride, int rows, void* stream);
+
+/* Spatial sampling pool at the positions target[i], i < n: VertSpec(t) - the cached predictions
+ * made from t - delta * IW with depth delta, delta = 1..VSD, those that exist, in ascending delta
+ * - followed by the horizontal proposal q_horiz[i * horiz_stride ...] (the vertical candidate is
+ * verified first, as in the appendix).  pool_logits [n][VSD + 1][V_s] receives the members'
+ * logits packed to the front (rows beyond the count are left as they were), pool_m [n] the count,
+ * pool_delta [n][VSD + 1] each member's delta (0 = horizontal, -1 = no member).  target[i] outside
+ * 0 .. IW * IH - 1: count 0.  pool_logits, pool_m and pool_delta feed hawk_sample_rows (one
+ * candidate per member) and hawk_multi_verify (q_logits, m_rows). */
+int hawk_spec_pool(const void* cache, int IW, int IH, int VSD, int V_s, const int32_t* target, const float* q_horiz,
+                   size_t horiz_stride, int n, float* pool_logits, int32_t* pool_m, int32_t* pool_delta, void* stream);
+
+/* One draw per row from warp(logits[r]) by inverse CDF over ascending token index with u[r]
+ * (warp as in hawk_multi_verify): the candidates of a pool.  logits [rows][n] fp32, n <= 16384;
+ * skip (may be NULL) [rows]: rows with a negative entry are not read and give -1 (pass
+ * pool_delta). */
+int hawk_sample_rows(const float* logits, const int32_t* skip, const float* u, int rows, int n, float temperature,
+                     int top_k, int32_t* out_token, void* stream);
 
 #ifdef __cplusplus
 }

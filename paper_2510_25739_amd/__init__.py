@@ -13,5 +13,10 @@ from .hawk import (  # noqa: F401
     multi_verify,
     multi_verify_workspace_bytes,
     plan_info,
+    sample_rows,
+    spatial_heads,
+    spec_cache_bytes,
+    spec_cache_slot,
+    SpecCache,
     workspace_bytes,
 )

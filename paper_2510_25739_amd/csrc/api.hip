@@ -360,15 +360,60 @@ size_t hawk_multi_verify_workspace_bytes(int rows, int m) {
 }
 
 int hawk_multi_verify(const float* p_logits, const float* q_logits, const int32_t* cand, const float* u_acc,
-                      const float* u_final, int rows, int m, int n, float temperature, int top_k,
+                      const float* u_final, const int32_t* m_rows, int rows, int m, int n, float temperature, int top_k,
                       int32_t* out_index, int32_t* out_token, double* out_resid, void* workspace,
                       size_t workspace_bytes, void* stream) {
     if (!p_logits || !q_logits || !cand || !u_acc || !u_final || !out_index || !out_token) return HAWK_EINVAL;
     if (rows < 0 || m < 1 || n < 1 || top_k < 1 || !(temperature >= 0.0f)) return HAWK_EINVAL;
     if (rows == 0) return HAWK_OK;
-    return hawk::launch_multi_verify(p_logits, q_logits, cand, u_acc, u_final, rows, m, n, temperature, top_k,
+    return hawk::launch_multi_verify(p_logits, q_logits, cand, u_acc, u_final, m_rows, rows, m, n, temperature, top_k,
                                      out_index, out_token, out_resid, workspace, workspace_bytes,
                                      static_cast<hipStream_t>(stream));
+}
+
+size_t hawk_spatial_heads_workspace_bytes(int rows, int n_heads, int d) {
+    return rows > 0 && n_heads > 0 && d > 0 ? hawk::spatial_heads_workspace_bytes(rows, n_heads, d) : 0;
+}
+
+int hawk_spatial_heads(const float* h, const void* W_heads, const void* W_out, int rows, int n_heads, int d, int V_s,
+                       float* q_logits, float* g_out, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!h || !W_heads || !W_out || !q_logits) return HAWK_EINVAL;
+    if (rows < 0 || n_heads < 1 || d < 1 || V_s < 1 || (long)rows * n_heads > 65535) return HAWK_EINVAL;
+    if (rows == 0) return HAWK_OK;
+    return hawk::launch_spatial_heads(h, static_cast<const uint16_t*>(W_heads), static_cast<const uint16_t*>(W_out), rows,
+                                      n_heads, d, V_s, q_logits, g_out, workspace, workspace_bytes,
+                                      static_cast<hipStream_t>(stream));
+}
+
+size_t hawk_spec_cache_bytes(int IW, int VSD, int V_s) {
+    return IW > 0 && VSD > 0 && VSD <= 16 && V_s > 0 ? hawk::spec_cache_bytes(IW, VSD, V_s) : 0;
+}
+
+int hawk_spec_cache_slot(int IW, int VSD, int pos, int depth) { return hawk::spec_cache_slot(IW, VSD, pos, depth); }
+
+int hawk_spec_cache_reset(void* cache, int IW, int VSD, int V_s, void* stream) {
+    return hawk::launch_spec_cache_reset(cache, IW, VSD, V_s, static_cast<hipStream_t>(stream));
+}
+
+int hawk_spec_cache_push(void* cache, int IW, int IH, int VSD, int V_s, const int32_t* pos, const float* q_vert,
+                         size_t row_stride, int rows, void* stream) {
+    return hawk::launch_spec_cache_push(cache, IW, IH, VSD, V_s, pos, q_vert, row_stride, rows,
+                                        static_cast<hipStream_t>(stream));
+}
+
+int hawk_spec_pool(const void* cache, int IW, int IH, int VSD, int V_s, const int32_t* target, const float* q_horiz,
+                   size_t horiz_stride, int n, float* pool_logits, int32_t* pool_m, int32_t* pool_delta, void* stream) {
+    return hawk::launch_spec_pool(cache, IW, IH, VSD, V_s, target, q_horiz, horiz_stride, n, pool_logits, pool_m,
+                                  pool_delta, static_cast<hipStream_t>(stream));
+}
+
+int hawk_sample_rows(const float* logits, const int32_t* skip, const float* u, int rows, int n, float temperature,
+                     int top_k, int32_t* out_token, void* stream) {
+    if (!logits || !u || !out_token) return HAWK_EINVAL;
+    if (rows < 0 || n < 1 || top_k < 1 || !(temperature >= 0.0f)) return HAWK_EINVAL;
+    if (rows == 0) return HAWK_OK;
+    return hawk::launch_sample_rows(logits, skip, u, rows, n, temperature, top_k, out_token,
+                                    static_cast<hipStream_t>(stream));
 }
 
 int hawk_load(hawk_ctx* c, const void* host_blob, size_t nbytes) {

@@ -348,6 +348,42 @@ bool presplit_planes(hawk_ctx* c, size_t off_a, int M, int K, uint16_t** hi, uin
     return true;
 }
 
+// Tile choice and launch for Y (+)= A W^T with A given as its two bf16 planes.
+static void launch_tiles(hipStream_t stream, const uint16_t* hi, const uint16_t* lo, const uint16_t* W, int packed, int N,
+                         int K, float* Y, int ldy, int M, int acc, uint16_t* ohi, uint16_t* olo, int swiglu_m) {
+    // The smallest tile that still gives every compute unit at most one workgroup: with so few
+    // rows the kernel is bound by what one compute unit can stage and feed per k-stage, so the
+    // work is spread as widely as one round of workgroups allows; larger grids than that only
+    // re-read the activations more often.
+    static const int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        return n;
+    }();
+    auto tiles = [&](int bn, int bm) { return (long)((N + bn - 1) / bn) * ((M + bm - 1) / bm); };
+#define HAWK_GEMM_TILE(SR, CT, D)                                                                      \
+    do {                                                                                               \
+        dim3 grid((N + 32 * SR - 1) / (32 * SR), (M + 32 * CT - 1) / (32 * CT), 1);                    \
+        gemm_mfma_kernel<SR, CT, D><<<grid, 256, 0, stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc, ohi, olo,    \
+                                                                  swiglu_m);                            \
+    } while (0)
+    if (M <= 16 && K % 128 == 0) {   // a sliver of rows: barrier-free weight streaming, one wave per K quarter
+        if ((long)(N / 32) >= (long)cus) {
+            gemv_mfma_kernel<2, 8><<<(N + 31) / 32, 256, 0, stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc, ohi, olo, swiglu_m);
+        } else {
+            gemv_mfma_kernel<1, 8><<<(N + 15) / 16, 256, 0, stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc, ohi, olo, swiglu_m);
+        }
+        return;
+    }
+    if (tiles(32, 32) <= cus) HAWK_GEMM_TILE(1, 1, 4);
+    else if (tiles(32, 64) <= cus) HAWK_GEMM_TILE(1, 2, 4);
+    else if (tiles(64, 64) <= cus) HAWK_GEMM_TILE(2, 2, 3);   // at equal area more features per tile: fewer LDS reads per MFMA
+    else if (tiles(96, 64) <= cus) HAWK_GEMM_TILE(3, 2, 3);
+    else HAWK_GEMM_TILE(4, 3, 2);
+#undef HAWK_GEMM_TILE
+}
+
+
 // Common body: Y (+)= A W^T, or with swiglu_m > 0 the fused W1|W3 form (N = 2 swiglu_m).
 static bool run_mfma(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, int K, size_t off_y, int ldy, int M,
                      bool accumulate, int swiglu_m) {
@@ -383,37 +419,19 @@ static bool run_mfma(hawk_ctx* c, size_t off_a, int lda, size_t w_off, int N, in
         c->presplit_K = swiglu_m;
         c->presplit_buf = 1;
     }
-    // The smallest tile that still gives every compute unit at most one workgroup: with so few
-    // rows the kernel is bound by what one compute unit can stage and feed per k-stage, so the
-    // work is spread as widely as one round of workgroups allows; larger grids than that only
-    // re-read the activations more often.
-    static const int cus = [] {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        return n;
-    }();
-    auto tiles = [&](int bn, int bm) { return (long)((N + bn - 1) / bn) * ((M + bm - 1) / bm); };
-    const int acc = accumulate ? 1 : 0;
-#define HAWK_GEMM_TILE(SR, CT, D)                                                                      \
-    do {                                                                                               \
-        dim3 grid((N + 32 * SR - 1) / (32 * SR), (M + 32 * CT - 1) / (32 * CT), 1);                    \
-        gemm_mfma_kernel<SR, CT, D><<<grid, 256, 0, c->stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc, ohi, olo,    \
-                                                                  swiglu_m);                            \
-    } while (0)
-    if (M <= 16 && K % 128 == 0) {   // a sliver of rows: barrier-free weight streaming, one wave per K quarter
-        if ((long)(N / 32) >= (long)cus) {
-            gemv_mfma_kernel<2, 8><<<(N + 31) / 32, 256, 0, c->stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc, ohi, olo, swiglu_m);
-        } else {
-            gemv_mfma_kernel<1, 8><<<(N + 15) / 16, 256, 0, c->stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc, ohi, olo, swiglu_m);
-        }
-        return true;
+    launch_tiles(c->stream, hi, lo, W, packed, N, K, Y, ldy, M, accumulate ? 1 : 0, ohi, olo, swiglu_m);
+    return true;
+}
+
+bool gemm_rows_bf16(hipStream_t stream, const float* A, int lda, int M, int K, const uint16_t* W, int N, float* Y,
+                    int ldy, uint16_t* planes) {
+    if (M < 1 || K % kKC || N % 16 || ldy % 4 || lda % 4) return false;
+    uint16_t *hi = planes, *lo = planes + (size_t)M * K;
+    if (A) {
+        const size_t total4 = (size_t)M * (K / 4);
+        split_rows_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, stream>>>(A, lda, K, hi, lo, total4);
     }
-    if (tiles(32, 32) <= cus) HAWK_GEMM_TILE(1, 1, 4);
-    else if (tiles(32, 64) <= cus) HAWK_GEMM_TILE(1, 2, 4);
-    else if (tiles(64, 64) <= cus) HAWK_GEMM_TILE(2, 2, 3);   // at equal area more features per tile: fewer LDS reads per MFMA
-    else if (tiles(96, 64) <= cus) HAWK_GEMM_TILE(3, 2, 3);
-    else HAWK_GEMM_TILE(4, 3, 2);
-#undef HAWK_GEMM_TILE
+    launch_tiles(stream, hi, lo, W, 0, N, K, Y, ldy, M, 0, nullptr, nullptr, 0);
     return true;
 }
 

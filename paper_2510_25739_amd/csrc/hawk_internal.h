@@ -145,6 +145,12 @@ bool attention_does_rope(const hawk_ctx*, const RowMap&);
 // U[:, 0..m) = SiLU(A W1^T) * (A W3^T) in one MFMA kernel (and the bf16 planes of the result for the W2
 // GEMM); false: not applicable, the caller runs the GEMM and launch_swiglu
 bool launch_gemm_swiglu(hawk_ctx*, size_t off_a, int lda, size_t w13_off, int m, int K, size_t off_u, int M);
+// Without a context: Y[M][N] = A W^T, A fp32 [M][K] (row stride lda), W bf16 row-major [N][K], on
+// the MFMA kernels.  planes: room for 2 M K bf16 values (the two bf16 planes of A); A == nullptr:
+// the planes are filled already (hi first, then lo).  false: the shape is not supported
+// (K % 64, N % 16, lda % 4, ldy % 4).
+bool gemm_rows_bf16(hipStream_t stream, const float* A, int lda, int M, int K, const uint16_t* W, int N, float* Y,
+                    int ldy, uint16_t* planes);
 void launch_swiglu(hawk_ctx*, int M);
 void launch_draft_input(hawk_ctx*, int i);                     // [g | E[left] | E[up]]
 void launch_keep_hprev_prefill(hawk_ctx*);
@@ -171,9 +177,25 @@ void launch_force_setup(hawk_ctx*, int cnt);
 void launch_force_commit(hawk_ctx*, int cnt);
 // multi-candidate verification of `rows` independent positions (device pointers); HAWK_* code
 int launch_multi_verify(const float* p_logits, const float* q_logits, const int32_t* cand, const float* u_acc,
-                        const float* u_final, int rows, int m, int n, float temperature, int top_k,
+                        const float* u_final, const int32_t* m_rows, int rows, int m, int n, float temperature, int top_k,
                         int32_t* out_index, int32_t* out_token, double* out_resid, void* workspace,
                         size_t workspace_bytes, hipStream_t stream);
 size_t multi_verify_workspace_bytes(int rows, int m);
+int launch_sample_rows(const float* logits, const int32_t* skip, const float* u, int rows, int n, float temperature,
+                       int top_k, int32_t* out_token, hipStream_t stream);
+
+// ---- spatial drafting structures, implemented in spatial.hip (no context; HAWK_* codes) ----
+size_t spatial_heads_workspace_bytes(int rows, int n_heads, int d);
+int launch_spatial_heads(const float* h, const uint16_t* W_heads, const uint16_t* W_out, int rows, int n_heads, int d,
+                         int Vs, float* q_logits, float* g_out, void* workspace, size_t workspace_bytes,
+                         hipStream_t stream);
+size_t spec_cache_bytes(int IW, int VSD, int Vs);
+int spec_cache_slot(int IW, int VSD, int pos, int depth);
+int launch_spec_cache_reset(void* cache, int IW, int VSD, int Vs, hipStream_t stream);
+int launch_spec_cache_push(void* cache, int IW, int IH, int VSD, int Vs, const int32_t* pos, const float* q_vert,
+                           size_t row_stride, int rows, hipStream_t stream);
+int launch_spec_pool(const void* cache, int IW, int IH, int VSD, int Vs, const int32_t* target, const float* q_horiz,
+                     size_t horiz_stride, int n, float* pool_logits, int32_t* pool_m, int32_t* pool_delta,
+                     hipStream_t stream);
 
 }  // namespace hawk

@@ -1062,6 +1062,11 @@ __global__ __launch_bounds__(NT) void accept_commit_fast(
 // otherwise p^(i+1) = norm(max(0, p^(i) - q_i)) (unchanged if that residual has no mass); after m
 // rejections the token comes from p^(m+1) by inverse CDF.  One workgroup per position, the
 // running target in registers (E fp64 values per thread), every proposal row read once.
+// Candidates of a row: m, or the row's own count (clamped to 0 .. m) if the caller gives one.
+__device__ __forceinline__ int row_candidates(const int32_t* m_rows, int row, int m) {
+    return m_rows ? max(0, min(m, m_rows[row])) : m;
+}
+
 // Kept entries of a row gathered as scaled logits only (no indices): for the sum of their weights.
 template <int E>
 __device__ int compact_z(unsigned kmask, const float (&z)[E], float (&qz)[kCap], Shared& sh) {
@@ -1084,19 +1089,20 @@ __device__ int compact_z(unsigned kmask, const float (&z)[E], float (&qz)[kCap],
 template <int E>
 __global__ __launch_bounds__(NT) void multi_verify_list_kernel(const float* p_logits, const float* q_logits,
                                                                const int32_t* cand, const float* u_acc,
-                                                               const float* u_final, int m, int n, float inv_t,
-                                                               int top_k, int32_t* out_index, int32_t* out_token,
-                                                               double* out_resid) {
+                                                               const float* u_final, const int32_t* m_rows, int m,
+                                                               int n, float inv_t, int top_k, int32_t* out_index,
+                                                               int32_t* out_token, double* out_resid) {
     __shared__ FastShared fs;
     __shared__ CompactList L;       // entries of p with mass: index, scaled logit, current p^(i)
     __shared__ float qz[kCap];      // kept scaled logits of the proposal at hand
     __shared__ double pick;
     const int row = blockIdx.x, i0 = threadIdx.x * 2;
-    int Kp = 0, acc = m, tok = -1;
+    const int mr = row_candidates(m_rows, row, m);
+    int Kp = 0, acc = mr, tok = -1;
     // One loop over the target row (i = -1) and the proposal rows, so that the top-k selection has
     // a single call site and is inlined with its LDS operands (a second copy would be called
     // through generic pointers).
-    for (int i = -1; i < m; ++i) {
+    for (int i = -1; i < mr; ++i) {
         const float* qrow = i < 0 ? p_logits + (size_t)row * n : q_logits + ((size_t)row * m + i) * n;
         float z[E];
         unsigned km = 0u;
@@ -1145,7 +1151,7 @@ __global__ __launch_bounds__(NT) void multi_verify_list_kernel(const float* p_lo
                 if (i0 + e < Kp) L.w[i0 + e] = res[e] / R;
         }
     }
-    if (acc == m) {
+    if (acc == mr) {
         double sp = 0.0;
 #pragma unroll
         for (int e = 0; e < 2; ++e)
@@ -1165,11 +1171,13 @@ __global__ __launch_bounds__(NT) void multi_verify_list_kernel(const float* p_lo
 // selection of the target row and of every proposal row runs in a workgroup of its own (all of
 // them in parallel), and the walk over the candidates then only gathers.
 template <int E>
-__global__ __launch_bounds__(NT) void multi_row_stats_kernel(const float* p_logits, const float* q_logits, int m, int n,
-                                                             float inv_t, int top_k, WarpStat* stats) {
+__global__ __launch_bounds__(NT) void multi_row_stats_kernel(const float* p_logits, const float* q_logits,
+                                                             const int32_t* m_rows, int m, int n, float inv_t,
+                                                             int top_k, WarpStat* stats) {
     __shared__ FastShared fs;
     __shared__ CompactList L;
     const int j = blockIdx.x, row = blockIdx.y;   // j = 0: the target row, j >= 1: proposal j - 1
+    if (j > row_candidates(m_rows, row, m)) return;
     const float* l = j == 0 ? p_logits + (size_t)row * n : q_logits + ((size_t)row * m + (j - 1)) * n;
     float z[E];
     load_row<E>(l, nullptr, 0.f, inv_t, nullptr, n, z);
@@ -1180,13 +1188,15 @@ __global__ __launch_bounds__(NT) void multi_row_stats_kernel(const float* p_logi
 template <int E>
 __global__ __launch_bounds__(NT) void multi_verify_walk_kernel(const float* p_logits, const float* q_logits,
                                                                const int32_t* cand, const float* u_acc,
-                                                               const float* u_final, int m, int n, float inv_t,
-                                                               const WarpStat* stats, int32_t* out_index,
-                                                               int32_t* out_token, double* out_resid) {
+                                                               const float* u_final, const int32_t* m_rows, int m,
+                                                               int n, float inv_t, const WarpStat* stats,
+                                                               int32_t* out_index, int32_t* out_token,
+                                                               double* out_resid) {
     __shared__ Shared sh;
     __shared__ CompactList L;       // entries of p with mass: index, scaled logit, current p^(i)
     __shared__ double pick;
     const int row = blockIdx.x, i0 = threadIdx.x * 2;
+    const int mr = row_candidates(m_rows, row, m);
     const WarpStat ps = stats[(size_t)row * (m + 1)];
     float z[E];
     load_row<E>(p_logits + (size_t)row * n, nullptr, 0.f, inv_t, nullptr, n, z);
@@ -1195,8 +1205,8 @@ __global__ __launch_bounds__(NT) void multi_verify_walk_kernel(const float* p_lo
 #pragma unroll
     for (int e = 0; e < 2; ++e)
         if (i0 + e < Kp) L.w[i0 + e] /= Zp;   // the thread's own entries
-    int acc = m, tok = -1;
-    for (int i = 0; i < m; ++i) {
+    int acc = mr, tok = -1;
+    for (int i = 0; i < mr; ++i) {
         const float* qrow = q_logits + ((size_t)row * m + i) * n;
         const WarpStat qs = stats[(size_t)row * (m + 1) + 1 + i];
         const int s = cand[(size_t)row * m + i];
@@ -1230,7 +1240,7 @@ __global__ __launch_bounds__(NT) void multi_verify_walk_kernel(const float* p_lo
                 if (i0 + e < Kp) L.w[i0 + e] = res[e] / R;
         }
     }
-    if (acc == m) {
+    if (acc == mr) {
         double sp = 0.0;
 #pragma unroll
         for (int e = 0; e < 2; ++e)
@@ -1249,12 +1259,13 @@ __global__ __launch_bounds__(NT) void multi_verify_walk_kernel(const float* p_lo
 template <int E>
 __global__ __launch_bounds__(NT) void multi_verify_kernel(const float* p_logits, const float* q_logits,
                                                           const int32_t* cand, const float* u_acc,
-                                                          const float* u_final, int m, int n, float inv_t, int top_k,
-                                                          int greedy, int32_t* out_index, int32_t* out_token,
-                                                          double* out_resid) {
+                                                          const float* u_final, const int32_t* m_rows, int m, int n,
+                                                          float inv_t, int top_k, int greedy, int32_t* out_index,
+                                                          int32_t* out_token, double* out_resid) {
     __shared__ FastShared fs;
     __shared__ double pick[2];
     const int row = blockIdx.x, base = threadIdx.x * E;
+    const int mr = row_candidates(m_rows, row, m);
     float z[E];
     unsigned km;
     load_row<E>(p_logits + (size_t)row * n, nullptr, 0.f, inv_t, nullptr, n, z);
@@ -1263,8 +1274,8 @@ __global__ __launch_bounds__(NT) void multi_verify_kernel(const float* p_logits,
     dense_weights<E>(ps, z, p, fs.sh);
 #pragma unroll
     for (int e = 0; e < E; ++e) p[e] /= ps.total;
-    int acc = m, tok = -1;
-    for (int i = 0; i < m; ++i) {
+    int acc = mr, tok = -1;
+    for (int i = 0; i < mr; ++i) {
         load_row<E>(q_logits + ((size_t)row * m + i) * n, nullptr, 0.f, inv_t, nullptr, n, z);
         WarpStat qs = warp_select<E>(z, n, top_k, greedy, fs, &km);
         double q[E];
@@ -1297,7 +1308,7 @@ __global__ __launch_bounds__(NT) void multi_verify_kernel(const float* p_logits,
             for (int e = 0; e < E; ++e) p[e] = q[e] / R;
         }
     }
-    if (acc == m) {
+    if (acc == mr) {
         double sp = 0.0;
 #pragma unroll
         for (int e = 0; e < E; ++e) sp += p[e];
@@ -1310,6 +1321,26 @@ __global__ __launch_bounds__(NT) void multi_verify_kernel(const float* p_logits,
         if (out_resid)
             for (int i = acc + 1; i < m; ++i) out_resid[(size_t)row * m + i] = -1.0;
     }
+}
+
+// One draw per row from the row's warped distribution (inverse CDF over ascending index): the
+// candidates of a sampling pool.  Rows whose entry of `skip` is negative give -1.
+template <int E>
+__global__ __launch_bounds__(NT) void sample_rows_kernel(const float* logits, const int32_t* skip, const float* u, int n,
+                                                         float inv_t, int top_k, int greedy, int32_t* out_token) {
+    __shared__ FastShared fs;
+    __shared__ CompactList L;
+    const int row = blockIdx.x;
+    if (skip && skip[row] < 0) {
+        if (threadIdx.x == 0) out_token[row] = -1;
+        return;
+    }
+    float z[E];
+    load_row<E>(logits + (size_t)row * n, nullptr, 0.f, inv_t, nullptr, n, z);
+    const float ur = u[row];
+    int drawn = 0;
+    (void)warp_and_draw<E>(z, n, top_k, greedy, fs, L, &ur, &drawn);
+    if (threadIdx.x == 0) out_token[row] = drawn;
 }
 
 SampParams samp_params(const hawk_ctx* c) {
@@ -1409,10 +1440,22 @@ void launch_force_commit(hawk_ctx* c, int cnt) {
                                                      c->N, cnt, c->S);
 }
 
+int launch_sample_rows(const float* logits, const int32_t* skip, const float* u, int rows, int n, float temperature,
+                       int top_k, int32_t* out_token, hipStream_t stream) {
+    const int E = n <= 4 * NT ? 4 : (n <= 16 * NT ? 16 : 0);
+    if (!E) return HAWK_EINVAL;
+    const int greedy = (temperature == 0.0f || top_k == 1) ? 1 : 0;
+    const float inv_t = greedy ? 1.0f : 1.0f / temperature;
+    const int tk = top_k < n ? top_k : n;
+    auto kern = E == 4 ? sample_rows_kernel<4> : sample_rows_kernel<16>;
+    kern<<<rows, NT, 0, stream>>>(logits, skip, u, n, inv_t, tk, greedy, out_token);
+    return hipGetLastError() == hipSuccess ? HAWK_OK : HAWK_EDEVICE;
+}
+
 size_t multi_verify_workspace_bytes(int rows, int m) { return (size_t)rows * (m + 1) * sizeof(WarpStat); }
 
 int launch_multi_verify(const float* p_logits, const float* q_logits, const int32_t* cand, const float* u_acc,
-                        const float* u_final, int rows, int m, int n, float temperature, int top_k,
+                        const float* u_final, const int32_t* m_rows, int rows, int m, int n, float temperature, int top_k,
                         int32_t* out_index, int32_t* out_token, double* out_resid, void* workspace,
                         size_t workspace_bytes, hipStream_t stream) {
     const int E = n <= 4 * NT ? 4 : (n <= 16 * NT ? 16 : 0);
@@ -1424,16 +1467,16 @@ int launch_multi_verify(const float* p_logits, const float* q_logits, const int3
         WarpStat* stats = static_cast<WarpStat*>(workspace);
         auto k1 = E == 4 ? multi_row_stats_kernel<4> : multi_row_stats_kernel<16>;
         auto k2 = E == 4 ? multi_verify_walk_kernel<4> : multi_verify_walk_kernel<16>;
-        k1<<<dim3(m + 1, rows), NT, 0, stream>>>(p_logits, q_logits, m, n, inv_t, tk, stats);
-        k2<<<rows, NT, 0, stream>>>(p_logits, q_logits, cand, u_acc, u_final, m, n, inv_t, stats, out_index, out_token,
+        k1<<<dim3(m + 1, rows), NT, 0, stream>>>(p_logits, q_logits, m_rows, m, n, inv_t, tk, stats);
+        k2<<<rows, NT, 0, stream>>>(p_logits, q_logits, cand, u_acc, u_final, m_rows, m, n, inv_t, stats, out_index, out_token,
                                     out_resid);
     } else if (use_list(tk, n, greedy)) {
         auto kern = E == 4 ? multi_verify_list_kernel<4> : multi_verify_list_kernel<16>;
-        kern<<<rows, NT, 0, stream>>>(p_logits, q_logits, cand, u_acc, u_final, m, n, inv_t, tk, out_index, out_token,
+        kern<<<rows, NT, 0, stream>>>(p_logits, q_logits, cand, u_acc, u_final, m_rows, m, n, inv_t, tk, out_index, out_token,
                                       out_resid);
     } else {
         auto kern = E == 4 ? multi_verify_kernel<4> : multi_verify_kernel<16>;
-        kern<<<rows, NT, 0, stream>>>(p_logits, q_logits, cand, u_acc, u_final, m, n, inv_t, tk, greedy, out_index,
+        kern<<<rows, NT, 0, stream>>>(p_logits, q_logits, cand, u_acc, u_final, m_rows, m, n, inv_t, tk, greedy, out_index,
                                       out_token, out_resid);
     }
     return hipGetLastError() == hipSuccess ? HAWK_OK : HAWK_EDEVICE;

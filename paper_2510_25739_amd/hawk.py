@@ -72,9 +72,21 @@ EXPORTS = {
     "hawk_last_path": (C.c_int, [C.c_void_p]),
     "hawk_phase_trace": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t]),
     "hawk_multi_verify_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int]),
-    "hawk_multi_verify": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
-                                    C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
-                                    C.c_size_t, C.c_void_p]),
+    "hawk_multi_verify": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                    C.c_int, C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.c_void_p, C.c_size_t, C.c_void_p]),
+    "hawk_spatial_heads_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int]),
+    "hawk_spatial_heads": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "hawk_spec_cache_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int]),
+    "hawk_spec_cache_slot": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int]),
+    "hawk_spec_cache_reset": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]),
+    "hawk_spec_cache_push": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                       C.c_size_t, C.c_int, C.c_void_p]),
+    "hawk_spec_pool": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_size_t,
+                                 C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "hawk_sample_rows": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_int,
+                                   C.c_void_p, C.c_void_p]),
 }
 
 
@@ -127,24 +139,27 @@ def multi_verify_workspace_bytes(rows: int, m: int) -> int:
 
 
 def multi_verify(p_logits, q_logits, cand, u_acc, u_final, temperature: float, top_k: int, want_resid: bool = False,
-                 workspace=None):
+                 workspace=None, m_rows=None):
     """hawk_multi_verify on device tensors (torch, on the GPU): p_logits [rows, n] fp32, q_logits
     [rows, m, n] fp32, cand [rows, m] int32, u_acc [rows, m] fp32, u_final [rows] fp32.
     workspace: None, or a device uint8 tensor of at least multi_verify_workspace_bytes(rows, m) bytes.
+    m_rows: None, or a device int32 tensor [rows] with each position's own number of candidates.
     Returns device tensors (index [rows] int32, token [rows] int32[, residual masses [rows, m] fp64]);
     the launch is asynchronous on torch's current stream."""
     import torch  # device memory and stream only
     rows, m, n = q_logits.shape
     for t, shape, dt in ((p_logits, (rows, n), torch.float32), (q_logits, (rows, m, n), torch.float32),
                          (cand, (rows, m), torch.int32), (u_acc, (rows, m), torch.float32),
-                         (u_final, (rows,), torch.float32)):
+                         (u_final, (rows,), torch.float32)) + (
+                                 ((m_rows, (rows,), torch.int32),) if m_rows is not None else ()):
         if not (t.is_cuda and t.is_contiguous() and t.dtype == dt and tuple(t.shape) == shape):
             raise HawkError(-1, "hawk_multi_verify", "arguments must be contiguous device tensors of the documented shapes")
     idx = torch.empty(rows, dtype=torch.int32, device=p_logits.device)
     tok = torch.empty(rows, dtype=torch.int32, device=p_logits.device)
     resid = torch.empty((rows, m), dtype=torch.float64, device=p_logits.device) if want_resid else None
     rc = load_library().hawk_multi_verify(p_logits.data_ptr(), q_logits.data_ptr(), cand.data_ptr(), u_acc.data_ptr(),
-                                          u_final.data_ptr(), rows, m, n, float(temperature), int(top_k),
+                                          u_final.data_ptr(), m_rows.data_ptr() if m_rows is not None else None,
+                                          rows, m, n, float(temperature), int(top_k),
                                           idx.data_ptr(), tok.data_ptr(), resid.data_ptr() if want_resid else None,
                                           workspace.data_ptr() if workspace is not None else None,
                                           workspace.numel() * workspace.element_size() if workspace is not None else 0,
@@ -152,6 +167,110 @@ def multi_verify(p_logits, q_logits, cand, u_acc, u_final, temperature: float, t
     if rc != 0:
         raise HawkError(rc, "hawk_multi_verify")
     return (idx, tok, resid) if want_resid else (idx, tok)
+
+
+def _stream_of(t):
+    import torch  # device memory and stream only
+    return torch.cuda.current_stream(t.device).cuda_stream
+
+
+def _dev_ok(t, dtype, shape=None):
+    return t.is_cuda and t.is_contiguous() and t.dtype == dtype and (shape is None or tuple(t.shape) == tuple(shape))
+
+
+def spatial_heads(h, W_heads, W_out, want_g: bool = False):
+    """hawk_spatial_heads on device tensors: h [rows, d] fp32, W_heads [n_heads, d, d] bf16, W_out
+    [V_s, d] bf16.  Returns q_logits [rows, n_heads, V_s] fp32 (and g [rows, n_heads, d] fp32)."""
+    import torch  # device memory and stream only
+    rows, d = h.shape
+    n_heads, v_s = W_heads.shape[0], W_out.shape[0]
+    if not (_dev_ok(h, torch.float32) and _dev_ok(W_heads, torch.bfloat16, (n_heads, d, d))
+            and _dev_ok(W_out, torch.bfloat16, (v_s, d))):
+        raise HawkError(-1, "hawk_spatial_heads", "arguments must be contiguous device tensors of the documented shapes")
+    L = load_library()
+    nws = int(L.hawk_spatial_heads_workspace_bytes(rows, n_heads, d))
+    ws = torch.empty(max(nws, 16), dtype=torch.uint8, device=h.device)
+    q = torch.empty((rows, n_heads, v_s), dtype=torch.float32, device=h.device)
+    g = torch.empty((rows, n_heads, d), dtype=torch.float32, device=h.device) if want_g else None
+    rc = L.hawk_spatial_heads(h.data_ptr(), W_heads.data_ptr(), W_out.data_ptr(), rows, n_heads, d, v_s, q.data_ptr(),
+                              g.data_ptr() if want_g else None, ws.data_ptr(), nws, _stream_of(h))
+    if rc != 0:
+        raise HawkError(rc, "hawk_spatial_heads")
+    return (q, g) if want_g else q
+
+
+def spec_cache_bytes(IW: int, VSD: int, v_s: int) -> int:
+    return int(load_library().hawk_spec_cache_bytes(IW, VSD, v_s))
+
+
+def spec_cache_slot(IW: int, VSD: int, pos: int, depth: int) -> int:
+    return int(load_library().hawk_spec_cache_slot(IW, VSD, pos, depth))
+
+
+class SpecCache:
+    """The speculation cache of one image in device memory (a torch uint8 tensor) and its calls."""
+
+    def __init__(self, IW: int, IH: int, VSD: int, v_s: int, device: str = "cuda:0"):
+        import torch  # device memory and stream only
+        self._torch = torch
+        self.IW, self.IH, self.VSD, self.v_s = IW, IH, VSD, v_s
+        self._L = load_library()
+        nbytes = spec_cache_bytes(IW, VSD, v_s)
+        if nbytes == 0:
+            raise HawkError(-1, "hawk_spec_cache_bytes", "invalid cache shape")
+        self.mem = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        self.reset()
+
+    def reset(self):
+        rc = self._L.hawk_spec_cache_reset(self.mem.data_ptr(), self.IW, self.VSD, self.v_s, _stream_of(self.mem))
+        if rc != 0:
+            raise HawkError(rc, "hawk_spec_cache_reset")
+
+    def push(self, pos, q_vert, row_stride: int):
+        """pos [rows] int32; q_vert: a device fp32 tensor whose row r starts r * row_stride floats in."""
+        torch = self._torch
+        rows = pos.numel()
+        if not (_dev_ok(pos, torch.int32) and q_vert.is_cuda and q_vert.dtype == torch.float32
+                and q_vert.numel() >= (rows - 1) * row_stride + self.VSD * self.v_s):
+            raise HawkError(-1, "hawk_spec_cache_push", "bad arguments")
+        rc = self._L.hawk_spec_cache_push(self.mem.data_ptr(), self.IW, self.IH, self.VSD, self.v_s, pos.data_ptr(),
+                                          q_vert.data_ptr(), row_stride, rows, _stream_of(self.mem))
+        if rc != 0:
+            raise HawkError(rc, "hawk_spec_cache_push")
+
+    def pool(self, target, q_horiz, horiz_stride: int):
+        """target [n] int32; q_horiz: device fp32 tensor, item i's horizontal logits i * horiz_stride
+        floats in.  Returns pool_logits [n, VSD + 1, V_s], pool_m [n], pool_delta [n, VSD + 1]."""
+        torch = self._torch
+        n = target.numel()
+        if not (_dev_ok(target, torch.int32) and q_horiz.is_cuda and q_horiz.dtype == torch.float32
+                and q_horiz.numel() >= (n - 1) * horiz_stride + self.v_s):
+            raise HawkError(-1, "hawk_spec_pool", "bad arguments")
+        dev = self.mem.device
+        logits = torch.zeros((n, self.VSD + 1, self.v_s), dtype=torch.float32, device=dev)
+        m = torch.empty(n, dtype=torch.int32, device=dev)
+        delta = torch.empty((n, self.VSD + 1), dtype=torch.int32, device=dev)
+        rc = self._L.hawk_spec_pool(self.mem.data_ptr(), self.IW, self.IH, self.VSD, self.v_s, target.data_ptr(),
+                                    q_horiz.data_ptr(), horiz_stride, n, logits.data_ptr(), m.data_ptr(),
+                                    delta.data_ptr(), _stream_of(self.mem))
+        if rc != 0:
+            raise HawkError(rc, "hawk_spec_pool")
+        return logits, m, delta
+
+
+def sample_rows(logits, u, temperature: float, top_k: int, skip=None):
+    """hawk_sample_rows on device tensors: logits [rows, n] fp32, u [rows] fp32, skip None or [rows] int32."""
+    import torch  # device memory and stream only
+    rows, n = logits.shape
+    if not (_dev_ok(logits, torch.float32) and _dev_ok(u, torch.float32, (rows,))
+            and (skip is None or _dev_ok(skip, torch.int32, (rows,)))):
+        raise HawkError(-1, "hawk_sample_rows", "arguments must be contiguous device tensors of the documented shapes")
+    out = torch.empty(rows, dtype=torch.int32, device=logits.device)
+    rc = load_library().hawk_sample_rows(logits.data_ptr(), skip.data_ptr() if skip is not None else None, u.data_ptr(),
+                                         rows, n, float(temperature), int(top_k), out.data_ptr(), _stream_of(logits))
+    if rc != 0:
+        raise HawkError(rc, "hawk_sample_rows")
+    return out
 
 
 class Hawk:

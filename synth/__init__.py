@@ -13,6 +13,8 @@ from .inputs import (  # noqa: F401
     make_weights,
     make_cond,
     make_uniforms,
+    make_spatial_heads,
+    make_logit_rows,
     bf16_bits_to_f32,
     f32_to_bf16_bits,
 )

@@ -189,3 +189,21 @@ def make_uniforms(seed: int, shape) -> np.ndarray:
     rng = np.random.Generator(np.random.PCG64(seed))
     bits = rng.integers(0, 1 << 24, size=shape, dtype=np.uint32)
     return (bits.astype(np.float32) / np.float32(1 << 24)).astype(np.float32)
+
+
+def make_spatial_heads(seed: int, rows: int, n_heads: int, d: int, v_s: int, std_head: float = 0.02,
+                       std_out: float = 0.04):
+    """Inputs of the dual-direction draft heads: hidden states N(0,1) fp32 [rows, d], head
+    matrices N(0, std_head^2) [n_heads, d, d] and the output layer's sampled rows
+    N(0, std_out^2) [v_s, d], both as bf16 bit patterns (round to nearest even)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    h = rng.standard_normal((rows, d), dtype=np.float32)
+    w_heads = rng.standard_normal((n_heads, d, d), dtype=np.float32) * np.float32(std_head)
+    w_out = rng.standard_normal((v_s, d), dtype=np.float32) * np.float32(std_out)
+    return h, f32_to_bf16_bits(w_heads), f32_to_bf16_bits(w_out)
+
+
+def make_logit_rows(seed: int, shape, std: float = 1.5) -> np.ndarray:
+    """Logit rows N(0, std^2), fp32."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    return (rng.standard_normal(shape, dtype=np.float32) * np.float32(std)).astype(np.float32)

@@ -65,18 +65,62 @@ def test_multi_verify_rejects_bad_arguments_before_any_launch(H):
     lib = C.CDLL(H.lib_path())
     fn = lib.hawk_multi_verify
     fn.restype = C.c_int
-    fn.argtypes = [C.c_void_p] * 5 + [C.c_int] * 3 + [C.c_float, C.c_int] + [C.c_void_p] * 4 + [C.c_size_t, C.c_void_p]
+    fn.argtypes = [C.c_void_p] * 6 + [C.c_int] * 3 + [C.c_float, C.c_int] + [C.c_void_p] * 4 + [C.c_size_t, C.c_void_p]
     one = C.c_void_p(16)   # never dereferenced: every call below fails validation first
-    assert fn(None, one, one, one, one, 1, 1, 8, 1.0, 8, one, one, None, None, 0, None) == -1
-    assert fn(one, one, one, one, one, 1, 0, 8, 1.0, 8, one, one, None, None, 0, None) == -1      # no candidates
-    assert fn(one, one, one, one, one, 1, 1, 0, 1.0, 8, one, one, None, None, 0, None) == -1      # empty vocabulary
-    assert fn(one, one, one, one, one, 1, 1, 8, -1.0, 8, one, one, None, None, 0, None) == -1     # negative temperature
-    assert fn(one, one, one, one, one, 1, 1, 8, 1.0, 0, one, one, None, None, 0, None) == -1      # top_k < 1
-    assert fn(one, one, one, one, one, -1, 1, 8, 1.0, 8, one, one, None, None, 0, None) == -1
-    assert fn(one, one, one, one, one, 0, 1, 8, 1.0, 8, one, one, None, None, 0, None) == 0       # no rows: nothing to do
+    assert fn(None, one, one, one, one, None, 1, 1, 8, 1.0, 8, one, one, None, None, 0, None) == -1
+    assert fn(one, one, one, one, one, None, 1, 0, 8, 1.0, 8, one, one, None, None, 0, None) == -1      # no candidates
+    assert fn(one, one, one, one, one, None, 1, 1, 0, 1.0, 8, one, one, None, None, 0, None) == -1      # empty vocabulary
+    assert fn(one, one, one, one, one, None, 1, 1, 8, -1.0, 8, one, one, None, None, 0, None) == -1     # negative temperature
+    assert fn(one, one, one, one, one, None, 1, 1, 8, 1.0, 0, one, one, None, None, 0, None) == -1      # top_k < 1
+    assert fn(one, one, one, one, one, None, -1, 1, 8, 1.0, 8, one, one, None, None, 0, None) == -1
+    assert fn(one, one, one, one, one, None, 0, 1, 8, 1.0, 8, one, one, None, None, 0, None) == 0       # no rows: nothing to do
     ws = lib.hawk_multi_verify_workspace_bytes
     ws.restype, ws.argtypes = C.c_size_t, [C.c_int, C.c_int]
     assert ws(6, 2) == 6 * 3 * 24 and ws(12, 2) == 2 * ws(6, 2) and ws(0, 2) == 0   # one 24-byte record per logit row
+
+
+def test_spec_cache_layout_holds_every_outstanding_prediction(H):
+    # host logic of the speculation cache (Method, "Dual Direction Drafting Heads": the cache of
+    # IW * VSD * (VSD + 1) / 2 entries): the slot arithmetic against a raster walk that keeps every
+    # outstanding prediction in a plain dictionary
+    for IW, IH, VSD, v_s in ((6, 9, 2, 32), (5, 12, 3, 8), (24, 24, 1, 16), (7, 5, 4, 4)):
+        slots = IW * VSD * (VSD + 1) // 2
+        tags = (slots * 4 + 255) // 256 * 256
+        assert H.spec_cache_bytes(IW, VSD, v_s) == tags + slots * v_s * 4
+        held = {}   # slot -> (target, depth) outstanding
+        for T in range(IW * IH):
+            for d in range(1, VSD + 1):           # what pointed to T is read before T is committed ...
+                s = H.spec_cache_slot(IW, VSD, T, d)
+                assert 0 <= s < slots
+                if T - d * IW >= 0:
+                    assert held.get(s) == (T, d)
+            for d in range(1, VSD + 1):           # ... and its slot may be taken over right after
+                t = T + d * IW
+                if t < IW * IH:
+                    s = H.spec_cache_slot(IW, VSD, t, d)
+                    assert s not in held or held[s] == (T, d), "slot still holds an outstanding prediction"
+                    held[s] = (t, d)
+    assert H.spec_cache_slot(6, 2, 5, 3) == -1 and H.spec_cache_slot(6, 2, -1, 1) == -1
+    assert H.spec_cache_bytes(0, 2, 8) == 0 and H.spec_cache_bytes(4, 17, 8) == 0
+
+
+def test_spatial_entry_points_reject_bad_arguments_before_any_launch(H):
+    L = H.load_library()
+    one = C.c_void_p(4096)   # never dereferenced: every call below fails validation first
+    assert L.hawk_spatial_heads(None, one, one, 1, 4, 64, 16, one, None, one, 1 << 20, None) == -1
+    assert L.hawk_spatial_heads(one, one, one, 1, 4, 60, 16, one, None, one, 1 << 20, None) == -1    # d % 64
+    assert L.hawk_spatial_heads(one, one, one, 1, 4, 64, 24, one, None, one, 1 << 20, None) == -1    # V_s % 16
+    assert L.hawk_spatial_heads(one, one, one, 1, 4, 64, 16, one, None, one, 16, None) == -1         # workspace too small
+    assert L.hawk_spatial_heads(one, one, one, 0, 4, 64, 16, one, None, None, 0, None) == 0
+    assert L.hawk_spatial_heads_workspace_bytes(6, 4, 1280) >= 6 * 4 * 1280 * 4 + 2 * 6 * 1280 * 2 + 2 * 24 * 1280 * 2
+    assert L.hawk_spec_cache_reset(None, 4, 2, 8, None) == -1
+    assert L.hawk_spec_cache_push(one, 4, 4, 2, 8, one, one, 8, 1, None) == -1     # row stride below VSD * V_s
+    assert L.hawk_spec_cache_push(one, 4, 4, 2, 8, one, one, 16, 5, None) == -1    # more rows than a line holds
+    assert L.hawk_spec_cache_push(one, 4, 4, 2, 8, one, one, 16, 0, None) == 0
+    assert L.hawk_spec_pool(one, 4, 4, 2, 8, one, one, 4, 1, one, one, one, None) == -1   # stride below V_s
+    assert L.hawk_spec_pool(one, 4, 4, 2, 8, one, one, 8, 0, one, one, one, None) == 0
+    assert L.hawk_sample_rows(one, None, one, 1, 0, 1.0, 8, one, None) == -1
+    assert L.hawk_sample_rows(one, None, one, 0, 8, 1.0, 8, one, None) == 0
 
 
 def test_product_never_imports_the_oracle():

@@ -110,10 +110,10 @@ def test_multi_verify_rejects_bad_arguments(H):
     L = H.load_library()
     z = torch.zeros(8, device="cuda:0")
     ptr = z.data_ptr()
-    assert L.hawk_multi_verify(None, ptr, ptr, ptr, ptr, 1, 1, 8, 1.0, 8, ptr, ptr, None, None, 0, None) == -1
-    assert L.hawk_multi_verify(ptr, ptr, ptr, ptr, ptr, 1, 0, 8, 1.0, 8, ptr, ptr, None, None, 0, None) == -1
-    assert L.hawk_multi_verify(ptr, ptr, ptr, ptr, ptr, 1, 1, 16385, 1.0, 8, ptr, ptr, None, None, 0, None) == -1
-    assert L.hawk_multi_verify(ptr, ptr, ptr, ptr, ptr, 0, 1, 8, 1.0, 8, ptr, ptr, None, None, 0, None) == 0
+    assert L.hawk_multi_verify(None, ptr, ptr, ptr, ptr, None, 1, 1, 8, 1.0, 8, ptr, ptr, None, None, 0, None) == -1
+    assert L.hawk_multi_verify(ptr, ptr, ptr, ptr, ptr, None, 1, 0, 8, 1.0, 8, ptr, ptr, None, None, 0, None) == -1
+    assert L.hawk_multi_verify(ptr, ptr, ptr, ptr, ptr, None, 1, 1, 16385, 1.0, 8, ptr, ptr, None, None, 0, None) == -1
+    assert L.hawk_multi_verify(ptr, ptr, ptr, ptr, ptr, None, 0, 1, 8, 1.0, 8, ptr, ptr, None, None, 0, None) == 0
 
 
 def test_rejection_probability_curve_matches_oracle(H):
