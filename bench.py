@@ -185,6 +185,8 @@ def main():
     hk.close()
     from paper_2510_25739_amd.multi_verify_timing import bench_multi_verify
     out["multi_verify"] = bench_multi_verify(H, s)
+    from paper_2510_25739_amd.spatial_timing import bench_spatial_draft
+    out["spatial_draft"] = bench_spatial_draft(H, s)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(s, blob, cond, unc)
     print(json.dumps(out))
