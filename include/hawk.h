@@ -213,6 +213,35 @@ int hawk_last_path(const hawk_ctx* ctx);
  * barrier's release. */
 int hawk_phase_trace(hawk_ctx* ctx, int enable, uint64_t* out, size_t n_words);
 
+/* Tree verification (Method, "Spatial Sampling Pool": the candidate tree is the Cartesian product
+ * of the candidates of the positions ahead; "Sampling and Verification": candidates of one depth
+ * are verified in order, an acceptance moves one depth down, a rejection of all of them ends the
+ * step with a draw from the updated target).  Takes the place of hawk_draft + hawk_verify for one
+ * step (call it after hawk_prefill, hawk_verify, hawk_force or itself).
+ *   depth D (1..8) positions ahead; m_depth [D] (host) candidates per depth; the tree has
+ *   1 + m_1 + m_1 m_2 + ... nodes (the root is the last committed token), at most 64 and at most
+ *   k_max + 1 (the rows a context has room for); every unfinished prompt needs that many free
+ *   positions left in its image (HAWK_EINVAL otherwise: finish with hawk_draft / hawk_verify).
+ *   cand (host) [D][batch][m_max], m_max = max m_depth: candidate s of depth j + 1 as an index into
+ *   the sampled slice; q_logits (DEVICE) [D][batch][m_max][V_s] fp32: the proposal each candidate
+ *   was drawn from (e.g. the members of hawk_spec_pool); u_acc (host) [D][batch][m_max], u_final
+ *   (host) [D + 1][batch] in [0, 1): u_final[j] draws the token after a rejection at depth j + 1,
+ *   u_final[D] the extra token after D acceptances.  Entries beyond m_depth[j] are not read.
+ * One target pass scores every node: node r's row sits at the root's position plus its depth and
+ * attends the committed entries, its ancestors and itself (its keys and values go to the cache
+ * entry root + r); the walk applies hawk_multi_verify's rule at each depth to the row of the node
+ * it stands on; then the accepted path's cache entries are moved to their positions, tokens, n and
+ * the hidden state for the next draft are committed as by hawk_verify.
+ * out_n_accept (host, may be NULL) [batch]: candidates accepted (-1: prompt finished before the
+ * call); out_tokens (host, may be NULL) [batch][D + 1]: the accepted + 1 tokens emitted (vocabulary
+ * ids), -1 beyond.  Runs one kernel per operation (not the persistent kernel); classifier-free
+ * guidance is not covered (HAWK_EINVAL).  Synchronises the stream several times (the walk is driven
+ * from the host).  hawk_get_tree_logits: the rows of the last tree pass, out (host)
+ * [batch][n_nodes][V_s]. */
+int hawk_verify_tree(hawk_ctx* ctx, int depth, const int32_t* m_depth, const int32_t* cand, const float* q_logits,
+                     const float* u_acc, const float* u_final, int32_t* out_n_accept, int32_t* out_tokens);
+int hawk_get_tree_logits(hawk_ctx* ctx, float* out, int n_nodes);
+
 /* Verification of several candidates at one position, each drawn from a proposal of its own
  * (Method, "Sampling and Verification": the iterated update of the target after consecutive
  * rejections; appendix "Theoretical Justification": general form for an ordered sequence of

@@ -10,6 +10,8 @@
 
 #include "hawk_internal.h"
 
+#include <vector>
+
 using namespace hawk;
 
 namespace {
@@ -99,6 +101,7 @@ bool derive(const hawk_config* g, hawk_ctx* c) {
     o.u_draft = take(B * ks * 4); o.u_acc = take(B * ks * 4); o.u_fin = take(B * 4);
     o.out_na = take(B * 4); o.out_tok = take(B * ks * 4); o.inv_freq = take((size_t)(hd / 2) * 8);
     o.replay = take(B * c->Nmax * 4); o.cond = take(S * (size_t)g->max_cond * d * 4);
+    o.tree = take(768 + B * 88);
     const size_t widest = 3 * d > m ? 3 * d : m;
     c->split_bytes = g->dtype == HAWK_BF16 ? M * widest * 4 : 0;
     o.split = c->split_bytes ? take(c->split_bytes) : 0;
@@ -133,6 +136,7 @@ RowMap step_map(hawk_ctx* c, int k) {
     RowMap m;
     m.mode = 1; m.rows_per_seq = k + 1; m.n_seq = c->S; m.batch = c->B; m.n_cond = c->C;
     m.n = wsp<int32_t>(c, c->off.n); m.k_eff = wsp<int32_t>(c, c->off.k_eff);
+    m.tree_depth = nullptr; m.tree_anc = nullptr;
     return m;
 }
 
@@ -230,7 +234,7 @@ int enqueue_prefill(hawk_ctx* c, const float* cond, const float* uncond, int bat
     const int M = c->S * n_cond;
     RowMap map;
     map.mode = 0; map.rows_per_seq = n_cond; map.n_seq = c->S; map.batch = c->B; map.n_cond = n_cond;
-    map.n = nullptr; map.k_eff = nullptr;
+    map.n = nullptr; map.k_eff = nullptr; map.tree_depth = nullptr; map.tree_anc = nullptr;
     launch_cond_rows(c, M);
     run_layers(c, map, M);
     launch_keep_hprev_prefill(c);
@@ -529,6 +533,156 @@ int hawk_verify(hawk_ctx* c, int k, const float* u_acc, const float* u_final, in
     return HAWK_OK;
 }
 
+int hawk_verify_tree(hawk_ctx* c, int depth, const int32_t* m_depth, const int32_t* cand, const float* q_logits,
+                     const float* u_acc, const float* u_final, int32_t* out_n_accept, int32_t* out_tokens) {
+    if (!c) return HAWK_EINVAL;
+    if (c->phase < 2) return fail(c, HAWK_ESTATE, "hawk_verify_tree before hawk_prefill");
+    if (c->cfg.use_cfg) return fail(c, HAWK_EINVAL, "hawk_verify_tree does not cover classifier-free guidance");
+    if (!m_depth || !cand || !q_logits || !u_acc || !u_final) return fail(c, HAWK_EINVAL, "null input");
+    if (depth < 1 || depth > kTreeMaxDepth) return fail(c, HAWK_EINVAL, "depth = %d outside [1, %d]", depth, kTreeMaxDepth);
+    const int B = c->B;
+    // the tree: node 0 is the root, then depth by depth the Cartesian product of the candidate lists,
+    // a node's children next to each other in candidate order
+    int m_max = 0, n_nodes = 1, first[kTreeMaxDepth + 2];   // first[j]: first node of depth j
+    first[0] = 0;
+    first[1] = 1;
+    for (int j = 0, width = 1; j < depth; ++j) {
+        if (m_depth[j] < 1 || m_depth[j] > kTreeMaxNodes) return fail(c, HAWK_EINVAL, "m_depth[%d] = %d", j, m_depth[j]);
+        width *= m_depth[j];
+        n_nodes += width;
+        if (n_nodes > kTreeMaxNodes || n_nodes > c->kmax + 1)
+            return fail(c, HAWK_EINVAL, "the tree has more than %d nodes (64, or k_max + 1 rows per sequence)",
+                        n_nodes > kTreeMaxNodes ? kTreeMaxNodes : c->kmax + 1);
+        first[j + 2] = n_nodes;
+        m_max = m_depth[j] > m_max ? m_depth[j] : m_max;
+    }
+    if (c->Vs > 16384) return fail(c, HAWK_EINVAL, "sampled slice beyond 16384 entries");
+    for (size_t i = 0; i < (size_t)depth * B * m_max; ++i) {
+        const int j = (int)(i / ((size_t)B * m_max)), slot = (int)(i % m_max);
+        if (slot < m_depth[j] && (cand[i] < 0 || cand[i] >= c->Vs)) return fail(c, HAWK_EINVAL, "candidate outside the sampled slice");
+        if (slot < m_depth[j] && !(u_acc[i] >= 0.f && u_acc[i] < 1.f)) return fail(c, HAWK_EINVAL, "uniforms must lie in [0, 1)");
+    }
+    if (!uniforms_ok(u_final, (size_t)(depth + 1) * B)) return fail(c, HAWK_EINVAL, "uniforms must lie in [0, 1)");
+    int32_t n_now[256];
+    if (B > 256) return fail(c, HAWK_EINVAL, "batch beyond 256");
+    int rc = download(c, n_now, c->off.n, (size_t)B * 4);
+    if (rc) return rc;
+    bool any = false;
+    for (int b = 0; b < B; ++b) {
+        if (n_now[b] >= c->N) continue;   // finished
+        if (n_now[b] + n_nodes > c->N)
+            return fail(c, HAWK_EINVAL, "prompt %d: %d tokens left, the tree needs room for %d rows (use hawk_verify near the end)",
+                        b, c->N - n_now[b], n_nodes);
+        any = true;
+    }
+    // host image of the device arrays
+    const int ks = c->kmax + 1;
+    std::vector<int32_t> node_depth(kTreeMaxNodes, 0), parent(n_nodes, -1), digit(n_nodes, 0), keff(B), tokens((size_t)B * ks, -1);
+    std::vector<unsigned long long> anc(kTreeMaxNodes, 0ull);
+    for (int j = 1; j <= depth; ++j)
+        for (int i = first[j]; i < first[j + 1]; ++i) {
+            const int idx = i - first[j];
+            node_depth[i] = j;
+            parent[i] = j == 1 ? 0 : first[j - 1] + idx / m_depth[j - 1];
+            digit[i] = idx % m_depth[j - 1];
+            anc[i] = anc[parent[i]] | (1ull << parent[i]);
+        }
+    for (int b = 0; b < B; ++b) {
+        keff[b] = n_now[b] >= c->N ? -1 : n_nodes - 1;
+        for (int i = 1; i < n_nodes; ++i)
+            tokens[(size_t)b * ks + i - 1] = c->cfg.samp_lo + cand[((size_t)(node_depth[i] - 1) * B + b) * m_max + digit[i]];
+    }
+    const size_t t0 = c->off.tree, t_anc = t0 + 256, t_cur = t0 + 768, t_m = t_cur + (size_t)B * 4, t_idx = t_m + (size_t)B * 4,
+                 t_tok = t_idx + (size_t)B * 4, t_acc = t_tok + (size_t)B * 4, t_path = t_acc + (size_t)B * 4,
+                 t_toks = t_path + (size_t)B * kTreeMaxDepth * 4;
+    rc = upload(c, t0, node_depth.data(), kTreeMaxNodes * 4);
+    if (!rc) rc = upload(c, t_anc, anc.data(), kTreeMaxNodes * 8);
+    if (!rc) rc = upload(c, c->off.k_eff, keff.data(), (size_t)B * 4);
+    if (!rc) rc = upload(c, c->off.draft, tokens.data(), tokens.size() * 4);
+    if (rc) return rc;
+    std::vector<int32_t> acc(B, -1), path((size_t)B * kTreeMaxDepth, 0), toks((size_t)B * (kTreeMaxDepth + 1), -1), cur(B, 0),
+        mrows(B, 0), idx(B), tok(B);
+    if (any) {
+        // the target pass over all nodes: one kernel per operation, tree rows
+        RowMap map = step_map(c, n_nodes - 1);
+        map.mode = 2;
+        map.tree_depth = wsp<int32_t>(c, t0);
+        map.tree_anc = wsp<unsigned long long>(c, t_anc);
+        const int M = c->S * n_nodes;
+        c->presplit_off = 0;
+        launch_embed_rows(c, map, M);
+        c->last_path = 0;
+        run_layers(c, map, M);
+        launch_rmsnorm(c, c->off.x, c->d, c->w.g_f, c->off.a, M, true);
+        launch_gemm(c, c->off.a, c->d, slice_off(c), c->Vs, c->d, c->off.logit_s, c->Vs, M, false, true);
+        HIP_TRY(c, hipGetLastError());
+        // the walk, one depth at a time: the row of the node each prompt stands on is the target of
+        // that depth's candidates
+        std::vector<char> walking(B);
+        for (int b = 0; b < B; ++b) {
+            walking[b] = keff[b] >= 0;
+            acc[b] = keff[b] >= 0 ? 0 : -1;
+        }
+        float* p_rows = wsp<float>(c, c->off.logit_b);
+        for (int j = 0; j <= depth; ++j) {
+            bool left = false;
+            int spare = -1;   // a row with valid logits for the prompts that are not walking (their result is ignored)
+            for (int b = 0; b < B; ++b) {
+                cur[b] = walking[b] ? b * n_nodes + (acc[b] > 0 ? path[(size_t)b * kTreeMaxDepth + acc[b] - 1] : 0) : -1;
+                mrows[b] = walking[b] && j < depth ? m_depth[j] : 0;
+                left = left || walking[b];
+                if (walking[b] && spare < 0) spare = cur[b];
+            }
+            if (!left) break;
+            for (int b = 0; b < B; ++b)
+                if (cur[b] < 0) cur[b] = spare;
+            rc = upload(c, t_cur, cur.data(), (size_t)B * 4);
+            if (!rc) rc = upload(c, t_m, mrows.data(), (size_t)B * 4);
+            if (!rc) rc = upload(c, c->off.u_fin, u_final + (size_t)j * B, (size_t)B * 4);
+            if (!rc && j < depth) rc = upload(c, c->off.u_acc, u_acc + (size_t)j * B * m_max, (size_t)B * m_max * 4);
+            if (!rc && j < depth) rc = upload(c, c->off.forced, cand + (size_t)j * B * m_max, (size_t)B * m_max * 4);
+            if (rc) return rc;
+            launch_gather_rows(c, wsp<float>(c, c->off.logit_s), wsp<int32_t>(c, t_cur), p_rows, B, c->Vs);
+            // prompts that are not walking: m_rows = 0 makes the call draw from the spare row, ignored below
+            const int m_call = j < depth ? m_max : 1;
+            rc = launch_multi_verify(p_rows, j < depth ? q_logits + (size_t)j * B * m_max * c->Vs : p_rows,
+                                     wsp<int32_t>(c, c->off.forced), wsp<float>(c, c->off.u_acc), wsp<float>(c, c->off.u_fin),
+                                     wsp<int32_t>(c, t_m), B, m_call, c->Vs, c->temperature, c->top_k, wsp<int32_t>(c, t_idx),
+                                     wsp<int32_t>(c, t_tok), nullptr, nullptr, 0, c->stream);
+            if (rc) return fail(c, rc, "launch of the verification kernel failed");
+            rc = download(c, idx.data(), t_idx, (size_t)B * 4);
+            if (!rc) rc = download(c, tok.data(), t_tok, (size_t)B * 4);
+            if (rc) return rc;
+            for (int b = 0; b < B; ++b) {
+                if (!walking[b]) continue;
+                toks[(size_t)b * (kTreeMaxDepth + 1) + acc[b]] = c->cfg.samp_lo + tok[b];
+                if (j < depth && idx[b] < m_depth[j]) {   // accepted: one depth down, to that child
+                    const int here = acc[b] > 0 ? path[(size_t)b * kTreeMaxDepth + acc[b] - 1] : 0;
+                    path[(size_t)b * kTreeMaxDepth + acc[b]] = first[j + 1] + (here - first[j]) * m_depth[j] + idx[b];
+                    ++acc[b];
+                } else {
+                    walking[b] = 0;   // rejected (the token is the draw from the updated target) or the extra token
+                }
+            }
+        }
+        rc = upload(c, t_acc, acc.data(), (size_t)B * 4);
+        if (!rc) rc = upload(c, t_path, path.data(), path.size() * 4);
+        if (!rc) rc = upload(c, t_toks, toks.data(), toks.size() * 4);
+        if (rc) return rc;
+        launch_tree_commit(c, wsp<int32_t>(c, t_acc), wsp<int32_t>(c, t_path), wsp<int32_t>(c, t_toks), n_nodes);
+        HIP_TRY(c, hipGetLastError());
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+    }
+    c->phase = 2;
+    for (int b = 0; b < B; ++b) {
+        if (out_n_accept) out_n_accept[b] = acc[b];
+        if (out_tokens)
+            for (int i = 0; i <= depth; ++i)
+                out_tokens[(size_t)b * (depth + 1) + i] = acc[b] >= 0 && i <= acc[b] ? toks[(size_t)b * (kTreeMaxDepth + 1) + i] : -1;
+    }
+    return HAWK_OK;
+}
+
 int hawk_force(hawk_ctx* c, const int32_t* n_from, const int32_t* tokens, int cnt) {
     if (!c) return HAWK_EINVAL;
     if (c->phase < 2) return fail(c, HAWK_ESTATE, "hawk_force before hawk_prefill");
@@ -734,6 +888,13 @@ int hawk_get_logits(hawk_ctx* c, float* out, int rows) {
         if (rc) return rc;
     }
     return HAWK_OK;
+}
+
+int hawk_get_tree_logits(hawk_ctx* c, float* out, int n_nodes) {
+    if (!c || !out) return HAWK_EINVAL;
+    if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
+    if (c->cfg.use_cfg || n_nodes < 1 || n_nodes > c->kmax + 1) return fail(c, HAWK_EINVAL, "n_nodes outside [1, k_max + 1]");
+    return download(c, out, c->off.logit_s, (size_t)c->B * n_nodes * c->Vs * 4);
 }
 
 int hawk_get_draft_logits(hawk_ctx* c, float* out, int k) {

@@ -73,7 +73,8 @@ template <typename T> __device__ __forceinline__ T block_max256(T v, T* red) {
 }
 
 // Row R of a pass -> sequence, row within the sequence, prompt, absolute position.
-struct RowInfo { int s, r, b, pos; bool valid; };
+// pos: position (rotary angle); slot: index of the row's entry in the cache (= pos except for tree rows).
+struct RowInfo { int s, r, b, pos, slot; bool valid; };
 __device__ __forceinline__ RowInfo row_info(const RowMap& m, int R) {
     RowInfo o;
     o.s = R / m.rows_per_seq;
@@ -85,8 +86,9 @@ __device__ __forceinline__ RowInfo row_info(const RowMap& m, int R) {
     } else {
         int ke = m.k_eff[o.b];
         o.valid = o.r <= ke;
-        o.pos = o.valid ? m.n_cond + m.n[o.b] - 1 + o.r : 0;
+        o.pos = o.valid ? m.n_cond + m.n[o.b] - 1 + (m.mode == 2 ? m.tree_depth[o.r] : o.r) : 0;
     }
+    o.slot = (m.mode == 2 && o.valid) ? m.n_cond + m.n[o.b] - 1 + o.r : o.pos;
     return o;
 }
 
@@ -237,7 +239,7 @@ __global__ void rope_append_kernel(typename Cfg::AT* QKV, typename Cfg::KT* Kc, 
     const int H = d / hd;
     auto at = [&](int e) {   // element e of the row (feature index within d)
         const int h = e / hd;
-        return ((((size_t)layer * Smax + ri.s) * H + h) * Tmax + ri.pos) * hd + (e - h * hd);
+        return ((((size_t)layer * Smax + ri.s) * H + h) * Tmax + ri.slot) * hd + (e - h * hd);
     };
     // the angles depend on the position and the pair index within a head only: one sincos per pair
     // index and row, shared by all heads through LDS (hd <= 512)
@@ -276,7 +278,8 @@ __global__ void rope_append_kernel(typename Cfg::AT* QKV, typename Cfg::KT* Kc, 
 // ------------------------------------------------------------------ attention
 
 // One workgroup per (head, row): the row attends cache entries 0..pos of its sequence
-// (its own entry included), i.e. causal inside the block of new rows.
+// (its own entry included), i.e. causal inside the block of new rows.  Tree rows: entries up to
+// the root's, then of the new entries only the row's ancestors and its own.
 template <class Cfg>
 __global__ __launch_bounds__(256) void attention_kernel(const typename Cfg::AT* QKV, const typename Cfg::KT* Kc,
                                                         const typename Cfg::KT* Vc, typename Cfg::AT* O,
@@ -294,17 +297,20 @@ __global__ __launch_bounds__(256) void attention_kernel(const typename Cfg::AT* 
     for (int i = tid; i < hd; i += 256) sq[i] = QKV[(size_t)R * 3 * d + (size_t)h * hd + i];
     __syncthreads();
     const AT scale = (AT)1 / sqrt((AT)hd);
+    const int root = ri.slot - ri.r;   // tree rows: entry of node 0
+    const unsigned long long anc = map.mode == 2 ? (map.tree_anc[ri.r] | (1ull << ri.r)) : ~0ull;
     AT mx = -INFINITY;
-    for (int t = tid; t <= ri.pos; t += 256) {
+    for (int t = tid; t <= ri.slot; t += 256) {
         AT s = 0;
         for (int i = 0; i < hd; ++i) s += sq[i] * kload(Kc, base + (size_t)t * hd + i);
         s *= scale;
+        if (map.mode == 2 && t > root && !((anc >> (t - root)) & 1ull)) s = -INFINITY;   // not on the row's path
         sc[t] = s;
         mx = s > mx ? s : mx;
     }
     mx = block_max256(mx, red);
     AT den = 0;
-    for (int t = tid; t <= ri.pos; t += 256) {
+    for (int t = tid; t <= ri.slot; t += 256) {
         AT e = exp(sc[t] - mx);
         sc[t] = e;
         den += e;
@@ -312,7 +318,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const typename Cfg::AT* 
     den = block_sum256(den, red);  // also orders the sc[] writes before the reads below
     const int i = tid % hd, sl = tid / hd, nsl = 256 / hd;
     AT acc = 0;
-    for (int t = sl; t <= ri.pos; t += nsl) acc += sc[t] * kload(Vc, base + (size_t)t * hd + i);
+    for (int t = sl; t <= ri.slot; t += nsl) acc += sc[t] * kload(Vc, base + (size_t)t * hd + i);
     part[tid] = acc;
     __syncthreads();
     if (tid < hd) {

@@ -43,17 +43,23 @@ struct DraftMode {
 
 // How the rows of a forward pass map to sequences and positions.
 struct RowMap {
-    int32_t mode;          // 0 = prefill (row r of sequence s at position r), 1 = step rows
-    int32_t rows_per_seq;  // C in prefill, k+1 in a step
+    int32_t mode;          // 0 = prefill (row r of sequence s at position r), 1 = step rows, 2 = tree rows
+    int32_t rows_per_seq;  // C in prefill, k+1 in a step, nodes of the candidate tree
     int32_t n_seq, batch, n_cond;
     const int32_t* n;      // [B] committed tokens (step rows)
     const int32_t* k_eff;  // [B] drafts in flight, -1 = finished (step rows)
+    // tree rows: row r is node r of the candidate tree (node 0 = the last committed token); its
+    // position is that of the root plus its depth, its cache entry the root's plus r, and it attends
+    // the committed entries, its ancestors (bit j of tree_anc[r]: node j) and itself
+    const int32_t* tree_depth;            // [nodes]
+    const unsigned long long* tree_anc;   // [nodes]
 };
 
 struct Offsets {  // byte offsets into the workspace
     size_t blob, kc, vc, n, k_eff, step, done, counters, grid, draft, forced, hprev, qstat, pstat;
     size_t x, a, qkv, o, u, din, g0, g1, ga, logit_s, logit_b, dlogit_s, dlogit_b;
     size_t u_draft, u_acc, u_fin, out_na, out_tok, inv_freq, replay, cond;
+    size_t tree;    // candidate tree of a tree pass: int32 depth[64], then uint64 ancestors[64], then walk state
     size_t split;   // bf16 hi / lo planes of a GEMM input (batched shapes; 0: not present)
     size_t split2;  // second pair of planes: written by a GEMM's own epilogue while it reads the first
     size_t gpack;   // tile-major copy of the GEMM weights for the MFMA GEMM / GEMV kernels (0: not present)
@@ -183,6 +189,15 @@ int launch_multi_verify(const float* p_logits, const float* q_logits, const int3
 size_t multi_verify_workspace_bytes(int rows, int m);
 int launch_sample_rows(const float* logits, const int32_t* skip, const float* u, int rows, int n, float temperature,
                        int top_k, int32_t* out_token, hipStream_t stream);
+
+// ---- tree verification, implemented in tree.hip ----
+constexpr int kTreeMaxDepth = 8;    // depths of a candidate tree
+constexpr int kTreeMaxNodes = 64;   // nodes, the root included (one bit each in a row's ancestor mask)
+void launch_gather_rows(hawk_ctx*, const float* src, const int32_t* index, float* dst, int rows, int n);
+// moves the accepted paths' cache entries into place, then commits tokens, n and the kept hidden state;
+// acc [B] (-1: prompt not part of the pass), path [B][kTreeMaxDepth] node of the accepted candidate
+// per depth, toks [B][kTreeMaxDepth + 1] vocabulary ids: device arrays
+void launch_tree_commit(hawk_ctx*, const int32_t* acc, const int32_t* path, const int32_t* toks, int n_nodes);
 
 // ---- spatial drafting structures, implemented in spatial.hip (no context; HAWK_* codes) ----
 size_t spatial_heads_workspace_bytes(int rows, int n_heads, int d);

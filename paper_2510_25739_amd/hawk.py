@@ -71,6 +71,9 @@ EXPORTS = {
     "hawk_set_path": (C.c_int, [C.c_void_p, C.c_int]),
     "hawk_last_path": (C.c_int, [C.c_void_p]),
     "hawk_phase_trace": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t]),
+    "hawk_verify_tree": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                   C.c_void_p, C.c_void_p]),
+    "hawk_get_tree_logits": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int]),
     "hawk_multi_verify_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int]),
     "hawk_multi_verify": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                     C.c_int, C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -367,6 +370,29 @@ class Hawk:
         toks = np.zeros((self.batch, k + 1), dtype=np.int32) if want else None
         self._chk(self._L.hawk_verify(self._h, k, _p(ua), _p(_f32(u_final)), _p(na), _p(toks)), "hawk_verify")
         return na, toks
+
+    def verify_tree(self, m_depth, cand, q_logits, u_acc, u_final):
+        """hawk_verify_tree: m_depth [D]; cand [D, batch, m_max] int32 (host); q_logits a device fp32
+        tensor [D, batch, m_max, V_s]; u_acc [D, batch, m_max], u_final [D + 1, batch] (host).
+        Returns (accepted [batch], tokens [batch, D + 1])."""
+        md = _i32(m_depth)
+        D, m_max = len(md), int(md.max())
+        cand, ua, uf = _i32(cand), _f32(u_acc), _f32(u_final)
+        if cand.shape != (D, self.batch, m_max) or ua.shape != cand.shape or uf.shape != (D + 1, self.batch):
+            raise HawkError(-1, "hawk_verify_tree", "host arrays do not have the documented shapes")
+        if not (q_logits.is_cuda and q_logits.is_contiguous() and q_logits.dtype == self._torch.float32
+                and tuple(q_logits.shape) == (D, self.batch, m_max, self.v_s)):
+            raise HawkError(-1, "hawk_verify_tree", "q_logits must be a contiguous device fp32 tensor [D, batch, m_max, V_s]")
+        na = np.zeros(self.batch, dtype=np.int32)
+        toks = np.zeros((self.batch, D + 1), dtype=np.int32)
+        self._chk(self._L.hawk_verify_tree(self._h, D, _p(md), _p(cand), C.c_void_p(q_logits.data_ptr()), _p(ua), _p(uf),
+                                           _p(na), _p(toks)), "hawk_verify_tree")
+        return na, toks
+
+    def tree_logits(self, n_nodes):
+        out = np.zeros((self.batch, n_nodes, self.v_s), dtype=np.float32)
+        self._chk(self._L.hawk_get_tree_logits(self._h, _p(out), n_nodes), "hawk_get_tree_logits")
+        return out
 
     def generate(self, cond, uncond, grid_h, grid_w, k, temperature, top_k, cfg_scale, seed, replay=None):
         cond = _f32(cond)

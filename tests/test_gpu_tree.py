@@ -1,0 +1,241 @@
+"""GPU parity of tree verification (Method, "Spatial Sampling Pool": the candidate tree;
+"Sampling and Verification": the walk) against the oracle: the rows of the target pass over the
+tree against the model fed path by path, the walk's result, and - through the steps that follow -
+the cache entries and the hidden state the call leaves behind.
+
+fp32 configuration: everything exact.  bf16: node logits within 2e-2, the walk exact on the GPU's
+own logits, and the ordinary step after the tree step within 2e-2 of the oracle's (which only holds
+if the accepted path's keys and values were moved to the right entries).
+
+Inputs are seeded and synthetic: the proposals of depth j are the target's logits after the first
+candidates of the depths before (from the oracle) plus noise of half the logits' standard deviation
+- drafts that are right fairly often -, candidates drawn from them by inverse CDF, uniforms on the 2^-24 grid.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from oracle import tree
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    import torch
+    import paper_2510_25739_amd as H
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return H
+
+
+def uni(rng, *shp):
+    return (rng.integers(0, 1 << 24, size=shp).astype(np.float32) / np.float32(1 << 24)).astype(np.float32)
+
+
+def build_pools(orc, E, s, n, grid, m_depth, rng, T, K, sigma=0.5):
+    """Proposals and candidates for every prompt: cand [D, B, m_max], q [D, B, m_max, V_s]."""
+    B, D, m_max = len(n), len(m_depth), max(m_depth)
+    cand = np.zeros((D, B, m_max), dtype=np.int32)
+    q = np.zeros((D, B, m_max, s.v_s), dtype=np.float32)
+    for b in range(B):
+        base = s.n_cond + int(n[b]) - 1
+        toks = [int(grid[b, n[b] - 1])]
+        for j in range(D):
+            lg = None
+            for r, t in enumerate(toks):
+                _, lg = orc.forward_row(b, base + r, E[t], want_logits=(r == len(toks) - 1))
+            noise = rng.standard_normal((m_depth[j], s.v_s)).astype(np.float32) * np.float32(sigma * lg.std())
+            q[j, b, :m_depth[j]] = lg[None, :] + noise
+            for i in range(m_depth[j]):
+                w, z = oracle.warp(q[j, b, i], T, K)
+                cand[j, b, i] = oracle.inv_cdf(w, z, float(uni(rng, 1)[0]))
+            toks.append(s.samp_lo + int(cand[j, b, 0]))
+    return cand, q
+
+
+def n_nodes_of(m_depth):
+    return len(tree.tree_nodes(m_depth))
+
+
+def same_committed(hk, orc):
+    """Committed tokens agree (entries beyond n are whatever the workspace held)."""
+    n = orc.n()
+    np.testing.assert_array_equal(hk.n(), n)
+    g, o = hk.grid(), orc.grid()
+    for b in range(len(n)):
+        np.testing.assert_array_equal(g[b, :n[b]], o[b, :n[b]])
+
+
+def tree_step(H, hk, orc, E, s, m_depth, rng, T, K):
+    """One tree step on both sides from the same committed state; returns what was compared."""
+    import torch
+    B, D = hk.batch, len(m_depth)
+    n, grid = orc.n().copy(), orc.grid()
+    cand, q = build_pools(orc, E, s, n, grid, m_depth, rng, T, K)
+    u_acc, u_fin = uni(rng, D, B, max(m_depth)), uni(rng, D + 1, B)
+    na, toks = hk.verify_tree(m_depth, cand, torch.from_numpy(q).to("cuda:0"), u_acc, u_fin)
+    nn = n_nodes_of(m_depth)
+    lg_g = hk.tree_logits(nn)
+    out = dict(err=0.0, acc=[], same=True)
+    for b in range(B):
+        cb = [[int(c) for c in cand[j, b, :m_depth[j]]] for j in range(D)]
+        lg_o = tree.tree_logits(orc, E, b, s.n_cond + int(n[b]) - 1, int(grid[b, n[b] - 1]),
+                                [[s.samp_lo + c for c in row] for row in cb], m_depth)
+        out["err"] = max(out["err"], float(np.abs(lg_g[b].astype(np.float64) - lg_o).max()))
+        args = (m_depth, [q[j, b] for j in range(D)], cb, [u_acc[j, b] for j in range(D)], u_fin[:, b], T, K)
+        # the walk on the GPU's own rows must give the GPU's result exactly
+        a_s, t_s, _ = tree.tree_walk(lg_g[b], *args)
+        assert na[b] == a_s and list(toks[b, :a_s + 1]) == [s.samp_lo + t for t in t_s], (na[b], toks[b], a_s, t_s)
+        assert (toks[b, a_s + 1:] == -1).all()
+        a_o, t_o, _ = tree.tree_walk(lg_o, *args)
+        out["same"] = out["same"] and (a_o == a_s and t_o == t_s)
+        out["acc"].append(int(na[b]))
+    out["n"], out["toks"], out["n_before"] = hk.n(), toks, n
+    return out
+
+
+def chain_step(hk, orc, s, k, rng, exact):
+    """An ordinary draft + verify step on both sides; returns the largest logit error."""
+    B = hk.batch
+    ud, ua, uf = uni(rng, B, k), uni(rng, B, k), uni(rng, B)
+    d_o, d_g = orc.draft(k, ud), hk.draft(k, ud)
+    if exact:
+        np.testing.assert_array_equal(d_g, d_o)
+    elif not np.array_equal(d_g, d_o):   # a draft that differs changes the inputs of the ones after it: same drafts first
+        hk.draft_forced(k, np.where(d_o >= 0, d_o, s.samp_lo).astype(np.int32), False)
+    err = float(np.abs(hk.draft_logits(k) - orc.draft_logits()).max())
+    na_g, t_g = hk.verify(k, ua, uf)
+    na_o, t_o = orc.verify(k, ua, uf)
+    err = max(err, float(np.abs(hk.logits(k + 1) - orc.logits()).max()))
+    if exact:
+        np.testing.assert_array_equal(na_g, na_o)
+        np.testing.assert_array_equal(t_g, t_o)
+    elif not (np.array_equal(na_g, na_o) and np.array_equal(t_g, t_o)):
+        n0 = orc.n() - (na_o + 1)
+        hk.force(n0, np.stack([t_o[b, :na_o[b] + 1] for b in range(B)]))
+    return err
+
+
+def start(H, s, k_max, batch=1):
+    blob = synth.make_weights(s, seed=0)
+    hk = H.Hawk(H.HawkConfig.from_shape(s, batch=batch, k_max=k_max))
+    hk.load(blob)
+    orc = oracle.Oracle.from_shape(s, blob, batch=batch, k_max=k_max)
+    cond = synth.make_cond(s, seed=2, batch=batch)
+    u0 = synth.make_uniforms(9, (batch,))
+    hk.prefill(cond, None, s.grid_h, s.grid_w, s.temperature, s.top_k, 1.0, u0)
+    orc.prefill(cond, None, s.temperature, s.top_k, 1.0, u0)
+    E = synth.blob_tensor(s, blob, "E").astype(np.float64)
+    return hk, orc, E
+
+
+@pytest.mark.parametrize("m_depth", [(3, 3), (2, 2, 2), (4,), (1, 1, 1, 1), (2, 3, 1)])
+def test_tree_steps_fp32_exact(H, m_depth):
+    s = synth.CONFIGS[0].replace(top_k=64)   # top-k 64 of 4096: drafts get accepted often enough to walk deep
+    hk, orc, E = start(H, s, k_max=14)
+    np.testing.assert_array_equal(hk.grid()[:, 0], orc.grid()[:, 0])
+    rng = np.random.Generator(np.random.PCG64(sum(m_depth) * 7 + len(m_depth)))
+    nn, accs, moved = n_nodes_of(m_depth), [], 0
+    while orc.n()[0] + nn <= s.n_img:
+        r = tree_step(H, hk, orc, E, s, m_depth, rng, s.temperature, s.top_k)
+        assert r["err"] < 1e-4 and r["same"]
+        a = r["acc"][0]
+        accs.append(a)
+        # the oracle commits the same tokens the plain way: fed one after the other
+        orc.force(r["n_before"], r["toks"][:, :a + 1])
+        np.testing.assert_array_equal(hk.n(), orc.n())
+        same_committed(hk, orc)
+        # an ordinary step from the state the tree step left: exact only if the cache entries of the
+        # accepted path and the kept hidden state are the right ones
+        if orc.n()[0] + s.k + 1 <= s.n_img:
+            chain_step(hk, orc, s, s.k, rng, exact=True)
+    print("accepted per tree step:", accs)
+    assert max(accs) >= min(2, len(m_depth)) and min(accs) == 0
+
+
+def test_tree_step_two_prompts_fp32(H):
+    s = synth.CONFIGS[0].replace(top_k=64)
+    hk, orc, E = start(H, s, k_max=12, batch=2)
+    rng = np.random.Generator(np.random.PCG64(21))
+    chain_step(hk, orc, s, s.k, rng, exact=True)   # the prompts stand at different positions afterwards
+    seen = set()
+    for _ in range(4):
+        r = tree_step(H, hk, orc, E, s, (3, 3), rng, s.temperature, s.top_k)
+        assert r["err"] < 1e-4 and r["same"]
+        seen.update(r["acc"])
+        # prompts accept different numbers of candidates and the oracle's forced call takes one count:
+        # the shorter ones start further back and feed tokens that are committed already
+        n0, g0 = r["n_before"], orc.grid()
+        cnt = max(r["acc"]) + 1
+        rows, begin = [], []
+        for bb in range(2):
+            own = list(r["toks"][bb, :r["acc"][bb] + 1])
+            pad = cnt - len(own)
+            begin.append(n0[bb] - pad)
+            rows.append(list(g0[bb, n0[bb] - pad:n0[bb]]) + own)
+        assert min(begin) >= 1
+        orc.force(np.array(begin, dtype=np.int32), np.array(rows, dtype=np.int32))
+        np.testing.assert_array_equal(hk.n(), orc.n())
+        same_committed(hk, orc)
+        chain_step(hk, orc, s, s.k, rng, exact=True)
+    assert len(seen) > 1
+
+
+def test_tree_steps_bf16(H):
+    # the XL shape at four layers: node logits within tolerance, the walk exact on the GPU's own rows,
+    # and the ordinary steps in between stay within tolerance (keys and values of the accepted path in place)
+    s = synth.CONFIGS[2].replace(n_layers=4)
+    hk, orc, E = start(H, s, k_max=12)
+    if hk.grid()[0, 0] != orc.grid()[0, 0]:
+        pytest.skip("token 0 differs in bf16 for this seed")
+    rng = np.random.Generator(np.random.PCG64(4))
+    worst, accs, agree = 0.0, [], 0
+    for step in range(6):
+        r = tree_step(H, hk, orc, E, s, (3, 3), rng, s.temperature, s.top_k)
+        worst = max(worst, r["err"])
+        agree += int(r["same"])
+        a = r["acc"][0]
+        accs.append(a)
+        orc.force(r["n_before"], r["toks"][:, :a + 1])   # the oracle follows the GPU's tokens
+        same_committed(hk, orc)
+        ce = chain_step(hk, orc, s, s.k, rng, exact=False)
+        print(f"step {step}: tree rows {r['err']:.2e}, accepted {a}, ordinary step after it {ce:.2e}")
+        worst = max(worst, ce)
+    print(f"max-abs logit error {worst:.2e}, accepted {accs}, walks identical to the oracle's {agree}/6")
+    assert worst < 2e-2
+    assert max(accs) >= 1
+
+
+def test_tree_rejects_what_it_cannot_run(H):
+    s = synth.CONFIGS[0]
+    hk, orc, E = start(H, s, k_max=6)
+    import torch
+    def call(m_depth):
+        D, m = len(m_depth), max(m_depth)
+        q = torch.zeros((D, 1, m, s.v_s), device="cuda:0")
+        return hk.verify_tree(m_depth, np.zeros((D, 1, m), np.int32), q, np.zeros((D, 1, m), np.float32),
+                              np.zeros((D + 1, 1), np.float32))
+    with pytest.raises(H.HawkError):
+        call((3, 3))          # 13 nodes, the context has room for 7 rows
+    with pytest.raises(H.HawkError):
+        call((1,) * 9)        # deeper than 8
+    na, toks = call((2, 2))   # 7 nodes: fits
+    assert na[0] >= 0
+    # near the end of the image the tree no longer fits
+    rng = np.random.Generator(np.random.PCG64(3))
+    while hk.n()[0] + 7 <= s.n_img:
+        hk.draft(s.k, uni(rng, 1, s.k))
+        hk.verify(s.k, uni(rng, 1, s.k), uni(rng, 1))
+    if hk.n()[0] < s.n_img:
+        with pytest.raises(H.HawkError):
+            call((2, 2))
+    s4 = synth.CONFIGS[0].replace(cfg_scale=2.0)
+    blob = synth.make_weights(s4, seed=0)
+    hg = H.Hawk(H.HawkConfig.from_shape(s4, k_max=6))
+    hg.load(blob)
+    cond, unc = synth.make_cond(s4, seed=2), synth.make_cond(s4, seed=3)
+    hg.prefill(cond, unc, s4.grid_h, s4.grid_w, 1.0, s4.top_k, 2.0, synth.make_uniforms(1, (1,)))
+    with pytest.raises(H.HawkError):
+        hg.verify_tree((2,), np.zeros((1, 1, 2), np.int32), torch.zeros((1, 1, 2, s4.v_s), device="cuda:0"),
+                       np.zeros((1, 1, 2), np.float32), np.zeros((2, 1), np.float32))
