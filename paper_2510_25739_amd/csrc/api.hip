@@ -648,7 +648,8 @@ int hawk_verify_tree(hawk_ctx* c, int depth, const int32_t* m_depth, const int32
             rc = launch_multi_verify(p_rows, j < depth ? q_logits + (size_t)j * B * m_max * c->Vs : p_rows,
                                      wsp<int32_t>(c, c->off.forced), wsp<float>(c, c->off.u_acc), wsp<float>(c, c->off.u_fin),
                                      wsp<int32_t>(c, t_m), B, m_call, c->Vs, c->temperature, c->top_k, wsp<int32_t>(c, t_idx),
-                                     wsp<int32_t>(c, t_tok), nullptr, nullptr, 0, c->stream);
+                                     wsp<int32_t>(c, t_tok), nullptr, wsp<void>(c, c->off.qstat),
+                                     2 * (size_t)B * ks * sizeof(WarpStat), c->stream);
             if (rc) return fail(c, rc, "launch of the verification kernel failed");
             rc = download(c, idx.data(), t_idx, (size_t)B * 4);
             if (!rc) rc = download(c, tok.data(), t_tok, (size_t)B * 4);

@@ -283,7 +283,8 @@ __global__ void rope_append_kernel(typename Cfg::AT* QKV, typename Cfg::KT* Kc, 
 template <class Cfg>
 __global__ __launch_bounds__(256) void attention_kernel(const typename Cfg::AT* QKV, const typename Cfg::KT* Kc,
                                                         const typename Cfg::KT* Vc, typename Cfg::AT* O,
-                                                        RowMap map, int layer, int d, int hd, int Smax, int Tmax) {
+                                                        RowMap map, int layer, int d, int hd, int Smax, int Tmax,
+                                                        uint16_t* hi, uint16_t* lo) {
     using AT = typename Cfg::AT;
     extern __shared__ double smem_raw[];
     AT* sc = reinterpret_cast<AT*>(smem_raw);  // [Tmax] scores, then [hd] q, then [256] partials
@@ -324,7 +325,14 @@ __global__ __launch_bounds__(256) void attention_kernel(const typename Cfg::AT* 
     if (tid < hd) {
         AT o = 0;
         for (int s2 = 0; s2 < nsl; ++s2) o += part[s2 * hd + tid];
-        O[(size_t)R * d + (size_t)h * hd + tid] = o / den;
+        o /= den;
+        O[(size_t)R * d + (size_t)h * hd + tid] = o;
+        if (hi) {   // the bf16 planes the projection that follows reads
+            unsigned a, b;
+            bf16_split((float)o, a, b);
+            hi[(size_t)R * d + (size_t)h * hd + tid] = (uint16_t)a;
+            lo[(size_t)R * d + (size_t)h * hd + tid] = (uint16_t)b;
+        }
     }
 }
 
@@ -696,11 +704,13 @@ void launch_attention(hawk_ctx* c, const RowMap& map, int layer, int M) {
         }
     }
     dim3 grid(c->H, M);
+    uint16_t *hi = nullptr, *lo = nullptr;
+    if (map.mode == 2) presplit_planes(c, c->off.o, M, c->d, &hi, &lo);   // tree rows: the Wo product reads the result next
     DISPATCH(c, (attention_kernel<Cfg><<<grid, 256, (size_t)(c->Tmax + c->hd + 256) * sizeof(typename Cfg::AT),
                                          c->stream>>>(
                     wsp<typename Cfg::AT>(c, c->off.qkv), wsp<typename Cfg::KT>(c, c->off.kc),
                     wsp<typename Cfg::KT>(c, c->off.vc), wsp<typename Cfg::AT>(c, c->off.o), map, layer, c->d, c->hd,
-                    c->Smax, c->Tmax)));
+                    c->Smax, c->Tmax, hi, lo)));
 }
 
 void launch_swiglu(hawk_ctx* c, int M) {
