@@ -226,6 +226,46 @@ def test_tree_step_full_depth_bf16(H):
     assert worst < 2e-2
 
 
+@pytest.mark.parametrize("cfg,m_depth", [(0, (2, 2)), (0, (3, 2, 1)), (1, (3, 3))])
+def test_greedy_tree_decoding_is_plain_greedy_decoding(H, cfg, m_depth):
+    # whole images: with temperature 0 the tokens must be those of token-by-token arg-max decoding,
+    # whatever the candidates are (some are planted from the reference so that the walk goes deep,
+    # the others are random); the image's last positions, where the tree no longer fits, are ordinary steps
+    import torch
+    s = synth.CONFIGS[cfg]
+    blob = synth.make_weights(s, seed=0)
+    cond = synth.make_cond(s, seed=2, batch=1)
+    nn = n_nodes_of(m_depth)
+    hk = H.Hawk(H.HawkConfig.from_shape(s, batch=1, k_max=max(nn - 1, s.k)))
+    hk.load(blob)
+    ref, _ = hk.generate(cond, None, s.grid_h, s.grid_w, 0, 0.0, s.top_k, 1.0, 1)
+    hk.prefill(cond, None, s.grid_h, s.grid_w, 0.0, s.top_k, 1.0, np.array([0.5], np.float32))
+    rng = np.random.Generator(np.random.PCG64(cfg + 40))
+    D, m_max = len(m_depth), max(m_depth)
+    accs = []
+    while hk.n()[0] < s.n_img:
+        n = int(hk.n()[0])
+        if n + nn > s.n_img:
+            hk.draft(1, uni(rng, 1, 1))
+            hk.verify(1, uni(rng, 1, 1), uni(rng, 1))
+            continue
+        cand = rng.integers(0, s.v_s, size=(D, 1, m_max)).astype(np.int32)
+        for j in range(D):
+            if rng.random() < 0.8:
+                cand[j, 0, int(rng.integers(0, m_depth[j]))] = ref[0, n + j] - s.samp_lo
+        q = torch.zeros((D, 1, m_max, s.v_s), device="cuda:0")
+        q.scatter_(3, torch.from_numpy(cand.astype(np.int64)).to("cuda:0")[..., None], 50.0)   # point masses on the candidates
+        na, toks = hk.verify_tree(m_depth, cand, q, uni(rng, D, 1, m_max), uni(rng, D + 1, 1))
+        accs.append(int(na[0]))
+        expect = 0
+        while expect < D and ref[0, n + expect] - s.samp_lo in cand[expect, 0, :m_depth[expect]]:
+            expect += 1
+        assert na[0] == expect
+    np.testing.assert_array_equal(hk.grid(), ref)
+    print("accepted per tree step, histogram:", np.bincount(accs, minlength=D + 1))
+    assert max(accs) == D
+
+
 def test_tree_rejects_what_it_cannot_run(H):
     s = synth.CONFIGS[0]
     hk, orc, E = start(H, s, k_max=6)
