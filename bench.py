@@ -187,7 +187,7 @@ def main():
     out["multi_verify"] = bench_multi_verify(H, s)
     from paper_2510_25739_amd.spatial_timing import bench_spatial_draft
     out["spatial_draft"] = bench_spatial_draft(H, s)
-    if not s.use_cfg:   # tree verification does not cover guidance
+    if not s.use_cfg:   # timed without guidance (one prompt)
         from paper_2510_25739_amd.tree_timing import bench_tree
         out["tree_verify"] = bench_tree(H, s, blob, cond)
     if not args.no_cpu:

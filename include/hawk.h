@@ -234,9 +234,10 @@ int hawk_phase_trace(hawk_ctx* ctx, int enable, uint64_t* out, size_t n_words);
  * the hidden state for the next draft are committed as by hawk_verify.
  * out_n_accept (host, may be NULL) [batch]: candidates accepted (-1: prompt finished before the
  * call); out_tokens (host, may be NULL) [batch][D + 1]: the accepted + 1 tokens emitted (vocabulary
- * ids), -1 beyond.  Runs one kernel per operation (not the persistent kernel); classifier-free
- * guidance is not covered (HAWK_EINVAL).  Synchronises the stream several times (the walk is driven
- * from the host).  hawk_get_tree_logits: the rows of the last tree pass, out (host)
+ * ids), -1 beyond.  Runs one kernel per operation (not the persistent kernel).  With classifier-free
+ * guidance both streams of a prompt go through the pass with the same tree and every target row
+ * is the guided combination, as in hawk_verify.  Synchronises the stream several times (the walk is
+ * driven from the host).  hawk_get_tree_logits: the (guided) rows of the last tree pass, out (host)
  * [batch][n_nodes][V_s]. */
 int hawk_verify_tree(hawk_ctx* ctx, int depth, const int32_t* m_depth, const int32_t* cand, const float* q_logits,
                      const float* u_acc, const float* u_final, int32_t* out_n_accept, int32_t* out_tokens);

@@ -63,6 +63,7 @@ def lib() -> C.CDLL:
             "orc_multi_verify": (i32, [i32, i32, vp, vp, vp, f32, i32, vp, f32, vp, vp]),
             "orc_forward_row": (i32, [vp, i32, i32, vp, vp]),
             "orc_draft_head": (i32, [vp, vp, i32, i32, vp, vp]),
+            "orc_guide": (None, [vp, vp, f32, i32, vp]),
             "orc_margins": (None, [vp, i32]),
             "orc_num_threads": (i32, []),
         }
@@ -141,6 +142,14 @@ def multi_verify(p_logits, q_logits, cand, u_acc, u_final: float, temperature: f
     a = lib().orc_multi_verify(m, n, _p(p), _p(q), _p(c), temperature, n if top_k is None else top_k, _p(ua),
                                u_final, _p(tok), _p(resid))
     return (int(a), int(tok[0]), resid) if want_resid else (int(a), int(tok[0]))
+
+
+def guide(lc, lu, scale: float) -> np.ndarray:
+    """Guided logits lu + scale * (lc - lu), by the oracle's own routine."""
+    lc, lu = _f32(lc), _f32(lu)
+    out = np.zeros_like(lc)
+    lib().orc_guide(_p(lc), _p(lu), scale, lc.size, _p(out))
+    return out
 
 
 def num_threads() -> int:

@@ -124,6 +124,8 @@ static void guide(const float* lc, const float* lu, float s, int n, float* out) 
     for (int j = 0; j < n; ++j) out[j] = fmaf(s, lc[j] - lu[j], lu[j]);
 }
 
+void orc_guide(const float* lc, const float* lu, float scale, int n, float* out) { guide(lc, lu, scale, n, out); }
+
 /* ------------------------------------------------------------ uniform source */
 
 static inline uint64_t mix64(uint64_t z) {

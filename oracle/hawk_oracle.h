@@ -95,6 +95,9 @@ int orc_multi_verify(int m, int n, const float* p_logits, const float* q_logits,
 /* One target row: x (d values: in = input embedding, out = hidden before the final
  * norm) at absolute position pos of sequence seq; appends K,V; logits may be NULL. */
 int orc_forward_row(orc_state*, int seq, int pos, double* x, float* logits);
+/* Classifier-free guidance on logit rows, as every guided row of the oracle is formed:
+ * out = lu + scale * (lc - lu). */
+void orc_guide(const float* lc, const float* lu, float scale, int n, float* out);
 int orc_draft_head(const orc_state*, const double* g_prev, int left, int up, double* g_out,
                    float* logits);
 

@@ -28,17 +28,23 @@ def tree_nodes(m_depth: Sequence[int]) -> List[Tuple[int, ...]]:
 
 
 def tree_logits(orc: "oracle.Oracle", E: np.ndarray, seq: int, base_pos: int, root_token: int,
-                cand: Sequence[Sequence[int]], m_depth: Sequence[int]) -> np.ndarray:
+                cand: Sequence[Sequence[int]], m_depth: Sequence[int], uncond_seq: int = -1,
+                cfg_scale: float = 1.0) -> np.ndarray:
     """Target logits after every node: the root's row (the last committed token, at absolute
     position base_pos) and then the node's candidates, one row each at the following positions, fed
-    through the model one after the other.  E: the embedding table [V, d].  Returns [nodes, V_s]."""
+    through the model one after the other.  E: the embedding table [V, d].  With guidance
+    (uncond_seq >= 0) the same rows go through the unconditional sequence as well and the two are
+    combined as everywhere else (Experiment, "Model and Benchmark").  Returns [nodes, V_s]."""
     out = []
     for path in tree_nodes(m_depth):
         toks = [root_token] + [cand[j][i] for j, i in enumerate(path)]
-        lg = None
+        lg = lu = None
         for r, t in enumerate(toks):
-            _, lg = orc.forward_row(seq, base_pos + r, E[t], want_logits=(r == len(toks) - 1))
-        out.append(lg)
+            last = r == len(toks) - 1
+            _, lg = orc.forward_row(seq, base_pos + r, E[t], want_logits=last)
+            if uncond_seq >= 0:
+                _, lu = orc.forward_row(uncond_seq, base_pos + r, E[t], want_logits=last)
+        out.append(oracle.guide(lg, lu, cfg_scale) if uncond_seq >= 0 else lg)
     return np.stack(out)
 
 

@@ -537,7 +537,6 @@ int hawk_verify_tree(hawk_ctx* c, int depth, const int32_t* m_depth, const int32
                      const float* u_acc, const float* u_final, int32_t* out_n_accept, int32_t* out_tokens) {
     if (!c) return HAWK_EINVAL;
     if (c->phase < 2) return fail(c, HAWK_ESTATE, "hawk_verify_tree before hawk_prefill");
-    if (c->cfg.use_cfg) return fail(c, HAWK_EINVAL, "hawk_verify_tree does not cover classifier-free guidance");
     if (!m_depth || !cand || !q_logits || !u_acc || !u_final) return fail(c, HAWK_EINVAL, "null input");
     if (depth < 1 || depth > kTreeMaxDepth) return fail(c, HAWK_EINVAL, "depth = %d outside [1, %d]", depth, kTreeMaxDepth);
     const int B = c->B;
@@ -642,7 +641,8 @@ int hawk_verify_tree(hawk_ctx* c, int depth, const int32_t* m_depth, const int32
             if (!rc && j < depth) rc = upload(c, c->off.u_acc, u_acc + (size_t)j * B * m_max, (size_t)B * m_max * 4);
             if (!rc && j < depth) rc = upload(c, c->off.forced, cand + (size_t)j * B * m_max, (size_t)B * m_max * 4);
             if (rc) return rc;
-            launch_gather_rows(c, wsp<float>(c, c->off.logit_s), wsp<int32_t>(c, t_cur), p_rows, B, c->Vs);
+            launch_gather_rows(c, wsp<float>(c, c->off.logit_s), wsp<int32_t>(c, t_cur), p_rows, B, c->Vs,
+                               c->cfg.use_cfg ? B * n_nodes : 0);
             // prompts that are not walking: m_rows = 0 makes the call draw from the spare row, ignored below
             const int m_call = j < depth ? m_max : 1;
             rc = launch_multi_verify(p_rows, j < depth ? q_logits + (size_t)j * B * m_max * c->Vs : p_rows,
@@ -894,8 +894,17 @@ int hawk_get_logits(hawk_ctx* c, float* out, int rows) {
 int hawk_get_tree_logits(hawk_ctx* c, float* out, int n_nodes) {
     if (!c || !out) return HAWK_EINVAL;
     if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
-    if (c->cfg.use_cfg || n_nodes < 1 || n_nodes > c->kmax + 1) return fail(c, HAWK_EINVAL, "n_nodes outside [1, k_max + 1]");
-    return download(c, out, c->off.logit_s, (size_t)c->B * n_nodes * c->Vs * 4);
+    if (n_nodes < 1 || n_nodes > c->kmax + 1) return fail(c, HAWK_EINVAL, "n_nodes outside [1, k_max + 1]");
+    if (!c->cfg.use_cfg) return download(c, out, c->off.logit_s, (size_t)c->B * n_nodes * c->Vs * 4);
+    // guided rows of all nodes, formed like the rows the walk used
+    std::vector<int32_t> all((size_t)c->B * n_nodes);
+    for (size_t i = 0; i < all.size(); ++i) all[i] = (int32_t)i;
+    int rc = upload(c, c->off.forced, all.data(), all.size() * 4);
+    if (rc) return rc;
+    launch_gather_rows(c, wsp<float>(c, c->off.logit_s), wsp<int32_t>(c, c->off.forced), wsp<float>(c, c->off.logit_b),
+                       c->B * n_nodes, c->Vs, c->B * n_nodes);
+    HIP_TRY(c, hipGetLastError());
+    return download(c, out, c->off.logit_b, (size_t)c->B * n_nodes * c->Vs * 4);
 }
 
 int hawk_get_draft_logits(hawk_ctx* c, float* out, int k) {

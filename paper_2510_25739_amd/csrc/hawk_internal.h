@@ -193,7 +193,8 @@ int launch_sample_rows(const float* logits, const int32_t* skip, const float* u,
 // ---- tree verification, implemented in tree.hip ----
 constexpr int kTreeMaxDepth = 8;    // depths of a candidate tree
 constexpr int kTreeMaxNodes = 64;   // nodes, the root included (one bit each in a row's ancestor mask)
-void launch_gather_rows(hawk_ctx*, const float* src, const int32_t* index, float* dst, int rows, int n);
+// dst[r] = src[index[r]] (rows of n floats); uncond_shift > 0: guided with the row that many rows further on
+void launch_gather_rows(hawk_ctx*, const float* src, const int32_t* index, float* dst, int rows, int n, int uncond_shift);
 // moves the accepted paths' cache entries into place, then commits tokens, n and the kept hidden state;
 // acc [B] (-1: prompt not part of the pass), path [B][kTreeMaxDepth] node of the accepted candidate
 // per depth, toks [B][kTreeMaxDepth + 1] vocabulary ids: device arrays

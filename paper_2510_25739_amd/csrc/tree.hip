@@ -9,13 +9,17 @@ namespace hawk {
 
 namespace {
 
-// dst[r][0..n) = src[index[r]][0..n); rows with a negative index are left alone.
-__global__ __launch_bounds__(256) void gather_rows_kernel(const float* src, const int32_t* index, float* dst, int n) {
+// dst[r][0..n) = src[index[r]][0..n); rows with a negative index are left alone.  With guidance
+// (uncond_shift > 0: the unconditional stream's row lies that many rows further on) the row is the
+// guided combination lu + scale (lc - lu), formed as in the sampling kernels.
+__global__ __launch_bounds__(256) void gather_rows_kernel(const float* src, const int32_t* index, float* dst, int n,
+                                                          int uncond_shift, float scale) {
     const int r = blockIdx.x, i = index[r];
     if (i < 0) return;
     const float* s = src + (size_t)i * n;
+    const float* su = src + (size_t)(i + uncond_shift) * n;
     float* d = dst + (size_t)r * n;
-    for (int e = threadIdx.x; e < n; e += 256) d[e] = s[e];
+    for (int e = threadIdx.x; e < n; e += 256) d[e] = uncond_shift > 0 ? fmaf(scale, s[e] - su[e], su[e]) : s[e];
 }
 
 // The pass wrote node r's keys and values to the entry root + r.  The accepted path's nodes
@@ -68,8 +72,8 @@ __global__ __launch_bounds__(256) void tree_commit_kernel(const int32_t* acc, co
 
 }  // namespace
 
-void launch_gather_rows(hawk_ctx* c, const float* src, const int32_t* index, float* dst, int rows, int n) {
-    gather_rows_kernel<<<rows, 256, 0, c->stream>>>(src, index, dst, n);
+void launch_gather_rows(hawk_ctx* c, const float* src, const int32_t* index, float* dst, int rows, int n, int uncond_shift) {
+    gather_rows_kernel<<<rows, 256, 0, c->stream>>>(src, index, dst, n, uncond_shift, c->cfg_scale);
 }
 
 void launch_tree_commit(hawk_ctx* c, const int32_t* acc, const int32_t* path, const int32_t* toks, int n_nodes) {
