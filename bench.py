@@ -187,9 +187,9 @@ def main():
     out["multi_verify"] = bench_multi_verify(H, s)
     from paper_2510_25739_amd.spatial_timing import bench_spatial_draft
     out["spatial_draft"] = bench_spatial_draft(H, s)
-    if not s.use_cfg:   # timed without guidance (one prompt)
+    if s.batch == 1:   # one prompt (with its unconditional stream under guidance)
         from paper_2510_25739_amd.tree_timing import bench_tree
-        out["tree_verify"] = bench_tree(H, s, blob, cond)
+        out["tree_verify"] = bench_tree(H, s, blob, cond, uncond=unc)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(s, blob, cond, unc)
     print(json.dumps(out))

@@ -7,7 +7,7 @@ import sys
 import time
 
 
-def bench_tree(H, s, blob, cond, m_depth=(3, 3), steps=20):
+def bench_tree(H, s, blob, cond, m_depth=(3, 3), steps=20, uncond=None):
     """Milliseconds per call (host clock around the synchronous call), synthetic proposals N(0, 1.5^2)
     and candidates drawn from them on the GPU; k_max is sized for the tree's rows."""
     import numpy as np
@@ -17,11 +17,13 @@ def bench_tree(H, s, blob, cond, m_depth=(3, 3), steps=20):
         width *= m
         n_nodes += width
     D, m_max = len(m_depth), max(m_depth)
-    hk = H.Hawk(H.HawkConfig.from_shape(s, batch=1, k_max=max(n_nodes - 1, s.k)))
+    hk = H.Hawk(H.HawkConfig.from_shape(s if uncond is not None else s.replace(cfg_scale=1.0), batch=1,
+                                        k_max=max(n_nodes - 1, s.k)))
     hk.load(blob)
     rng = np.random.Generator(np.random.PCG64(1))
     uni = lambda *shp: (rng.integers(0, 1 << 24, size=shp).astype(np.float32) / np.float32(1 << 24)).astype(np.float32)
-    hk.prefill(cond[:1], None, s.grid_h, s.grid_w, s.temperature, s.top_k, 1.0, uni(1))
+    hk.prefill(cond[:1], None if uncond is None else uncond[:1], s.grid_h, s.grid_w, s.temperature, s.top_k,
+               s.cfg_scale if uncond is not None else 1.0, uni(1))
     g = torch.Generator(device="cuda:0")
     g.manual_seed(3)
     out = {"rows": n_nodes, "m_depth": list(m_depth)}
@@ -54,12 +56,12 @@ def main():
     sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
     import synth
     import paper_2510_25739_amd as H
-    s = synth.CONFIGS[int(sys.argv[1]) if len(sys.argv) > 1 else 2]
-    if s.use_cfg:
-        s = s.replace(cfg_scale=1.0, batch=1)
+    s = synth.CONFIGS[int(sys.argv[1]) if len(sys.argv) > 1 else 2].replace(batch=1)
     blob = synth.make_weights(s, seed=0)
     cond = synth.make_cond(s, seed=2, batch=1)
-    print(json.dumps({"tree": [bench_tree(H, s, blob, cond, m) for m in ((3, 3), (2, 2), (3,))]}))
+    unc = synth.make_cond(s, seed=3, batch=1) if s.use_cfg else None
+    shapes = ((3, 3), (2, 2), (3,)) if len(sys.argv) < 3 else (tuple(int(x) for x in sys.argv[2].split("x")),)
+    print(json.dumps({"tree": [bench_tree(H, s, blob, cond, m, uncond=unc) for m in shapes]}))
 
 
 if __name__ == "__main__":
