@@ -242,6 +242,16 @@ int hawk_phase_trace(hawk_ctx* ctx, int enable, uint64_t* out, size_t n_words);
 int hawk_verify_tree(hawk_ctx* ctx, int depth, const int32_t* m_depth, const int32_t* cand, const float* q_logits,
                      const float* u_acc, const float* u_final, int32_t* out_n_accept, int32_t* out_tokens);
 int hawk_get_tree_logits(hawk_ctx* ctx, float* out, int n_nodes);
+/* The accepted path of the last tree step: out (host) [batch][8], entry j = node index of the
+ * candidate accepted at depth j + 1 (valid for j < accepted count). */
+int hawk_get_tree_path(hawk_ctx* ctx, int32_t* out);
+/* Where the last target pass (hawk_verify, hawk_verify_tree, hawk_force) left the hidden states of
+ * its rows - the final layer's output before the final norm, which draft heads read (Preliminary,
+ * "Utilization of Draft Heads Structure"): *device_ptr points into the context's workspace, rows
+ * [sequence][row of the pass][d_model], contiguous, elements of *elem_bytes bytes (4: fp32 in the
+ * bf16 configurations, 8: fp64 in the fp32 configuration).  Valid until the next call that runs a
+ * pass; the caller must not write there. */
+int hawk_last_hidden(hawk_ctx* ctx, const void** device_ptr, int* elem_bytes);
 
 /* Verification of several candidates at one position, each drawn from a proposal of its own
  * (Method, "Sampling and Verification": the iterated update of the target after consecutive

@@ -907,6 +907,21 @@ int hawk_get_tree_logits(hawk_ctx* c, float* out, int n_nodes) {
     return download(c, out, c->off.logit_b, (size_t)c->B * n_nodes * c->Vs * 4);
 }
 
+int hawk_get_tree_path(hawk_ctx* c, int32_t* out) {
+    if (!c || !out) return HAWK_EINVAL;
+    if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
+    const size_t t_path = c->off.tree + 768 + (size_t)c->B * 20;
+    return download(c, out, t_path, (size_t)c->B * kTreeMaxDepth * 4);
+}
+
+int hawk_last_hidden(hawk_ctx* c, const void** device_ptr, int* elem_bytes) {
+    if (!c || !device_ptr || !elem_bytes) return HAWK_EINVAL;
+    if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
+    *device_ptr = c->ws + c->off.x;
+    *elem_bytes = (int)c->asz;
+    return HAWK_OK;
+}
+
 int hawk_get_draft_logits(hawk_ctx* c, float* out, int k) {
     if (!c || !out) return HAWK_EINVAL;
     if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");

@@ -74,6 +74,8 @@ EXPORTS = {
     "hawk_verify_tree": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.c_void_p]),
     "hawk_get_tree_logits": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int]),
+    "hawk_get_tree_path": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "hawk_last_hidden": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "hawk_multi_verify_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int]),
     "hawk_multi_verify": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                     C.c_int, C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -388,6 +390,23 @@ class Hawk:
         self._chk(self._L.hawk_verify_tree(self._h, D, _p(md), _p(cand), C.c_void_p(q_logits.data_ptr()), _p(ua), _p(uf),
                                            _p(na), _p(toks)), "hawk_verify_tree")
         return na, toks
+
+    def tree_path(self):
+        out = np.zeros((self.batch, 8), dtype=np.int32)
+        self._chk(self._L.hawk_get_tree_path(self._h, _p(out)), "hawk_get_tree_path")
+        return out
+
+    def last_hidden(self, rows_per_seq: int):
+        """The hidden states of the last pass's rows as a device tensor view [sequences * rows_per_seq, d]
+        (fp32 in the bf16 configurations, fp64 in the fp32 one) into the workspace: read only."""
+        ptr, eb = C.c_void_p(), C.c_int()
+        self._chk(self._L.hawk_last_hidden(self._h, C.byref(ptr), C.byref(eb)), "hawk_last_hidden")
+        torch = self._torch
+        n_seq = self.batch * (2 if self.cfg.use_cfg else 1)
+        off = ptr.value - self._ws.data_ptr()
+        nbytes = n_seq * rows_per_seq * self.cfg.d_model * eb.value
+        return self._ws[off:off + nbytes].view(torch.float32 if eb.value == 4 else torch.float64).view(
+            n_seq * rows_per_seq, self.cfg.d_model)
 
     def tree_logits(self, n_nodes):
         out = np.zeros((self.batch, n_nodes, self.v_s), dtype=np.float32)
