@@ -610,10 +610,15 @@ int hawk_verify_tree(hawk_ctx* c, int depth, const int32_t* m_depth, const int32
         const int M = c->S * n_nodes;
         c->presplit_off = 0;
         launch_embed_rows(c, map, M);
-        c->last_path = 0;
-        run_layers(c, map, M);
-        launch_rmsnorm(c, c->off.x, c->d, c->w.g_f, c->off.a, M, true);
-        launch_gemm(c, c->off.a, c->d, slice_off(c), c->Vs, c->d, c->off.logit_s, c->Vs, M, false, true);
+        if (stream_tree_ok(c, n_nodes)) {   // one persistent kernel: all layers and the output projection
+            if (launch_verify_stream_tree(c, n_nodes, map.tree_depth, map.tree_anc) != 0) c->launch_failed = 1;
+            c->last_path = 1;
+        } else {
+            c->last_path = 0;
+            run_layers(c, map, M);
+            launch_rmsnorm(c, c->off.x, c->d, c->w.g_f, c->off.a, M, true);
+            launch_gemm(c, c->off.a, c->d, slice_off(c), c->Vs, c->d, c->off.logit_s, c->Vs, M, false, true);
+        }
         HIP_TRY(c, hipGetLastError());
         // the walk, one depth at a time: the row of the node each prompt stands on is the target of
         // that depth's candidates
@@ -675,6 +680,10 @@ int hawk_verify_tree(hawk_ctx* c, int depth, const int32_t* m_depth, const int32
         HIP_TRY(c, hipStreamSynchronize(c->stream));
     }
     c->phase = 2;
+    if (any) {
+        rc = check_stream(c);
+        if (rc) return rc;
+    }
     for (int b = 0; b < B; ++b) {
         if (out_n_accept) out_n_accept[b] = acc[b];
         if (out_tokens)

@@ -169,6 +169,8 @@ void stream_plan_info(const hawk_ctx*, int64_t* out8);  // host-only summary of 
 int stream_repack(hawk_ctx*);             // after the blob is on the device; 0 = ok
 bool stream_ok(const hawk_ctx*, int k);   // can a step with k drafts run on the streaming path?
 int launch_verify_stream(hawk_ctx*, int k);  // 0 = enqueued
+bool stream_tree_ok(const hawk_ctx*, int n_nodes);   // can a pass over tree rows run on the streaming path?
+int launch_verify_stream_tree(hawk_ctx*, int n_nodes, const int32_t* tree_depth, const unsigned long long* tree_anc);
 bool stream_draft_ok(const hawk_ctx*);      // can draft micro-steps run on the streaming path?
 int launch_draft_stream(hawk_ctx*, int i, size_t off_prev, size_t off_out);  // micro-step i up to its logits
 int stream_error(hawk_ctx*);              // 1 if a grid barrier timed out (synchronises)

@@ -89,6 +89,9 @@ struct SP {
     const int32_t* draft;
     u64 E_off;
     int32_t step_i, N, IW, kstride;
+    // tree rows only (see RowMap): depth and ancestor mask of the tree's nodes
+    const int32_t* tdepth;
+    const u64* tanc;
 };
 
 // ------------------------------------------------------------------------- device helpers
@@ -389,7 +392,10 @@ __device__ __forceinline__ void mfma_job(const v4u (&w)[NS * TPS], int wave, int
     for (int si = 0; si < NS; ++si) acc[si] += acl[si];
 }
 
-struct RowPos { int seq, r, pos; bool valid; };
+// pos: the row's position (rotary angle); slot: its entry in the cache.  Tree rows: node r of the
+// candidate tree sits at the root's position plus its depth and in the entry root + r.
+struct RowPos { int seq, r, pos, slot; bool valid; };
+template <bool TREE = false>
 __device__ __forceinline__ RowPos row_pos(const SP& p, int c) {
     RowPos o;
     o.seq = c / p.RS;
@@ -397,7 +403,9 @@ __device__ __forceinline__ RowPos row_pos(const SP& p, int c) {
     const int b = o.seq % p.B;
     const int ke = p.k_eff[b];
     o.valid = o.r <= ke;
-    o.pos = o.valid ? p.C + p.n[b] - 1 + o.r : 0;
+    o.slot = o.valid ? p.C + p.n[b] - 1 + o.r : 0;
+    o.pos = o.slot;
+    if constexpr (TREE) o.pos = o.valid ? p.C + p.n[b] - 1 + p.tdepth[o.r] : 0;
     return o;
 }
 
@@ -419,7 +427,7 @@ struct EpiPre {
     uint2 gain;      // stages C, E: gain of the following norm for the lane's four rows (bf16 x 4)
 };
 
-template <int KIND>
+template <int KIND, bool TREE = false>
 __device__ __forceinline__ void epilogue_prefetch(const SP& p, int layer, int strip, int lane, EpiPre& pre) {
     const int c = lane & 15, quad = lane >> 4, d = p.d;
     pre.rot[0] = pre.rot[1] = make_float2(1.f, 0.f);
@@ -427,7 +435,7 @@ __device__ __forceinline__ void epilogue_prefetch(const SP& p, int layer, int st
     if (KIND == K_A) {
         const int o0 = strip * 16, seg = o0 / d, j0 = o0 - seg * d, hd = d / p.H;
         if (c < p.MR && seg < 2) {
-            const RowPos rp = row_pos(p, c);
+            const RowPos rp = row_pos<TREE>(p, c);
             const float2* rt = p.rope + (size_t)rp.pos * (hd / 2) + ((j0 % hd) >> 1) + 2 * quad;
             pre.rot[0] = rt[0];
             pre.rot[1] = rt[1];
@@ -462,7 +470,7 @@ __device__ __forceinline__ void put_stream(const SP& p, uint16_t* hi, uint16_t* 
 }
 
 // v: the finished strip in accumulator layout (lane: rows 4*(lane/16)..+3 of column lane%16).
-template <int KIND>
+template <int KIND, bool TREE = false>
 __device__ __forceinline__ void epilogue(const SP& p, const Lds& s, int layer, int strip, f32x4 v, int lane,
                                          const EpiPre& pre, f32x4& resid) {
     const int c = lane & 15, quad = lane >> 4, d = p.d;
@@ -478,11 +486,11 @@ __device__ __forceinline__ void epilogue(const SP& p, const Lds& s, int layer, i
                 st_f32x4(slot(p, layer) + p.o_q + (size_t)c * d + j0 + 4 * quad,
                          (f32x4){a0 * 0.125f, b0 * 0.125f, a1 * 0.125f, b1 * 0.125f});
             } else {
-                const RowPos rp = row_pos(p, c);
+                const RowPos rp = row_pos<TREE>(p, c);
                 if (rp.valid) {
                     // cache layout [layer][sequence][head][position][64]: a strip lies inside one head
                     _Float16* dst = (seg == 1 ? p.Kc : p.Vc) +
-                                    ((((size_t)layer * p.Smax + rp.seq) * p.H + j0 / 64) * p.Tmax + rp.pos) * 64 + j0 % 64 + 4 * quad;
+                                    ((((size_t)layer * p.Smax + rp.seq) * p.H + j0 / 64) * p.Tmax + rp.slot) * 64 + j0 % 64 + 4 * quad;
                     const _Float16 h0 = (_Float16)a0, h1 = (_Float16)b0, h2 = (_Float16)a1, h3 = (_Float16)b1;
                     st_u64(dst,
                            (unsigned)__builtin_bit_cast(unsigned short, h0) | ((unsigned)__builtin_bit_cast(unsigned short, h1) << 16),
@@ -651,7 +659,7 @@ __device__ __forceinline__ void stage_head_output(const SP& p, int io, int lane,
 // KIND: which matrix; TPS: k-tiles per compute wave and strip; NSS: per-strip sums of squares
 // per lane of the row-scale reduction (0: the stage input is not normalised); BATCH: chunks in
 // flight per IO thread while copying the stage input.
-template <int KIND, int TPS, int NSS, int BATCH, int KREG, int STAGE = 0>
+template <int KIND, int TPS, int NSS, int BATCH, int KREG, int STAGE = 0, bool TREE = false>
 __device__ __forceinline__ void gemv_phase(const SP& p, const Lds& s, Barrier& bar, int layer, int round,
                                            const uint16_t* src_hi, const uint16_t* src_lo, const float* ss, int K, int Kp,
                                            f32x4& resid) {
@@ -672,7 +680,7 @@ __device__ __forceinline__ void gemv_phase(const SP& p, const Lds& s, Barrier& b
         stamp_c(p, ph, 1);
     } else {
         stamp(p, ph, 0);
-        if (wave - kCW < job.nstrips) epilogue_prefetch<KIND>(p, layer, job.strip[wave - kCW], lane, pre);
+        if (wave - kCW < job.nstrips) epilogue_prefetch<KIND, TREE>(p, layer, job.strip[wave - kCW], lane, pre);
         if (fresh) {
             bar.wait();
             stamp(p, ph, 1);
@@ -716,7 +724,7 @@ __device__ __forceinline__ void gemv_phase(const SP& p, const Lds& s, Barrier& b
 #pragma unroll
             for (int cw = 0; cw < kCW; ++cw)
                 v += *reinterpret_cast<const f32x4*>(s.red + (((size_t)cw * kMaxStrips + i) * 64 + lane) * 4);
-            epilogue<KIND>(p, s, layer, job.strip[i], v, lane, pre, resid);
+            epilogue<KIND, TREE>(p, s, layer, job.strip[i], v, lane, pre, resid);
         }
     }
     if (is_io) {
@@ -868,6 +876,30 @@ __device__ __forceinline__ void attend(const float (&q)[RPJ][8], int r0, v4u kra
     }
 }
 
+// The same for tree rows: bit r of vis says whether absolute row r sees the position.
+template <int RPJ>
+__device__ __forceinline__ void attend_vis(const float (&q)[RPJ][8], int r0, v4u kraw, v4u vraw, unsigned vis, int ke,
+                                           AttnAcc (&A)[RPJ]) {
+    float kf[8], vf[8];
+    halves8(kraw, kf);
+    halves8(vraw, vf);
+#pragma unroll
+    for (int r = 0; r < RPJ; ++r) {
+        float sc = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sc += q[r][e] * kf[e];
+        sc = sum8(sc);
+        if (((vis >> (r0 + r)) & 1u) && r0 + r <= ke) {
+            const float mn = fmaxf(A[r].mx, sc);
+            const float corr = __expf(A[r].mx - mn), pw = __expf(sc - mn);
+            A[r].den = A[r].den * corr + pw;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) A[r].acc[e] = A[r].acc[e] * corr + pw * vf[e];
+            A[r].mx = mn;
+        }
+    }
+}
+
 // kNIT cache positions per lane group at once (positions pos0 + it * stride, those < o1 count):
 // all scores first, one running-maximum update per row, then the weighted values - independent
 // work for the VALU instead of one dependent chain per position.
@@ -917,7 +949,7 @@ __device__ __forceinline__ void attend_round(const float (&q)[RPJ][8], int r0, c
     }
 }
 
-template <int RPJ>
+template <int RPJ, bool TREE = false>
 __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& bar, int layer) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const bool is_io = wave >= kCW;
@@ -997,6 +1029,29 @@ __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& b
             fetch(kb, vb, rnd + 3);
         }
         stamp_c(p, ph, 3);
+        if constexpr (TREE) {
+            // entries appended by this launch (node a in entry kv0 + a, up to 16 of them): a row
+            // sees its ancestors' and its own
+            if (ch == p.NC - 1 && wave == 0) {
+                for (int a = pg; a <= ke; a += 8) {
+                    const _Float16* kp = p.Kc + base + (size_t)(kv0 + a) * 64;
+                    const _Float16* vp = p.Vc + base + (size_t)(kv0 + a) * 64;
+                    const u64 a0 = __hip_atomic_load(reinterpret_cast<const u64*>(kp), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const u64 a1 = __hip_atomic_load(reinterpret_cast<const u64*>(kp) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const u64 b0 = __hip_atomic_load(reinterpret_cast<const u64*>(vp), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const u64 b1 = __hip_atomic_load(reinterpret_cast<const u64*>(vp) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const v4u kraw = (v4u){(unsigned)a0, (unsigned)(a0 >> 32), (unsigned)a1, (unsigned)(a1 >> 32)};
+                    const v4u vraw = (v4u){(unsigned)b0, (unsigned)(b0 >> 32), (unsigned)b1, (unsigned)(b1 >> 32)};
+                    unsigned vis = 0u;
+#pragma unroll
+                    for (int r = 0; r < RPJ; ++r) {
+                        const int row = r0 + r;
+                        if (row < RS && (row == a || ((p.tanc[row] >> a) & 1ull))) vis |= 1u << row;
+                    }
+                    attend_vis<RPJ>(q, r0, kraw, vraw, vis, ke, A);
+                }
+            }
+        } else
         if (ch == p.NC - 1 && wave == 0 && pg <= ke) {  // rows appended by this launch: coherent loads
             const _Float16* kp = p.Kc + base + (size_t)(kv0 + pg) * 64;
             const _Float16* vp = p.Vc + base + (size_t)(kv0 + pg) * 64;
@@ -1071,7 +1126,8 @@ __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& b
 
 // ------------------------------------------------------------------------- the kernel
 
-template <int TPS_D, int TPS_M, int KREG_D, int RSMAX>
+// TREE: the rows are the nodes of a candidate tree (two rows per attention job).
+template <int TPS_D, int TPS_M, int KREG_D, int RSMAX, bool TREE = false>
 __global__ __launch_bounds__(kThreads, 1) void verify_stream_kernel(SP p) {
     extern __shared__ uint4 smem_raw[];
     Lds s;
@@ -1089,9 +1145,9 @@ __global__ __launch_bounds__(kThreads, 1) void verify_stream_kernel(SP p) {
     constexpr int NSS = 2 * TPS_D;             // (d / 16 strips) / 4 lane groups
     prologue_phase(p, s, bar, resid);
     for (int l = 0; l < p.L; ++l) {
-        gemv_phase<K_A, TPS_D, NSS, 8, KREG_D>(p, s, bar, l, 0, plane(p, l, p.o_xh), plane(p, l, p.o_xl),
-                                               slot(p, l) + p.o_ssx, p.d, p.Kpd, resid);
-        attn_phase<1>(p, s, bar, l);
+        gemv_phase<K_A, TPS_D, NSS, 8, KREG_D, 0, TREE>(p, s, bar, l, 0, plane(p, l, p.o_xh), plane(p, l, p.o_xl),
+                                                        slot(p, l) + p.o_ssx, p.d, p.Kpd, resid);
+        attn_phase<TREE ? 2 : 1, TREE>(p, s, bar, l);
         gemv_phase<K_C, TPS_D, 0, 8, KREG_D>(p, s, bar, l, 0, plane(p, l, p.o_oh), plane(p, l, p.o_ol), nullptr, p.d,
                                              p.Kpd, resid);
         gemv_phase<K_D, TPS_D, NSS, 8, KREG_D>(p, s, bar, l, 0, plane(p, l, p.o_x2h), plane(p, l, p.o_x2l),
@@ -1559,6 +1615,30 @@ int launch_verify_stream(hawk_ctx* c, int k) {
     const void* kern = c->d == 1280 ? reinterpret_cast<const void*>(verify_stream_kernel<10, 9, 5, 6>)
                                     : reinterpret_cast<const void*>(verify_stream_kernel<6, 4, 3, 6>);
     // prologue + five stages per layer; nothing follows the output projection
+    return launch_coop(c, kern, p, 1u + 5u * (unsigned)c->L);
+}
+
+// Tree rows on the streaming path: the nodes of one candidate tree per sequence, at most 16 rows in
+// all, two rows per attention job (their jobs must fit the workgroups of an XCD).
+bool stream_tree_ok(const hawk_ctx* c, int n_nodes) {
+    if (!c->plan || !c->plan->ok || c->path != 1) return false;
+    const int MR = c->S * n_nodes;
+    if (MR > 16 || n_nodes < 1) return false;
+    const int heads_per_xcd = (c->S * c->H + kXcd - 1) / kXcd;
+    if (heads_per_xcd * ((n_nodes + 1) / 2) > kPerXcd) return false;
+    return stream_lds_bytes(c, MR) <= 150 * 1024;
+}
+
+int launch_verify_stream_tree(hawk_ctx* c, int n_nodes, const int32_t* tree_depth, const unsigned long long* tree_anc) {
+    SP p;
+    fill_params(c, p, c->S * n_nodes);
+    p.logit_s = wsp<float>(c, c->off.logit_s);
+    p.RS = n_nodes;
+    p.NC = 1; p.RPJ = 2; p.NRG = (n_nodes + 1) / 2;
+    p.tdepth = tree_depth;
+    p.tanc = reinterpret_cast<const u64*>(tree_anc);
+    const void* kern = c->d == 1280 ? reinterpret_cast<const void*>(verify_stream_kernel<10, 9, 5, 6, true>)
+                                    : reinterpret_cast<const void*>(verify_stream_kernel<6, 4, 3, 6, true>);
     return launch_coop(c, kern, p, 1u + 5u * (unsigned)c->L);
 }
 

@@ -118,10 +118,11 @@ def chain_step(hk, orc, s, k, rng, exact):
     return err
 
 
-def start(H, s, k_max, batch=1):
+def start(H, s, k_max, batch=1, path=1):
     blob = synth.make_weights(s, seed=0)
     hk = H.Hawk(H.HawkConfig.from_shape(s, batch=batch, k_max=k_max))
     hk.load(blob)
+    hk.set_path(path)   # 1: the persistent kernel where it applies, 0: one kernel per operation
     orc = oracle.Oracle.from_shape(s, blob, batch=batch, k_max=k_max)
     cond = synth.make_cond(s, seed=2, batch=batch)
     unc = synth.make_cond(s, seed=3, batch=batch) if s.use_cfg else None
@@ -204,17 +205,20 @@ def test_tree_step_two_prompts_fp32(H):
     assert len(seen) > 1
 
 
-def test_tree_steps_bf16(H):
+@pytest.mark.parametrize("path,m_depth", [(1, (3, 3)), (0, (3, 3)), (1, (5, 2)), (1, (2, 2, 1))])
+def test_tree_steps_bf16(H, path, m_depth):
     # the XL shape at four layers: node logits within tolerance, the walk exact on the GPU's own rows,
-    # and the ordinary steps in between stay within tolerance (keys and values of the accepted path in place)
+    # and the ordinary steps in between stay within tolerance (keys and values of the accepted path in place);
+    # on the persistent kernel (trees of up to 16 rows) and with one kernel per operation
     s = synth.CONFIGS[2].replace(n_layers=4)
-    hk, orc, E = start(H, s, k_max=12)
+    hk, orc, E = start(H, s, k_max=15, path=path)
     if hk.grid()[0, 0] != orc.grid()[0, 0]:
         pytest.skip("token 0 differs in bf16 for this seed")
     rng = np.random.Generator(np.random.PCG64(4))
     worst, accs, agree = 0.0, [], 0
     for step in range(6):
-        r = tree_step(H, hk, orc, E, s, (3, 3), rng, s.temperature, s.top_k)
+        r = tree_step(H, hk, orc, E, s, m_depth, rng, s.temperature, s.top_k)
+        assert hk.last_path() == path
         worst = max(worst, r["err"])
         agree += int(r["same"])
         a = r["acc"][0]
@@ -268,8 +272,8 @@ def test_tree_step_full_depth_bf16(H):
     assert worst < 2e-2
 
 
-@pytest.mark.parametrize("cfg,m_depth", [(0, (2, 2)), (0, (3, 2, 1)), (1, (3, 3))])
-def test_greedy_tree_decoding_is_plain_greedy_decoding(H, cfg, m_depth):
+@pytest.mark.parametrize("cfg,m_depth,path", [(0, (2, 2), 1), (0, (3, 2, 1), 1), (1, (3, 3), 1), (1, (3, 3), 0), (1, (3, 4), 1)])
+def test_greedy_tree_decoding_is_plain_greedy_decoding(H, cfg, m_depth, path):
     # whole images: with temperature 0 the tokens must be those of token-by-token arg-max decoding,
     # whatever the candidates are (some are planted from the reference so that the walk goes deep,
     # the others are random); the image's last positions, where the tree no longer fits, are ordinary steps
@@ -280,6 +284,7 @@ def test_greedy_tree_decoding_is_plain_greedy_decoding(H, cfg, m_depth):
     nn = n_nodes_of(m_depth)
     hk = H.Hawk(H.HawkConfig.from_shape(s, batch=1, k_max=max(nn - 1, s.k)))
     hk.load(blob)
+    hk.set_path(path)
     ref, _ = hk.generate(cond, None, s.grid_h, s.grid_w, 0, 0.0, s.top_k, 1.0, 1)
     hk.prefill(cond, None, s.grid_h, s.grid_w, 0.0, s.top_k, 1.0, np.array([0.5], np.float32))
     rng = np.random.Generator(np.random.PCG64(cfg + 40))
