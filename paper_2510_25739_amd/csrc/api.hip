@@ -39,6 +39,24 @@ int fail(hawk_ctx* c, int code, const char* fmt, ...) {
 size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Fills the derived dimensions; false if the configuration is invalid.
+// Layout of the workspace region a tree step keeps its small arrays in (byte offsets from off.tree).
+struct TreeArea {
+    static constexpr size_t kCandCap = 512;   // depth x widest candidate list, per prompt
+    static constexpr int kMetaFirst = 3, kMetaWidth = 16;   // meta: depth, nodes, m_max, first[10], ..., m_depth[8]
+    enum { kCur = 0, kRows, kIdx, kTok, kWalking, kAcc, kStateWords };   // per-prompt words, [word][B]; kAcc last: acc, path, toks are contiguous
+    size_t depth, anc, meta, state, path, toks, cand, u_acc, u_fin, bytes;
+    explicit TreeArea(const hawk_ctx* c) : TreeArea((size_t)c->B) {}
+    explicit TreeArea(size_t B) {
+        depth = 0; anc = 256; meta = 768; state = 896;
+        path = state + B * kStateWords * 4;
+        toks = path + B * kTreeMaxDepth * 4;
+        cand = (toks + B * (kTreeMaxDepth + 1) * 4 + 15) & ~(size_t)15;
+        u_acc = cand + B * kCandCap * 4;
+        u_fin = u_acc + B * kCandCap * 4;
+        bytes = u_fin + B * (kTreeMaxDepth + 1) * 4;
+    }
+};
+
 bool derive(const hawk_config* g, hawk_ctx* c) {
     if (!g) return false;
     if (g->n_layers < 1 || g->n_layers > 128 || g->d_model < 8 || g->d_model % 8 || g->n_heads < 1 ||
@@ -101,7 +119,7 @@ bool derive(const hawk_config* g, hawk_ctx* c) {
     o.u_draft = take(B * ks * 4); o.u_acc = take(B * ks * 4); o.u_fin = take(B * 4);
     o.out_na = take(B * 4); o.out_tok = take(B * ks * 4); o.inv_freq = take((size_t)(hd / 2) * 8);
     o.replay = take(B * c->Nmax * 4); o.cond = take(S * (size_t)g->max_cond * d * 4);
-    o.tree = take(768 + B * 88);
+    o.tree = take(TreeArea(B).bytes);
     const size_t widest = 3 * d > m ? 3 * d : m;
     c->split_bytes = g->dtype == HAWK_BF16 ? M * widest * 4 : 0;
     o.split = c->split_bytes ? take(c->split_bytes) : 0;
@@ -574,10 +592,20 @@ int hawk_verify_tree(hawk_ctx* c, int depth, const int32_t* m_depth, const int32
                         b, c->N - n_now[b], n_nodes);
         any = true;
     }
-    // host image of the device arrays
+    // host image of everything the device needs, staged in page-locked memory and sent in one go
     const int ks = c->kmax + 1;
-    std::vector<int32_t> node_depth(kTreeMaxNodes, 0), parent(n_nodes, -1), digit(n_nodes, 0), keff(B), tokens((size_t)B * ks, -1);
-    std::vector<unsigned long long> anc(kTreeMaxNodes, 0ull);
+    const TreeArea ta(c);
+    if ((size_t)depth * m_max > TreeArea::kCandCap) return fail(c, HAWK_EINVAL, "depth x widest candidate list beyond %d", (int)TreeArea::kCandCap);
+    char* stage = static_cast<char*>(c->pinned);
+    const size_t tok_at = (ta.bytes + 255) & ~(size_t)255, keff_at = tok_at + (((size_t)B * ks * 4 + 255) & ~(size_t)255);
+    if (keff_at + (size_t)B * 4 > kPinnedBytes) return fail(c, HAWK_EINVAL, "batch too large for the staging buffer");
+    memset(stage, 0, keff_at + (size_t)B * 4);
+    int32_t* node_depth = reinterpret_cast<int32_t*>(stage + ta.depth);
+    unsigned long long* anc = reinterpret_cast<unsigned long long*>(stage + ta.anc);
+    int32_t* meta = reinterpret_cast<int32_t*>(stage + ta.meta);
+    int32_t* tokens = reinterpret_cast<int32_t*>(stage + tok_at);
+    int32_t* keff = reinterpret_cast<int32_t*>(stage + keff_at);
+    std::vector<int32_t> parent(n_nodes, -1), digit(n_nodes, 0);
     for (int j = 1; j <= depth; ++j)
         for (int i = first[j]; i < first[j + 1]; ++i) {
             const int idx = i - first[j];
@@ -586,109 +614,87 @@ int hawk_verify_tree(hawk_ctx* c, int depth, const int32_t* m_depth, const int32
             digit[i] = idx % m_depth[j - 1];
             anc[i] = anc[parent[i]] | (1ull << parent[i]);
         }
+    meta[0] = depth; meta[1] = n_nodes; meta[2] = m_max;
+    for (int j = 0; j <= depth + 1; ++j) meta[TreeArea::kMetaFirst + j] = first[j];
+    for (int j = 0; j < depth; ++j) meta[TreeArea::kMetaWidth + j] = m_depth[j];
+    int spare = -1;   // a row with valid logits for prompts that take no part (their results are ignored)
+    for (int b = 0; b < B; ++b)
+        if (n_now[b] < c->N && spare < 0) spare = b * n_nodes;
+    int32_t* st = reinterpret_cast<int32_t*>(stage + ta.state);
     for (int b = 0; b < B; ++b) {
-        keff[b] = n_now[b] >= c->N ? -1 : n_nodes - 1;
+        const bool on = n_now[b] < c->N;
+        keff[b] = on ? n_nodes - 1 : -1;
+        for (int i = 0; i < ks; ++i) tokens[(size_t)b * ks + i] = -1;
         for (int i = 1; i < n_nodes; ++i)
             tokens[(size_t)b * ks + i - 1] = c->cfg.samp_lo + cand[((size_t)(node_depth[i] - 1) * B + b) * m_max + digit[i]];
+        st[TreeArea::kCur * B + b] = on ? b * n_nodes : (spare < 0 ? 0 : spare);
+        st[TreeArea::kRows * B + b] = on ? m_depth[0] : 0;
+        st[TreeArea::kAcc * B + b] = on ? 0 : -1;
+        st[TreeArea::kWalking * B + b] = on ? 1 : 0;
     }
-    const size_t t0 = c->off.tree, t_anc = t0 + 256, t_cur = t0 + 768, t_m = t_cur + (size_t)B * 4, t_idx = t_m + (size_t)B * 4,
-                 t_tok = t_idx + (size_t)B * 4, t_acc = t_tok + (size_t)B * 4, t_path = t_acc + (size_t)B * 4,
-                 t_toks = t_path + (size_t)B * kTreeMaxDepth * 4;
-    rc = upload(c, t0, node_depth.data(), kTreeMaxNodes * 4);
-    if (!rc) rc = upload(c, t_anc, anc.data(), kTreeMaxNodes * 8);
-    if (!rc) rc = upload(c, c->off.k_eff, keff.data(), (size_t)B * 4);
-    if (!rc) rc = upload(c, c->off.draft, tokens.data(), tokens.size() * 4);
-    if (rc) return rc;
-    std::vector<int32_t> acc(B, -1), path((size_t)B * kTreeMaxDepth, 0), toks((size_t)B * (kTreeMaxDepth + 1), -1), cur(B, 0),
-        mrows(B, 0), idx(B), tok(B);
+    int32_t* toks_img = reinterpret_cast<int32_t*>(stage + ta.toks);
+    for (size_t i = 0; i < (size_t)B * (kTreeMaxDepth + 1); ++i) toks_img[i] = -1;
+    memcpy(stage + ta.cand, cand, (size_t)depth * B * m_max * 4);
+    memcpy(stage + ta.u_acc, u_acc, (size_t)depth * B * m_max * 4);
+    memcpy(stage + ta.u_fin, u_final, (size_t)(depth + 1) * B * 4);
     if (any) {
-        // the target pass over all nodes: one kernel per operation, tree rows
+        HIP_TRY(c, hipMemcpyAsync(c->ws + c->off.tree, stage, ta.bytes, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(c->ws + c->off.draft, tokens, (size_t)B * ks * 4, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(c->ws + c->off.k_eff, keff, (size_t)B * 4, hipMemcpyHostToDevice, c->stream));
+        // the target pass over all nodes
+        const size_t t0 = c->off.tree;
         RowMap map = step_map(c, n_nodes - 1);
         map.mode = 2;
-        map.tree_depth = wsp<int32_t>(c, t0);
-        map.tree_anc = wsp<unsigned long long>(c, t_anc);
+        map.tree_depth = wsp<int32_t>(c, t0 + ta.depth);
+        map.tree_anc = wsp<unsigned long long>(c, t0 + ta.anc);
         const int M = c->S * n_nodes;
         c->presplit_off = 0;
         launch_embed_rows(c, map, M);
         if (stream_tree_ok(c, n_nodes)) {   // one persistent kernel: all layers and the output projection
             if (launch_verify_stream_tree(c, n_nodes, map.tree_depth, map.tree_anc) != 0) c->launch_failed = 1;
             c->last_path = 1;
-        } else {
+        } else {                            // one kernel per operation
             c->last_path = 0;
             run_layers(c, map, M);
             launch_rmsnorm(c, c->off.x, c->d, c->w.g_f, c->off.a, M, true);
             launch_gemm(c, c->off.a, c->d, slice_off(c), c->Vs, c->d, c->off.logit_s, c->Vs, M, false, true);
         }
         HIP_TRY(c, hipGetLastError());
-        // the walk, one depth at a time: the row of the node each prompt stands on is the target of
-        // that depth's candidates
-        std::vector<char> walking(B);
-        for (int b = 0; b < B; ++b) {
-            walking[b] = keff[b] >= 0;
-            acc[b] = keff[b] >= 0 ? 0 : -1;
-        }
+        // The walk, on the device: per depth, the row of the node each prompt stands on is gathered as
+        // the target of that depth's candidates, verified, and a small kernel moves the prompt to the
+        // accepted child or ends its walk.  All depth + 1 rounds are enqueued; prompts that have
+        // stopped take part with no candidates and their results are ignored.
+        int32_t* dstate = wsp<int32_t>(c, t0 + ta.state);
         float* p_rows = wsp<float>(c, c->off.logit_b);
         for (int j = 0; j <= depth; ++j) {
-            bool left = false;
-            int spare = -1;   // a row with valid logits for the prompts that are not walking (their result is ignored)
-            for (int b = 0; b < B; ++b) {
-                cur[b] = walking[b] ? b * n_nodes + (acc[b] > 0 ? path[(size_t)b * kTreeMaxDepth + acc[b] - 1] : 0) : -1;
-                mrows[b] = walking[b] && j < depth ? m_depth[j] : 0;
-                left = left || walking[b];
-                if (walking[b] && spare < 0) spare = cur[b];
-            }
-            if (!left) break;
-            for (int b = 0; b < B; ++b)
-                if (cur[b] < 0) cur[b] = spare;
-            rc = upload(c, t_cur, cur.data(), (size_t)B * 4);
-            if (!rc) rc = upload(c, t_m, mrows.data(), (size_t)B * 4);
-            if (!rc) rc = upload(c, c->off.u_fin, u_final + (size_t)j * B, (size_t)B * 4);
-            if (!rc && j < depth) rc = upload(c, c->off.u_acc, u_acc + (size_t)j * B * m_max, (size_t)B * m_max * 4);
-            if (!rc && j < depth) rc = upload(c, c->off.forced, cand + (size_t)j * B * m_max, (size_t)B * m_max * 4);
-            if (rc) return rc;
-            launch_gather_rows(c, wsp<float>(c, c->off.logit_s), wsp<int32_t>(c, t_cur), p_rows, B, c->Vs,
+            launch_gather_rows(c, wsp<float>(c, c->off.logit_s), dstate + TreeArea::kCur * B, p_rows, B, c->Vs,
                                c->cfg.use_cfg ? B * n_nodes : 0);
-            // prompts that are not walking: m_rows = 0 makes the call draw from the spare row, ignored below
             const int m_call = j < depth ? m_max : 1;
             rc = launch_multi_verify(p_rows, j < depth ? q_logits + (size_t)j * B * m_max * c->Vs : p_rows,
-                                     wsp<int32_t>(c, c->off.forced), wsp<float>(c, c->off.u_acc), wsp<float>(c, c->off.u_fin),
-                                     wsp<int32_t>(c, t_m), B, m_call, c->Vs, c->temperature, c->top_k, wsp<int32_t>(c, t_idx),
-                                     wsp<int32_t>(c, t_tok), nullptr, wsp<void>(c, c->off.qstat),
-                                     2 * (size_t)B * ks * sizeof(WarpStat), c->stream);
+                                     wsp<int32_t>(c, t0 + ta.cand) + (j < depth ? (size_t)j * B * m_max : 0),
+                                     wsp<float>(c, t0 + ta.u_acc) + (j < depth ? (size_t)j * B * m_max : 0),
+                                     wsp<float>(c, t0 + ta.u_fin) + (size_t)j * B, dstate + TreeArea::kRows * B, B, m_call,
+                                     c->Vs, c->temperature, c->top_k, dstate + TreeArea::kIdx * B, dstate + TreeArea::kTok * B,
+                                     nullptr, wsp<void>(c, c->off.qstat), 2 * (size_t)B * ks * sizeof(WarpStat), c->stream);
             if (rc) return fail(c, rc, "launch of the verification kernel failed");
-            rc = download(c, idx.data(), t_idx, (size_t)B * 4);
-            if (!rc) rc = download(c, tok.data(), t_tok, (size_t)B * 4);
-            if (rc) return rc;
-            for (int b = 0; b < B; ++b) {
-                if (!walking[b]) continue;
-                toks[(size_t)b * (kTreeMaxDepth + 1) + acc[b]] = c->cfg.samp_lo + tok[b];
-                if (j < depth && idx[b] < m_depth[j]) {   // accepted: one depth down, to that child
-                    const int here = acc[b] > 0 ? path[(size_t)b * kTreeMaxDepth + acc[b] - 1] : 0;
-                    path[(size_t)b * kTreeMaxDepth + acc[b]] = first[j + 1] + (here - first[j]) * m_depth[j] + idx[b];
-                    ++acc[b];
-                } else {
-                    walking[b] = 0;   // rejected (the token is the draw from the updated target) or the extra token
-                }
-            }
+            launch_tree_advance(c, wsp<int32_t>(c, t0 + ta.meta), dstate, wsp<int32_t>(c, t0 + ta.path),
+                                wsp<int32_t>(c, t0 + ta.toks), j);
         }
-        rc = upload(c, t_acc, acc.data(), (size_t)B * 4);
-        if (!rc) rc = upload(c, t_path, path.data(), path.size() * 4);
-        if (!rc) rc = upload(c, t_toks, toks.data(), toks.size() * 4);
-        if (rc) return rc;
-        launch_tree_commit(c, wsp<int32_t>(c, t_acc), wsp<int32_t>(c, t_path), wsp<int32_t>(c, t_toks), n_nodes);
+        launch_tree_commit(c, dstate + TreeArea::kAcc * B, wsp<int32_t>(c, t0 + ta.path), wsp<int32_t>(c, t0 + ta.toks), n_nodes);
         HIP_TRY(c, hipGetLastError());
+        // acc, path and tokens come back in one copy (they are contiguous)
+        HIP_TRY(c, hipMemcpyAsync(stage + ta.state, c->ws + t0 + ta.state, ta.cand - ta.state, hipMemcpyDeviceToHost, c->stream));
         HIP_TRY(c, hipStreamSynchronize(c->stream));
-    }
-    c->phase = 2;
-    if (any) {
         rc = check_stream(c);
         if (rc) return rc;
     }
+    c->phase = 2;
     for (int b = 0; b < B; ++b) {
-        if (out_n_accept) out_n_accept[b] = acc[b];
+        const int a = st[TreeArea::kAcc * B + b];
+        if (out_n_accept) out_n_accept[b] = a;
         if (out_tokens)
             for (int i = 0; i <= depth; ++i)
-                out_tokens[(size_t)b * (depth + 1) + i] = acc[b] >= 0 && i <= acc[b] ? toks[(size_t)b * (kTreeMaxDepth + 1) + i] : -1;
+                out_tokens[(size_t)b * (depth + 1) + i] = a >= 0 && i <= a ? toks_img[(size_t)b * (kTreeMaxDepth + 1) + i] : -1;
     }
     return HAWK_OK;
 }
@@ -919,8 +925,7 @@ int hawk_get_tree_logits(hawk_ctx* c, float* out, int n_nodes) {
 int hawk_get_tree_path(hawk_ctx* c, int32_t* out) {
     if (!c || !out) return HAWK_EINVAL;
     if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
-    const size_t t_path = c->off.tree + 768 + (size_t)c->B * 20;
-    return download(c, out, t_path, (size_t)c->B * kTreeMaxDepth * 4);
+    return download(c, out, c->off.tree + TreeArea(c).path, (size_t)c->B * kTreeMaxDepth * 4);
 }
 
 int hawk_last_hidden(hawk_ctx* c, const void** device_ptr, int* elem_bytes) {

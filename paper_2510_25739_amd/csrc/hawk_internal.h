@@ -197,6 +197,8 @@ constexpr int kTreeMaxDepth = 8;    // depths of a candidate tree
 constexpr int kTreeMaxNodes = 64;   // nodes, the root included (one bit each in a row's ancestor mask)
 // dst[r] = src[index[r]] (rows of n floats); uncond_shift > 0: guided with the row that many rows further on
 void launch_gather_rows(hawk_ctx*, const float* src, const int32_t* index, float* dst, int rows, int n, int uncond_shift);
+// one round of the walk (see tree_advance_kernel for the arrays)
+void launch_tree_advance(hawk_ctx*, const int32_t* meta, int32_t* state, int32_t* path, int32_t* toks, int j);
 // moves the accepted paths' cache entries into place, then commits tokens, n and the kept hidden state;
 // acc [B] (-1: prompt not part of the pass), path [B][kTreeMaxDepth] node of the accepted candidate
 // per depth, toks [B][kTreeMaxDepth + 1] vocabulary ids: device arrays

@@ -46,6 +46,38 @@ __global__ __launch_bounds__(256) void kv_compact_kernel(uint16_t* Kc, uint16_t*
     }
 }
 
+// One round of the walk for every prompt (thread b), after the verification of depth j + 1 (or, for
+// j = depth, after the draw of the extra token): the token of the round is recorded; an accepted
+// candidate moves the prompt to that child - children of a node lie next to each other in candidate
+// order, depth by depth - and gives it the next depth's candidates; otherwise its walk is over.
+// meta: depth, nodes, widest list, then first node of every depth (from word 3) and the number of
+// candidates per depth (from word 16).  state: [word][B] with words cur (row of the node the prompt
+// stands on), rows (candidates in the coming round), idx, tok (the verification's results),
+// walking, acc.
+__global__ void tree_advance_kernel(const int32_t* meta, int32_t* state, int32_t* path, int32_t* toks, int j, int B,
+                                    int samp_lo) {
+    const int b = threadIdx.x;
+    if (b >= B) return;
+    int32_t *cur = state, *rows = state + B, *idx = state + 2 * B, *tok = state + 3 * B, *walking = state + 4 * B,
+            *acc = state + 5 * B;
+    if (!walking[b]) return;
+    const int depth = meta[0], n_nodes = meta[1];
+    const int32_t *first = meta + 3, *width = meta + 16;
+    const int a = acc[b];
+    toks[b * (kTreeMaxDepth + 1) + a] = samp_lo + tok[b];
+    if (j < depth && idx[b] < width[j]) {
+        const int here = a > 0 ? path[b * kTreeMaxDepth + a - 1] : 0;
+        const int node = first[j + 1] + (here - first[j]) * width[j] + idx[b];
+        path[b * kTreeMaxDepth + a] = node;
+        acc[b] = a + 1;
+        cur[b] = b * n_nodes + node;
+        rows[b] = j + 1 < depth ? width[j + 1] : 0;
+    } else {
+        walking[b] = 0;
+        rows[b] = 0;
+    }
+}
+
 // Prompt b: tokens toks[0..a] into the grid, n += a + 1, the hidden state of the last accepted node
 // (the root if none) kept for the next draft, counters as in the chain's commit.
 __global__ __launch_bounds__(256) void tree_commit_kernel(const int32_t* acc, const int32_t* path, const int32_t* toks,
@@ -74,6 +106,10 @@ __global__ __launch_bounds__(256) void tree_commit_kernel(const int32_t* acc, co
 
 void launch_gather_rows(hawk_ctx* c, const float* src, const int32_t* index, float* dst, int rows, int n, int uncond_shift) {
     gather_rows_kernel<<<rows, 256, 0, c->stream>>>(src, index, dst, n, uncond_shift, c->cfg_scale);
+}
+
+void launch_tree_advance(hawk_ctx* c, const int32_t* meta, int32_t* state, int32_t* path, int32_t* toks, int j) {
+    tree_advance_kernel<<<1, 64 * ((c->B + 63) / 64), 0, c->stream>>>(meta, state, path, toks, j, c->B, c->cfg.samp_lo);
 }
 
 void launch_tree_commit(hawk_ctx* c, const int32_t* acc, const int32_t* path, const int32_t* toks, int n_nodes) {
