@@ -19,7 +19,8 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const float* src, cons
     const float* s = src + (size_t)i * n;
     const float* su = src + (size_t)(i + uncond_shift) * n;
     float* d = dst + (size_t)r * n;
-    for (int e = threadIdx.x; e < n; e += 256) d[e] = uncond_shift > 0 ? fmaf(scale, s[e] - su[e], su[e]) : s[e];
+    for (int e = blockIdx.y * 256 + threadIdx.x; e < n; e += 256 * gridDim.y)   // a row is spread over gridDim.y workgroups
+        d[e] = uncond_shift > 0 ? fmaf(scale, s[e] - su[e], su[e]) : s[e];
 }
 
 // The pass wrote node r's keys and values to the entry root + r.  The accepted path's nodes
@@ -105,7 +106,7 @@ __global__ __launch_bounds__(256) void tree_commit_kernel(const int32_t* acc, co
 }  // namespace
 
 void launch_gather_rows(hawk_ctx* c, const float* src, const int32_t* index, float* dst, int rows, int n, int uncond_shift) {
-    gather_rows_kernel<<<rows, 256, 0, c->stream>>>(src, index, dst, n, uncond_shift, c->cfg_scale);
+    gather_rows_kernel<<<dim3(rows, 16), 256, 0, c->stream>>>(src, index, dst, n, uncond_shift, c->cfg_scale);
 }
 
 void launch_tree_advance(hawk_ctx* c, const int32_t* meta, int32_t* state, int32_t* path, int32_t* toks, int j) {
