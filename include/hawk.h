@@ -239,6 +239,15 @@ int hawk_phase_trace(hawk_ctx* ctx, int enable, uint64_t* out, size_t n_words);
  * is the guided combination, as in hawk_verify.  Synchronises the stream several times (the walk is
  * driven from the host).  hawk_get_tree_logits: the (guided) rows of the last tree pass, out (host)
  * [batch][n_nodes][V_s]. */
+/* The order hawk_verify_tree gives the tree's nodes (host arithmetic only, all pointers host, each
+ * out array may be NULL, room for 64 entries): node 0 is the root; then depth by depth every
+ * combination of the candidates so far, the children of a node next to each other in candidate
+ * order.  out_parent (-1 for the root), out_depth, out_candidate (which candidate of its depth; -1
+ * for the root), out_ancestors (bit j set: node j lies on the path from the root, root included).
+ * Returns the number of nodes, -1 for a bad shape (depth outside 1..8, a depth without candidates,
+ * more than 64 nodes). */
+int hawk_tree_layout(int depth, const int32_t* m_depth, int32_t* out_parent, int32_t* out_depth, int32_t* out_candidate,
+                     uint64_t* out_ancestors);
 int hawk_verify_tree(hawk_ctx* ctx, int depth, const int32_t* m_depth, const int32_t* cand, const float* q_logits,
                      const float* u_acc, const float* u_final, int32_t* out_n_accept, int32_t* out_tokens);
 int hawk_get_tree_logits(hawk_ctx* ctx, float* out, int n_nodes);

@@ -17,6 +17,7 @@ from .hawk import (  # noqa: F401
     spatial_heads,
     spec_cache_bytes,
     spec_cache_slot,
+    tree_layout,
     SpecCache,
     workspace_bytes,
 )

@@ -39,6 +39,41 @@ int fail(hawk_ctx* c, int code, const char* fmt, ...) {
 size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Fills the derived dimensions; false if the configuration is invalid.
+// The candidate tree of a tree step (Method, "Spatial Sampling Pool": Cartesian product of the
+// per-position candidates): node 0 is the root, then depth by depth all combinations of the
+// candidates so far, a node's children next to each other in candidate order.
+struct TreeShape {
+    int n_nodes, m_max;
+    int first[kTreeMaxDepth + 2];               // first node of every depth; first[depth + 1] = n_nodes
+    int depth[kTreeMaxNodes], parent[kTreeMaxNodes], digit[kTreeMaxNodes];   // digit: which candidate of its depth
+    unsigned long long anc[kTreeMaxNodes];      // bit j: node j is an ancestor (the root included)
+};
+// 0 = ok, 1 = a depth without candidates (or too many), 2 = more nodes than max_nodes or 64
+int tree_shape(int depth, const int32_t* m_depth, int max_nodes, TreeShape* t) {
+    memset(t, 0, sizeof *t);
+    t->n_nodes = 1;
+    t->first[0] = 0;
+    t->first[1] = 1;
+    t->parent[0] = -1;
+    for (int j = 0, width = 1; j < depth; ++j) {
+        if (m_depth[j] < 1 || m_depth[j] > kTreeMaxNodes) return 1;
+        width *= m_depth[j];
+        t->n_nodes += width;
+        if (t->n_nodes > kTreeMaxNodes || t->n_nodes > max_nodes) return 2;
+        t->first[j + 2] = t->n_nodes;
+        t->m_max = m_depth[j] > t->m_max ? m_depth[j] : t->m_max;
+    }
+    for (int j = 1; j <= depth; ++j)
+        for (int i = t->first[j]; i < t->first[j + 1]; ++i) {
+            const int idx = i - t->first[j];
+            t->depth[i] = j;
+            t->parent[i] = j == 1 ? 0 : t->first[j - 1] + idx / m_depth[j - 1];
+            t->digit[i] = idx % m_depth[j - 1];
+            t->anc[i] = t->anc[t->parent[i]] | (1ull << t->parent[i]);
+        }
+    return 0;
+}
+
 // Layout of the workspace region a tree step keeps its small arrays in (byte offsets from off.tree).
 struct TreeArea {
     static constexpr size_t kCandCap = 512;   // depth x widest candidate list, per prompt
@@ -551,6 +586,20 @@ int hawk_verify(hawk_ctx* c, int k, const float* u_acc, const float* u_final, in
     return HAWK_OK;
 }
 
+int hawk_tree_layout(int depth, const int32_t* m_depth, int32_t* out_parent, int32_t* out_depth, int32_t* out_candidate,
+                     uint64_t* out_ancestors) {
+    if (!m_depth || depth < 1 || depth > kTreeMaxDepth) return -1;
+    TreeShape ts;
+    if (tree_shape(depth, m_depth, kTreeMaxNodes, &ts) != 0) return -1;
+    for (int i = 0; i < ts.n_nodes; ++i) {
+        if (out_parent) out_parent[i] = ts.parent[i];
+        if (out_depth) out_depth[i] = ts.depth[i];
+        if (out_candidate) out_candidate[i] = i ? ts.digit[i] : -1;
+        if (out_ancestors) out_ancestors[i] = ts.anc[i];
+    }
+    return ts.n_nodes;
+}
+
 int hawk_verify_tree(hawk_ctx* c, int depth, const int32_t* m_depth, const int32_t* cand, const float* q_logits,
                      const float* u_acc, const float* u_final, int32_t* out_n_accept, int32_t* out_tokens) {
     if (!c) return HAWK_EINVAL;
@@ -558,21 +607,14 @@ int hawk_verify_tree(hawk_ctx* c, int depth, const int32_t* m_depth, const int32
     if (!m_depth || !cand || !q_logits || !u_acc || !u_final) return fail(c, HAWK_EINVAL, "null input");
     if (depth < 1 || depth > kTreeMaxDepth) return fail(c, HAWK_EINVAL, "depth = %d outside [1, %d]", depth, kTreeMaxDepth);
     const int B = c->B;
-    // the tree: node 0 is the root, then depth by depth the Cartesian product of the candidate lists,
-    // a node's children next to each other in candidate order
-    int m_max = 0, n_nodes = 1, first[kTreeMaxDepth + 2];   // first[j]: first node of depth j
-    first[0] = 0;
-    first[1] = 1;
-    for (int j = 0, width = 1; j < depth; ++j) {
-        if (m_depth[j] < 1 || m_depth[j] > kTreeMaxNodes) return fail(c, HAWK_EINVAL, "m_depth[%d] = %d", j, m_depth[j]);
-        width *= m_depth[j];
-        n_nodes += width;
-        if (n_nodes > kTreeMaxNodes || n_nodes > c->kmax + 1)
-            return fail(c, HAWK_EINVAL, "the tree has more than %d nodes (64, or k_max + 1 rows per sequence)",
-                        n_nodes > kTreeMaxNodes ? kTreeMaxNodes : c->kmax + 1);
-        first[j + 2] = n_nodes;
-        m_max = m_depth[j] > m_max ? m_depth[j] : m_max;
-    }
+    TreeShape ts;
+    const int shape_rc = tree_shape(depth, m_depth, c->kmax + 1, &ts);
+    if (shape_rc == 1) return fail(c, HAWK_EINVAL, "every depth needs between 1 and %d candidates", kTreeMaxNodes);
+    if (shape_rc == 2)
+        return fail(c, HAWK_EINVAL, "the tree has more than %d nodes (64, or k_max + 1 rows per sequence)",
+                    c->kmax + 1 < kTreeMaxNodes ? c->kmax + 1 : kTreeMaxNodes);
+    const int m_max = ts.m_max, n_nodes = ts.n_nodes;
+    const int* first = ts.first;
     if (c->Vs > 16384) return fail(c, HAWK_EINVAL, "sampled slice beyond 16384 entries");
     for (size_t i = 0; i < (size_t)depth * B * m_max; ++i) {
         const int j = (int)(i / ((size_t)B * m_max)), slot = (int)(i % m_max);
@@ -605,15 +647,11 @@ int hawk_verify_tree(hawk_ctx* c, int depth, const int32_t* m_depth, const int32
     int32_t* meta = reinterpret_cast<int32_t*>(stage + ta.meta);
     int32_t* tokens = reinterpret_cast<int32_t*>(stage + tok_at);
     int32_t* keff = reinterpret_cast<int32_t*>(stage + keff_at);
-    std::vector<int32_t> parent(n_nodes, -1), digit(n_nodes, 0);
-    for (int j = 1; j <= depth; ++j)
-        for (int i = first[j]; i < first[j + 1]; ++i) {
-            const int idx = i - first[j];
-            node_depth[i] = j;
-            parent[i] = j == 1 ? 0 : first[j - 1] + idx / m_depth[j - 1];
-            digit[i] = idx % m_depth[j - 1];
-            anc[i] = anc[parent[i]] | (1ull << parent[i]);
-        }
+    for (int i = 0; i < n_nodes; ++i) {
+        node_depth[i] = ts.depth[i];
+        anc[i] = ts.anc[i];
+    }
+    const int* digit = ts.digit;
     meta[0] = depth; meta[1] = n_nodes; meta[2] = m_max;
     for (int j = 0; j <= depth + 1; ++j) meta[TreeArea::kMetaFirst + j] = first[j];
     for (int j = 0; j < depth; ++j) meta[TreeArea::kMetaWidth + j] = m_depth[j];

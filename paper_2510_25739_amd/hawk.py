@@ -71,6 +71,7 @@ EXPORTS = {
     "hawk_set_path": (C.c_int, [C.c_void_p, C.c_int]),
     "hawk_last_path": (C.c_int, [C.c_void_p]),
     "hawk_phase_trace": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t]),
+    "hawk_tree_layout": (C.c_int, [C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hawk_verify_tree": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.c_void_p]),
     "hawk_get_tree_logits": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int]),
@@ -172,6 +173,17 @@ def multi_verify(p_logits, q_logits, cand, u_acc, u_final, temperature: float, t
     if rc != 0:
         raise HawkError(rc, "hawk_multi_verify")
     return (idx, tok, resid) if want_resid else (idx, tok)
+
+
+def tree_layout(m_depth):
+    """hawk_tree_layout: (parent, depth, candidate, ancestors) arrays of the candidate tree's nodes."""
+    md = _i32(m_depth)
+    parent, depth, cand = (np.zeros(64, dtype=np.int32) for _ in range(3))
+    anc = np.zeros(64, dtype=np.uint64)
+    n = load_library().hawk_tree_layout(len(md), _p(md), _p(parent), _p(depth), _p(cand), _p(anc))
+    if n < 0:
+        raise HawkError(-1, "hawk_tree_layout", "bad tree shape")
+    return parent[:n], depth[:n], cand[:n], anc[:n]
 
 
 def _stream_of(t):

@@ -104,6 +104,29 @@ def test_spec_cache_layout_holds_every_outstanding_prediction(H):
     assert H.spec_cache_bytes(0, 2, 8) == 0 and H.spec_cache_bytes(4, 17, 8) == 0
 
 
+def test_tree_layout_is_the_cartesian_product(H):
+    # host logic of tree verification (Method, "Spatial Sampling Pool": the candidate tree as a Cartesian
+    # product): node order, parents, candidate indices and ancestor masks against the oracle's plain
+    # enumeration of the product
+    from oracle import tree
+    for m_depth in ((3,), (2, 3), (3, 3), (5, 2), (2, 2, 1), (1, 1, 1, 1, 1, 1, 1, 1), (4, 2, 3), (63,), (2, 5)):
+        parent, depth, cand, anc = H.tree_layout(m_depth)
+        nodes = tree.tree_nodes(m_depth)
+        assert len(parent) == len(nodes)
+        index = {p: i for i, p in enumerate(nodes)}
+        for i, path in enumerate(nodes):
+            assert depth[i] == len(path)
+            assert parent[i] == (index[path[:-1]] if path else -1)
+            assert cand[i] == (path[-1] if path else -1)
+            want = 0
+            for j in range(len(path)):
+                want |= 1 << index[path[:j]]
+            assert int(anc[i]) == want
+    for bad in ((), (0,), (64,), (8, 8), (1,) * 9):
+        with pytest.raises(H.HawkError):
+            H.tree_layout(bad)
+
+
 def test_spatial_entry_points_reject_bad_arguments_before_any_launch(H):
     L = H.load_library()
     one = C.c_void_p(4096)   # never dereferenced: every call below fails validation first
