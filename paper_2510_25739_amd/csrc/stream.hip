@@ -1126,8 +1126,8 @@ __device__ __forceinline__ void attn_phase(const SP& p, const Lds& s, Barrier& b
 
 // ------------------------------------------------------------------------- the kernel
 
-// TREE: the rows are the nodes of a candidate tree (two rows per attention job).
-template <int TPS_D, int TPS_M, int KREG_D, int RSMAX, bool TREE = false>
+// TREE: the rows are the nodes of a candidate tree, TRPJ of them per attention job.
+template <int TPS_D, int TPS_M, int KREG_D, int RSMAX, bool TREE = false, int TRPJ = 2>
 __global__ __launch_bounds__(kThreads, 1) void verify_stream_kernel(SP p) {
     extern __shared__ uint4 smem_raw[];
     Lds s;
@@ -1147,7 +1147,7 @@ __global__ __launch_bounds__(kThreads, 1) void verify_stream_kernel(SP p) {
     for (int l = 0; l < p.L; ++l) {
         gemv_phase<K_A, TPS_D, NSS, 8, KREG_D, 0, TREE>(p, s, bar, l, 0, plane(p, l, p.o_xh), plane(p, l, p.o_xl),
                                                         slot(p, l) + p.o_ssx, p.d, p.Kpd, resid);
-        attn_phase<TREE ? 2 : 1, TREE>(p, s, bar, l);
+        attn_phase<TREE ? TRPJ : 1, TREE>(p, s, bar, l);
         gemv_phase<K_C, TPS_D, 0, 8, KREG_D>(p, s, bar, l, 0, plane(p, l, p.o_oh), plane(p, l, p.o_ol), nullptr, p.d,
                                              p.Kpd, resid);
         gemv_phase<K_D, TPS_D, NSS, 8, KREG_D>(p, s, bar, l, 0, plane(p, l, p.o_x2h), plane(p, l, p.o_x2l),
@@ -1634,11 +1634,17 @@ int launch_verify_stream_tree(hawk_ctx* c, int n_nodes, const int32_t* tree_dept
     fill_params(c, p, c->S * n_nodes);
     p.logit_s = wsp<float>(c, c->off.logit_s);
     p.RS = n_nodes;
-    p.NC = 1; p.RPJ = 2; p.NRG = (n_nodes + 1) / 2;
+    // one row per attention job while the jobs of the heads that share an XCD fit its workgroups, else two
+    const int heads_per_xcd = (c->S * c->H + kXcd - 1) / kXcd;
+    const bool single = heads_per_xcd * n_nodes <= kPerXcd;
+    p.NC = 1; p.RPJ = single ? 1 : 2; p.NRG = single ? n_nodes : (n_nodes + 1) / 2;
     p.tdepth = tree_depth;
     p.tanc = reinterpret_cast<const u64*>(tree_anc);
-    const void* kern = c->d == 1280 ? reinterpret_cast<const void*>(verify_stream_kernel<10, 9, 5, 6, true>)
-                                    : reinterpret_cast<const void*>(verify_stream_kernel<6, 4, 3, 6, true>);
+    const void* kern =
+        c->d == 1280 ? (single ? reinterpret_cast<const void*>(verify_stream_kernel<10, 9, 5, 6, true, 1>)
+                               : reinterpret_cast<const void*>(verify_stream_kernel<10, 9, 5, 6, true, 2>))
+                     : (single ? reinterpret_cast<const void*>(verify_stream_kernel<6, 4, 3, 6, true, 1>)
+                               : reinterpret_cast<const void*>(verify_stream_kernel<6, 4, 3, 6, true, 2>));
     return launch_coop(c, kern, p, 1u + 5u * (unsigned)c->L);
 }
 

@@ -205,11 +205,12 @@ def test_tree_step_two_prompts_fp32(H):
     assert len(seen) > 1
 
 
-@pytest.mark.parametrize("path,m_depth", [(1, (3, 3)), (0, (3, 3)), (1, (5, 2)), (1, (2, 2, 1))])
+@pytest.mark.parametrize("path,m_depth", [(1, (3, 3)), (0, (3, 3)), (1, (5, 2)), (1, (2, 2, 1)), (1, (2, 2)), (1, (4, 1))])
 def test_tree_steps_bf16(H, path, m_depth):
     # the XL shape at four layers: node logits within tolerance, the walk exact on the GPU's own rows,
     # and the ordinary steps in between stay within tolerance (keys and values of the accepted path in place);
-    # on the persistent kernel (trees of up to 16 rows) and with one kernel per operation
+    # on the persistent kernel (trees of up to 16 rows; one row per attention job up to 10 rows, two beyond)
+    # and with one kernel per operation
     s = synth.CONFIGS[2].replace(n_layers=4)
     hk, orc, E = start(H, s, k_max=15, path=path)
     if hk.grid()[0, 0] != orc.grid()[0, 0]:
