@@ -234,8 +234,10 @@ def test_tree_steps_bf16(H, path, m_depth):
     assert max(accs) >= 1
 
 
-def test_tree_steps_with_guidance_bf16(H):
-    # the XL shape at four layers with guidance 4.0 (the batched configuration's scale), one prompt
+@pytest.mark.parametrize("m_depth,path", [((3, 3), 0), ((2, 2), 1)])
+def test_tree_steps_with_guidance_bf16(H, m_depth, path):
+    # the XL shape at four layers with guidance 4.0 (the batched configuration's scale), one prompt: 26 rows
+    # per pass run one kernel per operation, 14 rows (two streams of a 7-node tree) on the persistent kernel
     s = synth.CONFIGS[3].replace(n_layers=4, batch=1)
     hk, orc, E = start(H, s, k_max=12)
     if hk.grid()[0, 0] != orc.grid()[0, 0]:
@@ -243,7 +245,8 @@ def test_tree_steps_with_guidance_bf16(H):
     rng = np.random.Generator(np.random.PCG64(12))
     worst, accs = 0.0, []
     for step in range(4):
-        r = tree_step(H, hk, orc, E, s, (3, 3), rng, s.temperature, s.top_k)
+        r = tree_step(H, hk, orc, E, s, m_depth, rng, s.temperature, s.top_k)
+        assert hk.last_path() == path
         a = r["acc"][0]
         accs.append(a)
         orc.force(r["n_before"], r["toks"][:, :a + 1])
