@@ -96,6 +96,19 @@ def tree_step(H, hk, orc, E, s, m_depth, rng, T, K):
     return out
 
 
+def force_rows(obj, grid, n0, rows):
+    """Forces prompt b onto the tokens rows[b] from position n0[b]; the forced call takes one count for all
+    prompts, so the shorter ones start further back and feed tokens that are committed already."""
+    cnt = max(len(r) for r in rows)
+    begin, data = [], []
+    for b, own in enumerate(rows):
+        pad = cnt - len(own)
+        begin.append(int(n0[b]) - pad)
+        data.append([int(t) for t in grid[b, n0[b] - pad:n0[b]]] + [int(t) for t in own])
+    assert min(begin) >= 1
+    obj.force(np.array(begin, dtype=np.int32), np.array(data, dtype=np.int32))
+
+
 def chain_step(hk, orc, s, k, rng, exact):
     """An ordinary draft + verify step on both sides; returns the largest logit error."""
     B = hk.batch
@@ -113,8 +126,7 @@ def chain_step(hk, orc, s, k, rng, exact):
         np.testing.assert_array_equal(na_g, na_o)
         np.testing.assert_array_equal(t_g, t_o)
     elif not (np.array_equal(na_g, na_o) and np.array_equal(t_g, t_o)):
-        n0 = orc.n() - (na_o + 1)
-        hk.force(n0, np.stack([t_o[b, :na_o[b] + 1] for b in range(B)]))
+        force_rows(hk, orc.grid(), orc.n() - (na_o + 1), [t_o[b, :na_o[b] + 1] for b in range(B)])
     return err
 
 
@@ -187,22 +199,33 @@ def test_tree_step_two_prompts_fp32(H):
         r = tree_step(H, hk, orc, E, s, (3, 3), rng, s.temperature, s.top_k)
         assert r["err"] < 1e-4 and r["same"]
         seen.update(r["acc"])
-        # prompts accept different numbers of candidates and the oracle's forced call takes one count:
-        # the shorter ones start further back and feed tokens that are committed already
-        n0, g0 = r["n_before"], orc.grid()
-        cnt = max(r["acc"]) + 1
-        rows, begin = [], []
-        for bb in range(2):
-            own = list(r["toks"][bb, :r["acc"][bb] + 1])
-            pad = cnt - len(own)
-            begin.append(n0[bb] - pad)
-            rows.append(list(g0[bb, n0[bb] - pad:n0[bb]]) + own)
-        assert min(begin) >= 1
-        orc.force(np.array(begin, dtype=np.int32), np.array(rows, dtype=np.int32))
-        np.testing.assert_array_equal(hk.n(), orc.n())
+        # prompts accept different numbers of candidates
+        force_rows(orc, orc.grid(), r["n_before"], [r["toks"][bb, :r["acc"][bb] + 1] for bb in range(2)])
         same_committed(hk, orc)
         chain_step(hk, orc, s, s.k, rng, exact=True)
     assert len(seen) > 1
+
+
+def test_tree_step_two_prompts_bf16(H):
+    # two prompts, 7-node trees: 14 rows on the persistent kernel
+    s = synth.CONFIGS[2].replace(n_layers=4)
+    hk, orc, E = start(H, s, k_max=12, batch=2)
+    if not np.array_equal(hk.grid()[:, 0], orc.grid()[:, 0]):
+        pytest.skip("token 0 differs in bf16 for this seed")
+    rng = np.random.Generator(np.random.PCG64(22))
+    worst = chain_step(hk, orc, s, s.k, rng, exact=False)
+    same_committed(hk, orc)
+    seen = set()
+    for _ in range(4):
+        r = tree_step(H, hk, orc, E, s, (2, 2), rng, s.temperature, s.top_k)
+        assert hk.last_path() == 1
+        seen.update(r["acc"])
+        force_rows(orc, orc.grid(), r["n_before"], [r["toks"][bb, :r["acc"][bb] + 1] for bb in range(2)])
+        same_committed(hk, orc)
+        worst = max(worst, r["err"], chain_step(hk, orc, s, s.k, rng, exact=False))
+        same_committed(hk, orc)
+    print(f"max-abs logit error {worst:.2e}, accepted counts seen {sorted(seen)}")
+    assert worst < 2e-2
 
 
 @pytest.mark.parametrize("path,m_depth", [(1, (3, 3)), (0, (3, 3)), (1, (5, 2)), (1, (2, 2, 1)), (1, (2, 2)), (1, (4, 1))])
