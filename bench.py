@@ -190,6 +190,9 @@ def main():
     if s.batch == 1:   # one prompt (with its unconditional stream under guidance)
         from paper_2510_25739_amd.tree_timing import bench_tree
         out["tree_verify"] = bench_tree(H, s, blob, cond, uncond=unc)
+    if s.batch == 1 and not s.use_cfg:   # heads -> cache -> pool -> candidates -> tree step over one image
+        from paper_2510_25739_amd.scheme_timing import bench_scheme
+        out["whole_scheme"] = bench_scheme(H, s, blob, cond)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(s, blob, cond, unc)
     print(json.dumps(out))
