@@ -11,11 +11,32 @@ What is fixed outside the oracle:
     t - delta * IW with depth delta, checked against a scan of the whole history of predictions
     that is written here, not taken from the oracle.
 """
+import json
+import os
+
 import numpy as np
 import pytest
 import torch
 
+import synth
 from oracle import spatial
+
+GOLDEN = json.load(open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_values.json")))
+
+
+def test_paper_values_fix_the_head_shape_and_the_cache_size():
+    # the 134 MB the appendix quotes are four d x d fp16 matrices at the 7B model's hidden size: heads
+    # without output layers of their own (the reading the head oracle and kernels follow)
+    s = synth.CONFIGS[4]
+    h, wh, wo = synth.make_spatial_heads(0, 1, 4, 64, 16)
+    assert wh.shape == (4, 64, 64) and wh.dtype == np.uint16        # one square matrix per head, 2 bytes a weight
+    head_bytes = 4 * s.d_model * s.d_model * 2
+    assert abs(head_bytes / 1e6 - GOLDEN["draft_heads_fp16_megabytes"]["value"]) < 0.5
+    assert 4 * s.d_model * s.d_model / s.n_params() < GOLDEN["draft_heads_fraction_of_base_model_below"]["value"]
+    # a head with an output layer of its own would be far beyond both figures
+    assert (4 * (s.d_model * s.d_model + s.vocab * s.d_model)) * 2 / 1e6 > 10 * GOLDEN["draft_heads_fp16_megabytes"]["value"]
+    for IW, VSD, entries in GOLDEN["speculation_cache_entries"]["examples"]:
+        assert spatial.cache_entries(IW, VSD) == entries
 
 
 def test_head_special_weights():
