@@ -234,10 +234,13 @@ int hawk_phase_trace(hawk_ctx* ctx, int enable, uint64_t* out, size_t n_words);
  * the hidden state for the next draft are committed as by hawk_verify.
  * out_n_accept (host, may be NULL) [batch]: candidates accepted (-1: prompt finished before the
  * call); out_tokens (host, may be NULL) [batch][D + 1]: the accepted + 1 tokens emitted (vocabulary
- * ids), -1 beyond.  Runs one kernel per operation (not the persistent kernel).  With classifier-free
- * guidance both streams of a prompt go through the pass with the same tree and every target row
- * is the guided combination, as in hawk_verify.  Synchronises the stream several times (the walk is
- * driven from the host).  hawk_get_tree_logits: the (guided) rows of the last tree pass, out (host)
+ * ids), -1 beyond.  Passes of at most 16 rows in all (sequences x nodes) of the shapes the
+ * persistent kernel takes run on it, compiled with tree rows; larger ones run one kernel per
+ * operation (hawk_last_path tells which).  With classifier-free guidance both streams of a prompt
+ * go through the pass with the same tree and every target row is the guided combination, as in
+ * hawk_verify.  The walk runs on the device; the call synchronises the stream twice (reading the
+ * prompts' positions before, the results after).  depth x m_max <= 512.
+ * hawk_get_tree_logits: the (guided) rows of the last tree pass, out (host)
  * [batch][n_nodes][V_s]. */
 /* The order hawk_verify_tree gives the tree's nodes (host arithmetic only, all pointers host, each
  * out array may be NULL, room for 64 entries): node 0 is the root; then depth by depth every
