@@ -368,11 +368,17 @@ static void launch_tiles(hipStream_t stream, const uint16_t* hi, const uint16_t*
                                                                   swiglu_m);                            \
     } while (0)
     if (M <= 16 && K % 128 == 0) {   // a sliver of rows: barrier-free weight streaming, one wave per K quarter
-        if ((long)(N / 32) >= (long)cus) {
-            gemv_mfma_kernel<2, 8><<<(N + 31) / 32, 256, 0, stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc, ohi, olo, swiglu_m);
-        } else {
-            gemv_mfma_kernel<1, 8><<<(N + 15) / 16, 256, 0, stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc, ohi, olo, swiglu_m);
-        }
+        // Strips per workgroup and k-steps in flight, from timings over weights that do not fit the
+        // last-level cache (7B and XL shapes, 12 rows): 64 features per workgroup when that gives one
+        // round of workgroups over most of the chip, 32 when there are enough strips to fill it,
+        // else 16 with a deeper ring (a shallower one again for long K).
+#define HAWK_GEMV(SR, D) gemv_mfma_kernel<SR, D><<<(N + 16 * SR - 1) / (16 * SR), 256, 0, stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc, ohi, olo, swiglu_m)
+        const long s64 = N / 64, s32 = N / 32;
+        if (4 * s64 >= 3 * (long)cus && s64 <= (long)cus) HAWK_GEMV(4, 3);
+        else if (5 * s32 >= 3 * (long)cus) HAWK_GEMV(2, 6);
+        else if (K / 128 <= 32) HAWK_GEMV(1, 12);
+        else HAWK_GEMV(1, 8);
+#undef HAWK_GEMV
         return;
     }
     if (tiles(32, 32) <= cus) HAWK_GEMM_TILE(1, 1, 4);
