@@ -517,31 +517,30 @@ struct FastShared {
     unsigned tot[256];
     alignas(16) unsigned cand_rel[kCand];
     int cand_idx[kCand];
+    unsigned cand_rank[kCand];   // candidates that come before each one (see rank_candidates)
     unsigned cand_n;
     Shared sh;
 };
 
-// Number of gathered candidates that come before candidate i (larger key first, lower index
-// first among equal keys).  Whole waves call this (i = threadIdx.x, also for i >= cnt): each
-// lane loads one candidate per group of 64 and the wave walks them with lane broadcasts, so the
-// loop has no LDS latency in it.
-__device__ __forceinline__ unsigned cand_rank(const FastShared& fs, unsigned i, unsigned cnt) {
-    const unsigned lane = threadIdx.x & 63u;
-    const unsigned mine = i < cnt ? fs.cand_rel[i] : 0u;
-    const int mi = i < cnt ? fs.cand_idx[i] : 0x7FFFFFFF;
-    unsigned rank = 0u;
-    for (unsigned g = 0; g * 64u < cnt; ++g) {
-        const bool on = g * 64u + lane < cnt;
-        const unsigned kj = on ? fs.cand_rel[g * 64u + lane] : 0u;
-        const int ij = on ? fs.cand_idx[g * 64u + lane] : 0x7FFFFFFF;
-        const unsigned lim = min(64u, cnt - g * 64u);
-        for (unsigned j = 0; j < lim; ++j) {
-            const unsigned r = (unsigned)__builtin_amdgcn_readlane((int)kj, (int)j);
-            const int ix = __builtin_amdgcn_readlane(ij, (int)j);
-            rank += (r > mine || (r == mine && ix < mi)) ? 1u : 0u;
+// Ranks of all gathered candidates at once (fs.cand_rank[i] = candidates that come before candidate
+// i - larger key first, lower index first among equal keys -, zeroed by the caller): the cnt x cnt comparisons are spread over the block - NT / cnt threads share a
+// candidate, each compares it with a slice of the list and adds its count with one LDS atomic -
+// instead of one wave walking the whole list per 64 candidates.  All threads call; ends with a barrier.
+__device__ __forceinline__ void rank_candidates(FastShared& fs, unsigned cnt) {
+    const unsigned per = max(1u, (unsigned)NT / cnt), len = (cnt + per - 1u) / per;
+    const unsigned i = threadIdx.x % cnt, c = threadIdx.x / cnt;
+    if (c < per) {
+        const unsigned mine = fs.cand_rel[i];
+        const int mi = fs.cand_idx[i];
+        const unsigned j1 = min(cnt, (c + 1u) * len);
+        unsigned part = 0u;
+        for (unsigned j = c * len; j < j1; ++j) {
+            const unsigned r = fs.cand_rel[j];
+            part += (r > mine || (r == mine && fs.cand_idx[j] < mi)) ? 1u : 0u;
         }
+        if (part) atomicAdd(&fs.cand_rank[i], part);
     }
-    return rank;
+    __syncthreads();
 }
 
 // Inverse of fkey (the key of -0 maps back to +0).
@@ -584,7 +583,7 @@ __device__ __forceinline__ void load_row(const float* lc, const float* lu, float
 // and tie cut, maximum.  The weights themselves come from dense_weights or from a CompactList.
 // *kmask: bit e set iff the thread's entry e is kept (not set in the greedy case).
 template <int E>
-__device__ WarpStat warp_select(const float (&z)[E], int n, int top_k, int greedy, FastShared& fs, unsigned* kmask) {
+__device__ __forceinline__ WarpStat warp_select(const float (&z)[E], int n, int top_k, int greedy, FastShared& fs, unsigned* kmask) {
     Shared& sh = fs.sh;
     const int base = threadIdx.x * E, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     WarpStat st;
@@ -675,6 +674,7 @@ __device__ WarpStat warp_select(const float (&z)[E], int n, int top_k, int greed
                 const unsigned bin = sh.b_prefix, want = sh.b_remaining, cnt = sh.b_count_eq;
                 if (cnt > (unsigned)kCand) { lin = false; continue; }  // same digit again, on the keys
                 if (threadIdx.x == 0) fs.cand_n = 0u;
+                if (threadIdx.x < (unsigned)kCand) fs.cand_rank[threadIdx.x] = 0u;
                 __syncthreads();
 #pragma unroll
                 for (int e = 0; e < E; ++e)
@@ -683,10 +683,8 @@ __device__ WarpStat warp_select(const float (&z)[E], int n, int top_k, int greed
                         if (at < (unsigned)kCand) { fs.cand_rel[at] = rel[e]; fs.cand_idx[at] = base + e; }
                     }
                 __syncthreads();
-                if ((threadIdx.x & ~63u) < cnt) {  // whole waves
-                    const unsigned rank = cand_rank(fs, threadIdx.x, cnt);
-                    if (threadIdx.x < cnt && rank + 1u == want) { sh.b_prefix = fs.cand_rel[threadIdx.x]; sh.b_int = fs.cand_idx[threadIdx.x]; }
-                }
+                rank_candidates(fs, cnt);
+                if (threadIdx.x < cnt && fs.cand_rank[threadIdx.x] + 1u == want) { sh.b_prefix = fs.cand_rel[threadIdx.x]; sh.b_int = fs.cand_idx[threadIdx.x]; }
                 __syncthreads();
                 prefix = sh.b_prefix;
                 ranked_cut = sh.b_int;
@@ -701,6 +699,7 @@ __device__ WarpStat warp_select(const float (&z)[E], int n, int top_k, int greed
                 // directly (larger value first, lower index first among equals); the entry of
                 // rank `remaining` is the threshold and the tie cut in one.
                 if (threadIdx.x == 0) fs.cand_n = 0u;
+                if (threadIdx.x < (unsigned)kCand) fs.cand_rank[threadIdx.x] = 0u;
                 __syncthreads();
 #pragma unroll
                 for (int e = 0; e < E; ++e)
@@ -709,10 +708,8 @@ __device__ WarpStat warp_select(const float (&z)[E], int n, int top_k, int greed
                         if (at < (unsigned)kCand) { fs.cand_rel[at] = rel[e]; fs.cand_idx[at] = base + e; }
                     }
                 __syncthreads();
-                if ((threadIdx.x & ~63u) < count_eq) {  // whole waves
-                    const unsigned rank = cand_rank(fs, threadIdx.x, count_eq);
-                    if (threadIdx.x < count_eq && rank + 1u == remaining) { sh.b_prefix = fs.cand_rel[threadIdx.x]; sh.b_int = fs.cand_idx[threadIdx.x]; }
-                }
+                rank_candidates(fs, count_eq);
+                if (threadIdx.x < count_eq && fs.cand_rank[threadIdx.x] + 1u == remaining) { sh.b_prefix = fs.cand_rel[threadIdx.x]; sh.b_int = fs.cand_idx[threadIdx.x]; }
                 __syncthreads();
                 prefix = sh.b_prefix;
                 ranked_cut = sh.b_int;
