@@ -4,15 +4,15 @@ image by image, with every intermediate staying in device memory.
 
 What is checked: at temperature 0 the image must be the token-by-token arg-max image whatever the
 heads propose (random head weights; in a second run the horizontal proposal is replaced by the
-reference's token, which makes the walk go to full depth every step); and at every step the pools
-the cache hands out are, bit for bit, what the oracle's dictionary cache holds for those positions
-when it is fed the same rows.
+reference's token, which makes the walk go to full depth every step); and at every step the rows
+the cache hands out are, bit for bit, the rows that were pushed for those positions and depths
+(a dictionary kept by the test: a check of where rows go - what the rows hold is checked against the
+oracle in the tests of the heads), with the member counts and order the definition of the pool gives.
 """
 import numpy as np
 import pytest
 
 import synth
-from oracle import spatial
 
 pytestmark = pytest.mark.gpu
 
@@ -45,7 +45,7 @@ def test_whole_scheme_greedy_image(H, perfect_horizontal):
 
     hk.prefill(cond, None, IH, IW, 0.0, s.top_k, 1.0, uni(1))
     cache = H.SpecCache(IW, IH, VSD, v_s)
-    mirror = spatial.SpecCache(IW, IH, VSD)
+    pushed = {}   # (position pointed to, depth) -> the row pushed for it
     # the hidden state that predicted position 0: the last condition row of the prefill
     h_rows, positions, n = hk.last_hidden(C)[C - 1:C].clone(), [0], 1
     accepted, steps = [], 0
@@ -53,7 +53,8 @@ def test_whole_scheme_greedy_image(H, perfect_horizontal):
         q_all = H.spatial_heads(h_rows.contiguous(), Wh, Wo)                      # [rows, heads, V_s]: heads 0..HD-1 horizontal
         cache.push(dev(np.array(positions, np.int32)), q_all.view(-1)[HD * v_s:], n_heads * v_s)
         for i, T in enumerate(positions):
-            mirror.push(T, [q_all[i, HD + d].cpu().numpy() for d in range(VSD)])
+            for d in range(1, VSD + 1):
+                pushed[(T + d * IW, d)] = q_all[i, HD + d - 1].cpu().numpy()
         targets = [n - 1 + j for j in range(1, HD + 1)]                           # the positions the last row's horizontal heads point to
         q_h = q_all[-1, :HD].contiguous()
         if perfect_horizontal:
@@ -62,8 +63,8 @@ def test_whole_scheme_greedy_image(H, perfect_horizontal):
                 q_h[j, int(ref[0, t]) - s.samp_lo] = 50.0
         logits, m, delta = cache.pool(dev(np.array(targets, np.int32)), q_h.view(-1), v_s)
         m_host = [int(x) for x in m.cpu()]
-        for j, t in enumerate(targets):                                          # bit for bit what the dictionary cache holds
-            want = mirror.pool(t, q_h[j].cpu().numpy())
+        for j, t in enumerate(targets):                                          # bit for bit the rows pushed for t, nearest row first
+            want = [(dv, pushed[(t, dv)]) for dv in range(1, VSD + 1) if (t, dv) in pushed] + [(0, q_h[j].cpu().numpy())]
             assert m_host[j] == len(want) == min(VSD, t // IW) + 1
             assert delta[j].cpu().tolist() == [dv for dv, _ in want] + [-1] * (m_max - len(want))
             for i, (_, row) in enumerate(want):
