@@ -236,7 +236,7 @@ template <int SR, int D>
 __global__ __launch_bounds__(256) void gemv_mfma_kernel(const uint16_t* __restrict__ hi, const uint16_t* __restrict__ lo,
                                                         const uint16_t* __restrict__ W, int packed, int N, int K,
                                                         float* Y, int ldy, int M, int accumulate, uint16_t* ohi,
-                                                        uint16_t* olo, int om) {
+                                                        uint16_t* olo, int om, const float* resid) {
     __shared__ f32x4 red[3][SR][64];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r16 = lane & 15, kg = lane >> 4;
@@ -308,6 +308,23 @@ __global__ __launch_bounds__(256) void gemv_mfma_kernel(const uint16_t* __restri
                 swiglu_store(v, Y, ldy, ohi, olo, om, r16, n / 2);
                 continue;
             }
+            if (om < 0) {   // -om square blocks of K features (draft heads): g = a + silu(y) with a = resid[row],
+                            // stored as row (row * blocks + block) of Y ([M * blocks][K] fp32) and of the planes
+                const int nb = -om, j = n / K, f = n - j * K;
+                const float4 a = *reinterpret_cast<const float4*>(resid + (size_t)r16 * K + f);
+                const float g0 = a.x + v[0] / (1.0f + expf(-v[0])), g1 = a.y + v[1] / (1.0f + expf(-v[1]));
+                const float g2 = a.z + v[2] / (1.0f + expf(-v[2])), g3 = a.w + v[3] / (1.0f + expf(-v[3]));
+                const size_t at = ((size_t)r16 * nb + j) * K + f;
+                *reinterpret_cast<float4*>(Y + at) = make_float4(g0, g1, g2, g3);
+                unsigned h0, h1, h2, h3, l0, l1, l2, l3;
+                bf16_split(g0, h0, l0);
+                bf16_split(g1, h1, l1);
+                bf16_split(g2, h2, l2);
+                bf16_split(g3, h3, l3);
+                *reinterpret_cast<uint2*>(ohi + at) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+                *reinterpret_cast<uint2*>(olo + at) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+                continue;
+            }
             if (accumulate) {
                 const float4 old = *reinterpret_cast<const float4*>(dst);
                 v += (f32x4){old.x, old.y, old.z, old.w};
@@ -350,7 +367,8 @@ bool presplit_planes(hawk_ctx* c, size_t off_a, int M, int K, uint16_t** hi, uin
 
 // Tile choice and launch for Y (+)= A W^T with A given as its two bf16 planes.
 static void launch_tiles(hipStream_t stream, const uint16_t* hi, const uint16_t* lo, const uint16_t* W, int packed, int N,
-                         int K, float* Y, int ldy, int M, int acc, uint16_t* ohi, uint16_t* olo, int swiglu_m) {
+                         int K, float* Y, int ldy, int M, int acc, uint16_t* ohi, uint16_t* olo, int swiglu_m,
+                         const float* resid = nullptr) {
     // The smallest tile that still gives every compute unit at most one workgroup: with so few
     // rows the kernel is bound by what one compute unit can stage and feed per k-stage, so the
     // work is spread as widely as one round of workgroups allows; larger grids than that only
@@ -372,7 +390,7 @@ static void launch_tiles(hipStream_t stream, const uint16_t* hi, const uint16_t*
         // last-level cache (7B and XL shapes, 12 rows): 64 features per workgroup when that gives one
         // round of workgroups over most of the chip, 32 when there are enough strips to fill it,
         // else 16 with a deeper ring (a shallower one again for long K).
-#define HAWK_GEMV(SR, D) gemv_mfma_kernel<SR, D><<<(N + 16 * SR - 1) / (16 * SR), 256, 0, stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc, ohi, olo, swiglu_m)
+#define HAWK_GEMV(SR, D) gemv_mfma_kernel<SR, D><<<(N + 16 * SR - 1) / (16 * SR), 256, 0, stream>>>(hi, lo, W, packed, N, K, Y, ldy, M, acc, ohi, olo, swiglu_m, resid)
         const long s64 = N / 64, s32 = N / 32;
         if (4 * s64 >= 3 * (long)cus && s64 <= (long)cus) HAWK_GEMV(4, 3);
         else if (5 * s32 >= 3 * (long)cus) HAWK_GEMV(2, 6);
@@ -438,6 +456,16 @@ bool gemm_rows_bf16(hipStream_t stream, const float* A, int lda, int M, int K, c
         split_rows_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, stream>>>(A, lda, K, hi, lo, total4);
     }
     launch_tiles(stream, hi, lo, W, 0, N, K, Y, ldy, M, 0, nullptr, nullptr, 0);
+    return true;
+}
+
+bool gemm_rows_heads(hipStream_t stream, const float* A, int M, int K, const uint16_t* W, int blocks, float* G,
+                     uint16_t* planes_a, uint16_t* planes_g) {
+    if (M < 1 || M > 16 || K % 128 || blocks < 1) return false;
+    const size_t total4 = (size_t)M * (K / 4);
+    split_rows_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, stream>>>(A, K, K, planes_a, planes_a + (size_t)M * K, total4);
+    launch_tiles(stream, planes_a, planes_a + (size_t)M * K, W, 0, blocks * K, K, G, K, M, 0, planes_g,
+                 planes_g + (size_t)M * blocks * K, -blocks, A);
     return true;
 }
 

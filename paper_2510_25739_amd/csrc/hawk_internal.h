@@ -157,6 +157,12 @@ bool launch_gemm_swiglu(hawk_ctx*, size_t off_a, int lda, size_t w13_off, int m,
 // (K % 64, N % 16, lda % 4, ldy % 4).
 bool gemm_rows_bf16(hipStream_t stream, const float* A, int lda, int M, int K, const uint16_t* W, int N, float* Y,
                     int ldy, uint16_t* planes);
+// The draft heads' blocks in one launch (at most 16 rows, K % 128 == 0): W holds `blocks` square
+// [K][K] matrices one after the other; G[(r * blocks + j)][K] = A[r] + silu(W_j A[r]) as fp32 and as
+// the two bf16 planes the product that follows reads (planes_g: 2 M blocks K values; planes_a: 2 M K).
+// false: shape not covered, the caller runs the product and the activation separately.
+bool gemm_rows_heads(hipStream_t stream, const float* A, int M, int K, const uint16_t* W, int blocks, float* G,
+                     uint16_t* planes_a, uint16_t* planes_g);
 void launch_swiglu(hawk_ctx*, int M);
 void launch_draft_input(hawk_ctx*, int i);                     // [g | E[left] | E[up]]
 void launch_keep_hprev_prefill(hawk_ctx*);

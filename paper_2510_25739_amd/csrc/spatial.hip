@@ -155,11 +155,14 @@ int launch_spatial_heads(const float* h, const uint16_t* W_heads, const uint16_t
     uint16_t* hplanes = reinterpret_cast<uint16_t*>(w);
     w += align_up(2 * (size_t)rows * d * 2);
     uint16_t* gplanes = reinterpret_cast<uint16_t*>(w);
-    // every head's linear layer in one product: Y[r][j d + f] = (W_j h_r)[f]
-    if (!gemm_rows_bf16(stream, h, d, rows, d, W_heads, n_heads * d, Y, n_heads * d, hplanes)) return HAWK_EINVAL;
-    const size_t total = (size_t)M * (d / 4);
-    head_act_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(h, Y, rows, n_heads, d, gplanes,
-                                                                        gplanes + (size_t)M * d, g_out);
+    // every head's linear layer in one product, Y[r][j d + f] = (W_j h_r)[f], with the residual and
+    // the activation in its epilogue where the shape allows (the workspace's Y then holds g)
+    if (!gemm_rows_heads(stream, h, rows, d, W_heads, n_heads, g_out ? g_out : Y, hplanes, gplanes)) {
+        if (!gemm_rows_bf16(stream, h, d, rows, d, W_heads, n_heads * d, Y, n_heads * d, hplanes)) return HAWK_EINVAL;
+        const size_t total = (size_t)M * (d / 4);
+        head_act_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(h, Y, rows, n_heads, d, gplanes,
+                                                                            gplanes + (size_t)M * d, g_out);
+    }
     // the shared output layer over all (row, head) pairs
     if (!gemm_rows_bf16(stream, nullptr, d, M, d, W_out, Vs, q_logits, Vs, gplanes)) return HAWK_EINVAL;
     return hipGetLastError() == hipSuccess ? HAWK_OK : HAWK_EDEVICE;
