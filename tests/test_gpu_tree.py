@@ -173,6 +173,25 @@ def test_tree_steps_fp32_exact(H, m_depth):
     assert max(accs) >= min(2, len(m_depth)) and min(accs) == 0
 
 
+@pytest.mark.parametrize("m_depth", [(63,), (1,) * 8, (7, 7), (3, 3, 3)])
+def test_tree_extreme_shapes_fp32_exact(H, m_depth):
+    # the largest tree (64 nodes: 63 candidates at one depth), the deepest (8 depths), 57 and 40 nodes
+    s = synth.CONFIGS[0].replace(top_k=64, grid_h=12, grid_w=12)
+    hk, orc, E = start(H, s, k_max=63)
+    np.testing.assert_array_equal(hk.grid()[:, 0], orc.grid()[:, 0])
+    rng = np.random.Generator(np.random.PCG64(len(m_depth) * 100 + m_depth[0]))
+    accs = []
+    for _ in range(3):
+        if orc.n()[0] + n_nodes_of(m_depth) > s.n_img:
+            break
+        r = tree_step(H, hk, orc, E, s, m_depth, rng, s.temperature, s.top_k)
+        assert r["err"] < 1e-4 and r["same"]
+        accs.append(r["acc"][0])
+        chain_step(hk, orc, s, s.k, rng, exact=True)
+    print("accepted per tree step:", accs)
+    assert len(accs) >= 2
+
+
 def test_tree_steps_with_guidance_fp32_exact(H):
     # classifier-free guidance: both streams go through the tree pass, every target row is guided
     s = synth.CONFIGS[0].replace(top_k=64, cfg_scale=2.0)
