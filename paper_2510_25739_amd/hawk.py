@@ -264,7 +264,7 @@ class SpecCache:
                 and q_horiz.numel() >= (n - 1) * horiz_stride + self.v_s):
             raise HawkError(-1, "hawk_spec_pool", "bad arguments")
         dev = self.mem.device
-        logits = torch.zeros((n, self.VSD + 1, self.v_s), dtype=torch.float32, device=dev)
+        logits = torch.empty((n, self.VSD + 1, self.v_s), dtype=torch.float32, device=dev)   # rows beyond the count stay unwritten
         m = torch.empty(n, dtype=torch.int32, device=dev)
         delta = torch.empty((n, self.VSD + 1), dtype=torch.int32, device=dev)
         rc = self._L.hawk_spec_pool(self.mem.data_ptr(), self.IW, self.IH, self.VSD, self.v_s, target.data_ptr(),
