@@ -156,3 +156,22 @@ def test_emitted_tokens_follow_the_autoregressive_law():
     first = counts.sum(axis=(1, 2))
     p0 = soft(tab.logits(()))
     assert ((first - samples * p0) ** 2 / (samples * p0)).sum() < 16.27
+
+
+def test_guidance_routine_is_the_formula_of_the_guided_rows():
+    # the routine the tree oracle combines two streams with (Experiment, "Model and Benchmark": guidance
+    # scale): lu + s (lc - lu), against the formula in fp64 and its special cases
+    rng = np.random.default_rng(9)
+    lc = (rng.standard_normal(4096) * 3).astype(np.float32)
+    lu = (rng.standard_normal(4096) * 3).astype(np.float32)
+    for scale in (3.0, 4.0, 1.5):
+        out = oracle.guide(lc, lu, scale)
+        ref = lu.astype(np.float64) + scale * (lc.astype(np.float64) - lu.astype(np.float64))
+        assert out.dtype == np.float32
+        np.testing.assert_allclose(out, ref, rtol=3e-7, atol=1e-6)   # one rounding of the difference, one of the result
+    np.testing.assert_array_equal(oracle.guide(lc, lu, 0.0), lu)       # scale 0: the unconditional stream
+    np.testing.assert_array_equal(oracle.guide(lc, lc, 3.0), lc)       # equal streams: unchanged
+    # scale 1 gives back the conditional stream up to the rounding of the difference
+    np.testing.assert_allclose(oracle.guide(lc, lu, 1.0), lc, rtol=0, atol=1e-6)
+    # the direction matters: a larger scale moves further from the unconditional stream
+    assert np.all(np.abs(oracle.guide(lc, lu, 4.0) - lu) >= np.abs(oracle.guide(lc, lu, 2.0) - lu) - 1e-6)
