@@ -278,7 +278,8 @@ int hawk_last_hidden(hawk_ctx* ctx, const void** device_ptr, int* elem_bytes);
  * warp = temperature and top-k as in hawk_prefill (temperature 0 or top_k 1: point mass on the
  * arg-max); probabilities and sums in fp64.
  * All pointers are DEVICE pointers, rows contiguous: p_logits [rows][n] fp32, q_logits
- * [rows][m][n] fp32, cand [rows][m] (0 <= token < n), u_acc [rows][m] and u_final [rows] in
+ * [rows][m][n] fp32, cand [rows][m] (0 <= token < n; a value outside that range is rejected like a
+ * token without target mass and nothing is read through it), u_acc [rows][m] and u_final [rows] in
  * [0, 1), out_index [rows] (0-based index of the accepted candidate, m if none), out_token
  * [rows], out_resid (may be NULL) [rows][m] fp64: the residual mass sum_x max(0, p^(i) - q_i)
  * = 1 - acceptance probability of every evaluated step, -1 for steps after an acceptance.

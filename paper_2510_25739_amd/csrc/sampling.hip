@@ -1120,7 +1120,9 @@ __global__ __launch_bounds__(NT) void multi_verify_list_kernel(const float* p_lo
             if (i0 + e < Kq) sq += exp((double)qz[i0 + e] - (double)qs.zmax);
         if (threadIdx.x == 0) pick = 0.0;   // p^(i)(s) if s has no mass left
         qs.total = block_sum_d(sq, fs.sh);
-        const int s = cand[(size_t)row * m + i];
+        const int s_in = cand[(size_t)row * m + i];
+        const bool s_ok = (unsigned)s_in < (unsigned)n;   // a token outside the slice is rejected, never read
+        const int s = s_ok ? s_in : 0;
         double res[2], rs = 0.0;
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
@@ -1135,7 +1137,7 @@ __global__ __launch_bounds__(NT) void multi_verify_list_kernel(const float* p_lo
             }
         }
         const double R = block_sum_d(rs, fs.sh);   // its barriers also publish pick
-        const double pd = pick, qd = weight_of(qs, qrow, inv_t, s) / qs.total;
+        const double pd = s_ok ? pick : 0.0, qd = s_ok ? weight_of(qs, qrow, inv_t, s) / qs.total : 1.0;
         if (out_resid && threadIdx.x == 0) out_resid[(size_t)row * m + i] = R;
         if ((double)u_acc[(size_t)row * m + i] * qd < pd) {
             acc = i;
@@ -1160,7 +1162,7 @@ __global__ __launch_bounds__(NT) void multi_verify_list_kernel(const float* p_lo
         out_index[row] = acc;
         out_token[row] = tok;
         if (out_resid)
-            for (int i = acc + 1; i < m; ++i) out_resid[(size_t)row * m + i] = -1.0;
+            for (int i = (acc == mr ? mr : acc + 1); i < m; ++i) out_resid[(size_t)row * m + i] = -1.0;   // steps not evaluated
     }
 }
 
@@ -1206,7 +1208,9 @@ __global__ __launch_bounds__(NT) void multi_verify_walk_kernel(const float* p_lo
     for (int i = 0; i < mr; ++i) {
         const float* qrow = q_logits + ((size_t)row * m + i) * n;
         const WarpStat qs = stats[(size_t)row * (m + 1) + 1 + i];
-        const int s = cand[(size_t)row * m + i];
+        const int s_in = cand[(size_t)row * m + i];
+        const bool s_ok = (unsigned)s_in < (unsigned)n;   // a token outside the slice is rejected, never read
+        const int s = s_ok ? s_in : 0;
         if (threadIdx.x == 0) pick = 0.0;   // p^(i)(s) if s has no mass left
         __syncthreads();
         double res[2], rs = 0.0;
@@ -1223,7 +1227,7 @@ __global__ __launch_bounds__(NT) void multi_verify_walk_kernel(const float* p_lo
             }
         }
         const double R = block_sum_d(rs, sh);   // its barriers also publish pick
-        const double pd = pick, qd = weight_of(qs, qrow, inv_t, s) / qs.total;
+        const double pd = s_ok ? pick : 0.0, qd = s_ok ? weight_of(qs, qrow, inv_t, s) / qs.total : 1.0;
         __syncthreads();   // pick is rewritten at the top of the next round
         if (out_resid && threadIdx.x == 0) out_resid[(size_t)row * m + i] = R;
         if ((double)u_acc[(size_t)row * m + i] * qd < pd) {
@@ -1249,7 +1253,7 @@ __global__ __launch_bounds__(NT) void multi_verify_walk_kernel(const float* p_lo
         out_index[row] = acc;
         out_token[row] = tok;
         if (out_resid)
-            for (int i = acc + 1; i < m; ++i) out_resid[(size_t)row * m + i] = -1.0;
+            for (int i = (acc == mr ? mr : acc + 1); i < m; ++i) out_resid[(size_t)row * m + i] = -1.0;   // steps not evaluated
     }
 }
 
@@ -1273,6 +1277,10 @@ __global__ __launch_bounds__(NT) void multi_verify_kernel(const float* p_logits,
     for (int e = 0; e < E; ++e) p[e] /= ps.total;
     int acc = mr, tok = -1;
     for (int i = 0; i < mr; ++i) {
+        if (threadIdx.x == 0) {   // a candidate outside the slice has no owner: p = 0, q = 1 rejects it
+            pick[0] = 0.0;
+            pick[1] = 1.0;
+        }
         load_row<E>(q_logits + ((size_t)row * m + i) * n, nullptr, 0.f, inv_t, nullptr, n, z);
         WarpStat qs = warp_select<E>(z, n, top_k, greedy, fs, &km);
         double q[E];
@@ -1316,7 +1324,7 @@ __global__ __launch_bounds__(NT) void multi_verify_kernel(const float* p_logits,
         out_index[row] = acc;
         out_token[row] = tok;
         if (out_resid)
-            for (int i = acc + 1; i < m; ++i) out_resid[(size_t)row * m + i] = -1.0;
+            for (int i = (acc == mr ? mr : acc + 1); i < m; ++i) out_resid[(size_t)row * m + i] = -1.0;   // steps not evaluated
     }
 }
 

@@ -105,6 +105,63 @@ def test_multi_verify_edge_candidates(H):
     np.testing.assert_allclose(resid, o_res, rtol=1e-11, atol=1e-13)
 
 
+def test_short_pools_all_rejected_leave_no_unwritten_residual(H):
+    # positions with fewer candidates than m (a sampling pool near the top of the image) whose
+    # candidates are all rejected: every residual entry beyond the row's own count must read -1,
+    # whatever the output buffer held before; all three kernel forms
+    import torch
+    dev = "cuda:0"
+    for n, top_k in ((16384, 1000), (16384, 3000)):
+        rows, m = 12, 3
+        p, q, cand, u_acc, u_fin = make_rows(31 + top_k, rows, m, n, 1.0, top_k)
+        cand[:] = np.argmin(p, axis=1).astype(np.int32)[:, None]      # no target mass: always rejected
+        m_rows = np.array([r % (m + 1) for r in range(rows)], dtype=np.int32)
+        t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        args = (t(p), t(q), t(cand), t(u_acc), t(u_fin), 1.0, top_k)
+        for ws in (None, torch.empty(H.multi_verify_workspace_bytes(rows, m), dtype=torch.uint8, device=dev)):
+            junk = torch.full((rows, m), 7.0, dtype=torch.float64, device=dev)   # what torch.empty hands out next
+            del junk
+            idx, tok, resid = H.multi_verify(*args, want_resid=True, workspace=ws, m_rows=t(m_rows))
+            idx, tok, resid = idx.cpu().numpy(), tok.cpu().numpy(), resid.cpu().numpy()
+            for r in range(rows):
+                mr = int(m_rows[r])
+                if mr == 0:
+                    w, z = oracle.warp(p[r], 1.0, top_k)
+                    assert idx[r] == 0 and tok[r] == oracle.inv_cdf(w, z, float(u_fin[r]))
+                    assert (resid[r] == -1.0).all()
+                    continue
+                oi, ot, ores = oracle.multi_verify(p[r], q[r, :mr], cand[r, :mr], u_acc[r, :mr], float(u_fin[r]), 1.0,
+                                                   top_k, want_resid=True)
+                assert oi == mr and idx[r] == mr and tok[r] == ot
+                np.testing.assert_allclose(resid[r, :mr], ores, rtol=1e-11, atol=1e-13)
+                assert (resid[r, mr:] == -1.0).all(), (r, mr, resid[r])
+
+
+def test_candidates_outside_the_slice_are_rejected(H):
+    # a device-side candidate that is no token of the slice must not be read through: it is rejected,
+    # with the residual of an ordinary rejection (the residual does not depend on the candidate)
+    import torch
+    dev = "cuda:0"
+    for n, top_k in ((4096, 64), (16384, 3000)):
+        rows, m = 8, 2
+        p, q, cand, u_acc, u_fin = make_rows(91 + n, rows, m, n, 1.0, top_k)
+        ref_cand = cand.copy()
+        ref_cand[:, 0] = np.argmin(p, axis=1)          # what the oracle sees instead: a token without target mass
+        bad = cand.copy()
+        bad[0::2, 0] = n + 5
+        bad[1::2, 0] = -3
+        u_acc[:, 0] = 0.0                               # anything with mass would be accepted
+        t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        for ws in (None, torch.empty(H.multi_verify_workspace_bytes(rows, m), dtype=torch.uint8, device=dev)):
+            idx, tok, resid = H.multi_verify(t(p), t(q), t(bad), t(u_acc), t(u_fin), 1.0, top_k, want_resid=True, workspace=ws)
+            idx, tok, resid = idx.cpu().numpy(), tok.cpu().numpy(), resid.cpu().numpy()
+            for r in range(rows):
+                oi, ot, ores = oracle.multi_verify(p[r], q[r], ref_cand[r], u_acc[r], float(u_fin[r]), 1.0, top_k,
+                                                   want_resid=True)
+                assert oi >= 1 and idx[r] == oi and tok[r] == ot
+                np.testing.assert_allclose(resid[r], ores, rtol=1e-11, atol=1e-13)
+
+
 def test_multi_verify_rejects_bad_arguments(H):
     import torch
     L = H.load_library()
