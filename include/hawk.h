@@ -301,6 +301,19 @@ int hawk_multi_verify(const float* p_logits, const float* q_logits, const int32_
                       int32_t* out_index, int32_t* out_token, double* out_resid, void* workspace,
                       size_t workspace_bytes, void* stream);
 
+/* hawk_multi_verify for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation): the same operation, arguments, kernels and
+ * results as hawk_multi_verify with a workspace, but the rows' statistics are kept in a fixed array
+ * of 96 KiB that the library holds in device memory (one copy per GPU for the life of the process)
+ * instead of a caller-provided buffer.  Nothing is allocated or freed by the call.
+ * Limit: rows * (m + 1) <= 4096 logit rows per call; beyond it HAWK_ENOMEM is returned and nothing is
+ * launched.  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two threads) race and must be serialised by the caller; calls on one stream are ordered.
+ * Nothing in the array has to be cleared between calls.  Other return codes as hawk_multi_verify. */
+int hawk_multi_verify_static(const float* p_logits, const float* q_logits, const int32_t* cand, const float* u_acc,
+                             const float* u_final, const int32_t* m_rows, int rows, int m, int n, float temperature,
+                             int top_k, int32_t* out_index, int32_t* out_token, double* out_resid, void* stream);
+
 /* ---- Spatial drafting structures ------------------------------------------------------------
  * Method, "Dual Direction Drafting Heads" and "Spatial Sampling Pool"; appendix "Draft Heads
  * Structure and Memory Overhead".  Positions count in raster order (position = row * IW +

@@ -11,6 +11,7 @@ from .hawk import (  # noqa: F401
     lib_path,
     load_library,
     multi_verify,
+    multi_verify_static,
     multi_verify_workspace_bytes,
     plan_info,
     sample_rows,

@@ -428,6 +428,16 @@ int hawk_multi_verify(const float* p_logits, const float* q_logits, const int32_
                                      static_cast<hipStream_t>(stream));
 }
 
+int hawk_multi_verify_static(const float* p_logits, const float* q_logits, const int32_t* cand, const float* u_acc,
+                             const float* u_final, const int32_t* m_rows, int rows, int m, int n, float temperature,
+                             int top_k, int32_t* out_index, int32_t* out_token, double* out_resid, void* stream) {
+    if (!p_logits || !q_logits || !cand || !u_acc || !u_final || !out_index || !out_token) return HAWK_EINVAL;
+    if (rows < 0 || m < 1 || n < 1 || top_k < 1 || !(temperature >= 0.0f)) return HAWK_EINVAL;
+    if (rows == 0) return HAWK_OK;
+    return hawk::launch_multi_verify_static(p_logits, q_logits, cand, u_acc, u_final, m_rows, rows, m, n, temperature,
+                                            top_k, out_index, out_token, out_resid, static_cast<hipStream_t>(stream));
+}
+
 size_t hawk_spatial_heads_workspace_bytes(int rows, int n_heads, int d) {
     return rows > 0 && n_heads > 0 && d > 0 ? hawk::spatial_heads_workspace_bytes(rows, n_heads, d) : 0;
 }

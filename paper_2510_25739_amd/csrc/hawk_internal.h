@@ -195,6 +195,9 @@ int launch_multi_verify(const float* p_logits, const float* q_logits, const int3
                         int32_t* out_index, int32_t* out_token, double* out_resid, void* workspace,
                         size_t workspace_bytes, hipStream_t stream);
 size_t multi_verify_workspace_bytes(int rows, int m);
+int launch_multi_verify_static(const float* p_logits, const float* q_logits, const int32_t* cand, const float* u_acc,
+                               const float* u_final, const int32_t* m_rows, int rows, int m, int n, float temperature,
+                               int top_k, int32_t* out_index, int32_t* out_token, double* out_resid, hipStream_t stream);
 int launch_sample_rows(const float* logits, const int32_t* skip, const float* u, int rows, int n, float temperature,
                        int top_k, int32_t* out_token, hipStream_t stream);
 

@@ -7,6 +7,7 @@
 // One workgroup of 1024 threads handles one logit row; thread t owns the contiguous index
 // segment [t*E, (t+1)*E), which makes every scan an in-order prefix over token indices.
 // Reductions use wavefront shuffles, then one LDS exchange across the 16 waves.
+#include <mutex>
 #include "hawk_internal.h"
 
 namespace hawk {
@@ -1485,6 +1486,44 @@ int launch_multi_verify(const float* p_logits, const float* q_logits, const int3
                                       out_token, out_resid);
     }
     return hipGetLastError() == hipSuccess ? HAWK_OK : HAWK_EDEVICE;
+}
+
+// ---- hawk_multi_verify for callers that cannot allocate: the rows' statistics live in a fixed array in
+// device memory instead of a caller-provided workspace.  Every GPU holds its own copy of the array at
+// its own address, looked up once per device; host code only ever uses that address.
+constexpr int kStaticStatRows = 4096;   // logit rows (positions x (candidates + 1)) one call may have
+static __device__ __align__(256) unsigned char scratch[(size_t)kStaticStatRows * sizeof(WarpStat)];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU (null: not looked up yet)
+
+int scratch_address(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return HAWK_EDEVICE;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return HAWK_EDEVICE;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return HAWK_OK;
+}
+}  // namespace
+
+int launch_multi_verify_static(const float* p_logits, const float* q_logits, const int32_t* cand, const float* u_acc,
+                               const float* u_final, const int32_t* m_rows, int rows, int m, int n, float temperature,
+                               int top_k, int32_t* out_index, int32_t* out_token, double* out_resid, hipStream_t stream) {
+    if ((long long)rows * (m + 1) > kStaticStatRows) return HAWK_ENOMEM;
+    void* ws = nullptr;
+    const int rc = scratch_address(&ws);
+    if (rc != HAWK_OK) return rc;
+    // every record the second launch reads is written by the first launch of the same call, so
+    // nothing in the array has to be cleared between calls
+    return launch_multi_verify(p_logits, q_logits, cand, u_acc, u_final, m_rows, rows, m, n, temperature, top_k, out_index,
+                               out_token, out_resid, ws, multi_verify_workspace_bytes(rows, m), stream);
 }
 
 }  // namespace hawk

@@ -81,6 +81,9 @@ EXPORTS = {
     "hawk_multi_verify": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                     C.c_int, C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_size_t, C.c_void_p]),
+    "hawk_multi_verify_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_int, C.c_int, C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p,
+                                           C.c_void_p, C.c_void_p]),
     "hawk_spatial_heads_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int]),
     "hawk_spatial_heads": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
@@ -173,6 +176,22 @@ def multi_verify(p_logits, q_logits, cand, u_acc, u_final, temperature: float, t
     if rc != 0:
         raise HawkError(rc, "hawk_multi_verify")
     return (idx, tok, resid) if want_resid else (idx, tok)
+
+
+def multi_verify_static(p_logits, q_logits, cand, u_acc, u_final, temperature: float, top_k: int, out_index, out_token,
+                        out_resid=None, m_rows=None):
+    """hawk_multi_verify_static: hawk_multi_verify without any allocation - the caller passes the output
+    tensors too (out_index, out_token int32 [rows]; out_resid None or fp64 [rows, m]); the statistics go
+    to the library's fixed device array.  At most 4096 logit rows (rows * (m + 1)) per call."""
+    import torch  # stream handle only
+    rows, m, n = q_logits.shape
+    rc = load_library().hawk_multi_verify_static(p_logits.data_ptr(), q_logits.data_ptr(), cand.data_ptr(), u_acc.data_ptr(),
+                                                 u_final.data_ptr(), m_rows.data_ptr() if m_rows is not None else None,
+                                                 rows, m, n, float(temperature), int(top_k), out_index.data_ptr(),
+                                                 out_token.data_ptr(), out_resid.data_ptr() if out_resid is not None else None,
+                                                 torch.cuda.current_stream(p_logits.device).cuda_stream)
+    if rc != 0:
+        raise HawkError(rc, "hawk_multi_verify_static")
 
 
 def tree_layout(m_depth):
