@@ -96,3 +96,33 @@ def test_bf16_blob_values_are_exact_bf16_of_the_fp32_draw():
     ref = torch.from_numpy(w32).to(torch.bfloat16).float().numpy()  # torch rounds to nearest even
     assert (w16 == ref).all()
     assert np.all(synth.blob_tensor(s16, synth.make_weights(s16, 3), "g_f") == 1.0)
+
+
+@pytest.mark.parametrize("guided", [False, True])
+def test_prefill_hands_over_the_last_condition_rows_hidden_state(micro_shape, guided):
+    # The hidden state the draft head continues from after the prefill (Preliminary, "Utilization of
+    # Draft Heads Structure": heads read the final hidden layer) is the last condition row's output of
+    # the last layer, before the final norm - per stream under guidance.  Pinned against the full causal
+    # PyTorch forward over the condition vectors, which shares nothing with the oracle's prefill.
+    s = micro_shape.replace(cfg_scale=2.5) if guided else micro_shape
+    blob = synth.make_weights(s, seed=5, std=0.2)
+    B = 2
+    cond = synth.make_cond(s, seed=2, batch=B)
+    unc = synth.make_cond(s, seed=3, batch=B) if guided else None
+    o = oracle.Oracle.from_shape(s, blob, batch=B)
+    o.prefill(cond, unc, 1.0, 10, s.cfg_scale, [0.3, 0.7])
+    hp = o.h_prev()
+    assert hp.shape == ((2 if guided else 1) * B, s.d_model)
+    for b in range(B):
+        h_ref, lg_ref = torch_forward(s, blob, torch.from_numpy(cond[b].astype(np.float64)))
+        np.testing.assert_allclose(hp[b], h_ref[-1].numpy(), rtol=1e-10, atol=1e-11)
+        if guided:   # the unconditional stream of prompt b is sequence B + b
+            hu_ref, lu_ref = torch_forward(s, blob, torch.from_numpy(unc[b].astype(np.float64)))
+            np.testing.assert_allclose(hp[B + b], hu_ref[-1].numpy(), rtol=1e-10, atol=1e-11)
+            assert not np.allclose(hp[b], hp[B + b])
+            lg_ref = lu_ref[-1] + s.cfg_scale * (lg_ref[-1] - lu_ref[-1])
+        else:
+            lg_ref = lg_ref[-1]
+        # and the first token is the draw from that row's (guided) logits
+        w, z = oracle.warp(lg_ref.numpy().astype(np.float32), 1.0, 10)
+        assert o.grid()[b, 0] == s.samp_lo + oracle.inv_cdf(w, z, [0.3, 0.7][b])
