@@ -194,12 +194,16 @@ int hawk_get_logits(hawk_ctx* ctx, float* out, int rows);
 /* guided draft logits of the last draft, [batch, k, samp_n] */
 int hawk_get_draft_logits(hawk_ctx* ctx, float* out, int k);
 
-/* Selects the kernel set: 0 = generic kernels (any shape), 1 = the persistent
- * weight-streaming kernel where the shape allows (default).  hawk_last_path reports which
- * one the last target pass of hawk_verify / hawk_force / hawk_generate / hawk_run_steps
- * actually used (0 or 1; -1 before any). */
+/* Selects the kernel set: 0 = one kernel per operation (any shape); 1 = a persistent
+ * weight-streaming kernel where the shape allows (default): the one laid out on the chip's XCDs
+ * for the step rows of hawk_verify / hawk_force / hawk_generate / hawk_run_steps, else the one
+ * with grid barriers; 2 = as 1 but only the grid-barrier kernel.  hawk_last_path reports what the
+ * last target pass actually used (0: one kernel per operation, 1: a persistent kernel; -1 before
+ * any), hawk_last_kernel which kernel (0: one per operation, 1: grid-barrier kernel, 2: the kernel
+ * laid out on the XCDs). */
 int hawk_set_path(hawk_ctx* ctx, int path);
 int hawk_last_path(const hawk_ctx* ctx);
+int hawk_last_kernel(const hawk_ctx* ctx);
 
 /* Diagnostic: switches per-stage time stamps of the streaming kernel on or off (they cost
  * a few stores per stage) and, if out != NULL, copies the stamps of the last launch to

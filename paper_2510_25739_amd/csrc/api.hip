@@ -181,6 +181,7 @@ bool derive(const hawk_config* g, hawk_ctx* c) {
         o.gpack = take(q);
     }
     p += stream_workspace(c, p, &c->soff);
+    p += xcd_workspace(c, p, &c->xoff);
     o.total = p;
     return true;
 }
@@ -219,14 +220,24 @@ void run_step_rows(hawk_ctx* c, int k) {
     const int M = c->S * (k + 1);
     RowMap map = step_map(c, k);
     launch_embed_rows(c, map, M);
+    if (xcd_ok(c, k)) {  // one persistent kernel laid out on the XCDs: all layers and the output projection
+        if (c->kev_a) (void)hipEventRecord(c->kev_a, c->stream);
+        if (launch_verify_xcd(c, k) != 0) c->launch_failed = 1;
+        if (c->kev_b) (void)hipEventRecord(c->kev_b, c->stream);
+        c->last_path = 1;
+        c->last_kernel = 2;
+        return;
+    }
     if (stream_ok(c, k)) {  // one persistent kernel: all layers and the output projection
         if (c->kev_a) (void)hipEventRecord(c->kev_a, c->stream);
         if (launch_verify_stream(c, k) != 0) c->launch_failed = 1;
         if (c->kev_b) (void)hipEventRecord(c->kev_b, c->stream);
         c->last_path = 1;
+        c->last_kernel = 1;
         return;
     }
     c->last_path = 0;
+    c->last_kernel = 0;
     run_layers(c, map, M);
     launch_rmsnorm(c, c->off.x, c->d, c->w.g_f, c->off.a, M, true);
     launch_gemm(c, c->off.a, c->d, slice_off(c), c->Vs, c->d, c->off.logit_s, c->Vs, M, false, true);
@@ -371,6 +382,7 @@ int hawk_create(const hawk_config* cfg, void* workspace, size_t workspace_bytes,
         return HAWK_EDEVICE;
     }
     c->plan = stream_create(c);
+    c->xplan = xcd_create(c);
     if (hipGetLastError() != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
         hawk_destroy(c);
         return HAWK_EDEVICE;
@@ -383,6 +395,7 @@ void hawk_destroy(hawk_ctx* c) {
     if (!c) return;
     (void)hipStreamSynchronize(c->stream);
     stream_destroy(c->plan);
+    xcd_destroy(c->xplan);
     for (int i = 0; i < 3; ++i)
         if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
     if (c->pinned) (void)hipHostFree(c->pinned);
@@ -395,16 +408,22 @@ const char* hawk_last_error(const hawk_ctx* c) { return c ? c->err : "null conte
 
 int hawk_set_path(hawk_ctx* c, int path) {
     if (!c) return HAWK_EINVAL;
-    if (path != 0 && path != 1) return fail(c, HAWK_EINVAL, "path must be 0 or 1");
+    if (path < 0 || path > 2) return fail(c, HAWK_EINVAL, "path must be 0, 1 or 2");
     c->path = path;
     return HAWK_OK;
 }
 
 int hawk_last_path(const hawk_ctx* c) { return c ? c->last_path : -1; }
 
+int hawk_last_kernel(const hawk_ctx* c) { return c ? c->last_kernel : -1; }
+
 int hawk_phase_trace(hawk_ctx* c, int enable, uint64_t* out, size_t n_words) {
     if (!c) return HAWK_EINVAL;
     c->stream_dbg = enable ? 1 : 0;
+    if (out && c->xplan && c->last_kernel == 2) {   // the XCD-partitioned kernel's stamps: [2 workgroups][512 stages][16]
+        if (n_words > 2 * 512 * 16) n_words = 2 * 512 * 16;
+        return download(c, out, c->xoff.dbg, n_words * 8);
+    }
     if (out && c->plan) {
         if (n_words > 4 * 4096 * 8 + 2 * 256 * 256) n_words = 4 * 4096 * 8 + 2 * 256 * 256;
         return download(c, out, c->soff.dbg, n_words * 8);
@@ -494,6 +513,7 @@ int hawk_load(hawk_ctx* c, const void* host_blob, size_t nbytes) {
         return fail(c, HAWK_EINVAL, "blob header does not match the context's configuration");
     HIP_TRY(c, hipMemcpy(c->ws + c->off.blob, host_blob, nbytes, hipMemcpyHostToDevice));
     if (stream_repack(c) != 0) return fail(c, HAWK_EDEVICE, "re-tiling the weights for the streaming path failed");
+    if (xcd_repack(c) != 0) return fail(c, HAWK_EDEVICE, "re-tiling the weights for the XCD-partitioned pass failed");
     if (gemm_pack_weights(c) != 0) return fail(c, HAWK_EDEVICE, "re-tiling the weights for the MFMA GEMMs failed");
     c->phase = 1;
     return HAWK_OK;

@@ -71,6 +71,10 @@ enum StreamKind { K_A = 0, K_C, K_D, K_E, K_LM, K_WD, K_NKIND };  // QKV, Wo, W1
 constexpr int kNWG = 256;  // persistent workgroups: one per compute unit
 struct StreamOffsets { size_t wpack, tab, desc, arena, slot_bytes, bar, err, dbg, rope; };
 struct StreamPlan;
+// The same pass laid out on the chip's XCDs (xcd.hip): packed weights, job tables, tagged partial sums and
+// sums of squares, per-XCD buffers, flag words.
+struct XcdOffsets { size_t zero, wpack, desc, gtab, rtab, ptab, atab, xp, part[5], pss[5], xbuf, xcd_bytes, lflag, dbg; };
+struct XcdPlan;
 
 struct Weights {  // byte offsets into the blob
     size_t E, g_f, W_out, W_d;
@@ -89,6 +93,9 @@ struct hawk_ctx {
     hawk::Weights w;
     hawk::StreamOffsets soff;
     hawk::StreamPlan* plan;  // streaming path: job tables and barrier epoch (null until created)
+    hawk::XcdOffsets xoff;
+    hawk::XcdPlan* xplan;    // XCD-partitioned pass: plan and tag epoch (null until created)
+    int last_kernel;         // kernel of the last target pass: 0 one per operation, 1 grid-barrier kernel, 2 XCD-partitioned kernel
     size_t blob_bytes;
     size_t split_bytes;
     // matrices in the tile-major copy; pairs = m for W1|W3 stored with rows interleaved (W1 row f, W3 row f, ...)
@@ -180,6 +187,14 @@ int launch_verify_stream_tree(hawk_ctx*, int n_nodes, const int32_t* tree_depth,
 bool stream_draft_ok(const hawk_ctx*);      // can draft micro-steps run on the streaming path?
 int launch_draft_stream(hawk_ctx*, int i, size_t off_prev, size_t off_out);  // micro-step i up to its logits
 int stream_error(hawk_ctx*);              // 1 if a grid barrier timed out (synchronises)
+
+// ---- XCD-partitioned target pass, implemented in xcd.hip ----
+size_t xcd_workspace(const hawk_ctx*, size_t base, XcdOffsets* out);   // extra workspace bytes (0: shape not covered)
+XcdPlan* xcd_create(hawk_ctx*);           // plans the jobs, uploads tables, clears tags (context has its workspace)
+void xcd_destroy(XcdPlan*);
+int xcd_repack(hawk_ctx*);                // after the blob is on the device; 0 = ok
+bool xcd_ok(const hawk_ctx*, int k);      // can a step with k drafts run on it?
+int launch_verify_xcd(hawk_ctx*, int k);  // 0 = enqueued
 
 // ---- launchers implemented in sampling.hip ----
 void launch_plan(hawk_ctx*, int k);

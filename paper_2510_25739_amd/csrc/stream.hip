@@ -1521,7 +1521,7 @@ static size_t stream_lds_bytes(const hawk_ctx* c, int MR) {
 }
 
 bool stream_ok(const hawk_ctx* c, int k) {
-    if (!c->plan || !c->plan->ok || c->path != 1) return false;
+    if (!c->plan || !c->plan->ok || c->path < 1) return false;
     const int MR = c->S * (k + 1);
     if (MR > 16 || k + 1 > 6) return false;
     if (!attn_cut(c, k + 1).ok) return false;
@@ -1621,7 +1621,7 @@ int launch_verify_stream(hawk_ctx* c, int k) {
 // Tree rows on the streaming path: the nodes of one candidate tree per sequence, at most 16 rows in
 // all, two rows per attention job (their jobs must fit the workgroups of an XCD).
 bool stream_tree_ok(const hawk_ctx* c, int n_nodes) {
-    if (!c->plan || !c->plan->ok || c->path != 1) return false;
+    if (!c->plan || !c->plan->ok || c->path < 1) return false;
     const int MR = c->S * n_nodes;
     if (MR > 16 || n_nodes < 1) return false;
     const int heads_per_xcd = (c->S * c->H + kXcd - 1) / kXcd;
@@ -1650,7 +1650,7 @@ int launch_verify_stream_tree(hawk_ctx* c, int n_nodes, const int32_t* tree_dept
 
 // Can draft micro-steps run on the streaming path?
 bool stream_draft_ok(const hawk_ctx* c) {
-    if (!c->plan || !c->plan->ok || c->path != 1) return false;
+    if (!c->plan || !c->plan->ok || c->path < 1) return false;
     return c->S <= 16 && stream_lds_bytes(c, c->S) <= 150 * 1024 && c->plan->kind[K_WD].rounds == 1;
 }
 

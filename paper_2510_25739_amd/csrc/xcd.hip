@@ -1,0 +1,1361 @@
+// Target pass over the k+1 rows of a step as ONE persistent kernel laid out on the chip's eight XCDs
+// (32 compute units and one L2 each): the dependent chain of a layer runs on flags and data that
+// cross between XCDs once per matrix product and otherwise stay inside one XCD's L2.
+//
+// Measured on MI355X (256 workgroups, one per unit): a store that goes through to memory is seen by a
+// polling workgroup of another XCD after ~0.55 us; inside an XCD an ordinary store (it stays in that
+// XCD's L2) is seen by a device-scope load of another unit after ~0.22 us; a grid barrier plus the
+// fetch of a fresh 32 KB input by every workgroup costs ~4.0 us, which bounds a kernel that exchanges
+// whole activation vectors between all workgroups five times per layer at ~6 us per stage.
+//
+// Hence, per matrix product y = W x:
+//   - XCD c owns a K-slice of x (an eighth of the columns; for the attention output the columns of the
+//     heads it owns; for the MLP's hidden vector an eighth of its k-tiles) and keeps it in a buffer only
+//     its own units read: consumers fetch an eighth of the vector, from their own L2;
+//   - workgroup (c, j) streams the weights of its output strips x that K-slice (bf16 tiles straight into
+//     registers as MFMA A operands, one wave per strip group, no cross-wave reduction) and writes the
+//     partial sums to memory as 8-byte {value, tag} words (tag = stage number: a reader knows a word is
+//     of this stage without any barrier, and nothing has to be re-armed);
+//   - the strip's owner - an IO wave on the XCD that owns those output columns as its K-slice of the
+//     NEXT product - polls the eight partials, adds them in fixed order, applies the epilogue (norm
+//     scale, rotary embedding, residual, SwiGLU), stores the result into its XCD's buffer with ordinary
+//     stores and raises a flag word there; the XCD's units poll those flag words (one L2 line).
+// Attention for a head runs on the XCD that owns the head: queries, new keys/values and the output
+// rows never leave that XCD.  A product that follows a norm needs every row's sum of squares over the
+// whole vector: each XCD sums its slice while staging it and sends that share along with its partial
+// sums (one tagged word per wave and row), so the owner has norm scale and dot products from the same
+// poll.  No grid barrier anywhere; every wait is a bounded poll that ends in an error code.
+//
+// In the loaded kernel the latencies are two to three times the idle ones (a partial sum is in its
+// owner's registers 1.3 - 2.7 us after its store was issued, a local flag is seen after ~0.4 us, the
+// staging copy takes ~0.55 us), which is what bounds a stage at 4.3 - 8.3 us (see the stage table that
+// hawk_phase_trace gives); the weight stream itself accounts for ~5 % of the kernel's time.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <algorithm>
+#include <vector>
+
+#include "hawk_internal.h"
+
+namespace hawk {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned long long u64;
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+
+constexpr int kCW = 4, kNIO = 4;                 // compute / IO waves per workgroup
+constexpr int kThreads = (kCW + kNIO) * 64, kIOThreads = kNIO * 64;
+constexpr int kXcd = 8, kPer = kNWG / kXcd;      // workgroup i runs on XCD i % 8 (checked by every workgroup)
+constexpr unsigned kSpinLimit = 1u << 20;
+constexpr int kPS = 68;                          // floats per attention partial row: 64 outputs, max, sum, pad
+constexpr int kNIT = 4;                          // cache positions per lane group and register buffer
+constexpr int kRing = 2;                         // partial-sum areas and XCD buffers alternate between layers
+constexpr int kMaxJobs = 64;                     // reduce / attention jobs of one XCD and stage that others wait for
+
+enum XKind { X_A = 0, X_C, X_D, X_E, X_LM, X_NK };   // QKV, Wo, W1|W3, W2, output projection
+enum XFlag { F_A = 0, F_B, F_C, F_D, F_E, F_NF };    // who raised a flag: reduce of A, attention, reduce of C, D, E
+
+struct XP {
+    const uint4* wpack;
+    const uint4* zero_tile;     // 1 KB of zeros: what absent strips / k-tiles of a wave's job read
+    u64 layer_tiles;            // tiles of one layer
+    u64 xbase[X_NK][kXcd];      // first tile of (kind, XCD) inside a layer (output projection: after all layers)
+    int32_t KT[X_NK][kXcd];     // k-tiles of the XCD's slice of the kind's input
+    int32_t nstrips[X_NK];
+    int32_t hd0[kXcd + 1];      // heads of XCD c: hd0[c] .. hd0[c + 1] - 1
+    int32_t ke0[kXcd + 1];      // k-tiles of the MLP's hidden vector of XCD c
+    const int16_t* gtab;        // [kind][32][kCW][2]: first strip and strip count of (unit j, compute wave w)
+    const int16_t* ptab;        // [poff[kind] + strip]: producer of the strip, (unit * kCW + wave) * 2 + round
+    int poff[X_NK];
+    const int16_t* rtab;        // [kind][8][32][kNIO][2]: strip (-1: none) and flag slot of (XCD, unit, IO wave)
+    const int16_t* atab;        // [8][32][4]: sequence, head, row group (-1: none), flag slot
+    int32_t njobs[F_NF][kXcd];  // flag slots a consumer of that stage waits for
+    u64* part[X_NK];            // partial sums: [ring][8 source XCDs][strip][16 rows][4][4] {value, tag}
+    u64* pss[X_NK];             // per-XCD sums of squares that ride along (products after a norm): [ring][8][unit][wave][round][16 rows] {value, tag}
+    uint8_t* xbuf;              // per-XCD buffers: [8][ring][xcd_bytes]
+    u64 xcd_bytes, o_a, o_q, o_o, o_x2, o_h, o_ss;   // regions of one XCD buffer (bytes)
+    unsigned* lflag;            // [8][F_NF][kMaxJobs]
+    const uint16_t* blob;
+    u64 g1_off, g2_off, layer_bytes, gf_off;
+    const float2* rope;
+    _Float16* Kc;
+    _Float16* Vc;
+    float* X;                   // embedded rows in, final hidden rows out ([MR][d] fp32)
+    float* logit_s;
+    unsigned* err;
+    const int32_t* n;
+    const int32_t* k_eff;
+    int32_t L, d, H, m, Vs, S, B, C, RS, MR, RPJ, Smax, Tmax;
+    int32_t KpA, KpO, KpH;      // row strides (elements) of the split planes: d / 8 + 8, widest head group + 8, widest hidden slice + 8
+    int32_t lm_rounds;
+    float eps;
+};
+
+// ------------------------------------------------------------------------- device helpers
+
+__device__ __forceinline__ unsigned xcc_id() {
+    unsigned v;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(v));
+    return v & 0xFu;
+}
+__device__ __forceinline__ void compiler_fence() { __atomic_signal_fence(__ATOMIC_SEQ_CST); }
+// A pointer the compiler must treat as new: addresses derived from it are computed where they are used
+// instead of once before the layer loop (dozens of 64-bit addresses kept alive across the whole kernel).
+template <typename T>
+__device__ __forceinline__ T* fresh(T* ptr) {
+    asm volatile("" : "+v"(ptr));
+    return ptr;
+}
+
+// Loads that must see what another unit of the same XCD stored (they skip the unit's own L1 and are
+// served by the XCD's L2), or what another XCD wrote through to memory: device scope.  The 16-byte forms
+// go through a buffer resource (32-bit byte offsets from a wave-uniform base), which the compiler tracks
+// like any other load.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr int kDevScope = 16;   // cache-policy bit of device scope in the buffer instructions
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7FFFFFFF, 0x00020000);
+}
+__device__ __forceinline__ v4u ld_16(rsrc_t r, unsigned byte_off) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, kDevScope);
+}
+__device__ __forceinline__ void st_16(rsrc_t r, unsigned byte_off, v4u v) {   // goes through to memory
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_off, 0, kDevScope);
+}
+__device__ __forceinline__ u64 ld_u64(const void* p) {
+    return __hip_atomic_load(reinterpret_cast<const u64*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned ld_u32(const void* p) {
+    return __hip_atomic_load(reinterpret_cast<const unsigned*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Stores that go through to memory (sums of squares: read by other XCDs).
+__device__ __forceinline__ void st_tagged(u64* p, float v, unsigned tag) {
+    __hip_atomic_store(p, (u64)__float_as_uint(v) | ((u64)tag << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ float sum_xor16(float v) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float sum_xor32(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float lane_xor16(float v) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float((threadIdx.x & 16u) ? r[0] : r[1]);
+}
+__device__ __forceinline__ float lane_xor32(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float((threadIdx.x & 32u) ? r[0] : r[1]);
+}
+__device__ __forceinline__ float lane_xor8(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128, 0xF, 0xF, true));
+}
+
+__device__ __forceinline__ unsigned bf16_rne(float f) {
+    unsigned u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ float bf16_f32(unsigned b) { return __uint_as_float(b << 16); }
+
+// Four consecutive elements of a split vector (bf16 hi and lo halves), ordinary stores: the XCD's buffer.
+__device__ __forceinline__ void put_split4(uint16_t* hi, uint16_t* lo, f32x4 v) {
+    const unsigned h0 = bf16_rne(v[0]), h1 = bf16_rne(v[1]), h2 = bf16_rne(v[2]), h3 = bf16_rne(v[3]);
+    const unsigned l0 = bf16_rne(v[0] - bf16_f32(h0)), l1 = bf16_rne(v[1] - bf16_f32(h1));
+    const unsigned l2 = bf16_rne(v[2] - bf16_f32(h2)), l3 = bf16_rne(v[3] - bf16_f32(h3));
+    *reinterpret_cast<uint2*>(hi) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+    *reinterpret_cast<uint2*>(lo) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+}
+__device__ __forceinline__ f32x4 times_gain(f32x4 x, uint2 g) {
+    return (f32x4){x[0] * bf16_f32(g.x & 0xFFFFu), x[1] * bf16_f32(g.x >> 16), x[2] * bf16_f32(g.y & 0xFFFFu),
+                   x[3] * bf16_f32(g.y >> 16)};
+}
+
+// State of one wave: where it sits, the stage counter, whether a wait has given up.
+struct Ctx {
+    unsigned x, j;        // XCD and unit of the workgroup
+    unsigned epoch0;      // tags of this launch start behind it
+    bool dead;
+    unsigned* err;
+    u64* dbg;             // time stamps of two workgroups (null: off)
+};
+
+// Tag of (layer, stage); the prologue counts as stage E of layer -1.
+__device__ __forceinline__ unsigned tag_of(const Ctx& c, int layer, int flag) {
+    return c.epoch0 + 1u + 5u * (unsigned)(layer + 1) + (unsigned)flag;
+}
+
+__device__ __forceinline__ void give_up(Ctx& c) {
+    c.dead = true;
+    __hip_atomic_store(c.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Waits until the first `n` flag words of this XCD's stage `flag` have reached `tag` (whole wave).
+__device__ __forceinline__ void wait_flags(const XP& p, Ctx& c, int flag, int n, unsigned tag) {
+    if (c.dead) return;
+    const unsigned l = threadIdx.x & 63u;
+    const unsigned* f = p.lflag + ((size_t)c.x * F_NF + flag) * kMaxJobs + (l < (unsigned)n ? l : 0u);
+    for (unsigned spins = 0; spins < kSpinLimit; ++spins) {
+        const unsigned v = ld_u32(f);
+        if (__all((int)(v - tag) >= 0)) { compiler_fence(); return; }
+        if ((spins & 255u) == 255u && ld_u32(c.err) != 0u) break;
+    }
+    give_up(c);
+}
+
+// After the wave's ordinary stores into the XCD's buffer: they are in the L2 once acknowledged, then
+// the flag word goes up.
+__device__ __forceinline__ void raise_flag(const XP& p, const Ctx& c, int flag, int slot, unsigned tag) {
+    __builtin_amdgcn_s_waitcnt(0);
+    if ((threadIdx.x & 63u) == 0u)
+        __hip_atomic_store(p.lflag + ((size_t)c.x * F_NF + flag) * kMaxJobs + slot, tag, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+__device__ __forceinline__ uint8_t* xcd_buf(const XP& p, unsigned x, int ring) {
+    return p.xbuf + ((size_t)x * kRing + ring) * p.xcd_bytes;
+}
+
+__device__ __forceinline__ void stamp(const Ctx& c, unsigned stage, int what) {
+    if (c.dbg && (threadIdx.x & 63) == 0 && (blockIdx.x == 0 || blockIdx.x == 248) && stage < 512u)
+        c.dbg[((size_t)(blockIdx.x ? 1 : 0) * 512 + stage) * 16 + what + ((threadIdx.x >> 6) >= kCW ? 8 : 0)] =
+            __builtin_amdgcn_s_memrealtime();
+}
+
+struct RowPos { int seq, r, pos; bool valid; };
+__device__ __forceinline__ RowPos row_pos(const XP& p, int c) {
+    RowPos o;
+    o.seq = c / p.RS;
+    o.r = c - o.seq * p.RS;
+    const int b = o.seq % p.B;
+    o.valid = o.r <= p.k_eff[b];
+    o.pos = o.valid ? p.C + p.n[b] - 1 + o.r : 0;
+    return o;
+}
+
+// ------------------------------------------------------------------------- matrix products
+
+// A compute wave's share of one kind of product, read from the tables once at kernel start (a table
+// load behind a workgroup barrier would sit on every stage's critical path).
+struct GJob {
+    int s0, ns, KT;   // first strip, strips, k-tiles of the XCD's slice
+    u64 tile0;        // first tile inside a layer (output projection: in the stream)
+};
+__device__ __forceinline__ GJob load_gjob(const XP& p, int kind, const Ctx& c, int wave) {
+    const int16_t* g = p.gtab + (((size_t)kind * kPer + c.j) * kCW + wave) * 2;
+    GJob j;
+    j.s0 = g[0]; j.ns = g[1]; j.KT = p.KT[kind][c.x];
+    j.tile0 = p.xbase[kind][c.x] + (u64)j.s0 * j.KT;
+    return j;
+}
+
+// Issues the loads of a wave's tiles of one stage: strips x the XCD's k-tiles, in that order in the
+// packed stream.  Straight-line code: absent strips / k-tiles read one shared tile of zeros (a cache
+// hit), so that the number of requests is fixed and the wait before the products can be for exactly
+// this stage's tiles - not for the tiles of later stages requested behind them.
+template <int NSW, int KTM>
+__device__ __forceinline__ void issue_tiles(const XP& p, const GJob& g, u64 layer_base, int lane, v4u (&w)[NSW * KTM],
+                                            int round = 0) {
+    const int ns = min(max(g.ns - round * NSW, 0), NSW), KT = g.KT;
+    const v4u* src = reinterpret_cast<const v4u*>(p.wpack + (layer_base + g.tile0 + (u64)round * NSW * KT) * 64 + lane);
+    const v4u* zero = reinterpret_cast<const v4u*>(p.zero_tile) + lane;
+#pragma unroll
+    for (int si = 0; si < NSW; ++si)
+#pragma unroll
+        for (int kt = 0; kt < KTM; ++kt) {
+            const bool on = si < ns && kt < KT;
+            w[si * KTM + kt] = __builtin_nontemporal_load(on ? src + (size_t)(si * KT + kt) * 64 : zero);
+        }
+}
+
+// The wave's products of a stage from the staged K-slice (LDS planes [16][Kp]) and the partial sums
+// out as tagged words: part[ring][XCD][strip][row][quad][4].  No branches up to the stores (see above).
+template <int NSW, int KTM>
+__device__ __forceinline__ void mfma_store(const XP& p, int kind, const GJob& g, const Ctx& c, int lane, const v4u (&w)[NSW * KTM],
+                                           const uint16_t* act_hi, const uint16_t* act_lo, const float* ssrow, int Kp, int ring,
+                                           unsigned tag, int round = 0, unsigned dbg_stage = 0) {
+    const int s0 = g.s0 + round * NSW, ns = min(max(g.ns - round * NSW, 0), NSW);
+    const int col = lane & 15, kg = lane >> 4;
+    const size_t at = (size_t)(col < p.MR ? col : 0) * Kp + kg * 8;
+    f32x4 acc[NSW], acl[NSW];
+#pragma unroll
+    for (int si = 0; si < NSW; ++si) {
+        acc[si] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        acl[si] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int kt = 0; kt < KTM; ++kt) {   // k-tiles beyond the XCD's slice: zero weights (their LDS columns are in bounds)
+        const bf16x8 h = __builtin_bit_cast(bf16x8, *reinterpret_cast<const v4u*>(act_hi + at + kt * 32));
+        const bf16x8 l = __builtin_bit_cast(bf16x8, *reinterpret_cast<const v4u*>(act_lo + at + kt * 32));
+#pragma unroll
+        for (int si = 0; si < NSW; ++si) {
+            const bf16x8 a = __builtin_bit_cast(bf16x8, w[si * KTM + kt]);
+            acc[si] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, h, acc[si], 0, 0, 0);
+            acl[si] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, l, acl[si], 0, 0, 0);
+        }
+    }
+    if (c.dbg) {   // when tracing: the products are done (the stamp follows them in program order only through this)
+#pragma unroll
+        for (int si = 0; si < NSW; ++si) asm volatile("" :: "v"(acc[si]), "v"(acl[si]));
+        stamp(c, dbg_stage, 3);
+    }
+    // One 128-byte line per (strip, row): the first 64 bytes hold the {value, tag} pairs of features 4q, 4q + 1
+    // (q = lane / 16), the second 64 those of features 4q + 2, 4q + 3.  Every 8-byte pair is written whole,
+    // so a reader never sees a value without its tag.  With at most 8 rows the idle lanes of columns 8..15
+    // carry the second halves of columns 0..7 (one cross-lane move) and one store instruction per strip
+    // writes whole lines; write-through stores cost the wave ~0.15 us per instruction.
+    const rsrc_t out = make_rsrc(p.part[kind]);
+    const bool packed = p.MR <= 8;
+    const int row = packed ? (col & 7) : col;
+    const bool second = packed && col >= 8;
+    const unsigned at8 = (unsigned)((((size_t)ring * kXcd + c.x) * p.nstrips[kind] + s0) * 16 + row) * 128u + kg * 16u + (second ? 64u : 0u);
+#pragma unroll
+    for (int si = 0; si < NSW; ++si) {
+        const f32x4 v = acc[si] + acl[si];
+        const float v2 = lane_xor8(v[2]), v3 = lane_xor8(v[3]);   // columns 8..15 receive columns 0..7
+        if (si < ns && row < p.MR) {
+            if (packed) {
+                st_16(out, at8 + si * 2048u, second ? (v4u){__float_as_uint(v2), tag, __float_as_uint(v3), tag}
+                                                    : (v4u){__float_as_uint(v[0]), tag, __float_as_uint(v[1]), tag});
+            } else {
+                st_16(out, at8 + si * 2048u, (v4u){__float_as_uint(v[0]), tag, __float_as_uint(v[1]), tag});
+                st_16(out, at8 + si * 2048u + 64u, (v4u){__float_as_uint(v[2]), tag, __float_as_uint(v[3]), tag});
+            }
+        }
+    }
+    if (ssrow && kg == 0 && col < p.MR && ns > 0)   // the product follows a norm: this XCD's share of the row's sum of squares
+                                                    // rides along, once per wave and round
+        st_tagged(p.pss[kind] + ((((size_t)ring * kXcd + c.x) * kPer + c.j) * kCW + (threadIdx.x >> 6)) * 32 + (round & 1) * 16 + col,
+                  ssrow[col], tag);
+}
+
+// IO waves: copy the XCD's slice of a stage input (split planes [2][16][Kp], the first MR rows of each)
+// from the XCD's buffer (byte offset `src` from the base of `r`) into LDS, which has the same layout:
+// two contiguous runs of MR * Kp elements, up to four 16-byte chunks per thread in flight.
+__device__ __forceinline__ void stage_copy(rsrc_t r, unsigned src, int MR, int Kp, uint16_t* act, int t) {
+    const int per_plane = MR * Kp / 8, total = 2 * per_plane;   // Kp % 8 == 0
+    const unsigned plane_bytes = 16u * (unsigned)Kp * 2u;
+    for (int base = 0; base < total; base += 4 * kIOThreads) {
+        v4u v[4];
+        unsigned at[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int q = base + i * kIOThreads + t;
+            at[i] = q >= per_plane ? plane_bytes + (unsigned)(q - per_plane) * 16u : (unsigned)q * 16u;
+            v[i] = q < total ? ld_16(r, src + at[i]) : (v4u){0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (base + i * kIOThreads + t < total) *reinterpret_cast<v4u*>(reinterpret_cast<char*>(act) + at[i]) = v[i];
+    }
+}
+
+// ------------------------------------------------------------------------- reduce jobs (IO waves)
+
+// Sum of the eight XCDs' partials of strip s in accumulator layout (lane: rows 4 * (lane / 16) .. + 3
+// of the strip = output features, column lane % 16 = activation row), added in XCD order.  scaled: the
+// product follows a norm; the XCDs' shares of every row's sum of squares came with their partial sums,
+// and *rn receives 1/rms of the lane's row.
+__device__ __forceinline__ f32x4 gather_partials(const XP& p, Ctx& c, int kind, int s, int prod, int ring, unsigned tag, int lane,
+                                                 bool scaled, float* rn) {
+    const int col = lane & 15, quad = lane >> 4;
+    const bool live = col < p.MR;
+    f32x4 val[kXcd];
+#pragma unroll
+    for (int x = 0; x < kXcd; ++x) val[x] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    unsigned need = live ? 0xFFu : 0u;
+    // (selects: indexing the kernel's parameter block with a run-time value is best avoided)
+    const u64* part = kind == X_A ? p.part[X_A] : kind == X_C ? p.part[X_C] : kind == X_D ? p.part[X_D]
+                                                                            : kind == X_E ? p.part[X_E] : p.part[X_LM];
+    const u64* pssb = kind == X_A ? p.pss[X_A] : kind == X_D ? p.pss[X_D] : p.pss[X_LM];
+    const int nstr = kind == X_A ? p.nstrips[X_A] : kind == X_C ? p.nstrips[X_C] : kind == X_D ? p.nstrips[X_D]
+                                                                               : kind == X_E ? p.nstrips[X_E] : p.nstrips[X_LM];
+    const rsrc_t in = make_rsrc(part);
+    const unsigned at8 = (unsigned)(((size_t)ring * kXcd * nstr + s) * 16 + col) * 128u + quad * 16u;
+    const unsigned xstride = (unsigned)nstr * 2048u;
+    // sums of squares: the lane's quarter looks at XCDs 2 * quad and 2 * quad + 1; `prod` = the strip's
+    // producer (unit * kCW + wave) * 2 + round, the same on every XCD
+    const u64* pss = pssb + (((size_t)ring * kXcd + 2 * quad) * kPer * kCW * 2 + prod) * 16 + col;
+    unsigned need_ss = (live && scaled) ? 3u : 0u;
+    float ssv[2] = {0.f, 0.f};
+    bool ok = c.dead;
+    for (unsigned spins = 0; spins < kSpinLimit && !ok; ++spins) {
+        v4u w[kXcd][2];
+        u64 sw[2] = {0ull, 0ull};
+#pragma unroll
+        for (int x = 0; x < kXcd; ++x)
+            if ((need >> x) & 1u) {
+                w[x][0] = ld_16(in, at8 + x * xstride);
+                w[x][1] = ld_16(in, at8 + x * xstride + 64u);
+            }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            if ((need_ss >> i) & 1u) sw[i] = ld_u64(pss + (size_t)i * kPer * kCW * 2 * 16);
+#pragma unroll
+        for (int x = 0; x < kXcd; ++x)
+            if ((need >> x) & 1u) {
+                if (w[x][0][1] == tag && w[x][0][3] == tag && w[x][1][1] == tag && w[x][1][3] == tag) {
+                    val[x] = (f32x4){__uint_as_float(w[x][0][0]), __uint_as_float(w[x][0][2]), __uint_as_float(w[x][1][0]),
+                                     __uint_as_float(w[x][1][2])};
+                    need &= ~(1u << x);
+                }
+            }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            if (((need_ss >> i) & 1u) && (unsigned)(sw[i] >> 32) == tag) {
+                ssv[i] = __uint_as_float((unsigned)sw[i]);
+                need_ss &= ~(1u << i);
+            }
+        ok = __all(need == 0u && need_ss == 0u);
+        if (!ok && (spins & 255u) == 255u && ld_u32(c.err) != 0u) break;
+    }
+    if (!ok) give_up(c);
+    if (scaled) {
+        float a = ssv[0] + ssv[1];
+        a = sum_xor16(a);
+        a = sum_xor32(a);
+        *rn = 1.0f / sqrtf(a / (float)p.d + p.eps);
+    }
+    f32x4 v = val[0];
+#pragma unroll
+    for (int x = 1; x < kXcd; ++x) v += val[x];
+    return v;
+}
+
+// Publishes a strip of the residual stream for the product that follows a norm: the values times the
+// norm's gain as split planes, and the strip's sums of squares, into the owner XCD's buffer (ring slot
+// `ring`; which = 0: x -> region o_a, 1: x' -> region o_x2).
+__device__ __forceinline__ void put_stream(const XP& p, const Ctx& c, int which, int ring, int strip, int lane, f32x4 x, uint2 gain) {
+    const int col = lane & 15, quad = lane >> 4;
+    const bool live = col < p.MR;
+    float s2 = live ? x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3] : 0.f;
+    s2 = sum_xor16(s2);
+    s2 = sum_xor32(s2);
+    uint8_t* buf = xcd_buf(p, c.x, ring);
+    if (live) {
+        const int per_xcd = p.d / 16 / kXcd;
+        uint16_t* hi = reinterpret_cast<uint16_t*>(buf + (which ? p.o_x2 : p.o_a));
+        uint16_t* lo = hi + (size_t)16 * p.KpA;
+        const size_t at = (size_t)col * p.KpA + (strip % per_xcd) * 16 + 4 * quad;
+        put_split4(hi + at, lo + at, times_gain(x, gain));
+        if (quad == 0) reinterpret_cast<float*>(buf + p.o_ss)[((size_t)which * per_xcd + strip % per_xcd) * 16 + col] = s2;
+    }
+}
+// What an IO wave does in every layer, read from the tables once at kernel start: its reduce job of
+// each kind (strip, flag slot; strip < 0: none), the lane's row of the step, the rotary factors of
+// its QKV strip, the number of flag words each stage's consumers wait for, the unit's attention job.
+struct IoJobs {
+    int sA, sC, sD, sE;          // strip of the wave's reduce job of each product (named fields, not arrays: a select
+    int tA, tC, tD, tE;          // between array elements by a run-time value would be turned into memory indexing); flag slots
+    RowPos rp;                   // row lane % 16 of the step
+    float2 rot0, rot1;           // QKV strip: cos, sin of the lane's two rotary pairs at the row's position
+    int nA, nB, nC, nD, nE;      // flag words the consumers of stage A (reduce of QKV), B (attention), C, D, E wait for
+    int a_seq, a_h, a_rg, a_slot;   // attention job of the unit (a_rg < 0: none)
+};
+__device__ __forceinline__ IoJobs load_io_jobs(const XP& p, const Ctx& c, int io, int lane) {
+    IoJobs j;
+    auto entry = [&](int k) { return p.rtab + ((((size_t)k * kXcd + c.x) * kPer + c.j) * kNIO + io) * 2; };
+    j.sA = entry(X_A)[0]; j.tA = entry(X_A)[1];
+    j.sC = entry(X_C)[0]; j.tC = entry(X_C)[1];
+    j.sD = entry(X_D)[0]; j.tD = entry(X_D)[1];
+    j.sE = entry(X_E)[0]; j.tE = entry(X_E)[1];
+    const int col = lane & 15, quad = lane >> 4;
+    j.rp = col < p.MR ? row_pos(p, col) : RowPos{0, 0, 0, false};
+    j.rot0 = j.rot1 = make_float2(1.f, 0.f);
+    if (j.sA >= 0 && col < p.MR) {
+        const int o0 = j.sA * 16, seg = o0 / p.d, j0 = o0 - seg * p.d;
+        if (seg < 2) {
+            const float2* rt = p.rope + (size_t)j.rp.pos * 32 + ((j0 % 64) >> 1) + 2 * quad;
+            j.rot0 = rt[0];
+            j.rot1 = rt[1];
+        }
+    }
+    j.nA = p.njobs[F_A][c.x]; j.nB = p.njobs[F_B][c.x]; j.nC = p.njobs[F_C][c.x]; j.nD = p.njobs[F_D][c.x];
+    j.nE = p.njobs[F_E][c.x];
+    const int16_t* a = p.atab + ((size_t)c.x * kPer + c.j) * 4;
+    j.a_seq = a[0]; j.a_h = a[1]; j.a_rg = a[2]; j.a_slot = a[3];
+    return j;
+}
+
+// The reduce job of an IO wave for product `kind` (X_A .. X_E, a run-time value: the four products share
+// one copy of this code, which keeps the kernel inside the instruction cache) of `layer`; none: returns
+// at once.  resid: the wave's strip of the residual stream (owners of Wo / W2 strips).
+__device__ __forceinline__ void reduce_job(const XP& p, Ctx& c, const IoJobs& jb, int kind, int layer, int lane, f32x4& resid,
+                                           unsigned stage) {
+    // (selects, not indexing with a run-time value: that would move the structure into memory)
+    const int s = kind == X_A ? jb.sA : kind == X_C ? jb.sC : kind == X_D ? jb.sD : jb.sE;
+    const int slot = kind == X_A ? jb.tA : kind == X_C ? jb.tC : kind == X_D ? jb.tD : jb.tE;
+    if (s < 0) return;
+    const int col = lane & 15, quad = lane >> 4, d = p.d, ring = layer & 1;
+    const bool live = col < p.MR;
+    const int flag = kind == X_A ? F_A : kind == X_C ? F_C : kind == X_D ? F_D : F_E;
+    const unsigned tag = tag_of(c, layer, flag);
+    uint8_t* buf = xcd_buf(p, c.x, ring);
+    const bool scaled = kind == X_A || kind == X_D;   // QKV and W1|W3 follow a norm
+    uint2 gain = make_uint2(0u, 0u);   // Wo, W2: gain of the norm that follows, for the lane's four features
+    if (kind == X_C) gain = *reinterpret_cast<const uint2*>(p.blob + (p.g2_off + (u64)layer * p.layer_bytes) / 2 + s * 16 + 4 * quad);
+    if (kind == X_E) {
+        const uint16_t* g = layer + 1 < p.L ? p.blob + (p.g1_off + (u64)(layer + 1) * p.layer_bytes) / 2 : p.blob + p.gf_off / 2;
+        gain = *reinterpret_cast<const uint2*>(g + s * 16 + 4 * quad);
+    }
+    float rn = 1.f;
+    f32x4 v = gather_partials(p, c, kind, s, scaled ? p.ptab[p.poff[kind] + s] : 0, ring, tag, lane, scaled, &rn);
+    stamp(c, stage, 4);
+    v *= rn;
+    stamp(c, stage, 5);
+    if (kind == X_A) {
+        const int seg = (s * 16) / d, j0 = s * 16 - seg * d, h = j0 / 64;
+        const float a0 = v[0] * jb.rot0.x - v[1] * jb.rot0.y, b0 = v[0] * jb.rot0.y + v[1] * jb.rot0.x;
+        const float a1 = v[2] * jb.rot1.x - v[3] * jb.rot1.y, b1 = v[2] * jb.rot1.y + v[3] * jb.rot1.x;
+        if (live) {
+            if (seg == 0) {   // queries of this XCD's heads, scaled by 1 / sqrt(64)
+                float* q = reinterpret_cast<float*>(buf + p.o_q) + (size_t)col * (p.KpO - 8) + (h - p.hd0[c.x]) * 64 + j0 % 64 + 4 * quad;
+                *reinterpret_cast<f32x4*>(q) = (f32x4){a0 * 0.125f, b0 * 0.125f, a1 * 0.125f, b1 * 0.125f};
+            } else if (jb.rp.valid) {
+                _Float16* dst = (seg == 1 ? p.Kc : p.Vc) +
+                                ((((size_t)layer * p.Smax + jb.rp.seq) * p.H + h) * p.Tmax + jb.rp.pos) * 64 + j0 % 64 + 4 * quad;
+                const _Float16 h0 = (_Float16)a0, h1 = (_Float16)b0, h2 = (_Float16)a1, h3 = (_Float16)b1;
+                *reinterpret_cast<uint2*>(dst) = make_uint2(
+                    (unsigned)__builtin_bit_cast(unsigned short, h0) | ((unsigned)__builtin_bit_cast(unsigned short, h1) << 16),
+                    (unsigned)__builtin_bit_cast(unsigned short, h2) | ((unsigned)__builtin_bit_cast(unsigned short, h3) << 16));
+            }
+        }
+    } else if (kind == X_D) {   // rows 0..7 of the strip: W1 rows s * 8 + i, rows 8..15 the matching W3 rows
+        f32x4 u3;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) u3[e] = lane_xor32(v[e]);
+        if (live && quad < 2) {
+            f32x4 hv;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) hv[e] = v[e] / (1.0f + expf(-v[e])) * u3[e];
+            uint16_t* hi = reinterpret_cast<uint16_t*>(buf + p.o_h);
+            uint16_t* lo = hi + (size_t)16 * p.KpH;
+            const size_t at = (size_t)col * p.KpH + (s * 8 - p.ke0[c.x] * 32) + 4 * quad;
+            put_split4(hi + at, lo + at, hv);
+        }
+    } else {   // Wo: x' = x + Wo o; W2: x (next layer) = x' + W2 h - published times the gain of the norm that follows
+        resid += v;
+        const int out_ring = kind == X_C ? ring : (layer + 1) & 1;
+        put_stream(p, c, kind == X_C, out_ring, s, lane, resid, gain);
+        if (kind == X_E && layer == p.L - 1 && live)   // final hidden rows, for the kernels that follow
+            *reinterpret_cast<f32x4*>(p.X + (size_t)col * d + s * 16 + 4 * quad) = resid;
+    }
+    raise_flag(p, c, flag, slot, tag);
+}
+
+// Output projection: logits of the strip's 16 vocabulary entries for every row.
+__device__ __forceinline__ void reduce_logits(const XP& p, Ctx& c, int io, int lane) {
+    const int col = lane & 15, quad = lane >> 4;
+    const unsigned tag = tag_of(c, p.L, F_A);
+    for (int i = 0;; ++i) {   // strips (i * 32 * kNIO + unit * kNIO + io) * 8 + XCD of the output projection
+        const int s = ((i * kPer + (int)c.j) * kNIO + io) * kXcd + (int)c.x;
+        if (s >= p.nstrips[X_LM]) break;
+        float rn = 1.f;
+        const f32x4 v = gather_partials(p, c, X_LM, s, p.ptab[p.poff[X_LM] + s], 0, tag, lane, true, &rn) * rn;
+        if (col < p.MR) *reinterpret_cast<f32x4*>(p.logit_s + (size_t)col * p.Vs + s * 16 + 4 * quad) = v;
+    }
+}
+
+// ------------------------------------------------------------------------- attention (as one unit's job)
+
+struct AttnAcc { float acc[8], mx, den; };
+
+__device__ __forceinline__ float sum8(float v) {
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));
+    return v;
+}
+__device__ __forceinline__ void halves8(v4u raw, float (&f)[8]) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        f[2 * e] = (float)__builtin_bit_cast(_Float16, (unsigned short)(raw[e] & 0xFFFFu));
+        f[2 * e + 1] = (float)__builtin_bit_cast(_Float16, (unsigned short)(raw[e] >> 16));
+    }
+}
+
+// One cache position per lane group; row r0 + r of the sequence sees it iff r0 + r >= row_lo.
+template <int RPJ>
+__device__ __forceinline__ void attend(const float (&q)[RPJ][8], int r0, v4u kraw, v4u vraw, int row_lo, int ke,
+                                       AttnAcc (&A)[RPJ]) {
+    float kf[8], vf[8];
+    halves8(kraw, kf);
+    halves8(vraw, vf);
+#pragma unroll
+    for (int r = 0; r < RPJ; ++r) {
+        float sc = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sc += q[r][e] * kf[e];
+        sc = sum8(sc);
+        if (r0 + r >= row_lo && r0 + r <= ke) {
+            const float mn = fmaxf(A[r].mx, sc);
+            const float corr = __expf(A[r].mx - mn), pw = __expf(sc - mn);
+            A[r].den = A[r].den * corr + pw;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) A[r].acc[e] = A[r].acc[e] * corr + pw * vf[e];
+            A[r].mx = mn;
+        }
+    }
+}
+
+// kNIT cache positions per lane group at once: all scores, one running-maximum update per row, then
+// the weighted values.
+template <int RPJ>
+__device__ __forceinline__ void attend_round(const float (&q)[RPJ][8], int r0, const v4u (&kk)[kNIT], const v4u (&vv)[kNIT],
+                                             int pos0, int stride, int o1, int ke, AttnAcc (&A)[RPJ]) {
+    float sc[RPJ][kNIT];
+#pragma unroll
+    for (int it = 0; it < kNIT; ++it) {
+        float kf[8];
+        halves8(kk[it], kf);
+        const bool on = pos0 + it * stride < o1;
+#pragma unroll
+        for (int r = 0; r < RPJ; ++r) {
+            float dd = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dd += q[r][e] * kf[e];
+            dd = sum8(dd);
+            sc[r][it] = (on && r0 + r <= ke) ? dd : -1e30f;
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < RPJ; ++r) {
+        float mn = A[r].mx;
+#pragma unroll
+        for (int it = 0; it < kNIT; ++it) mn = fmaxf(mn, sc[r][it]);
+        const float corr = __expf(A[r].mx - mn);
+        float sum = 0.f;
+#pragma unroll
+        for (int it = 0; it < kNIT; ++it) {
+            sc[r][it] = sc[r][it] > -1e29f ? __expf(sc[r][it] - mn) : 0.f;
+            sum += sc[r][it];
+        }
+        A[r].den = A[r].den * corr + sum;
+        A[r].mx = mn;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) A[r].acc[e] *= corr;
+    }
+#pragma unroll
+    for (int it = 0; it < kNIT; ++it) {
+        float vf[8];
+        halves8(vv[it], vf);
+#pragma unroll
+        for (int r = 0; r < RPJ; ++r)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) A[r].acc[e] += sc[r][it] * vf[e];
+    }
+}
+
+struct Lds {
+    unsigned* join;     // arrivals of the IO waves at their own barrier (only ever grows)
+    uint16_t* act0;     // staged K-slices, alternating between stages: hi plane, lo plane behind it; odd stages use
+    unsigned act_elems; //   the buffer act_elems elements further on (an offset, not a second pointer to choose from: a
+                        //   select between members by a run-time value tends to end up as indexing in memory)
+    float* ss0;         // sums of squares of the XCD's slice of the stage input, per row; odd stages 16 floats further on
+    float* part;        // attention: [kNIO][RPJ][kPS] partial rows of the IO waves
+    float* qs;          // attention: [RPJ][64] scaled queries
+};
+
+// Attention of one (sequence, head, row group) on the XCD that owns the head: the cached positions
+// (requested before the queries are there) and the rows appended by this launch.  The unit's compute
+// waves run attn_compute, its IO waves attn_io; both cross the same two workgroup barriers.
+
+// Workgroup barrier that orders LDS traffic only: the waves' own LDS accesses are done, nothing is said
+// about global memory (a full barrier would also wait for every weight tile in flight, including those
+// requested for later stages).
+__device__ __forceinline__ void lds_barrier() {
+    compiler_fence();
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    compiler_fence();
+}
+
+// Barrier of the unit's IO waves alone (LDS counter; the compute waves are busy fetching weights).
+// `joins`: barriers of this kind the wave has crossed so far.
+__device__ __forceinline__ void io_barrier(const Lds& s, unsigned& joins, int lane) {
+    const unsigned want = ++joins * kNIO;
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the wave's LDS writes are done
+    if (lane == 0) atomicAdd(s.join, 1u);
+    for (unsigned spins = 0; spins < kSpinLimit; ++spins) {
+        if ((int)(__hip_atomic_load(s.join, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - want) >= 0) break;
+        __builtin_amdgcn_s_sleep(1);
+    }
+    compiler_fence();
+}
+
+// Runs on the unit's four IO waves (they hold no weights): each takes a quarter of the cached positions.
+template <int RPJ>
+__device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, const Lds& s, int layer, unsigned stage,
+                                        unsigned& joins) {
+    if (jb.a_rg < 0) return;   // this unit has no job (the same for all its waves)
+    const int io = (threadIdx.x >> 6) - kCW, lane = threadIdx.x & 63;
+    const int seq = jb.a_seq, h = jb.a_h, RS = p.RS, r0 = jb.a_rg * RPJ;
+    const int pg = lane >> 3, dg = lane & 7;
+    const int b = seq % p.B, ke = p.k_eff[b];
+    const int kv0 = ke >= 0 ? p.C + p.n[b] - 1 : 0;   // positions cached before this launch
+    const int nrounds = (kv0 + kNIT * kNIO * 8 - 1) / (kNIT * kNIO * 8);
+    const size_t head0 = ((((size_t)layer * p.Smax + seq) * p.H + h) * p.Tmax) * 64;   // the head's entries, contiguous
+    const _Float16* Kb = fresh(p.Kc + head0 + dg * 8);
+    const _Float16* Vb = fresh(p.Vc + head0 + dg * 8);
+    const unsigned tag = tag_of(c, layer, F_B);
+    uint8_t* buf = xcd_buf(p, c.x, layer & 1);
+    v4u ka[kNIT], va[kNIT], kb[kNIT], vb[kNIT], kc[kNIT], vc[kNIT];   // three rounds in flight
+    auto fetch = [&](v4u (&kk)[kNIT], v4u (&vv)[kNIT], int rnd) {
+#pragma unroll
+        for (int it = 0; it < kNIT; ++it) {
+            const int pos = (rnd * kNIT + it) * (kNIO * 8) + io * 8 + pg;
+            if (pos < kv0) {
+                kk[it] = *reinterpret_cast<const v4u*>(Kb + (size_t)pos * 64);
+                vv[it] = *reinterpret_cast<const v4u*>(Vb + (size_t)pos * 64);
+            } else {
+                kk[it] = (v4u){0u, 0u, 0u, 0u};
+                vv[it] = (v4u){0u, 0u, 0u, 0u};
+            }
+        }
+    };
+    stamp(c, stage, 0);
+    fetch(ka, va, 0);
+    fetch(kb, vb, 1);
+    fetch(kc, vc, 2);
+    if (io == 0) {
+        wait_flags(p, c, F_A, jb.nA, tag_of(c, layer, F_A));
+        stamp(c, stage, 1);
+        const float* q = reinterpret_cast<const float*>(buf + p.o_q);
+        for (int r = 0; r < RPJ; ++r)
+            s.qs[r * 64 + lane] = r0 + r < RS ? __uint_as_float(ld_u32(q + (size_t)(seq * RS + r0 + r) * (p.KpO - 8) +
+                                                                        (h - p.hd0[c.x]) * 64 + lane))
+                                              : 0.f;
+    }
+    io_barrier(s, joins, lane);   // the queries are in LDS
+    {
+        AttnAcc A[RPJ];
+#pragma unroll
+        for (int r = 0; r < RPJ; ++r) {
+            A[r].mx = -1e30f; A[r].den = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) A[r].acc[e] = 0.f;
+        }
+        float q[RPJ][8];
+#pragma unroll
+        for (int r = 0; r < RPJ; ++r) {
+            const float4 qa = *reinterpret_cast<const float4*>(s.qs + r * 64 + dg * 8);
+            const float4 qb = *reinterpret_cast<const float4*>(s.qs + r * 64 + dg * 8 + 4);
+            q[r][0] = qa.x; q[r][1] = qa.y; q[r][2] = qa.z; q[r][3] = qa.w;
+            q[r][4] = qb.x; q[r][5] = qb.y; q[r][6] = qb.z; q[r][7] = qb.w;
+        }
+        auto run = [&](const v4u (&kk)[kNIT], const v4u (&vv)[kNIT], int rnd) {
+            const int pos0 = rnd * kNIT * (kNIO * 8) + io * 8 + pg;
+            attend_round<RPJ>(q, r0, kk, vv, pos0, kNIO * 8, kv0, ke, A);
+        };
+        // rows appended by this launch: stored by this XCD's reduce jobs (their flags have been seen);
+        // requested now, used after the cached positions
+        const bool fresh_row = io == 0 && pg <= ke && pg < RS;
+        v4u kn = (v4u){0u, 0u, 0u, 0u}, vn = (v4u){0u, 0u, 0u, 0u};
+        if (fresh_row) {
+            const unsigned at = (unsigned)((kv0 + pg) * 64 + dg * 8) * 2u;
+            kn = ld_16(make_rsrc(p.Kc + head0), at);
+            vn = ld_16(make_rsrc(p.Vc + head0), at);
+        }
+        for (int rnd = 0; rnd < nrounds; rnd += 3) {
+            run(ka, va, rnd);
+            if (rnd + 3 < nrounds) fetch(ka, va, rnd + 3);
+            if (rnd + 1 < nrounds) run(kb, vb, rnd + 1);
+            if (rnd + 4 < nrounds) fetch(kb, vb, rnd + 4);
+            if (rnd + 2 < nrounds) run(kc, vc, rnd + 2);
+            if (rnd + 5 < nrounds) fetch(kc, vc, rnd + 5);
+        }
+        if (fresh_row) attend<RPJ>(q, r0, kn, vn, pg, ke, A);   // row r sees appended row pg iff pg <= r
+#pragma unroll
+        for (int r = 0; r < RPJ; ++r) {
+#pragma unroll
+            for (int o = 8; o < 64; o <<= 1) {
+                auto other = [&](float xx) { return o == 8 ? lane_xor8(xx) : (o == 16 ? lane_xor16(xx) : lane_xor32(xx)); };
+                const float omx = other(A[r].mx), oden = other(A[r].den);
+                const float mn = fmaxf(A[r].mx, omx);
+                const float f0 = __expf(A[r].mx - mn), f1 = __expf(omx - mn);
+                A[r].den = A[r].den * f0 + oden * f1;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) A[r].acc[e] = A[r].acc[e] * f0 + other(A[r].acc[e]) * f1;
+                A[r].mx = mn;
+            }
+            if (pg == 0) {
+                float* mine = s.part + ((size_t)io * RPJ + r) * kPS;
+                *reinterpret_cast<float4*>(mine + dg * 8) = make_float4(A[r].acc[0], A[r].acc[1], A[r].acc[2], A[r].acc[3]);
+                *reinterpret_cast<float4*>(mine + dg * 8 + 4) = make_float4(A[r].acc[4], A[r].acc[5], A[r].acc[6], A[r].acc[7]);
+                if (dg == 0) *reinterpret_cast<float2*>(mine + 64) = make_float2(A[r].mx, A[r].den);
+            }
+        }
+    }
+    io_barrier(s, joins, lane);   // the waves' partial rows are in LDS
+    if (io == 0) {   // merge them; lane: row lane / 16 of the job, dims 4 * (lane % 16) .. + 3
+        const int r = lane >> 4, q4 = lane & 15;
+        if (r < RPJ && r0 + r < RS) {
+            float m2 = -1e30f;
+#pragma unroll
+            for (int w = 0; w < kNIO; ++w) m2 = fmaxf(m2, s.part[((size_t)w * RPJ + r) * kPS + 64]);
+            float dn = 0.f;
+            f32x4 o = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < kNIO; ++w) {
+                const float* src = s.part + ((size_t)w * RPJ + r) * kPS;
+                const float f = __expf(src[64] - m2);
+                dn += src[65] * f;
+                o += *reinterpret_cast<const f32x4*>(src + 4 * q4) * f;
+            }
+            const float inv = dn > 0.f ? 1.0f / dn : 0.f;
+            uint16_t* hi = reinterpret_cast<uint16_t*>(buf + p.o_o);
+            uint16_t* lo = hi + (size_t)16 * p.KpO;
+            const size_t at = (size_t)(seq * RS + r0 + r) * p.KpO + (h - p.hd0[c.x]) * 64 + 4 * q4;
+            put_split4(hi + at, lo + at, o * inv);
+        }
+        raise_flag(p, c, F_B, jb.a_slot, tag);
+        stamp(c, stage, 2);
+    }
+}
+
+// ------------------------------------------------------------------------- one matrix-product stage
+
+__device__ __forceinline__ unsigned product_tag(const XP& p, const Ctx& c, int kind, int layer) {
+    return kind == X_LM ? tag_of(c, p.L, F_A)
+                        : tag_of(c, layer, kind == X_A ? F_A : kind == X_C ? F_C : kind == X_D ? F_D : F_E);
+}
+
+// Compute waves.  KIND: which matrix; NSW: strips per wave and round; KTM: most k-tiles an XCD's slice
+// has.  w holds this stage's tiles, requested one or two stages ago.
+template <int KIND, int NSW, int KTM>
+__device__ __forceinline__ void compute_stage(const XP& p, const Ctx& c, const GJob& g, const Lds& s, int layer, unsigned stage,
+                                              int Kp, v4u (&w)[NSW * KTM]) {
+    const int lane = threadIdx.x & 63;
+    const uint16_t* act_hi = s.act0 + (size_t)(stage & 1u) * s.act_elems;
+    const uint16_t* act_lo = act_hi + (size_t)16 * Kp;
+    const unsigned tag = product_tag(p, c, KIND, layer);
+    const int ring = KIND == X_LM ? 0 : (layer & 1);
+    stamp(c, stage, 0);
+    lds_barrier();   // the XCD's slice of the stage input is in LDS
+    stamp(c, stage, 1);
+    const float* ssrow = (KIND == X_C || KIND == X_E) ? nullptr : s.ss0 + (stage & 1u) * 16;
+    mfma_store<NSW, KTM>(p, KIND, g, c, lane, w, act_hi, act_lo, ssrow, Kp, ring, tag, 0, stage);
+    stamp(c, stage, 2);
+    // Loads and stores share one counter and complete out of order among each other: with stores
+    // pending, "wait for the first n loads" is not expressible and every wait becomes "wait for
+    // everything".  So the stores are acknowledged before any further tile is requested.
+    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
+    stamp(c, stage, 4);
+    if (KIND == X_LM) {   // further rounds of the output projection: same staged input
+        for (int r = 1; r < p.lm_rounds; ++r) {
+            issue_tiles<NSW, KTM>(p, g, 0, lane, w, r);
+            mfma_store<NSW, KTM>(p, KIND, g, c, lane, w, act_hi, act_lo, ssrow, Kp, ring, tag, r);
+        }
+    }
+}
+
+// IO waves: wait for the producers of the stage input on this XCD, stage the XCD's slice in LDS, then -
+// while the compute waves multiply - do the wave's reduce job of this stage.  kind is a run-time value
+// (X_A .. X_LM): one copy of this code serves every product.
+__device__ __forceinline__ void io_stage(const XP& p, Ctx& c, const IoJobs& jb, const Lds& s, int kind, int layer, unsigned stage,
+                                         f32x4& resid) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    // whose flags announce the stage input, and where it is: QKV and the output projection read x (stage E
+    // of the layer before, or the prologue), Wo the attention's rows, W1|W3 x' (stage C), W2 the hidden vector
+    const int wait_flag = (kind == X_A || kind == X_LM) ? F_E : kind == X_C ? F_B : kind == X_D ? F_C : F_D;
+    const unsigned wait_tag = tag_of(c, (kind == X_A || kind == X_LM) ? layer - 1 : layer, wait_flag);
+    const u64 region = (kind == X_A || kind == X_LM) ? p.o_a : kind == X_C ? p.o_o : kind == X_D ? p.o_x2 : p.o_h;
+    const int Kp = kind == X_C ? p.KpO : kind == X_E ? p.KpH : p.KpA;
+    const int nwait = wait_flag == F_E ? jb.nE : wait_flag == F_B ? jb.nB : wait_flag == F_C ? jb.nC : jb.nD;
+    stamp(c, stage, 0);
+    wait_flags(p, c, wait_flag, nwait, wait_tag);
+    stamp(c, stage, 1);
+    if (kind != X_C && kind != X_E && wave == kCW + kNIO - 1 && lane < p.MR) {
+        // The product follows a norm: the sums of squares of this XCD's slice of its input, row by row - its
+        // owners' strips added in strip order - for the compute waves to send along with their partial sums.
+        const int per_xcd = p.d / 16 / kXcd;
+        const float* ss = reinterpret_cast<const float*>(xcd_buf(p, c.x, layer & 1) + p.o_ss) + (size_t)(kind == X_D) * per_xcd * 16 + lane;
+        float v[16], a = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = i < per_xcd ? __uint_as_float(ld_u32(ss + i * 16)) : 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) a += v[i];
+        s.ss0[(stage & 1u) * 16 + lane] = a;
+    }
+    stage_copy(make_rsrc(p.xbuf), (unsigned)(((size_t)c.x * kRing + (layer & 1)) * p.xcd_bytes + region), p.MR, Kp,
+               s.act0 + (size_t)(stage & 1u) * s.act_elems, threadIdx.x - kCW * 64);
+    stamp(c, stage, 2);
+    lds_barrier();
+    if (kind == X_LM) reduce_logits(p, c, wave - kCW, lane);
+    else reduce_job(p, c, jb, kind, layer, lane, resid, stage);
+    stamp(c, stage, 3);
+}
+
+// Template arguments: strips per compute wave and round / most k-tiles per XCD slice of QKV, Wo, W1|W3,
+// W2; strips per wave and round of the output projection.  Weights are requested one or two stages
+// ahead: Wo and W1|W3 behind QKV's products (they arrive while the attention runs), W2 and the next
+// layer's QKV behind W1|W3's.
+template <int NA, int KA, int NC, int KC, int ND, int KD, int NE, int KE, int NL>
+__device__ __forceinline__ void compute_main(const XP& p, const Ctx& c, const Lds& s) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const GJob gA = load_gjob(p, X_A, c, wave), gC = load_gjob(p, X_C, c, wave), gD = load_gjob(p, X_D, c, wave);
+    const GJob gE = load_gjob(p, X_E, c, wave), gL = load_gjob(p, X_LM, c, wave);
+    v4u wA[NA * KA], wC[NC * KC], wD[ND * KD], wE[NE * KE];
+    issue_tiles<NA, KA>(p, gA, 0, lane, wA);
+    unsigned stage = 0;
+    for (int l = 0; l < p.L; ++l) {
+        const u64 lb = (u64)l * p.layer_tiles;
+        compute_stage<X_A, NA, KA>(p, c, gA, s, l, stage++, p.KpA, wA);
+        issue_tiles<NC, KC>(p, gC, lb, lane, wC);   // both arrive while the attention runs
+        issue_tiles<ND, KD>(p, gD, lb, lane, wD);
+        ++stage;   // attention: the IO waves' business
+        compute_stage<X_C, NC, KC>(p, c, gC, s, l, stage++, p.KpO, wC);
+        compute_stage<X_D, ND, KD>(p, c, gD, s, l, stage++, p.KpA, wD);
+        issue_tiles<NE, KE>(p, gE, lb, lane, wE);
+        if (l + 1 < p.L) issue_tiles<NA, KA>(p, gA, lb + p.layer_tiles, lane, wA);
+        compute_stage<X_E, NE, KE>(p, c, gE, s, l, stage++, p.KpH, wE);
+    }
+    v4u wL[NL * KA];
+    issue_tiles<NL, KA>(p, gL, 0, lane, wL);
+    compute_stage<X_LM, NL, KA>(p, c, gL, s, p.L, stage++, p.KpA, wL);
+}
+
+template <int RPJ>
+__device__ __forceinline__ void io_main(const XP& p, Ctx& c, const Lds& s) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const IoJobs jb = load_io_jobs(p, c, wave - kCW, lane);
+    f32x4 resid = (f32x4){0.f, 0.f, 0.f, 0.f};   // the wave's strip of the residual stream (owners of Wo / W2 strips)
+    if (jb.sE >= 0) {   // Prologue: the owners of the residual strips pick their slice of the embedded rows up
+                                // and publish it as stage E of "layer -1" would.
+        const int strip = jb.sE, col = lane & 15, quad = lane >> 4;
+        const uint2 gain = *reinterpret_cast<const uint2*>(p.blob + p.g1_off / 2 + strip * 16 + 4 * quad);
+        resid = col < p.MR ? *reinterpret_cast<const f32x4*>(p.X + (size_t)col * p.d + strip * 16 + 4 * quad)
+                           : (f32x4){0.f, 0.f, 0.f, 0.f};
+        put_stream(p, c, 0, 0, strip, lane, resid, gain);
+        raise_flag(p, c, F_E, jb.tE, tag_of(c, -1, F_E));
+    }
+    unsigned joins = 0;
+    // stages of the pass in order: per layer QKV, attention, Wo, W1|W3, W2; then the output projection
+    // on the final norm's input (published by the last stage E into ring slot L & 1)
+    const unsigned nstages = 5u * (unsigned)p.L + 1u;
+#pragma nounroll
+    for (unsigned stage = 0; stage < nstages; ++stage) {
+        const int l = (int)(stage / 5u), st = (int)(stage - 5u * (unsigned)l);
+        if (st == 1) attn_io<RPJ>(p, c, jb, s, l, stage, joins);
+        else io_stage(p, c, jb, s, l == p.L ? X_LM : st == 0 ? X_A : st == 2 ? X_C : st == 3 ? X_D : X_E, l, stage, resid);
+    }
+}
+
+template <int NA, int KA, int NC, int KC, int ND, int KD, int NE, int KE, int NL, int RPJ>
+__global__ __launch_bounds__(kThreads, 1) void verify_xcd_kernel(const XP* __restrict__ params, unsigned epoch0, u64* dbg) {
+    // The parameter block lives in device memory (written when the step shape changes): tables in it are
+    // indexed with run-time values, which a by-value kernel argument would answer with a private copy.
+    const XP& p = *params;
+    extern __shared__ uint4 smem_raw[];
+    Lds s;
+    const size_t act_elems = (size_t)2 * 16 * max(max(p.KpA, p.KpO), p.KpH);
+    s.join = reinterpret_cast<unsigned*>(smem_raw);
+    s.act0 = reinterpret_cast<uint16_t*>(smem_raw + 1);
+    s.act_elems = (unsigned)act_elems;
+    s.part = reinterpret_cast<float*>(s.act0 + 2 * act_elems);
+    s.qs = s.part + kNIO * RPJ * kPS;
+    s.ss0 = s.qs + RPJ * 64;
+    if (threadIdx.x == 0) *s.join = 0u;
+    __syncthreads();
+    Ctx c;
+    c.x = blockIdx.x % kXcd; c.j = blockIdx.x / kXcd; c.epoch0 = epoch0; c.dead = false; c.err = p.err; c.dbg = dbg;
+    if (xcc_id() != c.x) give_up(c);   // the dispatch order this layout relies on does not hold: fail, never hang
+    // The two kinds of waves run separate code (and cross the same workgroup barriers), so that neither
+    // carries the other's registers: compute waves the weights in flight, IO waves the attention's keys
+    // and values and the partial sums of a reduce job.
+    if ((threadIdx.x >> 6) >= kCW) io_main<RPJ>(p, c, s);
+    else compute_main<NA, KA, NC, KC, ND, KD, NE, KE, NL>(p, c, s);
+}
+
+// Copies one matrix into the packed order: tile T of the stream is (strip, k-tile) = desc[T]; lane l
+// holds row l % 16, columns 8 * (l / 16) .. + 7 of that tile.  pairs > 0: W1 | W3 with strip rows 0..7
+// from W1 and 8..15 from W3 (pairs = rows of W1).
+__global__ void xcd_repack_kernel(const uint16_t* W, int K, int pairs, int row0, const uint32_t* desc, uint4* out) {
+    const size_t tile = blockIdx.x;
+    const int lane = threadIdx.x;
+    const uint32_t dsc = desc[tile];
+    const int strip = dsc >> 12, kt = dsc & 4095, r = lane & 15;
+    size_t row = (size_t)(row0 + strip * 16 + r);
+    if (pairs > 0) row = (size_t)((r < 8 ? 0 : pairs) + strip * 8 + (r & 7));
+    const size_t col = (size_t)kt * 32 + (lane >> 4) * 8;
+    out[tile * 64 + lane] = *reinterpret_cast<const uint4*>(W + row * K + col);
+}
+
+size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+}  // namespace
+
+// ------------------------------------------------------------------------- host: plan
+
+struct XcdPlan {
+    bool ok;
+    int KT[X_NK][kXcd], kt0[X_NK][kXcd], nstrips[X_NK];
+    int hd0[kXcd + 1], ke0[kXcd + 1];
+    size_t xbase[X_NK][kXcd], layer_tiles, total_tiles;
+    int njobs[F_NF][kXcd];
+    int NSW[X_NK];                 // strips per compute wave and round the plan needs
+    int lm_rounds;
+    int KpA, KpO, KpH;
+    std::vector<int16_t> gtab, rtab, ptab;
+    int poff[X_NK];
+    std::vector<uint8_t> params;   // the parameter block as last uploaded
+    std::vector<uint32_t> desc;    // (strip << 12) | k-tile per packed tile, kinds in stream order of one layer, then the output projection
+    size_t desc_kind[X_NK][kXcd];  // index of (kind, XCD)'s first descriptor
+    unsigned epoch;
+};
+
+namespace {
+
+bool xcd_shape_ok(const hawk_ctx* c) {
+    if (c->cfg.dtype != HAWK_BF16 || c->hd != 64) return false;
+    if (!((c->d == 1280 && c->m == 3456 && c->H == 20) || (c->d == 768 && c->m == 2048 && c->H == 12))) return false;
+    if (c->Vs % (16 * kXcd) || c->d % (32 * kXcd) || c->H < kXcd) return false;
+    return true;
+}
+
+// Contiguous split of n items into `parts` ranges; the first `n % parts` ranges (or the last, if
+// extra_last) take one more.
+void split_ranges(int n, int parts, bool extra_last, std::vector<int>& start) {
+    start.assign(parts + 1, 0);
+    const int base = n / parts, extra = n % parts;
+    for (int i = 0; i < parts; ++i) {
+        const bool more = extra_last ? i >= parts - extra : i < extra;
+        start[i + 1] = start[i] + base + (more ? 1 : 0);
+    }
+}
+
+void build_xcd_plan(const hawk_ctx* c, XcdPlan* P) {
+    P->ok = xcd_shape_ok(c);
+    P->epoch = 0;
+    if (!P->ok) return;
+    const int d = c->d, m = c->m, H = c->H;
+    P->nstrips[X_A] = 3 * d / 16; P->nstrips[X_C] = d / 16; P->nstrips[X_D] = 2 * m / 16; P->nstrips[X_E] = d / 16;
+    P->nstrips[X_LM] = c->Vs / 16;
+    std::vector<int> hs, es;
+    split_ranges(H, kXcd, false, hs);           // heads per XCD
+    split_ranges(m / 32, kXcd, false, es);      // k-tiles of the MLP's hidden vector per XCD
+    for (int x = 0; x <= kXcd; ++x) { P->hd0[x] = hs[x]; P->ke0[x] = es[x]; }
+    int maxO = 0, maxH = 0;
+    for (int x = 0; x < kXcd; ++x) {
+        P->KT[X_A][x] = P->KT[X_D][x] = P->KT[X_LM][x] = d / 32 / kXcd;
+        P->kt0[X_A][x] = P->kt0[X_D][x] = P->kt0[X_LM][x] = x * (d / 32 / kXcd);
+        P->KT[X_C][x] = 2 * (hs[x + 1] - hs[x]); P->kt0[X_C][x] = 2 * hs[x];
+        P->KT[X_E][x] = es[x + 1] - es[x]; P->kt0[X_E][x] = es[x];
+        maxO = std::max(maxO, P->KT[X_C][x] * 32);
+        maxH = std::max(maxH, P->KT[X_E][x] * 32);
+    }
+    P->KpA = d / kXcd + 8; P->KpO = maxO + 8; P->KpH = maxH + 8;
+    // strips of (unit j, compute wave w): contiguous; the kinds alternate which half of the units takes
+    // the extra strip so that every unit streams about the same bytes per layer
+    P->gtab.assign((size_t)X_NK * kPer * kCW * 2, 0);
+    for (int k = 0; k < X_NK; ++k) {
+        std::vector<int> us, ws;
+        split_ranges(P->nstrips[k], kPer, k == X_A || k == X_D, us);
+        int need = 0;
+        for (int j = 0; j < kPer; ++j) {
+            split_ranges(us[j + 1] - us[j], kCW, false, ws);
+            for (int w = 0; w < kCW; ++w) {
+                P->gtab[(((size_t)k * kPer + j) * kCW + w) * 2] = (int16_t)(us[j] + ws[w]);
+                P->gtab[(((size_t)k * kPer + j) * kCW + w) * 2 + 1] = (int16_t)(ws[w + 1] - ws[w]);
+                need = std::max(need, ws[w + 1] - ws[w]);
+            }
+        }
+        P->NSW[k] = need;
+        if (P->nstrips[k] > 32767) P->ok = false;
+    }
+    for (int k = 0; k < X_NK; ++k) {   // producer of every strip (the output projection takes two rounds of half the strips)
+        P->poff[k] = (int)P->ptab.size();
+        P->ptab.resize(P->ptab.size() + P->nstrips[k], 0);
+        const int per_round = k == X_LM ? 4 : P->NSW[k];   // the kernel's instances take 4 output-projection strips per round
+        for (int j = 0; j < kPer; ++j)
+            for (int w = 0; w < kCW; ++w) {
+                const int16_t* g = &P->gtab[(((size_t)k * kPer + j) * kCW + w) * 2];
+                for (int i = 0; i < g[1]; ++i)
+                    P->ptab[P->poff[k] + g[0] + i] = (int16_t)((j * kCW + w) * 2 + std::min(i / std::max(per_round, 1), 1));
+            }
+    }
+    // packed stream of a layer: per kind, per XCD, strips in order, the XCD's k-tiles of each
+    P->desc.clear();
+    size_t off = 0;
+    for (int k = 0; k < X_NK; ++k) {
+        if (k == X_LM) P->layer_tiles = off;
+        for (int x = 0; x < kXcd; ++x) {
+            P->xbase[k][x] = k == X_LM ? (size_t)c->L * P->layer_tiles + (off - P->layer_tiles) : off;
+            P->desc_kind[k][x] = P->desc.size();
+            for (int s = 0; s < P->nstrips[k]; ++s)
+                for (int t = 0; t < P->KT[k][x]; ++t) P->desc.push_back(((uint32_t)s << 12) | (uint32_t)(P->kt0[k][x] + t));
+            off += (size_t)P->nstrips[k] * P->KT[k][x];
+        }
+    }
+    P->total_tiles = (size_t)c->L * P->layer_tiles + (off - P->layer_tiles);
+    // reduce jobs: the IO wave (unit, wave) of the owner XCD that finishes a strip, and its flag slot
+    P->rtab.assign((size_t)X_NK * kXcd * kPer * kNIO * 2, -1);
+    for (int f = 0; f < F_NF; ++f)
+        for (int x = 0; x < kXcd; ++x) P->njobs[f][x] = 0;
+    auto owner_of = [&](int k, int s) -> int {
+        if (k == X_A) {   // the XCD that owns the strip's head
+            const int h = ((s * 16) % d) / 64;
+            for (int x = 0; x < kXcd; ++x)
+                if (h < hs[x + 1]) return x;
+        }
+        if (k == X_C || k == X_E) return s / (d / 16 / kXcd);
+        if (k == X_D) {   // the XCD that owns the k-tile of the hidden vector the strip's 8 values fall into
+            const int t = (s * 8) / 32;
+            for (int x = 0; x < kXcd; ++x)
+                if (t < es[x + 1]) return x;
+        }
+        return 0;
+    };
+    const int flag_of[4] = {F_A, F_C, F_D, F_E};
+    for (int k = X_A; k <= X_E; ++k) {
+        int count[kXcd] = {0}, total[kXcd] = {0};
+        for (int s = 0; s < P->nstrips[k]; ++s) total[owner_of(k, s)]++;
+        for (int s = 0; s < P->nstrips[k]; ++s) {
+            const int x = owner_of(k, s), i = count[x]++;
+            // Wo and W2 strips: the same wave owns the strip's residual in both (last IO wave of unit i).
+            // QKV strips: the last units of the XCD, three waves each - the first units run the attention
+            // jobs and should start on their keys and values at once.  W1|W3 strips go round the units.
+            const int nu = (total[x] + kNIO - 2) / (kNIO - 1);
+            const int j = (k == X_C || k == X_E) ? i : k == X_A ? kPer - 1 - i % nu : i % kPer;
+            const int w = (k == X_C || k == X_E) ? kNIO - 1 : k == X_A ? i / nu : i / kPer;
+            if (j >= kPer || w >= ((k == X_C || k == X_E) ? kNIO : kNIO - 1) || i >= kMaxJobs) { P->ok = false; return; }
+            int16_t* e = &P->rtab[((((size_t)k * kXcd + x) * kPer + j) * kNIO + w) * 2];
+            e[0] = (int16_t)s;
+            e[1] = (int16_t)i;
+        }
+        for (int x = 0; x < kXcd; ++x) P->njobs[flag_of[k]][x] = count[x];
+    }
+    const int per_round = kPer * kCW * P->NSW[X_LM];
+    (void)per_round;
+    P->lm_rounds = 1;
+}
+
+// Attention jobs of a step with RS rows per sequence: (sequence, head, row group) per unit of the XCD
+// that owns the head.
+bool attn_jobs(const hawk_ctx* c, const XcdPlan* P, int RS, int* RPJ, std::vector<int16_t>& atab, int (&nj)[kXcd]) {
+    int rpj = 1;
+    for (;; ++rpj) {
+        if (rpj > 2) return false;
+        bool fits = true;
+        for (int x = 0; x < kXcd; ++x)
+            fits = fits && (P->hd0[x + 1] - P->hd0[x]) * c->S * ((RS + rpj - 1) / rpj) <= kPer;
+        if (fits) break;
+    }
+    *RPJ = rpj;
+    atab.assign((size_t)kXcd * kPer * 4, -1);
+    for (int x = 0; x < kXcd; ++x) {
+        int i = 0;
+        for (int seq = 0; seq < c->S; ++seq)
+            for (int h = P->hd0[x]; h < P->hd0[x + 1]; ++h)
+                for (int rg = 0; rg < (RS + rpj - 1) / rpj; ++rg, ++i) {
+                    int16_t* e = &atab[((size_t)x * kPer + i) * 4];
+                    e[0] = (int16_t)seq; e[1] = (int16_t)h; e[2] = (int16_t)rg; e[3] = (int16_t)i;
+                }
+        nj[x] = i;
+    }
+    return true;
+}
+
+// Regions of one XCD buffer (bytes): split planes are uint16 [2][16][Kp].
+size_t xcd_buf_layout(const XcdPlan* P, XP* p) {
+    size_t at = 0;
+    auto take = [&](size_t n) { size_t a = at; at = up256(at + n); return a; };
+    const size_t a = take((size_t)2 * 16 * P->KpA * 2), q = take((size_t)16 * (P->KpO - 8) * 4);
+    const size_t o = take((size_t)2 * 16 * P->KpO * 2), x2 = take((size_t)2 * 16 * P->KpA * 2);
+    const size_t h = take((size_t)2 * 16 * P->KpH * 2);
+    const size_t ss = take((size_t)2 * 16 * 16 * 4);   // sums of squares of the XCD's strips: [2][strips of an XCD <= 16][16 rows]
+    if (p) { p->o_a = a; p->o_q = q; p->o_o = o; p->o_x2 = x2; p->o_h = h; p->o_ss = ss; }
+    return at;
+}
+
+}  // namespace
+
+size_t xcd_workspace(const hawk_ctx* c, size_t base, XcdOffsets* o) {
+    memset(o, 0, sizeof *o);
+    XcdPlan P;
+    build_xcd_plan(c, &P);
+    if (!P.ok) return 0;
+    size_t p = base;
+    auto take = [&](size_t bytes) { size_t at = p; p = up256(p + bytes); return at; };
+    o->wpack = take(P.total_tiles * 1024);
+    o->zero = take(1024);
+    o->desc = take(P.desc.size() * 4);
+    o->gtab = take(P.gtab.size() * 2);
+    o->rtab = take(P.rtab.size() * 2);
+    o->ptab = take(P.ptab.size() * 2);
+    o->atab = take((size_t)kXcd * kPer * 4 * 2);
+    o->xp = take(4096);
+    for (int k = 0; k < X_NK; ++k)
+        o->part[k] = take((size_t)(k == X_LM ? 1 : kRing) * kXcd * P.nstrips[k] * 16 * 16 * 8);
+    for (int k = 0; k < X_NK; ++k)
+        o->pss[k] = (k == X_C || k == X_E) ? 0 : take((size_t)kRing * kXcd * kPer * kCW * 2 * 16 * 8);
+    o->xcd_bytes = xcd_buf_layout(&P, nullptr);
+    o->xbuf = take((size_t)kXcd * kRing * o->xcd_bytes);
+    o->lflag = take((size_t)kXcd * F_NF * kMaxJobs * 4);
+    o->dbg = take((size_t)2 * 512 * 16 * 8);
+    return p - base;
+}
+
+XcdPlan* xcd_create(hawk_ctx* c) {
+    XcdPlan* P = new XcdPlan();
+    build_xcd_plan(c, P);
+    if (!P->ok) return P;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        cus != kNWG) {   // the layout needs exactly one workgroup per unit, 32 units per XCD
+        P->ok = false;
+        return P;
+    }
+    const XcdOffsets& o = c->xoff;
+    bool good = true;
+    good = good && hipMemcpyAsync(c->ws + o.desc, P->desc.data(), P->desc.size() * 4, hipMemcpyHostToDevice, c->stream) == hipSuccess;
+    good = good && hipMemcpyAsync(c->ws + o.gtab, P->gtab.data(), P->gtab.size() * 2, hipMemcpyHostToDevice, c->stream) == hipSuccess;
+    good = good && hipMemcpyAsync(c->ws + o.rtab, P->rtab.data(), P->rtab.size() * 2, hipMemcpyHostToDevice, c->stream) == hipSuccess;
+    good = good && hipMemcpyAsync(c->ws + o.ptab, P->ptab.data(), P->ptab.size() * 2, hipMemcpyHostToDevice, c->stream) == hipSuccess;
+    // tags start at 1: zeroed flag words, partial sums and sums of squares are "older than everything"
+    good = good && hipMemsetAsync(c->ws + o.zero, 0, 1024, c->stream) == hipSuccess;
+    good = good && hipMemsetAsync(c->ws + o.lflag, 0, (size_t)kXcd * F_NF * kMaxJobs * 4, c->stream) == hipSuccess;
+    for (int k = 0; k < X_NK; ++k)
+        good = good && hipMemsetAsync(c->ws + o.part[k], 0, (size_t)(k == X_LM ? 1 : kRing) * kXcd * P->nstrips[k] * 16 * 16 * 8,
+                                      c->stream) == hipSuccess;
+    for (int k = 0; k < X_NK; ++k)
+        if (k != X_C && k != X_E)
+            good = good && hipMemsetAsync(c->ws + o.pss[k], 0, (size_t)kRing * kXcd * kPer * kCW * 2 * 16 * 8, c->stream) == hipSuccess;
+    good = good && hipMemsetAsync(c->ws + o.xbuf, 0, (size_t)kXcd * kRing * o.xcd_bytes, c->stream) == hipSuccess;
+    good = good && hipStreamSynchronize(c->stream) == hipSuccess;
+    if (!good) P->ok = false;
+    return P;
+}
+
+void xcd_destroy(XcdPlan* P) { delete P; }
+
+// Re-tiles every matrix of the loaded blob into the packed order (after hawk_load).
+int xcd_repack(hawk_ctx* c) {
+    XcdPlan* P = c->xplan;
+    if (!P || !P->ok) return 0;
+    const uint16_t* blob = wsp<uint16_t>(c, c->off.blob);
+    uint4* wp = wsp<uint4>(c, c->xoff.wpack);
+    const uint32_t* desc = wsp<uint32_t>(c, c->xoff.desc);
+    auto run = [&](size_t blob_off, int K, int kind, size_t layer_base, int pairs, int row0) {
+        for (int x = 0; x < kXcd; ++x) {
+            const size_t tiles = (size_t)P->nstrips[kind] * P->KT[kind][x];
+            xcd_repack_kernel<<<(unsigned)tiles, 64, 0, c->stream>>>(blob + blob_off / 2, K, pairs, row0, desc + P->desc_kind[kind][x],
+                                                                    wp + (layer_base + P->xbase[kind][x]) * 64);
+        }
+    };
+    for (int l = 0; l < c->L; ++l) {
+        const size_t lb = (size_t)l * P->layer_tiles;
+        run(c->w.Wqkv[l], c->d, X_A, lb, 0, 0);
+        run(c->w.Wo[l], c->d, X_C, lb, 0, 0);
+        run(c->w.W13[l], c->d, X_D, lb, c->m, 0);
+        run(c->w.W2[l], c->m, X_E, lb, 0, 0);
+    }
+    run(c->w.W_out, c->d, X_LM, 0, 0, c->cfg.samp_lo);
+    if (hipGetLastError() != hipSuccess) return -1;
+    return hipStreamSynchronize(c->stream) == hipSuccess ? 0 : -1;
+}
+
+namespace {
+
+struct XcdShape { int NA, KA, NC, KC, ND, KD, NE, KE, NL; };
+
+size_t xcd_lds_bytes(const XcdPlan* P, int RPJ) {
+    const size_t act = (size_t)2 * 16 * std::max(std::max(P->KpA, P->KpO), P->KpH) * 2;
+    return 16 + 2 * act + (size_t)(kNIO * RPJ * kPS + RPJ * 64 + 32) * 4 + 64;
+}
+
+}  // namespace
+
+bool xcd_ok(const hawk_ctx* c, int k) {
+    const XcdPlan* P = c->xplan;
+    if (!P || !P->ok || c->path != 1) return false;
+    const int RS = k + 1, MR = c->S * RS;
+    if (MR > 16 || RS > 8) return false;
+    for (int x = 0; x < kXcd; ++x)
+        if ((P->hd0[x + 1] - P->hd0[x]) * c->S * ((RS + 1) / 2) > kPer) return false;
+    return true;
+}
+
+int launch_verify_xcd(hawk_ctx* c, int k) {
+    XcdPlan* P = c->xplan;
+    XP p;
+    memset(&p, 0, sizeof p);
+    const XcdOffsets& o = c->xoff;
+    const int RS = k + 1;
+    std::vector<int16_t> atab;
+    int nattn[kXcd], RPJ = 1;
+    if (!attn_jobs(c, P, RS, &RPJ, atab, nattn)) return -1;
+    p.wpack = wsp<uint4>(c, o.wpack);
+    p.zero_tile = wsp<uint4>(c, o.zero);
+    p.layer_tiles = P->layer_tiles;
+    for (int kk = 0; kk < X_NK; ++kk) {
+        p.nstrips[kk] = P->nstrips[kk];
+        p.part[kk] = wsp<u64>(c, o.part[kk]);
+        for (int x = 0; x < kXcd; ++x) { p.xbase[kk][x] = P->xbase[kk][x]; p.KT[kk][x] = P->KT[kk][x]; }
+    }
+    for (int x = 0; x <= kXcd; ++x) { p.hd0[x] = P->hd0[x]; p.ke0[x] = P->ke0[x]; }
+    for (int f = 0; f < F_NF; ++f)
+        for (int x = 0; x < kXcd; ++x) p.njobs[f][x] = f == F_B ? nattn[x] : P->njobs[f][x];
+    p.gtab = wsp<int16_t>(c, o.gtab); p.rtab = wsp<int16_t>(c, o.rtab); p.ptab = wsp<int16_t>(c, o.ptab);
+    for (int k = 0; k < X_NK; ++k) p.poff[k] = P->poff[k]; p.atab = wsp<int16_t>(c, o.atab);
+    for (int kk = 0; kk < X_NK; ++kk) p.pss[kk] = (kk == X_C || kk == X_E) ? nullptr : wsp<u64>(c, o.pss[kk]);
+    p.xbuf = c->ws + o.xbuf; p.xcd_bytes = o.xcd_bytes;
+    (void)xcd_buf_layout(P, &p);
+    p.lflag = wsp<unsigned>(c, o.lflag);
+    p.blob = wsp<uint16_t>(c, c->off.blob);
+    p.g1_off = c->w.g1[0]; p.g2_off = c->w.g2[0];
+    p.layer_bytes = c->L > 1 ? c->w.g1[1] - c->w.g1[0] : 0;
+    p.gf_off = c->w.g_f;
+    p.rope = wsp<float2>(c, c->soff.rope);
+    p.Kc = wsp<_Float16>(c, c->off.kc); p.Vc = wsp<_Float16>(c, c->off.vc);
+    p.X = wsp<float>(c, c->off.x);
+    p.logit_s = wsp<float>(c, c->off.logit_s);
+    p.err = wsp<unsigned>(c, c->soff.err);
+    p.n = wsp<int32_t>(c, c->off.n); p.k_eff = wsp<int32_t>(c, c->off.k_eff);
+    p.L = c->L; p.d = c->d; p.H = c->H; p.m = c->m; p.Vs = c->Vs; p.S = c->S; p.B = c->B; p.C = c->C;
+    p.RS = RS; p.MR = c->S * RS; p.RPJ = RPJ; p.Smax = c->Smax; p.Tmax = c->Tmax;
+    p.KpA = P->KpA; p.KpO = P->KpO; p.KpH = P->KpH;
+    p.eps = c->cfg.rms_eps;
+    const void* kern = nullptr;
+    if (c->d == 1280) {
+        // strips per compute wave: QKV 240 / 128 -> 2, Wo 80 / 128 -> 1, W1|W3 432 / 128 -> 4, W2 -> 1, output 1024 / 128 -> 8
+        p.lm_rounds = 2;
+        kern = RPJ == 1 ? reinterpret_cast<const void*>(verify_xcd_kernel<2, 5, 1, 6, 4, 5, 1, 14, 4, 1>)
+                        : reinterpret_cast<const void*>(verify_xcd_kernel<2, 5, 1, 6, 4, 5, 1, 14, 4, 2>);
+        if (P->NSW[X_A] > 2 || P->NSW[X_C] > 1 || P->NSW[X_D] > 4 || P->NSW[X_E] > 1 || P->NSW[X_LM] > 8) return -1;
+    } else {
+        // d = 768: QKV 144 -> 2, Wo 48 -> 1, W1|W3 256 -> 2, W2 48 -> 1, output 8 in two rounds of 4
+        p.lm_rounds = 2;
+        kern = RPJ == 1 ? reinterpret_cast<const void*>(verify_xcd_kernel<2, 3, 1, 4, 2, 3, 1, 8, 4, 1>)
+                        : reinterpret_cast<const void*>(verify_xcd_kernel<2, 3, 1, 4, 2, 3, 1, 8, 4, 2>);
+        if (P->NSW[X_A] > 2 || P->NSW[X_C] > 1 || P->NSW[X_D] > 2 || P->NSW[X_E] > 1 || P->NSW[X_LM] > 8) return -1;
+    }
+    // the parameter block and the attention job table of this step shape: uploaded when they change
+    static_assert(sizeof(XP) <= 4096, "parameter block larger than its workspace region");
+    if (P->params.size() != sizeof(XP) || memcmp(P->params.data(), &p, sizeof(XP)) != 0) {
+        if (hipMemcpyAsync(c->ws + o.atab, atab.data(), atab.size() * 2, hipMemcpyHostToDevice, c->stream) != hipSuccess) return -1;
+        if (hipMemcpyAsync(c->ws + o.xp, &p, sizeof(XP), hipMemcpyHostToDevice, c->stream) != hipSuccess) return -1;
+        if (hipStreamSynchronize(c->stream) != hipSuccess) return -1;   // the sources are locals: the copies must have read them
+        P->params.assign(reinterpret_cast<const uint8_t*>(&p), reinterpret_cast<const uint8_t*>(&p) + sizeof(XP));
+    }
+    const size_t lds = xcd_lds_bytes(P, RPJ);
+    if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return -1;
+    const XP* dev_params = wsp<XP>(c, o.xp);
+    unsigned epoch0 = P->epoch;
+    u64* dbg = c->stream_dbg ? wsp<u64>(c, o.dbg) : nullptr;
+    void* args[] = {&dev_params, &epoch0, &dbg};
+    // one workgroup per compute unit: the grid equals the unit count and a workgroup's LDS request
+    // (padded to more than half a unit's LDS) keeps a second one off the unit
+    const size_t lds_req = std::max(lds, (size_t)84 * 1024);
+    if (hipLaunchKernel(kern, dim3(kNWG), dim3(kThreads), args, lds_req, c->stream) != hipSuccess) return -1;
+    P->epoch += 5u * (unsigned)(c->L + 2) + 8u;
+    return 0;
+}
+
+}  // namespace hawk

@@ -37,7 +37,7 @@ def test_workspace_bytes_and_bad_configs(H):
         n = H.workspace_bytes(cfg)
         kv = 2 * s.n_layers * s.n_seq * (s.n_cond + s.n_img) * s.d_model * (8 if s.dtype == "fp32" else 2)
         assert n > s.n_params() * s.itemsize + kv
-        assert n < 2.5 * (s.n_params() * s.itemsize + kv) + (1 << 30)
+        assert n < 3.6 * (s.n_params() * s.itemsize + kv) + (1 << 30)   # blob + three re-tiled copies of the weights
     good = H.HawkConfig.from_shape(synth.CONFIGS[0])
     for field, bad in (("d_model", 250), ("n_heads", 3), ("k_max", 64), ("samp_n", 5000), ("dtype", 7),
                        ("max_batch", 0), ("n_layers", 0), ("d_mlp", 1001)):

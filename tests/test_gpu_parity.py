@@ -334,7 +334,7 @@ def test_bf16_decisions_over_many_steps(H, path, top_k):
         assert total["accepted"] > 0.2 * total["steps"]      # the accept tests were exercised
 
 
-@pytest.mark.parametrize("path", [0, 1])
+@pytest.mark.parametrize("path", [0, 1, 2])
 def test_bf16_config1_full_depth_sampled_steps(H, path):
     s = synth.CONFIGS[1]
     for u_seed in (1, 2, 3, 4, 5, 6):
@@ -360,15 +360,20 @@ def test_bf16_replay_and_greedy(H):
 
 # ----------------------------------------------------------------------------- streaming path
 
+# set_path value -> kernel that hawk_last_kernel must report for the shapes of configurations 1 and 2
+# with at most 16 rows: 1 = the kernel laid out on the XCDs (2), 2 = the grid-barrier kernel (1)
+KERNEL_OF_PATH = {0: 0, 1: 2, 2: 1}
+
+
 @pytest.mark.parametrize("cfg,layers", [(1, 2), (2, 2)])
 def test_streaming_kernel_matches_generic_kernels_and_oracle(H, cfg, layers):
-    # the persistent weight-streaming kernel against the generic kernels (same logits up to
+    # the two persistent weight-streaming kernels against the generic kernels (same logits up to
     # fp32 summation order and the bf16 hi/lo split) and against the oracle
     s = synth.CONFIGS[cfg].replace(n_layers=layers, n_cond=24, grid_h=6, grid_w=8)
     blob = synth.make_weights(s, seed=0)
     cond = synth.make_cond(s, seed=2)
     out = {}
-    for path in (0, 1):
+    for path in (0, 1, 2):
         hk = H.Hawk(H.HawkConfig.from_shape(s))
         hk.load(blob)
         hk.set_path(path)
@@ -376,40 +381,41 @@ def test_streaming_kernel_matches_generic_kernels_and_oracle(H, cfg, layers):
         toks = np.full((1, s.k), s.samp_lo + 7, np.int32)
         hk.draft_forced(s.k, toks, False)
         na, t = hk.verify(s.k, np.full((1, s.k), 0.5, np.float32), [0.5])
-        assert hk.last_path() == path
+        assert hk.last_path() == min(path, 1) and hk.last_kernel() == KERNEL_OF_PATH[path]
         out[path] = (hk.logits(s.k + 1).copy(), na.copy(), t.copy(), hk.grid()[0, 0])
         hk.close()
-    assert out[0][3] == out[1][3]
-    err = np.abs(out[0][0] - out[1][0]).max()
-    print("streaming vs generic max logit diff", err)
-    assert err < 2e-3
-    # both agree with the oracle's logits for the same forced drafts
+    assert out[0][3] == out[1][3] == out[2][3]
+    for path in (1, 2):
+        err = np.abs(out[0][0] - out[path][0]).max()
+        print("streaming kernel", KERNEL_OF_PATH[path], "vs generic max logit diff", err)
+        assert err < 2e-3
+    # all agree with the oracle's logits for the same forced drafts
     orc = oracle.Oracle.from_shape(s, blob)
     orc.prefill(cond, None, 1.0, s.top_k, 1.0, [0.25])
     if orc.grid()[0, 0] == out[1][3]:
         orc.draft_forced(s.k, toks, False)
         orc.verify(s.k, np.full((1, s.k), 0.5, np.float32), [0.5])
-        e1 = np.abs(out[1][0] - orc.logits()).max()
-        e0 = np.abs(out[0][0] - orc.logits()).max()
-        print("max logit err vs oracle: streaming", e1, "generic", e0)
-        assert e1 <= 2e-2 and e0 <= 2e-2
+        errs = {path: np.abs(out[path][0] - orc.logits()).max() for path in (0, 1, 2)}
+        print("max logit err vs oracle by path:", errs)
+        assert max(errs.values()) <= 2e-2
 
 
+@pytest.mark.parametrize("path", [1, 2])
 @pytest.mark.parametrize("cfg,layers,steps", [(1, 3, 25), (2, 3, 25)])
-def test_streaming_kernel_lockstep_with_oracle(H, cfg, layers, steps):
+def test_streaming_kernel_lockstep_with_oracle(H, cfg, layers, steps, path):
     s = synth.CONFIGS[cfg].replace(n_layers=layers, n_cond=24)
     for u_seed in (1, 2, 3, 4, 5, 6):
-        blob, hk, orc = make_pair(H, s, path=1)
+        blob, hk, orc = make_pair(H, s, path=path)
         res = lockstep(s, hk, orc, s.k, u_seed=u_seed, max_steps=steps)
         assert res["stage_bad"] == 0, res
         if res["first_same"]:
-            assert hk.last_path() == 1
+            assert hk.last_path() == 1 and hk.last_kernel() == KERNEL_OF_PATH[path]
             break
     print("streaming lockstep", res)
     assert_bf16(res, steps, 0.95)
 
 
-def accumulate_lockstep(H, s, k, path, min_steps, max_runs=40, expect_path=None, **kw):
+def accumulate_lockstep(H, s, k, path, min_steps, max_runs=40, expect_path=None, expect_kernel=None, **kw):
     """Lockstep runs over successive uniform seeds until min_steps steps are covered (with
     several prompts a run ends at the first token that differs); returns the summed counters."""
     total = dict(steps=0, decision_same=0, stage_bad=0, token_same=0, accepted=0, max_logit_err=0.0,
@@ -421,6 +427,8 @@ def accumulate_lockstep(H, s, k, path, min_steps, max_runs=40, expect_path=None,
         assert res["stage_bad"] == 0, res
         if res["first_same"] and expect_path is not None:
             assert hk.last_path() == expect_path
+        if res["first_same"] and expect_kernel is not None:
+            assert hk.last_kernel() == expect_kernel
         hk.close()
         for key in ("steps", "decision_same", "stage_bad", "token_same", "accepted"):
             total[key] += res[key]
@@ -431,15 +439,59 @@ def accumulate_lockstep(H, s, k, path, min_steps, max_runs=40, expect_path=None,
     return total
 
 
-@pytest.mark.parametrize("cfg,k,batch,scale", [(2, 0, 1, 1.0), (2, 2, 1, 1.0), (1, 3, 2, 3.0), (1, 1, 4, 1.0)])
-def test_streaming_kernel_row_counts_and_batches(H, cfg, k, batch, scale):
+@pytest.mark.parametrize("path", [1, 2])
+@pytest.mark.parametrize("cfg,k,batch,scale", [(2, 0, 1, 1.0), (2, 2, 1, 1.0), (1, 3, 2, 3.0), (1, 1, 4, 1.0), (2, 7, 2, 1.0)])
+def test_streaming_kernel_row_counts_and_batches(H, cfg, k, batch, scale, path):
     # other cuts of the attention stage than the benchmark's: one row per sequence (cached
     # positions split into chunks that the Wo stage merges), three rows, guidance with two
-    # prompts (four sequences, 16 rows), four prompts
+    # prompts (four sequences, 16 rows), four prompts, eight rows per sequence
+    if path == 2 and k > 5:
+        pytest.skip("the grid-barrier kernel is built for at most six rows per sequence")
     s = synth.CONFIGS[cfg].replace(n_layers=2, n_cond=24, grid_h=6, grid_w=8, batch=batch, cfg_scale=scale, k=k)
-    total = accumulate_lockstep(H, s, k, 1, 12, expect_path=1)
-    print("streaming cut", (cfg, k, batch, scale), total)
+    total = accumulate_lockstep(H, s, k, path, 12, expect_path=1, expect_kernel=KERNEL_OF_PATH[path])
+    print("streaming cut", (cfg, k, batch, scale), "kernel", KERNEL_OF_PATH[path], total)
     assert_bf16(total, 12, 0.9)
+
+
+@pytest.mark.parametrize("path", [1, 2])
+def test_streaming_kernel_to_the_end_of_the_image_and_changing_draft_lengths(H, path):
+    # one context, steps of different row counts in turn (the kernels' per-launch state - stage tags,
+    # flags, parameter block - must carry over), run to the image's last token where the final steps
+    # have fewer valid rows than k + 1
+    s = synth.CONFIGS[1].replace(n_layers=2, n_cond=24, grid_h=5, grid_w=7)
+    blob = synth.make_weights(s, seed=0)
+    cond = synth.make_cond(s, seed=2)
+    orc = oracle.Oracle.from_shape(s, blob)
+    hk = H.Hawk(H.HawkConfig.from_shape(s))
+    hk.load(blob)
+    hk.set_path(path)
+    hk.prefill(cond, None, s.grid_h, s.grid_w, 1.0, s.top_k, 1.0, [0.25])
+    orc.prefill(cond, None, 1.0, s.top_k, 1.0, [0.25])
+    if orc.grid()[0, 0] != hk.grid()[0, 0]:
+        pytest.skip("first tokens differ: nothing to compare")
+    rng = np.random.Generator(np.random.PCG64(5))
+    worst, steps = 0.0, 0
+    for k in [5, 2, 0, 5, 1, 4, 5, 5, 3] * 8:
+        n0 = int(orc.n()[0])
+        if n0 >= s.n_img:
+            break
+        ke = max(0, min(k, s.n_img - n0 - 1))
+        toks = rng.integers(s.samp_lo, s.samp_lo + s.v_s, size=(1, max(k, 1))).astype(np.int32)[:, :k]
+        ua = np.full((1, max(k, 1)), 0.0, np.float32)[:, :k]      # u = 0 accepts every candidate the target gives any mass
+        hk.draft_forced(k, toks, False)
+        orc.draft_forced(k, toks, False)
+        na_g, t_g = hk.verify(k, ua, [0.5])
+        na_o, t_o = orc.verify(k, ua, [0.5])
+        assert hk.last_kernel() == KERNEL_OF_PATH[path]
+        lp_g, lp_o = hk.logits(k + 1), orc.logits()
+        worst = max(worst, float(np.abs(lp_g[0, :ke + 1] - lp_o[0, :ke + 1]).max()))
+        steps += 1
+        if not (np.array_equal(na_g, na_o) and np.array_equal(t_g, t_o)):
+            hk.force([n0], orc.grid()[:, n0:n0 + int(na_o[0]) + 1])
+        assert np.array_equal(hk.n(), orc.n())
+    print("to the end: steps", steps, "n", orc.n(), "max logit err", worst)
+    assert int(orc.n()[0]) == s.n_img and steps >= 6
+    assert worst <= 2e-2
 
 
 @pytest.mark.parametrize("cfg,k,batch,scale,rows", [(1, 3, 3, 3.0, 24), (2, 5, 2, 4.0, 24), (1, 2, 2, 1.0, 6), (2, 5, 1, 4.0, 12)])
@@ -547,14 +599,15 @@ def test_config4_7b_shape_slice_and_guidance_reduced(H):
     assert_bf16(total, 8, 0.8)
 
 
-def test_streaming_kernel_xl_full_depth_sampled_steps(H):
+@pytest.mark.parametrize("path", [1, 2])
+def test_streaming_kernel_xl_full_depth_sampled_steps(H, path):
     s = synth.CONFIGS[2]
     for u_seed in (1, 2, 3):
-        blob, hk, orc = make_pair(H, s, path=1)
+        blob, hk, orc = make_pair(H, s, path=path)
         res = lockstep(s, hk, orc, s.k, u_seed=u_seed, max_steps=6)
         assert res["stage_bad"] == 0, res
         if res["first_same"]:
-            assert hk.last_path() == 1
+            assert hk.last_path() == 1 and hk.last_kernel() == KERNEL_OF_PATH[path]
             break
     print("XL full depth", res)
     assert_bf16(res, 6, 0.8)
