@@ -54,6 +54,7 @@ constexpr int kXcd = 8, kPer = kNWG / kXcd;      // workgroup i runs on XCD i % 
 constexpr unsigned kSpinLimit = 1u << 20;
 constexpr int kPS = 68;                          // floats per attention partial row: 64 outputs, max, sum, pad
 constexpr int kNIT = 4;                          // cache positions per lane group and register buffer
+constexpr int kPaceGap = 0, kPaceTiles = 4;   // weight requests go out four tiles per wave at a time (see issue_paced)
 constexpr int kRing = 2;                         // partial-sum areas and XCD buffers alternate between layers
 constexpr int kMaxJobs = 64;                     // reduce / attention jobs of one XCD and stage that others wait for
 
@@ -259,27 +260,42 @@ __device__ __forceinline__ GJob load_gjob(const XP& p, int kind, const Ctx& c, i
 // packed stream.  Straight-line code: absent strips / k-tiles read one shared tile of zeros (a cache
 // hit), so that the number of requests is fixed and the wait before the products can be for exactly
 // this stage's tiles - not for the tiles of later stages requested behind them.
-template <int NSW, int KTM>
+template <int NSW, int KTM, int T0 = 0, int T1 = NSW * KTM>
 __device__ __forceinline__ void issue_tiles(const XP& p, const GJob& g, u64 layer_base, int lane, v4u (&w)[NSW * KTM],
                                             int round = 0) {
     const int ns = min(max(g.ns - round * NSW, 0), NSW), KT = g.KT;
     const v4u* src = reinterpret_cast<const v4u*>(p.wpack + (layer_base + g.tile0 + (u64)round * NSW * KT) * 64 + lane);
     const v4u* zero = reinterpret_cast<const v4u*>(p.zero_tile) + lane;
 #pragma unroll
-    for (int si = 0; si < NSW; ++si)
-#pragma unroll
-        for (int kt = 0; kt < KTM; ++kt) {
-            const bool on = si < ns && kt < KT;
-            w[si * KTM + kt] = __builtin_nontemporal_load(on ? src + (size_t)(si * KT + kt) * 64 : zero);
+    for (int t = T0; t < T1; ++t) {   // (a sub-range of the wave's tiles: a request can be spread over several stages)
+        const int si = t / KTM, kt = t % KTM;
+        const bool on = si < ns && kt < KT;
+        w[t] = __builtin_nontemporal_load(on ? src + (size_t)(si * KT + kt) * 64 : zero);
+    }
+}
+// The same in parts of at most CH tiles, each waited for before the next is requested: what another wave
+// of the unit asks for in between waits for one part, not for the whole request.
+template <int NSW, int KTM, int T0, int T1, int CH>
+__device__ __forceinline__ void issue_paced(const XP& p, const GJob& g, u64 layer_base, int lane, v4u (&w)[NSW * KTM]) {
+    if constexpr (T0 < T1) {
+        constexpr int TE = T0 + CH < T1 ? T0 + CH : T1;
+        issue_tiles<NSW, KTM, T0, TE>(p, g, layer_base, lane, w);
+        if (kPaceGap >= 0) {
+            __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
+            if (kPaceGap > 0) __builtin_amdgcn_s_sleep(kPaceGap);
         }
+        issue_paced<NSW, KTM, TE, T1, CH>(p, g, layer_base, lane, w);
+    }
 }
 
 // The wave's products of a stage from the staged K-slice (LDS planes [16][Kp]) and the partial sums
 // out as tagged words: part[ring][XCD][strip][row][quad][4].  No branches up to the stores (see above).
-template <int NSW, int KTM>
+constexpr int kPrefetchAt = 3;
+struct NoPrefetch { __device__ void operator()() const {} };
+template <int NSW, int KTM, class Prefetch = NoPrefetch>
 __device__ __forceinline__ void mfma_store(const XP& p, int kind, const GJob& g, const Ctx& c, int lane, const v4u (&w)[NSW * KTM],
                                            const uint16_t* act_hi, const uint16_t* act_lo, const float* ssrow, int Kp, int ring,
-                                           unsigned tag, int round = 0, unsigned dbg_stage = 0) {
+                                           unsigned tag, int round = 0, unsigned dbg_stage = 0, Prefetch&& prefetch = Prefetch()) {
     const int s0 = g.s0 + round * NSW, ns = min(max(g.ns - round * NSW, 0), NSW);
     const int col = lane & 15, kg = lane >> 4;
     const size_t at = (size_t)(col < p.MR ? col : 0) * Kp + kg * 8;
@@ -304,6 +320,13 @@ __device__ __forceinline__ void mfma_store(const XP& p, int kind, const GJob& g,
 #pragma unroll
         for (int si = 0; si < NSW; ++si) asm volatile("" :: "v"(acc[si]), "v"(acl[si]));
         stamp(c, dbg_stage, 3);
+    }
+    if (kPrefetchAt == 1) {
+#pragma unroll
+        for (int si = 0; si < NSW; ++si) asm volatile("" : "+v"(acc[si]), "+v"(acl[si]));
+        __builtin_amdgcn_sched_barrier(0);
+        prefetch();
+        __builtin_amdgcn_sched_barrier(0);
     }
     // One 128-byte line per (strip, row): the first 64 bytes hold the {value, tag} pairs of features 4q, 4q + 1
     // (q = lane / 16), the second 64 those of features 4q + 2, 4q + 3.  Every 8-byte pair is written whole,
@@ -363,7 +386,7 @@ __device__ __forceinline__ void stage_copy(rsrc_t r, unsigned src, int MR, int K
 // product follows a norm; the XCDs' shares of every row's sum of squares came with their partial sums,
 // and *rn receives 1/rms of the lane's row.
 __device__ __forceinline__ f32x4 gather_partials(const XP& p, Ctx& c, int kind, int s, int prod, int ring, unsigned tag, int lane,
-                                                 bool scaled, float* rn) {
+                                                 bool scaled, float* rn, unsigned dbg_stage = 1000u) {
     const int col = lane & 15, quad = lane >> 4;
     const bool live = col < p.MR;
     f32x4 val[kXcd];
@@ -385,7 +408,9 @@ __device__ __forceinline__ f32x4 gather_partials(const XP& p, Ctx& c, int kind, 
     unsigned need_ss = (live && scaled) ? 3u : 0u;
     float ssv[2] = {0.f, 0.f};
     bool ok = c.dead;
+    unsigned nspin = 0;
     for (unsigned spins = 0; spins < kSpinLimit && !ok; ++spins) {
+        ++nspin;
         v4u w[kXcd][2];
         u64 sw[2] = {0ull, 0ull};
 #pragma unroll
@@ -416,6 +441,8 @@ __device__ __forceinline__ f32x4 gather_partials(const XP& p, Ctx& c, int kind, 
         if (!ok && (spins & 255u) == 255u && ld_u32(c.err) != 0u) break;
     }
     if (!ok) give_up(c);
+    if (c.dbg && (threadIdx.x & 63) == 0 && (blockIdx.x == 0 || blockIdx.x == 248) && dbg_stage < 512u)
+        c.dbg[((size_t)(blockIdx.x ? 1 : 0) * 512 + dbg_stage) * 16 + 14] = nspin;
     if (scaled) {
         float a = ssv[0] + ssv[1];
         a = sum_xor16(a);
@@ -505,7 +532,7 @@ __device__ __forceinline__ void reduce_job(const XP& p, Ctx& c, const IoJobs& jb
         gain = *reinterpret_cast<const uint2*>(g + s * 16 + 4 * quad);
     }
     float rn = 1.f;
-    f32x4 v = gather_partials(p, c, kind, s, scaled ? p.ptab[p.poff[kind] + s] : 0, ring, tag, lane, scaled, &rn);
+    f32x4 v = gather_partials(p, c, kind, s, scaled ? p.ptab[p.poff[kind] + s] : 0, ring, tag, lane, scaled, &rn, stage);
     stamp(c, stage, 4);
     v *= rn;
     stamp(c, stage, 5);
@@ -828,9 +855,9 @@ __device__ __forceinline__ unsigned product_tag(const XP& p, const Ctx& c, int k
 
 // Compute waves.  KIND: which matrix; NSW: strips per wave and round; KTM: most k-tiles an XCD's slice
 // has.  w holds this stage's tiles, requested one or two stages ago.
-template <int KIND, int NSW, int KTM>
+template <int KIND, int NSW, int KTM, class Prefetch>
 __device__ __forceinline__ void compute_stage(const XP& p, const Ctx& c, const GJob& g, const Lds& s, int layer, unsigned stage,
-                                              int Kp, v4u (&w)[NSW * KTM]) {
+                                              int Kp, v4u (&w)[NSW * KTM], Prefetch&& prefetch) {
     const int lane = threadIdx.x & 63;
     const uint16_t* act_hi = s.act0 + (size_t)(stage & 1u) * s.act_elems;
     const uint16_t* act_lo = act_hi + (size_t)16 * Kp;
@@ -839,14 +866,23 @@ __device__ __forceinline__ void compute_stage(const XP& p, const Ctx& c, const G
     stamp(c, stage, 0);
     lds_barrier();   // the XCD's slice of the stage input is in LDS
     stamp(c, stage, 1);
+    // A compute unit answers its waves' memory requests in the order they were made: whatever the IO
+    // waves ask for after a batch of weight tiles waits until that batch has come in (with every unit
+    // asking at once, ~0.15 us per KB and wave).  The one stretch of a stage in which the IO waves need
+    // nothing urgently is its beginning - the partial sums they will poll for are ~2 us away - so this
+    // is where the stage's share of the weight stream (about a fifth of a layer) is requested.
+    if (kPrefetchAt == 0) prefetch();
     const float* ssrow = (KIND == X_C || KIND == X_E) ? nullptr : s.ss0 + (stage & 1u) * 16;
-    mfma_store<NSW, KTM>(p, KIND, g, c, lane, w, act_hi, act_lo, ssrow, Kp, ring, tag, 0, stage);
+    mfma_store<NSW, KTM>(p, KIND, g, c, lane, w, act_hi, act_lo, ssrow, Kp, ring, tag, 0, stage, prefetch);
     stamp(c, stage, 2);
+    if (kPrefetchAt == 2) prefetch();
     // Loads and stores share one counter and complete out of order among each other: with stores
     // pending, "wait for the first n loads" is not expressible and every wait becomes "wait for
-    // everything".  So the stores are acknowledged before any further tile is requested.
+    // everything".  So everything is waited for here, tiles just requested included: they are in long
+    // before the next stage's input is, and the waits before the products become trivial.
     __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
     stamp(c, stage, 4);
+    if (kPrefetchAt == 3) prefetch();
     if (KIND == X_LM) {   // further rounds of the output projection: same staged input
         for (int r = 1; r < p.lm_rounds; ++r) {
             issue_tiles<NSW, KTM>(p, g, 0, lane, w, r);
@@ -902,23 +938,33 @@ __device__ __forceinline__ void compute_main(const XP& p, const Ctx& c, const Ld
     const GJob gA = load_gjob(p, X_A, c, wave), gC = load_gjob(p, X_C, c, wave), gD = load_gjob(p, X_D, c, wave);
     const GJob gE = load_gjob(p, X_E, c, wave), gL = load_gjob(p, X_LM, c, wave);
     v4u wA[NA * KA], wC[NC * KC], wD[ND * KD], wE[NE * KE];
+    // Requests, one part per stage (see compute_stage): a buffer is refilled at the start of a stage that
+    // does not use it, for its next use - QKV stage: second half of this layer's W1|W3 strips and Wo;
+    // Wo stage: the next layer's QKV; W1|W3 stage: this layer's W2; W2 stage: first half of the next
+    // layer's W1|W3.
+    constexpr int NDh = ((ND + 1) / 2) * KD, CH = kPaceTiles;
     issue_tiles<NA, KA>(p, gA, 0, lane, wA);
+    issue_tiles<ND, KD, 0, NDh>(p, gD, 0, lane, wD);
     unsigned stage = 0;
     for (int l = 0; l < p.L; ++l) {
         const u64 lb = (u64)l * p.layer_tiles;
-        compute_stage<X_A, NA, KA>(p, c, gA, s, l, stage++, p.KpA, wA);
-        issue_tiles<NC, KC>(p, gC, lb, lane, wC);   // both arrive while the attention runs
-        issue_tiles<ND, KD>(p, gD, lb, lane, wD);
+        const bool more = l + 1 < p.L;
+        compute_stage<X_A, NA, KA>(p, c, gA, s, l, stage++, p.KpA, wA, [&] {
+            issue_paced<ND, KD, NDh, ND * KD, CH>(p, gD, lb, lane, wD);
+            issue_paced<NC, KC, 0, NC * KC, CH>(p, gC, lb, lane, wC);
+        });
         ++stage;   // attention: the IO waves' business
-        compute_stage<X_C, NC, KC>(p, c, gC, s, l, stage++, p.KpO, wC);
-        compute_stage<X_D, ND, KD>(p, c, gD, s, l, stage++, p.KpA, wD);
-        issue_tiles<NE, KE>(p, gE, lb, lane, wE);
-        if (l + 1 < p.L) issue_tiles<NA, KA>(p, gA, lb + p.layer_tiles, lane, wA);
-        compute_stage<X_E, NE, KE>(p, c, gE, s, l, stage++, p.KpH, wE);
+        compute_stage<X_C, NC, KC>(p, c, gC, s, l, stage++, p.KpO, wC, [&] {
+            if (more) issue_paced<NA, KA, 0, NA * KA, CH>(p, gA, lb + p.layer_tiles, lane, wA);
+        });
+        compute_stage<X_D, ND, KD>(p, c, gD, s, l, stage++, p.KpA, wD, [&] { issue_paced<NE, KE, 0, NE * KE, CH>(p, gE, lb, lane, wE); });
+        compute_stage<X_E, NE, KE>(p, c, gE, s, l, stage++, p.KpH, wE, [&] {
+            if (more) issue_paced<ND, KD, 0, NDh, CH>(p, gD, lb + p.layer_tiles, lane, wD);
+        });
     }
     v4u wL[NL * KA];
     issue_tiles<NL, KA>(p, gL, 0, lane, wL);
-    compute_stage<X_LM, NL, KA>(p, c, gL, s, p.L, stage++, p.KpA, wL);
+    compute_stage<X_LM, NL, KA>(p, c, gL, s, p.L, stage++, p.KpA, wL, [] {});
 }
 
 template <int RPJ>
