@@ -290,49 +290,23 @@ __device__ __forceinline__ void issue_paced(const XP& p, const GJob& g, u64 laye
 
 // The wave's products of a stage from the staged K-slice (LDS planes [16][Kp]) and the partial sums
 // out as tagged words: part[ring][XCD][strip][row][quad][4].  No branches up to the stores (see above).
-constexpr int kPrefetchAt = 3;
-struct NoPrefetch { __device__ void operator()() const {} };
-template <int NSW, int KTM, class Prefetch = NoPrefetch>
+template <int NSW, int KTM>
 __device__ __forceinline__ void mfma_store(const XP& p, int kind, const GJob& g, const Ctx& c, int lane, const v4u (&w)[NSW * KTM],
                                            const uint16_t* act_hi, const uint16_t* act_lo, const float* ssrow, int Kp, int ring,
-                                           unsigned tag, int round = 0, unsigned dbg_stage = 0, Prefetch&& prefetch = Prefetch()) {
+                                           unsigned tag, int round = 0, unsigned dbg_stage = 0) {
     const int s0 = g.s0 + round * NSW, ns = min(max(g.ns - round * NSW, 0), NSW);
     const int col = lane & 15, kg = lane >> 4;
     const size_t at = (size_t)(col < p.MR ? col : 0) * Kp + kg * 8;
-    f32x4 acc[NSW], acl[NSW];
-#pragma unroll
-    for (int si = 0; si < NSW; ++si) {
-        acc[si] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        acl[si] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    }
-#pragma unroll
-    for (int kt = 0; kt < KTM; ++kt) {   // k-tiles beyond the XCD's slice: zero weights (their LDS columns are in bounds)
-        const bf16x8 h = __builtin_bit_cast(bf16x8, *reinterpret_cast<const v4u*>(act_hi + at + kt * 32));
-        const bf16x8 l = __builtin_bit_cast(bf16x8, *reinterpret_cast<const v4u*>(act_lo + at + kt * 32));
-#pragma unroll
-        for (int si = 0; si < NSW; ++si) {
-            const bf16x8 a = __builtin_bit_cast(bf16x8, w[si * KTM + kt]);
-            acc[si] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, h, acc[si], 0, 0, 0);
-            acl[si] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, l, acl[si], 0, 0, 0);
-        }
-    }
-    if (c.dbg) {   // when tracing: the products are done (the stamp follows them in program order only through this)
-#pragma unroll
-        for (int si = 0; si < NSW; ++si) asm volatile("" :: "v"(acc[si]), "v"(acl[si]));
-        stamp(c, dbg_stage, 3);
-    }
-    if (kPrefetchAt == 1) {
-#pragma unroll
-        for (int si = 0; si < NSW; ++si) asm volatile("" : "+v"(acc[si]), "+v"(acl[si]));
-        __builtin_amdgcn_sched_barrier(0);
-        prefetch();
-        __builtin_amdgcn_sched_barrier(0);
-    }
+    if (ssrow && kg == 0 && col < p.MR && ns > 0)   // the product follows a norm: this XCD's share of the row's sum of squares
+                                                    // rides along, once per wave and round (known before the products: it goes first)
+        st_tagged(p.pss[kind] + ((((size_t)ring * kXcd + c.x) * kPer + c.j) * kCW + (threadIdx.x >> 6)) * 32 + (round & 1) * 16 + col,
+                  ssrow[col], tag);
     // One 128-byte line per (strip, row): the first 64 bytes hold the {value, tag} pairs of features 4q, 4q + 1
     // (q = lane / 16), the second 64 those of features 4q + 2, 4q + 3.  Every 8-byte pair is written whole,
     // so a reader never sees a value without its tag.  With at most 8 rows the idle lanes of columns 8..15
     // carry the second halves of columns 0..7 (one cross-lane move) and one store instruction per strip
-    // writes whole lines; write-through stores cost the wave ~0.15 us per instruction.
+    // writes whole lines.  A write-through store occupies the wave for ~0.3 us, several times the products
+    // of a strip: strip by strip, so that a strip's store goes out while the next one is multiplied.
     const rsrc_t out = make_rsrc(p.part[kind]);
     const bool packed = p.MR <= 8;
     const int row = packed ? (col & 7) : col;
@@ -340,7 +314,20 @@ __device__ __forceinline__ void mfma_store(const XP& p, int kind, const GJob& g,
     const unsigned at8 = (unsigned)((((size_t)ring * kXcd + c.x) * p.nstrips[kind] + s0) * 16 + row) * 128u + kg * 16u + (second ? 64u : 0u);
 #pragma unroll
     for (int si = 0; si < NSW; ++si) {
-        const f32x4 v = acc[si] + acl[si];
+        f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f}, acl = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kt = 0; kt < KTM; ++kt) {   // k-tiles beyond the XCD's slice: zero weights (their LDS columns are in bounds)
+            const bf16x8 h = __builtin_bit_cast(bf16x8, *reinterpret_cast<const v4u*>(act_hi + at + kt * 32));
+            const bf16x8 l = __builtin_bit_cast(bf16x8, *reinterpret_cast<const v4u*>(act_lo + at + kt * 32));
+            const bf16x8 a = __builtin_bit_cast(bf16x8, w[si * KTM + kt]);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, h, acc, 0, 0, 0);
+            acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, l, acl, 0, 0, 0);
+        }
+        if (c.dbg && si == NSW - 1) {   // when tracing: the products are done (the stamp follows them in program order only through this)
+            asm volatile("" :: "v"(acc), "v"(acl));
+            stamp(c, dbg_stage, 3);
+        }
+        const f32x4 v = acc + acl;
         const float v2 = lane_xor8(v[2]), v3 = lane_xor8(v[3]);   // columns 8..15 receive columns 0..7
         if (si < ns && row < p.MR) {
             if (packed) {
@@ -352,30 +339,26 @@ __device__ __forceinline__ void mfma_store(const XP& p, int kind, const GJob& g,
             }
         }
     }
-    if (ssrow && kg == 0 && col < p.MR && ns > 0)   // the product follows a norm: this XCD's share of the row's sum of squares
-                                                    // rides along, once per wave and round
-        st_tagged(p.pss[kind] + ((((size_t)ring * kXcd + c.x) * kPer + c.j) * kCW + (threadIdx.x >> 6)) * 32 + (round & 1) * 16 + col,
-                  ssrow[col], tag);
 }
 
 // IO waves: copy the XCD's slice of a stage input (split planes [2][16][Kp], the first MR rows of each)
 // from the XCD's buffer (byte offset `src` from the base of `r`) into LDS, which has the same layout:
 // two contiguous runs of MR * Kp elements, up to four 16-byte chunks per thread in flight.
-__device__ __forceinline__ void stage_copy(rsrc_t r, unsigned src, int MR, int Kp, uint16_t* act, int t) {
+__device__ __forceinline__ void stage_copy(rsrc_t r, unsigned src, int MR, int Kp, uint16_t* act, int t, int nthreads) {
     const int per_plane = MR * Kp / 8, total = 2 * per_plane;   // Kp % 8 == 0
     const unsigned plane_bytes = 16u * (unsigned)Kp * 2u;
-    for (int base = 0; base < total; base += 4 * kIOThreads) {
+    for (int base = 0; base < total; base += 4 * nthreads) {
         v4u v[4];
         unsigned at[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int q = base + i * kIOThreads + t;
+            const int q = base + i * nthreads + t;
             at[i] = q >= per_plane ? plane_bytes + (unsigned)(q - per_plane) * 16u : (unsigned)q * 16u;
             v[i] = q < total ? ld_16(r, src + at[i]) : (v4u){0u, 0u, 0u, 0u};
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            if (base + i * kIOThreads + t < total) *reinterpret_cast<v4u*>(reinterpret_cast<char*>(act) + at[i]) = v[i];
+            if (base + i * nthreads + t < total) *reinterpret_cast<v4u*>(reinterpret_cast<char*>(act) + at[i]) = v[i];
     }
 }
 
@@ -866,23 +849,20 @@ __device__ __forceinline__ void compute_stage(const XP& p, const Ctx& c, const G
     stamp(c, stage, 0);
     lds_barrier();   // the XCD's slice of the stage input is in LDS
     stamp(c, stage, 1);
-    // A compute unit answers its waves' memory requests in the order they were made: whatever the IO
-    // waves ask for after a batch of weight tiles waits until that batch has come in (with every unit
-    // asking at once, ~0.15 us per KB and wave).  The one stretch of a stage in which the IO waves need
-    // nothing urgently is its beginning - the partial sums they will poll for are ~2 us away - so this
-    // is where the stage's share of the weight stream (about a fifth of a layer) is requested.
-    if (kPrefetchAt == 0) prefetch();
     const float* ssrow = (KIND == X_C || KIND == X_E) ? nullptr : s.ss0 + (stage & 1u) * 16;
-    mfma_store<NSW, KTM>(p, KIND, g, c, lane, w, act_hi, act_lo, ssrow, Kp, ring, tag, 0, stage, prefetch);
+    mfma_store<NSW, KTM>(p, KIND, g, c, lane, w, act_hi, act_lo, ssrow, Kp, ring, tag, 0, stage);
     stamp(c, stage, 2);
-    if (kPrefetchAt == 2) prefetch();
     // Loads and stores share one counter and complete out of order among each other: with stores
     // pending, "wait for the first n loads" is not expressible and every wait becomes "wait for
-    // everything".  So everything is waited for here, tiles just requested included: they are in long
-    // before the next stage's input is, and the waits before the products become trivial.
+    // everything".  So the stores are acknowledged before any further tile is requested.
     __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
     stamp(c, stage, 4);
-    if (kPrefetchAt == 3) prefetch();
+    // A compute unit answers its waves' memory requests in the order they were made: what the IO waves
+    // ask for behind a batch of weight tiles waits until the batch has come in (with every unit asking
+    // at once, ~0.15 us per KB and wave).  So every stage requests about a fifth of a layer, in small
+    // parts, here - where the unit's IO waves are between their first look at the partial sums and the
+    // look that finds them.
+    prefetch();
     if (KIND == X_LM) {   // further rounds of the output projection: same staged input
         for (int r = 1; r < p.lm_rounds; ++r) {
             issue_tiles<NSW, KTM>(p, g, 0, lane, w, r);
@@ -907,7 +887,9 @@ __device__ __forceinline__ void io_stage(const XP& p, Ctx& c, const IoJobs& jb, 
     stamp(c, stage, 0);
     wait_flags(p, c, wait_flag, nwait, wait_tag);
     stamp(c, stage, 1);
-    if (kind != X_C && kind != X_E && wave == kCW + kNIO - 1 && lane < p.MR) {
+    // a product that follows a norm: the last IO wave adds the sums of squares up while the other three copy
+    const bool normed = kind != X_C && kind != X_E;
+    if (normed && wave == kCW + kNIO - 1 && lane < p.MR) {
         // The product follows a norm: the sums of squares of this XCD's slice of its input, row by row - its
         // owners' strips added in strip order - for the compute waves to send along with their partial sums.
         const int per_xcd = p.d / 16 / kXcd;
@@ -919,8 +901,9 @@ __device__ __forceinline__ void io_stage(const XP& p, Ctx& c, const IoJobs& jb, 
         for (int i = 0; i < 16; ++i) a += v[i];
         s.ss0[(stage & 1u) * 16 + lane] = a;
     }
-    stage_copy(make_rsrc(p.xbuf), (unsigned)(((size_t)c.x * kRing + (layer & 1)) * p.xcd_bytes + region), p.MR, Kp,
-               s.act0 + (size_t)(stage & 1u) * s.act_elems, threadIdx.x - kCW * 64);
+    if (!normed || wave != kCW + kNIO - 1)
+        stage_copy(make_rsrc(p.xbuf), (unsigned)(((size_t)c.x * kRing + (layer & 1)) * p.xcd_bytes + region), p.MR, Kp,
+                   s.act0 + (size_t)(stage & 1u) * s.act_elems, threadIdx.x - kCW * 64, normed ? kIOThreads - 64 : kIOThreads);
     stamp(c, stage, 2);
     lds_barrier();
     if (kind == X_LM) reduce_logits(p, c, wave - kCW, lane);
