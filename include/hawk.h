@@ -43,7 +43,7 @@ enum {
     HAWK_EINVAL = -1,  /* bad argument */
     HAWK_ESTATE = -2,  /* call out of order */
     HAWK_ENOMEM = -3,  /* workspace too small */
-    HAWK_EDEVICE = -4  /* HIP runtime error */
+    HAWK_EDEVICE = -4  /* HIP runtime error, or a wait inside a persistent kernel ran out (the context is dead then) */
 };
 
 enum { HAWK_FP32 = 0, HAWK_BF16 = 1 };
@@ -204,6 +204,19 @@ int hawk_get_draft_logits(hawk_ctx* ctx, float* out, int k);
 int hawk_set_path(hawk_ctx* ctx, int path);
 int hawk_last_path(const hawk_ctx* ctx);
 int hawk_last_kernel(const hawk_ctx* ctx);
+
+/* Error behaviour of the persistent kernels: every wait inside them (grid barriers, polls for partial
+ * sums and flags) is bounded; a wait that runs out sets an error word in the workspace, the kernel
+ * runs to its end without waiting any further, and the next call that returns data to the host
+ * (hawk_draft with out_draft, hawk_verify with outputs, hawk_verify_tree, hawk_force, hawk_generate,
+ * hawk_run_steps, every hawk_get_*) returns HAWK_EDEVICE.  From then on the context is dead: the
+ * kernels' exchange buffers hold a mixture of two steps, so every further call on it returns
+ * HAWK_EDEVICE at once without launching anything; destroy it and create a new one (the workspace
+ * may be reused).
+ *
+ * Test hook: sets that error word from the host, as a timed-out wait would (no kernel is launched;
+ * HAWK_ESTATE if the context's shape has no persistent-kernel plan). */
+int hawk_debug_raise_timeout(hawk_ctx* ctx);
 
 /* Diagnostic: switches per-stage time stamps of the streaming kernel on or off (they cost
  * a few stores per stage) and, if out != NULL, copies the stamps of the last launch to

@@ -318,19 +318,41 @@ int upload(hawk_ctx* c, size_t off, const void* host, size_t bytes) {
     return HAWK_OK;
 }
 
+const char* const kDeadMsg =
+    "a wait inside a persistent kernel timed out: the results of that step are invalid and the context's exchange "
+    "buffers are in an undefined state - destroy the context and create a new one";
+
+// Copies results to the host.  Every result a caller sees passes through here, so this is also where
+// the persistent kernels' error word is read - in the same synchronisation as the data.
 int download(hawk_ctx* c, void* host, size_t off, size_t bytes) {
     if (bytes == 0) return HAWK_OK;
+    unsigned e = 0;
     HIP_TRY(c, hipMemcpyAsync(host, c->ws + off, bytes, hipMemcpyDeviceToHost, c->stream));
+    if (stream_has_err_word(c)) HIP_TRY(c, hipMemcpyAsync(&e, c->ws + c->soff.err, 4, hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (c->launch_failed) return fail(c, HAWK_EDEVICE, "launch of a persistent kernel failed");
+    if (e != 0) {
+        c->dead = 1;
+        return fail(c, HAWK_EDEVICE, "%s", kDeadMsg);
+    }
     return HAWK_OK;
 }
 
-// After a synchronisation: did a streaming kernel fail to launch or give up on a barrier?
+// After a synchronisation: did a persistent kernel fail to launch or give up on a wait?
 int check_stream(hawk_ctx* c) {
-    if (c->launch_failed) return fail(c, HAWK_EDEVICE, "launch of the streaming kernel failed");
-    if (stream_error(c)) return fail(c, HAWK_EDEVICE, "a grid barrier of the streaming kernel timed out");
+    if (c->launch_failed) return fail(c, HAWK_EDEVICE, "launch of a persistent kernel failed");
+    if (stream_error(c)) {
+        c->dead = 1;
+        return fail(c, HAWK_EDEVICE, "%s", kDeadMsg);
+    }
     return HAWK_OK;
 }
+
+// First line of every call that works on a context's state.
+#define HAWK_LIVE(c)                                             \
+    do {                                                         \
+        if ((c)->dead) return fail((c), HAWK_EDEVICE, "%s", kDeadMsg); \
+    } while (0)
 
 bool uniforms_ok(const float* u, size_t n) {
     for (size_t i = 0; i < n; ++i)
@@ -416,6 +438,15 @@ int hawk_set_path(hawk_ctx* c, int path) {
 int hawk_last_path(const hawk_ctx* c) { return c ? c->last_path : -1; }
 
 int hawk_last_kernel(const hawk_ctx* c) { return c ? c->last_kernel : -1; }
+
+int hawk_debug_raise_timeout(hawk_ctx* c) {
+    if (!c) return HAWK_EINVAL;
+    if (!stream_has_err_word(c)) return fail(c, HAWK_ESTATE, "this context has no persistent-kernel plan");
+    const unsigned one = 1;
+    HIP_TRY(c, hipMemcpyAsync(c->ws + c->soff.err, &one, 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return HAWK_OK;
+}
 
 int hawk_phase_trace(hawk_ctx* c, int enable, uint64_t* out, size_t n_words) {
     if (!c) return HAWK_EINVAL;
@@ -504,6 +535,7 @@ int hawk_sample_rows(const float* logits, const int32_t* skip, const float* u, i
 
 int hawk_load(hawk_ctx* c, const void* host_blob, size_t nbytes) {
     if (!c) return HAWK_EINVAL;
+    HAWK_LIVE(c);
     if (!host_blob) return fail(c, HAWK_EINVAL, "null blob");
     if (nbytes != c->blob_bytes)
         return fail(c, HAWK_EINVAL, "blob has %zu bytes, configuration needs %zu", nbytes, c->blob_bytes);
@@ -522,6 +554,7 @@ int hawk_load(hawk_ctx* c, const void* host_blob, size_t nbytes) {
 int hawk_prefill(hawk_ctx* c, const float* cond, const float* uncond, int batch, int n_cond, int grid_h, int grid_w,
                  float temperature, int top_k, float cfg_scale, const float* u_first) {
     if (!c) return HAWK_EINVAL;
+    HAWK_LIVE(c);
     if (c->phase < 1) return fail(c, HAWK_ESTATE, "hawk_prefill before hawk_load");
     if (!cond || !u_first || (c->cfg.use_cfg && !uncond)) return fail(c, HAWK_EINVAL, "null input");
     int rc = check_image_args(c, batch, n_cond, grid_h, grid_w, temperature, top_k, cfg_scale);
@@ -540,6 +573,7 @@ int hawk_prefill(hawk_ctx* c, const float* cond, const float* uncond, int batch,
 
 int hawk_draft(hawk_ctx* c, int k, const float* u_draft, int32_t* out_draft) {
     if (!c) return HAWK_EINVAL;
+    HAWK_LIVE(c);
     if (c->phase != 2 && c->phase != 3) return fail(c, HAWK_ESTATE, "hawk_draft needs a prefilled context");
     if (k < 0 || k > c->kmax || k > c->gw)
         return fail(c, HAWK_EINVAL, "k = %d outside [0, min(k_max = %d, grid_w = %d)]", k, c->kmax, c->gw);
@@ -567,6 +601,7 @@ int hawk_draft(hawk_ctx* c, int k, const float* u_draft, int32_t* out_draft) {
 
 int hawk_draft_forced(hawk_ctx* c, int k, const int32_t* tokens, int point_mass) {
     if (!c) return HAWK_EINVAL;
+    HAWK_LIVE(c);
     if (c->phase != 2 && c->phase != 3) return fail(c, HAWK_ESTATE, "hawk_draft_forced needs a prefilled context");
     if (k < 0 || k > c->kmax || k > c->gw)
         return fail(c, HAWK_EINVAL, "k = %d outside [0, min(k_max = %d, grid_w = %d)]", k, c->kmax, c->gw);
@@ -590,6 +625,7 @@ int hawk_draft_forced(hawk_ctx* c, int k, const int32_t* tokens, int point_mass)
 int hawk_verify(hawk_ctx* c, int k, const float* u_acc, const float* u_final, int32_t* out_n_accept,
                 int32_t* out_tokens) {
     if (!c) return HAWK_EINVAL;
+    HAWK_LIVE(c);
     if (c->phase != 3 || k != c->k_last) return fail(c, HAWK_ESTATE, "hawk_verify(k) must follow hawk_draft(k)");
     if (!u_final || (k > 0 && !u_acc)) return fail(c, HAWK_EINVAL, "null uniforms");
     if (!uniforms_ok(u_final, c->B) || (k > 0 && !uniforms_ok(u_acc, (size_t)c->B * k)))
@@ -633,6 +669,7 @@ int hawk_tree_layout(int depth, const int32_t* m_depth, int32_t* out_parent, int
 int hawk_verify_tree(hawk_ctx* c, int depth, const int32_t* m_depth, const int32_t* cand, const float* q_logits,
                      const float* u_acc, const float* u_final, int32_t* out_n_accept, int32_t* out_tokens) {
     if (!c) return HAWK_EINVAL;
+    HAWK_LIVE(c);
     if (c->phase < 2) return fail(c, HAWK_ESTATE, "hawk_verify_tree before hawk_prefill");
     if (!m_depth || !cand || !q_logits || !u_acc || !u_final) return fail(c, HAWK_EINVAL, "null input");
     if (depth < 1 || depth > kTreeMaxDepth) return fail(c, HAWK_EINVAL, "depth = %d outside [1, %d]", depth, kTreeMaxDepth);
@@ -769,6 +806,7 @@ int hawk_verify_tree(hawk_ctx* c, int depth, const int32_t* m_depth, const int32
 
 int hawk_force(hawk_ctx* c, const int32_t* n_from, const int32_t* tokens, int cnt) {
     if (!c) return HAWK_EINVAL;
+    HAWK_LIVE(c);
     if (c->phase < 2) return fail(c, HAWK_ESTATE, "hawk_force before hawk_prefill");
     if (!n_from || !tokens) return fail(c, HAWK_EINVAL, "null input");
     if (cnt < 1 || cnt > c->kmax + 1) return fail(c, HAWK_EINVAL, "cnt = %d outside [1, k_max + 1]", cnt);
@@ -800,6 +838,7 @@ int hawk_generate(hawk_ctx* c, const float* cond, const float* uncond, int batch
                   int k, float temperature, int top_k, float cfg_scale, uint64_t seed, const int32_t* replay_tokens,
                   int32_t* out_grid, hawk_stats* stats) {
     if (!c) return HAWK_EINVAL;
+    HAWK_LIVE(c);
     if (c->phase < 1) return fail(c, HAWK_ESTATE, "hawk_generate before hawk_load");
     if (!cond || (c->cfg.use_cfg && !uncond)) return fail(c, HAWK_EINVAL, "null input");
     int rc = check_image_args(c, batch, n_cond, grid_h, grid_w, temperature, top_k, cfg_scale);
@@ -866,6 +905,7 @@ int hawk_generate(hawk_ctx* c, const float* cond, const float* uncond, int batch
 
 int hawk_set_replay(hawk_ctx* c, const int32_t* replay_tokens) {
     if (!c) return HAWK_EINVAL;
+    HAWK_LIVE(c);
     if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
     if (!replay_tokens) return fail(c, HAWK_EINVAL, "null tokens");
     for (size_t i = 0; i < (size_t)c->B * c->N; ++i)
@@ -877,6 +917,7 @@ int hawk_set_replay(hawk_ctx* c, const int32_t* replay_tokens) {
 int hawk_run_steps(hawk_ctx* c, int k, int n_steps, uint64_t seed, int replay, float* ms_draft, float* ms_verify,
                    float* ms_kernel) {
     if (!c) return HAWK_EINVAL;
+    HAWK_LIVE(c);
     if (c->phase != 2) return fail(c, HAWK_ESTATE, "hawk_run_steps needs a prefilled context with no draft pending");
     if (k < 0 || k > c->kmax || k > c->gw)
         return fail(c, HAWK_EINVAL, "k = %d outside [0, min(k_max = %d, grid_w = %d)]", k, c->kmax, c->gw);
@@ -938,6 +979,7 @@ int hawk_run_steps(hawk_ctx* c, int k, int n_steps, uint64_t seed, int replay, f
 
 int hawk_get_stats(hawk_ctx* c, hawk_stats* out) {
     if (!c || !out) return HAWK_EINVAL;
+    HAWK_LIVE(c);
     if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
     unsigned long long cnt[4];
     int rc = download(c, cnt, c->off.counters, sizeof cnt);
@@ -952,18 +994,21 @@ int hawk_get_stats(hawk_ctx* c, hawk_stats* out) {
 
 int hawk_get_n(hawk_ctx* c, int32_t* n) {
     if (!c || !n) return HAWK_EINVAL;
+    HAWK_LIVE(c);
     if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
     return download(c, n, c->off.n, (size_t)c->B * 4);
 }
 
 int hawk_get_grid(hawk_ctx* c, int32_t* grid) {
     if (!c || !grid) return HAWK_EINVAL;
+    HAWK_LIVE(c);
     if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
     return download(c, grid, c->off.grid, (size_t)c->B * c->N * 4);
 }
 
 int hawk_get_logits(hawk_ctx* c, float* out, int rows) {
     if (!c || !out) return HAWK_EINVAL;
+    HAWK_LIVE(c);
     if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
     if (rows < 1 || rows > c->kmax + 1) return fail(c, HAWK_EINVAL, "rows outside [1, k_max + 1]");
     for (int b = 0; b < c->B; ++b) {
@@ -976,6 +1021,7 @@ int hawk_get_logits(hawk_ctx* c, float* out, int rows) {
 
 int hawk_get_tree_logits(hawk_ctx* c, float* out, int n_nodes) {
     if (!c || !out) return HAWK_EINVAL;
+    HAWK_LIVE(c);
     if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
     if (n_nodes < 1 || n_nodes > c->kmax + 1) return fail(c, HAWK_EINVAL, "n_nodes outside [1, k_max + 1]");
     if (!c->cfg.use_cfg) return download(c, out, c->off.logit_s, (size_t)c->B * n_nodes * c->Vs * 4);
@@ -992,12 +1038,14 @@ int hawk_get_tree_logits(hawk_ctx* c, float* out, int n_nodes) {
 
 int hawk_get_tree_path(hawk_ctx* c, int32_t* out) {
     if (!c || !out) return HAWK_EINVAL;
+    HAWK_LIVE(c);
     if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
     return download(c, out, c->off.tree + TreeArea(c).path, (size_t)c->B * kTreeMaxDepth * 4);
 }
 
 int hawk_last_hidden(hawk_ctx* c, const void** device_ptr, int* elem_bytes) {
     if (!c || !device_ptr || !elem_bytes) return HAWK_EINVAL;
+    HAWK_LIVE(c);
     if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
     *device_ptr = c->ws + c->off.x;
     *elem_bytes = (int)c->asz;
@@ -1006,6 +1054,7 @@ int hawk_last_hidden(hawk_ctx* c, const void** device_ptr, int* elem_bytes) {
 
 int hawk_get_draft_logits(hawk_ctx* c, float* out, int k) {
     if (!c || !out) return HAWK_EINVAL;
+    HAWK_LIVE(c);
     if (c->phase < 2) return fail(c, HAWK_ESTATE, "no image in progress");
     if (k < 1 || k > c->kmax) return fail(c, HAWK_EINVAL, "k outside [1, k_max]");
     for (int b = 0; b < c->B; ++b) {

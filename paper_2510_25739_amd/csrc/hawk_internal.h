@@ -95,6 +95,7 @@ struct hawk_ctx {
     hawk::StreamPlan* plan;  // streaming path: job tables and barrier epoch (null until created)
     hawk::XcdOffsets xoff;
     hawk::XcdPlan* xplan;    // XCD-partitioned pass: plan and tag epoch (null until created)
+    int dead;                // a persistent kernel gave up on a wait: its exchange state is undefined, every call fails
     int last_kernel;         // kernel of the last target pass: 0 one per operation, 1 grid-barrier kernel, 2 XCD-partitioned kernel
     size_t blob_bytes;
     size_t split_bytes;
@@ -186,7 +187,8 @@ bool stream_tree_ok(const hawk_ctx*, int n_nodes);   // can a pass over tree row
 int launch_verify_stream_tree(hawk_ctx*, int n_nodes, const int32_t* tree_depth, const unsigned long long* tree_anc);
 bool stream_draft_ok(const hawk_ctx*);      // can draft micro-steps run on the streaming path?
 int launch_draft_stream(hawk_ctx*, int i, size_t off_prev, size_t off_out);  // micro-step i up to its logits
-int stream_error(hawk_ctx*);              // 1 if a grid barrier timed out (synchronises)
+int stream_error(hawk_ctx*);              // 1 if a wait of a persistent kernel timed out (synchronises)
+bool stream_has_err_word(const hawk_ctx*);   // the persistent kernels' error word exists and is cleared
 
 // ---- XCD-partitioned target pass, implemented in xcd.hip ----
 size_t xcd_workspace(const hawk_ctx*, size_t base, XcdOffsets* out);   // extra workspace bytes (0: shape not covered)

@@ -1251,6 +1251,7 @@ struct StreamPlan {
     std::vector<uint32_t> desc;
     unsigned epoch;     // grid barriers completed by all launches so far
     unsigned launches;
+    bool err_word_ready;   // the error word (shared with the kernel laid out on the XCDs) has been cleared
 };
 
 namespace {
@@ -1421,6 +1422,7 @@ StreamPlan* stream_create(hawk_ctx* c) {
     build_plan(c, P);
     P->epoch = 0;
     P->launches = 0;
+    P->err_word_ready = false;
     if (!P->ok) return P;
     {   // the grid barrier needs all kNWG workgroups resident at once: one per compute unit
         int dev = 0, cus = 0;
@@ -1431,13 +1433,6 @@ StreamPlan* stream_create(hawk_ctx* c) {
         }
     }
     const StreamOffsets& o = c->soff;
-    // tables, rotary table, zeroed barrier memory
-    (void)hipMemcpy(c->ws + o.tab, P->tab.data(), P->tab.size() * 4, hipMemcpyHostToDevice);
-    (void)hipMemcpy(c->ws + o.desc, P->desc.data(), P->desc.size() * 4, hipMemcpyHostToDevice);
-    (void)hipMemset(c->ws + o.bar, 0, (size_t)(kGroups + 1 + kReplicas) * 4096);
-    // every word of the exchange arenas starts as the "not written yet" pattern the W2 stage polls for
-    (void)hipMemset(c->ws + o.arena, 0xFF, o.slot_bytes * (size_t)(c->L + 1) * kRing);
-    (void)hipMemset(c->ws + o.err, 0, 256);
     std::vector<float> rope((size_t)c->Tmax * (c->hd / 2) * 2);
     for (int pos = 0; pos < c->Tmax; ++pos)
         for (int j = 0; j < c->hd / 2; ++j) {
@@ -1445,7 +1440,28 @@ StreamPlan* stream_create(hawk_ctx* c) {
             rope[((size_t)pos * (c->hd / 2) + j) * 2] = (float)cos(ang);
             rope[((size_t)pos * (c->hd / 2) + j) * 2 + 1] = (float)sin(ang);
         }
-    (void)hipMemcpy(c->ws + o.rope, rope.data(), rope.size() * 4, hipMemcpyHostToDevice);
+    // tables, rotary table, zeroed barrier memory - on the context's stream, every return code checked: a
+    // plan whose tables did not reach the device must never be launched
+    bool good = true;
+    auto up = [&](size_t off, const void* src, size_t bytes) {
+        good = good && hipMemcpyAsync(c->ws + off, src, bytes, hipMemcpyHostToDevice, c->stream) == hipSuccess;
+    };
+    auto fill = [&](size_t off, int value, size_t bytes) {
+        good = good && hipMemsetAsync(c->ws + off, value, bytes, c->stream) == hipSuccess;
+    };
+    up(o.tab, P->tab.data(), P->tab.size() * 4);
+    up(o.desc, P->desc.data(), P->desc.size() * 4);
+    fill(o.bar, 0, (size_t)(kGroups + 1 + kReplicas) * 4096);
+    // every word of the exchange arenas starts as the "not written yet" pattern the W2 stage polls for
+    fill(o.arena, 0xFF, o.slot_bytes * (size_t)(c->L + 1) * kRing);
+    fill(o.err, 0, 256);
+    up(o.rope, rope.data(), rope.size() * 4);
+    good = good && hipStreamSynchronize(c->stream) == hipSuccess;   // the sources are locals and plan members
+    if (!good) {
+        (void)hipGetLastError();
+        P->ok = false;   // the context falls back to one kernel per operation
+    }
+    P->err_word_ready = good;
     return P;
 }
 
@@ -1673,9 +1689,13 @@ int launch_draft_stream(hawk_ctx* c, int i, size_t off_prev, size_t off_out) {
     return launch_coop(c, kern, p, 1u);
 }
 
-// 1 if a barrier of the streaming kernels ever timed out (the result of that step is invalid).
+// The persistent kernels' error word exists and has been cleared (its region is part of the workspace
+// whenever the shape has a streaming plan; the kernel laid out on the XCDs shares it).
+bool stream_has_err_word(const hawk_ctx* c) { return c->plan && c->plan->err_word_ready; }
+
+// 1 if a wait of the persistent kernels ever timed out (the result of that step is invalid).
 int stream_error(hawk_ctx* c) {
-    if (!c->plan || !c->plan->ok) return 0;
+    if (!stream_has_err_word(c)) return 0;
     unsigned e = 0;
     if (hipMemcpyAsync(&e, c->ws + c->soff.err, 4, hipMemcpyDeviceToHost, c->stream) != hipSuccess) return 1;
     if (hipStreamSynchronize(c->stream) != hipSuccess) return 1;

@@ -1303,7 +1303,7 @@ size_t xcd_lds_bytes(const XcdPlan* P, int RPJ) {
 
 bool xcd_ok(const hawk_ctx* c, int k) {
     const XcdPlan* P = c->xplan;
-    if (!P || !P->ok || c->path != 1) return false;
+    if (!P || !P->ok || c->path != 1 || !stream_has_err_word(c)) return false;   // (error word and rotary table: the streaming plan's)
     const int RS = k + 1, MR = c->S * RS;
     if (MR > 16 || RS > 8) return false;
     for (int x = 0; x < kXcd; ++x)

@@ -71,6 +71,7 @@ EXPORTS = {
     "hawk_set_path": (C.c_int, [C.c_void_p, C.c_int]),
     "hawk_last_path": (C.c_int, [C.c_void_p]),
     "hawk_last_kernel": (C.c_int, [C.c_void_p]),
+    "hawk_debug_raise_timeout": (C.c_int, [C.c_void_p]),
     "hawk_phase_trace": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t]),
     "hawk_tree_layout": (C.c_int, [C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hawk_verify_tree": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -370,6 +371,10 @@ class Hawk:
     def last_kernel(self) -> int:
         """0: one kernel per operation, 1: grid-barrier persistent kernel, 2: the kernel laid out on the XCDs."""
         return int(self._L.hawk_last_kernel(self._h))
+
+    def debug_raise_timeout(self):
+        """Test hook: sets the persistent kernels' error word from the host."""
+        self._chk(self._L.hawk_debug_raise_timeout(self._h), "hawk_debug_raise_timeout")
 
     def phase_trace(self, enable: bool, n_stages: int = 0):
         """Switches the streaming kernel's stage time stamps; returns [4, n_stages, 8] uint64 if asked."""

@@ -294,6 +294,81 @@ def test_error_paths(H):
     assert 0 <= na[0] <= 2
 
 
+def test_timed_out_wait_is_reported_and_the_context_is_dead_afterwards(H):
+    # the error word of the persistent kernels, set from the host as a timed-out wait would set it (no
+    # kernel runs in that state): the next call that returns data reports HAWK_EDEVICE, and so does every
+    # call after it, without touching the device
+    s = synth.CONFIGS[1].replace(n_layers=2, n_cond=24, grid_h=6, grid_w=8)
+    blob = synth.make_weights(s, seed=0)
+    cond = synth.make_cond(s, seed=2)
+    hk = H.Hawk(H.HawkConfig.from_shape(s))
+    hk.load(blob)
+    hk.prefill(cond, None, s.grid_h, s.grid_w, 1.0, s.top_k, 1.0, [0.25])
+    u = np.full((1, s.k), 0.5, np.float32)
+    hk.draft(s.k, u)
+    na, _ = hk.verify(s.k, u, [0.5])
+    assert hk.last_path() == 1 and 0 <= na[0] <= s.k
+    n_before = hk.n().copy()
+    hk.debug_raise_timeout()
+    with pytest.raises(H.HawkError) as e:
+        hk.n()
+    assert e.value.code == -4 and "timed out" in str(e.value)
+    for call in (lambda: hk.draft(s.k, u), lambda: hk.grid(), lambda: hk.logits(1), lambda: hk.stats(),
+                 lambda: hk.prefill(cond, None, s.grid_h, s.grid_w, 1.0, s.top_k, 1.0, [0.25]),
+                 lambda: hk.run_steps(s.k, 1, 1)):
+        with pytest.raises(H.HawkError) as e:
+            call()
+        assert e.value.code == -4
+    hk.close()
+    # a new context on the same shape works
+    hk = H.Hawk(H.HawkConfig.from_shape(s))
+    hk.load(blob)
+    hk.prefill(cond, None, s.grid_h, s.grid_w, 1.0, s.top_k, 1.0, [0.25])
+    hk.draft(s.k, u)
+    hk.verify(s.k, u, [0.5])
+    assert np.array_equal(hk.n(), n_before)
+    # a shape without a persistent-kernel plan has no such word
+    s0 = synth.CONFIGS[0].replace(n_layers=1)
+    h0 = H.Hawk(H.HawkConfig.from_shape(s0))
+    with pytest.raises(H.HawkError) as e:
+        h0.debug_raise_timeout()
+    assert e.value.code == -2
+
+
+@pytest.mark.parametrize("path", [0, 1, 2])
+def test_two_contexts_on_the_same_inputs_give_identical_bits(H, path):
+    # determinism: every sum is taken in a fixed order on all three kernel sets - two contexts fed the same
+    # weights, prompt and uniforms produce bit-identical logits, draft logits and tokens, step after step
+    s = synth.CONFIGS[1].replace(n_layers=3, n_cond=24, grid_h=6, grid_w=8)
+    blob = synth.make_weights(s, seed=0)
+    cond = synth.make_cond(s, seed=2)
+    runs = []
+    for rep in range(2):
+        hk = H.Hawk(H.HawkConfig.from_shape(s))
+        hk.load(blob)
+        hk.set_path(path)
+        hk.prefill(cond, None, s.grid_h, s.grid_w, 1.0, s.top_k, 1.0, [0.25])
+        rng = np.random.Generator(np.random.PCG64(11))
+        rec = [hk.logits(1).copy()]
+        for step in range(6):
+            k = [s.k, 2, s.k, 0, s.k, s.k][step]
+            ud = (rng.integers(0, 1 << 24, size=(1, max(k, 1))).astype(np.float32) / np.float32(1 << 24))[:, :k]
+            ua = (rng.integers(0, 1 << 24, size=(1, max(k, 1))).astype(np.float32) / np.float32(1 << 24))[:, :k]
+            d = hk.draft(k, ud)
+            if k > 0:
+                rec.append(hk.draft_logits(k).copy())
+            na, t = hk.verify(k, ua, [0.5])
+            assert hk.last_kernel() == KERNEL_OF_PATH[path]
+            rec += [np.asarray(d).copy(), na.copy(), t.copy(), hk.logits(k + 1).copy()]
+        rec.append(hk.grid().copy())
+        hk.close()
+        runs.append(rec)
+    assert len(runs[0]) == len(runs[1])
+    for a, b in zip(runs[0], runs[1]):
+        assert a.dtype == b.dtype and a.shape == b.shape
+        assert a.tobytes() == b.tobytes()
+
+
 # ----------------------------------------------------------------------------- bf16: tolerance
 
 def bf16_case(H, shape, k, path, steps, u_seed=1, **kw):
