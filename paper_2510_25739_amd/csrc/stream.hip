@@ -1604,7 +1604,7 @@ static void fill_params(hawk_ctx* c, SP& p, int MR) {
     p.act_bytes = (int32_t)std::max((size_t)p.MR * act_stride(c) * 4, (size_t)kCW * 6 * kPS * 4);
 }
 
-static int launch_coop(hawk_ctx* c, const void* kern, SP& p, unsigned barriers) {
+static int launch_persistent(hawk_ctx* c, const void* kern, SP& p, unsigned barriers) {
     StreamPlan* P = c->plan;
     const size_t lds = stream_lds_bytes(c, p.MR);
     if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return -1;
@@ -1631,7 +1631,7 @@ int launch_verify_stream(hawk_ctx* c, int k) {
     const void* kern = c->d == 1280 ? reinterpret_cast<const void*>(verify_stream_kernel<10, 9, 5, 6>)
                                     : reinterpret_cast<const void*>(verify_stream_kernel<6, 4, 3, 6>);
     // prologue + five stages per layer; nothing follows the output projection
-    return launch_coop(c, kern, p, 1u + 5u * (unsigned)c->L);
+    return launch_persistent(c, kern, p, 1u + 5u * (unsigned)c->L);
 }
 
 // Tree rows on the streaming path: the nodes of one candidate tree per sequence, at most 16 rows in
@@ -1661,7 +1661,7 @@ int launch_verify_stream_tree(hawk_ctx* c, int n_nodes, const int32_t* tree_dept
                                : reinterpret_cast<const void*>(verify_stream_kernel<10, 9, 5, 6, true, 2>))
                      : (single ? reinterpret_cast<const void*>(verify_stream_kernel<6, 4, 3, 6, true, 1>)
                                : reinterpret_cast<const void*>(verify_stream_kernel<6, 4, 3, 6, true, 2>));
-    return launch_coop(c, kern, p, 1u + 5u * (unsigned)c->L);
+    return launch_persistent(c, kern, p, 1u + 5u * (unsigned)c->L);
 }
 
 // Can draft micro-steps run on the streaming path?
@@ -1686,7 +1686,7 @@ int launch_draft_stream(hawk_ctx* c, int i, size_t off_prev, size_t off_out) {
     p.step_i = i; p.N = c->N; p.IW = c->gw; p.kstride = c->kmax + 1;
     const void* kern = c->d == 1280 ? reinterpret_cast<const void*>(draft_stream_kernel<10, 5, 6>)
                                     : reinterpret_cast<const void*>(draft_stream_kernel<6, 3, 6>);
-    return launch_coop(c, kern, p, 1u);
+    return launch_persistent(c, kern, p, 1u);
 }
 
 // The persistent kernels' error word exists and has been cleared (its region is part of the workspace

@@ -376,11 +376,62 @@ def bf16_case(H, shape, k, path, steps, u_seed=1, **kw):
     return lockstep(shape, hk, orc, k, u_seed=u_seed, max_steps=steps, **kw)
 
 
-def assert_bf16(res, min_steps, min_decision_rate):
-    assert res["stage_bad"] == 0, res                       # sampling stage exact on its own logits
+def assert_bf16(res, min_steps, max_disagree=1):
+    """bf16 bar: the sampling stage exact on the GPU's own logits, logits within 2e-2 of the oracle's, and at
+    most max_disagree steps whose accept / reject decision differs (short runs: one step, i.e. a near-tie
+    between the two sides' rounding; the long runs below state 0.1 % and 0.5 %)."""
+    assert res["stage_bad"] == 0, res
     assert res["max_logit_err"] <= 2e-2 and res["max_draft_logit_err"] <= 2e-2, res
     assert res["steps"] >= min_steps, res
-    assert res["decision_same"] >= min_decision_rate * res["steps"], res
+    assert res["steps"] - res["decision_same"] <= max_disagree, res
+
+
+def long_run(H, s, path, min_steps, expect_kernel, max_images=40):
+    """Images in lockstep with the oracle, one context pair, until min_steps steps are covered.  A first token
+    (sampled by the prefill itself) that differs counts as one step with a differing decision."""
+    blob, hk, orc = make_pair(H, s, path=path)
+    total = dict(steps=0, decision_same=0, token_same=0, draft_same=0, accepted=0, stage_bad=0, first_differs=0,
+                 max_logit_err=0.0, max_draft_logit_err=0.0)
+    for u_seed in range(1, max_images + 1):
+        res = lockstep(s, hk, orc, s.k, u_seed=u_seed, max_steps=min_steps - total["steps"])
+        total["stage_bad"] += res["stage_bad"]
+        if not res["first_same"]:
+            total["steps"] += 1
+            total["first_differs"] += 1
+            continue
+        assert hk.last_kernel() == expect_kernel
+        for key in ("steps", "decision_same", "token_same", "draft_same", "accepted"):
+            total[key] += res[key]
+        for key in ("max_logit_err", "max_draft_logit_err"):
+            total[key] = max(total[key], res[key])
+        print("  image", u_seed, {k: total[k] for k in ("steps", "decision_same", "token_same", "max_logit_err")}, flush=True)
+        if total["steps"] >= min_steps:
+            break
+    hk.close()
+    orc.close()
+    return total
+
+
+def test_bf16_config1_full_shape_1200_steps(H):
+    # north-star criterion at configuration 1's real shape (12 layers, d = 768, 16 x 16 grid, codebook 16384,
+    # top-k 1000, k = 5) on the default kernel set: >= 1200 steps over several images, identical accept /
+    # reject decisions on >= 99.9 % of them, logits within 2e-2
+    s = synth.CONFIGS[1]
+    total = long_run(H, s, 1, 1200, KERNEL_OF_PATH[1])
+    print("bf16 agreement, configuration 1 full shape:", total)
+    assert total["steps"] >= 1200 and total["stage_bad"] == 0
+    assert total["decision_same"] >= 0.999 * total["steps"], total
+    assert total["max_logit_err"] <= 2e-2 and total["max_draft_logit_err"] <= 2e-2, total
+
+
+def test_bf16_config2_full_depth_300_steps(H):
+    # the same at configuration 2 (XL shape, 36 layers, 24 x 24 grid): >= 300 steps, >= 99.5 % identical decisions
+    s = synth.CONFIGS[2]
+    total = long_run(H, s, 1, 300, KERNEL_OF_PATH[1])
+    print("bf16 agreement, configuration 2 full depth:", total)
+    assert total["steps"] >= 300 and total["stage_bad"] == 0
+    assert total["decision_same"] >= 0.995 * total["steps"], total
+    assert total["max_logit_err"] <= 2e-2 and total["max_draft_logit_err"] <= 2e-2, total
 
 
 @pytest.mark.parametrize("path,top_k", [(0, 1000), (1, 1000), (1, 16384)])
@@ -395,9 +446,10 @@ def test_bf16_decisions_over_many_steps(H, path, top_k):
     for u_seed in range(1, 60):
         res = bf16_case(H, s, s.k, path, steps=10 ** 6, u_seed=u_seed)
         assert res["stage_bad"] == 0, res
-        if not res["first_same"]:
+        if not res["first_same"]:   # the prefill's own token differs: one step, decision not the same
+            total["steps"] += 1
             continue
-        assert_bf16(res, 1, 0.0)
+        assert_bf16(res, 1, max_disagree=10 ** 9)
         for key in total:
             total[key] += res[key]
         if total["steps"] >= 1200:
@@ -417,7 +469,7 @@ def test_bf16_config1_full_depth_sampled_steps(H, path):
         assert res["stage_bad"] == 0, res
         if res["first_same"]:
             break
-    assert_bf16(res, 12, 0.99)
+    assert_bf16(res, 12, 0)
 
 
 def test_bf16_replay_and_greedy(H):
@@ -487,7 +539,7 @@ def test_streaming_kernel_lockstep_with_oracle(H, cfg, layers, steps, path):
             assert hk.last_path() == 1 and hk.last_kernel() == KERNEL_OF_PATH[path]
             break
     print("streaming lockstep", res)
-    assert_bf16(res, steps, 0.95)
+    assert_bf16(res, steps)
 
 
 def accumulate_lockstep(H, s, k, path, min_steps, max_runs=40, expect_path=None, expect_kernel=None, **kw):
@@ -507,6 +559,8 @@ def accumulate_lockstep(H, s, k, path, min_steps, max_runs=40, expect_path=None,
         hk.close()
         for key in ("steps", "decision_same", "stage_bad", "token_same", "accepted"):
             total[key] += res[key]
+        if not res["first_same"]:   # the prefill's own token differs: one step, decision not the same
+            total["steps"] += 1
         for key in ("max_logit_err", "max_draft_logit_err"):
             total[key] = max(total[key], res[key])
         if total["steps"] >= min_steps:
@@ -525,7 +579,7 @@ def test_streaming_kernel_row_counts_and_batches(H, cfg, k, batch, scale, path):
     s = synth.CONFIGS[cfg].replace(n_layers=2, n_cond=24, grid_h=6, grid_w=8, batch=batch, cfg_scale=scale, k=k)
     total = accumulate_lockstep(H, s, k, path, 12, expect_path=1, expect_kernel=KERNEL_OF_PATH[path])
     print("streaming cut", (cfg, k, batch, scale), "kernel", KERNEL_OF_PATH[path], total)
-    assert_bf16(total, 12, 0.9)
+    assert_bf16(total, 12)
 
 
 @pytest.mark.parametrize("path", [1, 2])
@@ -577,7 +631,7 @@ def test_one_kernel_per_operation_row_counts(H, cfg, k, batch, scale, rows):
     assert batch * (2 if scale != 1.0 else 1) * (k + 1) == rows
     total = accumulate_lockstep(H, s, k, 0, 10, expect_path=0)
     print("one kernel per operation", (cfg, k, batch, scale), total)
-    assert_bf16(total, 10, 0.9)
+    assert_bf16(total, 10)
 
 
 def test_one_kernel_per_operation_without_the_tile_major_copy(H):
@@ -586,7 +640,7 @@ def test_one_kernel_per_operation_without_the_tile_major_copy(H):
     s = synth.CONFIGS[1].replace(n_layers=2, n_cond=24, grid_h=6, grid_w=8, d_mlp=2056, k=3)
     total = accumulate_lockstep(H, s, s.k, 0, 10, expect_path=0)
     print("row-major weights", total)
-    assert_bf16(total, 10, 0.9)
+    assert_bf16(total, 10)
 
 
 def test_config3_guidance_batch16_reduced_depth(H):
@@ -595,10 +649,10 @@ def test_config3_guidance_batch16_reduced_depth(H):
     s = synth.CONFIGS[3].replace(n_layers=2, n_cond=16, grid_h=4, grid_w=8)
     total = accumulate_lockstep(H, s, s.k, 1, 6, max_runs=12)
     print("config 3 sampled", total)
-    assert_bf16(total, 6, 0.8)
+    assert_bf16(total, 6)
     greedy = accumulate_lockstep(H, s, s.k, 1, 6, max_runs=4, temperature=0.0)
     print("config 3 greedy", greedy)
-    assert_bf16(greedy, 6, 0.8)
+    assert_bf16(greedy, 6)
 
 
 def test_config3_full_depth_sampled_prompts(H):
@@ -671,7 +725,33 @@ def test_config4_7b_shape_slice_and_guidance_reduced(H):
     s = synth.CONFIGS[4].replace(n_layers=1, vocab=12288, n_cond=8, grid_h=4, grid_w=8)
     total = accumulate_lockstep(H, s, s.k, 1, 8, max_runs=10)
     print("config 4 shape", total)
-    assert_bf16(total, 8, 0.8)
+    assert_bf16(total, 8)
+
+
+def test_config4_full_depth_one_step(H):
+    # configuration 4 at its full depth and widths (32 layers, d = 4096, MLP 11008, vocabulary 65536, slice of
+    # 8192 at id 4, top-k 2000, guidance 3.0: 12 rows per target pass) with a condition of 8 vectors (the
+    # oracle's prefill is 13 GFLOP per row): prefill and one speculate-and-verify step against the oracle
+    s = synth.CONFIGS[4].replace(n_cond=8)
+    res = None
+    blob, hk, orc = make_pair(H, s, path=1)
+    for u_seed in (1, 2, 3):
+        res = lockstep(s, hk, orc, s.k, u_seed=u_seed, max_steps=1)
+        assert res["stage_bad"] == 0, res
+        if res["first_same"]:
+            break
+    assert res["first_same"], "no image whose first token agrees"
+    # The 2e-2 bound is stated for configuration 2, whose logits have a standard deviation of 0.72 (weights
+    # N(0, 0.02^2), d = 1280): 2.8 % of it.  The error is dominated by the fp16 rounding of cached keys and
+    # values and scales with the logits; here they are wider (d = 4096: 1.28) and the target rows are guided
+    # (l_u + 3 (l_c - l_u)), so the bound is taken relative to the standard deviation of the oracle's rows.
+    sig_p, sig_q = float(orc.logits()[0, 0].std()), float(orc.draft_logits()[0, 0].std())
+    print("config 4 full depth:", res, "logit std target (guided)", sig_p, "draft", sig_q,
+          "relative errors", res["max_logit_err"] / sig_p, res["max_draft_logit_err"] / sig_q)
+    assert res["stage_bad"] == 0 and res["steps"] == 1 and res["decision_same"] == 1, res
+    assert res["max_logit_err"] <= 0.028 * sig_p and res["max_draft_logit_err"] <= 0.028 * sig_q, res
+    hk.close()
+    orc.close()
 
 
 @pytest.mark.parametrize("path", [1, 2])
@@ -685,4 +765,4 @@ def test_streaming_kernel_xl_full_depth_sampled_steps(H, path):
             assert hk.last_path() == 1 and hk.last_kernel() == KERNEL_OF_PATH[path]
             break
     print("XL full depth", res)
-    assert_bf16(res, 6, 0.8)
+    assert_bf16(res, 6)
