@@ -25,9 +25,29 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
-# scaled by a 1 GiB device copy in the same run (FETCH_SIZE factor 2.000, WRITE_SIZE 1.000).
-TRAFFIC_BYTES_PER_LAUNCH = int(780214 * 1024 * 2.000 + 60533 * 1024 * 1.000)   # config 2, streaming kernel
+KERNEL_NAMES = {0: "verify phase (one kernel per operation)", 1: "verify_stream_kernel", 2: "verify_xcd_kernel"}
+
+
+def traffic_from_profile(kernel: str, config: int):
+    """HBM bytes per launch of `kernel` from the tracked rocprofv3 summary profiles/<kernel>_config<n>.txt,
+    which carries a line
+        TRAFFIC kernel=<name> config=<n> fetch_kib=<mean FETCH_SIZE> write_kib=<mean WRITE_SIZE> fetch_factor=<a>
+                write_factor=<b> head=<git short hash of the measured build>
+    (counters per dispatch from two rocprofv3 --pmc runs, factors from a 1 GiB device copy in the same
+    runs).  Returns (bytes, source) or (None, None) when there is no such summary."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_config{config}.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("TRAFFIC "):
+                    kv = dict(item.split("=", 1) for item in line.split()[1:])
+                    if kv.get("kernel") == kernel and int(kv.get("config", -1)) == config:
+                        b = float(kv["fetch_kib"]) * 1024 * float(kv["fetch_factor"]) + \
+                            float(kv["write_kib"]) * 1024 * float(kv["write_factor"])
+                        return int(b), f"profiles/{kernel}_config{config}.txt (build {kv.get('head', '?')})"
+    except OSError:
+        pass
+    return None, None
 
 
 def verify_bytes(s, kv_len: float) -> float:
@@ -83,7 +103,27 @@ def run_mode(hk, s, cond, unc, steps, warmup, replay_tokens, seed):
     return dict(tokens_per_s=tokens / (wall_ms * 1e-3), ms_per_step=wall_ms / steps,
                 tokens_per_step=tokens / max(1, st1["steps"] - st0["steps"]),
                 ms_draft=ms_draft / steps, ms_verify=ms_verify / steps, ms_kernel=ms_kernel / steps, kv_len=kv_mid,
-                n_window=[int(n0.min()), int(n2.max())])
+                n_window=[int(n0.min()), int(n2.max())], kernel=hk.last_kernel())
+
+
+def other_config(H, synth, cfg, steps, warmup, blob=None):
+    """Random-draft leg of another configuration of the table (3: 16 prompts with guidance, 192 rows per target
+    pass; 4: the 7B shape with guidance), as extra keys of the line: throughput, step time and the verify
+    step's rate over its algorithmic bytes.  Configuration 4's 13.6 GB blob repeats layer 0's draw."""
+    s = synth.CONFIGS[cfg]
+    if blob is None:
+        blob = synth.make_weights(s, seed=0, repeat_layer0=(cfg == 4))
+    cond = synth.make_cond(s, seed=2)
+    unc = synth.make_cond(s, seed=3) if s.use_cfg else None
+    hk = H.Hawk(H.HawkConfig.from_shape(s))
+    hk.load(blob)
+    r = run_mode(hk, s, cond, unc, steps, warmup, None, seed=1)
+    hk.close()
+    vb = verify_bytes(s, r["kv_len"])
+    r.update(workload=f"config {cfg}: {s.name}, {s.n_layers} layers d={s.d_model}, {s.grid_h}x{s.grid_w} grid, k={s.k}, "
+                      f"batch {s.batch}, guidance {s.cfg_scale}", steps=steps, verify_bytes=vb,
+             verify_GBs=vb / (r["ms_verify"] * 1e-3) / 1e9, verify_frac_of_hbm_peak=vb / (r["ms_verify"] * 1e-3) / 1e9 / HBM_PEAK_GBS)
+    return r
 
 
 def cpu_baseline(s, blob, cond, unc, budget_s=15.0, max_steps=8):
@@ -115,7 +155,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
-    ap.add_argument("--path", type=int, default=1, help="0 = generic kernels, 1 = fused kernels")
+    ap.add_argument("--path", type=int, default=1,
+                    help="0 = one kernel per operation, 1 = persistent kernels (default), 2 = grid-barrier persistent kernel only")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the config 3 / config 4 legs of the default run")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 1 GiB device-to-device copy three times (reference for hardware counters)")
     ap.add_argument("--only-random", action="store_true", help="skip the replay and plain-AR legs (profiling runs)")
@@ -161,8 +203,9 @@ def main():
     # dominant launch and the whole verify phase is used instead.
     vb = verify_bytes(s, rnd["kv_len"])
     ms_dom = rnd["ms_kernel"] if rnd["ms_kernel"] > 0 else rnd["ms_verify"]
-    kname = "verify_stream_kernel" if rnd["ms_kernel"] > 0 else "verify phase (all generic kernels)"
+    kname = KERNEL_NAMES[rnd["kernel"] if rnd["ms_kernel"] > 0 else 0]
     achieved = vb / (ms_dom * 1e-3) / 1e9
+    traffic, traffic_source = traffic_from_profile(kname, args.config) if rnd["ms_kernel"] > 0 else (None, None)
     out = {
         "metric": "image tokens/sec/GPU (speculate-and-verify, random-init acceptance)",
         "value": rnd["tokens_per_s"], "unit": "image tokens/s", "n_gpus": 1, "steps": steps,
@@ -177,7 +220,7 @@ def main():
                                 "paper_context": "1.71x on 1x RTX 3090 with trained heads (not comparable)"},
         "roofline": {"bound": "hbm", "kernel": kname,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": TRAFFIC_BYTES_PER_LAUNCH if (args.config == 2 and rnd["ms_kernel"] > 0) else None, "bytes_per_launch": vb, "ms_per_launch": ms_dom,
+                     "traffic": traffic, "traffic_source": traffic_source, "bytes_per_launch": vb, "ms_per_launch": ms_dom,
                      "verify_step_ms": rnd["ms_verify"],
                      "draft_phase": {"bytes": draft_bytes(s), "ms": rnd["ms_draft"],
                                      "GB/s": draft_bytes(s) / (rnd["ms_draft"] * 1e-3) / 1e9}},
@@ -193,6 +236,9 @@ def main():
     if s.batch == 1 and not s.use_cfg:   # heads -> cache -> pool -> candidates -> tree step over one image
         from paper_2510_25739_amd.scheme_timing import bench_scheme
         out["whole_scheme"] = bench_scheme(H, s, blob, cond)
+    if args.config == 2 and not args.no_other_configs:
+        out["config3"] = other_config(H, synth, 3, 40, 4, blob=blob)   # same shape and seed as configuration 2: same blob
+        out["config4"] = other_config(H, synth, 4, 40, 4)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(s, blob, cond, unc)
     print(json.dumps(out))

@@ -138,10 +138,26 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
-def make_weights(s: HawkShape, seed: int = 0, std: float = 0.02) -> np.ndarray:
+def make_weights(s: HawkShape, seed: int = 0, std: float = 0.02, repeat_layer0: bool = False) -> np.ndarray:
     """The weight blob (uint8 array): every matrix N(0, std^2) drawn in fp32 in blob
     order from one PCG64 stream, norm gains exactly 1; bf16 blobs hold the
-    round-to-nearest-even bf16 of the fp32 draw."""
+    round-to-nearest-even bf16 of the fp32 draw.  repeat_layer0: only the embedding, layer 0 and
+    the tensors behind the layers are drawn and layer 0's bytes are copied into the other layers
+    (timing runs of the largest shape: same sizes and value distribution in a tenth of the time;
+    not for parity tests, whose blobs are drawn in full)."""
+    if repeat_layer0 and s.n_layers > 1:
+        one = make_weights(s.replace(n_layers=1), seed=seed, std=std)
+        lay1, lay = blob_layout(s.replace(n_layers=1)), blob_layout(s)
+        blob = np.zeros(lay["__end__"][0], dtype=np.uint8)
+        a, b = lay1["l0.g1"][0], lay1["g_f"][0]            # layer 0's bytes in the one-layer blob
+        blob[:b] = one[:b]
+        for l in range(1, s.n_layers):
+            o = lay[f"l{l}.g1"][0]
+            blob[o:o + (b - a)] = one[a:b]
+        tail = lay["g_f"][0]
+        blob[tail:] = one[b:]
+        blob[:BLOB_HEADER_BYTES].view(np.int32)[3] = s.n_layers
+        return blob
     lay = blob_layout(s)
     blob = np.zeros(lay["__end__"][0], dtype=np.uint8)
     hdr = blob[:BLOB_HEADER_BYTES].view(np.int32)
