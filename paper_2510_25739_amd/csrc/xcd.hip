@@ -79,7 +79,7 @@ struct XP {
     u64* part[X_NK];            // partial sums: [ring][8 source XCDs][strip][16 rows][4][4] {value, tag}
     u64* pss[X_NK];             // per-XCD sums of squares that ride along (products after a norm): [ring][8][unit][wave][round][16 rows] {value, tag}
     uint8_t* xbuf;              // per-XCD buffers: [8][ring][xcd_bytes]
-    u64 xcd_bytes, o_a, o_q, o_o, o_x2, o_h, o_ss;   // regions of one XCD buffer (bytes)
+    u64 xcd_bytes, o_a, o_q, o_kv, o_o, o_x2, o_h, o_ss;   // regions of one XCD buffer (bytes)
     unsigned* lflag;            // [8][F_NF][kMaxJobs]
     const uint16_t* blob;
     u64 g1_off, g2_off, layer_bytes, gf_off;
@@ -524,16 +524,24 @@ __device__ __forceinline__ void reduce_job(const XP& p, Ctx& c, const IoJobs& jb
         const float a0 = v[0] * jb.rot0.x - v[1] * jb.rot0.y, b0 = v[0] * jb.rot0.y + v[1] * jb.rot0.x;
         const float a1 = v[2] * jb.rot1.x - v[3] * jb.rot1.y, b1 = v[2] * jb.rot1.y + v[3] * jb.rot1.x;
         if (live) {
-            if (seg == 0) {   // queries of this XCD's heads, scaled by 1 / sqrt(64)
-                float* q = reinterpret_cast<float*>(buf + p.o_q) + (size_t)col * (p.KpO - 8) + (h - p.hd0[c.x]) * 64 + j0 % 64 + 4 * quad;
-                *reinterpret_cast<f32x4*>(q) = (f32x4){a0 * 0.125f, b0 * 0.125f, a1 * 0.125f, b1 * 0.125f};
-            } else if (jb.rp.valid) {
-                _Float16* dst = (seg == 1 ? p.Kc : p.Vc) +
-                                ((((size_t)layer * p.Smax + jb.rp.seq) * p.H + h) * p.Tmax + jb.rp.pos) * 64 + j0 % 64 + 4 * quad;
+            const int hl = h - p.hd0[c.x], f0 = j0 % 64 + 4 * quad;   // head among the XCD's, first of the lane's four features
+            if (seg == 0) {   // queries of this XCD's heads, scaled by 1 / sqrt(64): {value, tag} pairs
+                v4u* q = reinterpret_cast<v4u*>(buf + p.o_q + ((size_t)col * (p.KpO - 8) + hl * 64 + f0) * 8);
+                q[0] = (v4u){__float_as_uint(a0 * 0.125f), tag, __float_as_uint(b0 * 0.125f), tag};
+                q[1] = (v4u){__float_as_uint(a1 * 0.125f), tag, __float_as_uint(b1 * 0.125f), tag};
+            } else {
+                // keys (rotated) / values as fp16 pairs: into the cache for the steps to come (valid rows), and
+                // as tagged pairs for this launch's attention jobs, which poll them ({pair, tag, pair, tag})
                 const _Float16 h0 = (_Float16)a0, h1 = (_Float16)b0, h2 = (_Float16)a1, h3 = (_Float16)b1;
-                *reinterpret_cast<uint2*>(dst) = make_uint2(
-                    (unsigned)__builtin_bit_cast(unsigned short, h0) | ((unsigned)__builtin_bit_cast(unsigned short, h1) << 16),
-                    (unsigned)__builtin_bit_cast(unsigned short, h2) | ((unsigned)__builtin_bit_cast(unsigned short, h3) << 16));
+                const unsigned p01 = (unsigned)__builtin_bit_cast(unsigned short, h0) | ((unsigned)__builtin_bit_cast(unsigned short, h1) << 16);
+                const unsigned p23 = (unsigned)__builtin_bit_cast(unsigned short, h2) | ((unsigned)__builtin_bit_cast(unsigned short, h3) << 16);
+                if (jb.rp.valid) {
+                    _Float16* dst = (seg == 1 ? p.Kc : p.Vc) +
+                                    ((((size_t)layer * p.Smax + jb.rp.seq) * p.H + h) * p.Tmax + jb.rp.pos) * 64 + f0;
+                    *reinterpret_cast<uint2*>(dst) = make_uint2(p01, p23);
+                }
+                *reinterpret_cast<v4u*>(buf + p.o_kv + ((((size_t)(seg - 1) * 16 + col) * (p.KpO - 8) / 64 + hl) * 16 + f0 / 4) * 16) =
+                    (v4u){p01, tag, p23, tag};
             }
         }
     } else if (kind == X_D) {   // rows 0..7 of the strip: W1 rows s * 8 + i, rows 8..15 the matching W3 rows
@@ -556,7 +564,7 @@ __device__ __forceinline__ void reduce_job(const XP& p, Ctx& c, const IoJobs& jb
         if (kind == X_E && layer == p.L - 1 && live)   // final hidden rows, for the kernels that follow
             *reinterpret_cast<f32x4*>(p.X + (size_t)col * d + s * 16 + 4 * quad) = resid;
     }
-    raise_flag(p, c, flag, slot, tag);
+    if (kind != X_A) raise_flag(p, c, flag, slot, tag);   // (queries, keys and values carry their own tags)
 }
 
 // Output projection: logits of the strip's 16 vocabulary entries for every row.
@@ -733,14 +741,31 @@ __device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, c
     fetch(ka, va, 0);
     fetch(kb, vb, 1);
     fetch(kc, vc, 2);
-    if (io == 0) {
-        wait_flags(p, c, F_A, jb.nA, tag_of(c, layer, F_A));
+    const unsigned tagA = tag_of(c, layer, F_A);   // what the reduce jobs of the QKV product wrote carries this tag
+    if (io == 0) {   // the job's queries: polled where the reduce jobs put them
+        const u64* q = reinterpret_cast<const u64*>(buf + p.o_q) + (size_t)(seq * RS + r0) * (p.KpO - 8) + (h - p.hd0[c.x]) * 64 + lane;
+        u64 qv[RPJ];
+        unsigned pend = 0u;
+#pragma unroll
+        for (int r = 0; r < RPJ; ++r) {
+            qv[r] = 0ull;
+            if (r0 + r < RS && !c.dead) pend |= 1u << r;
+        }
+        bool ok = false;
+        for (unsigned spins = 0; spins < kSpinLimit && !ok; ++spins) {
+#pragma unroll
+            for (int r = 0; r < RPJ; ++r)
+                if ((pend >> r) & 1u) qv[r] = ld_u64(q + (size_t)r * (p.KpO - 8));
+#pragma unroll
+            for (int r = 0; r < RPJ; ++r)
+                if (((pend >> r) & 1u) && (unsigned)(qv[r] >> 32) == tagA) pend &= ~(1u << r);
+            ok = __all(pend == 0u);
+            if (!ok && (spins & 255u) == 255u && ld_u32(c.err) != 0u) break;
+        }
+        if (!ok) give_up(c);
         stamp(c, stage, 1);
-        const float* q = reinterpret_cast<const float*>(buf + p.o_q);
-        for (int r = 0; r < RPJ; ++r)
-            s.qs[r * 64 + lane] = r0 + r < RS ? __uint_as_float(ld_u32(q + (size_t)(seq * RS + r0 + r) * (p.KpO - 8) +
-                                                                        (h - p.hd0[c.x]) * 64 + lane))
-                                              : 0.f;
+#pragma unroll
+        for (int r = 0; r < RPJ; ++r) s.qs[r * 64 + lane] = (r0 + r < RS && ok) ? __uint_as_float((unsigned)qv[r]) : 0.f;
     }
     io_barrier(s, joins, lane);   // the queries are in LDS
     {
@@ -767,10 +792,25 @@ __device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, c
         // requested now, used after the cached positions
         const bool fresh_row = io == 0 && pg <= ke && pg < RS;
         v4u kn = (v4u){0u, 0u, 0u, 0u}, vn = (v4u){0u, 0u, 0u, 0u};
-        if (fresh_row) {
-            const unsigned at = (unsigned)((kv0 + pg) * 64 + dg * 8) * 2u;
-            kn = ld_16(make_rsrc(p.Kc + head0), at);
-            vn = ld_16(make_rsrc(p.Vc + head0), at);
+        if (io == 0) {   // polled as tagged fp16 pairs: lane group pg = appended row, lane dg = features 8 dg .. 8 dg + 7
+            const rsrc_t kvr = make_rsrc(p.xbuf);
+            const unsigned hw = (unsigned)(p.KpO - 8) / 64u;   // heads a row of the region has room for
+            const unsigned atk = (unsigned)(((size_t)c.x * kRing + (layer & 1)) * p.xcd_bytes + p.o_kv) +
+                                 ((((unsigned)(seq * RS + pg)) * hw + (unsigned)(h - p.hd0[c.x])) * 16u + 2u * dg) * 16u;
+            const unsigned atv = atk + 16u * hw * 16u * 16u;
+            v4u k0, k1, v0, v1;
+            bool ok = !fresh_row || c.dead;
+            for (unsigned spins = 0; spins < kSpinLimit && !__all(ok); ++spins) {
+                if (!ok) {
+                    k0 = ld_16(kvr, atk); k1 = ld_16(kvr, atk + 16u);
+                    v0 = ld_16(kvr, atv); v1 = ld_16(kvr, atv + 16u);
+                    ok = k0[1] == tagA && k0[3] == tagA && k1[1] == tagA && k1[3] == tagA && v0[1] == tagA && v0[3] == tagA &&
+                         v1[1] == tagA && v1[3] == tagA;
+                    if (ok) { kn = (v4u){k0[0], k0[2], k1[0], k1[2]}; vn = (v4u){v0[0], v0[2], v1[0], v1[2]}; }
+                }
+                if ((spins & 255u) == 255u && ld_u32(c.err) != 0u) break;
+            }
+            if (!__all(ok)) give_up(c);
         }
         for (int rnd = 0; rnd < nrounds; rnd += 3) {
             run(ka, va, rnd);
@@ -1195,11 +1235,12 @@ bool attn_jobs(const hawk_ctx* c, const XcdPlan* P, int RS, int* RPJ, std::vecto
 size_t xcd_buf_layout(const XcdPlan* P, XP* p) {
     size_t at = 0;
     auto take = [&](size_t n) { size_t a = at; at = up256(at + n); return a; };
-    const size_t a = take((size_t)2 * 16 * P->KpA * 2), q = take((size_t)16 * (P->KpO - 8) * 4);
+    const size_t a = take((size_t)2 * 16 * P->KpA * 2), q = take((size_t)16 * (P->KpO - 8) * 8);   // queries: {value, tag}
+    const size_t kv = take((size_t)2 * 16 * ((P->KpO - 8) / 64) * 16 * 16);   // appended keys | values: [2][16 rows][heads][16 words] {fp16 pair, tag} x 2
     const size_t o = take((size_t)2 * 16 * P->KpO * 2), x2 = take((size_t)2 * 16 * P->KpA * 2);
     const size_t h = take((size_t)2 * 16 * P->KpH * 2);
     const size_t ss = take((size_t)2 * 16 * 16 * 4);   // sums of squares of the XCD's strips: [2][strips of an XCD <= 16][16 rows]
-    if (p) { p->o_a = a; p->o_q = q; p->o_o = o; p->o_x2 = x2; p->o_h = h; p->o_ss = ss; }
+    if (p) { p->o_a = a; p->o_q = q; p->o_kv = kv; p->o_o = o; p->o_x2 = x2; p->o_h = h; p->o_ss = ss; }
     return at;
 }
 
