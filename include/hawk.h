@@ -390,6 +390,36 @@ int hawk_spec_pool(const void* cache, int IW, int IH, int VSD, int V_s, const in
 int hawk_sample_rows(const float* logits, const int32_t* skip, const float* u, int rows, int n, float temperature,
                      int top_k, int32_t* out_token, void* stream);
 
+/* The whole scheme over one image as one call (Method, overview figure and "Sampling and Verification"):
+ * prefill; then, per pass: the dual-direction heads on the hidden states of the rows committed by the
+ * pass before (hawk_spatial_heads; heads 0..HD-1 horizontal - head j for position T + j + 1 -, heads
+ * HD..HD+VSD-1 vertical - depth 1..VSD), their vertical predictions into the speculation cache, the
+ * sampling pools of the HD positions ahead (cached vertical predictions in ascending depth, then the
+ * last row's horizontal proposal), one candidate per pool member (hawk_sample_rows), the target pass
+ * over the candidate tree with its walk (hawk_verify_tree), commit of the accepted candidates and the
+ * extra token.  When fewer positions are left than the widest tree has rows (1 + m + ... + m^HD, m = VSD
+ * + 1), ordinary steps with one draft token of the context's own draft head finish the image.
+ * One prompt (a context created for more can be used), no guidance (HAWK_EINVAL for a context created
+ * with it); the context's k_max + 1 must be
+ * at least the widest tree's rows; HD in 1..8, VSD in 0..7.
+ * cond (host) [n_cond][d_model]; W_heads (DEVICE) [HD + VSD][d][d] bf16, W_out (DEVICE) [V_s][d] bf16 as for
+ * hawk_spatial_heads; workspace (DEVICE, 256-byte aligned) of hawk_generate_spatial_workspace_bytes(cfg,
+ * grid_w, HD, VSD) bytes (0: bad arguments), which holds the speculation cache and every intermediate.
+ * Uniforms come from hawk_generate's counter-based generator with prompt 0 and step = pass number
+ * (from 1; the ordinary steps at the end go on counting): slot 8 j + i draws the candidate of member i of
+ * the pool at depth j + 1, slot 64 + 8 j + i is its acceptance test, slot 128 + j the draw after a
+ * rejection at depth j + 1 (j = HD: the extra token after HD acceptances); step 0 slot 128 samples token
+ * 0; an ordinary step uses slots 0, 64, 128 as in hawk_generate.
+ * out_grid (host) [grid_h * grid_w] vocabulary ids; out_stats (host, may be NULL) [4]: tree passes,
+ * candidates accepted in them, ordinary steps at the end, tokens.  The call synchronises once per pass
+ * (the candidates and the walk's result come back to the host, which lays out the next pass).
+ * Returns HAWK_OK or the first error of a step (HAWK_EINVAL, HAWK_ENOMEM for a workspace too small,
+ * HAWK_ESTATE before hawk_load, HAWK_EDEVICE). */
+size_t hawk_generate_spatial_workspace_bytes(const hawk_config* cfg, int grid_w, int HD, int VSD);
+int hawk_generate_spatial(hawk_ctx* ctx, const float* cond, int n_cond, int grid_h, int grid_w, float temperature, int top_k,
+                          const void* W_heads, const void* W_out, int HD, int VSD, uint64_t seed, void* workspace,
+                          size_t workspace_bytes, int32_t* out_grid, int64_t* out_stats);
+
 #ifdef __cplusplus
 }
 #endif

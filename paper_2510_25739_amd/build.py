@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhawk.so")
-SOURCES = ["api.hip", "generic.hip", "gemm.hip", "sampling.hip", "spatial.hip", "stream.hip", "tree.hip", "xcd.hip"]
+SOURCES = ["api.hip", "generic.hip", "gemm.hip", "sampling.hip", "spatial.hip", "scheme.hip", "stream.hip", "tree.hip", "xcd.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-function",
          # packed-fp32 instructions are kept out of the generated code on purpose

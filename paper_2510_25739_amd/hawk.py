@@ -98,6 +98,10 @@ EXPORTS = {
                                  C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hawk_sample_rows": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_int,
                                    C.c_void_p, C.c_void_p]),
+    "hawk_generate_spatial_workspace_bytes": (C.c_size_t, [C.c_void_p, C.c_int, C.c_int, C.c_int]),
+    "hawk_generate_spatial": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_float, C.c_int, C.c_void_p,
+                                        C.c_void_p, C.c_int, C.c_int, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p,
+                                        C.c_void_p]),
 }
 
 
@@ -431,6 +435,31 @@ class Hawk:
         self._chk(self._L.hawk_verify_tree(self._h, D, _p(md), _p(cand), C.c_void_p(q_logits.data_ptr()), _p(ua), _p(uf),
                                            _p(na), _p(toks)), "hawk_verify_tree")
         return na, toks
+
+    def generate_spatial(self, cond, grid_h, grid_w, temperature, top_k, W_heads, W_out, HD, VSD, seed):
+        """hawk_generate_spatial: the whole drafting and verification scheme over one image.  cond [1, n_cond, d]
+        (host); W_heads [HD + VSD, d, d], W_out [V_s, d]: contiguous device bf16 tensors.  Returns (grid [1, N],
+        dict(passes, accepted, tail_steps, tokens))."""
+        torch = self._torch
+        cond = _f32(cond)
+        self.batch, self.n_img = 1, grid_h * grid_w
+        d = self.cfg.d_model
+        if not (W_heads.is_cuda and W_heads.is_contiguous() and W_heads.dtype == torch.bfloat16
+                and tuple(W_heads.shape) == (HD + VSD, d, d) and W_out.is_cuda and W_out.is_contiguous()
+                and W_out.dtype == torch.bfloat16 and tuple(W_out.shape) == (self.v_s, d)):
+            raise HawkError(-1, "hawk_generate_spatial", "head weights must be contiguous device bf16 tensors [HD + VSD, d, d] and [V_s, d]")
+        nbytes = int(self._L.hawk_generate_spatial_workspace_bytes(C.byref(self.cfg), grid_w, HD, VSD))
+        if nbytes == 0:
+            raise HawkError(-1, "hawk_generate_spatial_workspace_bytes", "bad arguments")
+        ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=W_heads.device)
+        base = (ws.data_ptr() + 255) & ~255
+        grid = np.zeros((1, self.n_img), dtype=np.int32)
+        stats = np.zeros(4, dtype=np.int64)
+        self._chk(self._L.hawk_generate_spatial(self._h, _p(cond), cond.shape[1], grid_h, grid_w, float(temperature), int(top_k),
+                                                C.c_void_p(W_heads.data_ptr()), C.c_void_p(W_out.data_ptr()), HD, VSD,
+                                                C.c_uint64(seed), C.c_void_p(base), nbytes, _p(grid), _p(stats)),
+                  "hawk_generate_spatial")
+        return grid, dict(passes=int(stats[0]), accepted=int(stats[1]), tail_steps=int(stats[2]), tokens=int(stats[3]))
 
     def tree_path(self):
         out = np.zeros((self.batch, 8), dtype=np.int32)

@@ -72,7 +72,22 @@ def bench_scheme(H, s, blob, cond, HD=2, VSD=2):
     Wh = (torch.randn(HD + VSD, s.d_model, s.d_model, device="cuda:0", generator=g) * 0.02).to(torch.bfloat16)
     Wo = (torch.randn(s.v_s, s.d_model, device="cuda:0", generator=g) * 0.04).to(torch.bfloat16)
     ref, _ = hk.generate(cond[:1], None, s.grid_h, s.grid_w, 0, 0.0, s.top_k, 1.0, 1)
+    # the same loop inside the library (hawk_generate_spatial): one call per image, prefill included
+    hk.generate_spatial(cond[:1], s.grid_h, s.grid_w, s.temperature, s.top_k, Wh, Wo, HD, VSD, 1)   # warm-up
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    _, st = hk.generate_spatial(cond[:1], s.grid_h, s.grid_w, s.temperature, s.top_k, Wh, Wo, HD, VSD, 2)
+    dt = time.perf_counter() - t0
+    library = {"passes": st["passes"], "accepted": st["accepted"], "tail_steps": st["tail_steps"], "tokens": st["tokens"],
+               "ms_per_image_with_prefill": dt * 1e3, "tokens_per_s_with_prefill": st["tokens"] / dt}
+    t0 = time.perf_counter()
+    hk.prefill(cond[:1], None, s.grid_h, s.grid_w, s.temperature, s.top_k, 1.0, [0.5])
+    hk.synchronize()
+    t_prefill = time.perf_counter() - t0
+    library["ms_per_pass"] = (dt - t_prefill) * 1e3 / max(st["passes"] + st["tail_steps"], 1)
+    library["tokens_per_s"] = (st["tokens"] - 1) / (dt - t_prefill)
     out = {"config": f"{s.name}: HD={HD}, VSD={VSD}, trees up to {max_nodes} rows, one prompt, no guidance, driven from Python",
+           "library_loop_random_heads": library,
            "random_heads": decode_image(H, hk, s1, cond[:1], Wh, Wo, HD, VSD, s.temperature, 1),
            "perfect_horizontal_greedy": decode_image(H, hk, s1, cond[:1], Wh, Wo, HD, VSD, 0.0, 2, reference=ref)}
     same = bool(np.array_equal(hk.grid(), ref))

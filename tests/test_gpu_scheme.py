@@ -92,3 +92,88 @@ def test_whole_scheme_greedy_image(H, perfect_horizontal):
     print(f"{steps} tree steps, accepted per step: histogram {np.bincount(accepted, minlength=HD + 1)}")
     if perfect_horizontal:
         assert min(accepted) == HD          # every step walks to full depth: 3 tokens per pass
+
+
+# ----------------------------------------------------------------------------- the loop inside the library
+
+def heads_for(s, HD, VSD, seed=3):
+    import torch
+    _, wh, wo = synth.make_spatial_heads(seed, 1, HD + VSD, s.d_model, s.v_s)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    return (dev(wh.view(np.int16)).view(torch.bfloat16), dev(wo.view(np.int16)).view(torch.bfloat16),
+            synth.bf16_bits_to_f32(wh), synth.bf16_bits_to_f32(wo))
+
+
+@pytest.mark.parametrize("HD,VSD,grid", [(2, 2, (8, 8)), (1, 1, (4, 6)), (3, 1, (6, 5)), (2, 0, (4, 6))])
+def test_library_loop_fp32_images_equal_the_oracle_loop(H, HD, VSD, grid):
+    # hawk_generate_spatial against oracle.scheme.generate_spatial on the fp32 configuration, sampled
+    # (temperature 1, top-k of the configuration) with the same counter-based uniforms: identical images and
+    # pass statistics.  (The heads' logits differ by ~2e-5 between the two sides - fp32 accumulation against
+    # fp64 -, so a draw or an acceptance test within that distance of a boundary could differ; none does for
+    # these seeds.)
+    import oracle
+    from oracle import scheme
+    s = synth.CONFIGS[0].replace(grid_h=grid[0], grid_w=grid[1])
+    max_nodes = sum((VSD + 1) ** j for j in range(HD + 1))
+    blob = synth.make_weights(s, seed=0)
+    cond = synth.make_cond(s, seed=2, batch=1)
+    E = synth.blob_tensor(s, blob, "E")
+    Wh_d, Wo_d, Wh, Wo = heads_for(s, HD, VSD)
+    hk = H.Hawk(H.HawkConfig.from_shape(s, batch=1, k_max=max(max_nodes - 1, s.k)))
+    hk.load(blob)
+    orc = oracle.Oracle.from_shape(s, blob, batch=1, k_max=max(max_nodes - 1, s.k))
+    for seed in (11, 12):
+        g_o, st_o = scheme.generate_spatial(orc, E, cond, s.n_cond, s.grid_h, s.grid_w, s.samp_lo, Wh, Wo, HD, VSD,
+                                            s.temperature, s.top_k, seed)
+        g_g, st_g = hk.generate_spatial(cond, s.grid_h, s.grid_w, s.temperature, s.top_k, Wh_d, Wo_d, HD, VSD, seed)
+        np.testing.assert_array_equal(g_g[0], g_o)
+        assert {k: st_g[k] for k in st_o} == st_o and st_g["tokens"] == s.n_img
+        assert st_g["passes"] > 0
+    hk.close()
+    orc.close()
+
+
+@pytest.mark.parametrize("path", [0, 1])
+def test_library_loop_greedy_image_bf16(H, path):
+    # bf16 configuration 1 at reduced depth: at temperature 0 the library's loop commits the arg-max image,
+    # whatever the heads propose (verification is lossless); path 1 runs the tree rows on the persistent kernel
+    s = synth.CONFIGS[1].replace(n_layers=3, n_cond=24, grid_h=8, grid_w=8)
+    HD, VSD = 2, 2
+    max_nodes = sum((VSD + 1) ** j for j in range(HD + 1))
+    blob = synth.make_weights(s, seed=0)
+    cond = synth.make_cond(s, seed=2, batch=1)
+    Wh_d, Wo_d, _, _ = heads_for(s, HD, VSD)
+    hk = H.Hawk(H.HawkConfig.from_shape(s, batch=1, k_max=max_nodes - 1))
+    hk.load(blob)
+    hk.set_path(path)
+    ref, _ = hk.generate(cond, None, s.grid_h, s.grid_w, 0, 0.0, s.top_k, 1.0, 1)
+    g, st = hk.generate_spatial(cond, s.grid_h, s.grid_w, 0.0, s.top_k, Wh_d, Wo_d, HD, VSD, 5)
+    np.testing.assert_array_equal(g, ref)
+    assert st["passes"] > 0 and 1 + st["passes"] + st["accepted"] <= s.n_img
+    hk.close()
+
+
+def test_library_loop_rejects_what_it_cannot_run(H):
+    s = synth.CONFIGS[0]
+    blob = synth.make_weights(s, seed=0)
+    cond = synth.make_cond(s, seed=2, batch=1)
+    Wh_d, Wo_d, _, _ = heads_for(s, 2, 2)
+    hk = H.Hawk(H.HawkConfig.from_shape(s, batch=1, k_max=s.k))        # room for 5 rows: the 13-row tree does not fit
+    hk.load(blob)
+    with pytest.raises(H.HawkError) as e:
+        hk.generate_spatial(cond, s.grid_h, s.grid_w, 1.0, s.top_k, Wh_d, Wo_d, 2, 2, 1)
+    assert e.value.code == -1
+    hk.close()
+    sg = s.replace(cfg_scale=2.0)
+    hk2 = H.Hawk(H.HawkConfig.from_shape(sg, batch=1, k_max=12))       # a context with guidance
+    hk2.load(blob)
+    with pytest.raises(H.HawkError) as e:
+        hk2.generate_spatial(cond, s.grid_h, s.grid_w, 1.0, s.top_k, Wh_d, Wo_d, 2, 2, 1)
+    assert e.value.code == -1 and "guidance" in str(e.value)
+    hk2.close()
+    L = H.load_library()
+    cfg = H.HawkConfig.from_shape(s, batch=1, k_max=12)
+    import ctypes as C
+    assert L.hawk_generate_spatial_workspace_bytes(C.byref(cfg), s.grid_w, 0, 2) == 0
+    assert L.hawk_generate_spatial_workspace_bytes(C.byref(cfg), s.grid_w, 2, 8) == 0
+    assert L.hawk_generate_spatial_workspace_bytes(C.byref(cfg), s.grid_w, 2, 2) > 0
