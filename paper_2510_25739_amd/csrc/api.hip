@@ -755,11 +755,17 @@ int hawk_verify_tree(hawk_ctx* c, int depth, const int32_t* m_depth, const int32
         const int M = c->S * n_nodes;
         c->presplit_off = 0;
         launch_embed_rows(c, map, M);
-        if (stream_tree_ok(c, n_nodes)) {   // one persistent kernel: all layers and the output projection
+        if (xcd_ok(c, n_nodes - 1)) {       // one persistent kernel, laid out on the XCDs: all layers and the output projection
+            if (launch_verify_xcd(c, n_nodes - 1, map.tree_depth, map.tree_anc) != 0) c->launch_failed = 1;
+            c->last_path = 1;
+            c->last_kernel = 2;
+        } else if (stream_tree_ok(c, n_nodes)) {   // the same with grid barriers
             if (launch_verify_stream_tree(c, n_nodes, map.tree_depth, map.tree_anc) != 0) c->launch_failed = 1;
             c->last_path = 1;
+            c->last_kernel = 1;
         } else {                            // one kernel per operation
             c->last_path = 0;
+            c->last_kernel = 0;
             run_layers(c, map, M);
             launch_rmsnorm(c, c->off.x, c->d, c->w.g_f, c->off.a, M, true);
             launch_gemm(c, c->off.a, c->d, slice_off(c), c->Vs, c->d, c->off.logit_s, c->Vs, M, false, true);

@@ -196,7 +196,8 @@ XcdPlan* xcd_create(hawk_ctx*);           // plans the jobs, uploads tables, cle
 void xcd_destroy(XcdPlan*);
 int xcd_repack(hawk_ctx*);                // after the blob is on the device; 0 = ok
 bool xcd_ok(const hawk_ctx*, int k);      // can a step with k drafts run on it?
-int launch_verify_xcd(hawk_ctx*, int k);  // 0 = enqueued
+int launch_verify_xcd(hawk_ctx*, int k, const int32_t* tree_depth = nullptr,
+                      const unsigned long long* tree_anc = nullptr);   // the k + 1 step rows per sequence, or the k + 1 nodes of a candidate tree (device arrays)
 
 // ---- launchers implemented in sampling.hip ----
 void launch_plan(hawk_ctx*, int k);

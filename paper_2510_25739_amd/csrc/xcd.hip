@@ -91,6 +91,8 @@ struct XP {
     unsigned* err;
     const int32_t* n;
     const int32_t* k_eff;
+    const int32_t* tdepth;      // rows of a candidate tree (null: a chain): depth of node r, and bit a of tanc[r] set iff node a
+    const u64* tanc;            //   is an ancestor of node r; node r sits at the root's position + depth, in cache entry root + r
     int32_t L, d, H, m, Vs, S, B, C, RS, MR, RPJ, Smax, Tmax;
     int32_t KpA, KpO, KpH;      // row strides (elements) of the split planes: d / 8 + 8, widest head group + 8, widest hidden slice + 8
     int32_t lm_rounds;
@@ -229,14 +231,15 @@ __device__ __forceinline__ void stamp(const Ctx& c, unsigned stage, int what) {
             __builtin_amdgcn_s_memrealtime();
 }
 
-struct RowPos { int seq, r, pos; bool valid; };
+struct RowPos { int seq, r, pos, slot; bool valid; };   // pos: rotary position; slot: cache entry
 __device__ __forceinline__ RowPos row_pos(const XP& p, int c) {
     RowPos o;
     o.seq = c / p.RS;
     o.r = c - o.seq * p.RS;
     const int b = o.seq % p.B;
     o.valid = o.r <= p.k_eff[b];
-    o.pos = o.valid ? p.C + p.n[b] - 1 + o.r : 0;
+    o.slot = o.valid ? p.C + p.n[b] - 1 + o.r : 0;
+    o.pos = (o.valid && p.tdepth) ? p.C + p.n[b] - 1 + p.tdepth[o.r] : o.slot;
     return o;
 }
 
@@ -476,7 +479,7 @@ __device__ __forceinline__ IoJobs load_io_jobs(const XP& p, const Ctx& c, int io
     j.sD = entry(X_D)[0]; j.tD = entry(X_D)[1];
     j.sE = entry(X_E)[0]; j.tE = entry(X_E)[1];
     const int col = lane & 15, quad = lane >> 4;
-    j.rp = col < p.MR ? row_pos(p, col) : RowPos{0, 0, 0, false};
+    j.rp = col < p.MR ? row_pos(p, col) : RowPos{0, 0, 0, 0, false};
     j.rot0 = j.rot1 = make_float2(1.f, 0.f);
     if (j.sA >= 0 && col < p.MR) {
         const int o0 = j.sA * 16, seg = o0 / p.d, j0 = o0 - seg * p.d;
@@ -537,7 +540,7 @@ __device__ __forceinline__ void reduce_job(const XP& p, Ctx& c, const IoJobs& jb
                 const unsigned p23 = (unsigned)__builtin_bit_cast(unsigned short, h2) | ((unsigned)__builtin_bit_cast(unsigned short, h3) << 16);
                 if (jb.rp.valid) {
                     _Float16* dst = (seg == 1 ? p.Kc : p.Vc) +
-                                    ((((size_t)layer * p.Smax + jb.rp.seq) * p.H + h) * p.Tmax + jb.rp.pos) * 64 + f0;
+                                    ((((size_t)layer * p.Smax + jb.rp.seq) * p.H + h) * p.Tmax + jb.rp.slot) * 64 + f0;
                     *reinterpret_cast<uint2*>(dst) = make_uint2(p01, p23);
                 }
                 *reinterpret_cast<v4u*>(buf + p.o_kv + ((((size_t)(seg - 1) * 16 + col) * (p.KpO - 8) / 64 + hl) * 16 + f0 / 4) * 16) =
@@ -598,9 +601,9 @@ __device__ __forceinline__ void halves8(v4u raw, float (&f)[8]) {
     }
 }
 
-// One cache position per lane group; row r0 + r of the sequence sees it iff r0 + r >= row_lo.
+// One cache position per lane group; row r0 + r of the sequence sees it iff bit r0 + r of vis is set.
 template <int RPJ>
-__device__ __forceinline__ void attend(const float (&q)[RPJ][8], int r0, v4u kraw, v4u vraw, int row_lo, int ke,
+__device__ __forceinline__ void attend(const float (&q)[RPJ][8], int r0, v4u kraw, v4u vraw, unsigned vis, int ke,
                                        AttnAcc (&A)[RPJ]) {
     float kf[8], vf[8];
     halves8(kraw, kf);
@@ -611,7 +614,7 @@ __device__ __forceinline__ void attend(const float (&q)[RPJ][8], int r0, v4u kra
 #pragma unroll
         for (int e = 0; e < 8; ++e) sc += q[r][e] * kf[e];
         sc = sum8(sc);
-        if (r0 + r >= row_lo && r0 + r <= ke) {
+        if (((vis >> (r0 + r)) & 1u) && r0 + r <= ke) {
             const float mn = fmaxf(A[r].mx, sc);
             const float corr = __expf(A[r].mx - mn), pw = __expf(sc - mn);
             A[r].den = A[r].den * corr + pw;
@@ -788,18 +791,30 @@ __device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, c
             const int pos0 = rnd * kNIT * (kNIO * 8) + io * 8 + pg;
             attend_round<RPJ>(q, r0, kk, vv, pos0, kNIO * 8, kv0, ke, A);
         };
-        // rows appended by this launch: stored by this XCD's reduce jobs (their flags have been seen);
-        // requested now, used after the cached positions
-        const bool fresh_row = io == 0 && pg <= ke && pg < RS;
-        v4u kn = (v4u){0u, 0u, 0u, 0u}, vn = (v4u){0u, 0u, 0u, 0u};
-        if (io == 0) {   // polled as tagged fp16 pairs: lane group pg = appended row, lane dg = features 8 dg .. 8 dg + 7
+        // Rows appended by this launch (up to 16: lane group pg takes rows pg and pg + 8), polled as the tagged
+        // fp16 pairs this XCD's reduce jobs write.  Who sees them: in a chain row r sees row a iff a <= r, in a
+        // candidate tree iff a is r itself or an ancestor.  Row pg is requested now and used after the cached
+        // positions; row pg + 8 (trees of more than 8 nodes only) is fetched behind them.
+        auto seen_by = [&](int a) {
+            unsigned vis = 0u;
+            if (io == 0 && a <= ke && a < RS) {
+#pragma unroll
+                for (int r = 0; r < RPJ; ++r) {
+                    const int row = r0 + r;
+                    const bool sees = p.tanc ? (row == a || ((p.tanc[min(row, 15)] >> a) & 1ull)) : a <= row;
+                    if (row < RS && sees) vis |= 1u << row;
+                }
+            }
+            return vis;
+        };
+        auto fetch_row = [&](int a, unsigned& vis, v4u& kn, v4u& vn) {   // lane dg = features 8 dg .. 8 dg + 7
             const rsrc_t kvr = make_rsrc(p.xbuf);
             const unsigned hw = (unsigned)(p.KpO - 8) / 64u;   // heads a row of the region has room for
             const unsigned atk = (unsigned)(((size_t)c.x * kRing + (layer & 1)) * p.xcd_bytes + p.o_kv) +
-                                 ((((unsigned)(seq * RS + pg)) * hw + (unsigned)(h - p.hd0[c.x])) * 16u + 2u * dg) * 16u;
+                                 ((((unsigned)(seq * RS + a)) * hw + (unsigned)(h - p.hd0[c.x])) * 16u + 2u * dg) * 16u;
             const unsigned atv = atk + 16u * hw * 16u * 16u;
             v4u k0, k1, v0, v1;
-            bool ok = !fresh_row || c.dead;
+            bool ok = vis == 0u || c.dead;   // rows nobody of this job sees are not waited for
             for (unsigned spins = 0; spins < kSpinLimit && !__all(ok); ++spins) {
                 if (!ok) {
                     k0 = ld_16(kvr, atk); k1 = ld_16(kvr, atk + 16u);
@@ -810,8 +825,11 @@ __device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, c
                 }
                 if ((spins & 255u) == 255u && ld_u32(c.err) != 0u) break;
             }
-            if (!__all(ok)) give_up(c);
-        }
+            if (!__all(ok)) { give_up(c); vis = 0u; }
+        };
+        v4u kn = (v4u){0u, 0u, 0u, 0u}, vn = (v4u){0u, 0u, 0u, 0u};
+        unsigned vis0 = seen_by(pg);
+        if (io == 0) fetch_row(pg, vis0, kn, vn);
         for (int rnd = 0; rnd < nrounds; rnd += 3) {
             run(ka, va, rnd);
             if (rnd + 3 < nrounds) fetch(ka, va, rnd + 3);
@@ -820,7 +838,12 @@ __device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, c
             if (rnd + 2 < nrounds) run(kc, vc, rnd + 2);
             if (rnd + 5 < nrounds) fetch(kc, vc, rnd + 5);
         }
-        if (fresh_row) attend<RPJ>(q, r0, kn, vn, pg, ke, A);   // row r sees appended row pg iff pg <= r
+        if (vis0) attend<RPJ>(q, r0, kn, vn, vis0, ke, A);
+        if (RS > 8) {   // (uniform over the launch)
+            unsigned vis1 = seen_by(pg + 8);
+            if (io == 0) fetch_row(pg + 8, vis1, kn, vn);
+            if (vis1) attend<RPJ>(q, r0, kn, vn, vis1, ke, A);
+        }
 #pragma unroll
         for (int r = 0; r < RPJ; ++r) {
 #pragma unroll
@@ -1346,13 +1369,13 @@ bool xcd_ok(const hawk_ctx* c, int k) {
     const XcdPlan* P = c->xplan;
     if (!P || !P->ok || c->path != 1 || !stream_has_err_word(c)) return false;   // (error word and rotary table: the streaming plan's)
     const int RS = k + 1, MR = c->S * RS;
-    if (MR > 16 || RS > 8) return false;
+    if (MR > 16) return false;
     for (int x = 0; x < kXcd; ++x)
         if ((P->hd0[x + 1] - P->hd0[x]) * c->S * ((RS + 1) / 2) > kPer) return false;
     return true;
 }
 
-int launch_verify_xcd(hawk_ctx* c, int k) {
+int launch_verify_xcd(hawk_ctx* c, int k, const int32_t* tree_depth, const unsigned long long* tree_anc) {
     XcdPlan* P = c->xplan;
     XP p;
     memset(&p, 0, sizeof p);
@@ -1388,6 +1411,7 @@ int launch_verify_xcd(hawk_ctx* c, int k) {
     p.logit_s = wsp<float>(c, c->off.logit_s);
     p.err = wsp<unsigned>(c, c->soff.err);
     p.n = wsp<int32_t>(c, c->off.n); p.k_eff = wsp<int32_t>(c, c->off.k_eff);
+    p.tdepth = tree_depth; p.tanc = reinterpret_cast<const u64*>(tree_anc);   // rows of a candidate tree (null: a chain)
     p.L = c->L; p.d = c->d; p.H = c->H; p.m = c->m; p.Vs = c->Vs; p.S = c->S; p.B = c->B; p.C = c->C;
     p.RS = RS; p.MR = c->S * RS; p.RPJ = RPJ; p.Smax = c->Smax; p.Tmax = c->Tmax;
     p.KpA = P->KpA; p.KpO = P->KpO; p.KpH = P->KpH;
