@@ -76,7 +76,7 @@ struct XP {
     const int16_t* rtab;        // [kind][8][32][kNIO][2]: strip (-1: none) and flag slot of (XCD, unit, IO wave)
     const int16_t* atab;        // [8][32][4]: sequence, head, row group (-1: none), flag slot
     int32_t njobs[F_NF][kXcd];  // flag slots a consumer of that stage waits for
-    u64* part[X_NK];            // partial sums: [ring][8 source XCDs][strip][16 rows][4][4] {value, tag}
+    u64* part[X_NK];            // partial sums: [ring][8 source XCDs][strip][16 rows][16 features] fp32, parity in the lowest bit
     u64* pss[X_NK];             // per-XCD sums of squares that ride along (products after a norm): [ring][8][unit][wave][round][16 rows] {value, tag}
     uint8_t* xbuf;              // per-XCD buffers: [8][ring][xcd_bytes]
     u64 xcd_bytes, o_a, o_q, o_kv, o_o, o_x2, o_h, o_ss;   // regions of one XCD buffer (bytes)
@@ -184,6 +184,9 @@ __device__ __forceinline__ f32x4 times_gain(f32x4 x, uint2 g) {
 struct Ctx {
     unsigned x, j;        // XCD and unit of the workgroup
     unsigned epoch0;      // tags of this launch start behind it
+    unsigned par;         // partial sums: bit r of the low / high half = parity of the writes so far to row r's words of the
+                          //   even / odd layers' areas; bits 0..15 of par_lm the same for the output projection's
+    unsigned par_lm;
     bool dead;
     unsigned* err;
     u64* dbg;             // time stamps of two workgroups (null: off)
@@ -192,6 +195,16 @@ struct Ctx {
 // Tag of (layer, stage); the prologue counts as stage E of layer -1.
 __device__ __forceinline__ unsigned tag_of(const Ctx& c, int layer, int flag) {
     return c.epoch0 + 1u + 5u * (unsigned)(layer + 1) + (unsigned)flag;
+}
+
+// Partial sums carry no tag word: the lowest mantissa bit of every value is the parity of the number of
+// times its word has been written (the word is rewritten every second layer, by every launch, for the rows
+// in flight; the host keeps the parities per row between launches).  A reader that finds the expected
+// parity in all four values of a 16-byte word has the stage's values; it clears the bit before use, so the
+// sums do not depend on it.  Half the bytes of {value, tag} pairs cross between the XCDs.
+__device__ __forceinline__ unsigned parity_bit(const Ctx& c, int kind, int layer, int row) {
+    const unsigned base = kind == X_LM ? c.par_lm >> row : c.par >> (16 * (layer & 1) + row);
+    return (base ^ (kind == X_LM ? 0u : (unsigned)(layer >> 1)) ^ 1u) & 1u;
 }
 
 __device__ __forceinline__ void give_up(Ctx& c) {
@@ -296,7 +309,7 @@ __device__ __forceinline__ void issue_paced(const XP& p, const GJob& g, u64 laye
 template <int NSW, int KTM>
 __device__ __forceinline__ void mfma_store(const XP& p, int kind, const GJob& g, const Ctx& c, int lane, const v4u (&w)[NSW * KTM],
                                            const uint16_t* act_hi, const uint16_t* act_lo, const float* ssrow, int Kp, int ring,
-                                           unsigned tag, int round = 0, unsigned dbg_stage = 0) {
+                                           unsigned tag, unsigned pbit, int round = 0, unsigned dbg_stage = 0) {
     const int s0 = g.s0 + round * NSW, ns = min(max(g.ns - round * NSW, 0), NSW);
     const int col = lane & 15, kg = lane >> 4;
     const size_t at = (size_t)(col < p.MR ? col : 0) * Kp + kg * 8;
@@ -304,17 +317,12 @@ __device__ __forceinline__ void mfma_store(const XP& p, int kind, const GJob& g,
                                                     // rides along, once per wave and round (known before the products: it goes first)
         st_tagged(p.pss[kind] + ((((size_t)ring * kXcd + c.x) * kPer + c.j) * kCW + (threadIdx.x >> 6)) * 32 + (round & 1) * 16 + col,
                   ssrow[col], tag);
-    // One 128-byte line per (strip, row): the first 64 bytes hold the {value, tag} pairs of features 4q, 4q + 1
-    // (q = lane / 16), the second 64 those of features 4q + 2, 4q + 3.  Every 8-byte pair is written whole,
-    // so a reader never sees a value without its tag.  With at most 8 rows the idle lanes of columns 8..15
-    // carry the second halves of columns 0..7 (one cross-lane move) and one store instruction per strip
-    // writes whole lines.  A write-through store occupies the wave for ~0.3 us, several times the products
-    // of a strip: strip by strip, so that a strip's store goes out while the next one is multiplied.
+    // 64 bytes per (strip, row): lane (row, q) writes its four features 4q .. 4q + 3 as one 16-byte word, each
+    // value with the word's parity in its lowest bit (see parity_bit); one store instruction per strip.  A
+    // write-through store occupies the wave for ~0.3 us, several times the products of a strip: strip by
+    // strip, so that a strip's store goes out while the next one is multiplied.
     const rsrc_t out = make_rsrc(p.part[kind]);
-    const bool packed = p.MR <= 8;
-    const int row = packed ? (col & 7) : col;
-    const bool second = packed && col >= 8;
-    const unsigned at8 = (unsigned)((((size_t)ring * kXcd + c.x) * p.nstrips[kind] + s0) * 16 + row) * 128u + kg * 16u + (second ? 64u : 0u);
+    const unsigned at8 = (unsigned)((((size_t)ring * kXcd + c.x) * p.nstrips[kind] + s0) * 16 + col) * 64u + kg * 16u;
 #pragma unroll
     for (int si = 0; si < NSW; ++si) {
         f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f}, acl = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -331,16 +339,9 @@ __device__ __forceinline__ void mfma_store(const XP& p, int kind, const GJob& g,
             stamp(c, dbg_stage, 3);
         }
         const f32x4 v = acc + acl;
-        const float v2 = lane_xor8(v[2]), v3 = lane_xor8(v[3]);   // columns 8..15 receive columns 0..7
-        if (si < ns && row < p.MR) {
-            if (packed) {
-                st_16(out, at8 + si * 2048u, second ? (v4u){__float_as_uint(v2), tag, __float_as_uint(v3), tag}
-                                                    : (v4u){__float_as_uint(v[0]), tag, __float_as_uint(v[1]), tag});
-            } else {
-                st_16(out, at8 + si * 2048u, (v4u){__float_as_uint(v[0]), tag, __float_as_uint(v[1]), tag});
-                st_16(out, at8 + si * 2048u + 64u, (v4u){__float_as_uint(v[2]), tag, __float_as_uint(v[3]), tag});
-            }
-        }
+        if (si < ns && col < p.MR)
+            st_16(out, at8 + si * 1024u, (v4u){(__float_as_uint(v[0]) & ~1u) | pbit, (__float_as_uint(v[1]) & ~1u) | pbit,
+                                               (__float_as_uint(v[2]) & ~1u) | pbit, (__float_as_uint(v[3]) & ~1u) | pbit});
     }
 }
 
@@ -371,8 +372,8 @@ __device__ __forceinline__ void stage_copy(rsrc_t r, unsigned src, int MR, int K
 // of the strip = output features, column lane % 16 = activation row), added in XCD order.  scaled: the
 // product follows a norm; the XCDs' shares of every row's sum of squares came with their partial sums,
 // and *rn receives 1/rms of the lane's row.
-__device__ __forceinline__ f32x4 gather_partials(const XP& p, Ctx& c, int kind, int s, int prod, int ring, unsigned tag, int lane,
-                                                 bool scaled, float* rn, unsigned dbg_stage = 1000u) {
+__device__ __forceinline__ f32x4 gather_partials(const XP& p, Ctx& c, int kind, int s, int prod, int ring, unsigned tag, unsigned pbit,
+                                                 int lane, bool scaled, float* rn, unsigned dbg_stage = 1000u) {
     const int col = lane & 15, quad = lane >> 4;
     const bool live = col < p.MR;
     f32x4 val[kXcd];
@@ -386,8 +387,9 @@ __device__ __forceinline__ f32x4 gather_partials(const XP& p, Ctx& c, int kind, 
     const int nstr = kind == X_A ? p.nstrips[X_A] : kind == X_C ? p.nstrips[X_C] : kind == X_D ? p.nstrips[X_D]
                                                                                : kind == X_E ? p.nstrips[X_E] : p.nstrips[X_LM];
     const rsrc_t in = make_rsrc(part);
-    const unsigned at8 = (unsigned)(((size_t)ring * kXcd * nstr + s) * 16 + col) * 128u + quad * 16u;
-    const unsigned xstride = (unsigned)nstr * 2048u;
+    const unsigned at8 = (unsigned)(((size_t)ring * kXcd * nstr + s) * 16 + col) * 64u + quad * 16u;
+    const unsigned xstride = (unsigned)nstr * 1024u;
+    const unsigned pb = pbit * 0x1u;
     // sums of squares: the lane's quarter looks at XCDs 2 * quad and 2 * quad + 1; `prod` = the strip's
     // producer (unit * kCW + wave) * 2 + round, the same on every XCD
     const u64* pss = pssb + (((size_t)ring * kXcd + 2 * quad) * kPer * kCW * 2 + prod) * 16 + col;
@@ -397,23 +399,20 @@ __device__ __forceinline__ f32x4 gather_partials(const XP& p, Ctx& c, int kind, 
     unsigned nspin = 0;
     for (unsigned spins = 0; spins < kSpinLimit && !ok; ++spins) {
         ++nspin;
-        v4u w[kXcd][2];
+        v4u w[kXcd];
         u64 sw[2] = {0ull, 0ull};
 #pragma unroll
         for (int x = 0; x < kXcd; ++x)
-            if ((need >> x) & 1u) {
-                w[x][0] = ld_16(in, at8 + x * xstride);
-                w[x][1] = ld_16(in, at8 + x * xstride + 64u);
-            }
+            if ((need >> x) & 1u) w[x] = ld_16(in, at8 + x * xstride);
 #pragma unroll
         for (int i = 0; i < 2; ++i)
             if ((need_ss >> i) & 1u) sw[i] = ld_u64(pss + (size_t)i * kPer * kCW * 2 * 16);
 #pragma unroll
         for (int x = 0; x < kXcd; ++x)
             if ((need >> x) & 1u) {
-                if (w[x][0][1] == tag && w[x][0][3] == tag && w[x][1][1] == tag && w[x][1][3] == tag) {
-                    val[x] = (f32x4){__uint_as_float(w[x][0][0]), __uint_as_float(w[x][0][2]), __uint_as_float(w[x][1][0]),
-                                     __uint_as_float(w[x][1][2])};
+                if (((w[x][0] & w[x][1] & w[x][2] & w[x][3]) & 1u) == pb && ((w[x][0] | w[x][1] | w[x][2] | w[x][3]) & 1u) == pb) {
+                    val[x] = (f32x4){__uint_as_float(w[x][0] & ~1u), __uint_as_float(w[x][1] & ~1u), __uint_as_float(w[x][2] & ~1u),
+                                     __uint_as_float(w[x][3] & ~1u)};
                     need &= ~(1u << x);
                 }
             }
@@ -518,7 +517,8 @@ __device__ __forceinline__ void reduce_job(const XP& p, Ctx& c, const IoJobs& jb
         gain = *reinterpret_cast<const uint2*>(g + s * 16 + 4 * quad);
     }
     float rn = 1.f;
-    f32x4 v = gather_partials(p, c, kind, s, scaled ? p.ptab[p.poff[kind] + s] : 0, ring, tag, lane, scaled, &rn, stage);
+    f32x4 v = gather_partials(p, c, kind, s, scaled ? p.ptab[p.poff[kind] + s] : 0, ring, tag, parity_bit(c, kind, layer, col), lane,
+                              scaled, &rn, stage);
     stamp(c, stage, 4);
     v *= rn;
     stamp(c, stage, 5);
@@ -578,7 +578,7 @@ __device__ __forceinline__ void reduce_logits(const XP& p, Ctx& c, int io, int l
         const int s = ((i * kPer + (int)c.j) * kNIO + io) * kXcd + (int)c.x;
         if (s >= p.nstrips[X_LM]) break;
         float rn = 1.f;
-        const f32x4 v = gather_partials(p, c, X_LM, s, p.ptab[p.poff[X_LM] + s], 0, tag, lane, true, &rn) * rn;
+        const f32x4 v = gather_partials(p, c, X_LM, s, p.ptab[p.poff[X_LM] + s], 0, tag, parity_bit(c, X_LM, 0, col), lane, true, &rn) * rn;
         if (col < p.MR) *reinterpret_cast<f32x4*>(p.logit_s + (size_t)col * p.Vs + s * 16 + 4 * quad) = v;
     }
 }
@@ -913,7 +913,8 @@ __device__ __forceinline__ void compute_stage(const XP& p, const Ctx& c, const G
     lds_barrier();   // the XCD's slice of the stage input is in LDS
     stamp(c, stage, 1);
     const float* ssrow = (KIND == X_C || KIND == X_E) ? nullptr : s.ss0 + (stage & 1u) * 16;
-    mfma_store<NSW, KTM>(p, KIND, g, c, lane, w, act_hi, act_lo, ssrow, Kp, ring, tag, 0, stage);
+    const unsigned pbit = parity_bit(c, KIND, layer, lane & 15);
+    mfma_store<NSW, KTM>(p, KIND, g, c, lane, w, act_hi, act_lo, ssrow, Kp, ring, tag, pbit, 0, stage);
     stamp(c, stage, 2);
     // Loads and stores share one counter and complete out of order among each other: with stores
     // pending, "wait for the first n loads" is not expressible and every wait becomes "wait for
@@ -929,7 +930,7 @@ __device__ __forceinline__ void compute_stage(const XP& p, const Ctx& c, const G
     if (KIND == X_LM) {   // further rounds of the output projection: same staged input
         for (int r = 1; r < p.lm_rounds; ++r) {
             issue_tiles<NSW, KTM>(p, g, 0, lane, w, r);
-            mfma_store<NSW, KTM>(p, KIND, g, c, lane, w, act_hi, act_lo, ssrow, Kp, ring, tag, r);
+            mfma_store<NSW, KTM>(p, KIND, g, c, lane, w, act_hi, act_lo, ssrow, Kp, ring, tag, pbit, r);
         }
     }
 }
@@ -1040,7 +1041,7 @@ __device__ __forceinline__ void io_main(const XP& p, Ctx& c, const Lds& s) {
 }
 
 template <int NA, int KA, int NC, int KC, int ND, int KD, int NE, int KE, int NL, int RPJ>
-__global__ __launch_bounds__(kThreads, 1) void verify_xcd_kernel(const XP* __restrict__ params, unsigned epoch0, u64* dbg) {
+__global__ __launch_bounds__(kThreads, 1) void verify_xcd_kernel(const XP* __restrict__ params, unsigned epoch0, unsigned par, unsigned par_lm, u64* dbg) {
     // The parameter block lives in device memory (written when the step shape changes): tables in it are
     // indexed with run-time values, which a by-value kernel argument would answer with a private copy.
     const XP& p = *params;
@@ -1056,7 +1057,7 @@ __global__ __launch_bounds__(kThreads, 1) void verify_xcd_kernel(const XP* __res
     if (threadIdx.x == 0) *s.join = 0u;
     __syncthreads();
     Ctx c;
-    c.x = blockIdx.x % kXcd; c.j = blockIdx.x / kXcd; c.epoch0 = epoch0; c.dead = false; c.err = p.err; c.dbg = dbg;
+    c.x = blockIdx.x % kXcd; c.j = blockIdx.x / kXcd; c.epoch0 = epoch0; c.par = par; c.par_lm = par_lm; c.dead = false; c.err = p.err; c.dbg = dbg;
     if (xcc_id() != c.x) give_up(c);   // the dispatch order this layout relies on does not hold: fail, never hang
     // The two kinds of waves run separate code (and cross the same workgroup barriers), so that neither
     // carries the other's registers: compute waves the weights in flight, IO waves the attention's keys
@@ -1094,6 +1095,7 @@ struct XcdPlan {
     int NSW[X_NK];                 // strips per compute wave and round the plan needs
     int lm_rounds;
     int KpA, KpO, KpH;
+    unsigned par, par_lm;          // parities of the partial-sum words (see parity_bit), per row
     std::vector<int16_t> gtab, rtab, ptab;
     int poff[X_NK];
     std::vector<uint8_t> params;   // the parameter block as last uploaded
@@ -1125,6 +1127,7 @@ void split_ranges(int n, int parts, bool extra_last, std::vector<int>& start) {
 void build_xcd_plan(const hawk_ctx* c, XcdPlan* P) {
     P->ok = xcd_shape_ok(c);
     P->epoch = 0;
+    P->par = P->par_lm = 0;   // the areas are cleared below: parity 0 everywhere
     if (!P->ok) return;
     const int d = c->d, m = c->m, H = c->H;
     P->nstrips[X_A] = 3 * d / 16; P->nstrips[X_C] = d / 16; P->nstrips[X_D] = 2 * m / 16; P->nstrips[X_E] = d / 16;
@@ -1285,7 +1288,7 @@ size_t xcd_workspace(const hawk_ctx* c, size_t base, XcdOffsets* o) {
     o->atab = take((size_t)kXcd * kPer * 4 * 2);
     o->xp = take(4096);
     for (int k = 0; k < X_NK; ++k)
-        o->part[k] = take((size_t)(k == X_LM ? 1 : kRing) * kXcd * P.nstrips[k] * 16 * 16 * 8);
+        o->part[k] = take((size_t)(k == X_LM ? 1 : kRing) * kXcd * P.nstrips[k] * 16 * 16 * 4);
     for (int k = 0; k < X_NK; ++k)
         o->pss[k] = (k == X_C || k == X_E) ? 0 : take((size_t)kRing * kXcd * kPer * kCW * 2 * 16 * 8);
     o->xcd_bytes = xcd_buf_layout(&P, nullptr);
@@ -1315,7 +1318,7 @@ XcdPlan* xcd_create(hawk_ctx* c) {
     good = good && hipMemsetAsync(c->ws + o.zero, 0, 1024, c->stream) == hipSuccess;
     good = good && hipMemsetAsync(c->ws + o.lflag, 0, (size_t)kXcd * F_NF * kMaxJobs * 4, c->stream) == hipSuccess;
     for (int k = 0; k < X_NK; ++k)
-        good = good && hipMemsetAsync(c->ws + o.part[k], 0, (size_t)(k == X_LM ? 1 : kRing) * kXcd * P->nstrips[k] * 16 * 16 * 8,
+        good = good && hipMemsetAsync(c->ws + o.part[k], 0, (size_t)(k == X_LM ? 1 : kRing) * kXcd * P->nstrips[k] * 16 * 16 * 4,
                                       c->stream) == hipSuccess;
     for (int k = 0; k < X_NK; ++k)
         if (k != X_C && k != X_E)
@@ -1443,12 +1446,20 @@ int launch_verify_xcd(hawk_ctx* c, int k, const int32_t* tree_depth, const unsig
     const XP* dev_params = wsp<XP>(c, o.xp);
     unsigned epoch0 = P->epoch;
     u64* dbg = c->stream_dbg ? wsp<u64>(c, o.dbg) : nullptr;
-    void* args[] = {&dev_params, &epoch0, &dbg};
+    unsigned par = P->par, par_lm = P->par_lm;
+    void* args[] = {&dev_params, &epoch0, &par, &par_lm, &dbg};
     // one workgroup per compute unit: the grid equals the unit count and a workgroup's LDS request
     // (padded to more than half a unit's LDS) keeps a second one off the unit
     const size_t lds_req = std::max(lds, (size_t)84 * 1024);
     if (hipLaunchKernel(kern, dim3(kNWG), dim3(kThreads), args, lds_req, c->stream) != hipSuccess) return -1;
     P->epoch += 5u * (unsigned)(c->L + 2) + 8u;
+    // parities of the partial-sum words after this launch: rows in flight were written once per layer into the
+    // layer parity's area, once into the output projection's
+    const int MR = c->S * RS;
+    const unsigned rows = MR >= 16 ? 0xFFFFu : (1u << MR) - 1u;
+    if (((c->L + 1) / 2) & 1) P->par ^= rows;
+    if ((c->L / 2) & 1) P->par ^= rows << 16;
+    P->par_lm ^= rows;
     return 0;
 }
 
