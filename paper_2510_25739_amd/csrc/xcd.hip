@@ -54,7 +54,7 @@ constexpr int kXcd = 8, kPer = kNWG / kXcd;      // workgroup i runs on XCD i % 
 constexpr unsigned kSpinLimit = 1u << 20;
 constexpr int kPS = 68;                          // floats per attention partial row: 64 outputs, max, sum, pad
 constexpr int kNIT = 4;                          // cache positions per lane group and register buffer
-constexpr int kPaceGap = 0, kPaceTiles = 4;   // weight requests go out four tiles per wave at a time (see issue_paced)
+constexpr int kPaceGap = 0, kPaceTiles = 6;   // weight requests go out six tiles per wave at a time (see issue_paced)
 constexpr int kRing = 2;                         // partial-sum areas and XCD buffers alternate between layers
 constexpr int kMaxJobs = 64;                     // reduce / attention jobs of one XCD and stage that others wait for
 
