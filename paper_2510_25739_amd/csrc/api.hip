@@ -155,11 +155,6 @@ bool derive(const hawk_config* g, hawk_ctx* c) {
     o.out_na = take(B * 4); o.out_tok = take(B * ks * 4); o.inv_freq = take((size_t)(hd / 2) * 8);
     o.replay = take(B * c->Nmax * 4); o.cond = take(S * (size_t)g->max_cond * d * 4);
     o.tree = take(TreeArea(B).bytes);
-    // attention of the step rows with the cached positions cut over several workgroups: their partial
-    // rows ([sequence][head][part][8 rows][hd + 2] fp32) and one arrival counter per (sequence, head)
-    o.attn_part = g->dtype == HAWK_BF16 ? take(S * (size_t)c->H * kAttnSplitMax * 8 * (hd + 2) * 4) : 0;
-    o.attn_cnt = g->dtype == HAWK_BF16 ? take(S * (size_t)c->H * 4) : 0;
-    o.rope_tab = g->dtype == HAWK_BF16 ? take((size_t)c->Tmax * (hd / 2) * 8) : 0;   // (cos, sin) of position x pair, fp32
     const size_t widest = 3 * d > m ? 3 * d : m;
     c->split_bytes = g->dtype == HAWK_BF16 ? M * widest * 4 : 0;
     o.split = c->split_bytes ? take(c->split_bytes) : 0;
@@ -296,7 +291,6 @@ int enqueue_prefill(hawk_ctx* c, const float* cond, const float* uncond, int bat
     c->inv_t = c->greedy ? 1.0f : 1.0f / temperature;
     const size_t per = (size_t)batch * n_cond * c->d * 4;
     HIP_TRY(c, hipMemsetAsync(c->ws + c->off.n, 0, c->off.grid - c->off.n, c->stream));
-    if (c->off.attn_cnt) HIP_TRY(c, hipMemsetAsync(c->ws + c->off.attn_cnt, 0, (size_t)c->Smax * c->H * 4, c->stream));
     HIP_TRY(c, hipMemcpyAsync(c->ws + c->off.cond, cond, per, hipMemcpyHostToDevice, c->stream));
     if (c->cfg.use_cfg)
         HIP_TRY(c, hipMemcpyAsync(c->ws + c->off.cond + per, uncond, per, hipMemcpyHostToDevice, c->stream));
@@ -408,20 +402,6 @@ int hawk_create(const hawk_config* cfg, void* workspace, size_t workspace_bytes,
         hipStreamSynchronize(c->stream) != hipSuccess) {
         hawk_destroy(c);
         return HAWK_EDEVICE;
-    }
-    if (c->off.rope_tab) {   // the rotary factors of every position: cos / sin in double, rounded once
-        std::vector<float> tab((size_t)c->Tmax * (c->hd / 2) * 2);
-        for (int pos = 0; pos < c->Tmax; ++pos)
-            for (int j = 0; j < c->hd / 2; ++j) {
-                const double ang = (double)pos * f[j];
-                tab[((size_t)pos * (c->hd / 2) + j) * 2] = (float)cos(ang);
-                tab[((size_t)pos * (c->hd / 2) + j) * 2 + 1] = (float)sin(ang);
-            }
-        if (hipMemcpyAsync(c->ws + c->off.rope_tab, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, c->stream) != hipSuccess ||
-            hipStreamSynchronize(c->stream) != hipSuccess) {
-            hawk_destroy(c);
-            return HAWK_EDEVICE;
-        }
     }
     c->plan = stream_create(c);
     c->xplan = xcd_create(c);

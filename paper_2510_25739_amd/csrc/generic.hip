@@ -8,8 +8,6 @@
 // One wave computes one output column of a skinny GEMM for up to RT rows, streaming its
 // weight row with 16-byte loads; this is the fallback path and the only path of the
 // fp32 configuration.  The weight-streaming fast path lives in stream.hip.
-#include <algorithm>
-
 #include "hawk_internal.h"
 
 namespace hawk {
@@ -351,9 +349,8 @@ template <int CTRL> __device__ __forceinline__ float dpp_lane(float v) {
 // hd = 64 or 128.
 template <int RM, int NR>
 __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, _Float16* Kc, _Float16* Vc, float* O,
-                                                             RowMap map, const float2* rope_tab, int layer, int d,
-                                                             int hd, int Smax, int Tmax, uint16_t* hi, uint16_t* lo,
-                                                             float* split_part, unsigned* split_cnt) {
+                                                             RowMap map, const double* inv_freq, int layer, int d,
+                                                             int hd, int Smax, int Tmax, uint16_t* hi, uint16_t* lo) {
     extern __shared__ double smem_raw[];
     float* sq = reinterpret_cast<float*>(smem_raw);   // [RM][hd] queries
     float* sc = sq + RM * hd;                         // [Tmax][RM] scores, then weights
@@ -364,7 +361,7 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, _
     const int R0 = s * map.rows_per_seq;
     const RowInfo r0 = row_info(map, R0);
     const int nrows = r0.valid ? min(map.k_eff[r0.b] + 1, RM) : 0;
-    if (hi && blockIdx.z == 0)   // rows not in flight: defined planes (their results are never used)
+    if (hi)   // rows not in flight: defined planes (their results are never used)
         for (int j = nrows * hd + tid; j < map.rows_per_seq * hd; j += 256) {
             const size_t at = (size_t)(R0 + j / hd) * d + (size_t)h * hd + j % hd;
             hi[at] = 0;
@@ -372,19 +369,6 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, _
         }
     if (!r0.valid) return;
     const int pos0 = r0.pos, last = pos0 + nrows - 1;
-    // With few (sequence, head) pairs the cached positions are cut over gridDim.z workgroups (parts of whole
-    // 16-entry tiles; the last part also takes the rows appended here), each with its own running maximum
-    // and sum; the part that finishes last merges them, in part order.  t_lo .. t_hi: this workgroup's entries.
-    const int nsplit = gridDim.z, z = blockIdx.z;
-    int t_lo = 0, t_hi = last;
-    if (nsplit > 1) {
-        const int chunk = ((pos0 + nsplit - 1) / nsplit + 15) & ~15;
-        t_lo = min(z * chunk, pos0);
-        t_hi = z == nsplit - 1 ? last : min((z + 1) * chunk, pos0) - 1;
-    }
-    const bool appends = z == nsplit - 1;
-    const int t_base = t_lo & ~15;   // scores are kept from this entry on
-    const int t_end = t_hi >= t_lo ? t_hi : t_base - 1;   // (a part without entries runs no loop at all)
     const size_t base = ((((size_t)layer * Smax + s) * (d / hd) + h) * Tmax) * hd;   // this head's entries, contiguous
     // The rows' own rotary step and cache append happen here (QKV holds the raw projections): the
     // workgroup rotates its head's q and k rows (pair (2j, 2j+1) by pos * inv_freq[j], as
@@ -394,19 +378,18 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, _
         const int r = i / (hd / 2), j = i - r * (hd / 2);
         float q0 = 0.f, q1 = 0.f;
         if (r < nrows) {
-            const float2 cs = rope_tab[(size_t)(pos0 + r) * (hd / 2) + j];   // the table holds (float)cos, (float)sin of the double angle
-            const float c = cs.x, sf = cs.y;
+            double sn, cs;
+            sincos((double)(pos0 + r) * inv_freq[j], &sn, &cs);
+            const float c = (float)cs, sf = (float)sn;
             const float* row = QKV + (size_t)(R0 + r) * 3 * d + (size_t)h * hd + 2 * j;
             const float qa = row[0], qb = row[1], ka = row[d], kb = row[d + 1];
             q0 = qa * c - qb * sf;
             q1 = qa * sf + qb * c;
-            if (appends) {
-                const size_t at = base + (size_t)(pos0 + r) * hd + 2 * j;
-                Kc[at] = (_Float16)(ka * c - kb * sf);
-                Kc[at + 1] = (_Float16)(ka * sf + kb * c);
-                Vc[at] = (_Float16)row[2 * d];
-                Vc[at + 1] = (_Float16)row[2 * d + 1];
-            }
+            const size_t at = base + (size_t)(pos0 + r) * hd + 2 * j;
+            Kc[at] = (_Float16)(ka * c - kb * sf);
+            Kc[at + 1] = (_Float16)(ka * sf + kb * c);
+            Vc[at] = (_Float16)row[2 * d];
+            Vc[at + 1] = (_Float16)row[2 * d + 1];
         }
         sq[r * hd + 2 * j] = q0;
         sq[r * hd + 2 * j + 1] = q1;
@@ -435,14 +418,14 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, _
     float mxl = -INFINITY;   // running maximum of row r16 over this lane's entries
     {
         const _Float16* kp = Kc + base + kg * 8;
-        const int ntile = t_hi >= t_lo ? t_hi / 16 + 1 : 0;
+        const int ntile = last / 16 + 1;
         constexpr int TB = 4;   // tiles requested together: their loads overlap
-        for (int ib = t_base / 16 + wave; ib < ntile; ib += 4 * TB) {
+        for (int ib = wave; ib < ntile; ib += 4 * TB) {
             h8 k8[TB][4];
 #pragma unroll
             for (int u = 0; u < TB; ++u) {
                 // tiles and entries past the end repeat the last entry (masked below)
-                const _Float16* row = kp + (size_t)min((ib + 4 * u) * 16 + r16, t_hi) * hd;
+                const _Float16* row = kp + (size_t)min((ib + 4 * u) * 16 + r16, last) * hd;
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
                     if (ks < KS) k8[u][ks] = *reinterpret_cast<const h8*>(row + ks * 32);
@@ -461,8 +444,8 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, _
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int t = t0 + 4 * kg + e;
-                        const float v = (t >= t_lo && t <= t_hi && r16 < nrows && t <= pos0 + r16) ? acc[e] : -INFINITY;
-                        if (t <= t_hi) sc[(size_t)(t - t_base) * RM + r16] = v;
+                        const float v = (t <= last && r16 < nrows && t <= pos0 + r16) ? acc[e] : -INFINITY;
+                        if (t <= last) sc[(size_t)t * RM + r16] = v;
                         mxl = fmaxf(mxl, v);
                     }
                 }
@@ -482,12 +465,12 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, _
         den[r] = 0.f;
     }
     __syncthreads();
-    for (int t = t_base + tid; t <= t_end; t += 256) {
+    for (int t = tid; t <= last; t += 256) {
 #pragma unroll
         for (int r = 0; r < RM; ++r) {
-            const float v = sc[(size_t)(t - t_base) * RM + r];
+            const float v = sc[(size_t)t * RM + r];
             const float e = (r < nrows && v != -INFINITY) ? expf(v - mx[r]) : 0.f;
-            sc[(size_t)(t - t_base) * RM + r] = e;
+            sc[(size_t)t * RM + r] = e;
             den[r] += e;
         }
     }
@@ -514,7 +497,7 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, _
         float p[RM];
 #pragma unroll
         for (int r = 0; r < RM; r += 4) {
-            const float4 q4 = *reinterpret_cast<const float4*>(sc + (size_t)(t - t_base) * RM + r);
+            const float4 q4 = *reinterpret_cast<const float4*>(sc + (size_t)t * RM + r);
             p[r] = q4.x;
             p[r + 1] = q4.y;
             p[r + 2] = q4.z;
@@ -525,16 +508,15 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, _
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[r][e] += p[r] * (float)v[e];
     };
-    int t = t_base + slv;
-    const int last_v = t_end;
-    for (; t + 7 * nsv <= last_v; t += 8 * nsv) {   // eight entries in flight per lane
+    int t = slv;
+    for (; t + 7 * nsv <= last; t += 8 * nsv) {   // eight entries in flight per lane
         h8 v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const h8*>(vp + (size_t)(t + u * nsv) * hd);
 #pragma unroll
         for (int u = 0; u < 8; ++u) fold(t + u * nsv, v[u]);
     }
-    for (; t <= last_v; t += nsv) fold(t, *reinterpret_cast<const h8*>(vp + (size_t)t * hd));
+    for (; t <= last; t += nsv) fold(t, *reinterpret_cast<const h8*>(vp + (size_t)t * hd));
 #pragma unroll
     for (int r = 0; r < RM; ++r)
 #pragma unroll
@@ -552,55 +534,6 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const float* QKV, _
             for (int e = 0; e < 8; ++e) part[(wave * RM + r) * hd + c8v * 8 + e] = acc[r][e];
     }
     __syncthreads();
-    if (nsplit > 1) {
-        // this part's unnormalised rows, maxima and sums; then the arrival counter - the part that arrives
-        // last reads all of them back (device scope) and finishes the rows
-        float* mine = split_part + (((size_t)s * gridDim.y + h) * nsplit + z) * RM * (hd + 2);
-        for (int j = tid; j < nrows * hd; j += 256) {
-            const int r = j / hd, c = j - r * hd;
-            __hip_atomic_store(mine + r * (hd + 2) + c,
-                               (part[r * hd + c] + part[(RM + r) * hd + c]) + (part[(2 * RM + r) * hd + c] + part[(3 * RM + r) * hd + c]),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        if (tid < nrows) {
-            __hip_atomic_store(mine + tid * (hd + 2) + hd, mx[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(mine + tid * (hd + 2) + hd + 1, den[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        // device-scope stores go through to memory and are acknowledged from there: once every thread's are
-        // (no whole-cache write-back as a device-scope fence would do), the arrival may be counted
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
-        __shared__ unsigned arrived;
-        if (tid == 0) arrived = __hip_atomic_fetch_add(split_cnt + (size_t)s * gridDim.y + h, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __syncthreads();
-        if (arrived != (unsigned)nsplit - 1u) return;
-        if (tid == 0) __hip_atomic_store(split_cnt + (size_t)s * gridDim.y + h, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
-        const float* all = split_part + ((size_t)s * gridDim.y + h) * nsplit * RM * (hd + 2);
-        for (int j = tid; j < nrows * hd; j += 256) {
-            const int r = j / hd, c = j - r * hd;
-            float m = -INFINITY;
-            for (int q = 0; q < nsplit; ++q)
-                m = fmaxf(m, __hip_atomic_load(all + ((size_t)q * RM + r) * (hd + 2) + hd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-            float o = 0.f, dn = 0.f;
-            for (int q = 0; q < nsplit; ++q) {
-                const float* pr = all + ((size_t)q * RM + r) * (hd + 2);
-                const float mq = __hip_atomic_load(pr + hd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const float f = mq == -INFINITY ? 0.f : expf(mq - m);
-                o += __hip_atomic_load(pr + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) * f;
-                dn += __hip_atomic_load(pr + hd + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) * f;
-            }
-            const float v = o / dn;
-            const size_t at = (size_t)(R0 + r) * d + (size_t)h * hd + c;
-            O[at] = v;
-            if (hi) {
-                unsigned hh, ll;
-                bf16_split(v, hh, ll);
-                hi[at] = (uint16_t)hh;
-                lo[at] = (uint16_t)ll;
-            }
-        }
-        return;
-    }
     for (int j = tid; j < nrows * hd; j += 256) {
         const int r = j / hd, c = j - r * hd;
         const float o = (part[r * hd + c] + part[(RM + r) * hd + c]) + (part[(2 * RM + r) * hd + c] + part[(3 * RM + r) * hd + c]);
@@ -747,7 +680,7 @@ static size_t attention_rows_lds(const hawk_ctx* c) {
 }
 bool attention_does_rope(const hawk_ctx* c, const RowMap& map) {
     const int cpr = c->hd / 8;
-    return c->cfg.dtype == HAWK_BF16 && c->off.rope_tab && map.mode == 1 && map.rows_per_seq <= 8 && (cpr == 8 || cpr == 16) &&
+    return c->cfg.dtype == HAWK_BF16 && map.mode == 1 && map.rows_per_seq <= 8 && (cpr == 8 || cpr == 16) &&
            attention_rows_lds(c) <= 60 * 1024;
 }
 
@@ -755,17 +688,13 @@ void launch_attention(hawk_ctx* c, const RowMap& map, int layer, int M) {
     if (attention_does_rope(c, map)) {
         const size_t lds = attention_rows_lds(c);
         {
-            // few (sequence, head) pairs: the cached positions are cut over up to four workgroups each
-            const int pairs = (M / map.rows_per_seq) * c->H;
-            const int nsplit = (c->off.attn_part && pairs < 128) ? std::max(1, std::min(kAttnSplitMax, 256 / pairs)) : 1;
-            dim3 grid(M / map.rows_per_seq, c->H, nsplit);
+            dim3 grid(M / map.rows_per_seq, c->H);
             uint16_t *hi = nullptr, *lo = nullptr;
             presplit_planes(c, c->off.o, M, c->d, &hi, &lo);   // the Wo GEMM reads the result next
 #define HAWK_ATTN_ROWS(RMV, NRV)                                                                       \
     attention_rows_kernel<RMV, NRV><<<grid, 256, lds, c->stream>>>(                                    \
         wsp<float>(c, c->off.qkv), wsp<_Float16>(c, c->off.kc), wsp<_Float16>(c, c->off.vc),           \
-        wsp<float>(c, c->off.o), map, wsp<float2>(c, c->off.rope_tab), layer, c->d, c->hd, c->Smax, c->Tmax, hi, lo,   \
-        nsplit > 1 ? wsp<float>(c, c->off.attn_part) : nullptr, nsplit > 1 ? wsp<unsigned>(c, c->off.attn_cnt) : nullptr)
+        wsp<float>(c, c->off.o), map, wsp<double>(c, c->off.inv_freq), layer, c->d, c->hd, c->Smax, c->Tmax, hi, lo)
             if (map.rows_per_seq <= 2) HAWK_ATTN_ROWS(4, 2);
             else if (map.rows_per_seq <= 4) HAWK_ATTN_ROWS(4, 4);
             else if (map.rows_per_seq <= 6) HAWK_ATTN_ROWS(8, 6);

@@ -59,8 +59,6 @@ struct Offsets {  // byte offsets into the workspace
     size_t blob, kc, vc, n, k_eff, step, done, counters, grid, draft, forced, hprev, qstat, pstat;
     size_t x, a, qkv, o, u, din, g0, g1, ga, logit_s, logit_b, dlogit_s, dlogit_b;
     size_t u_draft, u_acc, u_fin, out_na, out_tok, inv_freq, replay, cond;
-    size_t rope_tab;              // rotary factors [Tmax][hd / 2] (cos, sin) fp32 (bf16 configurations; 0: not present)
-    size_t attn_part, attn_cnt;   // split attention of the step rows: partial rows and arrival counters (0: not present)
     size_t tree;    // candidate tree of a tree pass: int32 depth[64], then uint64 ancestors[64], then walk state
     size_t split;   // bf16 hi / lo planes of a GEMM input (batched shapes; 0: not present)
     size_t split2;  // second pair of planes: written by a GEMM's own epilogue while it reads the first
@@ -222,7 +220,6 @@ int launch_sample_rows(const float* logits, const int32_t* skip, const float* u,
                        int top_k, int32_t* out_token, hipStream_t stream);
 
 // ---- tree verification, implemented in tree.hip ----
-constexpr int kAttnSplitMax = 4;   // workgroups that share the cached positions of one (sequence, head)
 constexpr int kTreeMaxDepth = 8;    // depths of a candidate tree
 constexpr int kTreeMaxNodes = 64;   // nodes, the root included (one bit each in a row's ancestor mask)
 // dst[r] = src[index[r]] (rows of n floats); uncond_shift > 0: guided with the row that many rows further on
