@@ -328,7 +328,7 @@ int download(hawk_ctx* c, void* host, size_t off, size_t bytes) {
     if (bytes == 0) return HAWK_OK;
     unsigned e = 0;
     HIP_TRY(c, hipMemcpyAsync(host, c->ws + off, bytes, hipMemcpyDeviceToHost, c->stream));
-    if (stream_has_err_word(c)) HIP_TRY(c, hipMemcpyAsync(&e, c->ws + c->soff.err, 4, hipMemcpyDeviceToHost, c->stream));
+    if (stream_has_err_word(c)) HIP_TRY(c, hipMemcpyAsync(&e, c->ws + c->err_off, 4, hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     if (c->launch_failed) return fail(c, HAWK_EDEVICE, "launch of a persistent kernel failed");
     if (e != 0) {
@@ -443,7 +443,7 @@ int hawk_debug_raise_timeout(hawk_ctx* c) {
     if (!c) return HAWK_EINVAL;
     if (!stream_has_err_word(c)) return fail(c, HAWK_ESTATE, "this context has no persistent-kernel plan");
     const unsigned one = 1;
-    HIP_TRY(c, hipMemcpyAsync(c->ws + c->soff.err, &one, 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->ws + c->err_off, &one, 4, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     return HAWK_OK;
 }

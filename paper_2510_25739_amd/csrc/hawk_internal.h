@@ -73,7 +73,7 @@ struct StreamOffsets { size_t wpack, tab, desc, arena, slot_bytes, bar, err, dbg
 struct StreamPlan;
 // The same pass laid out on the chip's XCDs (xcd.hip): packed weights, job tables, tagged partial sums and
 // sums of squares, per-XCD buffers, flag words.
-struct XcdOffsets { size_t zero, wpack, desc, gtab, rtab, ptab, atab, xp, part[5], pss[5], xbuf, xcd_bytes, lflag, dbg; };
+struct XcdOffsets { size_t zero, wpack, desc, gtab, rtab, ptab, atab, xp, part[5], pss[5], xbuf, xcd_bytes, lflag, dbg, err, rope; };
 struct XcdPlan;
 
 struct Weights {  // byte offsets into the blob
@@ -95,6 +95,8 @@ struct hawk_ctx {
     hawk::StreamPlan* plan;  // streaming path: job tables and barrier epoch (null until created)
     hawk::XcdOffsets xoff;
     hawk::XcdPlan* xplan;    // XCD-partitioned pass: plan and tag epoch (null until created)
+    size_t err_off, rope_off;   // the persistent kernels' error word and rotary table [Tmax][hd / 2] (cos, sin) in the workspace
+    int err_ready;           //   (set up by whichever plan exists; err_ready: the word is there and cleared)
     int dead;                // a persistent kernel gave up on a wait: its exchange state is undefined, every call fails
     int last_kernel;         // kernel of the last target pass: 0 one per operation, 1 grid-barrier kernel, 2 XCD-partitioned kernel
     size_t blob_bytes;

@@ -1462,6 +1462,7 @@ StreamPlan* stream_create(hawk_ctx* c) {
         P->ok = false;   // the context falls back to one kernel per operation
     }
     P->err_word_ready = good;
+    if (good) { c->err_off = o.err; c->rope_off = o.rope; c->err_ready = 1; }
     return P;
 }
 
@@ -1691,13 +1692,13 @@ int launch_draft_stream(hawk_ctx* c, int i, size_t off_prev, size_t off_out) {
 
 // The persistent kernels' error word exists and has been cleared (its region is part of the workspace
 // whenever the shape has a streaming plan; the kernel laid out on the XCDs shares it).
-bool stream_has_err_word(const hawk_ctx* c) { return c->plan && c->plan->err_word_ready; }
+bool stream_has_err_word(const hawk_ctx* c) { return c->err_ready != 0; }
 
 // 1 if a wait of the persistent kernels ever timed out (the result of that step is invalid).
 int stream_error(hawk_ctx* c) {
     if (!stream_has_err_word(c)) return 0;
     unsigned e = 0;
-    if (hipMemcpyAsync(&e, c->ws + c->soff.err, 4, hipMemcpyDeviceToHost, c->stream) != hipSuccess) return 1;
+    if (hipMemcpyAsync(&e, c->ws + c->err_off, 4, hipMemcpyDeviceToHost, c->stream) != hipSuccess) return 1;
     if (hipStreamSynchronize(c->stream) != hipSuccess) return 1;
     return e != 0;
 }

@@ -52,7 +52,6 @@ constexpr int kCW = 4, kNIO = 4;                 // compute / IO waves per workg
 constexpr int kThreads = (kCW + kNIO) * 64, kIOThreads = kNIO * 64;
 constexpr int kXcd = 8, kPer = kNWG / kXcd;      // workgroup i runs on XCD i % 8 (checked by every workgroup)
 constexpr unsigned kSpinLimit = 1u << 20;
-constexpr int kPS = 68;                          // floats per attention partial row: 64 outputs, max, sum, pad
 constexpr int kNIT = 4;                          // cache positions per lane group and register buffer
 constexpr int kPaceGap = 0, kPaceTiles = 6;   // weight requests go out six tiles per wave at a time (see issue_paced)
 constexpr int kRing = 2;                         // partial-sum areas and XCD buffers alternate between layers
@@ -94,6 +93,8 @@ struct XP {
     const int32_t* tdepth;      // rows of a candidate tree (null: a chain): depth of node r, and bit a of tanc[r] set iff node a
     const u64* tanc;            //   is an ancestor of node r; node r sits at the root's position + depth, in cache entry root + r
     int32_t L, d, H, m, Vs, S, B, C, RS, MR, RPJ, Smax, Tmax;
+    int32_t hd;                 // head dimension (64 or 128)
+    float qscale;               // 1 / sqrt(hd)
     int32_t KpA, KpO, KpH;      // row strides (elements) of the split planes: d / 8 + 8, widest head group + 8, widest hidden slice + 8
     int32_t lm_rounds;
     float eps;
@@ -483,7 +484,7 @@ __device__ __forceinline__ IoJobs load_io_jobs(const XP& p, const Ctx& c, int io
     if (j.sA >= 0 && col < p.MR) {
         const int o0 = j.sA * 16, seg = o0 / p.d, j0 = o0 - seg * p.d;
         if (seg < 2) {
-            const float2* rt = p.rope + (size_t)j.rp.pos * 32 + ((j0 % 64) >> 1) + 2 * quad;
+            const float2* rt = p.rope + (size_t)j.rp.pos * (p.hd / 2) + ((j0 % p.hd) >> 1) + 2 * quad;
             j.rot0 = rt[0];
             j.rot1 = rt[1];
         }
@@ -523,15 +524,15 @@ __device__ __forceinline__ void reduce_job(const XP& p, Ctx& c, const IoJobs& jb
     v *= rn;
     stamp(c, stage, 5);
     if (kind == X_A) {
-        const int seg = (s * 16) / d, j0 = s * 16 - seg * d, h = j0 / 64;
+        const int seg = (s * 16) / d, j0 = s * 16 - seg * d, h = j0 / p.hd;
         const float a0 = v[0] * jb.rot0.x - v[1] * jb.rot0.y, b0 = v[0] * jb.rot0.y + v[1] * jb.rot0.x;
         const float a1 = v[2] * jb.rot1.x - v[3] * jb.rot1.y, b1 = v[2] * jb.rot1.y + v[3] * jb.rot1.x;
         if (live) {
-            const int hl = h - p.hd0[c.x], f0 = j0 % 64 + 4 * quad;   // head among the XCD's, first of the lane's four features
-            if (seg == 0) {   // queries of this XCD's heads, scaled by 1 / sqrt(64): {value, tag} pairs
-                v4u* q = reinterpret_cast<v4u*>(buf + p.o_q + ((size_t)col * (p.KpO - 8) + hl * 64 + f0) * 8);
-                q[0] = (v4u){__float_as_uint(a0 * 0.125f), tag, __float_as_uint(b0 * 0.125f), tag};
-                q[1] = (v4u){__float_as_uint(a1 * 0.125f), tag, __float_as_uint(b1 * 0.125f), tag};
+            const int hl = h - p.hd0[c.x], f0 = j0 % p.hd + 4 * quad;   // head among the XCD's, first of the lane's four features
+            if (seg == 0) {   // queries of this XCD's heads, scaled by 1 / sqrt(head dimension): {value, tag} pairs
+                v4u* q = reinterpret_cast<v4u*>(buf + p.o_q + ((size_t)col * (p.KpO - 8) + hl * p.hd + f0) * 8);
+                q[0] = (v4u){__float_as_uint(a0 * p.qscale), tag, __float_as_uint(b0 * p.qscale), tag};
+                q[1] = (v4u){__float_as_uint(a1 * p.qscale), tag, __float_as_uint(b1 * p.qscale), tag};
             } else {
                 // keys (rotated) / values as fp16 pairs: into the cache for the steps to come (valid rows), and
                 // as tagged pairs for this launch's attention jobs, which poll them ({pair, tag, pair, tag})
@@ -540,10 +541,10 @@ __device__ __forceinline__ void reduce_job(const XP& p, Ctx& c, const IoJobs& jb
                 const unsigned p23 = (unsigned)__builtin_bit_cast(unsigned short, h2) | ((unsigned)__builtin_bit_cast(unsigned short, h3) << 16);
                 if (jb.rp.valid) {
                     _Float16* dst = (seg == 1 ? p.Kc : p.Vc) +
-                                    ((((size_t)layer * p.Smax + jb.rp.seq) * p.H + h) * p.Tmax + jb.rp.slot) * 64 + f0;
+                                    ((((size_t)layer * p.Smax + jb.rp.seq) * p.H + h) * p.Tmax + jb.rp.slot) * p.hd + f0;
                     *reinterpret_cast<uint2*>(dst) = make_uint2(p01, p23);
                 }
-                *reinterpret_cast<v4u*>(buf + p.o_kv + ((((size_t)(seg - 1) * 16 + col) * (p.KpO - 8) / 64 + hl) * 16 + f0 / 4) * 16) =
+                *reinterpret_cast<v4u*>(buf + p.o_kv + ((((size_t)(seg - 1) * 16 + col) * ((p.KpO - 8) / p.hd) + hl) * (p.hd / 4) + f0 / 4) * 16) =
                     (v4u){p01, tag, p23, tag};
             }
         }
@@ -601,8 +602,16 @@ __device__ __forceinline__ void halves8(v4u raw, float (&f)[8]) {
     }
 }
 
+// Sum over the LPP (8 or 16) lanes that share a cache position.
+template <int LPP>
+__device__ __forceinline__ float sum_lanes(float v) {
+    v = sum8(v);
+    if (LPP == 16) v += lane_xor8(v);
+    return v;
+}
+
 // One cache position per lane group; row r0 + r of the sequence sees it iff bit r0 + r of vis is set.
-template <int RPJ>
+template <int RPJ, int LPP = 8>
 __device__ __forceinline__ void attend(const float (&q)[RPJ][8], int r0, v4u kraw, v4u vraw, unsigned vis, int ke,
                                        AttnAcc (&A)[RPJ]) {
     float kf[8], vf[8];
@@ -613,7 +622,7 @@ __device__ __forceinline__ void attend(const float (&q)[RPJ][8], int r0, v4u kra
         float sc = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) sc += q[r][e] * kf[e];
-        sc = sum8(sc);
+        sc = sum_lanes<LPP>(sc);
         if (((vis >> (r0 + r)) & 1u) && r0 + r <= ke) {
             const float mn = fmaxf(A[r].mx, sc);
             const float corr = __expf(A[r].mx - mn), pw = __expf(sc - mn);
@@ -627,7 +636,7 @@ __device__ __forceinline__ void attend(const float (&q)[RPJ][8], int r0, v4u kra
 
 // kNIT cache positions per lane group at once: all scores, one running-maximum update per row, then
 // the weighted values.
-template <int RPJ>
+template <int RPJ, int LPP = 8>
 __device__ __forceinline__ void attend_round(const float (&q)[RPJ][8], int r0, const v4u (&kk)[kNIT], const v4u (&vv)[kNIT],
                                              int pos0, int stride, int o1, int ke, AttnAcc (&A)[RPJ]) {
     float sc[RPJ][kNIT];
@@ -641,7 +650,7 @@ __device__ __forceinline__ void attend_round(const float (&q)[RPJ][8], int r0, c
             float dd = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) dd += q[r][e] * kf[e];
-            dd = sum8(dd);
+            dd = sum_lanes<LPP>(dd);
             sc[r][it] = (on && r0 + r <= ke) ? dd : -1e30f;
         }
     }
@@ -679,8 +688,8 @@ struct Lds {
     unsigned act_elems; //   the buffer act_elems elements further on (an offset, not a second pointer to choose from: a
                         //   select between members by a run-time value tends to end up as indexing in memory)
     float* ss0;         // sums of squares of the XCD's slice of the stage input, per row; odd stages 16 floats further on
-    float* part;        // attention: [kNIO][RPJ][kPS] partial rows of the IO waves
-    float* qs;          // attention: [RPJ][64] scaled queries
+    float* part;        // attention: [kNIO][RPJ][hd + 4] partial rows of the IO waves (outputs, max, sum, pad)
+    float* qs;          // attention: [RPJ][hd] scaled queries
 };
 
 // Attention of one (sequence, head, row group) on the XCD that owns the head: the cached positions
@@ -711,17 +720,18 @@ __device__ __forceinline__ void io_barrier(const Lds& s, unsigned& joins, int la
 }
 
 // Runs on the unit's four IO waves (they hold no weights): each takes a quarter of the cached positions.
-template <int RPJ>
+template <int RPJ, int HD = 64>
 __device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, const Lds& s, int layer, unsigned stage,
                                         unsigned& joins) {
     if (jb.a_rg < 0) return;   // this unit has no job (the same for all its waves)
     const int io = (threadIdx.x >> 6) - kCW, lane = threadIdx.x & 63;
     const int seq = jb.a_seq, h = jb.a_h, RS = p.RS, r0 = jb.a_rg * RPJ;
-    const int pg = lane >> 3, dg = lane & 7;
+    constexpr int LPP = HD / 8, PPW = 64 / LPP, PS = HD + 4;   // lanes per cache position, positions per wave and look, floats per partial row
+    const int pg = lane / LPP, dg = lane % LPP;
     const int b = seq % p.B, ke = p.k_eff[b];
     const int kv0 = ke >= 0 ? p.C + p.n[b] - 1 : 0;   // positions cached before this launch
-    const int nrounds = (kv0 + kNIT * kNIO * 8 - 1) / (kNIT * kNIO * 8);
-    const size_t head0 = ((((size_t)layer * p.Smax + seq) * p.H + h) * p.Tmax) * 64;   // the head's entries, contiguous
+    const int nrounds = (kv0 + kNIT * kNIO * PPW - 1) / (kNIT * kNIO * PPW);
+    const size_t head0 = ((((size_t)layer * p.Smax + seq) * p.H + h) * p.Tmax) * HD;   // the head's entries, contiguous
     const _Float16* Kb = fresh(p.Kc + head0 + dg * 8);
     const _Float16* Vb = fresh(p.Vc + head0 + dg * 8);
     const unsigned tag = tag_of(c, layer, F_B);
@@ -730,10 +740,10 @@ __device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, c
     auto fetch = [&](v4u (&kk)[kNIT], v4u (&vv)[kNIT], int rnd) {
 #pragma unroll
         for (int it = 0; it < kNIT; ++it) {
-            const int pos = (rnd * kNIT + it) * (kNIO * 8) + io * 8 + pg;
+            const int pos = (rnd * kNIT + it) * (kNIO * PPW) + io * PPW + pg;
             if (pos < kv0) {
-                kk[it] = *reinterpret_cast<const v4u*>(Kb + (size_t)pos * 64);
-                vv[it] = *reinterpret_cast<const v4u*>(Vb + (size_t)pos * 64);
+                kk[it] = *reinterpret_cast<const v4u*>(Kb + (size_t)pos * HD);
+                vv[it] = *reinterpret_cast<const v4u*>(Vb + (size_t)pos * HD);
             } else {
                 kk[it] = (v4u){0u, 0u, 0u, 0u};
                 vv[it] = (v4u){0u, 0u, 0u, 0u};
@@ -746,29 +756,40 @@ __device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, c
     fetch(kc, vc, 2);
     const unsigned tagA = tag_of(c, layer, F_A);   // what the reduce jobs of the QKV product wrote carries this tag
     if (io == 0) {   // the job's queries: polled where the reduce jobs put them
-        const u64* q = reinterpret_cast<const u64*>(buf + p.o_q) + (size_t)(seq * RS + r0) * (p.KpO - 8) + (h - p.hd0[c.x]) * 64 + lane;
-        u64 qv[RPJ];
+        constexpr int QL = HD / 64;   // query values per lane
+        const u64* q = reinterpret_cast<const u64*>(buf + p.o_q) + (size_t)(seq * RS + r0) * (p.KpO - 8) + (h - p.hd0[c.x]) * HD + lane;
+        u64 qv[RPJ][QL];
         unsigned pend = 0u;
 #pragma unroll
         for (int r = 0; r < RPJ; ++r) {
-            qv[r] = 0ull;
-            if (r0 + r < RS && !c.dead) pend |= 1u << r;
+#pragma unroll
+            for (int e = 0; e < QL; ++e) {
+                qv[r][e] = 0ull;
+                if (r0 + r < RS && !c.dead) pend |= 1u << (r * QL + e);
+            }
         }
         bool ok = false;
         for (unsigned spins = 0; spins < kSpinLimit && !ok; ++spins) {
 #pragma unroll
             for (int r = 0; r < RPJ; ++r)
-                if ((pend >> r) & 1u) qv[r] = ld_u64(q + (size_t)r * (p.KpO - 8));
+#pragma unroll
+                for (int e = 0; e < QL; ++e)
+                    if ((pend >> (r * QL + e)) & 1u) qv[r][e] = ld_u64(q + (size_t)r * (p.KpO - 8) + 64 * e);
 #pragma unroll
             for (int r = 0; r < RPJ; ++r)
-                if (((pend >> r) & 1u) && (unsigned)(qv[r] >> 32) == tagA) pend &= ~(1u << r);
+#pragma unroll
+                for (int e = 0; e < QL; ++e)
+                    if (((pend >> (r * QL + e)) & 1u) && (unsigned)(qv[r][e] >> 32) == tagA) pend &= ~(1u << (r * QL + e));
             ok = __all(pend == 0u);
             if (!ok && (spins & 255u) == 255u && ld_u32(c.err) != 0u) break;
         }
         if (!ok) give_up(c);
         stamp(c, stage, 1);
 #pragma unroll
-        for (int r = 0; r < RPJ; ++r) s.qs[r * 64 + lane] = (r0 + r < RS && ok) ? __uint_as_float((unsigned)qv[r]) : 0.f;
+        for (int r = 0; r < RPJ; ++r)
+#pragma unroll
+            for (int e = 0; e < QL; ++e)
+                s.qs[r * HD + lane + 64 * e] = (r0 + r < RS && ok) ? __uint_as_float((unsigned)qv[r][e]) : 0.f;
     }
     io_barrier(s, joins, lane);   // the queries are in LDS
     {
@@ -782,14 +803,14 @@ __device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, c
         float q[RPJ][8];
 #pragma unroll
         for (int r = 0; r < RPJ; ++r) {
-            const float4 qa = *reinterpret_cast<const float4*>(s.qs + r * 64 + dg * 8);
-            const float4 qb = *reinterpret_cast<const float4*>(s.qs + r * 64 + dg * 8 + 4);
+            const float4 qa = *reinterpret_cast<const float4*>(s.qs + r * HD + dg * 8);
+            const float4 qb = *reinterpret_cast<const float4*>(s.qs + r * HD + dg * 8 + 4);
             q[r][0] = qa.x; q[r][1] = qa.y; q[r][2] = qa.z; q[r][3] = qa.w;
             q[r][4] = qb.x; q[r][5] = qb.y; q[r][6] = qb.z; q[r][7] = qb.w;
         }
         auto run = [&](const v4u (&kk)[kNIT], const v4u (&vv)[kNIT], int rnd) {
-            const int pos0 = rnd * kNIT * (kNIO * 8) + io * 8 + pg;
-            attend_round<RPJ>(q, r0, kk, vv, pos0, kNIO * 8, kv0, ke, A);
+            const int pos0 = rnd * kNIT * (kNIO * PPW) + io * PPW + pg;
+            attend_round<RPJ, LPP>(q, r0, kk, vv, pos0, kNIO * PPW, kv0, ke, A);
         };
         // Rows appended by this launch (up to 16: lane group pg takes rows pg and pg + 8), polled as the tagged
         // fp16 pairs this XCD's reduce jobs write.  Who sees them: in a chain row r sees row a iff a <= r, in a
@@ -809,10 +830,10 @@ __device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, c
         };
         auto fetch_row = [&](int a, unsigned& vis, v4u& kn, v4u& vn) {   // lane dg = features 8 dg .. 8 dg + 7
             const rsrc_t kvr = make_rsrc(p.xbuf);
-            const unsigned hw = (unsigned)(p.KpO - 8) / 64u;   // heads a row of the region has room for
+            const unsigned hw = (unsigned)(p.KpO - 8) / (unsigned)HD;   // heads a row of the region has room for
             const unsigned atk = (unsigned)(((size_t)c.x * kRing + (layer & 1)) * p.xcd_bytes + p.o_kv) +
-                                 ((((unsigned)(seq * RS + a)) * hw + (unsigned)(h - p.hd0[c.x])) * 16u + 2u * dg) * 16u;
-            const unsigned atv = atk + 16u * hw * 16u * 16u;
+                                 ((((unsigned)(seq * RS + a)) * hw + (unsigned)(h - p.hd0[c.x])) * (unsigned)(HD / 4) + 2u * dg) * 16u;
+            const unsigned atv = atk + 16u * hw * (unsigned)(HD / 4) * 16u;
             v4u k0, k1, v0, v1;
             bool ok = vis == 0u || c.dead;   // rows nobody of this job sees are not waited for
             for (unsigned spins = 0; spins < kSpinLimit && !__all(ok); ++spins) {
@@ -838,16 +859,16 @@ __device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, c
             if (rnd + 2 < nrounds) run(kc, vc, rnd + 2);
             if (rnd + 5 < nrounds) fetch(kc, vc, rnd + 5);
         }
-        if (vis0) attend<RPJ>(q, r0, kn, vn, vis0, ke, A);
-        if (RS > 8) {   // (uniform over the launch)
-            unsigned vis1 = seen_by(pg + 8);
-            if (io == 0) fetch_row(pg + 8, vis1, kn, vn);
-            if (vis1) attend<RPJ>(q, r0, kn, vn, vis1, ke, A);
+        if (vis0) attend<RPJ, LPP>(q, r0, kn, vn, vis0, ke, A);
+        for (int a = pg + PPW; a - pg < RS; a += PPW) {   // (the trip count is uniform over the launch)
+            unsigned vis1 = seen_by(a);
+            if (io == 0) fetch_row(a, vis1, kn, vn);
+            if (vis1) attend<RPJ, LPP>(q, r0, kn, vn, vis1, ke, A);
         }
 #pragma unroll
         for (int r = 0; r < RPJ; ++r) {
 #pragma unroll
-            for (int o = 8; o < 64; o <<= 1) {
+            for (int o = LPP; o < 64; o <<= 1) {
                 auto other = [&](float xx) { return o == 8 ? lane_xor8(xx) : (o == 16 ? lane_xor16(xx) : lane_xor32(xx)); };
                 const float omx = other(A[r].mx), oden = other(A[r].den);
                 const float mn = fmaxf(A[r].mx, omx);
@@ -858,33 +879,33 @@ __device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, c
                 A[r].mx = mn;
             }
             if (pg == 0) {
-                float* mine = s.part + ((size_t)io * RPJ + r) * kPS;
+                float* mine = s.part + ((size_t)io * RPJ + r) * PS;
                 *reinterpret_cast<float4*>(mine + dg * 8) = make_float4(A[r].acc[0], A[r].acc[1], A[r].acc[2], A[r].acc[3]);
                 *reinterpret_cast<float4*>(mine + dg * 8 + 4) = make_float4(A[r].acc[4], A[r].acc[5], A[r].acc[6], A[r].acc[7]);
-                if (dg == 0) *reinterpret_cast<float2*>(mine + 64) = make_float2(A[r].mx, A[r].den);
+                if (dg == 0) *reinterpret_cast<float2*>(mine + HD) = make_float2(A[r].mx, A[r].den);
             }
         }
     }
     io_barrier(s, joins, lane);   // the waves' partial rows are in LDS
     if (io == 0) {   // merge them; lane: row lane / 16 of the job, dims 4 * (lane % 16) .. + 3
-        const int r = lane >> 4, q4 = lane & 15;
+        const int r = lane / (HD / 4), q4 = lane % (HD / 4);
         if (r < RPJ && r0 + r < RS) {
             float m2 = -1e30f;
 #pragma unroll
-            for (int w = 0; w < kNIO; ++w) m2 = fmaxf(m2, s.part[((size_t)w * RPJ + r) * kPS + 64]);
+            for (int w = 0; w < kNIO; ++w) m2 = fmaxf(m2, s.part[((size_t)w * RPJ + r) * PS + HD]);
             float dn = 0.f;
             f32x4 o = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int w = 0; w < kNIO; ++w) {
-                const float* src = s.part + ((size_t)w * RPJ + r) * kPS;
-                const float f = __expf(src[64] - m2);
-                dn += src[65] * f;
+                const float* src = s.part + ((size_t)w * RPJ + r) * PS;
+                const float f = __expf(src[HD] - m2);
+                dn += src[HD + 1] * f;
                 o += *reinterpret_cast<const f32x4*>(src + 4 * q4) * f;
             }
             const float inv = dn > 0.f ? 1.0f / dn : 0.f;
             uint16_t* hi = reinterpret_cast<uint16_t*>(buf + p.o_o);
             uint16_t* lo = hi + (size_t)16 * p.KpO;
-            const size_t at = (size_t)(seq * RS + r0 + r) * p.KpO + (h - p.hd0[c.x]) * 64 + 4 * q4;
+            const size_t at = (size_t)(seq * RS + r0 + r) * p.KpO + (h - p.hd0[c.x]) * HD + 4 * q4;
             put_split4(hi + at, lo + at, o * inv);
         }
         raise_flag(p, c, F_B, jb.a_slot, tag);
@@ -1014,7 +1035,7 @@ __device__ __forceinline__ void compute_main(const XP& p, const Ctx& c, const Ld
     compute_stage<X_LM, NL, KA>(p, c, gL, s, p.L, stage++, p.KpA, wL, [] {});
 }
 
-template <int RPJ>
+template <int RPJ, int HD>
 __device__ __forceinline__ void io_main(const XP& p, Ctx& c, const Lds& s) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const IoJobs jb = load_io_jobs(p, c, wave - kCW, lane);
@@ -1035,12 +1056,12 @@ __device__ __forceinline__ void io_main(const XP& p, Ctx& c, const Lds& s) {
 #pragma nounroll
     for (unsigned stage = 0; stage < nstages; ++stage) {
         const int l = (int)(stage / 5u), st = (int)(stage - 5u * (unsigned)l);
-        if (st == 1) attn_io<RPJ>(p, c, jb, s, l, stage, joins);
+        if (st == 1) attn_io<RPJ, HD>(p, c, jb, s, l, stage, joins);
         else io_stage(p, c, jb, s, l == p.L ? X_LM : st == 0 ? X_A : st == 2 ? X_C : st == 3 ? X_D : X_E, l, stage, resid);
     }
 }
 
-template <int NA, int KA, int NC, int KC, int ND, int KD, int NE, int KE, int NL, int RPJ>
+template <int NA, int KA, int NC, int KC, int ND, int KD, int NE, int KE, int NL, int RPJ, int HD = 64>
 __global__ __launch_bounds__(kThreads, 1) void verify_xcd_kernel(const XP* __restrict__ params, unsigned epoch0, unsigned par, unsigned par_lm, u64* dbg) {
     // The parameter block lives in device memory (written when the step shape changes): tables in it are
     // indexed with run-time values, which a by-value kernel argument would answer with a private copy.
@@ -1052,8 +1073,8 @@ __global__ __launch_bounds__(kThreads, 1) void verify_xcd_kernel(const XP* __res
     s.act0 = reinterpret_cast<uint16_t*>(smem_raw + 1);
     s.act_elems = (unsigned)act_elems;
     s.part = reinterpret_cast<float*>(s.act0 + 2 * act_elems);
-    s.qs = s.part + kNIO * RPJ * kPS;
-    s.ss0 = s.qs + RPJ * 64;
+    s.qs = s.part + kNIO * RPJ * (HD + 4);
+    s.ss0 = s.qs + RPJ * HD;
     if (threadIdx.x == 0) *s.join = 0u;
     __syncthreads();
     Ctx c;
@@ -1062,7 +1083,7 @@ __global__ __launch_bounds__(kThreads, 1) void verify_xcd_kernel(const XP* __res
     // The two kinds of waves run separate code (and cross the same workgroup barriers), so that neither
     // carries the other's registers: compute waves the weights in flight, IO waves the attention's keys
     // and values and the partial sums of a reduce job.
-    if ((threadIdx.x >> 6) >= kCW) io_main<RPJ>(p, c, s);
+    if ((threadIdx.x >> 6) >= kCW) io_main<RPJ, HD>(p, c, s);
     else compute_main<NA, KA, NC, KC, ND, KD, NE, KE, NL>(p, c, s);
 }
 
@@ -1295,6 +1316,8 @@ size_t xcd_workspace(const hawk_ctx* c, size_t base, XcdOffsets* o) {
     o->xbuf = take((size_t)kXcd * kRing * o->xcd_bytes);
     o->lflag = take((size_t)kXcd * F_NF * kMaxJobs * 4);
     o->dbg = take((size_t)2 * 512 * 16 * 8);
+    o->err = take(256);
+    o->rope = take((size_t)c->Tmax * (c->hd / 2) * 8);
     return p - base;
 }
 
@@ -1324,6 +1347,19 @@ XcdPlan* xcd_create(hawk_ctx* c) {
         if (k != X_C && k != X_E)
             good = good && hipMemsetAsync(c->ws + o.pss[k], 0, (size_t)kRing * kXcd * kPer * kCW * 2 * 16 * 8, c->stream) == hipSuccess;
     good = good && hipMemsetAsync(c->ws + o.xbuf, 0, (size_t)kXcd * kRing * o.xcd_bytes, c->stream) == hipSuccess;
+    if (!c->err_ready) {   // no streaming plan set them up (a shape only this layout takes): own error word and rotary table
+        std::vector<float> rope((size_t)c->Tmax * (c->hd / 2) * 2);
+        for (int pos = 0; pos < c->Tmax; ++pos)
+            for (int j = 0; j < c->hd / 2; ++j) {
+                const double ang = (double)pos * pow((double)c->cfg.rope_theta, -2.0 * j / (double)c->hd);
+                rope[((size_t)pos * (c->hd / 2) + j) * 2] = (float)cos(ang);
+                rope[((size_t)pos * (c->hd / 2) + j) * 2 + 1] = (float)sin(ang);
+            }
+        good = good && hipMemsetAsync(c->ws + o.err, 0, 256, c->stream) == hipSuccess;
+        good = good && hipMemcpyAsync(c->ws + o.rope, rope.data(), rope.size() * 4, hipMemcpyHostToDevice, c->stream) == hipSuccess;
+        good = good && hipStreamSynchronize(c->stream) == hipSuccess;   // the table is a local
+        if (good) { c->err_off = o.err; c->rope_off = o.rope; c->err_ready = 1; }
+    }
     good = good && hipStreamSynchronize(c->stream) == hipSuccess;
     if (!good) P->ok = false;
     return P;
@@ -1361,9 +1397,9 @@ namespace {
 
 struct XcdShape { int NA, KA, NC, KC, ND, KD, NE, KE, NL; };
 
-size_t xcd_lds_bytes(const XcdPlan* P, int RPJ) {
+size_t xcd_lds_bytes(const hawk_ctx* c, const XcdPlan* P, int RPJ) {
     const size_t act = (size_t)2 * 16 * std::max(std::max(P->KpA, P->KpO), P->KpH) * 2;
-    return 16 + 2 * act + (size_t)(kNIO * RPJ * kPS + RPJ * 64 + 32) * 4 + 64;
+    return 16 + 2 * act + (size_t)(kNIO * RPJ * (c->hd + 4) + RPJ * c->hd + 32) * 4 + 64;
 }
 
 }  // namespace
@@ -1408,15 +1444,16 @@ int launch_verify_xcd(hawk_ctx* c, int k, const int32_t* tree_depth, const unsig
     p.g1_off = c->w.g1[0]; p.g2_off = c->w.g2[0];
     p.layer_bytes = c->L > 1 ? c->w.g1[1] - c->w.g1[0] : 0;
     p.gf_off = c->w.g_f;
-    p.rope = wsp<float2>(c, c->soff.rope);
+    p.rope = wsp<float2>(c, c->rope_off);
     p.Kc = wsp<_Float16>(c, c->off.kc); p.Vc = wsp<_Float16>(c, c->off.vc);
     p.X = wsp<float>(c, c->off.x);
     p.logit_s = wsp<float>(c, c->off.logit_s);
-    p.err = wsp<unsigned>(c, c->soff.err);
+    p.err = wsp<unsigned>(c, c->err_off);
     p.n = wsp<int32_t>(c, c->off.n); p.k_eff = wsp<int32_t>(c, c->off.k_eff);
     p.tdepth = tree_depth; p.tanc = reinterpret_cast<const u64*>(tree_anc);   // rows of a candidate tree (null: a chain)
     p.L = c->L; p.d = c->d; p.H = c->H; p.m = c->m; p.Vs = c->Vs; p.S = c->S; p.B = c->B; p.C = c->C;
     p.RS = RS; p.MR = c->S * RS; p.RPJ = RPJ; p.Smax = c->Smax; p.Tmax = c->Tmax;
+    p.hd = c->hd; p.qscale = 1.0f / sqrtf((float)c->hd);
     p.KpA = P->KpA; p.KpO = P->KpO; p.KpH = P->KpH;
     p.eps = c->cfg.rms_eps;
     const void* kern = nullptr;
@@ -1441,7 +1478,7 @@ int launch_verify_xcd(hawk_ctx* c, int k, const int32_t* tree_depth, const unsig
         if (hipStreamSynchronize(c->stream) != hipSuccess) return -1;   // the sources are locals: the copies must have read them
         P->params.assign(reinterpret_cast<const uint8_t*>(&p), reinterpret_cast<const uint8_t*>(&p) + sizeof(XP));
     }
-    const size_t lds = xcd_lds_bytes(P, RPJ);
+    const size_t lds = xcd_lds_bytes(c, P, RPJ);
     if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return -1;
     const XP* dev_params = wsp<XP>(c, o.xp);
     unsigned epoch0 = P->epoch;
