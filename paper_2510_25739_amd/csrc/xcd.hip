@@ -55,7 +55,7 @@ constexpr unsigned kSpinLimit = 1u << 20;
 constexpr int kNIT = 4;                          // cache positions per lane group and register buffer
 constexpr int kPaceGap = 0, kPaceTiles = 6;   // weight requests go out six tiles per wave at a time (see issue_paced)
 constexpr int kRing = 2;                         // partial-sum areas and XCD buffers alternate between layers
-constexpr int kMaxJobs = 64;                     // reduce / attention jobs of one XCD and stage that others wait for
+constexpr int kMaxJobs = 128;                    // flag words of one XCD and stage that others wait for (one per IO wave with a job)
 
 enum XKind { X_A = 0, X_C, X_D, X_E, X_LM, X_NK };   // QKV, Wo, W1|W3, W2, output projection
 enum XFlag { F_A = 0, F_B, F_C, F_D, F_E, F_NF };    // who raised a flag: reduce of A, attention, reduce of C, D, E
@@ -72,7 +72,7 @@ struct XP {
     const int16_t* gtab;        // [kind][32][kCW][2]: first strip and strip count of (unit j, compute wave w)
     const int16_t* ptab;        // [poff[kind] + strip]: producer of the strip, (unit * kCW + wave) * 2 + round
     int poff[X_NK];
-    const int16_t* rtab;        // [kind][8][32][kNIO][2]: strip (-1: none) and flag slot of (XCD, unit, IO wave)
+    const int16_t* rtab;        // [kind][8][32][kNIO][3]: strip (-1: none), flag slot, second strip (-1: none) of (XCD, unit, IO wave)
     const int16_t* atab;        // [8][32][4]: sequence, head, row group (-1: none), flag slot
     int32_t njobs[F_NF][kXcd];  // flag slots a consumer of that stage waits for
     u64* part[X_NK];            // partial sums: [ring][8 source XCDs][strip][16 rows][16 features] fp32, parity in the lowest bit
@@ -217,10 +217,12 @@ __device__ __forceinline__ void give_up(Ctx& c) {
 __device__ __forceinline__ void wait_flags(const XP& p, Ctx& c, int flag, int n, unsigned tag) {
     if (c.dead) return;
     const unsigned l = threadIdx.x & 63u;
-    const unsigned* f = p.lflag + ((size_t)c.x * F_NF + flag) * kMaxJobs + (l < (unsigned)n ? l : 0u);
+    const unsigned* f = p.lflag + ((size_t)c.x * F_NF + flag) * kMaxJobs;
+    const unsigned i0 = l < (unsigned)n ? l : 0u, i1 = l + 64u < (unsigned)n ? l + 64u : 0u;   // a lane looks at flags l and l + 64
     for (unsigned spins = 0; spins < kSpinLimit; ++spins) {
-        const unsigned v = ld_u32(f);
-        if (__all((int)(v - tag) >= 0)) { compiler_fence(); return; }
+        const unsigned v = ld_u32(f + i0);
+        const unsigned w = n > 64 ? ld_u32(f + i1) : v;
+        if (__all((int)(v - tag) >= 0 && (int)(w - tag) >= 0)) { compiler_fence(); return; }
         if ((spins & 255u) == 255u && ld_u32(c.err) != 0u) break;
     }
     give_up(c);
@@ -351,15 +353,17 @@ __device__ __forceinline__ void mfma_store(const XP& p, int kind, const GJob& g,
 // two contiguous runs of MR * Kp elements, up to four 16-byte chunks per thread in flight.
 __device__ __forceinline__ void stage_copy(rsrc_t r, unsigned src, int MR, int Kp, uint16_t* act, int t, int nthreads) {
     const int per_plane = MR * Kp / 8, total = 2 * per_plane;   // Kp % 8 == 0
-    const unsigned plane_bytes = 16u * (unsigned)Kp * 2u;
+    const unsigned src_plane = 16u * (unsigned)Kp * 2u, dst_plane = (unsigned)MR * (unsigned)Kp * 2u;   // in LDS the planes hold MR rows only
     for (int base = 0; base < total; base += 4 * nthreads) {
         v4u v[4];
         unsigned at[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int q = base + i * nthreads + t;
-            at[i] = q >= per_plane ? plane_bytes + (unsigned)(q - per_plane) * 16u : (unsigned)q * 16u;
-            v[i] = q < total ? ld_16(r, src + at[i]) : (v4u){0u, 0u, 0u, 0u};
+            const bool second = q >= per_plane;
+            const unsigned in_plane = (unsigned)(second ? q - per_plane : q) * 16u;
+            at[i] = (second ? dst_plane : 0u) + in_plane;
+            v[i] = q < total ? ld_16(r, src + (second ? src_plane : 0u) + in_plane) : (v4u){0u, 0u, 0u, 0u};
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i)
@@ -464,6 +468,7 @@ __device__ __forceinline__ void put_stream(const XP& p, const Ctx& c, int which,
 // each kind (strip, flag slot; strip < 0: none), the lane's row of the step, the rotary factors of
 // its QKV strip, the number of flag words each stage's consumers wait for, the unit's attention job.
 struct IoJobs {
+    int sD2;                     // second W1|W3 strip of the wave (shapes with more such strips than IO waves; -1: none)
     int sA, sC, sD, sE;          // strip of the wave's reduce job of each product (named fields, not arrays: a select
     int tA, tC, tD, tE;          // between array elements by a run-time value would be turned into memory indexing); flag slots
     RowPos rp;                   // row lane % 16 of the step
@@ -471,12 +476,13 @@ struct IoJobs {
     int nA, nB, nC, nD, nE;      // flag words the consumers of stage A (reduce of QKV), B (attention), C, D, E wait for
     int a_seq, a_h, a_rg, a_slot;   // attention job of the unit (a_rg < 0: none)
 };
+template <int HD>
 __device__ __forceinline__ IoJobs load_io_jobs(const XP& p, const Ctx& c, int io, int lane) {
     IoJobs j;
-    auto entry = [&](int k) { return p.rtab + ((((size_t)k * kXcd + c.x) * kPer + c.j) * kNIO + io) * 2; };
+    auto entry = [&](int k) { return p.rtab + ((((size_t)k * kXcd + c.x) * kPer + c.j) * kNIO + io) * 3; };
     j.sA = entry(X_A)[0]; j.tA = entry(X_A)[1];
     j.sC = entry(X_C)[0]; j.tC = entry(X_C)[1];
-    j.sD = entry(X_D)[0]; j.tD = entry(X_D)[1];
+    j.sD = entry(X_D)[0]; j.tD = entry(X_D)[1]; j.sD2 = HD == 64 ? -1 : entry(X_D)[2];   // (second strips: the wide shape only)
     j.sE = entry(X_E)[0]; j.tE = entry(X_E)[1];
     const int col = lane & 15, quad = lane >> 4;
     j.rp = col < p.MR ? row_pos(p, col) : RowPos{0, 0, 0, 0, false};
@@ -484,7 +490,7 @@ __device__ __forceinline__ IoJobs load_io_jobs(const XP& p, const Ctx& c, int io
     if (j.sA >= 0 && col < p.MR) {
         const int o0 = j.sA * 16, seg = o0 / p.d, j0 = o0 - seg * p.d;
         if (seg < 2) {
-            const float2* rt = p.rope + (size_t)j.rp.pos * (p.hd / 2) + ((j0 % p.hd) >> 1) + 2 * quad;
+            const float2* rt = p.rope + (size_t)j.rp.pos * (HD / 2) + ((j0 % HD) >> 1) + 2 * quad;
             j.rot0 = rt[0];
             j.rot1 = rt[1];
         }
@@ -499,11 +505,14 @@ __device__ __forceinline__ IoJobs load_io_jobs(const XP& p, const Ctx& c, int io
 // The reduce job of an IO wave for product `kind` (X_A .. X_E, a run-time value: the four products share
 // one copy of this code, which keeps the kernel inside the instruction cache) of `layer`; none: returns
 // at once.  resid: the wave's strip of the residual stream (owners of Wo / W2 strips).
+template <int HD>
 __device__ __forceinline__ void reduce_job(const XP& p, Ctx& c, const IoJobs& jb, int kind, int layer, int lane, f32x4& resid,
-                                           unsigned stage) {
+                                           unsigned stage, bool second = false) {
     // (selects, not indexing with a run-time value: that would move the structure into memory)
-    const int s = kind == X_A ? jb.sA : kind == X_C ? jb.sC : kind == X_D ? jb.sD : jb.sE;
+    // second: the wave's second W1|W3 strip; the flag goes up behind the wave's last strip of the stage
+    const int s = (HD != 64 && second) ? jb.sD2 : kind == X_A ? jb.sA : kind == X_C ? jb.sC : kind == X_D ? jb.sD : jb.sE;
     const int slot = kind == X_A ? jb.tA : kind == X_C ? jb.tC : kind == X_D ? jb.tD : jb.tE;
+    const bool last_of_wave = HD == 64 || second || kind != X_D || jb.sD2 < 0;
     if (s < 0) return;
     const int col = lane & 15, quad = lane >> 4, d = p.d, ring = layer & 1;
     const bool live = col < p.MR;
@@ -524,15 +533,15 @@ __device__ __forceinline__ void reduce_job(const XP& p, Ctx& c, const IoJobs& jb
     v *= rn;
     stamp(c, stage, 5);
     if (kind == X_A) {
-        const int seg = (s * 16) / d, j0 = s * 16 - seg * d, h = j0 / p.hd;
+        const int seg = (s * 16) / d, j0 = s * 16 - seg * d, h = j0 / HD;
         const float a0 = v[0] * jb.rot0.x - v[1] * jb.rot0.y, b0 = v[0] * jb.rot0.y + v[1] * jb.rot0.x;
         const float a1 = v[2] * jb.rot1.x - v[3] * jb.rot1.y, b1 = v[2] * jb.rot1.y + v[3] * jb.rot1.x;
         if (live) {
-            const int hl = h - p.hd0[c.x], f0 = j0 % p.hd + 4 * quad;   // head among the XCD's, first of the lane's four features
+            const int hl = h - p.hd0[c.x], f0 = j0 % HD + 4 * quad;   // head among the XCD's, first of the lane's four features
             if (seg == 0) {   // queries of this XCD's heads, scaled by 1 / sqrt(head dimension): {value, tag} pairs
-                v4u* q = reinterpret_cast<v4u*>(buf + p.o_q + ((size_t)col * (p.KpO - 8) + hl * p.hd + f0) * 8);
-                q[0] = (v4u){__float_as_uint(a0 * p.qscale), tag, __float_as_uint(b0 * p.qscale), tag};
-                q[1] = (v4u){__float_as_uint(a1 * p.qscale), tag, __float_as_uint(b1 * p.qscale), tag};
+                v4u* q = reinterpret_cast<v4u*>(buf + p.o_q + ((size_t)col * (p.KpO - 8) + hl * HD + f0) * 8);
+                q[0] = (v4u){__float_as_uint(a0 * (HD == 64 ? 0.125f : 0.08838834764831845f)), tag, __float_as_uint(b0 * (HD == 64 ? 0.125f : 0.08838834764831845f)), tag};
+                q[1] = (v4u){__float_as_uint(a1 * (HD == 64 ? 0.125f : 0.08838834764831845f)), tag, __float_as_uint(b1 * (HD == 64 ? 0.125f : 0.08838834764831845f)), tag};
             } else {
                 // keys (rotated) / values as fp16 pairs: into the cache for the steps to come (valid rows), and
                 // as tagged pairs for this launch's attention jobs, which poll them ({pair, tag, pair, tag})
@@ -541,10 +550,10 @@ __device__ __forceinline__ void reduce_job(const XP& p, Ctx& c, const IoJobs& jb
                 const unsigned p23 = (unsigned)__builtin_bit_cast(unsigned short, h2) | ((unsigned)__builtin_bit_cast(unsigned short, h3) << 16);
                 if (jb.rp.valid) {
                     _Float16* dst = (seg == 1 ? p.Kc : p.Vc) +
-                                    ((((size_t)layer * p.Smax + jb.rp.seq) * p.H + h) * p.Tmax + jb.rp.slot) * p.hd + f0;
+                                    ((((size_t)layer * p.Smax + jb.rp.seq) * p.H + h) * p.Tmax + jb.rp.slot) * HD + f0;
                     *reinterpret_cast<uint2*>(dst) = make_uint2(p01, p23);
                 }
-                *reinterpret_cast<v4u*>(buf + p.o_kv + ((((size_t)(seg - 1) * 16 + col) * ((p.KpO - 8) / p.hd) + hl) * (p.hd / 4) + f0 / 4) * 16) =
+                *reinterpret_cast<v4u*>(buf + p.o_kv + ((((size_t)(seg - 1) * 16 + col) * ((p.KpO - 8) / HD) + hl) * (HD / 4) + f0 / 4) * 16) =
                     (v4u){p01, tag, p23, tag};
             }
         }
@@ -568,7 +577,7 @@ __device__ __forceinline__ void reduce_job(const XP& p, Ctx& c, const IoJobs& jb
         if (kind == X_E && layer == p.L - 1 && live)   // final hidden rows, for the kernels that follow
             *reinterpret_cast<f32x4*>(p.X + (size_t)col * d + s * 16 + 4 * quad) = resid;
     }
-    if (kind != X_A) raise_flag(p, c, flag, slot, tag);   // (queries, keys and values carry their own tags)
+    if (kind != X_A && last_of_wave) raise_flag(p, c, flag, slot, tag);   // (queries, keys and values carry their own tags)
 }
 
 // Output projection: logits of the strip's 16 vocabulary entries for every row.
@@ -927,7 +936,7 @@ __device__ __forceinline__ void compute_stage(const XP& p, const Ctx& c, const G
                                               int Kp, v4u (&w)[NSW * KTM], Prefetch&& prefetch) {
     const int lane = threadIdx.x & 63;
     const uint16_t* act_hi = s.act0 + (size_t)(stage & 1u) * s.act_elems;
-    const uint16_t* act_lo = act_hi + (size_t)16 * Kp;
+    const uint16_t* act_lo = act_hi + (size_t)p.MR * Kp;
     const unsigned tag = product_tag(p, c, KIND, layer);
     const int ring = KIND == X_LM ? 0 : (layer & 1);
     stamp(c, stage, 0);
@@ -959,6 +968,7 @@ __device__ __forceinline__ void compute_stage(const XP& p, const Ctx& c, const G
 // IO waves: wait for the producers of the stage input on this XCD, stage the XCD's slice in LDS, then -
 // while the compute waves multiply - do the wave's reduce job of this stage.  kind is a run-time value
 // (X_A .. X_LM): one copy of this code serves every product.
+template <int HD>
 __device__ __forceinline__ void io_stage(const XP& p, Ctx& c, const IoJobs& jb, const Lds& s, int kind, int layer, unsigned stage,
                                          f32x4& resid) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -984,6 +994,12 @@ __device__ __forceinline__ void io_stage(const XP& p, Ctx& c, const IoJobs& jb, 
         for (int i = 0; i < 16; ++i) v[i] = i < per_xcd ? __uint_as_float(ld_u32(ss + i * 16)) : 0.f;
 #pragma unroll
         for (int i = 0; i < 16; ++i) a += v[i];
+        if (HD != 64 && per_xcd > 16) {   // (the wide shape: up to 32 strips per XCD)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[i] = 16 + i < per_xcd ? __uint_as_float(ld_u32(ss + (16 + i) * 16)) : 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) a += v[i];
+        }
         s.ss0[(stage & 1u) * 16 + lane] = a;
     }
     if (!normed || wave != kCW + kNIO - 1)
@@ -992,7 +1008,10 @@ __device__ __forceinline__ void io_stage(const XP& p, Ctx& c, const IoJobs& jb, 
     stamp(c, stage, 2);
     lds_barrier();
     if (kind == X_LM) reduce_logits(p, c, wave - kCW, lane);
-    else reduce_job(p, c, jb, kind, layer, lane, resid, stage);
+    else {
+        reduce_job<HD>(p, c, jb, kind, layer, lane, resid, stage);
+        if (HD != 64 && kind == X_D && jb.sD2 >= 0) reduce_job<HD>(p, c, jb, kind, layer, lane, resid, stage, true);
+    }
     stamp(c, stage, 3);
 }
 
@@ -1038,7 +1057,7 @@ __device__ __forceinline__ void compute_main(const XP& p, const Ctx& c, const Ld
 template <int RPJ, int HD>
 __device__ __forceinline__ void io_main(const XP& p, Ctx& c, const Lds& s) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const IoJobs jb = load_io_jobs(p, c, wave - kCW, lane);
+    const IoJobs jb = load_io_jobs<HD>(p, c, wave - kCW, lane);
     f32x4 resid = (f32x4){0.f, 0.f, 0.f, 0.f};   // the wave's strip of the residual stream (owners of Wo / W2 strips)
     if (jb.sE >= 0) {   // Prologue: the owners of the residual strips pick their slice of the embedded rows up
                                 // and publish it as stage E of "layer -1" would.
@@ -1057,7 +1076,7 @@ __device__ __forceinline__ void io_main(const XP& p, Ctx& c, const Lds& s) {
     for (unsigned stage = 0; stage < nstages; ++stage) {
         const int l = (int)(stage / 5u), st = (int)(stage - 5u * (unsigned)l);
         if (st == 1) attn_io<RPJ, HD>(p, c, jb, s, l, stage, joins);
-        else io_stage(p, c, jb, s, l == p.L ? X_LM : st == 0 ? X_A : st == 2 ? X_C : st == 3 ? X_D : X_E, l, stage, resid);
+        else io_stage<HD>(p, c, jb, s, l == p.L ? X_LM : st == 0 ? X_A : st == 2 ? X_C : st == 3 ? X_D : X_E, l, stage, resid);
     }
 }
 
@@ -1068,7 +1087,7 @@ __global__ __launch_bounds__(kThreads, 1) void verify_xcd_kernel(const XP* __res
     const XP& p = *params;
     extern __shared__ uint4 smem_raw[];
     Lds s;
-    const size_t act_elems = (size_t)2 * 16 * max(max(p.KpA, p.KpO), p.KpH);
+    const size_t act_elems = (size_t)2 * p.MR * max(max(p.KpA, p.KpO), p.KpH);
     s.join = reinterpret_cast<unsigned*>(smem_raw);
     s.act0 = reinterpret_cast<uint16_t*>(smem_raw + 1);
     s.act_elems = (unsigned)act_elems;
@@ -1161,7 +1180,7 @@ void build_xcd_plan(const hawk_ctx* c, XcdPlan* P) {
     for (int x = 0; x < kXcd; ++x) {
         P->KT[X_A][x] = P->KT[X_D][x] = P->KT[X_LM][x] = d / 32 / kXcd;
         P->kt0[X_A][x] = P->kt0[X_D][x] = P->kt0[X_LM][x] = x * (d / 32 / kXcd);
-        P->KT[X_C][x] = 2 * (hs[x + 1] - hs[x]); P->kt0[X_C][x] = 2 * hs[x];
+        P->KT[X_C][x] = (c->hd / 32) * (hs[x + 1] - hs[x]); P->kt0[X_C][x] = (c->hd / 32) * hs[x];
         P->KT[X_E][x] = es[x + 1] - es[x]; P->kt0[X_E][x] = es[x];
         maxO = std::max(maxO, P->KT[X_C][x] * 32);
         maxH = std::max(maxH, P->KT[X_E][x] * 32);
@@ -1211,12 +1230,12 @@ void build_xcd_plan(const hawk_ctx* c, XcdPlan* P) {
     }
     P->total_tiles = (size_t)c->L * P->layer_tiles + (off - P->layer_tiles);
     // reduce jobs: the IO wave (unit, wave) of the owner XCD that finishes a strip, and its flag slot
-    P->rtab.assign((size_t)X_NK * kXcd * kPer * kNIO * 2, -1);
+    P->rtab.assign((size_t)X_NK * kXcd * kPer * kNIO * 3, -1);
     for (int f = 0; f < F_NF; ++f)
         for (int x = 0; x < kXcd; ++x) P->njobs[f][x] = 0;
     auto owner_of = [&](int k, int s) -> int {
         if (k == X_A) {   // the XCD that owns the strip's head
-            const int h = ((s * 16) % d) / 64;
+            const int h = ((s * 16) % d) / c->hd;
             for (int x = 0; x < kXcd; ++x)
                 if (h < hs[x + 1]) return x;
         }
@@ -1238,14 +1257,21 @@ void build_xcd_plan(const hawk_ctx* c, XcdPlan* P) {
             // QKV strips: the last units of the XCD, three waves each - the first units run the attention
             // jobs and should start on their keys and values at once.  W1|W3 strips go round the units.
             const int nu = (total[x] + kNIO - 2) / (kNIO - 1);
-            const int j = (k == X_C || k == X_E) ? i : k == X_A ? kPer - 1 - i % nu : i % kPer;
-            const int w = (k == X_C || k == X_E) ? kNIO - 1 : k == X_A ? i / nu : i / kPer;
-            if (j >= kPer || w >= ((k == X_C || k == X_E) ? kNIO : kNIO - 1) || i >= kMaxJobs) { P->ok = false; return; }
-            int16_t* e = &P->rtab[((((size_t)k * kXcd + x) * kPer + j) * kNIO + w) * 2];
-            e[0] = (int16_t)s;
-            e[1] = (int16_t)i;
+            const int slots_d = kPer * (kNIO - 1);   // W1|W3: IO waves 0 .. 2 of every unit; beyond that a wave takes a second strip
+            const bool second = k == X_D && i >= slots_d;
+            const int id = second ? i - slots_d : i;
+            const int j = (k == X_C || k == X_E) ? i : k == X_A ? kPer - 1 - i % nu : id % kPer;
+            const int w = (k == X_C || k == X_E) ? kNIO - 1 : k == X_A ? i / nu : id / kPer;
+            if (j >= kPer || w >= ((k == X_C || k == X_E) ? kNIO : kNIO - 1) || id >= kMaxJobs) { P->ok = false; return; }
+            int16_t* e = &P->rtab[((((size_t)k * kXcd + x) * kPer + j) * kNIO + w) * 3];
+            if (second) {
+                e[2] = (int16_t)s;
+            } else {
+                e[0] = (int16_t)s;
+                e[1] = (int16_t)i;
+            }
         }
-        for (int x = 0; x < kXcd; ++x) P->njobs[flag_of[k]][x] = count[x];
+        for (int x = 0; x < kXcd; ++x) P->njobs[flag_of[k]][x] = k == X_D ? std::min(count[x], kPer * (kNIO - 1)) : count[x];
     }
     const int per_round = kPer * kCW * P->NSW[X_LM];
     (void)per_round;
@@ -1286,7 +1312,7 @@ size_t xcd_buf_layout(const XcdPlan* P, XP* p) {
     const size_t kv = take((size_t)2 * 16 * ((P->KpO - 8) / 64) * 16 * 16);   // appended keys | values: [2][16 rows][heads][16 words] {fp16 pair, tag} x 2
     const size_t o = take((size_t)2 * 16 * P->KpO * 2), x2 = take((size_t)2 * 16 * P->KpA * 2);
     const size_t h = take((size_t)2 * 16 * P->KpH * 2);
-    const size_t ss = take((size_t)2 * 16 * 16 * 4);   // sums of squares of the XCD's strips: [2][strips of an XCD <= 16][16 rows]
+    const size_t ss = take((size_t)2 * 32 * 16 * 4);   // sums of squares of the XCD's strips: [2][strips of an XCD <= 32][16 rows]
     if (p) { p->o_a = a; p->o_q = q; p->o_kv = kv; p->o_o = o; p->o_x2 = x2; p->o_h = h; p->o_ss = ss; }
     return at;
 }
@@ -1397,8 +1423,8 @@ namespace {
 
 struct XcdShape { int NA, KA, NC, KC, ND, KD, NE, KE, NL; };
 
-size_t xcd_lds_bytes(const hawk_ctx* c, const XcdPlan* P, int RPJ) {
-    const size_t act = (size_t)2 * 16 * std::max(std::max(P->KpA, P->KpO), P->KpH) * 2;
+size_t xcd_lds_bytes(const hawk_ctx* c, const XcdPlan* P, int RPJ, int MR) {
+    const size_t act = (size_t)2 * MR * std::max(std::max(P->KpA, P->KpO), P->KpH) * 2;   // two planes of the rows in flight
     return 16 + 2 * act + (size_t)(kNIO * RPJ * (c->hd + 4) + RPJ * c->hd + 32) * 4 + 64;
 }
 
@@ -1478,7 +1504,8 @@ int launch_verify_xcd(hawk_ctx* c, int k, const int32_t* tree_depth, const unsig
         if (hipStreamSynchronize(c->stream) != hipSuccess) return -1;   // the sources are locals: the copies must have read them
         P->params.assign(reinterpret_cast<const uint8_t*>(&p), reinterpret_cast<const uint8_t*>(&p) + sizeof(XP));
     }
-    const size_t lds = xcd_lds_bytes(c, P, RPJ);
+    const size_t lds = xcd_lds_bytes(c, P, RPJ, c->S * RS);
+    if (lds > (size_t)160 * 1024) return -1;
     if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return -1;
     const XP* dev_params = wsp<XP>(c, o.xp);
     unsigned epoch0 = P->epoch;
