@@ -122,6 +122,7 @@ __device__ __forceinline__ T* fresh(T* ptr) {
 // like any other load.
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 constexpr int kDevScope = 16;   // cache-policy bit of device scope in the buffer instructions
+constexpr int kNonTemporal = 2; // ... of a streaming access (no reuse expected)
 __device__ __forceinline__ rsrc_t make_rsrc(const void* base) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7FFFFFFF, 0x00020000);
 }
@@ -1054,6 +1055,144 @@ __device__ __forceinline__ void compute_main(const XP& p, const Ctx& c, const Ld
     compute_stage<X_LM, NL, KA>(p, c, gL, s, p.L, stage++, p.KpA, wL, [] {});
 }
 
+// ------------------------------------------------------------------------- compute waves, streamed
+//
+// The wide shape (d = 4096): a wave's tiles of one layer (~1.6 MB) are far more than its registers hold,
+// so the weights stream through two register buffers of 16 tiles.  A stage is a list of items - (strip,
+// chunk of 16 k-tiles), strips outermost - with an even count, so that an item's buffer is known at
+// compile time; a buffer is refilled with the item two ahead as soon as its products are done, and the
+// last two refills of a stage fetch the first two items of the next stage: during the exchange of
+// activations between the stages two items per wave (32 MB chip-wide) are on their way.  One accumulator
+// per strip (both halves of the split activations add into it); all partial sums of a stage are stored
+// at its end, behind the products, so that no store is pending while loads are waited for one by one.
+template <int KTM, int SI, int KC>
+__device__ __forceinline__ void issue_item(const XP& p, const GJob& g, u64 layer_base, int lane, v4u (&buf)[16]) {
+    // A buffer resource per item whose extent is the tiles the item really has: requests beyond it (an
+    // absent strip, k-tiles past the XCD's slice) come back as zeros without touching memory.
+    int ns = g.ns, KT = g.KT;
+    asm volatile("" : "+s"(ns), "+s"(KT));   // worked out per item, not for every item of the layer ahead of the loop
+    const int have = SI < ns ? min(max(KT - KC * 16, 0), 16) : 0;
+    // (the job's fields are in scalar registers - see compute_main_stream - and so is everything here)
+    const char* base = reinterpret_cast<const char*>(p.wpack) + (layer_base + g.tile0 + (u64)SI * KT + KC * 16) * 1024;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {   // four tiles per resource: their offsets fit the instruction's immediate field
+        if (KC * 16 + q * 4 < KTM) {
+            const rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base + q * 4096), 0, max(have - q * 4, 0) * 1024, 0x00020000);
+#pragma unroll
+            for (int kt = q * 4; kt < q * 4 + 4; ++kt)
+                if (KC * 16 + kt < KTM) buf[kt] = __builtin_amdgcn_raw_buffer_load_b128(r, (unsigned)lane * 16u + (kt - q * 4) * 1024u, 0, kNonTemporal);
+        }
+    }
+}
+
+// Items IT, IT + 1, .. of a stage of NS strips x NKC chunks; cur holds item IT, nxt item IT + 1.
+template <int NS, int NKC, int KTM, int IT, class Next>
+__device__ __forceinline__ void stream_items(const XP& p, const GJob& g, u64 layer_base, int lane, const uint16_t* act_hi,
+                                             const uint16_t* act_lo, v4u (&cur)[16], v4u (&nxt)[16], f32x4 (&acc)[NS], Next&& next) {
+    if constexpr (IT < NS * NKC) {
+        constexpr int si = IT / NKC, kc = IT % NKC;
+#pragma unroll
+        for (int kt = 0; kt < 16; ++kt) {
+            if (kc * 16 + kt < KTM) {
+                const bf16x8 h = __builtin_bit_cast(bf16x8, *reinterpret_cast<const v4u*>(act_hi + (kc * 16 + kt) * 32));
+                const bf16x8 l = __builtin_bit_cast(bf16x8, *reinterpret_cast<const v4u*>(act_lo + (kc * 16 + kt) * 32));
+                const bf16x8 a = __builtin_bit_cast(bf16x8, cur[kt]);
+                acc[si] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, h, acc[si], 0, 0, 0);
+                acc[si] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, l, acc[si], 0, 0, 0);
+            }
+        }
+        if constexpr (IT + 2 < NS * NKC) {   // the freed buffer takes the item two ahead
+            issue_item<KTM, (IT + 2) / NKC, (IT + 2) % NKC>(p, g, layer_base, lane, cur);
+            stream_items<NS, NKC, KTM, IT + 1>(p, g, layer_base, lane, act_hi, act_lo, nxt, cur, acc, next);
+        } else if constexpr (IT + 2 == NS * NKC) {
+            next(0, cur);   // first item of the next stage
+            stream_items<NS, NKC, KTM, IT + 1>(p, g, layer_base, lane, act_hi, act_lo, nxt, cur, acc, next);
+        }
+    }
+}
+
+// One product stage of the streamed kind.  On entry b0 / b1 hold (or are about to receive) items 0 / 1.
+// next(i, buf) requests item i (0 or 1) of the following stage into buf.
+template <int KIND, int NS, int NKC, int KTM, class Next>
+__device__ __forceinline__ void stream_stage(const XP& p, const Ctx& c, const GJob& g, const Lds& s, int layer, unsigned stage, int Kp,
+                                             u64 layer_base, v4u (&b0)[16], v4u (&b1)[16], Next&& next) {
+    static_assert((NS * NKC) % 2 == 0 && NS * NKC >= 2, "a stage has an even number of items");
+    int lane = threadIdx.x & 63;
+    asm volatile("" : "+v"(lane));   // what depends on the lane is worked out again in every stage: kept across the
+                                     // layer loop for all stages at once it would not fit the registers next to the tiles
+    const int col = lane & 15, kg = lane >> 4;
+    const uint16_t* act_hi = s.act0 + (size_t)(stage & 1u) * s.act_elems + (size_t)(col < p.MR ? col : 0) * Kp + kg * 8;
+    const uint16_t* act_lo = act_hi + (size_t)p.MR * Kp;
+    const unsigned tag = product_tag(p, c, KIND, layer);
+    const int ring = KIND == X_LM ? 0 : (layer & 1);
+    const unsigned pbit = parity_bit(c, KIND, layer, col);
+    f32x4 acc[NS];
+#pragma unroll
+    for (int i = 0; i < NS; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    stamp(c, stage, 0);
+    lds_barrier();   // the XCD's slice of the stage input is in LDS
+    stamp(c, stage, 1);
+    stream_items<NS, NKC, KTM, 0>(p, g, layer_base, lane, act_hi, act_lo, b0, b1, acc, next);
+    if (c.dbg) {
+        asm volatile("" :: "v"(acc[NS - 1]));
+        stamp(c, stage, 3);
+    }
+    if (KIND != X_C && KIND != X_E && kg == 0 && col < p.MR && g.ns > 0)   // this XCD's share of the rows' sums of squares rides along
+        st_tagged(p.pss[KIND] + ((((size_t)ring * kXcd + c.x) * kPer + c.j) * kCW + (threadIdx.x >> 6)) * 32 + col,
+                  s.ss0[(stage & 1u) * 16 + col], tag);
+    const rsrc_t out = make_rsrc(p.part[KIND]);
+    const unsigned at8 = (unsigned)((((size_t)ring * kXcd + c.x) * p.nstrips[KIND] + g.s0) * 16 + col) * 64u + kg * 16u;
+#pragma unroll
+    for (int si = 0; si < NS; ++si) {
+        const f32x4 v = acc[si];
+        if (si < g.ns && col < p.MR)
+            st_16(out, at8 + si * 1024u, (v4u){(__float_as_uint(v[0]) & ~1u) | pbit, (__float_as_uint(v[1]) & ~1u) | pbit,
+                                               (__float_as_uint(v[2]) & ~1u) | pbit, (__float_as_uint(v[3]) & ~1u) | pbit});
+    }
+    stamp(c, stage, 2);
+    next(1, b1);   // behind the stores: they leave the unit first
+    stamp(c, stage, 4);
+}
+
+// Template arguments: strips per compute wave of QKV, Wo, W1|W3 (rounded up to even), W2, the output
+// projection; k-tiles of an XCD's slice of the hidden vector (the other slices have 16).
+template <int NA, int NC, int ND, int NE, int KE, int NL>
+__device__ __forceinline__ void compute_main_stream(const XP& p, const Ctx& c, const Lds& s) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    auto job = [&](int kind) {   // the same in every lane: kept in scalar registers
+        GJob g = load_gjob(p, kind, c, wave);
+        g.s0 = __builtin_amdgcn_readfirstlane(g.s0); g.ns = __builtin_amdgcn_readfirstlane(g.ns); g.KT = __builtin_amdgcn_readfirstlane(g.KT);
+        g.tile0 = ((u64)__builtin_amdgcn_readfirstlane((unsigned)(g.tile0 >> 32)) << 32) | __builtin_amdgcn_readfirstlane((unsigned)g.tile0);
+        return g;
+    };
+    const GJob gA = job(X_A), gC = job(X_C), gD = job(X_D), gE = job(X_E), gL = job(X_LM);
+    constexpr int NKE = (KE + 15) / 16;
+    v4u b0[16], b1[16];
+    issue_item<16, 0, 0>(p, gA, 0, lane, b0);
+    issue_item<16, 1, 0>(p, gA, 0, lane, b1);
+    unsigned stage = 0;
+    for (int l = 0; l < p.L; ++l) {
+        const u64 lb = (u64)l * p.layer_tiles;
+        const bool more = l + 1 < p.L;
+        stream_stage<X_A, NA, 1, 16>(p, c, gA, s, l, stage++, p.KpA, lb, b0, b1, [&](int i, v4u (&b)[16]) {
+            if (i == 0) issue_item<16, 0, 0>(p, gC, lb, lane, b); else issue_item<16, 1, 0>(p, gC, lb, lane, b);
+        });
+        ++stage;   // attention: the IO waves' business
+        stream_stage<X_C, NC, 1, 16>(p, c, gC, s, l, stage++, p.KpO, lb, b0, b1, [&](int i, v4u (&b)[16]) {
+            if (i == 0) issue_item<16, 0, 0>(p, gD, lb, lane, b); else issue_item<16, 1, 0>(p, gD, lb, lane, b);
+        });
+        stream_stage<X_D, ND, 1, 16>(p, c, gD, s, l, stage++, p.KpA, lb, b0, b1, [&](int i, v4u (&b)[16]) {
+            if (i == 0) issue_item<KE, 0, 0>(p, gE, lb, lane, b); else issue_item<KE, 1 / NKE, 1 % NKE>(p, gE, lb, lane, b);
+        });
+        stream_stage<X_E, NE, NKE, KE>(p, c, gE, s, l, stage++, p.KpH, lb, b0, b1, [&](int i, v4u (&b)[16]) {
+            const GJob& gn = more ? gA : gL;   // (the output projection's tiles follow the layers in the stream)
+            const u64 nb = more ? lb + p.layer_tiles : 0;
+            if (i == 0) issue_item<16, 0, 0>(p, gn, nb, lane, b); else issue_item<16, 1, 0>(p, gn, nb, lane, b);
+        });
+    }
+    stream_stage<X_LM, NL, 1, 16>(p, c, gL, s, p.L, stage++, p.KpA, 0, b0, b1, [](int, v4u (&)[16]) {});
+}
+
 template <int RPJ, int HD>
 __device__ __forceinline__ void io_main(const XP& p, Ctx& c, const Lds& s) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -1106,6 +1245,29 @@ __global__ __launch_bounds__(kThreads, 1) void verify_xcd_kernel(const XP* __res
     else compute_main<NA, KA, NC, KC, ND, KD, NE, KE, NL>(p, c, s);
 }
 
+// The same pass for the wide shape: the compute waves stream their tiles (see compute_main_stream).
+template <int NA, int NC, int ND, int NE, int KE, int NL, int RPJ, int HD>
+__global__ __launch_bounds__(kThreads, 1) void verify_xcd_stream_kernel(const XP* __restrict__ params, unsigned epoch0, unsigned par, unsigned par_lm,
+                                                                        u64* dbg) {
+    const XP& p = *params;
+    extern __shared__ uint4 smem_raw[];
+    Lds s;
+    const size_t act_elems = (size_t)2 * p.MR * max(max(p.KpA, p.KpO), p.KpH);
+    s.join = reinterpret_cast<unsigned*>(smem_raw);
+    s.act0 = reinterpret_cast<uint16_t*>(smem_raw + 1);
+    s.act_elems = (unsigned)act_elems;
+    s.part = reinterpret_cast<float*>(s.act0 + 2 * act_elems);
+    s.qs = s.part + kNIO * RPJ * (HD + 4);
+    s.ss0 = s.qs + RPJ * HD;
+    if (threadIdx.x == 0) *s.join = 0u;
+    __syncthreads();
+    Ctx c;
+    c.x = blockIdx.x % kXcd; c.j = blockIdx.x / kXcd; c.epoch0 = epoch0; c.par = par; c.par_lm = par_lm; c.dead = false; c.err = p.err; c.dbg = dbg;
+    if (xcc_id() != c.x) give_up(c);
+    if ((threadIdx.x >> 6) >= kCW) io_main<RPJ, HD>(p, c, s);
+    else compute_main_stream<NA, NC, ND, NE, KE, NL>(p, c, s);
+}
+
 // Copies one matrix into the packed order: tile T of the stream is (strip, k-tile) = desc[T]; lane l
 // holds row l % 16, columns 8 * (l / 16) .. + 7 of that tile.  pairs > 0: W1 | W3 with strip rows 0..7
 // from W1 and 8..15 from W3 (pairs = rows of W1).
@@ -1147,8 +1309,10 @@ struct XcdPlan {
 namespace {
 
 bool xcd_shape_ok(const hawk_ctx* c) {
-    if (c->cfg.dtype != HAWK_BF16 || c->hd != 64) return false;
-    if (!((c->d == 1280 && c->m == 3456 && c->H == 20) || (c->d == 768 && c->m == 2048 && c->H == 12))) return false;
+    if (c->cfg.dtype != HAWK_BF16) return false;
+    if (!((c->d == 1280 && c->m == 3456 && c->H == 20 && c->hd == 64) || (c->d == 768 && c->m == 2048 && c->H == 12 && c->hd == 64) ||
+          (c->d == 4096 && c->m == 11008 && c->H == 32 && c->hd == 128)))
+        return false;
     if (c->Vs % (16 * kXcd) || c->d % (32 * kXcd) || c->H < kXcd) return false;
     return true;
 }
@@ -1437,6 +1601,7 @@ bool xcd_ok(const hawk_ctx* c, int k) {
     if (MR > 16) return false;
     for (int x = 0; x < kXcd; ++x)
         if ((P->hd0[x + 1] - P->hd0[x]) * c->S * ((RS + 1) / 2) > kPer) return false;
+    if (xcd_lds_bytes(c, P, 2, MR) > (size_t)160 * 1024) return false;
     return true;
 }
 
@@ -1489,6 +1654,15 @@ int launch_verify_xcd(hawk_ctx* c, int k, const int32_t* tree_depth, const unsig
         kern = RPJ == 1 ? reinterpret_cast<const void*>(verify_xcd_kernel<2, 5, 1, 6, 4, 5, 1, 14, 4, 1>)
                         : reinterpret_cast<const void*>(verify_xcd_kernel<2, 5, 1, 6, 4, 5, 1, 14, 4, 2>);
         if (P->NSW[X_A] > 2 || P->NSW[X_C] > 1 || P->NSW[X_D] > 4 || P->NSW[X_E] > 1 || P->NSW[X_LM] > 8) return -1;
+    } else if (c->d == 4096) {
+        // streamed: QKV 768 strips / 128 waves -> 6, Wo 256 -> 2, W1|W3 1376 -> 11 (12 with an empty one), W2 256 -> 2 x 3 chunks
+        // of its 43 k-tiles, output 512 -> 4
+        p.lm_rounds = 1;
+        kern = RPJ == 1 ? reinterpret_cast<const void*>(verify_xcd_stream_kernel<6, 2, 12, 2, 43, 4, 1, 128>)
+                        : reinterpret_cast<const void*>(verify_xcd_stream_kernel<6, 2, 12, 2, 43, 4, 2, 128>);
+        if (P->NSW[X_A] > 6 || P->NSW[X_C] > 2 || P->NSW[X_D] > 12 || P->NSW[X_E] > 2 || P->NSW[X_LM] > 4) return -1;
+        for (int x = 0; x < kXcd; ++x)
+            if (P->KT[X_A][x] != 16 || P->KT[X_C][x] != 16 || P->KT[X_E][x] > 43) return -1;
     } else {
         // d = 768: QKV 144 -> 2, Wo 48 -> 1, W1|W3 256 -> 2, W2 48 -> 1, output 8 in two rounds of 4
         p.lm_rounds = 2;
