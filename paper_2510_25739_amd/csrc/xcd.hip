@@ -55,6 +55,10 @@ constexpr unsigned kSpinLimit = 1u << 20;
 constexpr int kNIT = 4;                          // cache positions per lane group and register buffer
 constexpr int kPaceGap = 0, kPaceTiles = 6;   // weight requests go out six tiles per wave at a time (see issue_paced)
 constexpr int kRing = 2;                         // partial-sum areas and XCD buffers alternate between layers
+#ifndef HAWK_STREAM_MODE
+#define HAWK_STREAM_MODE 2
+#endif
+constexpr int kStreamMode = HAWK_STREAM_MODE;
 constexpr int kMaxJobs = 128;                    // flag words of one XCD and stage that others wait for (one per IO wave with a job)
 
 enum XKind { X_A = 0, X_C, X_D, X_E, X_LM, X_NK };   // QKV, Wo, W1|W3, W2, output projection
@@ -106,6 +110,13 @@ __device__ __forceinline__ unsigned xcc_id() {
     unsigned v;
     asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(v));
     return v & 0xFu;
+}
+// A 64-bit value that is the same in every lane, moved to scalar registers.  (The builtin returns int: each
+// half goes through unsigned, or a low half with its top bit set would spill ones over the high half.)
+__device__ __forceinline__ unsigned long long uniform64(unsigned long long v) {
+    const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)v);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(v >> 32));
+    return ((unsigned long long)hi << 32) | (unsigned long long)lo;
 }
 __device__ __forceinline__ void compiler_fence() { __atomic_signal_fence(__ATOMIC_SEQ_CST); }
 // A pointer the compiler must treat as new: addresses derived from it are computed where they are used
@@ -596,7 +607,9 @@ __device__ __forceinline__ void reduce_logits(const XP& p, Ctx& c, int io, int l
 
 // ------------------------------------------------------------------------- attention (as one unit's job)
 
-struct AttnAcc { float acc[8], mx, den; };
+// A lane's share of one row's attention: the weighted sum over its 8 * NCH features, running maximum, denominator.
+template <int NCH>
+struct AttnAcc { float acc[8 * NCH], mx, den; };
 
 __device__ __forceinline__ float sum8(float v) {
     v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
@@ -604,7 +617,7 @@ __device__ __forceinline__ float sum8(float v) {
     v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));
     return v;
 }
-__device__ __forceinline__ void halves8(v4u raw, float (&f)[8]) {
+__device__ __forceinline__ void halves8(v4u raw, float* f) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         f[2 * e] = (float)__builtin_bit_cast(_Float16, (unsigned short)(raw[e] & 0xFFFFu));
@@ -612,55 +625,54 @@ __device__ __forceinline__ void halves8(v4u raw, float (&f)[8]) {
     }
 }
 
-// Sum over the LPP (8 or 16) lanes that share a cache position.
-template <int LPP>
-__device__ __forceinline__ float sum_lanes(float v) {
-    v = sum8(v);
-    if (LPP == 16) v += lane_xor8(v);
-    return v;
-}
-
+// Eight lanes share a cache position; lane dg of them holds features 64 c + 8 dg .. + 7 of every 64-feature
+// chunk c of the head (NCH chunks: one 16-byte load each).
+//
 // One cache position per lane group; row r0 + r of the sequence sees it iff bit r0 + r of vis is set.
-template <int RPJ, int LPP = 8>
-__device__ __forceinline__ void attend(const float (&q)[RPJ][8], int r0, v4u kraw, v4u vraw, unsigned vis, int ke,
-                                       AttnAcc (&A)[RPJ]) {
-    float kf[8], vf[8];
-    halves8(kraw, kf);
-    halves8(vraw, vf);
+template <int RPJ, int NCH>
+__device__ __forceinline__ void attend(const float (&q)[RPJ][8 * NCH], int r0, const v4u (&kraw)[NCH], const v4u (&vraw)[NCH], unsigned vis,
+                                       int ke, AttnAcc<NCH> (&A)[RPJ]) {
+    float kf[8 * NCH], vf[8 * NCH];
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+        halves8(kraw[ch], kf + 8 * ch);
+        halves8(vraw[ch], vf + 8 * ch);
+    }
 #pragma unroll
     for (int r = 0; r < RPJ; ++r) {
         float sc = 0.f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) sc += q[r][e] * kf[e];
-        sc = sum_lanes<LPP>(sc);
+        for (int e = 0; e < 8 * NCH; ++e) sc += q[r][e] * kf[e];
+        sc = sum8(sc);
         if (((vis >> (r0 + r)) & 1u) && r0 + r <= ke) {
             const float mn = fmaxf(A[r].mx, sc);
             const float corr = __expf(A[r].mx - mn), pw = __expf(sc - mn);
             A[r].den = A[r].den * corr + pw;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) A[r].acc[e] = A[r].acc[e] * corr + pw * vf[e];
+            for (int e = 0; e < 8 * NCH; ++e) A[r].acc[e] = A[r].acc[e] * corr + pw * vf[e];
             A[r].mx = mn;
         }
     }
 }
 
-// kNIT cache positions per lane group at once: all scores, one running-maximum update per row, then
+// NIT cache positions per lane group at once: all scores, one running-maximum update per row, then
 // the weighted values.
-template <int RPJ, int LPP = 8>
-__device__ __forceinline__ void attend_round(const float (&q)[RPJ][8], int r0, const v4u (&kk)[kNIT], const v4u (&vv)[kNIT],
-                                             int pos0, int stride, int o1, int ke, AttnAcc (&A)[RPJ]) {
-    float sc[RPJ][kNIT];
+template <int RPJ, int NCH, int NIT>
+__device__ __forceinline__ void attend_round(const float (&q)[RPJ][8 * NCH], int r0, const v4u (&kk)[NIT * NCH], const v4u (&vv)[NIT * NCH],
+                                             int pos0, int stride, int o1, int ke, AttnAcc<NCH> (&A)[RPJ]) {
+    float sc[RPJ][NIT];
 #pragma unroll
-    for (int it = 0; it < kNIT; ++it) {
-        float kf[8];
-        halves8(kk[it], kf);
+    for (int it = 0; it < NIT; ++it) {
+        float kf[8 * NCH];
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) halves8(kk[it * NCH + ch], kf + 8 * ch);
         const bool on = pos0 + it * stride < o1;
 #pragma unroll
         for (int r = 0; r < RPJ; ++r) {
             float dd = 0.f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) dd += q[r][e] * kf[e];
-            dd = sum_lanes<LPP>(dd);
+            for (int e = 0; e < 8 * NCH; ++e) dd += q[r][e] * kf[e];
+            dd = sum8(dd);
             sc[r][it] = (on && r0 + r <= ke) ? dd : -1e30f;
         }
     }
@@ -668,27 +680,28 @@ __device__ __forceinline__ void attend_round(const float (&q)[RPJ][8], int r0, c
     for (int r = 0; r < RPJ; ++r) {
         float mn = A[r].mx;
 #pragma unroll
-        for (int it = 0; it < kNIT; ++it) mn = fmaxf(mn, sc[r][it]);
+        for (int it = 0; it < NIT; ++it) mn = fmaxf(mn, sc[r][it]);
         const float corr = __expf(A[r].mx - mn);
         float sum = 0.f;
 #pragma unroll
-        for (int it = 0; it < kNIT; ++it) {
+        for (int it = 0; it < NIT; ++it) {
             sc[r][it] = sc[r][it] > -1e29f ? __expf(sc[r][it] - mn) : 0.f;
             sum += sc[r][it];
         }
         A[r].den = A[r].den * corr + sum;
         A[r].mx = mn;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) A[r].acc[e] *= corr;
+        for (int e = 0; e < 8 * NCH; ++e) A[r].acc[e] *= corr;
     }
 #pragma unroll
-    for (int it = 0; it < kNIT; ++it) {
-        float vf[8];
-        halves8(vv[it], vf);
+    for (int it = 0; it < NIT; ++it) {
+        float vf[8 * NCH];
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) halves8(vv[it * NCH + ch], vf + 8 * ch);
 #pragma unroll
         for (int r = 0; r < RPJ; ++r)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) A[r].acc[e] += sc[r][it] * vf[e];
+            for (int e = 0; e < 8 * NCH; ++e) A[r].acc[e] += sc[r][it] * vf[e];
     }
 }
 
@@ -736,27 +749,34 @@ __device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, c
     if (jb.a_rg < 0) return;   // this unit has no job (the same for all its waves)
     const int io = (threadIdx.x >> 6) - kCW, lane = threadIdx.x & 63;
     const int seq = jb.a_seq, h = jb.a_h, RS = p.RS, r0 = jb.a_rg * RPJ;
-    constexpr int LPP = HD / 8, PPW = 64 / LPP, PS = HD + 4;   // lanes per cache position, positions per wave and look, floats per partial row
+    // lanes per cache position, positions per wave and look, 64-feature chunks of a head, positions per lane group
+    // and register buffer, floats per partial row
+    constexpr int LPP = 8, PPW = 64 / LPP, NCH = HD / 64, NIT = kNIT / NCH, PS = HD + 4;
     const int pg = lane / LPP, dg = lane % LPP;
     const int b = seq % p.B, ke = p.k_eff[b];
     const int kv0 = ke >= 0 ? p.C + p.n[b] - 1 : 0;   // positions cached before this launch
-    const int nrounds = (kv0 + kNIT * kNIO * PPW - 1) / (kNIT * kNIO * PPW);
+    const int nrounds = (kv0 + NIT * kNIO * PPW - 1) / (NIT * kNIO * PPW);
     const size_t head0 = ((((size_t)layer * p.Smax + seq) * p.H + h) * p.Tmax) * HD;   // the head's entries, contiguous
-    const _Float16* Kb = fresh(p.Kc + head0 + dg * 8);
-    const _Float16* Vb = fresh(p.Vc + head0 + dg * 8);
+    // The head's cached keys / values through buffer resources that end at the cached length: requests past it
+    // (the tail of the last round, rounds asked for beyond the last) are answered with zeros and move nothing,
+    // so the requests need no branches - with loads under branches every wait would be for all of them.
+    auto head_rsrc = [&](const _Float16* base) {
+        const u64 a = reinterpret_cast<u64>(base + head0);   // the job is the unit's: the same in every lane
+        const u64 u = uniform64(a);
+        return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(u), 0, __builtin_amdgcn_readfirstlane(kv0 * HD * 2), 0x00020000);
+    };
+    const rsrc_t Kr = head_rsrc(p.Kc), Vr = head_rsrc(p.Vc);
     const unsigned tag = tag_of(c, layer, F_B);
     uint8_t* buf = xcd_buf(p, c.x, layer & 1);
-    v4u ka[kNIT], va[kNIT], kb[kNIT], vb[kNIT], kc[kNIT], vc[kNIT];   // three rounds in flight
+    v4u ka[kNIT], va[kNIT], kb[kNIT], vb[kNIT], kc[kNIT], vc[kNIT];   // three rounds in flight (kNIT = NIT * NCH loads each)
     auto fetch = [&](v4u (&kk)[kNIT], v4u (&vv)[kNIT], int rnd) {
 #pragma unroll
-        for (int it = 0; it < kNIT; ++it) {
-            const int pos = (rnd * kNIT + it) * (kNIO * PPW) + io * PPW + pg;
-            if (pos < kv0) {
-                kk[it] = *reinterpret_cast<const v4u*>(Kb + (size_t)pos * HD);
-                vv[it] = *reinterpret_cast<const v4u*>(Vb + (size_t)pos * HD);
-            } else {
-                kk[it] = (v4u){0u, 0u, 0u, 0u};
-                vv[it] = (v4u){0u, 0u, 0u, 0u};
+        for (int it = 0; it < NIT; ++it) {
+            const unsigned at = (unsigned)(((rnd * NIT + it) * (kNIO * PPW) + io * PPW + pg) * HD + dg * 8) * 2u;
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) {
+                vv[it * NCH + ch] = __builtin_amdgcn_raw_buffer_load_b128(Vr, at + ch * 128u, 0, 0);
+                kk[it * NCH + ch] = __builtin_amdgcn_raw_buffer_load_b128(Kr, at + ch * 128u, 0, 0);
             }
         }
     };
@@ -802,25 +822,29 @@ __device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, c
                 s.qs[r * HD + lane + 64 * e] = (r0 + r < RS && ok) ? __uint_as_float((unsigned)qv[r][e]) : 0.f;
     }
     io_barrier(s, joins, lane);   // the queries are in LDS
+    if (io == 0) stamp(c, stage, 3);
     {
-        AttnAcc A[RPJ];
+        AttnAcc<NCH> A[RPJ];
 #pragma unroll
         for (int r = 0; r < RPJ; ++r) {
             A[r].mx = -1e30f; A[r].den = 0.f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) A[r].acc[e] = 0.f;
+            for (int e = 0; e < 8 * NCH; ++e) A[r].acc[e] = 0.f;
         }
-        float q[RPJ][8];
+        float q[RPJ][8 * NCH];
 #pragma unroll
         for (int r = 0; r < RPJ; ++r) {
-            const float4 qa = *reinterpret_cast<const float4*>(s.qs + r * HD + dg * 8);
-            const float4 qb = *reinterpret_cast<const float4*>(s.qs + r * HD + dg * 8 + 4);
-            q[r][0] = qa.x; q[r][1] = qa.y; q[r][2] = qa.z; q[r][3] = qa.w;
-            q[r][4] = qb.x; q[r][5] = qb.y; q[r][6] = qb.z; q[r][7] = qb.w;
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) {
+                const float4 qa = *reinterpret_cast<const float4*>(s.qs + r * HD + ch * 64 + dg * 8);
+                const float4 qb = *reinterpret_cast<const float4*>(s.qs + r * HD + ch * 64 + dg * 8 + 4);
+                q[r][8 * ch + 0] = qa.x; q[r][8 * ch + 1] = qa.y; q[r][8 * ch + 2] = qa.z; q[r][8 * ch + 3] = qa.w;
+                q[r][8 * ch + 4] = qb.x; q[r][8 * ch + 5] = qb.y; q[r][8 * ch + 6] = qb.z; q[r][8 * ch + 7] = qb.w;
+            }
         }
         auto run = [&](const v4u (&kk)[kNIT], const v4u (&vv)[kNIT], int rnd) {
-            const int pos0 = rnd * kNIT * (kNIO * PPW) + io * PPW + pg;
-            attend_round<RPJ, LPP>(q, r0, kk, vv, pos0, kNIO * PPW, kv0, ke, A);
+            const int pos0 = rnd * NIT * (kNIO * PPW) + io * PPW + pg;
+            attend_round<RPJ, NCH, NIT>(q, r0, kk, vv, pos0, kNIO * PPW, kv0, ke, A);
         };
         // Rows appended by this launch (up to 16: lane group pg takes rows pg and pg + 8), polled as the tagged
         // fp16 pairs this XCD's reduce jobs write.  Who sees them: in a chain row r sees row a iff a <= r, in a
@@ -838,43 +862,69 @@ __device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, c
             }
             return vis;
         };
-        auto fetch_row = [&](int a, unsigned& vis, v4u& kn, v4u& vn) {   // lane dg = features 8 dg .. 8 dg + 7
+        auto fetch_row = [&](int a, unsigned& vis, v4u (&kn)[NCH], v4u (&vn)[NCH]) {   // lane dg = features 64 ch + 8 dg .. + 7
             const rsrc_t kvr = make_rsrc(p.xbuf);
             const unsigned hw = (unsigned)(p.KpO - 8) / (unsigned)HD;   // heads a row of the region has room for
             const unsigned atk = (unsigned)(((size_t)c.x * kRing + (layer & 1)) * p.xcd_bytes + p.o_kv) +
                                  ((((unsigned)(seq * RS + a)) * hw + (unsigned)(h - p.hd0[c.x])) * (unsigned)(HD / 4) + 2u * dg) * 16u;
             const unsigned atv = atk + 16u * hw * (unsigned)(HD / 4) * 16u;
-            v4u k0, k1, v0, v1;
+            v4u k0[NCH], k1[NCH], v0[NCH], v1[NCH];
             bool ok = vis == 0u || c.dead;   // rows nobody of this job sees are not waited for
             for (unsigned spins = 0; spins < kSpinLimit && !__all(ok); ++spins) {
                 if (!ok) {
-                    k0 = ld_16(kvr, atk); k1 = ld_16(kvr, atk + 16u);
-                    v0 = ld_16(kvr, atv); v1 = ld_16(kvr, atv + 16u);
-                    ok = k0[1] == tagA && k0[3] == tagA && k1[1] == tagA && k1[3] == tagA && v0[1] == tagA && v0[3] == tagA &&
-                         v1[1] == tagA && v1[3] == tagA;
-                    if (ok) { kn = (v4u){k0[0], k0[2], k1[0], k1[2]}; vn = (v4u){v0[0], v0[2], v1[0], v1[2]}; }
+                    ok = true;
+#pragma unroll
+                    for (int ch = 0; ch < NCH; ++ch) {   // (a chunk's 64 features: 16 words of 16 bytes)
+                        k0[ch] = ld_16(kvr, atk + ch * 256u); k1[ch] = ld_16(kvr, atk + ch * 256u + 16u);
+                        v0[ch] = ld_16(kvr, atv + ch * 256u); v1[ch] = ld_16(kvr, atv + ch * 256u + 16u);
+                    }
+#pragma unroll
+                    for (int ch = 0; ch < NCH; ++ch)
+                        ok = ok && k0[ch][1] == tagA && k0[ch][3] == tagA && k1[ch][1] == tagA && k1[ch][3] == tagA &&
+                             v0[ch][1] == tagA && v0[ch][3] == tagA && v1[ch][1] == tagA && v1[ch][3] == tagA;
+                    if (ok) {
+#pragma unroll
+                        for (int ch = 0; ch < NCH; ++ch) {
+                            kn[ch] = (v4u){k0[ch][0], k0[ch][2], k1[ch][0], k1[ch][2]};
+                            vn[ch] = (v4u){v0[ch][0], v0[ch][2], v1[ch][0], v1[ch][2]};
+                        }
+                    }
                 }
                 if ((spins & 255u) == 255u && ld_u32(c.err) != 0u) break;
             }
             if (!__all(ok)) { give_up(c); vis = 0u; }
         };
-        v4u kn = (v4u){0u, 0u, 0u, 0u}, vn = (v4u){0u, 0u, 0u, 0u};
+        v4u kn[NCH], vn[NCH];
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) kn[ch] = vn[ch] = (v4u){0u, 0u, 0u, 0u};
         unsigned vis0 = seen_by(pg);
         if (io == 0) fetch_row(pg, vis0, kn, vn);
+        // (nothing pending on entry: otherwise the wait at the loop's head is taken for both ways into it, as a wait
+        // for every request - those of the two rounds that should stay in flight included)
+        __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
         for (int rnd = 0; rnd < nrounds; rnd += 3) {
+            // (the fences keep a refill behind the last use of the registers it fills: moved ahead of it, it would
+            // go to other registers and be copied at the loop's end, behind a wait for every request)
             run(ka, va, rnd);
-            if (rnd + 3 < nrounds) fetch(ka, va, rnd + 3);
-            if (rnd + 1 < nrounds) run(kb, vb, rnd + 1);
-            if (rnd + 4 < nrounds) fetch(kb, vb, rnd + 4);
-            if (rnd + 2 < nrounds) run(kc, vc, rnd + 2);
-            if (rnd + 5 < nrounds) fetch(kc, vc, rnd + 5);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(ka, va, rnd + 3);
+            __builtin_amdgcn_sched_barrier(0);
+            run(kb, vb, rnd + 1);   // (rounds past the last: zeros that no row sees)
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(kb, vb, rnd + 4);
+            __builtin_amdgcn_sched_barrier(0);
+            run(kc, vc, rnd + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(kc, vc, rnd + 5);
         }
-        if (vis0) attend<RPJ, LPP>(q, r0, kn, vn, vis0, ke, A);
+        if (io == 0) stamp(c, stage, 4);
+        if (vis0) attend<RPJ, NCH>(q, r0, kn, vn, vis0, ke, A);
         for (int a = pg + PPW; a - pg < RS; a += PPW) {   // (the trip count is uniform over the launch)
             unsigned vis1 = seen_by(a);
             if (io == 0) fetch_row(a, vis1, kn, vn);
-            if (vis1) attend<RPJ, LPP>(q, r0, kn, vn, vis1, ke, A);
+            if (vis1) attend<RPJ, NCH>(q, r0, kn, vn, vis1, ke, A);
         }
+        if (io == 0) stamp(c, stage, 5);
 #pragma unroll
         for (int r = 0; r < RPJ; ++r) {
 #pragma unroll
@@ -885,18 +935,23 @@ __device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, c
                 const float f0 = __expf(A[r].mx - mn), f1 = __expf(omx - mn);
                 A[r].den = A[r].den * f0 + oden * f1;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) A[r].acc[e] = A[r].acc[e] * f0 + other(A[r].acc[e]) * f1;
+                for (int e = 0; e < 8 * NCH; ++e) A[r].acc[e] = A[r].acc[e] * f0 + other(A[r].acc[e]) * f1;
                 A[r].mx = mn;
             }
             if (pg == 0) {
                 float* mine = s.part + ((size_t)io * RPJ + r) * PS;
-                *reinterpret_cast<float4*>(mine + dg * 8) = make_float4(A[r].acc[0], A[r].acc[1], A[r].acc[2], A[r].acc[3]);
-                *reinterpret_cast<float4*>(mine + dg * 8 + 4) = make_float4(A[r].acc[4], A[r].acc[5], A[r].acc[6], A[r].acc[7]);
+#pragma unroll
+                for (int ch = 0; ch < NCH; ++ch) {
+                    const float* a8 = A[r].acc + 8 * ch;
+                    *reinterpret_cast<float4*>(mine + ch * 64 + dg * 8) = make_float4(a8[0], a8[1], a8[2], a8[3]);
+                    *reinterpret_cast<float4*>(mine + ch * 64 + dg * 8 + 4) = make_float4(a8[4], a8[5], a8[6], a8[7]);
+                }
                 if (dg == 0) *reinterpret_cast<float2*>(mine + HD) = make_float2(A[r].mx, A[r].den);
             }
         }
     }
     io_barrier(s, joins, lane);   // the waves' partial rows are in LDS
+    if (io == 0) stamp(c, stage, 6);
     if (io == 0) {   // merge them; lane: row lane / 16 of the job, dims 4 * (lane % 16) .. + 3
         const int r = lane / (HD / 4), q4 = lane % (HD / 4);
         if (r < RPJ && r0 + r < RS) {
@@ -1085,6 +1140,16 @@ __device__ __forceinline__ void issue_item(const XP& p, const GJob& g, u64 layer
     }
 }
 
+// The first items of the stage that follows, for the stage before it to request.
+template <int KTM, int NKC, int NI>
+struct NextItems {
+    const XP& p; const GJob& g; u64 lb; int lane;
+    __device__ __forceinline__ void operator()(int i, v4u (&b)[16]) const {
+        if (i == 0) issue_item<KTM, 0, 0>(p, g, lb, lane, b);
+        else issue_item<KTM, 1 / NKC, 1 % NKC>(p, g, lb, lane, b);
+    }
+};
+
 // Items IT, IT + 1, .. of a stage of NS strips x NKC chunks; cur holds item IT, nxt item IT + 1.
 template <int NS, int NKC, int KTM, int IT, class Next>
 __device__ __forceinline__ void stream_items(const XP& p, const GJob& g, u64 layer_base, int lane, const uint16_t* act_hi,
@@ -1105,7 +1170,7 @@ __device__ __forceinline__ void stream_items(const XP& p, const GJob& g, u64 lay
             issue_item<KTM, (IT + 2) / NKC, (IT + 2) % NKC>(p, g, layer_base, lane, cur);
             stream_items<NS, NKC, KTM, IT + 1>(p, g, layer_base, lane, act_hi, act_lo, nxt, cur, acc, next);
         } else if constexpr (IT + 2 == NS * NKC) {
-            next(0, cur);   // first item of the next stage
+            if (!(kStreamMode & 1)) next(0, cur);   // first item of the next stage
             stream_items<NS, NKC, KTM, IT + 1>(p, g, layer_base, lane, act_hi, act_lo, nxt, cur, acc, next);
         }
     }
@@ -1132,6 +1197,7 @@ __device__ __forceinline__ void stream_stage(const XP& p, const Ctx& c, const GJ
     stamp(c, stage, 0);
     lds_barrier();   // the XCD's slice of the stage input is in LDS
     stamp(c, stage, 1);
+    if (kStreamMode & 2) issue_item<KTM, 1 / NKC, 1 % NKC>(p, g, layer_base, lane, b1);
     stream_items<NS, NKC, KTM, 0>(p, g, layer_base, lane, act_hi, act_lo, b0, b1, acc, next);
     if (c.dbg) {
         asm volatile("" :: "v"(acc[NS - 1]));
@@ -1150,7 +1216,8 @@ __device__ __forceinline__ void stream_stage(const XP& p, const Ctx& c, const GJ
                                                (__float_as_uint(v[2]) & ~1u) | pbit, (__float_as_uint(v[3]) & ~1u) | pbit});
     }
     stamp(c, stage, 2);
-    next(1, b1);   // behind the stores: they leave the unit first
+    if (kStreamMode & 1) next(0, b0);
+    if (!(kStreamMode & 2)) next(1, b1);   // behind the stores: they leave the unit first
     stamp(c, stage, 4);
 }
 
@@ -1162,35 +1229,28 @@ __device__ __forceinline__ void compute_main_stream(const XP& p, const Ctx& c, c
     auto job = [&](int kind) {   // the same in every lane: kept in scalar registers
         GJob g = load_gjob(p, kind, c, wave);
         g.s0 = __builtin_amdgcn_readfirstlane(g.s0); g.ns = __builtin_amdgcn_readfirstlane(g.ns); g.KT = __builtin_amdgcn_readfirstlane(g.KT);
-        g.tile0 = ((u64)__builtin_amdgcn_readfirstlane((unsigned)(g.tile0 >> 32)) << 32) | __builtin_amdgcn_readfirstlane((unsigned)g.tile0);
+        g.tile0 = uniform64(g.tile0);
         return g;
     };
     const GJob gA = job(X_A), gC = job(X_C), gD = job(X_D), gE = job(X_E), gL = job(X_LM);
     constexpr int NKE = (KE + 15) / 16;
     v4u b0[16], b1[16];
     issue_item<16, 0, 0>(p, gA, 0, lane, b0);
-    issue_item<16, 1, 0>(p, gA, 0, lane, b1);
+    if (!(kStreamMode & 2)) issue_item<16, 1, 0>(p, gA, 0, lane, b1);
     unsigned stage = 0;
     for (int l = 0; l < p.L; ++l) {
         const u64 lb = (u64)l * p.layer_tiles;
         const bool more = l + 1 < p.L;
-        stream_stage<X_A, NA, 1, 16>(p, c, gA, s, l, stage++, p.KpA, lb, b0, b1, [&](int i, v4u (&b)[16]) {
-            if (i == 0) issue_item<16, 0, 0>(p, gC, lb, lane, b); else issue_item<16, 1, 0>(p, gC, lb, lane, b);
-        });
+        stream_stage<X_A, NA, 1, 16>(p, c, gA, s, l, stage++, p.KpA, lb, b0, b1, NextItems<16, 1, NC>{p, gC, lb, lane});
         ++stage;   // attention: the IO waves' business
-        stream_stage<X_C, NC, 1, 16>(p, c, gC, s, l, stage++, p.KpO, lb, b0, b1, [&](int i, v4u (&b)[16]) {
-            if (i == 0) issue_item<16, 0, 0>(p, gD, lb, lane, b); else issue_item<16, 1, 0>(p, gD, lb, lane, b);
-        });
-        stream_stage<X_D, ND, 1, 16>(p, c, gD, s, l, stage++, p.KpA, lb, b0, b1, [&](int i, v4u (&b)[16]) {
-            if (i == 0) issue_item<KE, 0, 0>(p, gE, lb, lane, b); else issue_item<KE, 1 / NKE, 1 % NKE>(p, gE, lb, lane, b);
-        });
-        stream_stage<X_E, NE, NKE, KE>(p, c, gE, s, l, stage++, p.KpH, lb, b0, b1, [&](int i, v4u (&b)[16]) {
-            const GJob& gn = more ? gA : gL;   // (the output projection's tiles follow the layers in the stream)
-            const u64 nb = more ? lb + p.layer_tiles : 0;
-            if (i == 0) issue_item<16, 0, 0>(p, gn, nb, lane, b); else issue_item<16, 1, 0>(p, gn, nb, lane, b);
-        });
+        stream_stage<X_C, NC, 1, 16>(p, c, gC, s, l, stage++, p.KpO, lb, b0, b1, NextItems<16, 1, ND>{p, gD, lb, lane});
+        stream_stage<X_D, ND, 1, 16>(p, c, gD, s, l, stage++, p.KpA, lb, b0, b1, NextItems<KE, NKE, NE * NKE>{p, gE, lb, lane});
+        // (the output projection's tiles follow the layers in the stream; it has no more strips per wave than QKV)
+        stream_stage<X_E, NE, NKE, KE>(p, c, gE, s, l, stage++, p.KpH, lb, b0, b1,
+                                       NextItems<16, 1, (NA < NL ? NA : NL)>{p, more ? gA : gL, more ? lb + p.layer_tiles : 0, lane});
     }
-    stream_stage<X_LM, NL, 1, 16>(p, c, gL, s, p.L, stage++, p.KpA, 0, b0, b1, [](int, v4u (&)[16]) {});
+    const GJob none = {0, 0, 0, 0};
+    stream_stage<X_LM, NL, 1, 16>(p, c, gL, s, p.L, stage++, p.KpA, 0, b0, b1, NextItems<16, 1, 2>{p, none, 0, lane});
 }
 
 template <int RPJ, int HD>

@@ -1,8 +1,9 @@
 """Stage table of the persistent target-pass kernels from their own time stamps (hawk_phase_trace).
 
-    python -m paper_2510_25739_amd.phase_trace [--path 1|2] [--kv 400] [--launches 3]
+    python -m paper_2510_25739_amd.phase_trace [--config 2|4] [--path 1|2] [--kv 400] [--launches 3]
 
-Configuration 2 (XL shape, one prompt, k = 5): the image is teacher-forced until the cache holds
+Configuration 2 (XL shape, one prompt, k = 5) or 4 (7B shape with guidance; every layer repeats layer 0's
+weights): the image is teacher-forced until the cache holds
 about --kv positions, then --launches traced steps run; the table averages the last launch's layers
 (the first three are skipped).  --path 1: the kernel laid out on the XCDs; --path 2: the grid-barrier
 kernel.  Times are in microseconds (the stamps tick at 100 MHz, so single figures are +-0.01 us and the
@@ -28,7 +29,7 @@ def xcd_table(hk, L):
     tr = out.reshape(2, 512, 16).astype(np.int64)
     # slots: compute waves 0 stage entry, 1 input in LDS (barrier crossed), 3 products done, 2 stores of the
     # partial sums issued, 4 stores acknowledged; IO waves 8 stage entry, 9 flags seen, 10 input staged
-    # (attention: output rows stored, flag raised), 12 partial sums of the wave's strip all there, 11 epilogue
+    # (attention: 9 queries seen, 11 .. 14 see the print below, 10 output rows stored and flag raised), 12 partial sums of the wave's strip all there, 11 epilogue
     # done and flag raised
     for wg, name in ((0, "workgroup 0 (XCD 0, unit 0)"), (1, "workgroup 248 (XCD 0, unit 31)")):
         t = tr[wg]
@@ -44,7 +45,10 @@ def xcd_table(hk, L):
             if k == 1:
                 job = rows[:, 10] > rows[:, 9]
                 pub = float(np.mean((rows[:, 10] - rows[:, 9])[job])) / 100.0 if job.any() else float("nan")
-                print(f"  {NAMES[k]:12s} stage {length:5.2f} | flags seen -> rows stored, flag raised {pub:5.2f}")
+                dj = lambda a, b: float(np.mean((rows[:, b] - rows[:, a])[job])) / 100.0 if job.any() else float("nan")  # noqa: E731
+                print(f"  {NAMES[k]:12s} stage {length:5.2f} | queries seen -> rows stored, flag raised {pub:5.2f}: queries in LDS "
+                      f"{dj(9, 11):5.2f} cached positions {dj(11, 12):5.2f} rows of this pass {dj(12, 13):5.2f} "
+                      f"waves' parts in LDS {dj(13, 14):5.2f} merged and stored {dj(14, 10):5.2f}")
                 continue
             job = rows[:, 12] > rows[:, 10]
             g = float(np.mean((rows[:, 12] - rows[:, 10])[job])) / 100.0 if job.any() else float("nan")
@@ -82,15 +86,17 @@ def barrier_table(hk, L):
 
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--config", type=int, default=2, choices=(2, 4))
     ap.add_argument("--path", type=int, default=1, choices=(1, 2))
     ap.add_argument("--kv", type=int, default=400)
     ap.add_argument("--launches", type=int, default=3)
     a = ap.parse_args()
-    s = synth.CONFIGS[2]
+    s = synth.CONFIGS[a.config]
     hk = H.Hawk(H.HawkConfig.from_shape(s))
-    hk.load(synth.make_weights(s))
+    hk.load(synth.make_weights(s, seed=0, repeat_layer0=(a.config == 4)))
     hk.set_path(a.path)
-    hk.prefill(synth.make_cond(s), None, s.grid_h, s.grid_w, 1.0, s.top_k, 1.0, [0.5])
+    unc = synth.make_cond(s, seed=3) if s.use_cfg else None
+    hk.prefill(synth.make_cond(s, seed=2), unc, s.grid_h, s.grid_w, 1.0, s.top_k, s.cfg_scale, [0.5])
     filler = np.random.default_rng(7).integers(0, s.v_s, size=(1, s.n_img)).astype(np.int32)
     n = 1
     while n + s.n_cond < a.kv and n + s.k + 1 < s.n_img:
@@ -99,7 +105,7 @@ def main():
     hk.phase_trace(True)
     ms = hk.run_steps(s.k, a.launches, 1, False, timed=True)
     kern = hk.last_kernel()
-    print(f"configuration 2, cache length ~{n + s.n_cond}, {a.launches} traced steps: (draft, verify, kernel) ms = {ms}; kernel {kern} "
+    print(f"configuration {a.config}, cache length ~{n + s.n_cond}, {a.launches} traced steps: (draft, verify, kernel) ms = {ms}; kernel {kern} "
           f"({'laid out on the XCDs' if kern == 2 else 'grid barriers'})")
     (xcd_table if kern == 2 else barrier_table)(hk, s.n_layers)
     hk.close()
