@@ -55,10 +55,6 @@ constexpr unsigned kSpinLimit = 1u << 20;
 constexpr int kNIT = 4;                          // cache positions per lane group and register buffer
 constexpr int kPaceGap = 0, kPaceTiles = 6;   // weight requests go out six tiles per wave at a time (see issue_paced)
 constexpr int kRing = 2;                         // partial-sum areas and XCD buffers alternate between layers
-#ifndef HAWK_STREAM_MODE
-#define HAWK_STREAM_MODE 2
-#endif
-constexpr int kStreamMode = HAWK_STREAM_MODE;
 constexpr int kMaxJobs = 128;                    // flag words of one XCD and stage that others wait for (one per IO wave with a job)
 
 enum XKind { X_A = 0, X_C, X_D, X_E, X_LM, X_NK };   // QKV, Wo, W1|W3, W2, output projection
@@ -362,15 +358,16 @@ __device__ __forceinline__ void mfma_store(const XP& p, int kind, const GJob& g,
 
 // IO waves: copy the XCD's slice of a stage input (split planes [2][16][Kp], the first MR rows of each)
 // from the XCD's buffer (byte offset `src` from the base of `r`) into LDS, which has the same layout:
-// two contiguous runs of MR * Kp elements, up to four 16-byte chunks per thread in flight.
+// two contiguous runs of MR * Kp elements, up to NB 16-byte chunks per thread in flight.
+template <int NB>
 __device__ __forceinline__ void stage_copy(rsrc_t r, unsigned src, int MR, int Kp, uint16_t* act, int t, int nthreads) {
     const int per_plane = MR * Kp / 8, total = 2 * per_plane;   // Kp % 8 == 0
     const unsigned src_plane = 16u * (unsigned)Kp * 2u, dst_plane = (unsigned)MR * (unsigned)Kp * 2u;   // in LDS the planes hold MR rows only
-    for (int base = 0; base < total; base += 4 * nthreads) {
-        v4u v[4];
-        unsigned at[4];
+    for (int base = 0; base < total; base += NB * nthreads) {
+        v4u v[NB];
+        unsigned at[NB];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < NB; ++i) {
             const int q = base + i * nthreads + t;
             const bool second = q >= per_plane;
             const unsigned in_plane = (unsigned)(second ? q - per_plane : q) * 16u;
@@ -378,7 +375,7 @@ __device__ __forceinline__ void stage_copy(rsrc_t r, unsigned src, int MR, int K
             v[i] = q < total ? ld_16(r, src + (second ? src_plane : 0u) + in_plane) : (v4u){0u, 0u, 0u, 0u};
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < NB; ++i)
             if (base + i * nthreads + t < total) *reinterpret_cast<v4u*>(reinterpret_cast<char*>(act) + at[i]) = v[i];
     }
 }
@@ -389,14 +386,24 @@ __device__ __forceinline__ void stage_copy(rsrc_t r, unsigned src, int MR, int K
 // of the strip = output features, column lane % 16 = activation row), added in XCD order.  scaled: the
 // product follows a norm; the XCDs' shares of every row's sum of squares came with their partial sums,
 // and *rn receives 1/rms of the lane's row.
+// TWO: the partials of a second strip s2 (same product, -1: none) are polled along with the first's and
+// their sum goes to *v2.
+template <bool TWO = false>
 __device__ __forceinline__ f32x4 gather_partials(const XP& p, Ctx& c, int kind, int s, int prod, int ring, unsigned tag, unsigned pbit,
-                                                 int lane, bool scaled, float* rn, unsigned dbg_stage = 1000u) {
+                                                 int lane, bool scaled, float* rn, unsigned dbg_stage = 1000u, int s2 = -1,
+                                                 f32x4* v2 = nullptr) {
     const int col = lane & 15, quad = lane >> 4;
     const bool live = col < p.MR;
     f32x4 val[kXcd];
 #pragma unroll
     for (int x = 0; x < kXcd; ++x) val[x] = (f32x4){0.f, 0.f, 0.f, 0.f};
     unsigned need = live ? 0xFFu : 0u;
+    f32x4 val2[TWO ? kXcd : 1];
+    unsigned need2 = (TWO && live && s2 >= 0) ? 0xFFu : 0u;
+    if (TWO) {
+#pragma unroll
+        for (int x = 0; x < kXcd; ++x) val2[x] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
     // (selects: indexing the kernel's parameter block with a run-time value is best avoided)
     const u64* part = kind == X_A ? p.part[X_A] : kind == X_C ? p.part[X_C] : kind == X_D ? p.part[X_D]
                                                                             : kind == X_E ? p.part[X_E] : p.part[X_LM];
@@ -406,6 +413,7 @@ __device__ __forceinline__ f32x4 gather_partials(const XP& p, Ctx& c, int kind, 
     const rsrc_t in = make_rsrc(part);
     const unsigned at8 = (unsigned)(((size_t)ring * kXcd * nstr + s) * 16 + col) * 64u + quad * 16u;
     const unsigned xstride = (unsigned)nstr * 1024u;
+    const unsigned at8b = at8 + (unsigned)((TWO ? s2 : s) - s) * 1024u;   // (the second strip's words)
     const unsigned pb = pbit * 0x1u;
     // sums of squares: the lane's quarter looks at XCDs 2 * quad and 2 * quad + 1; `prod` = the strip's
     // producer (unit * kCW + wave) * 2 + round, the same on every XCD
@@ -416,11 +424,16 @@ __device__ __forceinline__ f32x4 gather_partials(const XP& p, Ctx& c, int kind, 
     unsigned nspin = 0;
     for (unsigned spins = 0; spins < kSpinLimit && !ok; ++spins) {
         ++nspin;
-        v4u w[kXcd];
+        v4u w[kXcd], w2[TWO ? kXcd : 1];
         u64 sw[2] = {0ull, 0ull};
 #pragma unroll
         for (int x = 0; x < kXcd; ++x)
             if ((need >> x) & 1u) w[x] = ld_16(in, at8 + x * xstride);
+        if (TWO) {
+#pragma unroll
+            for (int x = 0; x < kXcd; ++x)
+                if ((need2 >> x) & 1u) w2[x] = ld_16(in, at8b + x * xstride);
+        }
 #pragma unroll
         for (int i = 0; i < 2; ++i)
             if ((need_ss >> i) & 1u) sw[i] = ld_u64(pss + (size_t)i * kPer * kCW * 2 * 16);
@@ -439,7 +452,18 @@ __device__ __forceinline__ f32x4 gather_partials(const XP& p, Ctx& c, int kind, 
                 ssv[i] = __uint_as_float((unsigned)sw[i]);
                 need_ss &= ~(1u << i);
             }
-        ok = __all(need == 0u && need_ss == 0u);
+        if (TWO) {
+#pragma unroll
+            for (int x = 0; x < kXcd; ++x)
+                if ((need2 >> x) & 1u) {
+                    if (((w2[x][0] & w2[x][1] & w2[x][2] & w2[x][3]) & 1u) == pb && ((w2[x][0] | w2[x][1] | w2[x][2] | w2[x][3]) & 1u) == pb) {
+                        val2[x] = (f32x4){__uint_as_float(w2[x][0] & ~1u), __uint_as_float(w2[x][1] & ~1u), __uint_as_float(w2[x][2] & ~1u),
+                                          __uint_as_float(w2[x][3] & ~1u)};
+                        need2 &= ~(1u << x);
+                    }
+                }
+        }
+        ok = __all(need == 0u && need_ss == 0u && need2 == 0u);
         if (!ok && (spins & 255u) == 255u && ld_u32(c.err) != 0u) break;
     }
     if (!ok) give_up(c);
@@ -454,6 +478,12 @@ __device__ __forceinline__ f32x4 gather_partials(const XP& p, Ctx& c, int kind, 
     f32x4 v = val[0];
 #pragma unroll
     for (int x = 1; x < kXcd; ++x) v += val[x];
+    if (TWO) {
+        f32x4 u = val2[0];
+#pragma unroll
+        for (int x = 1; x < kXcd; ++x) u += val2[x];
+        *v2 = u;
+    }
     return v;
 }
 
@@ -487,6 +517,10 @@ struct IoJobs {
     float2 rot0, rot1;           // QKV strip: cos, sin of the lane's two rotary pairs at the row's position
     int nA, nB, nC, nD, nE;      // flag words the consumers of stage A (reduce of QKV), B (attention), C, D, E wait for
     int a_seq, a_h, a_rg, a_slot;   // attention job of the unit (a_rg < 0: none)
+    int pA, pD;                  // producers (see gather_partials) of the wave's QKV and W1|W3 strips
+    int a_ke, a_kv0;             // ... its sequence's draft length this step and the positions cached before this launch
+                                 // (read here once: fetched at every attention stage they would add a memory round trip
+                                 // to every layer's critical path)
 };
 template <int HD>
 __device__ __forceinline__ IoJobs load_io_jobs(const XP& p, const Ctx& c, int io, int lane) {
@@ -511,6 +545,14 @@ __device__ __forceinline__ IoJobs load_io_jobs(const XP& p, const Ctx& c, int io
     j.nE = p.njobs[F_E][c.x];
     const int16_t* a = p.atab + ((size_t)c.x * kPer + c.j) * 4;
     j.a_seq = a[0]; j.a_h = a[1]; j.a_rg = a[2]; j.a_slot = a[3];
+    j.pA = j.sA >= 0 ? p.ptab[p.poff[X_A] + j.sA] : 0;
+    j.pD = j.sD >= 0 ? p.ptab[p.poff[X_D] + j.sD] : 0;
+    j.a_ke = -1; j.a_kv0 = 0;
+    if (j.a_rg >= 0) {
+        const int b = j.a_seq % p.B;
+        j.a_ke = p.k_eff[b];
+        j.a_kv0 = j.a_ke >= 0 ? p.C + p.n[b] - 1 : 0;
+    }
     return j;
 }
 
@@ -519,12 +561,12 @@ __device__ __forceinline__ IoJobs load_io_jobs(const XP& p, const Ctx& c, int io
 // at once.  resid: the wave's strip of the residual stream (owners of Wo / W2 strips).
 template <int HD>
 __device__ __forceinline__ void reduce_job(const XP& p, Ctx& c, const IoJobs& jb, int kind, int layer, int lane, f32x4& resid,
-                                           unsigned stage, bool second = false) {
+                                           unsigned stage) {
     // (selects, not indexing with a run-time value: that would move the structure into memory)
-    // second: the wave's second W1|W3 strip; the flag goes up behind the wave's last strip of the stage
-    const int s = (HD != 64 && second) ? jb.sD2 : kind == X_A ? jb.sA : kind == X_C ? jb.sC : kind == X_D ? jb.sD : jb.sE;
+    const int s = kind == X_A ? jb.sA : kind == X_C ? jb.sC : kind == X_D ? jb.sD : jb.sE;
     const int slot = kind == X_A ? jb.tA : kind == X_C ? jb.tC : kind == X_D ? jb.tD : jb.tE;
-    const bool last_of_wave = HD == 64 || second || kind != X_D || jb.sD2 < 0;
+    // the wide shape has more W1|W3 strips than IO waves: a wave's second strip is gathered along with its first
+    const int s2 = (HD != 64 && kind == X_D) ? jb.sD2 : -1;
     if (s < 0) return;
     const int col = lane & 15, quad = lane >> 4, d = p.d, ring = layer & 1;
     const bool live = col < p.MR;
@@ -539,8 +581,13 @@ __device__ __forceinline__ void reduce_job(const XP& p, Ctx& c, const IoJobs& jb
         gain = *reinterpret_cast<const uint2*>(g + s * 16 + 4 * quad);
     }
     float rn = 1.f;
-    f32x4 v = gather_partials(p, c, kind, s, scaled ? p.ptab[p.poff[kind] + s] : 0, ring, tag, parity_bit(c, kind, layer, col), lane,
-                              scaled, &rn, stage);
+    f32x4 v, vb = (f32x4){0.f, 0.f, 0.f, 0.f};
+    if (HD != 64 && kind == X_D)
+        v = gather_partials<true>(p, c, kind, s, jb.pD, ring, tag, parity_bit(c, kind, layer, col), lane, scaled, &rn,
+                                  stage, s2, &vb);
+    else
+        v = gather_partials(p, c, kind, s, kind == X_A ? jb.pA : kind == X_D ? jb.pD : 0, ring, tag, parity_bit(c, kind, layer, col), lane,
+                            scaled, &rn, stage);
     stamp(c, stage, 4);
     v *= rn;
     stamp(c, stage, 5);
@@ -570,18 +617,22 @@ __device__ __forceinline__ void reduce_job(const XP& p, Ctx& c, const IoJobs& jb
             }
         }
     } else if (kind == X_D) {   // rows 0..7 of the strip: W1 rows s * 8 + i, rows 8..15 the matching W3 rows
-        f32x4 u3;
+        auto swiglu = [&](f32x4 w, int strip) {
+            f32x4 u3;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) u3[e] = lane_xor32(v[e]);
-        if (live && quad < 2) {
-            f32x4 hv;
+            for (int e = 0; e < 4; ++e) u3[e] = lane_xor32(w[e]);
+            if (live && quad < 2) {
+                f32x4 hv;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) hv[e] = v[e] / (1.0f + expf(-v[e])) * u3[e];
-            uint16_t* hi = reinterpret_cast<uint16_t*>(buf + p.o_h);
-            uint16_t* lo = hi + (size_t)16 * p.KpH;
-            const size_t at = (size_t)col * p.KpH + (s * 8 - p.ke0[c.x] * 32) + 4 * quad;
-            put_split4(hi + at, lo + at, hv);
-        }
+                for (int e = 0; e < 4; ++e) hv[e] = w[e] / (1.0f + expf(-w[e])) * u3[e];
+                uint16_t* hi = reinterpret_cast<uint16_t*>(buf + p.o_h);
+                uint16_t* lo = hi + (size_t)16 * p.KpH;
+                const size_t at = (size_t)col * p.KpH + (strip * 8 - p.ke0[c.x] * 32) + 4 * quad;
+                put_split4(hi + at, lo + at, hv);
+            }
+        };
+        swiglu(v, s);
+        if (HD != 64 && s2 >= 0) swiglu(vb * rn, s2);
     } else {   // Wo: x' = x + Wo o; W2: x (next layer) = x' + W2 h - published times the gain of the norm that follows
         resid += v;
         const int out_ring = kind == X_C ? ring : (layer + 1) & 1;
@@ -589,7 +640,7 @@ __device__ __forceinline__ void reduce_job(const XP& p, Ctx& c, const IoJobs& jb
         if (kind == X_E && layer == p.L - 1 && live)   // final hidden rows, for the kernels that follow
             *reinterpret_cast<f32x4*>(p.X + (size_t)col * d + s * 16 + 4 * quad) = resid;
     }
-    if (kind != X_A && last_of_wave) raise_flag(p, c, flag, slot, tag);   // (queries, keys and values carry their own tags)
+    if (kind != X_A) raise_flag(p, c, flag, slot, tag);   // (queries, keys and values carry their own tags)
 }
 
 // Output projection: logits of the strip's 16 vocabulary entries for every row.
@@ -707,6 +758,7 @@ __device__ __forceinline__ void attend_round(const float (&q)[RPJ][8 * NCH], int
 
 struct Lds {
     unsigned* join;     // arrivals of the IO waves at their own barrier (only ever grows)
+    unsigned* go;       // streamed kind: 1 + the latest stage whose input the IO waves have seen announced (a hint, see stream_stage)
     uint16_t* act0;     // staged K-slices, alternating between stages: hi plane, lo plane behind it; odd stages use
     unsigned act_elems; //   the buffer act_elems elements further on (an offset, not a second pointer to choose from: a
                         //   select between members by a run-time value tends to end up as indexing in memory)
@@ -753,8 +805,7 @@ __device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, c
     // and register buffer, floats per partial row
     constexpr int LPP = 8, PPW = 64 / LPP, NCH = HD / 64, NIT = kNIT / NCH, PS = HD + 4;
     const int pg = lane / LPP, dg = lane % LPP;
-    const int b = seq % p.B, ke = p.k_eff[b];
-    const int kv0 = ke >= 0 ? p.C + p.n[b] - 1 : 0;   // positions cached before this launch
+    const int ke = jb.a_ke, kv0 = jb.a_kv0;   // draft length of the sequence's prompt; positions cached before this launch
     const int nrounds = (kv0 + NIT * kNIO * PPW - 1) / (NIT * kNIO * PPW);
     const size_t head0 = ((((size_t)layer * p.Smax + seq) * p.H + h) * p.Tmax) * HD;   // the head's entries, contiguous
     // The head's cached keys / values through buffer resources that end at the cached length: requests past it
@@ -1037,6 +1088,7 @@ __device__ __forceinline__ void io_stage(const XP& p, Ctx& c, const IoJobs& jb, 
     const int nwait = wait_flag == F_E ? jb.nE : wait_flag == F_B ? jb.nB : wait_flag == F_C ? jb.nC : jb.nD;
     stamp(c, stage, 0);
     wait_flags(p, c, wait_flag, nwait, wait_tag);
+    if (HD != 64 && wave == kCW && lane == 0) __hip_atomic_store(s.go, stage + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     stamp(c, stage, 1);
     // a product that follows a norm: the last IO wave adds the sums of squares up while the other three copy
     const bool normed = kind != X_C && kind != X_E;
@@ -1059,14 +1111,13 @@ __device__ __forceinline__ void io_stage(const XP& p, Ctx& c, const IoJobs& jb, 
         s.ss0[(stage & 1u) * 16 + lane] = a;
     }
     if (!normed || wave != kCW + kNIO - 1)
-        stage_copy(make_rsrc(p.xbuf), (unsigned)(((size_t)c.x * kRing + (layer & 1)) * p.xcd_bytes + region), p.MR, Kp,
+        stage_copy<(HD == 64 ? 4 : 8)>(make_rsrc(p.xbuf), (unsigned)(((size_t)c.x * kRing + (layer & 1)) * p.xcd_bytes + region), p.MR, Kp,
                    s.act0 + (size_t)(stage & 1u) * s.act_elems, threadIdx.x - kCW * 64, normed ? kIOThreads - 64 : kIOThreads);
     stamp(c, stage, 2);
     lds_barrier();
     if (kind == X_LM) reduce_logits(p, c, wave - kCW, lane);
     else {
         reduce_job<HD>(p, c, jb, kind, layer, lane, resid, stage);
-        if (HD != 64 && kind == X_D && jb.sD2 >= 0) reduce_job<HD>(p, c, jb, kind, layer, lane, resid, stage, true);
     }
     stamp(c, stage, 3);
 }
@@ -1115,11 +1166,13 @@ __device__ __forceinline__ void compute_main(const XP& p, const Ctx& c, const Ld
 // The wide shape (d = 4096): a wave's tiles of one layer (~1.6 MB) are far more than its registers hold,
 // so the weights stream through two register buffers of 16 tiles.  A stage is a list of items - (strip,
 // chunk of 16 k-tiles), strips outermost - with an even count, so that an item's buffer is known at
-// compile time; a buffer is refilled with the item two ahead as soon as its products are done, and the
-// last two refills of a stage fetch the first two items of the next stage: during the exchange of
-// activations between the stages two items per wave (32 MB chip-wide) are on their way.  One accumulator
-// per strip (both halves of the split activations add into it); all partial sums of a stage are stored
-// at its end, behind the products, so that no store is pending while loads are waited for one by one.
+// compile time; a buffer is refilled with the item two ahead as soon as its products are done.  Across
+// a stage boundary: the next stage's first item is requested before the last item's products, its second
+// when the next stage's input has been announced (see stream_stage) - more in flight during the exchange
+// of activations was measured slower (the IO waves' requests queue behind it), less leaves memory idle.
+// One accumulator per strip (both halves of the split activations add into it); all partial sums of a
+// stage are stored at its end, behind the products, so that no store is pending while loads are waited
+// for one by one.
 template <int KTM, int SI, int KC>
 __device__ __forceinline__ void issue_item(const XP& p, const GJob& g, u64 layer_base, int lane, v4u (&buf)[16]) {
     // A buffer resource per item whose extent is the tiles the item really has: requests beyond it (an
@@ -1140,14 +1193,11 @@ __device__ __forceinline__ void issue_item(const XP& p, const GJob& g, u64 layer
     }
 }
 
-// The first items of the stage that follows, for the stage before it to request.
-template <int KTM, int NKC, int NI>
-struct NextItems {
+// The first item of the stage that follows, for the stage before it to request.
+template <int KTM>
+struct NextItem {
     const XP& p; const GJob& g; u64 lb; int lane;
-    __device__ __forceinline__ void operator()(int i, v4u (&b)[16]) const {
-        if (i == 0) issue_item<KTM, 0, 0>(p, g, lb, lane, b);
-        else issue_item<KTM, 1 / NKC, 1 % NKC>(p, g, lb, lane, b);
-    }
+    __device__ __forceinline__ void operator()(v4u (&b)[16]) const { issue_item<KTM, 0, 0>(p, g, lb, lane, b); }
 };
 
 // Items IT, IT + 1, .. of a stage of NS strips x NKC chunks; cur holds item IT, nxt item IT + 1.
@@ -1170,14 +1220,14 @@ __device__ __forceinline__ void stream_items(const XP& p, const GJob& g, u64 lay
             issue_item<KTM, (IT + 2) / NKC, (IT + 2) % NKC>(p, g, layer_base, lane, cur);
             stream_items<NS, NKC, KTM, IT + 1>(p, g, layer_base, lane, act_hi, act_lo, nxt, cur, acc, next);
         } else if constexpr (IT + 2 == NS * NKC) {
-            if (!(kStreamMode & 1)) next(0, cur);   // first item of the next stage
+            next(cur);   // first item of the next stage
             stream_items<NS, NKC, KTM, IT + 1>(p, g, layer_base, lane, act_hi, act_lo, nxt, cur, acc, next);
         }
     }
 }
 
-// One product stage of the streamed kind.  On entry b0 / b1 hold (or are about to receive) items 0 / 1.
-// next(i, buf) requests item i (0 or 1) of the following stage into buf.
+// One product stage of the streamed kind.  On entry b0 holds (or is about to receive) item 0; next(buf) requests
+// the first item of the following stage into buf.
 template <int KIND, int NS, int NKC, int KTM, class Next>
 __device__ __forceinline__ void stream_stage(const XP& p, const Ctx& c, const GJob& g, const Lds& s, int layer, unsigned stage, int Kp,
                                              u64 layer_base, v4u (&b0)[16], v4u (&b1)[16], Next&& next) {
@@ -1195,9 +1245,17 @@ __device__ __forceinline__ void stream_stage(const XP& p, const Ctx& c, const GJ
 #pragma unroll
     for (int i = 0; i < NS; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
     stamp(c, stage, 0);
+    // The second item is requested when the IO waves have seen the stage input announced - they copy it into LDS
+    // next, and the item is on its way meanwhile.  Earlier, it would hold up what the IO waves ask for on the way
+    // there (a unit answers requests in order); behind the barrier, its whole latency would be exposed.  Only a
+    // hint: the wait is short and bounded, and running out of it changes nothing but the timing.
+    for (unsigned spins = 0; spins < 8192u; ++spins) {
+        if ((int)(__hip_atomic_load(s.go, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - (stage + 1u)) >= 0) break;
+        __builtin_amdgcn_s_sleep(1);
+    }
+    issue_item<KTM, 1 / NKC, 1 % NKC>(p, g, layer_base, lane, b1);
     lds_barrier();   // the XCD's slice of the stage input is in LDS
     stamp(c, stage, 1);
-    if (kStreamMode & 2) issue_item<KTM, 1 / NKC, 1 % NKC>(p, g, layer_base, lane, b1);
     stream_items<NS, NKC, KTM, 0>(p, g, layer_base, lane, act_hi, act_lo, b0, b1, acc, next);
     if (c.dbg) {
         asm volatile("" :: "v"(acc[NS - 1]));
@@ -1216,8 +1274,6 @@ __device__ __forceinline__ void stream_stage(const XP& p, const Ctx& c, const GJ
                                                (__float_as_uint(v[2]) & ~1u) | pbit, (__float_as_uint(v[3]) & ~1u) | pbit});
     }
     stamp(c, stage, 2);
-    if (kStreamMode & 1) next(0, b0);
-    if (!(kStreamMode & 2)) next(1, b1);   // behind the stores: they leave the unit first
     stamp(c, stage, 4);
 }
 
@@ -1236,21 +1292,20 @@ __device__ __forceinline__ void compute_main_stream(const XP& p, const Ctx& c, c
     constexpr int NKE = (KE + 15) / 16;
     v4u b0[16], b1[16];
     issue_item<16, 0, 0>(p, gA, 0, lane, b0);
-    if (!(kStreamMode & 2)) issue_item<16, 1, 0>(p, gA, 0, lane, b1);
     unsigned stage = 0;
     for (int l = 0; l < p.L; ++l) {
         const u64 lb = (u64)l * p.layer_tiles;
         const bool more = l + 1 < p.L;
-        stream_stage<X_A, NA, 1, 16>(p, c, gA, s, l, stage++, p.KpA, lb, b0, b1, NextItems<16, 1, NC>{p, gC, lb, lane});
+        stream_stage<X_A, NA, 1, 16>(p, c, gA, s, l, stage++, p.KpA, lb, b0, b1, NextItem<16>{p, gC, lb, lane});
         ++stage;   // attention: the IO waves' business
-        stream_stage<X_C, NC, 1, 16>(p, c, gC, s, l, stage++, p.KpO, lb, b0, b1, NextItems<16, 1, ND>{p, gD, lb, lane});
-        stream_stage<X_D, ND, 1, 16>(p, c, gD, s, l, stage++, p.KpA, lb, b0, b1, NextItems<KE, NKE, NE * NKE>{p, gE, lb, lane});
+        stream_stage<X_C, NC, 1, 16>(p, c, gC, s, l, stage++, p.KpO, lb, b0, b1, NextItem<16>{p, gD, lb, lane});
+        stream_stage<X_D, ND, 1, 16>(p, c, gD, s, l, stage++, p.KpA, lb, b0, b1, NextItem<KE>{p, gE, lb, lane});
         // (the output projection's tiles follow the layers in the stream; it has no more strips per wave than QKV)
         stream_stage<X_E, NE, NKE, KE>(p, c, gE, s, l, stage++, p.KpH, lb, b0, b1,
-                                       NextItems<16, 1, (NA < NL ? NA : NL)>{p, more ? gA : gL, more ? lb + p.layer_tiles : 0, lane});
+                                       NextItem<16>{p, more ? gA : gL, more ? lb + p.layer_tiles : 0, lane});
     }
     const GJob none = {0, 0, 0, 0};
-    stream_stage<X_LM, NL, 1, 16>(p, c, gL, s, p.L, stage++, p.KpA, 0, b0, b1, NextItems<16, 1, 2>{p, none, 0, lane});
+    stream_stage<X_LM, NL, 1, 16>(p, c, gL, s, p.L, stage++, p.KpA, 0, b0, b1, NextItem<16>{p, none, 0, lane});
 }
 
 template <int RPJ, int HD>
@@ -1288,12 +1343,13 @@ __global__ __launch_bounds__(kThreads, 1) void verify_xcd_kernel(const XP* __res
     Lds s;
     const size_t act_elems = (size_t)2 * p.MR * max(max(p.KpA, p.KpO), p.KpH);
     s.join = reinterpret_cast<unsigned*>(smem_raw);
+    s.go = s.join + 1;
     s.act0 = reinterpret_cast<uint16_t*>(smem_raw + 1);
     s.act_elems = (unsigned)act_elems;
     s.part = reinterpret_cast<float*>(s.act0 + 2 * act_elems);
     s.qs = s.part + kNIO * RPJ * (HD + 4);
     s.ss0 = s.qs + RPJ * HD;
-    if (threadIdx.x == 0) *s.join = 0u;
+    if (threadIdx.x == 0) { *s.join = 0u; *s.go = 0u; }
     __syncthreads();
     Ctx c;
     c.x = blockIdx.x % kXcd; c.j = blockIdx.x / kXcd; c.epoch0 = epoch0; c.par = par; c.par_lm = par_lm; c.dead = false; c.err = p.err; c.dbg = dbg;
@@ -1314,12 +1370,13 @@ __global__ __launch_bounds__(kThreads, 1) void verify_xcd_stream_kernel(const XP
     Lds s;
     const size_t act_elems = (size_t)2 * p.MR * max(max(p.KpA, p.KpO), p.KpH);
     s.join = reinterpret_cast<unsigned*>(smem_raw);
+    s.go = s.join + 1;
     s.act0 = reinterpret_cast<uint16_t*>(smem_raw + 1);
     s.act_elems = (unsigned)act_elems;
     s.part = reinterpret_cast<float*>(s.act0 + 2 * act_elems);
     s.qs = s.part + kNIO * RPJ * (HD + 4);
     s.ss0 = s.qs + RPJ * HD;
-    if (threadIdx.x == 0) *s.join = 0u;
+    if (threadIdx.x == 0) { *s.join = 0u; *s.go = 0u; }
     __syncthreads();
     Ctx c;
     c.x = blockIdx.x % kXcd; c.j = blockIdx.x / kXcd; c.epoch0 = epoch0; c.par = par; c.par_lm = par_lm; c.dead = false; c.err = p.err; c.dbg = dbg;
