@@ -732,6 +732,18 @@ def test_config4_7b_shape_slice_and_guidance_reduced(H):
     assert_bf16(total, 8)
 
 
+@pytest.mark.parametrize("k,scale,expect_kernel", [(0, 3.0, 2), (1, 1.0, 2), (6, 3.0, 2), (7, 3.0, 0), (7, 1.0, 2)])
+def test_config4_widths_row_counts_on_the_streamed_kernel(H, k, scale, expect_kernel):
+    # The 7B widths (d = 4096, 32 heads of 128, MLP 11008: weights streamed through register buffers, two
+    # W1|W3 strips per IO wave, attention over two 64-feature chunks per lane) at one layer, with other row
+    # counts than configuration 4's 2 x 6: 2 x 1, 1 x 2, 2 x 7 = 14 rows (the most whose planes fit the
+    # unit's LDS), 2 x 8 = 16 (does not fit: the pass runs as one kernel per operation), 1 x 8
+    s = synth.CONFIGS[4].replace(n_layers=1, vocab=12288, n_cond=8, grid_h=4, grid_w=8, k=k, cfg_scale=scale)
+    total = accumulate_lockstep(H, s, k, 1, 6, max_runs=10, expect_kernel=expect_kernel)
+    print("config 4 widths, k", k, "guidance", scale, "kernel", expect_kernel, total)
+    assert_bf16(total, 6)
+
+
 def test_config4_full_depth_one_step(H):
     # configuration 4 at its full depth and widths (32 layers, d = 4096, MLP 11008, vocabulary 65536, slice of
     # 8192 at id 4, top-k 2000, guidance 3.0: 12 rows per target pass) with a condition of 8 vectors (the
@@ -753,6 +765,7 @@ def test_config4_full_depth_one_step(H):
     print("config 4 full depth:", res, "logit std target (guided)", sig_p, "draft", sig_q,
           "relative errors", res["max_logit_err"] / sig_p, res["max_draft_logit_err"] / sig_q)
     assert res["stage_bad"] == 0 and res["steps"] == 1 and res["decision_same"] == 1, res
+    assert hk.last_kernel() == 2, "configuration 4's pass is expected to run as the kernel laid out on the XCDs"
     assert res["max_logit_err"] <= 0.028 * sig_p and res["max_draft_logit_err"] <= 0.028 * sig_q, res
     hk.close()
     orc.close()
