@@ -197,7 +197,9 @@ int hawk_get_draft_logits(hawk_ctx* ctx, float* out, int k);
 /* Selects the kernel set: 0 = one kernel per operation (any shape); 1 = a persistent
  * weight-streaming kernel where the shape allows (default): the one laid out on the chip's XCDs
  * for passes of at most 16 rows (step rows of hawk_verify / hawk_force / hawk_generate /
- * hawk_run_steps, tree rows of hawk_verify_tree), else the one with grid barriers; 2 = as 1 but only the grid-barrier kernel.  hawk_last_path reports what the
+ * hawk_run_steps, tree rows of hawk_verify_tree; shapes: d_model 768, 1280 or - with the weights
+ * streamed, at most 14 rows - 4096 with heads of 128), else the one with grid barriers; 2 = as 1 but
+ * only the grid-barrier kernel.  hawk_last_path reports what the
  * last target pass actually used (0: one kernel per operation, 1: a persistent kernel; -1 before
  * any), hawk_last_kernel which kernel (0: one per operation, 1: grid-barrier kernel, 2: the kernel
  * laid out on the XCDs). */
