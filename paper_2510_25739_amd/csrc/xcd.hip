@@ -380,6 +380,29 @@ __device__ __forceinline__ void stage_copy(rsrc_t r, unsigned src, int MR, int K
     }
 }
 
+// The same for the 16-byte words [w0, w1) of every row only (the wide shape's W2 input goes to LDS in parts,
+// one per chunk of 16 k-tiles, so that the products of the first part start while the rest is copied).
+__device__ __forceinline__ void stage_copy_cols(rsrc_t r, unsigned src, int MR, int Kp, uint16_t* act, int t, int nthreads, int w0, int w1) {
+    const int wpr = w1 - w0, per_plane = MR * wpr, total = 2 * per_plane;
+    const unsigned src_plane = 16u * (unsigned)Kp * 2u, dst_plane = (unsigned)MR * (unsigned)Kp * 2u;
+    for (int base = 0; base < total; base += 8 * nthreads) {
+        v4u v[8];
+        unsigned at[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int q = base + i * nthreads + t;
+            const bool second = q >= per_plane;
+            const int qq = second ? q - per_plane : q, row = qq / wpr, w = qq - row * wpr;
+            const unsigned in_plane = (unsigned)row * (unsigned)Kp * 2u + (unsigned)(w0 + w) * 16u;
+            at[i] = (second ? dst_plane : 0u) + in_plane;
+            v[i] = q < total ? ld_16(r, src + (second ? src_plane : 0u) + in_plane) : (v4u){0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (base + i * nthreads + t < total) *reinterpret_cast<v4u*>(reinterpret_cast<char*>(act) + at[i]) = v[i];
+    }
+}
+
 // ------------------------------------------------------------------------- reduce jobs (IO waves)
 
 // Sum of the eight XCDs' partials of strip s in accumulator layout (lane: rows 4 * (lane / 16) .. + 3
@@ -960,11 +983,14 @@ __device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, c
             __builtin_amdgcn_sched_barrier(0);
             fetch(ka, va, rnd + 3);
             __builtin_amdgcn_sched_barrier(0);
-            run(kb, vb, rnd + 1);   // (rounds past the last: zeros that no row sees)
+            // (Requests are made for rounds past the last as well: zeros, nothing moves.  Their products are skipped
+            // where a round is long - the wide heads - and done where the branch would cost more than it saves: with
+            // it, the waits of the narrow-head instances fall back to waits for every request.)
+            if (HD == 64 || rnd + 1 < nrounds) run(kb, vb, rnd + 1);
             __builtin_amdgcn_sched_barrier(0);
             fetch(kb, vb, rnd + 4);
             __builtin_amdgcn_sched_barrier(0);
-            run(kc, vc, rnd + 2);
+            if (HD == 64 || rnd + 2 < nrounds) run(kc, vc, rnd + 2);
             __builtin_amdgcn_sched_barrier(0);
             fetch(kc, vc, rnd + 5);
         }
@@ -1110,7 +1136,15 @@ __device__ __forceinline__ void io_stage(const XP& p, Ctx& c, const IoJobs& jb, 
         }
         s.ss0[(stage & 1u) * 16 + lane] = a;
     }
-    if (!normed || wave != kCW + kNIO - 1)
+    if (HD != 64 && kind == X_E) {   // in parts, a workgroup barrier behind each (the compute waves cross the same ones)
+        const int words = Kp / 8, nparts = (p.KT[X_E][c.x] + 15) / 16;
+        for (int part = 0; part < nparts; ++part) {
+            stage_copy_cols(make_rsrc(p.xbuf), (unsigned)(((size_t)c.x * kRing + (layer & 1)) * p.xcd_bytes + region), p.MR, Kp,
+                            s.act0 + (size_t)(stage & 1u) * s.act_elems, threadIdx.x - kCW * 64, kIOThreads, part * 64,
+                            part + 1 < nparts ? part * 64 + 64 : words);
+            if (part + 1 < nparts) lds_barrier();
+        }
+    } else if (!normed || wave != kCW + kNIO - 1)
         stage_copy<(HD == 64 ? 4 : 8)>(make_rsrc(p.xbuf), (unsigned)(((size_t)c.x * kRing + (layer & 1)) * p.xcd_bytes + region), p.MR, Kp,
                    s.act0 + (size_t)(stage & 1u) * s.act_elems, threadIdx.x - kCW * 64, normed ? kIOThreads - 64 : kIOThreads);
     stamp(c, stage, 2);
@@ -1201,11 +1235,12 @@ struct NextItem {
 };
 
 // Items IT, IT + 1, .. of a stage of NS strips x NKC chunks; cur holds item IT, nxt item IT + 1.
-template <int NS, int NKC, int KTM, int IT, class Next>
+template <int NS, int NKC, int KTM, int IT, bool PARTS, class Next>
 __device__ __forceinline__ void stream_items(const XP& p, const GJob& g, u64 layer_base, int lane, const uint16_t* act_hi,
                                              const uint16_t* act_lo, v4u (&cur)[16], v4u (&nxt)[16], f32x4 (&acc)[NS], Next&& next) {
     if constexpr (IT < NS * NKC) {
         constexpr int si = IT / NKC, kc = IT % NKC;
+        if (PARTS && IT > 0 && IT < NKC) lds_barrier();   // the input's next chunk of 16 k-tiles is in LDS
 #pragma unroll
         for (int kt = 0; kt < 16; ++kt) {
             if (kc * 16 + kt < KTM) {
@@ -1218,10 +1253,10 @@ __device__ __forceinline__ void stream_items(const XP& p, const GJob& g, u64 lay
         }
         if constexpr (IT + 2 < NS * NKC) {   // the freed buffer takes the item two ahead
             issue_item<KTM, (IT + 2) / NKC, (IT + 2) % NKC>(p, g, layer_base, lane, cur);
-            stream_items<NS, NKC, KTM, IT + 1>(p, g, layer_base, lane, act_hi, act_lo, nxt, cur, acc, next);
+            stream_items<NS, NKC, KTM, IT + 1, PARTS>(p, g, layer_base, lane, act_hi, act_lo, nxt, cur, acc, next);
         } else if constexpr (IT + 2 == NS * NKC) {
             next(cur);   // first item of the next stage
-            stream_items<NS, NKC, KTM, IT + 1>(p, g, layer_base, lane, act_hi, act_lo, nxt, cur, acc, next);
+            stream_items<NS, NKC, KTM, IT + 1, PARTS>(p, g, layer_base, lane, act_hi, act_lo, nxt, cur, acc, next);
         }
     }
 }
@@ -1256,7 +1291,7 @@ __device__ __forceinline__ void stream_stage(const XP& p, const Ctx& c, const GJ
     issue_item<KTM, 1 / NKC, 1 % NKC>(p, g, layer_base, lane, b1);
     lds_barrier();   // the XCD's slice of the stage input is in LDS
     stamp(c, stage, 1);
-    stream_items<NS, NKC, KTM, 0>(p, g, layer_base, lane, act_hi, act_lo, b0, b1, acc, next);
+    stream_items<NS, NKC, KTM, 0, (KIND == X_E && NKC > 1)>(p, g, layer_base, lane, act_hi, act_lo, b0, b1, acc, next);
     if (c.dbg) {
         asm volatile("" :: "v"(acc[NS - 1]));
         stamp(c, stage, 3);
@@ -1779,7 +1814,7 @@ int launch_verify_xcd(hawk_ctx* c, int k, const int32_t* tree_depth, const unsig
                         : reinterpret_cast<const void*>(verify_xcd_stream_kernel<6, 2, 12, 2, 43, 4, 2, 128>);
         if (P->NSW[X_A] > 6 || P->NSW[X_C] > 2 || P->NSW[X_D] > 12 || P->NSW[X_E] > 2 || P->NSW[X_LM] > 4) return -1;
         for (int x = 0; x < kXcd; ++x)
-            if (P->KT[X_A][x] != 16 || P->KT[X_C][x] != 16 || P->KT[X_E][x] > 43) return -1;
+            if (P->KT[X_A][x] != 16 || P->KT[X_C][x] != 16 || P->KT[X_E][x] != 43) return -1;   // (three parts of the W2 input on both sides)
     } else {
         // d = 768: QKV 144 -> 2, Wo 48 -> 1, W1|W3 256 -> 2, W2 48 -> 1, output 8 in two rounds of 4
         p.lm_rounds = 2;
