@@ -976,23 +976,45 @@ __device__ __forceinline__ void attn_io(const XP& p, Ctx& c, const IoJobs& jb, c
         // (nothing pending on entry: otherwise the wait at the loop's head is taken for both ways into it, as a wait
         // for every request - those of the two rounds that should stay in flight included)
         __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
-        for (int rnd = 0; rnd < nrounds; rnd += 3) {
-            // (the fences keep a refill behind the last use of the registers it fills: moved ahead of it, it would
-            // go to other registers and be copied at the loop's end, behind a wait for every request)
-            run(ka, va, rnd);
-            __builtin_amdgcn_sched_barrier(0);
-            fetch(ka, va, rnd + 3);
-            __builtin_amdgcn_sched_barrier(0);
-            // (Requests are made for rounds past the last as well: zeros, nothing moves.  Their products are skipped
-            // where a round is long - the wide heads - and done where the branch would cost more than it saves: with
-            // it, the waits of the narrow-head instances fall back to waits for every request.)
-            if (HD == 64 || rnd + 1 < nrounds) run(kb, vb, rnd + 1);
-            __builtin_amdgcn_sched_barrier(0);
-            fetch(kb, vb, rnd + 4);
-            __builtin_amdgcn_sched_barrier(0);
-            if (HD == 64 || rnd + 2 < nrounds) run(kc, vc, rnd + 2);
-            __builtin_amdgcn_sched_barrier(0);
-            fetch(kc, vc, rnd + 5);
+        // Requests are made for rounds past the last as well: zeros, nothing moves.  The fences keep a refill
+        // behind the last use of the registers it fills: moved ahead of it, it would go to other registers and be
+        // copied at the loop's end, behind a wait for every request.
+        if constexpr (HD == 64) {
+            // Whole trips of three rounds in the loop, straight-line code (with branches in it, the waits inside
+            // fall back to waits for every request); the last one or two rounds behind it.
+            int rnd = 0;
+            for (; rnd + 3 <= nrounds; rnd += 3) {
+                run(ka, va, rnd);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(ka, va, rnd + 3);
+                __builtin_amdgcn_sched_barrier(0);
+                run(kb, vb, rnd + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(kb, vb, rnd + 4);
+                __builtin_amdgcn_sched_barrier(0);
+                run(kc, vc, rnd + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(kc, vc, rnd + 5);
+            }
+            if (rnd < nrounds) run(ka, va, rnd);
+            if (rnd + 1 < nrounds) run(kb, vb, rnd + 1);
+        } else {
+            // The wide heads: a round's products are long and the registers full - the rounds past the last are
+            // skipped inside the loop (the two extra copies of the products that a tail needs cost 40 spilled
+            // registers here, and 4 % of the kernel).
+            for (int rnd = 0; rnd < nrounds; rnd += 3) {
+                run(ka, va, rnd);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(ka, va, rnd + 3);
+                __builtin_amdgcn_sched_barrier(0);
+                if (rnd + 1 < nrounds) run(kb, vb, rnd + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(kb, vb, rnd + 4);
+                __builtin_amdgcn_sched_barrier(0);
+                if (rnd + 2 < nrounds) run(kc, vc, rnd + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(kc, vc, rnd + 5);
+            }
         }
         if (io == 0) stamp(c, stage, 4);
         if (vis0) attend<RPJ, NCH>(q, r0, kn, vn, vis0, ke, A);
