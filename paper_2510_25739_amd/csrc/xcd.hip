@@ -14,8 +14,9 @@
 //     its own units read: consumers fetch an eighth of the vector, from their own L2;
 //   - workgroup (c, j) streams the weights of its output strips x that K-slice (bf16 tiles straight into
 //     registers as MFMA A operands, one wave per strip group, no cross-wave reduction) and writes the
-//     partial sums to memory as 8-byte {value, tag} words (tag = stage number: a reader knows a word is
-//     of this stage without any barrier, and nothing has to be re-armed);
+//     partial sums to memory as fp32 values whose lowest mantissa bit carries the parity of the number of
+//     times the word has been written (a reader knows a word is of this stage without any barrier, and
+//     nothing has to be re-armed);
 //   - the strip's owner - an IO wave on the XCD that owns those output columns as its K-slice of the
 //     NEXT product - polls the eight partials, adds them in fixed order, applies the epilogue (norm
 //     scale, rotary embedding, residual, SwiGLU), stores the result into its XCD's buffer with ordinary
@@ -28,8 +29,11 @@
 //
 // In the loaded kernel the latencies are two to three times the idle ones (a partial sum is in its
 // owner's registers 1.3 - 2.7 us after its store was issued, a local flag is seen after ~0.4 us, the
-// staging copy takes ~0.55 us), which is what bounds a stage at 4.3 - 8.3 us (see the stage table that
-// hawk_phase_trace gives); the weight stream itself accounts for ~5 % of the kernel's time.
+// staging copy takes ~0.55 us), which is what bounds a stage at 4.4 - 5.5 us at the XL shape (see the
+// stage table that hawk_phase_trace gives); the weight stream itself accounts for ~5 % of that kernel's
+// time.  Two forms of the compute side: verify_xcd_kernel keeps a layer's tiles in registers, requested
+// a fifth of a layer per stage (d_model 768 / 1280); verify_xcd_stream_kernel streams them through two
+// register buffers (d_model 4096, where the stream is two thirds of the time).  The IO side is shared.
 #include <math.h>
 #include <stdlib.h>
 #include <string.h>
