@@ -1310,7 +1310,9 @@ __device__ __forceinline__ void stream_stage(const XP& p, const Ctx& c, const GJ
     // next, and the item is on its way meanwhile.  Earlier, it would hold up what the IO waves ask for on the way
     // there (a unit answers requests in order); behind the barrier, its whole latency would be exposed.  Only a
     // hint: the wait is short and bounded, and running out of it changes nothing but the timing.
-    for (unsigned spins = 0; spins < 8192u; ++spins) {
+    // (Wo's two items are both requested at once: the attention runs in between, and they are in long before its
+    // output is staged.)
+    for (unsigned spins = 0; KIND != X_C && spins < 8192u; ++spins) {
         if ((int)(__hip_atomic_load(s.go, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - (stage + 1u)) >= 0) break;
         __builtin_amdgcn_s_sleep(1);
     }
