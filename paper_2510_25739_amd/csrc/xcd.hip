@@ -360,11 +360,20 @@ __device__ __forceinline__ void mfma_store(const XP& p, int kind, const GJob& g,
     }
 }
 
+// Streamed kind: an IO wave tells the compute waves that its first requests for the stage input are out (see
+// stream_stage) - behind them in program order, which is the order the unit serves requests in.
+__device__ __forceinline__ void announce(unsigned* go) {
+    __builtin_amdgcn_sched_barrier(0);
+    if (go && (threadIdx.x & 63) == 0) atomicAdd(go, 1u);
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 // IO waves: copy the XCD's slice of a stage input (split planes [2][16][Kp], the first MR rows of each)
 // from the XCD's buffer (byte offset `src` from the base of `r`) into LDS, which has the same layout:
 // two contiguous runs of MR * Kp elements, up to NB 16-byte chunks per thread in flight.
 template <int NB>
-__device__ __forceinline__ void stage_copy(rsrc_t r, unsigned src, int MR, int Kp, uint16_t* act, int t, int nthreads) {
+__device__ __forceinline__ void stage_copy(rsrc_t r, unsigned src, int MR, int Kp, uint16_t* act, int t, int nthreads,
+                                           unsigned* go = nullptr) {
     const int per_plane = MR * Kp / 8, total = 2 * per_plane;   // Kp % 8 == 0
     const unsigned src_plane = 16u * (unsigned)Kp * 2u, dst_plane = (unsigned)MR * (unsigned)Kp * 2u;   // in LDS the planes hold MR rows only
     for (int base = 0; base < total; base += NB * nthreads) {
@@ -378,6 +387,7 @@ __device__ __forceinline__ void stage_copy(rsrc_t r, unsigned src, int MR, int K
             at[i] = (second ? dst_plane : 0u) + in_plane;
             v[i] = q < total ? ld_16(r, src + (second ? src_plane : 0u) + in_plane) : (v4u){0u, 0u, 0u, 0u};
         }
+        if (base == 0) announce(go);
 #pragma unroll
         for (int i = 0; i < NB; ++i)
             if (base + i * nthreads + t < total) *reinterpret_cast<v4u*>(reinterpret_cast<char*>(act) + at[i]) = v[i];
@@ -386,7 +396,8 @@ __device__ __forceinline__ void stage_copy(rsrc_t r, unsigned src, int MR, int K
 
 // The same for the 16-byte words [w0, w1) of every row only (the wide shape's W2 input goes to LDS in parts,
 // one per chunk of 16 k-tiles, so that the products of the first part start while the rest is copied).
-__device__ __forceinline__ void stage_copy_cols(rsrc_t r, unsigned src, int MR, int Kp, uint16_t* act, int t, int nthreads, int w0, int w1) {
+__device__ __forceinline__ void stage_copy_cols(rsrc_t r, unsigned src, int MR, int Kp, uint16_t* act, int t, int nthreads, int w0, int w1,
+                                                unsigned* go) {
     const int wpr = w1 - w0, per_plane = MR * wpr, total = 2 * per_plane;
     const unsigned src_plane = 16u * (unsigned)Kp * 2u, dst_plane = (unsigned)MR * (unsigned)Kp * 2u;
     for (int base = 0; base < total; base += 8 * nthreads) {
@@ -401,6 +412,7 @@ __device__ __forceinline__ void stage_copy_cols(rsrc_t r, unsigned src, int MR, 
             at[i] = (second ? dst_plane : 0u) + in_plane;
             v[i] = q < total ? ld_16(r, src + (second ? src_plane : 0u) + in_plane) : (v4u){0u, 0u, 0u, 0u};
         }
+        if (base == 0) announce(go);
 #pragma unroll
         for (int i = 0; i < 8; ++i)
             if (base + i * nthreads + t < total) *reinterpret_cast<v4u*>(reinterpret_cast<char*>(act) + at[i]) = v[i];
@@ -785,7 +797,7 @@ __device__ __forceinline__ void attend_round(const float (&q)[RPJ][8 * NCH], int
 
 struct Lds {
     unsigned* join;     // arrivals of the IO waves at their own barrier (only ever grows)
-    unsigned* go;       // streamed kind: 1 + the latest stage whose input the IO waves have seen announced (a hint, see stream_stage)
+    unsigned* go;       // streamed kind: IO waves that have requested a stage input, counted over the launch (a hint, see stream_stage)
     uint16_t* act0;     // staged K-slices, alternating between stages: hi plane, lo plane behind it; odd stages use
     unsigned act_elems; //   the buffer act_elems elements further on (an offset, not a second pointer to choose from: a
                         //   select between members by a run-time value tends to end up as indexing in memory)
@@ -1140,7 +1152,7 @@ __device__ __forceinline__ void io_stage(const XP& p, Ctx& c, const IoJobs& jb, 
     const int nwait = wait_flag == F_E ? jb.nE : wait_flag == F_B ? jb.nB : wait_flag == F_C ? jb.nC : jb.nD;
     stamp(c, stage, 0);
     wait_flags(p, c, wait_flag, nwait, wait_tag);
-    if (HD != 64 && wave == kCW && lane == 0) __hip_atomic_store(s.go, stage + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    unsigned* const go = HD != 64 ? s.go : nullptr;   // every IO wave announces once per product stage
     stamp(c, stage, 1);
     // a product that follows a norm: the last IO wave adds the sums of squares up while the other three copy
     const bool normed = kind != X_C && kind != X_E;
@@ -1149,17 +1161,13 @@ __device__ __forceinline__ void io_stage(const XP& p, Ctx& c, const IoJobs& jb, 
         // owners' strips added in strip order - for the compute waves to send along with their partial sums.
         const int per_xcd = p.d / 16 / kXcd;
         const float* ss = reinterpret_cast<const float*>(xcd_buf(p, c.x, layer & 1) + p.o_ss) + (size_t)(kind == X_D) * per_xcd * 16 + lane;
-        float v[16], a = 0.f;
+        constexpr int NSS = HD == 64 ? 16 : 32;   // strips an XCD owns at most (all requested at once: one round trip)
+        float v[NSS], a = 0.f;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) v[i] = i < per_xcd ? __uint_as_float(ld_u32(ss + i * 16)) : 0.f;
+        for (int i = 0; i < NSS; ++i) v[i] = i < per_xcd ? __uint_as_float(ld_u32(ss + i * 16)) : 0.f;
+        announce(go);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) a += v[i];
-        if (HD != 64 && per_xcd > 16) {   // (the wide shape: up to 32 strips per XCD)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) v[i] = 16 + i < per_xcd ? __uint_as_float(ld_u32(ss + (16 + i) * 16)) : 0.f;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) a += v[i];
-        }
+        for (int i = 0; i < NSS; ++i) a += v[i];
         s.ss0[(stage & 1u) * 16 + lane] = a;
     }
     if (HD != 64 && kind == X_E) {   // in parts, a workgroup barrier behind each (the compute waves cross the same ones)
@@ -1167,12 +1175,12 @@ __device__ __forceinline__ void io_stage(const XP& p, Ctx& c, const IoJobs& jb, 
         for (int part = 0; part < nparts; ++part) {
             stage_copy_cols(make_rsrc(p.xbuf), (unsigned)(((size_t)c.x * kRing + (layer & 1)) * p.xcd_bytes + region), p.MR, Kp,
                             s.act0 + (size_t)(stage & 1u) * s.act_elems, threadIdx.x - kCW * 64, kIOThreads, part * 64,
-                            part + 1 < nparts ? part * 64 + 64 : words);
+                            part + 1 < nparts ? part * 64 + 64 : words, part == 0 ? go : nullptr);
             if (part + 1 < nparts) lds_barrier();
         }
     } else if (!normed || wave != kCW + kNIO - 1)
         stage_copy<(HD == 64 ? 4 : 8)>(make_rsrc(p.xbuf), (unsigned)(((size_t)c.x * kRing + (layer & 1)) * p.xcd_bytes + region), p.MR, Kp,
-                   s.act0 + (size_t)(stage & 1u) * s.act_elems, threadIdx.x - kCW * 64, normed ? kIOThreads - 64 : kIOThreads);
+                   s.act0 + (size_t)(stage & 1u) * s.act_elems, threadIdx.x - kCW * 64, normed ? kIOThreads - 64 : kIOThreads, go);
     stamp(c, stage, 2);
     lds_barrier();
     if (kind == X_LM) reduce_logits(p, c, wave - kCW, lane);
@@ -1306,14 +1314,17 @@ __device__ __forceinline__ void stream_stage(const XP& p, const Ctx& c, const GJ
 #pragma unroll
     for (int i = 0; i < NS; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
     stamp(c, stage, 0);
-    // The second item is requested when the IO waves have seen the stage input announced - they copy it into LDS
-    // next, and the item is on its way meanwhile.  Earlier, it would hold up what the IO waves ask for on the way
-    // there (a unit answers requests in order); behind the barrier, its whole latency would be exposed.  Only a
-    // hint: the wait is short and bounded, and running out of it changes nothing but the timing.
+    // The second item is requested when all four IO waves have made their first requests for the stage input (they
+    // count themselves in LDS, see announce): the unit answers requests in order, so the item comes in behind
+    // the input and is on its way while the input goes to LDS.  Earlier, it would hold up what the IO waves ask
+    // for on the way there; behind the barrier, its whole latency would be exposed.  Only a hint: the wait is
+    // short and bounded, and running out of it changes nothing but the timing.
     // (Wo's two items are both requested at once: the attention runs in between, and they are in long before its
     // output is staged.)
+    const unsigned l5 = stage / 5u, st5 = stage - 5u * l5;                        // (stage = 5 layer + 0, 2, 3, 4; the output projection 5 L)
+    const unsigned want = 4u * (4u * l5 + (st5 ? st5 - 1u : 0u) + 1u);           // four announcements per product stage so far
     for (unsigned spins = 0; KIND != X_C && spins < 8192u; ++spins) {
-        if ((int)(__hip_atomic_load(s.go, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - (stage + 1u)) >= 0) break;
+        if ((int)(__hip_atomic_load(s.go, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - want) >= 0) break;
         __builtin_amdgcn_s_sleep(1);
     }
     issue_item<KTM, 1 / NKC, 1 % NKC>(p, g, layer_base, lane, b1);
