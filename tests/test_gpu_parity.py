@@ -744,6 +744,41 @@ def test_config4_widths_row_counts_on_the_streamed_kernel(H, k, scale, expect_ke
     assert_bf16(total, 6)
 
 
+def test_config4_widths_120_steps_and_identical_bits(H):
+    # The streamed kernel over many steps: configuration 4's widths and guidance at two layers, 8 x 8 images,
+    # >= 120 steps in lockstep with the oracle (at most one differing decision, logits within 2e-2); then the
+    # same prompt and uniforms through two fresh contexts: bit-identical logits and tokens (fixed summation
+    # order across XCDs, items and attention rounds).
+    s = synth.CONFIGS[4].replace(n_layers=2, vocab=12288, n_cond=8, grid_h=8, grid_w=8)
+    total = long_run(H, s, 1, 120, 2)
+    print("config 4 widths, 2 layers:", total)
+    assert total["steps"] >= 120 and total["stage_bad"] == 0
+    assert total["steps"] - total["decision_same"] <= 1, total
+    assert total["max_logit_err"] <= 2e-2 and total["max_draft_logit_err"] <= 2e-2, total
+    blob = synth.make_weights(s, seed=0)
+    cond, unc = synth.make_cond(s, seed=2), synth.make_cond(s, seed=3)
+    runs = []
+    for rep in range(2):
+        hk = H.Hawk(H.HawkConfig.from_shape(s))
+        hk.load(blob)
+        hk.prefill(cond, unc, s.grid_h, s.grid_w, 1.0, s.top_k, s.cfg_scale, [0.25])
+        rng = np.random.Generator(np.random.PCG64(11))
+        rec = [hk.logits(1).copy()]
+        for step in range(6):
+            k = [s.k, 2, s.k, 0, 3, s.k][step]
+            ud = (rng.integers(0, 1 << 24, size=(1, max(k, 1))).astype(np.float32) / np.float32(1 << 24))[:, :k]
+            ua = (rng.integers(0, 1 << 24, size=(1, max(k, 1))).astype(np.float32) / np.float32(1 << 24))[:, :k]
+            d = hk.draft(k, ud)
+            na, t = hk.verify(k, ua, [0.5])
+            assert hk.last_kernel() == 2
+            rec += [np.asarray(d).copy(), na.copy(), t.copy(), hk.logits(k + 1).copy()]
+        rec.append(hk.grid().copy())
+        hk.close()
+        runs.append(rec)
+    for a, b in zip(runs[0], runs[1]):
+        assert a.dtype == b.dtype and a.shape == b.shape and a.tobytes() == b.tobytes()
+
+
 def test_config4_full_depth_one_step(H):
     # configuration 4 at its full depth and widths (32 layers, d = 4096, MLP 11008, vocabulary 65536, slice of
     # 8192 at id 4, top-k 2000, guidance 3.0: 12 rows per target pass) with a condition of 8 vectors (the
